@@ -1,0 +1,164 @@
+/*
+ * lisa.h -- C ABI of the LiSA attention-layer library for AMD MI355X (gfx950).
+ *
+ * LiSA (cross-layer attention sharing) replaces the full-rank Q K^T of a layer by
+ *   (1) the previous layer's pre-softmax scores A_{n-1}, re-aligned across heads by a
+ *       small feed-forward network applied over the head axis at every (query, key)
+ *       position (Sec. 5.1, "Learn to share attention weights"),
+ *   (2) a low-rank correction A_delta = Q_LR K_LR^T / sqrt(r) (Sec. 5.1, Eq. 3),
+ *   (3) Integrate(A_align, A_delta) (Eq. 4), followed by the usual softmax and P V of
+ *       Sec. 2.1, Eq. 1-2.
+ * A standard-attention entry point that emits the shared score tensor A (the bracketed
+ * term of Eq. 2) is included, because a LiSA layer needs a producer for A_{n-1}.
+ *
+ * General rules for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller, valid on the device that
+ *     is current when the call is made.  The descriptor pointer is a HOST pointer.  The
+ *     library never allocates, frees or retains memory.
+ *   - Calls only enqueue work on `hip_stream` (a hipStream_t cast to void*, NULL = the
+ *     default stream) and return without synchronising.  No global state; re-entrant.
+ *   - Return value: 0 (LISA_OK) or a negative lisa_status.  All argument validation is
+ *     done on the host before any HIP call, so a rejected call has touched nothing.
+ *   - Tensors are dense, row-major, innermost index last, base pointers 16-byte aligned.
+ *   - Element types: `dtype` is the type of Q, K, V, Q_LR, K_LR, W1, W2 and of the
+ *     attention output O.  Score tensors (A_{n-1}, A_n) use the *score type*:
+ *     float32 when dtype = LISA_F32, IEEE binary16 (half) when dtype = LISA_BF16 -- the
+ *     2-byte score element assumed by the memory analysis of Sec. 5.2, chosen as half
+ *     because the softmax that consumes A needs absolute, not relative, precision.
+ *   - Visibility: with causal = 1 query row i (0-based, of Lq) sees key j (of Lk) iff
+ *     j <= i + (Lk - Lq); with causal = 0 every key is visible.  Score entries of
+ *     invisible keys are never read and never written.
+ *   - Grouped KV heads: query head h uses KV head h / (H / Hkv).
+ */
+#ifndef LISA_H_
+#define LISA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { LISA_F32 = 0, LISA_BF16 = 1 } lisa_dtype;
+
+/* Integrate() of Eq. 4.  ADD:    A_n = FFN(A_{n-1}) + A_delta, FFN input width Din = H.
+ *                        CONCAT: A_n = FFN([A_{n-1} ; A_delta]), Din = 2H, rows 0..H-1 of W1
+ *                                act on A_{n-1} and rows H..2H-1 on A_delta (Sec. 5.1,
+ *                                "An overview of LiSA"). */
+typedef enum { LISA_MIX_ADD = 0, LISA_MIX_CONCAT = 1 } lisa_mix;
+
+/* Activation between the two FFN layers (Sec. 6.1 "Model configuration": ReLU). */
+typedef enum { LISA_ACT_RELU = 0 } lisa_act;
+
+typedef enum {
+  LISA_OK = 0,
+  LISA_ERR_NULL = -1,        /* a required pointer is NULL                              */
+  LISA_ERR_SHAPE = -2,       /* a dimension is non-positive or inconsistent             */
+  LISA_ERR_UNSUPPORTED = -3, /* valid request outside what the kernels implement        */
+  LISA_ERR_ALIGN = -4,       /* a base pointer is not 16-byte aligned                   */
+  LISA_ERR_WORKSPACE = -5,   /* workspace missing or smaller than lisa_workspace_bytes  */
+  LISA_ERR_HIP = -6          /* a HIP launch failed; see lisa_last_hip_error()          */
+} lisa_status;
+
+typedef enum { LISA_WS_PREFILL = 0, LISA_WS_DECODE = 1, LISA_WS_STD = 2 } lisa_ws_kind;
+
+/* Problem descriptor (host memory, plain data, zero-initialise then fill). */
+typedef struct lisa_desc {
+  int32_t dtype;            /* lisa_dtype                                                     */
+  int32_t B;                /* sequences in the batch                                         */
+  int32_t H;                /* query heads (h of Sec. 2.1)                                    */
+  int32_t Hkv;              /* key/value heads, divides H                                     */
+  int32_t Lq;               /* query rows in this call (decode: 1)                            */
+  int32_t Lk;               /* keys attended (decode: cached context + the new token)         */
+  int32_t d_k;              /* head dimension of V (and of Q, K in std_attn_scores)           */
+  int32_t r;                /* per-head low-rank dimension of Q_LR, K_LR (Eq. 3)              */
+  int32_t F;                /* hidden width of the head-alignment FFN                         */
+  int32_t mix;              /* lisa_mix                                                       */
+  int32_t act;              /* lisa_act                                                       */
+  float delta_scale;        /* scale of A_delta; 0 selects 1/sqrt(r)   (Eq. 3)                */
+  float std_scale;          /* scale of the standard scores; 0 selects 1/sqrt(d_k) (Eq. 2)    */
+  int32_t causal;           /* 1 causal, 0 full visibility                                    */
+  int32_t write_scores;     /* lisa_*: 1 = emit A_n for the next layer                        */
+  int32_t kcache_dim_major; /* decode: K_LR cache is [B,Hkv,r,Lmax] (1) or [B,Hkv,Lmax,r] (0) */
+  int32_t Lmax;             /* decode: capacity of the caches along the key axis, >= Lk       */
+} lisa_desc;
+
+/*
+ * lisa_attn_prefill -- one LiSA attention layer over Lq query rows (Sec. 5.1, Eq. 3-4,
+ * then Sec. 2.1 Eq. 1-2 without W^O).
+ *   q_lr        [B,H,Lq,r]     in   low-rank queries  H W^Q_LR, split in heads
+ *   k_lr        [B,Hkv,Lk,r]   in   low-rank keys     H W^K_LR
+ *   v           [B,Hkv,Lk,d_k] in   values
+ *   scores_prev [B,H,Lq,Lk]    in   A_{n-1}, score type
+ *   w1 [Din,F], w2 [F,H]       in   FFN weights (no bias), dtype
+ *   out         [B,Lq,H,d_k]   out  concatenated heads softmax(A_n) V, dtype
+ *   scores_out  [B,H,Lq,Lk]    out  A_n, score type; required iff write_scores = 1; must not
+ *                                   alias scores_prev
+ *   workspace                  scratch of at least lisa_workspace_bytes(desc, LISA_WS_PREFILL)
+ *                              bytes (may be NULL when that is 0); contents undefined after
+ */
+int lisa_attn_prefill(const lisa_desc* desc, const void* q_lr, const void* k_lr, const void* v,
+                      const void* scores_prev, const void* w1, const void* w2, void* out,
+                      void* scores_out, void* workspace, size_t workspace_bytes,
+                      void* hip_stream);
+
+/*
+ * lisa_attn_decode -- the same layer for one new token per sequence against the caches
+ * (Sec. 2.2 prefilling/decoding stages; Sec. 5.2: the cache holds K_LR instead of K).
+ * Requires Lq = 1 and Lk <= Lmax.
+ *   q_lr           [B,H,r]          in
+ *   k_lr_new       [B,Hkv,r]        in   or NULL; when given it is stored at key index Lk-1
+ *   v_new          [B,Hkv,d_k]      in   or NULL; likewise (both or neither)
+ *   k_lr_cache     [B,Hkv,Lmax,r] or [B,Hkv,r,Lmax]   in/out (only index Lk-1 is written)
+ *   v_cache        [B,Hkv,Lmax,d_k]                   in/out (only index Lk-1 is written)
+ *   score_row_prev [B,H,Lk]         in   A_{n-1} row of the new token, score type
+ *   out            [B,H,d_k]        out
+ *   score_row_out  [B,H,Lk]         out  required iff write_scores = 1 (the "small weight
+ *                                        matrix" of h*l elements in Sec. 5.2)
+ */
+int lisa_attn_decode(const lisa_desc* desc, const void* q_lr, const void* k_lr_new,
+                     const void* v_new, void* k_lr_cache, void* v_cache,
+                     const void* score_row_prev, const void* w1, const void* w2, void* out,
+                     void* score_row_out, void* workspace, size_t workspace_bytes,
+                     void* hip_stream);
+
+/*
+ * std_attn_scores -- standard scaled dot-product attention (Sec. 2.1 Eq. 1-2) that also
+ * emits the pre-softmax scores A = Q K^T * std_scale shared with the following LiSA layer.
+ *   q [B,H,Lq,d_k], k [B,Hkv,Lk,d_k]   in
+ *   v [B,Hkv,Lk,d_k]                   in   or NULL (then `out` must be NULL too)
+ *   scores_out [B,H,Lq,Lk]             out  A, score type; or NULL when only `out` is wanted
+ *   out [B,Lq,H,d_k]                   out  or NULL
+ * With Lq = 1 this is the decode step of a standard layer on a [B,Hkv,Lk,d_k] cache.
+ */
+int std_attn_scores(const lisa_desc* desc, const void* q, const void* k, const void* v,
+                    void* scores_out, void* out, void* workspace, size_t workspace_bytes,
+                    void* hip_stream);
+
+/* Host-only helpers (no HIP call). */
+
+/* Scratch bytes the given entry point (lisa_ws_kind) needs for this descriptor. */
+size_t lisa_workspace_bytes(const lisa_desc* desc, int which);
+/* Bytes of one score tensor [B,H,Lq,Lk] in the score type (Sec. 5.2: h*l*l*2 per
+ * sequence in prefill, h*l*2 per sequence in decode). */
+size_t lisa_scores_bytes(const lisa_desc* desc);
+/* Bytes per score element: 4 (LISA_F32) or 2 (LISA_BF16). */
+size_t lisa_score_elem_bytes(const lisa_desc* desc);
+/* Bytes of key cache saved by storing K_LR instead of K in n_lisa_layers layers
+ * (Sec. 5.2: |S| * h * l * (d_k - r) * element size, per sequence, times B). */
+size_t lisa_kcache_saved_bytes(const lisa_desc* desc, int n_lisa_layers);
+/* LISA_OK if the three entry points accept this descriptor, else the status they return. */
+int lisa_supported(const lisa_desc* desc);
+/* Static, human-readable text for a lisa_status. */
+const char* lisa_strerror(int status);
+/* hipGetErrorString of the last failed launch seen by this thread ("" if none). */
+const char* lisa_last_hip_error(void);
+/* Name of the kernel family the last successful call on this thread dispatched to
+ * ("generic", "mfma", ...); for tests and benchmark reports. */
+const char* lisa_last_path(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LISA_H_ */

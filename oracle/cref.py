@@ -1,0 +1,111 @@
+"""ctypes binding of the C oracle (``lisa_oracle.c``).  Test infrastructure only.
+
+All arrays are float64, C-contiguous, one sequence per call (see the C header comment
+for the layouts).  Functions return freshly allocated numpy arrays.
+"""
+import ctypes as C
+
+import numpy as np
+
+from . import build as _build
+
+MIX_ADD = 0
+MIX_CONCAT = 1
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(_build.build())
+        _lib.lisa_oracle_num_threads.restype = C.c_int
+    return _lib
+
+
+def num_threads() -> int:
+    return int(lib().lisa_oracle_num_threads())
+
+
+def _d(a):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    return a, a.ctypes.data_as(C.POINTER(C.c_double))
+
+
+def _rows(rows):
+    r = np.ascontiguousarray(rows, dtype=np.int32)
+    return r, r.ctypes.data_as(C.POINTER(C.c_int))
+
+
+def std_scores_rows(q, k, rows, scale=None):
+    """A[h,i,j] = scale <q[h,i], k[kv(h),j]> for the requested rows -> [n_rows, H, Lk]."""
+    q, qp = _d(q)
+    k, kp = _d(k)
+    H, Lq, dk = q.shape
+    Hkv, Lk, dk2 = k.shape
+    assert dk == dk2
+    if scale is None:
+        scale = 1.0 / np.sqrt(dk)
+    rows, rp = _rows(rows)
+    out = np.empty((len(rows), H, Lk), dtype=np.float64)
+    rc = lib().lisa_oracle_std_scores_rows(H, Hkv, Lq, Lk, dk, C.c_double(scale), qp, kp,
+                                           len(rows), rp, out.ctypes.data_as(C.POINTER(C.c_double)))
+    if rc:
+        raise ValueError("lisa_oracle_std_scores_rows: bad shape")
+    return out
+
+
+def softmax_v_rows(v, rows, scores_rows, Lq, want_probs=False):
+    """Causal softmax of the given score rows times V -> out [n_rows, H, dk] (and P)."""
+    v, vp = _d(v)
+    s, sp = _d(scores_rows)
+    Hkv, Lk, dk = v.shape
+    n, H, Lk2 = s.shape
+    assert Lk == Lk2
+    rows, rp = _rows(rows)
+    assert len(rows) == n
+    out = np.empty((n, H, dk), dtype=np.float64)
+    probs = np.empty((n, H, Lk), dtype=np.float64) if want_probs else None
+    pp = probs.ctypes.data_as(C.POINTER(C.c_double)) if want_probs else None
+    rc = lib().lisa_oracle_softmax_v_rows(H, Hkv, Lq, Lk, dk, vp, n, rp, sp, pp,
+                                          out.ctypes.data_as(C.POINTER(C.c_double)))
+    if rc:
+        raise ValueError("lisa_oracle_softmax_v_rows: bad shape")
+    return (out, probs) if want_probs else out
+
+
+def lisa_rows(q_lr, k_lr, v, w1, w2, rows, prev_rows, mix=MIX_ADD, delta_scale=None,
+              want_probs=False):
+    """One LiSA layer for the requested query rows.
+
+    Returns (scores [n,H,Lk], out [n,H,dk]) and P [n,H,Lk] when ``want_probs``.
+    """
+    q_lr, qp = _d(q_lr)
+    k_lr, kp = _d(k_lr)
+    v, vp = _d(v)
+    w1, w1p = _d(w1)
+    w2, w2p = _d(w2)
+    prev, pp = _d(prev_rows)
+    H, Lq, r = q_lr.shape
+    Hkv, Lk, r2 = k_lr.shape
+    assert r == r2 and v.shape[:2] == (Hkv, Lk)
+    dk = v.shape[2]
+    Din, F = w1.shape
+    assert w2.shape == (F, H)
+    assert Din == (2 * H if mix == MIX_CONCAT else H)
+    rows, rp = _rows(rows)
+    n = len(rows)
+    assert prev.shape == (n, H, Lk)
+    if delta_scale is None:
+        delta_scale = 1.0 / np.sqrt(r)
+    scores = np.empty((n, H, Lk), dtype=np.float64)
+    out = np.empty((n, H, dk), dtype=np.float64)
+    probs = np.empty((n, H, Lk), dtype=np.float64) if want_probs else None
+    prp = probs.ctypes.data_as(C.POINTER(C.c_double)) if want_probs else None
+    rc = lib().lisa_oracle_lisa_rows(H, Hkv, Lq, Lk, dk, r, F, int(mix), C.c_double(delta_scale),
+                                     qp, kp, vp, w1p, w2p, n, rp, pp,
+                                     scores.ctypes.data_as(C.POINTER(C.c_double)), prp,
+                                     out.ctypes.data_as(C.POINTER(C.c_double)))
+    if rc:
+        raise ValueError("lisa_oracle_lisa_rows: bad shape")
+    return (scores, out, probs) if want_probs else (scores, out)
