@@ -21,7 +21,8 @@
  *     done on the host before any HIP call, so a rejected call has touched nothing.
  *   - Tensors are dense, row-major, innermost index last, base pointers 16-byte aligned.
  *   - Element types: `dtype` is the type of Q, K, V, Q_LR, K_LR, W1, W2 and of the
- *     attention output O.  Score tensors (A_{n-1}, A_n) use the *score type*:
+ *     attention output O (float32 instead when out_f32 = 1: the accumulators are float32
+ *     and rounding O to bfloat16 alone costs up to 2^-9 of each element).  Score tensors (A_{n-1}, A_n) use the *score type*:
  *     float32 when dtype = LISA_F32, IEEE binary16 (half) when dtype = LISA_BF16 -- the
  *     2-byte score element assumed by the memory analysis of Sec. 5.2, chosen as half
  *     because the softmax that consumes A needs absolute, not relative, precision.
@@ -82,6 +83,7 @@ typedef struct lisa_desc {
   int32_t write_scores;     /* lisa_*: 1 = emit A_n for the next layer                        */
   int32_t kcache_dim_major; /* decode: K_LR cache is [B,Hkv,r,Lmax] (1) or [B,Hkv,Lmax,r] (0) */
   int32_t Lmax;             /* decode: capacity of the caches along the key axis, >= Lk       */
+  int32_t out_f32;          /* 1: the attention output O is written as float32 whatever dtype */
 } lisa_desc;
 
 /*
@@ -96,7 +98,9 @@ typedef struct lisa_desc {
  *   scores_out  [B,H,Lq,Lk]    out  A_n, score type; required iff write_scores = 1; must not
  *                                   alias scores_prev
  *   workspace                  scratch of at least lisa_workspace_bytes(desc, LISA_WS_PREFILL)
- *                              bytes (may be NULL when that is 0); contents undefined after
+ *                              bytes (may be NULL when that is 0); contents undefined after.
+ *                              The softmax never reads the rounded 2-byte A_n: kernels that
+ *                              cannot keep A_n in registers stage it here as float32.
  */
 int lisa_attn_prefill(const lisa_desc* desc, const void* q_lr, const void* k_lr, const void* v,
                       const void* scores_prev, const void* w1, const void* w2, void* out,
@@ -130,7 +134,8 @@ int lisa_attn_decode(const lisa_desc* desc, const void* q_lr, const void* k_lr_n
  *   v [B,Hkv,Lk,d_k]                   in   or NULL (then `out` must be NULL too)
  *   scores_out [B,H,Lq,Lk]             out  A, score type; or NULL when only `out` is wanted
  *   out [B,Lq,H,d_k]                   out  or NULL
- * With Lq = 1 this is the decode step of a standard layer on a [B,Hkv,Lk,d_k] cache.
+ * With Lq = 1 and Lmax >= Lk this is the decode step of a standard layer: k and v are then
+ * caches [B,Hkv,Lmax,d_k] of which the first Lk keys are attended (Lmax = 0: dense, Lk keys).
  */
 int std_attn_scores(const lisa_desc* desc, const void* q, const void* k, const void* v,
                     void* scores_out, void* out, void* workspace, size_t workspace_bytes,
@@ -157,6 +162,24 @@ const char* lisa_last_hip_error(void);
 /* Name of the kernel family the last successful call on this thread dispatched to
  * ("generic", "mfma", ...); for tests and benchmark reports. */
 const char* lisa_last_path(void);
+
+/*
+ * Stage timing for benchmarks (diagnostic, per calling thread, off by default).  While
+ * enabled, every entry point brackets each kernel it launches with HIP events recorded on
+ * the call's own stream; nothing is synchronised until lisa_profile_collect().
+ *   lisa_profile_enable(1)  start (drops earlier records);  lisa_profile_enable(0)  stop.
+ *   lisa_profile_collect    waits for the recorded events, sums them per stage name and
+ *                           fills up to max_stages entries; returns the number of stages
+ *                           (or a negative lisa_status) and clears the records.
+ * At most 16384 kernel launches are recorded between two collects; later ones are skipped.
+ */
+typedef struct lisa_stage_time {
+  const char* name; /* static string: kernel (stage) name      */
+  int32_t launches; /* launches recorded under that name       */
+  float total_ms;   /* sum of their event-to-event durations   */
+} lisa_stage_time;
+int lisa_profile_enable(int on);
+int lisa_profile_collect(lisa_stage_time* out, int max_stages);
 
 #ifdef __cplusplus
 }

@@ -1,0 +1,407 @@
+// C ABI of the LiSA attention-layer library: argument validation (host only, before any
+// HIP call), workspace accounting and kernel dispatch.  See include/lisa.h for the contract.
+#include "../../include/lisa.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "kernels_generic.h"
+
+using namespace lisa;
+
+namespace {
+
+thread_local char g_hip_err[256] = "";
+thread_local const char* g_path = "";
+
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Limits of the kernels in this library (see lisa_supported()).
+constexpr int kMaxHeadDim = 256;      // k_softmax_v: 8 rows * d_k outputs over 256 threads * 8
+constexpr int kMaxRank = 256;
+constexpr int kMaxFfnRows = 640;      // (Din + F + H) * 64 floats of LDS <= 160 KB
+constexpr int kMaxGridYZ = 65535;
+
+int check_common(const lisa_desc* d) {
+  if (!d) return LISA_ERR_NULL;
+  if (d->dtype != LISA_F32 && d->dtype != LISA_BF16) return LISA_ERR_UNSUPPORTED;
+  if (d->B <= 0 || d->H <= 0 || d->Hkv <= 0 || d->Lq <= 0 || d->Lk <= 0 || d->d_k <= 0)
+    return LISA_ERR_SHAPE;
+  if (d->H % d->Hkv != 0) return LISA_ERR_SHAPE;
+  if (d->causal != 0 && d->causal != 1) return LISA_ERR_SHAPE;
+  if (d->out_f32 != 0 && d->out_f32 != 1) return LISA_ERR_SHAPE;
+  if (d->causal && d->Lk < d->Lq) return LISA_ERR_SHAPE;
+  if (d->d_k > kMaxHeadDim) return LISA_ERR_UNSUPPORTED;
+  if (d->B > kMaxGridYZ || d->Lq > kMaxGridYZ || (long long)d->B * d->H > kMaxGridYZ)
+    return LISA_ERR_UNSUPPORTED;
+  if (d->std_scale < 0.f || !std::isfinite(d->std_scale)) return LISA_ERR_SHAPE;
+  return LISA_OK;
+}
+
+int check_lisa(const lisa_desc* d) {
+  int rc = check_common(d);
+  if (rc) return rc;
+  if (d->r <= 0 || d->F <= 0) return LISA_ERR_SHAPE;
+  if (d->mix != LISA_MIX_ADD && d->mix != LISA_MIX_CONCAT) return LISA_ERR_UNSUPPORTED;
+  if (d->act != LISA_ACT_RELU) return LISA_ERR_UNSUPPORTED;
+  if (d->write_scores != 0 && d->write_scores != 1) return LISA_ERR_SHAPE;
+  if (d->delta_scale < 0.f || !std::isfinite(d->delta_scale)) return LISA_ERR_SHAPE;
+  if (d->r > kMaxRank) return LISA_ERR_UNSUPPORTED;
+  const int Din = d->mix == LISA_MIX_CONCAT ? 2 * d->H : d->H;
+  if (Din + d->F + d->H > kMaxFfnRows) return LISA_ERR_UNSUPPORTED;
+  return LISA_OK;
+}
+
+int check_decode(const lisa_desc* d) {
+  int rc = check_lisa(d);
+  if (rc) return rc;
+  if (d->Lq != 1) return LISA_ERR_SHAPE;
+  if (d->Lmax < d->Lk) return LISA_ERR_SHAPE;
+  if (d->kcache_dim_major != 0 && d->kcache_dim_major != 1) return LISA_ERR_SHAPE;
+  return LISA_OK;
+}
+
+size_t score_elem(const lisa_desc* d) { return d->dtype == LISA_F32 ? 4 : 2; }
+
+size_t scores_bytes(const lisa_desc* d) {
+  return (size_t)d->B * d->H * d->Lq * d->Lk * score_elem(d);
+}
+
+// float32 copy of the score tensor that the generic softmax kernel reads
+size_t exact_bytes(const lisa_desc* d) {
+  return round_up((size_t)d->B * d->H * d->Lq * d->Lk * sizeof(float), 256);
+}
+
+int hip_fail(hipError_t e) {
+  snprintf(g_hip_err, sizeof(g_hip_err), "%s", hipGetErrorString(e));
+  return LISA_ERR_HIP;
+}
+
+int check_launch() {
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? LISA_OK : hip_fail(e);
+}
+
+float pick_scale(float given, int n) { return given > 0.f ? given : 1.0f / std::sqrt((float)n); }
+
+// ---- optional stage timing (lisa_profile_*) -------------------------------------------
+struct ProfRec {
+  const char* name;
+  hipEvent_t beg, end;
+};
+constexpr size_t kMaxProfRecs = 16384;
+thread_local bool g_prof_on = false;
+thread_local std::vector<ProfRec> g_prof_recs;
+thread_local std::vector<hipEvent_t> g_prof_pool;
+
+hipEvent_t prof_event() {
+  if (!g_prof_pool.empty()) {
+    hipEvent_t e = g_prof_pool.back();
+    g_prof_pool.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+// Brackets the launches made while it is alive with two events on their stream.
+struct StageScope {
+  hipStream_t st;
+  ProfRec rec{nullptr, nullptr, nullptr};
+  StageScope(const char* name, hipStream_t s) : st(s) {
+    if (!g_prof_on || g_prof_recs.size() >= kMaxProfRecs) return;
+    rec.beg = prof_event();
+    rec.end = prof_event();
+    if (!rec.beg || !rec.end) { rec.beg = rec.end = nullptr; return; }
+    rec.name = name;
+    (void)hipEventRecord(rec.beg, st);
+  }
+  ~StageScope() {
+    if (!rec.name) return;
+    (void)hipEventRecord(rec.end, st);
+    g_prof_recs.push_back(rec);
+  }
+};
+
+// ---- generic launches ----------------------------------------------------------------
+template <typename T, typename S>
+int launch_std_scores(const lisa_desc* d, const void* q, const void* k, KeyStrides ks, void* scores,
+                      float* exact, hipStream_t st) {
+  dim3 grid((d->Lk + 63) / 64, (d->Lq + 63) / 64, d->B * d->H);
+  StageScope prof("k_std_scores", st);
+  k_std_scores<T, S><<<grid, 256, 0, st>>>((const T*)q, (const T*)k, ks, (S*)scores, exact, d->H, d->Hkv,
+                                           d->Lq, d->Lk, d->d_k, pick_scale(d->std_scale, d->d_k),
+                                           d->causal);
+  return check_launch();
+}
+
+template <typename T, typename S>
+int launch_lisa_scores(const lisa_desc* d, const void* q_lr, const void* k_lr, KeyStrides ks,
+                       const void* prev, const void* w1, const void* w2, void* scores,
+                       float* exact, hipStream_t st) {
+  const int concat = d->mix == LISA_MIX_CONCAT;
+  const int Din = concat ? 2 * d->H : d->H;
+  const size_t lds = (size_t)(Din + d->F + d->H) * 64 * sizeof(float);
+  auto kern = k_lisa_scores<T, S>;
+  if (lds > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)lds);
+    if (e != hipSuccess) return hip_fail(e);
+  }
+  dim3 grid((d->Lk + 63) / 64, d->Lq, d->B);
+  StageScope prof("k_lisa_scores", st);
+  kern<<<grid, 256, lds, st>>>((const T*)q_lr, (const T*)k_lr, ks, (const S*)prev, (const T*)w1,
+                               (const T*)w2, (S*)scores, exact, d->H, d->Hkv, d->Lq, d->Lk, d->r, d->F,
+                               concat, pick_scale(d->delta_scale, d->r), d->causal);
+  return check_launch();
+}
+
+template <typename T>
+int launch_softmax_v(const lisa_desc* d, const float* scores, const void* v, KeyStrides vs, void* out,
+                     hipStream_t st) {
+  dim3 grid((d->Lq + 7) / 8, d->H, d->B);
+  const long long sh = d->d_k, si = (long long)d->H * d->d_k, sb = si * d->Lq;
+  StageScope prof("k_softmax_v", st);
+  if (d->out_f32)
+    k_softmax_v<T, float, float><<<grid, 256, 0, st>>>(scores, (const T*)v, vs, (float*)out, sb, si,
+                                                       sh, d->H, d->Hkv, d->Lq, d->Lk, d->d_k,
+                                                       d->causal);
+  else
+    k_softmax_v<T, float, T><<<grid, 256, 0, st>>>(scores, (const T*)v, vs, (T*)out, sb, si, sh,
+                                                   d->H, d->Hkv, d->Lq, d->Lk, d->d_k, d->causal);
+  return check_launch();
+}
+
+KeyStrides dense_keys(const lisa_desc* d, int len, int width) {
+  KeyStrides s;
+  s.t = 1;
+  s.j = width;
+  s.h = (long long)len * width;
+  s.b = s.h * d->Hkv;
+  return s;
+}
+
+KeyStrides dim_major_keys(const lisa_desc* d, int len, int width) {
+  KeyStrides s;
+  s.j = 1;
+  s.t = len;
+  s.h = (long long)len * width;
+  s.b = s.h * d->Hkv;
+  return s;
+}
+
+template <typename T, typename S>
+int run_lisa(const lisa_desc* d, const void* q_lr, const void* k_lr, KeyStrides ks, const void* v,
+             KeyStrides vs, const void* prev, const void* w1, const void* w2, void* out,
+             void* scores, float* exact, hipStream_t st) {
+  // The softmax reads the unrounded float32 A_n from the workspace: rounding A_n to the
+  // 2-byte score type first would move each probability by up to |A_n| 2^-11.
+  int rc = launch_lisa_scores<T, S>(d, q_lr, k_lr, ks, prev, w1, w2, scores, exact, st);
+  if (rc) return rc;
+  rc = launch_softmax_v<T>(d, exact, v, vs, out, st);
+  if (rc == LISA_OK) g_path = "generic";
+  return rc;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t lisa_score_elem_bytes(const lisa_desc* desc) {
+  if (!desc || (desc->dtype != LISA_F32 && desc->dtype != LISA_BF16)) return 0;
+  return score_elem(desc);
+}
+
+size_t lisa_scores_bytes(const lisa_desc* desc) {
+  if (check_common(desc) != LISA_OK) return 0;
+  return scores_bytes(desc);
+}
+
+size_t lisa_kcache_saved_bytes(const lisa_desc* desc, int n_lisa_layers) {
+  if (check_common(desc) != LISA_OK || desc->r <= 0 || desc->r > desc->d_k || n_lisa_layers < 0)
+    return 0;
+  const size_t e = desc->dtype == LISA_F32 ? 4 : 2;
+  return (size_t)n_lisa_layers * desc->B * desc->Hkv * desc->Lk * (size_t)(desc->d_k - desc->r) * e;
+}
+
+size_t lisa_workspace_bytes(const lisa_desc* desc, int which) {
+  switch (which) {
+    case LISA_WS_PREFILL:
+      if (check_lisa(desc) != LISA_OK) return 0;
+      return exact_bytes(desc);
+    case LISA_WS_DECODE:
+      if (check_decode(desc) != LISA_OK) return 0;
+      return exact_bytes(desc);
+    case LISA_WS_STD:
+      if (check_common(desc) != LISA_OK) return 0;
+      return exact_bytes(desc);   // needed only when `out` is requested
+    default:
+      return 0;
+  }
+}
+
+int lisa_supported(const lisa_desc* desc) { return check_lisa(desc); }
+
+const char* lisa_strerror(int status) {
+  switch (status) {
+    case LISA_OK: return "ok";
+    case LISA_ERR_NULL: return "a required pointer is NULL";
+    case LISA_ERR_SHAPE: return "a dimension or flag is invalid or inconsistent";
+    case LISA_ERR_UNSUPPORTED: return "valid request outside the supported kernel range";
+    case LISA_ERR_ALIGN: return "a base pointer is not 16-byte aligned";
+    case LISA_ERR_WORKSPACE: return "workspace missing or too small";
+    case LISA_ERR_HIP: return "a HIP call failed (see lisa_last_hip_error)";
+    default: return "unknown status";
+  }
+}
+
+int lisa_profile_enable(int on) {
+  for (ProfRec& r : g_prof_recs) {
+    g_prof_pool.push_back(r.beg);
+    g_prof_pool.push_back(r.end);
+  }
+  g_prof_recs.clear();
+  g_prof_on = on != 0;
+  return LISA_OK;
+}
+
+int lisa_profile_collect(lisa_stage_time* out, int max_stages) {
+  if (!out && max_stages > 0) return LISA_ERR_NULL;
+  int n = 0;
+  int rc = LISA_OK;
+  for (ProfRec& r : g_prof_recs) {
+    float ms = 0.f;
+    hipError_t e = hipEventSynchronize(r.end);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.beg, r.end);
+    if (e != hipSuccess) rc = hip_fail(e);
+    g_prof_pool.push_back(r.beg);
+    g_prof_pool.push_back(r.end);
+    if (e != hipSuccess) continue;
+    int s = 0;
+    while (s < n && std::strcmp(out[s].name, r.name) != 0) ++s;
+    if (s == n) {
+      if (n >= max_stages) continue;
+      out[n].name = r.name;
+      out[n].launches = 0;
+      out[n].total_ms = 0.f;
+      ++n;
+    }
+    out[s].launches += 1;
+    out[s].total_ms += ms;
+  }
+  g_prof_recs.clear();
+  return rc == LISA_OK ? n : rc;
+}
+
+const char* lisa_last_hip_error(void) { return g_hip_err; }
+const char* lisa_last_path(void) { return g_path; }
+
+int lisa_attn_prefill(const lisa_desc* desc, const void* q_lr, const void* k_lr, const void* v,
+                      const void* scores_prev, const void* w1, const void* w2, void* out,
+                      void* scores_out, void* workspace, size_t workspace_bytes,
+                      void* hip_stream) {
+  int rc = check_lisa(desc);
+  if (rc) return rc;
+  if (!q_lr || !k_lr || !v || !scores_prev || !w1 || !w2 || !out) return LISA_ERR_NULL;
+  if (desc->write_scores && !scores_out) return LISA_ERR_NULL;
+  if (desc->write_scores && scores_out == scores_prev) return LISA_ERR_SHAPE;
+  const void* ptrs[] = {q_lr, k_lr, v, scores_prev, w1, w2, out, scores_out, workspace};
+  for (const void* p : ptrs)
+    if (p && !aligned16(p)) return LISA_ERR_ALIGN;
+  if (!workspace || workspace_bytes < lisa_workspace_bytes(desc, LISA_WS_PREFILL))
+    return LISA_ERR_WORKSPACE;
+  void* scores = desc->write_scores ? scores_out : nullptr;
+  float* exact = (float*)workspace;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const KeyStrides ks = dense_keys(desc, desc->Lk, desc->r);
+  const KeyStrides vs = dense_keys(desc, desc->Lk, desc->d_k);
+  if (desc->dtype == LISA_F32)
+    return run_lisa<float, float>(desc, q_lr, k_lr, ks, v, vs, scores_prev, w1, w2, out, scores,
+                                  exact, st);
+  return run_lisa<bf16_t, half_t>(desc, q_lr, k_lr, ks, v, vs, scores_prev, w1, w2, out, scores,
+                                  exact, st);
+}
+
+int lisa_attn_decode(const lisa_desc* desc, const void* q_lr, const void* k_lr_new,
+                     const void* v_new, void* k_lr_cache, void* v_cache,
+                     const void* score_row_prev, const void* w1, const void* w2, void* out,
+                     void* score_row_out, void* workspace, size_t workspace_bytes,
+                     void* hip_stream) {
+  int rc = check_decode(desc);
+  if (rc) return rc;
+  if (!q_lr || !k_lr_cache || !v_cache || !score_row_prev || !w1 || !w2 || !out)
+    return LISA_ERR_NULL;
+  if ((k_lr_new == nullptr) != (v_new == nullptr)) return LISA_ERR_NULL;
+  if (desc->write_scores && !score_row_out) return LISA_ERR_NULL;
+  if (desc->write_scores && score_row_out == score_row_prev) return LISA_ERR_SHAPE;
+  const void* ptrs[] = {q_lr, k_lr_new, v_new, k_lr_cache, v_cache, score_row_prev,
+                        w1,   w2,       out,   score_row_out, workspace};
+  for (const void* p : ptrs)
+    if (p && !aligned16(p)) return LISA_ERR_ALIGN;
+  if (!workspace || workspace_bytes < lisa_workspace_bytes(desc, LISA_WS_DECODE))
+    return LISA_ERR_WORKSPACE;
+  void* scores = desc->write_scores ? score_row_out : nullptr;
+  float* exact = (float*)workspace;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const KeyStrides ks = desc->kcache_dim_major ? dim_major_keys(desc, desc->Lmax, desc->r)
+                                               : dense_keys(desc, desc->Lmax, desc->r);
+  const KeyStrides vs = dense_keys(desc, desc->Lmax, desc->d_k);
+  if (k_lr_new) {
+    dim3 grid(desc->Hkv, desc->B);
+    if (desc->dtype == LISA_F32)
+      k_append<float><<<grid, 128, 0, st>>>((const float*)k_lr_new, (const float*)v_new,
+                                            (float*)k_lr_cache, ks, (float*)v_cache, vs, desc->Hkv,
+                                            desc->r, desc->d_k, desc->Lk - 1);
+    else
+      k_append<bf16_t><<<grid, 128, 0, st>>>((const bf16_t*)k_lr_new, (const bf16_t*)v_new,
+                                             (bf16_t*)k_lr_cache, ks, (bf16_t*)v_cache, vs,
+                                             desc->Hkv, desc->r, desc->d_k, desc->Lk - 1);
+    rc = check_launch();
+    if (rc) return rc;
+  }
+  if (desc->dtype == LISA_F32)
+    return run_lisa<float, float>(desc, q_lr, k_lr_cache, ks, v_cache, vs, score_row_prev, w1, w2,
+                                  out, scores, exact, st);
+  return run_lisa<bf16_t, half_t>(desc, q_lr, k_lr_cache, ks, v_cache, vs, score_row_prev, w1, w2,
+                                  out, scores, exact, st);
+}
+
+int std_attn_scores(const lisa_desc* desc, const void* q, const void* k, const void* v,
+                    void* scores_out, void* out, void* workspace, size_t workspace_bytes,
+                    void* hip_stream) {
+  int rc = check_common(desc);
+  if (rc) return rc;
+  if (!q || !k) return LISA_ERR_NULL;
+  if (!scores_out && !out) return LISA_ERR_NULL;
+  if ((v == nullptr) != (out == nullptr)) return LISA_ERR_NULL;
+  const void* ptrs[] = {q, k, v, scores_out, out, workspace};
+  for (const void* p : ptrs)
+    if (p && !aligned16(p)) return LISA_ERR_ALIGN;
+  float* exact = nullptr;
+  if (out) {
+    if (!workspace || workspace_bytes < lisa_workspace_bytes(desc, LISA_WS_STD))
+      return LISA_ERR_WORKSPACE;
+    exact = (float*)workspace;
+  }
+  hipStream_t st = (hipStream_t)hip_stream;
+  // With Lq = 1 and Lmax set, K and V are caches of capacity Lmax along the key axis.
+  const int cap = (desc->Lq == 1 && desc->Lmax >= desc->Lk) ? desc->Lmax : desc->Lk;
+  const KeyStrides ks = dense_keys(desc, cap, desc->d_k);
+  if (desc->dtype == LISA_F32) {
+    rc = launch_std_scores<float, float>(desc, q, k, ks, scores_out, exact, st);
+    if (rc == LISA_OK && out) rc = launch_softmax_v<float>(desc, exact, v, ks, out, st);
+  } else {
+    rc = launch_std_scores<bf16_t, half_t>(desc, q, k, ks, scores_out, exact, st);
+    if (rc == LISA_OK && out) rc = launch_softmax_v<bf16_t>(desc, exact, v, ks, out, st);
+  }
+  if (rc == LISA_OK) g_path = "generic";
+  return rc;
+}
+
+}  // extern "C"

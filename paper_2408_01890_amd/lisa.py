@@ -1,0 +1,298 @@
+"""Thin ctypes binding of ``liblisa_mi355x.so`` (see include/lisa.h for the contract).
+
+Only argument marshalling happens here: tensors are checked for device, dtype, shape and
+contiguity, their device pointers and the current HIP stream are handed to the C ABI, and a
+negative status raises ``LisaError``.  There is no fallback: without the built library or
+without a GPU the calls fail loudly.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import math
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblisa_mi355x.so")
+
+F32, BF16 = 0, 1
+MIX_ADD, MIX_CONCAT = 0, 1
+ACT_RELU = 0
+WS_PREFILL, WS_DECODE, WS_STD = 0, 1, 2
+
+EXPORTS = (
+    "lisa_attn_prefill", "lisa_attn_decode", "std_attn_scores", "lisa_workspace_bytes",
+    "lisa_scores_bytes", "lisa_score_elem_bytes", "lisa_kcache_saved_bytes", "lisa_supported",
+    "lisa_strerror", "lisa_last_hip_error", "lisa_last_path", "lisa_profile_enable",
+    "lisa_profile_collect",
+)
+
+
+class LisaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = _lib().lisa_strerror(status).decode()
+        if status == -6:
+            msg += ": " + _lib().lisa_last_hip_error().decode()
+        super().__init__(f"{where}: {msg} (status {status})")
+
+
+class Desc(C.Structure):
+    _fields_ = [
+        ("dtype", C.c_int32), ("B", C.c_int32), ("H", C.c_int32), ("Hkv", C.c_int32),
+        ("Lq", C.c_int32), ("Lk", C.c_int32), ("d_k", C.c_int32), ("r", C.c_int32),
+        ("F", C.c_int32), ("mix", C.c_int32), ("act", C.c_int32),
+        ("delta_scale", C.c_float), ("std_scale", C.c_float), ("causal", C.c_int32),
+        ("write_scores", C.c_int32), ("kcache_dim_major", C.c_int32), ("Lmax", C.c_int32),
+        ("out_f32", C.c_int32),
+    ]
+
+
+class StageTime(C.Structure):
+    _fields_ = [("name", C.c_char_p), ("launches", C.c_int32), ("total_ms", C.c_float)]
+
+
+_handle = None
+
+
+def _lib():
+    global _handle
+    if _handle is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2408_01890_amd.build` "
+                "(there is no CPU fallback)")
+        h = C.CDLL(LIB_PATH)
+        vp, sz = C.c_void_p, C.c_size_t
+        dp = C.POINTER(Desc)
+        h.lisa_attn_prefill.argtypes = [dp] + [vp] * 9 + [sz, vp]
+        h.lisa_attn_prefill.restype = C.c_int
+        h.lisa_attn_decode.argtypes = [dp] + [vp] * 11 + [sz, vp]
+        h.lisa_attn_decode.restype = C.c_int
+        h.std_attn_scores.argtypes = [dp] + [vp] * 6 + [sz, vp]
+        h.std_attn_scores.restype = C.c_int
+        h.lisa_workspace_bytes.argtypes = [dp, C.c_int]
+        h.lisa_workspace_bytes.restype = sz
+        h.lisa_scores_bytes.argtypes = [dp]
+        h.lisa_scores_bytes.restype = sz
+        h.lisa_score_elem_bytes.argtypes = [dp]
+        h.lisa_score_elem_bytes.restype = sz
+        h.lisa_kcache_saved_bytes.argtypes = [dp, C.c_int]
+        h.lisa_kcache_saved_bytes.restype = sz
+        h.lisa_supported.argtypes = [dp]
+        h.lisa_supported.restype = C.c_int
+        h.lisa_strerror.argtypes = [C.c_int]
+        h.lisa_strerror.restype = C.c_char_p
+        h.lisa_last_hip_error.restype = C.c_char_p
+        h.lisa_last_path.restype = C.c_char_p
+        h.lisa_profile_enable.argtypes = [C.c_int]
+        h.lisa_profile_enable.restype = C.c_int
+        h.lisa_profile_collect.argtypes = [C.POINTER(StageTime), C.c_int]
+        h.lisa_profile_collect.restype = C.c_int
+        _handle = h
+    return _handle
+
+
+def library():
+    """The loaded ctypes library (raises ImportError if it has not been built)."""
+    return _lib()
+
+
+def make_desc(dtype, B, H, Hkv, Lq, Lk, d_k, r=0, F=0, mix=MIX_ADD, act=ACT_RELU,
+              delta_scale=0.0, std_scale=0.0, causal=1, write_scores=0, kcache_dim_major=0,
+              Lmax=0, out_f32=0) -> Desc:
+    code = {torch.float32: F32, torch.bfloat16: BF16, F32: F32, BF16: BF16}[dtype]
+    return Desc(code, B, H, Hkv, Lq, Lk, d_k, r, F, mix, act, delta_scale, std_scale, causal,
+                write_scores, kcache_dim_major, Lmax, out_f32)
+
+
+def score_dtype(dtype) -> torch.dtype:
+    return torch.float32 if dtype in (torch.float32, F32) else torch.float16
+
+
+def workspace_bytes(desc: Desc, which: int) -> int:
+    return int(_lib().lisa_workspace_bytes(C.byref(desc), which))
+
+
+def scores_bytes(desc: Desc) -> int:
+    return int(_lib().lisa_scores_bytes(C.byref(desc)))
+
+
+def kcache_saved_bytes(desc: Desc, n_layers: int) -> int:
+    return int(_lib().lisa_kcache_saved_bytes(C.byref(desc), n_layers))
+
+
+def supported(desc: Desc) -> int:
+    return int(_lib().lisa_supported(C.byref(desc)))
+
+
+def last_path() -> str:
+    return _lib().lisa_last_path().decode()
+
+
+def profile_enable(on: bool) -> None:
+    _lib().lisa_profile_enable(int(on))
+
+
+def profile_collect(max_stages: int = 32):
+    """{stage name: (launches, total_ms)} of the launches recorded since profile_enable(True)."""
+    buf = (StageTime * max_stages)()
+    n = _lib().lisa_profile_collect(buf, max_stages)
+    if n < 0:
+        raise LisaError(n, "lisa_profile_collect")
+    return {buf[i].name.decode(): (int(buf[i].launches), float(buf[i].total_ms)) for i in range(n)}
+
+
+def _ptr(t: Optional[torch.Tensor], name: str, shape=None, dtype=None):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name}: expected a GPU tensor (the library has no CPU path)")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name}: dtype {t.dtype}, expected {dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: shape {tuple(t.shape)}, expected {tuple(shape)}")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _workspace(nbytes: int, like: torch.Tensor, workspace: Optional[torch.Tensor]):
+    if nbytes == 0:
+        return workspace, (C.c_void_p(workspace.data_ptr()) if workspace is not None else None), \
+            (workspace.numel() * workspace.element_size() if workspace is not None else 0)
+    if workspace is None:
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=like.device)
+    have = workspace.numel() * workspace.element_size()
+    return workspace, C.c_void_p(workspace.data_ptr()), have
+
+
+def _out_dtype(dt, out_dtype):
+    """O is float32 unless the caller asks for the input dtype."""
+    out_dtype = torch.float32 if out_dtype is None else out_dtype
+    if out_dtype not in (torch.float32, dt):
+        raise ValueError(f"out_dtype must be float32 or {dt}")
+    return out_dtype, int(out_dtype == torch.float32 and dt != torch.float32)
+
+
+def std_attn_scores(q, k, v=None, *, want_scores=True, causal=True, std_scale=0.0,
+                    scores_out=None, out=None, out_dtype=None, workspace=None):
+    """Standard attention that emits the shared scores.  q [B,H,Lq,d_k], k/v [B,Hkv,Lk,d_k].
+    Returns (scores [B,H,Lq,Lk] or None, out [B,Lq,H,d_k] or None)."""
+    B, H, Lq, dk = q.shape
+    _, Hkv, Lk, _ = k.shape
+    odt, of32 = _out_dtype(q.dtype, out.dtype if out is not None else out_dtype)
+    desc = make_desc(q.dtype, B, H, Hkv, Lq, Lk, dk, causal=int(causal), std_scale=std_scale,
+                     out_f32=of32)
+    sdt = score_dtype(q.dtype)
+    if want_scores and scores_out is None:
+        scores_out = torch.empty((B, H, Lq, Lk), dtype=sdt, device=q.device)
+    if v is not None and out is None:
+        out = torch.empty((B, Lq, H, dk), dtype=odt, device=q.device)
+    need = workspace_bytes(desc, WS_STD) if out is not None else 0
+    workspace, wp, wb = _workspace(need, q, workspace)
+    rc = _lib().std_attn_scores(
+        C.byref(desc), _ptr(q, "q", dtype=q.dtype), _ptr(k, "k", (B, Hkv, Lk, dk), q.dtype),
+        _ptr(v, "v", (B, Hkv, Lk, dk), q.dtype), _ptr(scores_out, "scores_out", (B, H, Lq, Lk), sdt),
+        _ptr(out, "out", (B, Lq, H, dk), odt), wp, wb, _stream())
+    if rc:
+        raise LisaError(rc, "std_attn_scores")
+    return scores_out, out
+
+
+def std_attn_decode(q, k_cache, v_cache, Lk, *, want_scores=True, std_scale=0.0,
+                    score_row_out=None, out=None, out_dtype=None, workspace=None):
+    """Decode step of a standard layer: q [B,H,d_k] against caches [B,Hkv,Lmax,d_k], first Lk
+    keys.  Returns (score row [B,H,Lk] or None, out [B,H,d_k])."""
+    B, H, dk = q.shape
+    _, Hkv, Lmax, _ = k_cache.shape
+    odt, of32 = _out_dtype(q.dtype, out.dtype if out is not None else out_dtype)
+    desc = make_desc(q.dtype, B, H, Hkv, 1, Lk, dk, std_scale=std_scale, Lmax=Lmax, out_f32=of32)
+    sdt = score_dtype(q.dtype)
+    if want_scores and score_row_out is None:
+        score_row_out = torch.empty((B, H, Lk), dtype=sdt, device=q.device)
+    if out is None:
+        out = torch.empty((B, H, dk), dtype=odt, device=q.device)
+    need = workspace_bytes(desc, WS_STD)
+    workspace, wp, wb = _workspace(need, q, workspace)
+    rc = _lib().std_attn_scores(
+        C.byref(desc), _ptr(q, "q", dtype=q.dtype), _ptr(k_cache, "k_cache", dtype=q.dtype),
+        _ptr(v_cache, "v_cache", (B, Hkv, Lmax, dk), q.dtype),
+        _ptr(score_row_out, "score_row_out", (B, H, Lk), sdt), _ptr(out, "out", (B, H, dk), odt),
+        wp, wb, _stream())
+    if rc:
+        raise LisaError(rc, "std_attn_scores(decode)")
+    return score_row_out, out
+
+
+def lisa_attn_prefill(q_lr, k_lr, v, scores_prev, w1, w2, *, mix=MIX_ADD, write_scores=True,
+                      causal=True, delta_scale=0.0, out=None, out_dtype=None, scores_out=None,
+                      workspace=None):
+    """One LiSA layer.  q_lr [B,H,Lq,r], k_lr [B,Hkv,Lk,r], v [B,Hkv,Lk,d_k],
+    scores_prev [B,H,Lq,Lk] (score dtype), w1 [Din,F], w2 [F,H].
+    Returns (out [B,Lq,H,d_k], scores_out [B,H,Lq,Lk] or None)."""
+    B, H, Lq, r = q_lr.shape
+    _, Hkv, Lk, dk = v.shape
+    Din, F = w1.shape
+    dt = q_lr.dtype
+    sdt = score_dtype(dt)
+    odt, of32 = _out_dtype(dt, out.dtype if out is not None else out_dtype)
+    desc = make_desc(dt, B, H, Hkv, Lq, Lk, dk, r, F, mix=mix, delta_scale=delta_scale,
+                     causal=int(causal), write_scores=int(write_scores), out_f32=of32)
+    if Din != (2 * H if mix == MIX_CONCAT else H):
+        raise ValueError(f"w1 has {Din} rows, expected {2 * H if mix == MIX_CONCAT else H}")
+    if out is None:
+        out = torch.empty((B, Lq, H, dk), dtype=odt, device=q_lr.device)
+    if write_scores and scores_out is None:
+        scores_out = torch.empty((B, H, Lq, Lk), dtype=sdt, device=q_lr.device)
+    need = workspace_bytes(desc, WS_PREFILL)
+    workspace, wp, wb = _workspace(need, q_lr, workspace)
+    rc = _lib().lisa_attn_prefill(
+        C.byref(desc), _ptr(q_lr, "q_lr", dtype=dt), _ptr(k_lr, "k_lr", (B, Hkv, Lk, r), dt),
+        _ptr(v, "v", (B, Hkv, Lk, dk), dt), _ptr(scores_prev, "scores_prev", (B, H, Lq, Lk), sdt),
+        _ptr(w1, "w1", (Din, F), dt), _ptr(w2, "w2", (F, H), dt), _ptr(out, "out", (B, Lq, H, dk), odt),
+        _ptr(scores_out if write_scores else None, "scores_out", (B, H, Lq, Lk), sdt), wp, wb,
+        _stream())
+    if rc:
+        raise LisaError(rc, "lisa_attn_prefill")
+    return out, (scores_out if write_scores else None)
+
+
+def lisa_attn_decode(q_lr, k_lr_cache, v_cache, Lk, score_row_prev, w1, w2, *, k_lr_new=None,
+                     v_new=None, dim_major=True, mix=MIX_ADD, write_scores=True, delta_scale=0.0,
+                     out=None, out_dtype=None, score_row_out=None, workspace=None):
+    """One LiSA decode step.  q_lr [B,H,r]; k_lr_cache [B,Hkv,r,Lmax] (dim_major) or
+    [B,Hkv,Lmax,r]; v_cache [B,Hkv,Lmax,d_k]; score_row_prev [B,H,Lk].
+    Returns (out [B,H,d_k], score_row_out [B,H,Lk] or None)."""
+    B, H, r = q_lr.shape
+    _, Hkv, Lmax, dk = v_cache.shape
+    Din, F = w1.shape
+    dt = q_lr.dtype
+    sdt = score_dtype(dt)
+    odt, of32 = _out_dtype(dt, out.dtype if out is not None else out_dtype)
+    desc = make_desc(dt, B, H, Hkv, 1, Lk, dk, r, F, mix=mix, delta_scale=delta_scale,
+                     write_scores=int(write_scores), kcache_dim_major=int(dim_major), Lmax=Lmax,
+                     out_f32=of32)
+    kshape = (B, Hkv, r, Lmax) if dim_major else (B, Hkv, Lmax, r)
+    if out is None:
+        out = torch.empty((B, H, dk), dtype=odt, device=q_lr.device)
+    if write_scores and score_row_out is None:
+        score_row_out = torch.empty((B, H, Lk), dtype=sdt, device=q_lr.device)
+    need = workspace_bytes(desc, WS_DECODE)
+    workspace, wp, wb = _workspace(need, q_lr, workspace)
+    rc = _lib().lisa_attn_decode(
+        C.byref(desc), _ptr(q_lr, "q_lr", dtype=dt), _ptr(k_lr_new, "k_lr_new", (B, Hkv, r), dt),
+        _ptr(v_new, "v_new", (B, Hkv, dk), dt), _ptr(k_lr_cache, "k_lr_cache", kshape, dt),
+        _ptr(v_cache, "v_cache", dtype=dt), _ptr(score_row_prev, "score_row_prev", (B, H, Lk), sdt),
+        _ptr(w1, "w1", (Din, F), dt), _ptr(w2, "w2", (F, H), dt), _ptr(out, "out", (B, H, dk), odt),
+        _ptr(score_row_out if write_scores else None, "score_row_out", (B, H, Lk), sdt), wp, wb,
+        _stream())
+    if rc:
+        raise LisaError(rc, "lisa_attn_decode")
+    return out, (score_row_out if write_scores else None)

@@ -1,0 +1,77 @@
+"""Shared helpers of the parity tests: the error metric, the tolerances and adapters that run
+the CPU oracle on (sampled rows of) the tensors handed to the HIP library."""
+import numpy as np
+import torch
+
+from oracle import cref
+
+# Tolerance of the benchmark definition: max abs error relative to the output RMS,
+# 1e-5 for the fp32 path and 2e-2 for the bf16 path.  The RMS is taken per query row
+# (over heads x features for O, over heads x visible keys for A_n): causal rows average
+# very different numbers of values, so their magnitudes differ by an order of magnitude
+# and one global RMS would let the small late rows pass with any error at all while the
+# bf16 rounding of a single large early-row element already exceeds 2e-2 of it.
+TOL = {torch.float32: 1e-5, torch.bfloat16: 2e-2}
+
+
+def f64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to("cpu").double().numpy()
+
+
+def n_visible(i, Lq, Lk, causal=True):
+    return min(Lk, i + 1 + (Lk - Lq)) if causal else Lk
+
+
+def row_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """max over rows of  max|got - ref| / RMS(ref), rows along axis 0."""
+    n = ref.shape[0]
+    g, r = got.reshape(n, -1), ref.reshape(n, -1)
+    rms = np.sqrt((r * r).mean(axis=1))
+    err = np.abs(g - r).max(axis=1)
+    assert np.all(rms > 0), "degenerate reference row"
+    return float((err / rms).max())
+
+
+def row_rel_err_stored_bf16(got: np.ndarray, ref: np.ndarray) -> float:
+    """The same metric for an output that was *stored* as bfloat16: the rounding of the store
+    itself, at most 2^-9 of the element (half a unit in the last of 8 significand bits, 2^-8
+    allowed here to cover the element landing in the next binade), is not charged."""
+    n = ref.shape[0]
+    g, r = got.reshape(n, -1), ref.reshape(n, -1)
+    rms = np.sqrt((r * r).mean(axis=1))
+    err = np.maximum(np.abs(g - r) - np.abs(r) * 2.0 ** -8, 0.0).max(axis=1)
+    return float((err / rms).max())
+
+
+def scores_row_rel_err(got_rows, ref_rows, rows, Lq, Lk, causal=True) -> float:
+    """Same metric for score rows [n,H,Lk], restricted to each row's visible keys."""
+    worst = 0.0
+    for n, i in enumerate(rows):
+        nv = n_visible(int(i), Lq, Lk, causal)
+        worst = max(worst, row_rel_err(got_rows[n:n + 1, :, :nv], ref_rows[n:n + 1, :, :nv]))
+    return worst
+
+
+def oracle_std_rows(q, k, b, rows, scale=None):
+    """Oracle standard scores for batch element b -> [n,H,Lk] float64."""
+    return cref.std_scores_rows(f64(q[b]), f64(k[b]), rows, scale)
+
+
+def oracle_lisa_rows(inp, b, rows, prev_rows, mix=0, delta_scale=None):
+    """Oracle LiSA layer for batch element b on the given rows.
+    prev_rows: float64 [n,H,Lk].  Returns (A_n rows [n,H,Lk], O rows [n,H,dk])."""
+    return cref.lisa_rows(f64(inp["q_lr"][b]), f64(inp["k_lr"][b]), f64(inp["v"][b]),
+                          f64(inp["w1"]), f64(inp["w2"]), rows, prev_rows, mix=mix,
+                          delta_scale=delta_scale)
+
+
+def gather_score_rows(scores: torch.Tensor, b: int, rows) -> np.ndarray:
+    """scores [B,H,Lq,Lk] (device) -> float64 [n,H,Lk] for batch b, rows."""
+    idx = torch.as_tensor(np.asarray(rows), device=scores.device, dtype=torch.long)
+    return f64(scores[b].index_select(1, idx).permute(1, 0, 2))
+
+
+def gather_out_rows(out: torch.Tensor, b: int, rows) -> np.ndarray:
+    """out [B,Lq,H,dk] -> float64 [n,H,dk]."""
+    idx = torch.as_tensor(np.asarray(rows), device=out.device, dtype=torch.long)
+    return f64(out[b].index_select(0, idx))

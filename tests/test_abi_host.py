@@ -1,0 +1,125 @@
+"""Host-only checks of the C ABI (no GPU, no compute call): the shared library loads, exports
+every function include/lisa.h declares, rejects bad arguments before touching HIP, and its
+size helpers equal the closed forms of the paper's memory analysis (Sec. 5.2)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2408_01890_amd import lisa
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = C.c_void_p(0x10000)          # non-NULL, 16-byte aligned, never dereferenced on the host
+ODD = C.c_void_p(0x10008)
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "lisa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"^\s*(?:int|size_t|const char\*)\s+(\w+)\s*\(", text, flags=re.M)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = lisa.library()
+    names = declared_functions()
+    assert {"lisa_attn_prefill", "lisa_attn_decode", "std_attn_scores"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in include/lisa.h but not exported"
+    assert set(names) == set(lisa.EXPORTS)
+
+
+def test_desc_struct_matches_header_field_order():
+    text = open(os.path.join(ROOT, "include", "lisa.h")).read()
+    body = re.search(r"typedef struct lisa_desc \{(.*?)\} lisa_desc;", text, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"(?:int32_t|float)\s+(\w+);", body)
+    assert fields == [f[0] for f in lisa.Desc._fields_]
+    assert C.sizeof(lisa.Desc) == 4 * len(fields)
+
+
+def good_desc(**kw):
+    base = dict(dtype=lisa.BF16, B=2, H=8, Hkv=4, Lq=16, Lk=16, d_k=64, r=11, F=32)
+    base.update(kw)
+    return lisa.make_desc(**base)
+
+
+def call_prefill(desc, **over):
+    args = dict(q_lr=FAKE, k_lr=FAKE, v=FAKE, prev=FAKE, w1=FAKE, w2=FAKE, out=FAKE, sout=FAKE,
+                ws=FAKE, wsb=1 << 40)
+    args.update(over)
+    return lisa.library().lisa_attn_prefill(
+        C.byref(desc), args["q_lr"], args["k_lr"], args["v"], args["prev"], args["w1"], args["w2"],
+        args["out"], args["sout"], args["ws"], args["wsb"], None)
+
+
+def test_prefill_rejects_bad_arguments_before_any_hip_call():
+    assert lisa.supported(good_desc()) == 0
+    assert call_prefill(good_desc(), q_lr=None) == -1                       # NULL
+    assert call_prefill(good_desc(write_scores=1), sout=None) == -1
+    assert call_prefill(good_desc(H=6)) == -2                               # H % Hkv
+    assert call_prefill(good_desc(Lq=32, Lk=16)) == -2                      # causal needs Lk >= Lq
+    assert call_prefill(good_desc(r=0)) == -2
+    assert call_prefill(good_desc(dtype=1, d_k=512)) == -3                  # beyond kernel range
+    assert call_prefill(good_desc(mix=7)) == -3
+    assert call_prefill(good_desc(act=3)) == -3
+    assert call_prefill(good_desc(), v=ODD) == -4                           # alignment
+    assert call_prefill(good_desc(write_scores=0), ws=None, sout=None) == -5   # workspace
+    assert call_prefill(good_desc(write_scores=0), wsb=16, sout=None) == -5
+    d = good_desc(write_scores=1)
+    assert call_prefill(d, prev=FAKE, sout=FAKE) == -2                      # aliasing
+    assert lisa.library().lisa_attn_prefill(None, *([FAKE] * 9), 0, None) == -1
+
+
+def test_decode_and_std_reject_bad_arguments():
+    lib = lisa.library()
+    d = good_desc(Lq=1, Lk=9, Lmax=8, write_scores=1)
+    a = [FAKE] * 11
+    assert lib.lisa_attn_decode(C.byref(d), *a, 0, None) == -2              # Lmax < Lk
+    d = good_desc(Lq=2, Lk=9, Lmax=16, write_scores=1)
+    assert lib.lisa_attn_decode(C.byref(d), *a, 0, None) == -2              # Lq must be 1
+    d = good_desc(Lq=1, Lk=9, Lmax=16, write_scores=1)
+    b = list(a)
+    b[1] = None                                                             # k_lr_new without v_new
+    assert lib.lisa_attn_decode(C.byref(d), *b, 0, None) == -1
+    d = good_desc()
+    assert lib.std_attn_scores(C.byref(d), FAKE, FAKE, None, None, None, None, 0, None) == -1
+    assert lib.std_attn_scores(C.byref(d), FAKE, FAKE, FAKE, FAKE, None, None, 0, None) == -1
+    assert lib.std_attn_scores(C.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, None, 0, None) == -5
+
+
+def test_strerror_is_defined_for_every_status():
+    lib = lisa.library()
+    seen = set()
+    for s in range(0, -7, -1):
+        msg = lib.lisa_strerror(s).decode()
+        assert msg and msg != "unknown status"
+        seen.add(msg)
+    assert len(seen) == 7
+    assert lib.lisa_strerror(-99).decode() == "unknown status"
+
+
+@pytest.mark.parametrize("h,l,dk,r,nS", [(32, 2048, 128, 20, 17), (40, 4096, 128, 20, 26),
+                                          (32, 1024, 128, 22, 27)])
+def test_size_helpers_equal_the_memory_analysis(h, l, dk, r, nS):
+    """Sec. 5.2: a prefill score matrix takes h*l*l*2 bytes, the decode row h*l*2 bytes and the
+    K cache shrinks by |S|*h*l*(d_k-r)*2 bytes (per sequence)."""
+    pre = lisa.make_desc(lisa.BF16, 1, h, h, l, l, dk, r, 64)
+    dec = lisa.make_desc(lisa.BF16, 1, h, h, 1, l, dk, r, 64, Lmax=l)
+    assert lisa.scores_bytes(pre) == h * l * l * 2
+    assert lisa.scores_bytes(dec) == h * l * 2
+    assert lisa.kcache_saved_bytes(pre, nS) == nS * h * l * (dk - r) * 2
+    # net prefill saving of the paper turns negative exactly when l > |S| (d_k - r)
+    net = lisa.kcache_saved_bytes(pre, nS) - lisa.scores_bytes(pre)
+    assert net == h * l * (nS * (dk - r) - l) * 2
+    assert (net < 0) == (l > nS * (dk - r))
+    # the workspace never exceeds one float32 copy of the score tensor
+    assert lisa.workspace_bytes(pre, lisa.WS_PREFILL) <= h * l * l * 4 + 256
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    x = torch.zeros(1, 2, 4, 8)
+    with pytest.raises(ValueError, match="GPU tensor"):
+        lisa.std_attn_scores(x, x)

@@ -1,0 +1,312 @@
+"""Parity of the HIP library against the float64 CPU oracle, element by element, through the
+C ABI.  Small cases compare every row; full-size cases compare sampled rows (rows are
+independent in the definition, so a sampled row is checked exactly)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2408_01890_amd import lisa, synth
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+SENTINEL = 77.0
+
+
+def log(*a):
+    print(*a, flush=True)
+
+
+def check_prefill(cfg, inp, prev, out, scores, rows_by_b, mix=0, causal=True, tag=""):
+    tol = hp.TOL[cfg.torch_dtype]
+    worst_o = worst_a = 0.0
+    Lq, Lk = inp["q_lr"].shape[2], inp["k_lr"].shape[2]
+    for b, rows in rows_by_b.items():
+        prev_rows = hp.gather_score_rows(prev, b, rows)
+        a_ref, o_ref = hp.oracle_lisa_rows(inp, b, rows, prev_rows, mix=mix)
+        worst_o = max(worst_o, hp.row_rel_err(hp.gather_out_rows(out, b, rows), o_ref))
+        if scores is not None:
+            worst_a = max(worst_a, hp.scores_row_rel_err(hp.gather_score_rows(scores, b, rows), a_ref,
+                                                         rows, Lq, Lk, causal))
+    log(f"[parity] {cfg.name}{tag}: path={lisa.last_path()} err_out={worst_o:.3e} "
+        f"err_scores={worst_a:.3e} tol={tol:g}")
+    assert worst_o <= tol, f"O error {worst_o} > {tol}"
+    assert worst_a <= tol, f"A_n error {worst_a} > {tol}"
+
+
+def std_prev(inp):
+    """Previous-layer scores from the library's own standard layer."""
+    prev, _ = lisa.std_attn_scores(inp["q"], inp["k"])
+    return prev
+
+
+# ---------------------------------------------------------------------------------------
+# standard layer
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,H,Hkv,Lq,Lk,dk", [(2, 4, 2, 150, 150, 64), (1, 3, 3, 70, 201, 40),
+                                                (1, 8, 2, 1, 333, 128)])
+def test_std_attn_scores_small(dtype, B, H, Hkv, Lq, Lk, dk):
+    log(f"[case] std small {dtype} B{B} H{H}/{Hkv} Lq{Lq} Lk{Lk} dk{dk}")
+    dt = torch.float32 if dtype == "f32" else torch.bfloat16
+    g = torch.Generator(device=DEV).manual_seed(11)
+    q = torch.randn((B, H, Lq, dk), generator=g, device=DEV).to(dt)
+    k = torch.randn((B, Hkv, Lk, dk), generator=g, device=DEV).to(dt)
+    v = torch.randn((B, Hkv, Lk, dk), generator=g, device=DEV).to(dt)
+    sdt = lisa.score_dtype(dt)
+    scores = torch.full((B, H, Lq, Lk), SENTINEL, dtype=sdt, device=DEV)
+    _, out = lisa.std_attn_scores(q, k, v, scores_out=scores)
+    torch.cuda.synchronize()
+    rows = np.arange(Lq)
+    tol = hp.TOL[dt]
+    for b in range(B):
+        ref = hp.oracle_std_rows(q, k, b, rows)
+        got = hp.gather_score_rows(scores, b, rows)
+        assert hp.scores_row_rel_err(got, ref, rows, Lq, Lk) <= tol
+        for i in rows:                       # invisible entries are never written
+            nv = hp.n_visible(int(i), Lq, Lk)
+            assert np.all(got[i, :, nv:] == SENTINEL)
+        from oracle import cref
+        o_ref = cref.softmax_v_rows(hp.f64(v[b]), rows, ref, Lq)
+        assert hp.row_rel_err(hp.gather_out_rows(out, b, rows), o_ref) <= tol
+    # scores-only and output-only calls give the same results
+    s2, _ = lisa.std_attn_scores(q, k)
+    _, o2 = lisa.std_attn_scores(q, k, v, want_scores=False)
+    torch.cuda.synchronize()
+    vis = torch.ones(Lq, Lk, dtype=torch.bool, device=DEV).tril(Lk - Lq)
+    assert torch.equal(s2[..., vis], scores[..., vis])
+    assert torch.equal(o2, out)
+
+
+# ---------------------------------------------------------------------------------------
+# LiSA prefill: configuration 1 (fp32) in full, with the stress FFNs and both mix modes
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("mix,ffn", [("add", "paper"), ("add", "identity_noise"), ("add", "fan_in"),
+                                     ("concat", "paper"), ("concat", "fan_in")])
+def test_lisa_prefill_c1_all_rows(mix, ffn):
+    cfg = synth.C1
+    log(f"[case] prefill {cfg.name} mix={mix} ffn={ffn}")
+    inp = synth.make_prefill_inputs(cfg, synth.BASE_SEED + 1, DEV, mix=mix, ffn=ffn)
+    prev = std_prev(inp)
+    m = lisa.MIX_CONCAT if mix == "concat" else lisa.MIX_ADD
+    out, scores = lisa.lisa_attn_prefill(inp["q_lr"], inp["k_lr"], inp["v"], prev, inp["w1"],
+                                         inp["w2"], mix=m)
+    torch.cuda.synchronize()
+    # the previous scores themselves: library standard layer vs oracle
+    rows = np.arange(cfg.L)
+    ref_prev = hp.oracle_std_rows(inp["q"], inp["k"], 0, rows)
+    assert hp.scores_row_rel_err(hp.gather_score_rows(prev, 0, rows), ref_prev, rows, cfg.L,
+                                 cfg.L) <= hp.TOL[cfg.torch_dtype]
+    check_prefill(cfg, inp, prev, out, scores, {0: rows}, mix=m, tag=f"/{mix}/{ffn}")
+    # without emitting A_n the output is bit-identical
+    out2, none = lisa.lisa_attn_prefill(inp["q_lr"], inp["k_lr"], inp["v"], prev, inp["w1"],
+                                        inp["w2"], mix=m, write_scores=False)
+    torch.cuda.synchronize()
+    assert none is None and torch.equal(out, out2)
+
+
+SMALL_BF16 = [
+    # name, B, H, Hkv, Lq(=L), d_k, r, F, rope
+    ("llama7b_like_l300", 2, 32, 32, 300, 128, 22, 64, None),
+    ("gqa_l257", 1, 32, 8, 257, 128, 22, 64, 500000.0),
+    ("llama13b_like_l130", 1, 40, 40, 130, 128, 22, 80, None),
+    ("paper_dims_l100", 1, 32, 32, 100, 128, 20, 256, None),
+]
+
+
+@pytest.mark.parametrize("case", SMALL_BF16, ids=[c[0] for c in SMALL_BF16])
+@pytest.mark.parametrize("mix,ffn", [("add", "paper"), ("add", "identity_noise"), ("add", "fan_in"),
+                                     ("concat", "fan_in")])
+def test_lisa_prefill_small_bf16(case, mix, ffn):
+    name, B, H, Hkv, L, dk, r, F, rope = case
+    cfg = synth.LayerShape(name, "bf16", B, H, Hkv, L, 256, dk, r, F, rope)
+    log(f"[case] prefill small {name} mix={mix} ffn={ffn}")
+    inp = synth.make_prefill_inputs(cfg, synth.BASE_SEED + 7, DEV, mix=mix, ffn=ffn)
+    prev = std_prev(inp)
+    m = lisa.MIX_CONCAT if mix == "concat" else lisa.MIX_ADD
+    sent = torch.full((B, H, L, L), SENTINEL, dtype=torch.float16, device=DEV)
+    out, scores = lisa.lisa_attn_prefill(inp["q_lr"], inp["k_lr"], inp["v"], prev, inp["w1"],
+                                         inp["w2"], mix=m, scores_out=sent)
+    torch.cuda.synchronize()
+    rows = np.arange(L)
+    check_prefill(cfg, inp, prev, out, scores, {b: rows for b in range(B)}, mix=m,
+                  tag=f"/{mix}/{ffn}")
+    above = torch.ones(L, L, dtype=torch.bool, device=DEV).triu(1)
+    assert torch.all(scores[..., above] == SENTINEL)      # nothing written above the diagonal
+
+
+def test_bf16_output_option_differs_only_by_the_final_rounding():
+    cfg = synth.LayerShape("bf16out", "bf16", 1, 32, 32, 200, 256, 128, 22, 64)
+    inp = synth.make_prefill_inputs(cfg, 21, DEV, ffn="identity_noise")
+    prev = std_prev(inp)
+    args = (inp["q_lr"], inp["k_lr"], inp["v"], prev, inp["w1"], inp["w2"])
+    o32, _ = lisa.lisa_attn_prefill(*args)
+    o16, _ = lisa.lisa_attn_prefill(*args, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    assert o32.dtype == torch.float32 and o16.dtype == torch.bfloat16
+    assert torch.equal(o32.to(torch.bfloat16), o16)          # same accumulators, one rounding
+    rows = np.arange(cfg.L)
+    _, o_ref = hp.oracle_lisa_rows(inp, 0, rows, hp.gather_score_rows(prev, 0, rows))
+    assert hp.row_rel_err_stored_bf16(hp.gather_out_rows(o16, 0, rows), o_ref) <= hp.TOL[torch.bfloat16]
+
+
+def test_lisa_prefill_chunked_rows_match_full_prefill():
+    """Lq < Lk: the last 40 query rows against all keys equal the same rows of a full prefill."""
+    cfg = synth.LayerShape("chunk", "bf16", 1, 8, 4, 200, 128, 64, 11, 32)
+    inp = synth.make_prefill_inputs(cfg, 5, DEV)
+    prev = std_prev(inp)
+    out, scores = lisa.lisa_attn_prefill(inp["q_lr"], inp["k_lr"], inp["v"], prev, inp["w1"],
+                                         inp["w2"])
+    t = 40
+    out_t, scores_t = lisa.lisa_attn_prefill(inp["q_lr"][:, :, -t:].contiguous(), inp["k_lr"],
+                                             inp["v"], prev[:, :, -t:].contiguous(), inp["w1"],
+                                             inp["w2"])
+    torch.cuda.synchronize()
+    assert torch.equal(out_t, out[:, -t:])
+    vis = torch.ones(t, cfg.L, dtype=torch.bool, device=DEV).tril(cfg.L - t)
+    assert torch.equal(scores_t[..., vis], scores[:, :, -t:][..., vis])
+
+
+# ---------------------------------------------------------------------------------------
+# LiSA prefill at the benchmark sizes
+# ---------------------------------------------------------------------------------------
+def test_lisa_prefill_c2_full_size_all_rows():
+    cfg = synth.C2
+    log(f"[case] prefill {cfg.name} full")
+    inp = synth.make_prefill_inputs(cfg, synth.BASE_SEED + 2, DEV)
+    prev = std_prev(inp)
+    out, scores = lisa.lisa_attn_prefill(inp["q_lr"], inp["k_lr"], inp["v"], prev, inp["w1"],
+                                         inp["w2"])
+    torch.cuda.synchronize()
+    rows = np.arange(cfg.L)
+    ref_prev = hp.oracle_std_rows(inp["q"], inp["k"], 0, rows)
+    assert hp.scores_row_rel_err(hp.gather_score_rows(prev, 0, rows), ref_prev, rows, cfg.L,
+                                 cfg.L) <= hp.TOL[cfg.torch_dtype]
+    check_prefill(cfg, inp, prev, out, scores, {0: rows})
+
+
+@pytest.mark.parametrize("cfg,ffn", [(synth.C3, "paper"), (synth.C3, "identity_noise"),
+                                     (synth.C4, "paper"), (synth.C4, "fan_in")],
+                         ids=["c3", "c3_identity_noise", "c4", "c4_fan_in"])
+def test_lisa_prefill_full_size_sampled_rows(cfg, ffn):
+    log(f"[case] prefill {cfg.name} ffn={ffn} sampled")
+    idx = 3 if cfg is synth.C3 else 4
+    inp = synth.make_prefill_inputs(cfg, synth.BASE_SEED + idx, DEV, ffn=ffn)
+    prev = std_prev(inp)
+    del inp["q"], inp["k"]
+    out, scores = lisa.lisa_attn_prefill(inp["q_lr"], inp["k_lr"], inp["v"], prev, inp["w1"],
+                                         inp["w2"])
+    torch.cuda.synchronize()
+    per_b = 256 // cfg.B + 24
+    rows_by_b = {b: synth.sample_rows(cfg.L, per_b, 100 + b) for b in range(cfg.B)}
+    assert sum(len(r) for r in rows_by_b.values()) >= 256
+    check_prefill(cfg, inp, prev, out, scores, rows_by_b, tag=f"/{ffn}")
+
+
+# ---------------------------------------------------------------------------------------
+# decode
+# ---------------------------------------------------------------------------------------
+def oracle_decode_lisa(layer, b, Lk, prev_row, dim_major, mix=0):
+    from oracle import cref
+    kc = layer["k_lr_cache"][b]
+    kc = kc.permute(0, 2, 1) if dim_major else kc
+    k_lr = hp.f64(kc[:, :Lk])
+    v = hp.f64(layer["v_cache"][b][:, :Lk])
+    q_lr = hp.f64(layer["q_lr"][b])[:, None, :]
+    return cref.lisa_rows(q_lr, k_lr, v, hp.f64(layer["w1"]), hp.f64(layer["w2"]), [0],
+                          prev_row[None], mix=mix)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dim_major", [True, False])
+@pytest.mark.parametrize("append", [False, True])
+def test_lisa_decode_small(dtype, dim_major, append):
+    stk = synth.DecodeStack("dec_small", dtype, 3, 8, 4, 180, 128, 64, 11, 32, 2, 1)
+    log(f"[case] decode small {dtype} dim_major={dim_major} append={append}")
+    Lk, Lmax = stk.ctx + 1, stk.ctx + 12
+    layer = synth.make_decode_layer(stk, 1, device=DEV, dim_major=dim_major, Lmax=Lmax)
+    sdt = stk.score_dtype
+    g = torch.Generator(device=DEV).manual_seed(3)
+    prev = torch.randn((stk.B, stk.H, Lk), generator=g, device=DEV).to(sdt)
+    kc, vc = layer["k_lr_cache"].clone(), layer["v_cache"].clone()
+    kw = {}
+    if append:                                  # wipe the slot, let the call store the new token
+        if dim_major:
+            kc[:, :, :, Lk - 1] = 0
+        else:
+            kc[:, :, Lk - 1] = 0
+        vc[:, :, Lk - 1] = 0
+        kw = dict(k_lr_new=layer["k_lr_new"], v_new=layer["v_new"])
+    out, row = lisa.lisa_attn_decode(layer["q_lr"], kc, vc, Lk, prev, layer["w1"], layer["w2"],
+                                     dim_major=dim_major, **kw)
+    torch.cuda.synchronize()
+    assert torch.equal(kc, layer["k_lr_cache"]) and torch.equal(vc, layer["v_cache"])
+    tol = hp.TOL[stk.torch_dtype]
+    for b in range(stk.B):
+        a_ref, o_ref = oracle_decode_lisa(layer, b, Lk, hp.f64(prev[b]), dim_major)
+        assert hp.row_rel_err(hp.f64(row[b])[None], a_ref) <= tol
+        assert hp.row_rel_err(hp.f64(out[b])[None], o_ref) <= tol
+
+
+def test_decode_equals_last_prefill_row_on_gpu():
+    cfg = synth.LayerShape("pd", "bf16", 2, 8, 8, 97, 128, 64, 12, 32)
+    inp = synth.make_prefill_inputs(cfg, 9, DEV)
+    prev = std_prev(inp)
+    out, scores = lisa.lisa_attn_prefill(inp["q_lr"], inp["k_lr"], inp["v"], prev, inp["w1"],
+                                         inp["w2"])
+    L = cfg.L
+    o_d, row = lisa.lisa_attn_decode(inp["q_lr"][:, :, L - 1].contiguous(), inp["k_lr"], inp["v"], L,
+                                     prev[:, :, L - 1].contiguous(), inp["w1"], inp["w2"],
+                                     dim_major=False)
+    torch.cuda.synchronize()
+    tol = hp.TOL[cfg.torch_dtype]
+    assert hp.row_rel_err(hp.f64(row), hp.f64(scores[:, :, L - 1])) <= tol
+    assert hp.row_rel_err(hp.f64(o_d), hp.f64(out[:, L - 1])) <= tol
+
+
+def test_decode_stack_c5_shape_sampled_sequences():
+    """Configuration 5 at its real per-layer shape (B=64, ctx=4096), chained through the score
+    row: 2 standard layers then 4 LiSA layers (the full 32-layer stack is what bench.py runs;
+    every layer here has the shape and launch configuration of a layer there)."""
+    stk = synth.C5.scaled(n_layers=6, n_std=2)
+    log(f"[case] decode stack {stk.name} layers={stk.n_layers}")
+    Lk = stk.ctx + 1
+    from oracle import cref
+    sample_b = [0, 17, 63]
+    row = None
+    ref_rows = {}
+    tol = hp.TOL[stk.torch_dtype]
+    for n in range(stk.n_layers):
+        layer = synth.make_decode_layer(stk, n, device=DEV, dim_major=True)
+        if n < stk.n_std:
+            row, out = lisa.std_attn_decode(layer["q"], layer["k_cache"], layer["v_cache"], Lk)
+        else:
+            out, row_new = lisa.lisa_attn_decode(layer["q_lr"], layer["k_lr_cache"], layer["v_cache"],
+                                                 Lk, row, layer["w1"], layer["w2"], dim_major=True)
+        torch.cuda.synchronize()
+        for b in sample_b:
+            if n < stk.n_std:
+                a_ref = cref.std_scores_rows(hp.f64(layer["q"][b])[:, None, :],
+                                             hp.f64(layer["k_cache"][b][:, :Lk]), [0])
+                o_ref = cref.softmax_v_rows(hp.f64(layer["v_cache"][b][:, :Lk]), [0], a_ref, 1)
+                got_row = row
+            else:
+                # the oracle consumes exactly the (rounded) score row the library consumed
+                a_ref, o_ref = oracle_decode_lisa(layer, b, Lk, hp.f64(row[b]), True)
+                got_row = row_new
+            ea = hp.row_rel_err(hp.f64(got_row[b])[None], a_ref)
+            eo = hp.row_rel_err(hp.f64(out[b])[None], o_ref)
+            log(f"[parity] decode layer {n} b={b} path={lisa.last_path()} err_row={ea:.3e} err_out={eo:.3e}")
+            assert ea <= tol and eo <= tol
+        if n >= stk.n_std:
+            row = row_new
+        del layer
+
+
+def test_error_path_on_gpu_is_reported_not_raised_as_fault():
+    q = torch.zeros((1, 2, 4, 8), device=DEV, dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        lisa.std_attn_scores(q, q.transpose(2, 3))            # non-contiguous / wrong shape
+    with pytest.raises(lisa.LisaError) as e:
+        lisa.std_attn_scores(torch.zeros((1, 3, 4, 8), device=DEV, dtype=torch.bfloat16), q)
+    assert e.value.status == -2
