@@ -1,0 +1,205 @@
+// Decode-step kernels (one query row per sequence, Sec. 2.2 / Sec. 5.2): a split-over-context
+// pass that streams the key-side cache once, then a small combine.
+//
+// k_decode_part: one workgroup = one sequence x DEC_CK consecutive keys x ALL heads (the
+// alignment FFN couples the heads of a position, Sec. 5.1).  Stages:
+//   S1  scores of the chunk into LDS:   LiSA  a_delta[h][j] = scale <q_lr[h], K_LR[kv][j]>  (Eq. 3)
+//                                       std   a[h][j]       = scale <q[h],    K[kv][j]>     (Eq. 2)
+//   S2  (LiSA) A_n = FFN(A_{n-1}) + a_delta on the matrix cores, 16 positions per MFMA block
+//   S3  per head: chunk maximum, p = exp(a - max), chunk sum; the score row is stored here
+//   S4  per head: partial O = sum_j p[j] V[kv][j][:]  -- the HBM stream that dominates
+// k_decode_combine merges the per-chunk (max, sum, O) triples of each (sequence, head).
+//
+// The V (and, for a standard layer, K) stream is read with 16-byte loads, 8 features per lane,
+// 64 / (d_k / 8) keys per wave instruction, so every wave instruction covers 1 KB contiguous.
+#pragma once
+#include "kernels_generic.h"
+#include "mfma_ffn.h"
+
+namespace lisa {
+
+constexpr int DEC_CK = 128;      // keys per workgroup
+constexpr int DEC_THREADS = 256;
+
+struct DecodeArgs {
+  const bf16_t* q;       // LiSA: q_lr [B,H,r]; std: q [B,H,d_k]
+  const bf16_t* kc;      // LiSA: K_LR cache; std: K cache
+  KeyStrides ks;
+  const bf16_t* vc;      // V cache
+  KeyStrides vs;
+  const half_t* prev;    // [B,H,Lk]   (LiSA)
+  const bf16_t* w1;      // [H,F]      (LiSA)
+  const bf16_t* w2;      // [F,H]      (LiSA)
+  half_t* row_out;       // [B,H,Lk] or null
+  float* part_o;         // [B][n_chunk][H][d_k]
+  float* part_ml;        // [B][n_chunk][H][2]  (max, sum)
+  int H, Hkv, Lk, r, F, n_chunk;
+  float scale;
+};
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// LISA_MODE: 1 = LiSA layer, 0 = standard layer.  DK: head dimension (64 or 128).
+template <int LISA_MODE, int HB, int FS, int DK>
+__global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
+  constexpr int LPK = DK / 8;        // lanes per key in the 16-byte streams
+  constexpr int KPW = 64 / LPK;      // keys per wave instruction
+  extern __shared__ float dec_lds[];
+  const int H = a.H, Lk = a.Lk;
+  float* a_s = dec_lds;                       // [H][DEC_CK] scores, later probabilities
+  float* q_s = a_s + H * DEC_CK;              // LiSA: [H][r]
+  const int chunk = blockIdx.x, b = blockIdx.y;
+  const int j0 = chunk * DEC_CK;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int group = H / a.Hkv;
+  const int n_here = min(DEC_CK, Lk - j0);    // keys of this chunk that exist (>= 1)
+
+  // ---- S1 ------------------------------------------------------------------------------
+  if (LISA_MODE) {
+    for (int e = tid; e < H * a.r; e += DEC_THREADS)
+      q_s[e] = elem<bf16_t>::load(a.q + (size_t)b * H * a.r + e);
+    __syncthreads();
+    const int pj = tid & (DEC_CK - 1), sl = tid / DEC_CK;       // 2 head slices
+    const int j = j0 + pj;
+    for (int h = sl; h < H; h += DEC_THREADS / DEC_CK) {
+      float acc = 0.f;
+      if (j < Lk) {
+        const bf16_t* kp = a.kc + b * a.ks.b + (h / group) * a.ks.h + j * a.ks.j;
+        for (int t = 0; t < a.r; ++t) acc += q_s[h * a.r + t] * elem<bf16_t>::load(kp + t * a.ks.t);
+      }
+      a_s[h * DEC_CK + pj] = acc * a.scale;
+    }
+  } else {
+    const int js = lane / LPK, dc = lane % LPK;
+    for (int h = wv; h < H; h += 4) {
+      float qf[8];
+      const u32x4 qv = *(const u32x4*)(a.q + ((size_t)b * H + h) * DK + dc * 8);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        qf[2 * e] = bf16_bits_to_f32(qv[e] & 0xffffu);
+        qf[2 * e + 1] = bf16_bits_to_f32(qv[e] >> 16);
+      }
+      const bf16_t* kb = a.kc + b * a.ks.b + (h / group) * a.ks.h + dc * 8;
+#pragma unroll 4
+      for (int jj = js; jj < DEC_CK; jj += KPW) {
+        float acc = 0.f;
+        if (jj < n_here) {
+          const u32x4 kvv = *(const u32x4*)(kb + (size_t)(j0 + jj) * a.ks.j);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            acc += qf[2 * e] * bf16_bits_to_f32(kvv[e] & 0xffffu);
+            acc += qf[2 * e + 1] * bf16_bits_to_f32(kvv[e] >> 16);
+          }
+        }
+#pragma unroll
+        for (int o = LPK / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+        if (dc == 0) a_s[h * DEC_CK + jj] = acc * a.scale;
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- S2: A_n = FFN(A_{n-1}) + a_delta ------------------------------------------------
+  if (LISA_MODE) {
+    MfmaFfn<HB, FS> ffn;
+    ffn.load(a.w1, a.w2, H, a.F);
+    const int c = lane & 15, g = lane >> 4;
+    for (int nb = wv; nb < DEC_CK / 16; nb += 4) {
+      const int pj = nb * 16 + c, j = j0 + pj;
+      f16x8 x[MfmaFfn<HB, FS>::KS];
+#pragma unroll
+      for (int ks = 0; ks < MfmaFfn<HB, FS>::KS; ++ks)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int ch = 32 * ks + 8 * g + e;
+          x[ks][e] = (ch < H && j < Lk) ? a.prev[((size_t)b * H + ch) * Lk + j] : (_Float16)0.f;
+        }
+      f32x4 y[HB];
+      ffn.apply(x, y);
+#pragma unroll
+      for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int h = 16 * hb + 4 * g + v;
+          if (h < H) a_s[h * DEC_CK + pj] += y[hb][v];
+        }
+    }
+    __syncthreads();
+  }
+
+  // ---- S3: chunk softmax statistics, score row ------------------------------------------
+  for (int h = wv; h < H; h += 4) {
+    float* row = a_s + h * DEC_CK;
+    const bool va = lane < n_here, vb = lane + 64 < n_here;
+    const float sa = va ? row[lane] : -INFINITY, sb = vb ? row[lane + 64] : -INFINITY;
+    if (a.row_out) {
+      half_t* ro = a.row_out + ((size_t)b * H + h) * Lk + j0;
+      if (va) ro[lane] = f32_to_half_sat(sa);
+      if (vb) ro[lane + 64] = f32_to_half_sat(sb);
+    }
+    const float m = wave_max(fmaxf(sa, sb));
+    const float pa = va ? __expf(sa - m) : 0.f, pb = vb ? __expf(sb - m) : 0.f;
+    const float s = wave_sum(pa + pb);
+    row[lane] = pa;
+    row[lane + 64] = pb;
+    if (lane == 0) {
+      float* ml = a.part_ml + (((size_t)b * a.n_chunk + chunk) * H + h) * 2;
+      ml[0] = m;
+      ml[1] = s;
+    }
+  }
+  __syncthreads();
+
+  // ---- S4: partial O ---------------------------------------------------------------------
+  {
+    const int js = lane / LPK, dc = lane % LPK;
+    for (int h = wv; h < H; h += 4) {
+      const bf16_t* vb = a.vc + b * a.vs.b + (h / group) * a.vs.h + dc * 8;
+      const float* p = a_s + h * DEC_CK;
+      float acc[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+#pragma unroll 8
+      for (int jj = js; jj < DEC_CK; jj += KPW) {
+        if (jj < n_here) {
+          const u32x4 vv = *(const u32x4*)(vb + (size_t)(j0 + jj) * a.vs.j);
+          const float pj = p[jj];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            acc[2 * e] += pj * bf16_bits_to_f32(vv[e] & 0xffffu);
+            acc[2 * e + 1] += pj * bf16_bits_to_f32(vv[e] >> 16);
+          }
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+#pragma unroll
+        for (int o = LPK; o < 64; o <<= 1) acc[e] += __shfl_xor(acc[e], o, 64);
+      if (js == 0) {
+        float* po = a.part_o + (((size_t)b * a.n_chunk + chunk) * H + h) * DK + dc * 8;
+        *(float4*)po = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        *(float4*)(po + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+      }
+    }
+  }
+}
+
+// out[b][h][:] = sum_c e^{m_c - M} O_c / sum_c e^{m_c - M} s_c,  M = max_c m_c.
+// grid (H, B), block DK.
+template <typename O, int DK>
+__global__ void k_decode_combine(const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                                 O* __restrict__ out, int H, int n_chunk) {
+  const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+  float M = -INFINITY;
+  for (int c = 0; c < n_chunk; ++c) M = fmaxf(M, part_ml[(((size_t)b * n_chunk + c) * H + h) * 2]);
+  float num = 0.f, den = 0.f;
+  for (int c = 0; c < n_chunk; ++c) {
+    const size_t at = ((size_t)b * n_chunk + c) * H + h;
+    const float w = __expf(part_ml[at * 2] - M);
+    den += w * part_ml[at * 2 + 1];
+    num += w * part_o[at * DK + d];
+  }
+  elem<O>::store(out + ((size_t)b * H + h) * DK + d, num / den);
+}
+
+}  // namespace lisa

@@ -9,6 +9,7 @@
 #include <cstring>
 #include <vector>
 
+#include "kernels_decode.h"
 #include "kernels_generic.h"
 
 using namespace lisa;
@@ -209,6 +210,93 @@ int run_lisa(const lisa_desc* d, const void* q_lr, const void* k_lr, KeyStrides 
   return rc;
 }
 
+// ---- split-context decode (bf16) -----------------------------------------------------
+// Shapes the decode kernels are instantiated for.
+bool decode_fast_ok(const lisa_desc* d, bool lisa_layer) {
+  if (d->dtype != LISA_BF16 || d->Lq != 1) return false;
+  if (d->d_k != 64 && d->d_k != 128) return false;
+  if (d->H > 64) return false;
+  if (lisa_layer) {
+    if (d->mix != LISA_MIX_ADD || d->act != LISA_ACT_RELU) return false;
+    if (d->F > 128 || d->r > 64) return false;
+  }
+  return true;
+}
+
+int decode_chunks(const lisa_desc* d) { return (d->Lk + DEC_CK - 1) / DEC_CK; }
+
+size_t decode_fast_bytes(const lisa_desc* d) {
+  const size_t units = (size_t)d->B * decode_chunks(d) * d->H;
+  return round_up(units * d->d_k * sizeof(float), 256) + round_up(units * 2 * sizeof(float), 256);
+}
+
+template <int LISA_MODE, int HB, int FS>
+int launch_decode_part_dk(const lisa_desc* d, const DecodeArgs& a, size_t lds, hipStream_t st) {
+  dim3 grid(a.n_chunk, d->B);
+  StageScope prof(LISA_MODE ? "k_decode_part_lisa" : "k_decode_part_std", st);
+  if (d->d_k == 128)
+    k_decode_part<LISA_MODE, HB, FS, 128><<<grid, DEC_THREADS, lds, st>>>(a);
+  else
+    k_decode_part<LISA_MODE, HB, FS, 64><<<grid, DEC_THREADS, lds, st>>>(a);
+  return check_launch();
+}
+
+template <int HB>
+int launch_decode_lisa_fs(const lisa_desc* d, const DecodeArgs& a, size_t lds, hipStream_t st) {
+  switch ((d->F + 31) / 32) {
+    case 1: return launch_decode_part_dk<1, HB, 1>(d, a, lds, st);
+    case 2: return launch_decode_part_dk<1, HB, 2>(d, a, lds, st);
+    case 3: return launch_decode_part_dk<1, HB, 3>(d, a, lds, st);
+    default: return launch_decode_part_dk<1, HB, 4>(d, a, lds, st);
+  }
+}
+
+int run_decode_fast(const lisa_desc* d, bool lisa_layer, DecodeArgs a, void* out, void* workspace,
+                    hipStream_t st) {
+  const size_t units = (size_t)d->B * decode_chunks(d) * d->H;
+  a.part_o = (float*)workspace;
+  a.part_ml = (float*)((char*)workspace + round_up(units * d->d_k * sizeof(float), 256));
+  a.H = d->H;
+  a.Hkv = d->Hkv;
+  a.Lk = d->Lk;
+  a.r = d->r;
+  a.F = d->F;
+  a.n_chunk = decode_chunks(d);
+  const size_t lds = ((size_t)d->H * DEC_CK + (lisa_layer ? (size_t)d->H * d->r : 0)) * sizeof(float);
+  int rc;
+  if (lisa_layer) {
+    a.scale = pick_scale(d->delta_scale, d->r);
+    switch ((d->H + 15) / 16) {
+      case 1: rc = launch_decode_lisa_fs<1>(d, a, lds, st); break;
+      case 2: rc = launch_decode_lisa_fs<2>(d, a, lds, st); break;
+      case 3: rc = launch_decode_lisa_fs<3>(d, a, lds, st); break;
+      default: rc = launch_decode_lisa_fs<4>(d, a, lds, st); break;
+    }
+  } else {
+    a.scale = pick_scale(d->std_scale, d->d_k);
+    rc = launch_decode_part_dk<0, 1, 1>(d, a, lds, st);
+  }
+  if (rc) return rc;
+  {
+    dim3 grid(d->H, d->B);
+    StageScope prof("k_decode_combine", st);
+    if (d->d_k == 128) {
+      if (d->out_f32)
+        k_decode_combine<float, 128><<<grid, 128, 0, st>>>(a.part_o, a.part_ml, (float*)out, d->H, a.n_chunk);
+      else
+        k_decode_combine<bf16_t, 128><<<grid, 128, 0, st>>>(a.part_o, a.part_ml, (bf16_t*)out, d->H, a.n_chunk);
+    } else {
+      if (d->out_f32)
+        k_decode_combine<float, 64><<<grid, 64, 0, st>>>(a.part_o, a.part_ml, (float*)out, d->H, a.n_chunk);
+      else
+        k_decode_combine<bf16_t, 64><<<grid, 64, 0, st>>>(a.part_o, a.part_ml, (bf16_t*)out, d->H, a.n_chunk);
+    }
+    rc = check_launch();
+  }
+  if (rc == LISA_OK) g_path = "decode_split";
+  return rc;
+}
+
 }  // namespace
 
 extern "C" {
@@ -237,10 +325,11 @@ size_t lisa_workspace_bytes(const lisa_desc* desc, int which) {
       return exact_bytes(desc);
     case LISA_WS_DECODE:
       if (check_decode(desc) != LISA_OK) return 0;
-      return exact_bytes(desc);
+      return decode_fast_ok(desc, true) ? decode_fast_bytes(desc) : exact_bytes(desc);
     case LISA_WS_STD:
       if (check_common(desc) != LISA_OK) return 0;
-      return exact_bytes(desc);   // needed only when `out` is requested
+      // needed only when `out` is requested
+      return decode_fast_ok(desc, false) ? decode_fast_bytes(desc) : exact_bytes(desc);
     default:
       return 0;
   }
@@ -365,6 +454,19 @@ int lisa_attn_decode(const lisa_desc* desc, const void* q_lr, const void* k_lr_n
     rc = check_launch();
     if (rc) return rc;
   }
+  if (decode_fast_ok(desc, true)) {
+    DecodeArgs a{};
+    a.q = (const bf16_t*)q_lr;
+    a.kc = (const bf16_t*)k_lr_cache;
+    a.ks = ks;
+    a.vc = (const bf16_t*)v_cache;
+    a.vs = vs;
+    a.prev = (const half_t*)score_row_prev;
+    a.w1 = (const bf16_t*)w1;
+    a.w2 = (const bf16_t*)w2;
+    a.row_out = (half_t*)scores;
+    return run_decode_fast(desc, true, a, out, workspace, st);
+  }
   if (desc->dtype == LISA_F32)
     return run_lisa<float, float>(desc, q_lr, k_lr_cache, ks, v_cache, vs, score_row_prev, w1, w2,
                                   out, scores, exact, st);
@@ -393,6 +495,16 @@ int std_attn_scores(const lisa_desc* desc, const void* q, const void* k, const v
   // With Lq = 1 and Lmax set, K and V are caches of capacity Lmax along the key axis.
   const int cap = (desc->Lq == 1 && desc->Lmax >= desc->Lk) ? desc->Lmax : desc->Lk;
   const KeyStrides ks = dense_keys(desc, cap, desc->d_k);
+  if (out && decode_fast_ok(desc, false)) {
+    DecodeArgs a{};
+    a.q = (const bf16_t*)q;
+    a.kc = (const bf16_t*)k;
+    a.ks = ks;
+    a.vc = (const bf16_t*)v;
+    a.vs = ks;
+    a.row_out = (half_t*)scores_out;
+    return run_decode_fast(desc, false, a, out, workspace, st);
+  }
   if (desc->dtype == LISA_F32) {
     rc = launch_std_scores<float, float>(desc, q, k, ks, scores_out, exact, st);
     if (rc == LISA_OK && out) rc = launch_softmax_v<float>(desc, exact, v, ks, out, st);

@@ -1,0 +1,107 @@
+// The head-alignment FFN of Sec. 5.1 on the matrix cores, for one block of 16 positions.
+//
+//   hid = ReLU(W1^T x),  y = W2^T hid,   x in R^H (scores of all heads at one position)
+//
+// Both products use the 16x16x32 MFMA with the *positions* as the N dimension, so the lane
+// that owns position n after the first product owns it again as B operand of the second: the
+// two products chain through registers with no shuffle.
+//
+// 16x16x32 MFMA operand layout (wave of 64 lanes, g = lane / 16, c = lane % 16):
+//   A (M x K):  lane holds row m = c,  k = 8 g + e        (e = 0..7)
+//   B (K x N):  lane holds col n = c,  k = 8 g + e
+//   D (M x N):  lane holds col n = c,  rows m = 4 g + v    (v = 0..3)
+// The contraction index may be numbered in any order as long as A and B agree.  For the
+// second product it is numbered so that slot (k-step s, g, e) is hidden unit
+//   f = 16 (2 s + e / 4) + 4 g + e % 4,
+// which is exactly the D register v = e % 4 of f-block 2 s + e / 4 of the first product.
+//
+// Precision: x arrives as half (the score type) and W1 is converted to half once (exact for
+// |w| >= 2^-14, absolute error < 2^-25 below); the hidden units are rounded to bfloat16 as
+// operands of the second product; accumulation is float32.
+#pragma once
+#include "lisa_types.h"
+
+namespace lisa {
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ bf16x8 bf16x8_from_bits(u16x8 b) { return __builtin_bit_cast(bf16x8, b); }
+
+// HB = ceil(H / 16) head blocks, FS = ceil(F / 32) hidden k-steps (2 FS hidden blocks of 16),
+// KS = ceil(H / 32) k-steps of the first product.
+template <int HB, int FS>
+struct MfmaFfn {
+  static constexpr int KS = (HB + 1) / 2;
+  static constexpr int FB = 2 * FS;
+  f16x8 w1[FB][KS];   // A operands of the first product:  W1^T, rows f, contraction c
+  bf16x8 w2[HB][FS];  // A operands of the second product: W2^T, rows h, contraction f
+
+  // w1g [H][F], w2g [F][H] bfloat16 in global memory.
+  __device__ __forceinline__ void load(const bf16_t* __restrict__ w1g, const bf16_t* __restrict__ w2g,
+                                       int H, int F) {
+    const int lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
+#pragma unroll
+    for (int fb = 0; fb < FB; ++fb) {
+      const int f = 16 * fb + c;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        f16x8 a;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int ch = 32 * ks + 8 * g + e;
+          const float w = (f < F && ch < H) ? elem<bf16_t>::load(w1g + (size_t)ch * F + f) : 0.f;
+          a[e] = (_Float16)w;
+        }
+        w1[fb][ks] = a;
+      }
+    }
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+      const int h = 16 * hb + c;
+#pragma unroll
+      for (int s = 0; s < FS; ++s) {
+        u16x8 a;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int f = 16 * (2 * s + e / 4) + 4 * g + e % 4;
+          a[e] = (f < F && h < H) ? w2g[(size_t)f * H + h].bits : (unsigned short)0;
+        }
+        w2[hb][s] = bf16x8_from_bits(a);
+      }
+    }
+  }
+
+  // x[ks]: B operand of the first product: lane (c, g) holds x[head 32 ks + 8 g + e] of its
+  // position (zero for heads >= H).  y[hb][v] = FFN output of head 16 hb + 4 g + v.
+  __device__ __forceinline__ void apply(const f16x8 (&x)[KS], f32x4 (&y)[HB]) const {
+    bf16x8 hid[FS];
+#pragma unroll
+    for (int s = 0; s < FS; ++s) {
+      u16x8 bits;
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1[2 * s + half][ks], x[ks], acc, 0, 0, 0);
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+          bits[4 * half + v] = (unsigned short)f32_to_bf16_bits(fmaxf(acc[v], 0.f));
+      }
+      hid[s] = bf16x8_from_bits(bits);
+    }
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < FS; ++s)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w2[hb][s], hid[s], acc, 0, 0, 0);
+      y[hb] = acc;
+    }
+  }
+};
+
+}  // namespace lisa

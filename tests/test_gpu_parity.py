@@ -69,13 +69,15 @@ def test_std_attn_scores_small(dtype, B, H, Hkv, Lq, Lk, dk):
         from oracle import cref
         o_ref = cref.softmax_v_rows(hp.f64(v[b]), rows, ref, Lq)
         assert hp.row_rel_err(hp.gather_out_rows(out, b, rows), o_ref) <= tol
-    # scores-only and output-only calls give the same results
+    # scores-only and output-only calls (they may take other kernels) meet the same bar
     s2, _ = lisa.std_attn_scores(q, k)
     _, o2 = lisa.std_attn_scores(q, k, v, want_scores=False)
     torch.cuda.synchronize()
-    vis = torch.ones(Lq, Lk, dtype=torch.bool, device=DEV).tril(Lk - Lq)
-    assert torch.equal(s2[..., vis], scores[..., vis])
-    assert torch.equal(o2, out)
+    for b in range(B):
+        ref = hp.oracle_std_rows(q, k, b, rows)
+        assert hp.scores_row_rel_err(hp.gather_score_rows(s2, b, rows), ref, rows, Lq, Lk) <= tol
+        o_ref = cref.softmax_v_rows(hp.f64(v[b]), rows, ref, Lq)
+        assert hp.row_rel_err(hp.gather_out_rows(o2, b, rows), o_ref) <= tol
 
 
 # ---------------------------------------------------------------------------------------
