@@ -102,12 +102,14 @@ def decode_stack(stk, steps, warmup):
     from paper_2408_01890_amd import lisa, synth
     dev = "cuda"
     Lk = stk.ctx + 1
-    layers = [synth.make_decode_layer(stk, n, device=dev, dim_major=True) for n in range(stk.n_layers)]
+    Lmax = (Lk + 127) // 128 * 128       # cache capacity, as a serving system would allocate it
+    layers = [synth.make_decode_layer(stk, n, device=dev, dim_major=True, Lmax=Lmax)
+              for n in range(stk.n_layers)]
     sdt = stk.score_dtype
     rows = [torch.empty((stk.B, stk.H, Lk), dtype=sdt, device=dev) for _ in range(2)]
     out = torch.empty((stk.B, stk.H, stk.d_k), dtype=torch.float32, device=dev)
     dd = lisa.make_desc(stk.torch_dtype, stk.B, stk.H, stk.Hkv, 1, Lk, stk.d_k, stk.r, stk.F,
-                        write_scores=1, kcache_dim_major=1, Lmax=Lk, out_f32=1)
+                        write_scores=1, kcache_dim_major=1, Lmax=Lmax, out_f32=1)
     ws = torch.empty(max(lisa.workspace_bytes(dd, lisa.WS_DECODE), lisa.workspace_bytes(dd, lisa.WS_STD),
                          256), dtype=torch.uint8, device=dev)
 

@@ -44,10 +44,12 @@ template <int LISA_MODE, int HB, int FS, int DK>
 __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
   constexpr int LPK = DK / 8;        // lanes per key in the 16-byte streams
   constexpr int KPW = 64 / LPK;      // keys per wave instruction
+  constexpr int UN = 8;              // independent loads in flight per lane in the streams
   extern __shared__ float dec_lds[];
   const int H = a.H, Lk = a.Lk;
   float* a_s = dec_lds;                       // [H][DEC_CK] scores, later probabilities
-  float* q_s = a_s + H * DEC_CK;              // LiSA: [H][r]
+  float* q_s = a_s + H * DEC_CK;              // LiSA: [H][r], then the FFN weights
+  unsigned short* w_s = (unsigned short*)(q_s + ((H * a.r + 3) & ~3));   // 16-byte aligned
   const int chunk = blockIdx.x, b = blockIdx.y;
   const int j0 = chunk * DEC_CK;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -58,16 +60,43 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
   if (LISA_MODE) {
     for (int e = tid; e < H * a.r; e += DEC_THREADS)
       q_s[e] = elem<bf16_t>::load(a.q + (size_t)b * H * a.r + e);
+    MfmaFfn<HB, FS>::stage(a.w1, a.w2, H, a.F, w_s, tid, DEC_THREADS);
     __syncthreads();
-    const int pj = tid & (DEC_CK - 1), sl = tid / DEC_CK;       // 2 head slices
-    const int j = j0 + pj;
-    for (int h = sl; h < H; h += DEC_THREADS / DEC_CK) {
-      float acc = 0.f;
-      if (j < Lk) {
-        const bf16_t* kp = a.kc + b * a.ks.b + (h / group) * a.ks.h + j * a.ks.j;
-        for (int t = 0; t < a.r; ++t) acc += q_s[h * a.r + t] * elem<bf16_t>::load(kp + t * a.ks.t);
+    if (a.ks.j == 1 && (a.ks.t & 7) == 0 && (a.ks.h & 7) == 0 && (a.ks.b & 7) == 0) {
+      // dimension-major cache with 16-byte aligned rows: 8 keys per lane and load
+      const int jo = tid & 15, sl = tid >> 4;                    // 16 head slices
+      const int jb = j0 + jo * 8;
+      for (int h = sl; h < H; h += DEC_THREADS / 16) {
+        float acc[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+        if (jb < Lk) {      // the cache holds Lmax >= 8 ceil(Lk / 8) keys per row (ks.t % 8 == 0)
+          const bf16_t* kp = a.kc + b * a.ks.b + (h / group) * a.ks.h + jb;
+          for (int t = 0; t < a.r; ++t) {
+            const u32x4 kvv = *(const u32x4*)(kp + (size_t)t * a.ks.t);
+            const float qt = q_s[h * a.r + t];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              acc[2 * e] += qt * bf16_bits_to_f32(kvv[e] & 0xffffu);
+              acc[2 * e + 1] += qt * bf16_bits_to_f32(kvv[e] >> 16);
+            }
+          }
+        }
+        float4* dst = (float4*)(a_s + h * DEC_CK + jo * 8);
+        dst[0] = make_float4(acc[0] * a.scale, acc[1] * a.scale, acc[2] * a.scale, acc[3] * a.scale);
+        dst[1] = make_float4(acc[4] * a.scale, acc[5] * a.scale, acc[6] * a.scale, acc[7] * a.scale);
       }
-      a_s[h * DEC_CK + pj] = acc * a.scale;
+    } else {
+      const int pj = tid & (DEC_CK - 1), sl = tid / DEC_CK;       // 2 head slices
+      const int j = j0 + pj;
+      for (int h = sl; h < H; h += DEC_THREADS / DEC_CK) {
+        float acc = 0.f;
+        if (j < Lk) {
+          const bf16_t* kp = a.kc + b * a.ks.b + (h / group) * a.ks.h + j * a.ks.j;
+          for (int t = 0; t < a.r; ++t) acc += q_s[h * a.r + t] * elem<bf16_t>::load(kp + t * a.ks.t);
+        }
+        a_s[h * DEC_CK + pj] = acc * a.scale;
+      }
     }
   } else {
     const int js = lane / LPK, dc = lane % LPK;
@@ -80,20 +109,25 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
         qf[2 * e + 1] = bf16_bits_to_f32(qv[e] >> 16);
       }
       const bf16_t* kb = a.kc + b * a.ks.b + (h / group) * a.ks.h + dc * 8;
-#pragma unroll 4
-      for (int jj = js; jj < DEC_CK; jj += KPW) {
-        float acc = 0.f;
-        if (jj < n_here) {
-          const u32x4 kvv = *(const u32x4*)(kb + (size_t)(j0 + jj) * a.ks.j);
+      for (int it = 0; it < DEC_CK / KPW; it += UN) {
+        u32x4 kvv[UN];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            acc += qf[2 * e] * bf16_bits_to_f32(kvv[e] & 0xffffu);
-            acc += qf[2 * e + 1] * bf16_bits_to_f32(kvv[e] >> 16);
-          }
+        for (int u = 0; u < UN; ++u) {
+          const int jc = min(js + (it + u) * KPW, n_here - 1);     // clamped, result unused
+          kvv[u] = *(const u32x4*)(kb + (size_t)(j0 + jc) * a.ks.j);
         }
 #pragma unroll
-        for (int o = LPK / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-        if (dc == 0) a_s[h * DEC_CK + jj] = acc * a.scale;
+        for (int u = 0; u < UN; ++u) {
+          float acc = 0.f;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            acc += qf[2 * e] * bf16_bits_to_f32(kvv[u][e] & 0xffffu);
+            acc += qf[2 * e + 1] * bf16_bits_to_f32(kvv[u][e] >> 16);
+          }
+#pragma unroll
+          for (int o = LPK / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+          if (dc == 0) a_s[h * DEC_CK + js + (it + u) * KPW] = acc * a.scale;
+        }
       }
     }
   }
@@ -102,7 +136,7 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
   // ---- S2: A_n = FFN(A_{n-1}) + a_delta ------------------------------------------------
   if (LISA_MODE) {
     MfmaFfn<HB, FS> ffn;
-    ffn.load(a.w1, a.w2, H, a.F);
+    ffn.fetch(w_s);
     const int c = lane & 15, g = lane >> 4;
     for (int nb = wv; nb < DEC_CK / 16; nb += 4) {
       const int pj = nb * 16 + c, j = j0 + pj;
@@ -159,15 +193,22 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
       float acc[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-#pragma unroll 8
-      for (int jj = js; jj < DEC_CK; jj += KPW) {
-        if (jj < n_here) {
-          const u32x4 vv = *(const u32x4*)(vb + (size_t)(j0 + jj) * a.vs.j);
-          const float pj = p[jj];
+      // Batches of UN independent 16-byte loads; keys past the end of the chunk are clamped to
+      // its last key and carry probability 0 (set in S3), so no lane branches on validity.
+      for (int it = 0; it < DEC_CK / KPW; it += UN) {
+        u32x4 vv[UN];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+          const int jc = min(js + (it + u) * KPW, n_here - 1);
+          vv[u] = *(const u32x4*)(vb + (size_t)(j0 + jc) * a.vs.j);
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+          const float pj = p[js + (it + u) * KPW];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            acc[2 * e] += pj * bf16_bits_to_f32(vv[e] & 0xffffu);
-            acc[2 * e + 1] += pj * bf16_bits_to_f32(vv[e] >> 16);
+            acc[2 * e] += pj * bf16_bits_to_f32(vv[u][e] & 0xffffu);
+            acc[2 * e + 1] += pj * bf16_bits_to_f32(vv[u][e] >> 16);
           }
         }
       }

@@ -233,11 +233,14 @@ size_t decode_fast_bytes(const lisa_desc* d) {
 template <int LISA_MODE, int HB, int FS>
 int launch_decode_part_dk(const lisa_desc* d, const DecodeArgs& a, size_t lds, hipStream_t st) {
   dim3 grid(a.n_chunk, d->B);
+  auto kern = d->d_k == 128 ? k_decode_part<LISA_MODE, HB, FS, 128> : k_decode_part<LISA_MODE, HB, FS, 64>;
+  if (lds > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)lds);
+    if (e != hipSuccess) return hip_fail(e);
+  }
   StageScope prof(LISA_MODE ? "k_decode_part_lisa" : "k_decode_part_std", st);
-  if (d->d_k == 128)
-    k_decode_part<LISA_MODE, HB, FS, 128><<<grid, DEC_THREADS, lds, st>>>(a);
-  else
-    k_decode_part<LISA_MODE, HB, FS, 64><<<grid, DEC_THREADS, lds, st>>>(a);
+  kern<<<grid, DEC_THREADS, lds, st>>>(a);
   return check_launch();
 }
 
@@ -262,9 +265,12 @@ int run_decode_fast(const lisa_desc* d, bool lisa_layer, DecodeArgs a, void* out
   a.r = d->r;
   a.F = d->F;
   a.n_chunk = decode_chunks(d);
-  const size_t lds = ((size_t)d->H * DEC_CK + (lisa_layer ? (size_t)d->H * d->r : 0)) * sizeof(float);
+  size_t lds = (size_t)d->H * DEC_CK * sizeof(float);
   int rc;
   if (lisa_layer) {
+    // + q_lr [H][r] as float + the FFN weights in MFMA operand order (mfma_ffn.h: kStageBytes)
+    const int hb = (d->H + 15) / 16, fs = (d->F + 31) / 32, ks1 = (hb + 1) / 2;
+    lds += (size_t)((d->H * d->r + 3) & ~3) * sizeof(float) + (size_t)(2 * fs * ks1 + hb * fs) * 1024;
     a.scale = pick_scale(d->delta_scale, d->r);
     switch ((d->H + 15) / 16) {
       case 1: rc = launch_decode_lisa_fs<1>(d, a, lds, st); break;

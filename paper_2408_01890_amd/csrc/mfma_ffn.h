@@ -74,6 +74,47 @@ struct MfmaFfn {
     }
   }
 
+  // Bytes of LDS that stage() fills.
+  static constexpr int kStageBytes = (FB * KS + HB * FS) * 64 * 16;
+
+  // Cooperative version of load(): all `nthreads` threads of the workgroup convert the weights
+  // once into `lds` in operand order (operand o, lane l -> 16 bytes at (o * 64 + l) * 16); after
+  // a barrier every wave fetches its registers with fetch().
+  __device__ __forceinline__ static void stage(const bf16_t* __restrict__ w1g,
+                                               const bf16_t* __restrict__ w2g, int H, int F,
+                                               unsigned short* lds, int tid, int nthreads) {
+    for (int idx = tid; idx < FB * KS * 512; idx += nthreads) {
+      const int e = idx & 7, l = (idx >> 3) & 63, o = idx >> 9;
+      const int fb = o / KS, ks = o % KS, c = l & 15, g = l >> 4;
+      const int f = 16 * fb + c, ch = 32 * ks + 8 * g + e;
+      const float w = (f < F && ch < H) ? elem<bf16_t>::load(w1g + (size_t)ch * F + f) : 0.f;
+      const _Float16 hw = (_Float16)w;
+      lds[idx] = __builtin_bit_cast(unsigned short, hw);
+    }
+    unsigned short* lds2 = lds + FB * KS * 512;
+    for (int idx = tid; idx < HB * FS * 512; idx += nthreads) {
+      const int e = idx & 7, l = (idx >> 3) & 63, o = idx >> 9;
+      const int hb = o / FS, s = o % FS, c = l & 15, g = l >> 4;
+      const int h = 16 * hb + c, f = 16 * (2 * s + e / 4) + 4 * g + e % 4;
+      lds2[idx] = (f < F && h < H) ? w2g[(size_t)f * H + h].bits : (unsigned short)0;
+    }
+  }
+
+  __device__ __forceinline__ void fetch(const unsigned short* lds) {
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        w1[fb][ks] = *(const f16x8*)(lds + ((fb * KS + ks) * 64 + lane) * 8);
+    const unsigned short* lds2 = lds + FB * KS * 512;
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+      for (int s = 0; s < FS; ++s)
+        w2[hb][s] = *(const bf16x8*)(lds2 + ((hb * FS + s) * 64 + lane) * 8);
+  }
+
   // x[ks]: B operand of the first product: lane (c, g) holds x[head 32 ks + 8 g + e] of its
   // position (zero for heads >= H).  y[hb][v] = FFN output of head 16 hb + 4 g + v.
   __device__ __forceinline__ void apply(const f16x8 (&x)[KS], f32x4 (&y)[HB]) const {

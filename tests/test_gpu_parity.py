@@ -279,7 +279,9 @@ def test_decode_stack_c5_shape_sampled_sequences():
     ref_rows = {}
     tol = hp.TOL[stk.torch_dtype]
     for n in range(stk.n_layers):
-        layer = synth.make_decode_layer(stk, n, device=DEV, dim_major=True)
+        # odd layers: cache capacity rounded up (16-byte aligned K_LR rows), even: exactly Lk
+        layer = synth.make_decode_layer(stk, n, device=DEV, dim_major=True,
+                                        Lmax=(Lk + 127) // 128 * 128 if n % 2 else Lk)
         if n < stk.n_std:
             row, out = lisa.std_attn_decode(layer["q"], layer["k_cache"], layer["v_cache"], Lk)
         else:
