@@ -1,0 +1,363 @@
+// Fused LiSA prefill layer on the matrix cores (bf16 inputs, half scores, float32 softmax).
+//
+// One workgroup owns 16 query rows of one sequence and a group of GH = NW * HPW heads (NW waves,
+// HPW heads per wave).  The alignment FFN couples the heads of a position (Sec. 5.1), while
+// softmax and P V are per head (Sec. 2.1 Eq. 1-2), so the waves split the work two ways and swap
+// roles inside every tile of 32 keys:
+//   stage A (by position): the 32 blocks of 16 positions (one query row, 16 consecutive keys)
+//           are dealt to the waves; a wave reads A_{n-1} of ALL heads for its block and runs the
+//           FFN on MFMA (mfma_ffn.h), producing y = FFN(A_{n-1}) for the GH heads of the group;
+//           y goes to LDS as float32, indexed [head][row][key].
+//   stage B (by head): wave w owns heads w*HPW .. w*HPW+HPW-1 of the group.  Per head: low-rank
+//           scores A_delta = K_LR Q_LR^T (Eq. 3) by MFMA, A_n = y + A_delta (Eq. 4), half store of
+//           A_n for the next layer, online softmax in float32, O^T += V^T P^T by MFMA.
+// A_n never leaves registers between the FFN and the softmax.  With more than one head group
+// per row block (grid.z > 1) the first FFN layer is recomputed by every group; that buys
+// parallelism and registers (the float32 output accumulators of 16 rows x GH heads x 128 must
+// fit the register file of one compute unit).
+//
+// Layout of the per-head products (16x16x32 MFMA, lane = 16 g + c):
+//   scores  D[key, row] = sum_t K_LR[key,t] Q_LR[row,t]: A = K_LR (rows = keys), B = Q_LR^T.
+//           Two MFMAs cover 32 keys; MFMA u in {0,1} takes keys 8 (m/4) + 4 u + m % 4 for its
+//           rows m, so that lane (c = row, g) ends with the 8 consecutive keys 8 g .. 8 g + 7.
+//   output  D[d, row] = sum_key V^T[d,key] P^T[key,row]: A = V^T (16 features), B = P^T; the
+//           lane's 8 probabilities are exactly its B operand (k = 8 g + e), no data movement.
+//   Both leave "row" on the lane index c, where the softmax statistics of that row live.
+//
+// Inputs are repacked once per call into the workspace: Q_LR and K_LR rows zero-padded from r to
+// 32 elements (64-byte rows, aligned 16-byte operand loads) and V regrouped as
+// [B,Hkv,Lkp/8,d_k,8] (8 consecutive keys of one feature = one 16-byte load, the 128 features of
+// a key chunk contiguous, so the 8 feature blocks of a lane differ by an immediate offset).
+//
+// Software pipeline of one workgroup (tile t = 32 keys):
+//   top of tile t : the A_{n-1} tile t is already in LDS buffer t % 2; barrier B1
+//   stage A(t)    : reads xs[t % 2], writes ys; barrier B2
+//   stage B(t)    : first issues the global loads of the A_{n-1} tile t+1 into registers; then,
+//                   head by head, consumes the K_LR / V operand registers and immediately refills
+//                   them with the operands of the next head (or of the first head of tile t+1), so
+//                   every operand load has one head of work to hide its latency; finally writes
+//                   the A_{n-1} tile t+1 into xs[(t+1) % 2].
+#pragma once
+#include "kernels_generic.h"
+#include "mfma_ffn.h"
+
+namespace lisa {
+
+constexpr int PF_ROWS = 16;       // query rows per workgroup
+constexpr int PF_TK = 32;         // keys per tile
+constexpr int PF_XS_HEAD = PF_ROWS * PF_TK * 2 + 32;        // bytes per head of the A_{n-1} tile
+constexpr int PF_YS_ROW = PF_TK * 4 + 16;                   // bytes per (head,row) of the y tile
+constexpr int PF_YS_HEAD = PF_ROWS * PF_YS_ROW + 16;
+
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int pf_u32x4 __attribute__((ext_vector_type(4)));
+
+struct PrefillArgs {
+  const bf16_t* qp;       // [B,H,Lqp,32]       Q_LR padded (Lqp = Lq rounded up to 16)
+  const bf16_t* kp;       // [B,Hkv,Lkp,32]     K_LR padded (Lkp = Lk rounded up to 64)
+  const bf16_t* vt;       // [B,Hkv,Lkp/8,128,8] V by key chunks
+  const half_t* prev;     // [B,H,Lq,Lk]
+  const bf16_t* w1;
+  const bf16_t* w2;
+  half_t* scores;         // [B,H,Lq,Lk] or null
+  void* out;              // [B,Lq,H,128] float32 or bf16
+  int H, Hkv, Lq, Lk, Lqp, Lkp, F, causal, out_f32;
+  float dscale;
+};
+
+// Grid-stride, block 256: zero-pads the Q_LR / K_LR rows from r to 32 elements.
+__global__ void k_pack_prefill(const bf16_t* __restrict__ q_lr, const bf16_t* __restrict__ k_lr,
+                               bf16_t* __restrict__ qp, bf16_t* __restrict__ kp, int B, int H, int Hkv,
+                               int Lq, int Lk, int Lqp, int Lkp, int r) {
+  const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t nth = (size_t)gridDim.x * blockDim.x;
+  const size_t nq = (size_t)B * H * Lqp * 32, nk = (size_t)B * Hkv * Lkp * 32;
+  bf16_t z;
+  z.bits = 0;
+  for (size_t e = tid; e < nq; e += nth) {
+    const int t = e & 31;
+    const size_t row = e >> 5;
+    const int i = row % Lqp;
+    const size_t bh = row / Lqp;
+    qp[e] = (t < r && i < Lq) ? q_lr[(bh * Lq + i) * r + t] : z;
+  }
+  for (size_t e = tid; e < nk; e += nth) {
+    const int t = e & 31;
+    const size_t row = e >> 5;
+    const int j = row % Lkp;
+    const size_t bh = row / Lkp;
+    kp[e] = (t < r && j < Lk) ? k_lr[(bh * Lk + j) * r + t] : z;
+  }
+}
+
+// vt[bh][j / 8][d][j % 8] = v[bh][j][d] through a 64 x 64 LDS tile (zero for j >= Lk).
+// grid (Lkp / 64, dk / 64, B * Hkv), block 256.
+__global__ __launch_bounds__(256) void k_regroup_v(const bf16_t* __restrict__ v, bf16_t* __restrict__ vt,
+                                                   int Lk, int Lkp, int dk) {
+  __shared__ unsigned short tile[64][66];
+  const int j0 = blockIdx.x * 64, d0 = blockIdx.y * 64;
+  const size_t bh = blockIdx.z;
+  for (int idx = threadIdx.x; idx < 64 * 64; idx += 256) {
+    const int jl = idx >> 6, dl = idx & 63;
+    tile[jl][dl] = (j0 + jl < Lk) ? v[(bh * Lk + j0 + jl) * dk + d0 + dl].bits : (unsigned short)0;
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < 64 * 64; idx += 256) {
+    const int e = idx & 7, dl = (idx >> 3) & 63, jc = idx >> 9;
+    vt[((bh * (Lkp / 8) + j0 / 8 + jc) * dk + d0 + dl) * 8 + e].bits = tile[8 * jc + e][dl];
+  }
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// HB: blocks of 16 input heads (all H); FS: hidden k-steps; HPW heads per wave; NW waves.
+// grid (Lqp / 16, B, H / (NW * HPW)), block NW * 64.  Requires Lk % 8 == 0.
+template <int HB, int FS, int HPW, int NW>
+__global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
+  constexpr int DK = 128;
+  constexpr int THREADS = NW * 64;
+  constexpr int GH = NW * HPW;                       // heads of this workgroup's group
+  constexpr int HBO = (GH + 15) / 16;
+  typedef MfmaFfn<HB, FS, HBO> Ffn;
+  constexpr int KS = Ffn::KS;
+  constexpr int XCH = (HB * 16 * 64 + THREADS - 1) / THREADS;   // 16-byte chunks of a tile per thread
+  extern __shared__ __align__(16) unsigned char pf_lds[];
+  const int H = a.H, Lq = a.Lq, Lk = a.Lk;
+  unsigned char* xs0 = pf_lds;                              // A_{n-1} tiles, half, two buffers
+  unsigned char* ys = xs0 + 2 * H * PF_XS_HEAD;             // y tile of the group, float
+  unsigned short* w_s = (unsigned short*)(ys + GH * PF_YS_HEAD);
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int c = lane & 15, g = lane >> 4;
+  const int b = blockIdx.y;
+  const int hg0 = blockIdx.z * GH;                          // first head of the group
+  const int rb = gridDim.x - 1 - blockIdx.x;                // long row blocks first
+  const int i0 = rb * PF_ROWS;
+  const int shift = Lk - Lq;                                // key j visible to row i iff j <= i + shift
+  const int group = H / a.Hkv;
+  const float LOG2E = 1.4426950408889634f;
+
+  const int i_last = min(i0 + PF_ROWS - 1, Lq - 1);
+  const int n_keys = a.causal ? min(Lk, i_last + 1 + shift) : Lk;
+  const int n_tiles = (n_keys + PF_TK - 1) / PF_TK;
+
+  Ffn::stage(a.w1, a.w2, H, a.F, w_s, tid, THREADS, hg0, GH);
+
+  // A_{n-1} tile: thread -> up to XCH chunks (head, row, 8 keys) of 16 bytes
+  auto load_x = [&](int tile, pf_u32x4 (&xr)[XCH]) {
+    const int j0 = tile * PF_TK;
+#pragma unroll
+    for (int u = 0; u < XCH; ++u) {
+      const int e = tid + u * THREADS;
+      const int q4 = e & 3, i = (e >> 2) & 15, h = min(e >> 6, H - 1);
+      const int row = min(i0 + i, Lq - 1);
+      // keys >= Lk: any in-bounds chunk will do, those positions are masked in stage B
+      const int jc = min(j0 + 8 * q4, Lk - 8);
+      xr[u] = *(const pf_u32x4*)(a.prev + (((size_t)b * H + h) * Lq + row) * Lk + jc);
+    }
+  };
+  auto store_x = [&](unsigned char* xs, const pf_u32x4 (&xr)[XCH]) {
+#pragma unroll
+    for (int u = 0; u < XCH; ++u) {
+      const int e = tid + u * THREADS;
+      const int q4 = e & 3, i = (e >> 2) & 15, h = e >> 6;
+      if (h < H) *(pf_u32x4*)(xs + h * PF_XS_HEAD + i * 64 + q4 * 16) = xr[u];
+    }
+  };
+
+  // per-head state of stage B
+  const int my_row = min(i0 + c, Lq - 1);                   // clamped for loads; stores check i0 + c
+  const int vis_row = a.causal ? min(Lk, my_row + 1 + shift) : Lk;   // keys visible to my row
+  f32x4 o[HPW][DK / 16];
+  float m_run[HPW], l_run[HPW];
+#pragma unroll
+  for (int hh = 0; hh < HPW; ++hh) {
+    m_run[hh] = -INFINITY;
+    l_run[hh] = 0.f;
+#pragma unroll
+    for (int nb = 0; nb < DK / 16; ++nb) o[hh][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  // operand registers of the head that stage B handles next, refilled right after use
+  const int h_first = hg0 + wv * HPW;
+  const int key_in_tile = 8 * (c >> 2) + (c & 3);
+  auto q_ptr = [&](int h) { return a.qp + (((size_t)b * H + h) * a.Lqp + i0 + c) * 32 + 8 * g; };
+  auto k_ptr = [&](int h, int tile) {
+    return a.kp + (((size_t)b * a.Hkv + h / group) * a.Lkp + tile * PF_TK + key_in_tile) * 32 + 8 * g;
+  };
+  auto v_ptr = [&](int h, int tile) {
+    return a.vt + ((((size_t)b * a.Hkv + h / group) * (a.Lkp / 8) + tile * (PF_TK / 8) + g) * DK + c) * 8;
+  };
+  bf16x8 qop, ka, kb, vop[DK / 16];
+  {
+    qop = *(const bf16x8*)q_ptr(h_first);
+    const bf16_t* kp0 = k_ptr(h_first, 0);
+    ka = *(const bf16x8*)kp0;
+    kb = *(const bf16x8*)(kp0 + 4 * 32);
+    const bf16_t* vp0 = v_ptr(h_first, 0);
+#pragma unroll
+    for (int nb = 0; nb < DK / 16; ++nb) vop[nb] = *(const bf16x8*)(vp0 + nb * 128);
+  }
+  {
+    pf_u32x4 xr[XCH];
+    load_x(0, xr);
+    store_x(xs0, xr);
+  }
+
+  for (int tile = 0; tile < n_tiles; ++tile) {
+    const int j0 = tile * PF_TK;
+    unsigned char* xs = xs0 + (tile & 1) * H * PF_XS_HEAD;
+    __syncthreads();                                                     // B1
+    {
+      // ---- stage A: y = FFN(A_{n-1}) for this wave's blocks of 16 positions --------------------
+      // the FFN weights live in registers during stage A only (stage B needs the registers for
+      // the output accumulators and the operand prefetch)
+      Ffn ffn;
+      ffn.fetch(w_s);
+#pragma unroll 1
+      for (int nb = wv; nb < 2 * PF_ROWS; nb += NW) {          // block = (row i, key half kh)
+        const int i = nb >> 1, kh = nb & 1;
+        f16x8 x[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          // transposing LDS read: lane s = 4 k' + q4 of a 16-lane group passes the address of head
+          // k', keys 4 q4 .. 4 q4 + 3; it receives key c of heads k' = 0..3.
+          const int hA = min(32 * ks + 8 * g + (c >> 2), H - 1);
+          const int hB = min(32 * ks + 8 * g + 4 + (c >> 2), H - 1);
+          const unsigned char* pa = xs + hA * PF_XS_HEAD + i * 64 + (16 * kh + 4 * (c & 3)) * 2;
+          const unsigned char* pb = xs + hB * PF_XS_HEAD + i * 64 + (16 * kh + 4 * (c & 3)) * 2;
+          const f16x4 lo = __builtin_bit_cast(
+              f16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)pa));
+          const f16x4 hi = __builtin_bit_cast(
+              f16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)pb));
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const bool la = 32 * ks + 8 * g + e < H, lb = 32 * ks + 8 * g + 4 + e < H;
+            x[ks][e] = la ? lo[e] : (_Float16)0.f;
+            x[ks][4 + e] = lb ? hi[e] : (_Float16)0.f;
+          }
+        }
+        f32x4 y[HBO];
+        ffn.apply(x, y);
+#pragma unroll
+        for (int hb = 0; hb < HBO; ++hb)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int hl = 16 * hb + 4 * g + v;
+            if (hl < GH) *(float*)(ys + hl * PF_YS_HEAD + i * PF_YS_ROW + (16 * kh + c) * 4) = y[hb][v];
+          }
+      }
+    }
+    __syncthreads();                                                     // B2
+
+    // ---- stage B: per head scores, softmax, P V ------------------------------------------------
+    const int tile_n = min(tile + 1, n_tiles - 1);            // next tile (clamped: loads stay valid)
+    pf_u32x4 xr[XCH];
+    load_x(tile_n, xr);
+    const bool full = j0 + PF_TK <= (a.causal ? min(Lk, i0 + 1 + shift) : Lk) && i0 + PF_ROWS <= Lq;
+#pragma unroll
+    for (int hh = 0; hh < HPW; ++hh) {
+      const int h = h_first + hh;
+      const int h_next = hh + 1 < HPW ? h + 1 : h_first;
+      const int t_next = hh + 1 < HPW ? tile : tile_n;
+      // low-rank scores for keys j0 + 8 g + e of row c
+      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+      const f32x4 s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qop, zero, 0, 0, 0);
+      const f32x4 s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb, qop, zero, 0, 0, 0);
+      {
+        qop = *(const bf16x8*)q_ptr(h_next);
+        const bf16_t* kpn = k_ptr(h_next, t_next);
+        ka = *(const bf16x8*)kpn;
+        kb = *(const bf16x8*)(kpn + 4 * 32);
+      }
+      const float* yp = (const float*)(ys + (wv * HPW + hh) * PF_YS_HEAD + c * PF_YS_ROW + 8 * g * 4);
+      const f32x4 y0 = *(const f32x4*)yp, y1 = *(const f32x4*)(yp + 4);
+      float an[8];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        an[e] = s0[e] * a.dscale + y0[e];
+        an[4 + e] = s1[e] * a.dscale + y1[e];
+      }
+      const int jl = j0 + 8 * g;                // first of my 8 keys
+      if (a.scores && i0 + c < Lq) {
+        half_t* sp = a.scores + (((size_t)b * H + h) * Lq + i0 + c) * Lk + jl;
+        if (jl + 8 <= vis_row) {
+          f16x8 hv;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) hv[e] = f32_to_half_sat(an[e]);
+          *(f16x8*)sp = hv;
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (jl + e < vis_row) sp[e] = f32_to_half_sat(an[e]);
+        }
+      }
+      // online softmax (base-2 exponent), statistics of row c kept by all four lanes 16 g + c
+      float mx = -INFINITY;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        if (!full && jl + e >= vis_row) an[e] = -INFINITY;
+        an[e] *= LOG2E;
+        mx = fmaxf(mx, an[e]);
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run[hh], mx);
+      // every row sees key 0, so m_new is finite from the first tile on
+      const float alpha = fast_exp2(m_run[hh] - m_new);
+      m_run[hh] = m_new;
+      float ps = 0.f;
+      u16x8 pbits;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float p = fast_exp2(an[e] - m_new);
+        ps += p;
+        pbits[e] = (unsigned short)f32_to_bf16_bits(p);
+      }
+      l_run[hh] = l_run[hh] * alpha + ps;       // partial sum over my keys; groups merged at the end
+      const bf16x8 pop = bf16x8_from_bits(pbits);
+      const bool rescale = __any(alpha != 1.f);
+      const bf16_t* vpn = v_ptr(h_next, t_next);
+#pragma unroll
+      for (int nb = 0; nb < DK / 16; ++nb) {
+        f32x4 acc = o[hh][nb];
+        if (rescale) {
+#pragma unroll
+          for (int v = 0; v < 4; ++v) acc[v] *= alpha;
+        }
+        o[hh][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[nb], pop, acc, 0, 0, 0);
+        vop[nb] = *(const bf16x8*)(vpn + nb * 128);
+      }
+    }
+    // the other A_{n-1} buffer was last read in stage A of tile - 1, which every wave left
+    // before B2 of this tile
+    store_x(xs0 + ((tile + 1) & 1) * H * PF_XS_HEAD, xr);
+  }
+
+  // ---- epilogue: O[row][h][d] = o / l ---------------------------------------------------------
+#pragma unroll
+  for (int hh = 0; hh < HPW; ++hh) {
+    const int h = h_first + hh;
+    float l = l_run[hh];
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    const float inv = 1.f / l;
+    if (i0 + c < Lq) {
+      const size_t at = (((size_t)b * Lq + i0 + c) * H + h) * DK + 4 * g;
+#pragma unroll
+      for (int nb = 0; nb < DK / 16; ++nb) {
+        const f32x4 acc = o[hh][nb];
+        if (a.out_f32) {
+          *(float4*)((float*)a.out + at + nb * 16) =
+              make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
+        } else {
+          uint2 pk;
+          pk.x = f32_to_bf16_bits(acc[0] * inv) | (f32_to_bf16_bits(acc[1] * inv) << 16);
+          pk.y = f32_to_bf16_bits(acc[2] * inv) | (f32_to_bf16_bits(acc[3] * inv) << 16);
+          *(uint2*)((bf16_t*)a.out + at + nb * 16) = pk;
+        }
+      }
+    }
+  }
+}
+
+}  // namespace lisa

@@ -11,6 +11,7 @@
 
 #include "kernels_decode.h"
 #include "kernels_generic.h"
+#include "kernels_prefill.h"
 
 using namespace lisa;
 
@@ -303,6 +304,102 @@ int run_decode_fast(const lisa_desc* d, bool lisa_layer, DecodeArgs a, void* out
   return rc;
 }
 
+// ---- fused MFMA prefill (bf16) ---------------------------------------------------------
+// Head counts the fused kernel is instantiated for: H -> (waves, heads per wave, head groups).
+bool prefill_fused_ok(const lisa_desc* d) {
+  if (d->dtype != LISA_BF16 || d->d_k != 128) return false;
+  if (d->mix != LISA_MIX_ADD || d->act != LISA_ACT_RELU) return false;
+  if (d->Lk % 8 != 0 || d->F > 128 || d->r > 32) return false;   // 16-byte aligned score rows
+  return d->H == 8 || d->H == 16 || d->H == 24 || d->H == 32 || d->H == 40;
+}
+
+struct PrefillWs {
+  size_t qp, kp, vt, total;   // byte offsets of the packed tensors in the workspace
+  int Lqp, Lkp;
+};
+
+PrefillWs prefill_fused_ws(const lisa_desc* d) {
+  PrefillWs w;
+  w.Lqp = (d->Lq + PF_ROWS - 1) / PF_ROWS * PF_ROWS;
+  w.Lkp = (d->Lk + 63) / 64 * 64;
+  w.qp = 0;
+  w.kp = w.qp + round_up((size_t)d->B * d->H * w.Lqp * 32 * 2, 256);
+  w.vt = w.kp + round_up((size_t)d->B * d->Hkv * w.Lkp * 32 * 2, 256);
+  w.total = w.vt + round_up((size_t)d->B * d->Hkv * d->d_k * w.Lkp * 2, 256);
+  return w;
+}
+
+template <int HB, int FS, int HPW, int NW>
+int launch_prefill_fused_t(const lisa_desc* d, const PrefillArgs& a, hipStream_t st) {
+  constexpr int GH = NW * HPW;
+  typedef MfmaFfn<HB, FS, (GH + 15) / 16> Ffn;
+  const size_t lds = (size_t)d->H * 2 * PF_XS_HEAD + (size_t)GH * PF_YS_HEAD + Ffn::kStageBytes;
+  auto kern = k_lisa_prefill_fused<HB, FS, HPW, NW>;
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)lds);
+  if (e != hipSuccess) return hip_fail(e);
+  dim3 grid(a.Lqp / PF_ROWS, d->B, d->H / GH);
+  StageScope prof("k_lisa_prefill_fused", st);
+  kern<<<grid, NW * 64, lds, st>>>(a);
+  return check_launch();
+}
+
+template <int HB, int HPW, int NW>
+int launch_prefill_fused_fs(const lisa_desc* d, const PrefillArgs& a, hipStream_t st) {
+  switch ((d->F + 31) / 32) {
+    case 1: return launch_prefill_fused_t<HB, 1, HPW, NW>(d, a, st);
+    case 2: return launch_prefill_fused_t<HB, 2, HPW, NW>(d, a, st);
+    case 3: return launch_prefill_fused_t<HB, 3, HPW, NW>(d, a, st);
+    default: return launch_prefill_fused_t<HB, 4, HPW, NW>(d, a, st);
+  }
+}
+
+int run_prefill_fused(const lisa_desc* d, const void* q_lr, const void* k_lr, const void* v,
+                      const void* prev, const void* w1, const void* w2, void* out, void* scores,
+                      void* workspace, hipStream_t st) {
+  const PrefillWs w = prefill_fused_ws(d);
+  char* ws = (char*)workspace;
+  PrefillArgs a{};
+  a.qp = (const bf16_t*)(ws + w.qp);
+  a.kp = (const bf16_t*)(ws + w.kp);
+  a.vt = (const bf16_t*)(ws + w.vt);
+  a.prev = (const half_t*)prev;
+  a.w1 = (const bf16_t*)w1;
+  a.w2 = (const bf16_t*)w2;
+  a.scores = (half_t*)scores;
+  a.out = out;
+  a.H = d->H;
+  a.Hkv = d->Hkv;
+  a.Lq = d->Lq;
+  a.Lk = d->Lk;
+  a.Lqp = w.Lqp;
+  a.Lkp = w.Lkp;
+  a.F = d->F;
+  a.causal = d->causal;
+  a.out_f32 = d->out_f32;
+  a.dscale = pick_scale(d->delta_scale, d->r);
+  {
+    StageScope prof("k_pack_prefill", st);
+    k_pack_prefill<<<1024, 256, 0, st>>>((const bf16_t*)q_lr, (const bf16_t*)k_lr, (bf16_t*)(ws + w.qp),
+                                         (bf16_t*)(ws + w.kp), d->B, d->H, d->Hkv, d->Lq, d->Lk, w.Lqp,
+                                         w.Lkp, d->r);
+    dim3 grid(w.Lkp / 64, d->d_k / 64, d->B * d->Hkv);
+    k_regroup_v<<<grid, 256, 0, st>>>((const bf16_t*)v, (bf16_t*)(ws + w.vt), d->Lk, w.Lkp, d->d_k);
+    int rc = check_launch();
+    if (rc) return rc;
+  }
+  int rc;
+  switch (d->H) {
+    case 8: rc = launch_prefill_fused_fs<1, 1, 8>(d, a, st); break;    // one group of 8 heads
+    case 16: rc = launch_prefill_fused_fs<1, 2, 8>(d, a, st); break;   // one group of 16
+    case 24: rc = launch_prefill_fused_fs<2, 3, 8>(d, a, st); break;   // one group of 24
+    case 32: rc = launch_prefill_fused_fs<2, 2, 8>(d, a, st); break;   // two groups of 16
+    default: rc = launch_prefill_fused_fs<3, 2, 10>(d, a, st); break;  // H = 40: two groups of 20
+  }
+  if (rc == LISA_OK) g_path = "mfma_fused";
+  return rc;
+}
+
 }  // namespace
 
 extern "C" {
@@ -328,7 +425,7 @@ size_t lisa_workspace_bytes(const lisa_desc* desc, int which) {
   switch (which) {
     case LISA_WS_PREFILL:
       if (check_lisa(desc) != LISA_OK) return 0;
-      return exact_bytes(desc);
+      return prefill_fused_ok(desc) ? prefill_fused_ws(desc).total : exact_bytes(desc);
     case LISA_WS_DECODE:
       if (check_decode(desc) != LISA_OK) return 0;
       return decode_fast_ok(desc, true) ? decode_fast_bytes(desc) : exact_bytes(desc);
@@ -416,6 +513,8 @@ int lisa_attn_prefill(const lisa_desc* desc, const void* q_lr, const void* k_lr,
   hipStream_t st = (hipStream_t)hip_stream;
   const KeyStrides ks = dense_keys(desc, desc->Lk, desc->r);
   const KeyStrides vs = dense_keys(desc, desc->Lk, desc->d_k);
+  if (prefill_fused_ok(desc))
+    return run_prefill_fused(desc, q_lr, k_lr, v, scores_prev, w1, w2, out, scores, workspace, st);
   if (desc->dtype == LISA_F32)
     return run_lisa<float, float>(desc, q_lr, k_lr, ks, v, vs, scores_prev, w1, w2, out, scores,
                                   exact, st);

@@ -15,9 +15,12 @@
 //   f = 16 (2 s + e / 4) + 4 g + e % 4,
 // which is exactly the D register v = e % 4 of f-block 2 s + e / 4 of the first product.
 //
-// Precision: x arrives as half (the score type) and W1 is converted to half once (exact for
-// |w| >= 2^-14, absolute error < 2^-25 below); the hidden units are rounded to bfloat16 as
-// operands of the second product; accumulation is float32.
+// Precision: both products run in half (11-bit significand) with float32 accumulation.  x
+// arrives as half (the score type).  W1 and W2 are converted from bfloat16 to half once (exact
+// for |w| >= 2^-14, absolute error < 2^-25 below).  The hidden units are rounded to half, not
+// bfloat16: with an identity-like FFN they carry the scores themselves, and 8 significant bits
+// there would move A_n by up to 2^-9 |A_n|, which the softmax turns into percent-level errors.
+// ReLU and the saturation at the half range are one v_med3.
 #pragma once
 #include "lisa_types.h"
 
@@ -30,73 +33,45 @@ typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
 
 __device__ __forceinline__ bf16x8 bf16x8_from_bits(u16x8 b) { return __builtin_bit_cast(bf16x8, b); }
 
-// HB = ceil(H / 16) head blocks, FS = ceil(F / 32) hidden k-steps (2 FS hidden blocks of 16),
-// KS = ceil(H / 32) k-steps of the first product.
-template <int HB, int FS>
+__device__ __forceinline__ unsigned short half_bits(float f) {
+  const _Float16 h = (_Float16)f;
+  return __builtin_bit_cast(unsigned short, h);
+}
+
+// HB = ceil(H / 16) input head blocks (KS = ceil(H / 32) k-steps of the first product),
+// FS = ceil(F / 32) hidden k-steps (2 FS hidden blocks of 16), HBO = blocks of 16 output heads
+// (the caller may ask for a sub-range of the H output heads: h_first .. h_first + n_out - 1).
+template <int HB, int FS, int HBO = HB>
 struct MfmaFfn {
   static constexpr int KS = (HB + 1) / 2;
   static constexpr int FB = 2 * FS;
   f16x8 w1[FB][KS];   // A operands of the first product:  W1^T, rows f, contraction c
-  bf16x8 w2[HB][FS];  // A operands of the second product: W2^T, rows h, contraction f
-
-  // w1g [H][F], w2g [F][H] bfloat16 in global memory.
-  __device__ __forceinline__ void load(const bf16_t* __restrict__ w1g, const bf16_t* __restrict__ w2g,
-                                       int H, int F) {
-    const int lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
-#pragma unroll
-    for (int fb = 0; fb < FB; ++fb) {
-      const int f = 16 * fb + c;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        f16x8 a;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int ch = 32 * ks + 8 * g + e;
-          const float w = (f < F && ch < H) ? elem<bf16_t>::load(w1g + (size_t)ch * F + f) : 0.f;
-          a[e] = (_Float16)w;
-        }
-        w1[fb][ks] = a;
-      }
-    }
-#pragma unroll
-    for (int hb = 0; hb < HB; ++hb) {
-      const int h = 16 * hb + c;
-#pragma unroll
-      for (int s = 0; s < FS; ++s) {
-        u16x8 a;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int f = 16 * (2 * s + e / 4) + 4 * g + e % 4;
-          a[e] = (f < F && h < H) ? w2g[(size_t)f * H + h].bits : (unsigned short)0;
-        }
-        w2[hb][s] = bf16x8_from_bits(a);
-      }
-    }
-  }
+  f16x8 w2[HBO][FS];  // A operands of the second product: W2^T, rows h, contraction f
 
   // Bytes of LDS that stage() fills.
-  static constexpr int kStageBytes = (FB * KS + HB * FS) * 64 * 16;
+  static constexpr int kStageBytes = (FB * KS + HBO * FS) * 64 * 16;
 
-  // Cooperative version of load(): all `nthreads` threads of the workgroup convert the weights
-  // once into `lds` in operand order (operand o, lane l -> 16 bytes at (o * 64 + l) * 16); after
-  // a barrier every wave fetches its registers with fetch().
+  // All `nthreads` threads of the workgroup convert the weights (w1g [H][F], w2g [F][H],
+  // bfloat16, global memory) once into `lds` in operand order (operand o, lane l -> 16 bytes at
+  // (o * 64 + l) * 16); after a barrier every wave fetches its registers with fetch().
   __device__ __forceinline__ static void stage(const bf16_t* __restrict__ w1g,
                                                const bf16_t* __restrict__ w2g, int H, int F,
-                                               unsigned short* lds, int tid, int nthreads) {
+                                               unsigned short* lds, int tid, int nthreads,
+                                               int h_first = 0, int n_out = 1 << 30) {
     for (int idx = tid; idx < FB * KS * 512; idx += nthreads) {
       const int e = idx & 7, l = (idx >> 3) & 63, o = idx >> 9;
       const int fb = o / KS, ks = o % KS, c = l & 15, g = l >> 4;
       const int f = 16 * fb + c, ch = 32 * ks + 8 * g + e;
       const float w = (f < F && ch < H) ? elem<bf16_t>::load(w1g + (size_t)ch * F + f) : 0.f;
-      const _Float16 hw = (_Float16)w;
-      lds[idx] = __builtin_bit_cast(unsigned short, hw);
+      lds[idx] = half_bits(w);
     }
     unsigned short* lds2 = lds + FB * KS * 512;
-    for (int idx = tid; idx < HB * FS * 512; idx += nthreads) {
+    for (int idx = tid; idx < HBO * FS * 512; idx += nthreads) {
       const int e = idx & 7, l = (idx >> 3) & 63, o = idx >> 9;
       const int hb = o / FS, s = o % FS, c = l & 15, g = l >> 4;
-      const int h = 16 * hb + c, f = 16 * (2 * s + e / 4) + 4 * g + e % 4;
-      lds2[idx] = (f < F && h < H) ? w2g[(size_t)f * H + h].bits : (unsigned short)0;
+      const int hl = 16 * hb + c, h = h_first + hl, f = 16 * (2 * s + e / 4) + 4 * g + e % 4;
+      const float w = (f < F && h < H && hl < n_out) ? elem<bf16_t>::load(w2g + (size_t)f * H + h) : 0.f;
+      lds2[idx] = half_bits(w);
     }
   }
 
@@ -109,19 +84,18 @@ struct MfmaFfn {
         w1[fb][ks] = *(const f16x8*)(lds + ((fb * KS + ks) * 64 + lane) * 8);
     const unsigned short* lds2 = lds + FB * KS * 512;
 #pragma unroll
-    for (int hb = 0; hb < HB; ++hb)
+    for (int hb = 0; hb < HBO; ++hb)
 #pragma unroll
       for (int s = 0; s < FS; ++s)
-        w2[hb][s] = *(const bf16x8*)(lds2 + ((hb * FS + s) * 64 + lane) * 8);
+        w2[hb][s] = *(const f16x8*)(lds2 + ((hb * FS + s) * 64 + lane) * 8);
   }
 
   // x[ks]: B operand of the first product: lane (c, g) holds x[head 32 ks + 8 g + e] of its
-  // position (zero for heads >= H).  y[hb][v] = FFN output of head 16 hb + 4 g + v.
-  __device__ __forceinline__ void apply(const f16x8 (&x)[KS], f32x4 (&y)[HB]) const {
-    bf16x8 hid[FS];
+  // position (zero for heads >= H).  y[hb][v] = FFN output of head h_first + 16 hb + 4 g + v.
+  __device__ __forceinline__ void apply(const f16x8 (&x)[KS], f32x4 (&y)[HBO]) const {
+    f16x8 hid[FS];
 #pragma unroll
     for (int s = 0; s < FS; ++s) {
-      u16x8 bits;
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -130,16 +104,15 @@ struct MfmaFfn {
           acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1[2 * s + half][ks], x[ks], acc, 0, 0, 0);
 #pragma unroll
         for (int v = 0; v < 4; ++v)
-          bits[4 * half + v] = (unsigned short)f32_to_bf16_bits(fmaxf(acc[v], 0.f));
+          hid[s][4 * half + v] = (_Float16)__builtin_amdgcn_fmed3f(acc[v], 0.f, 65504.f);
       }
-      hid[s] = bf16x8_from_bits(bits);
     }
 #pragma unroll
-    for (int hb = 0; hb < HB; ++hb) {
+    for (int hb = 0; hb < HBO; ++hb) {
       f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int s = 0; s < FS; ++s)
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w2[hb][s], hid[s], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(w2[hb][s], hid[s], acc, 0, 0, 0);
       y[hb] = acc;
     }
   }

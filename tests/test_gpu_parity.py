@@ -221,12 +221,12 @@ def oracle_decode_lisa(layer, b, Lk, prev_row, dim_major, mix=0):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("dim_major", [True, False])
-@pytest.mark.parametrize("append", [False, True])
-def test_lisa_decode_small(dtype, dim_major, append):
+@pytest.mark.parametrize("append,ffn", [(False, "paper"), (True, "identity_noise"), (False, "fan_in")])
+def test_lisa_decode_small(dtype, dim_major, append, ffn):
     stk = synth.DecodeStack("dec_small", dtype, 3, 8, 4, 180, 128, 64, 11, 32, 2, 1)
-    log(f"[case] decode small {dtype} dim_major={dim_major} append={append}")
+    log(f"[case] decode small {dtype} dim_major={dim_major} append={append} ffn={ffn}")
     Lk, Lmax = stk.ctx + 1, stk.ctx + 12
-    layer = synth.make_decode_layer(stk, 1, device=DEV, dim_major=dim_major, Lmax=Lmax)
+    layer = synth.make_decode_layer(stk, 1, device=DEV, dim_major=dim_major, Lmax=Lmax, ffn=ffn)
     sdt = stk.score_dtype
     g = torch.Generator(device=DEV).manual_seed(3)
     prev = torch.randn((stk.B, stk.H, Lk), generator=g, device=DEV).to(sdt)
@@ -281,7 +281,8 @@ def test_decode_stack_c5_shape_sampled_sequences():
     for n in range(stk.n_layers):
         # odd layers: cache capacity rounded up (16-byte aligned K_LR rows), even: exactly Lk
         layer = synth.make_decode_layer(stk, n, device=DEV, dim_major=True,
-                                        Lmax=(Lk + 127) // 128 * 128 if n % 2 else Lk)
+                                        Lmax=(Lk + 127) // 128 * 128 if n % 2 else Lk,
+                                        ffn=("paper", "identity_noise", "fan_in")[n % 3])
         if n < stk.n_std:
             row, out = lisa.std_attn_decode(layer["q"], layer["k_cache"], layer["v_cache"], Lk)
         else:
