@@ -140,22 +140,22 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
     const int c = lane & 15, g = lane >> 4;
     for (int nb = wv; nb < DEC_CK / 16; nb += 4) {
       const int pj = nb * 16 + c, j = j0 + pj;
-      f16x8 x[MfmaFfn<HB, FS>::KS];
+      f16x8 x[1][MfmaFfn<HB, FS>::KS];
 #pragma unroll
       for (int ks = 0; ks < MfmaFfn<HB, FS>::KS; ++ks)
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           const int ch = 32 * ks + 8 * g + e;
-          x[ks][e] = (ch < H && j < Lk) ? a.prev[((size_t)b * H + ch) * Lk + j] : (_Float16)0.f;
+          x[0][ks][e] = (ch < H && j < Lk) ? a.prev[((size_t)b * H + ch) * Lk + j] : (_Float16)0.f;
         }
-      f32x4 y[HB];
-      ffn.apply(x, y);
+      f32x4 y[1][HB];
+      ffn.template apply<1>(x, y);
 #pragma unroll
       for (int hb = 0; hb < HB; ++hb)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           const int h = 16 * hb + 4 * g + v;
-          if (h < H) a_s[h * DEC_CK + pj] += y[hb][v];
+          if (h < H) a_s[h * DEC_CK + pj] += y[0][hb][v];
         }
     }
     __syncthreads();

@@ -111,23 +111,53 @@ __global__ __launch_bounds__(256) void k_regroup_v(const bf16_t* __restrict__ v,
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// HB: blocks of 16 input heads (all H); FS: hidden k-steps; HPW heads per wave; NW waves.
-// grid (Lqp / 16, B, H / (NW * HPW)), block NW * 64.  Requires Lk % 8 == 0.
-template <int HB, int FS, int HPW, int NW>
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global
+// load and store in flight (workgroup-scope fence), which would drain the operand prefetch of
+// the pipeline at every tile; the tiles exchange data through LDS alone.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Butterflies across the four 16-lane rows of a wave with the row-swap instructions of gfx950
+// (no LDS crossbar): after both steps every lane 16 g + c holds the reduction over g.
+__device__ __forceinline__ float rows_max(float v) {
+  const unsigned u = __float_as_uint(v);
+  auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);   // rows (0,1) and (2,3) exchanged
+  v = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  const unsigned w = __float_as_uint(v);
+  auto q = __builtin_amdgcn_permlane32_swap(w, w, false, false);   // halves exchanged
+  return fmaxf(__uint_as_float(q[0]), __uint_as_float(q[1]));
+}
+__device__ __forceinline__ float rows_sum(float v) {
+  const unsigned u = __float_as_uint(v);
+  auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  v = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  const unsigned w = __float_as_uint(v);
+  auto q = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+  return __uint_as_float(q[0]) + __uint_as_float(q[1]);
+}
+
+// H = NG * NW * HPW heads in NG groups; NW waves per workgroup, HPW heads per wave; FS hidden
+// k-steps of the FFN.  grid (Lqp / 16, B, NG), block NW * 64.  Requires Lk % 8 == 0.
+template <int NG, int FS, int HPW, int NW>
 __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
   constexpr int DK = 128;
   constexpr int THREADS = NW * 64;
   constexpr int GH = NW * HPW;                       // heads of this workgroup's group
+  constexpr int H = NG * GH;
+  constexpr int HB = (H + 15) / 16;
   constexpr int HBO = (GH + 15) / 16;
   typedef MfmaFfn<HB, FS, HBO> Ffn;
   constexpr int KS = Ffn::KS;
-  constexpr int XCH = (HB * 16 * 64 + THREADS - 1) / THREADS;   // 16-byte chunks of a tile per thread
+  constexpr int XCH = (H * 64 + THREADS - 1) / THREADS;   // 16-byte chunks of a tile per thread
+  constexpr int NBW = ((2 * PF_ROWS + NW - 1) / NW + 1) / 2 * 2;   // position blocks per wave in stage A (even)
   extern __shared__ __align__(16) unsigned char pf_lds[];
-  const int H = a.H, Lq = a.Lq, Lk = a.Lk;
+  const int Lq = a.Lq, Lk = a.Lk;
   unsigned char* xs0 = pf_lds;                              // A_{n-1} tiles, half, two buffers
   unsigned char* ys = xs0 + 2 * H * PF_XS_HEAD;             // y tile of the group, float
   unsigned short* w_s = (unsigned short*)(ys + GH * PF_YS_HEAD);
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform
   const int c = lane & 15, g = lane >> 4;
   const int b = blockIdx.y;
   const int hg0 = blockIdx.z * GH;                          // first head of the group
@@ -140,132 +170,157 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
   const int i_last = min(i0 + PF_ROWS - 1, Lq - 1);
   const int n_keys = a.causal ? min(Lk, i_last + 1 + shift) : Lk;
   const int n_tiles = (n_keys + PF_TK - 1) / PF_TK;
+  // tiles whose 32 keys are visible to all 16 rows (and all 16 rows exist) need no masking
+  const int n_full = (i0 + PF_ROWS <= Lq) ? (a.causal ? min(Lk, i0 + 1 + shift) : Lk) / PF_TK : 0;
 
   Ffn::stage(a.w1, a.w2, H, a.F, w_s, tid, THREADS, hg0, GH);
 
-  // A_{n-1} tile: thread -> up to XCH chunks (head, row, 8 keys) of 16 bytes
+  // ---- A_{n-1} tile: thread -> XCH chunks (head, row, 8 keys) of 16 bytes ------------------------
+  const half_t* xsrc[XCH];       // row start of each chunk's (head, row)
+  int xq4[XCH], xdst[XCH];
+#pragma unroll
+  for (int u = 0; u < XCH; ++u) {
+    const int e = tid + u * THREADS;
+    const int q4 = e & 3, i = (e >> 2) & 15, h = min(e >> 6, H - 1);
+    xsrc[u] = a.prev + (((size_t)b * H + h) * Lq + min(i0 + i, Lq - 1)) * Lk;
+    xq4[u] = 8 * q4;
+    xdst[u] = (e >> 6) < H ? h * PF_XS_HEAD + i * 64 + q4 * 16 : -1;
+  }
   auto load_x = [&](int tile, pf_u32x4 (&xr)[XCH]) {
-    const int j0 = tile * PF_TK;
 #pragma unroll
     for (int u = 0; u < XCH; ++u) {
-      const int e = tid + u * THREADS;
-      const int q4 = e & 3, i = (e >> 2) & 15, h = min(e >> 6, H - 1);
-      const int row = min(i0 + i, Lq - 1);
       // keys >= Lk: any in-bounds chunk will do, those positions are masked in stage B
-      const int jc = min(j0 + 8 * q4, Lk - 8);
-      xr[u] = *(const pf_u32x4*)(a.prev + (((size_t)b * H + h) * Lq + row) * Lk + jc);
+      const int jc = min(tile * PF_TK + xq4[u], Lk - 8);
+      xr[u] = *(const pf_u32x4*)(xsrc[u] + jc);
     }
   };
   auto store_x = [&](unsigned char* xs, const pf_u32x4 (&xr)[XCH]) {
 #pragma unroll
-    for (int u = 0; u < XCH; ++u) {
-      const int e = tid + u * THREADS;
-      const int q4 = e & 3, i = (e >> 2) & 15, h = e >> 6;
-      if (h < H) *(pf_u32x4*)(xs + h * PF_XS_HEAD + i * 64 + q4 * 16) = xr[u];
-    }
+    for (int u = 0; u < XCH; ++u)
+      if (H * 64 % THREADS == 0 || xdst[u] >= 0) *(pf_u32x4*)(xs + xdst[u]) = xr[u];
   };
 
-  // per-head state of stage B
+  // ---- per-head state of stage B ------------------------------------------------------------------
   const int my_row = min(i0 + c, Lq - 1);                   // clamped for loads; stores check i0 + c
   const int vis_row = a.causal ? min(Lk, my_row + 1 + shift) : Lk;   // keys visible to my row
   f32x4 o[HPW][DK / 16];
   float m_run[HPW], l_run[HPW];
+  const bf16_t* kbase[HPW];      // K_LR operand rows of this lane, tile 0
+  const bf16_t* vbase[HPW];      // V operand chunk of this lane, tile 0
+  const bf16_t* qrow[HPW];
+  half_t* srow[HPW];             // A_n row of this lane (key 8 g of tile 0)
+  const int h_first = hg0 + wv * HPW;
 #pragma unroll
   for (int hh = 0; hh < HPW; ++hh) {
+    const int h = h_first + hh, kv = h / group;
     m_run[hh] = -INFINITY;
     l_run[hh] = 0.f;
 #pragma unroll
     for (int nb = 0; nb < DK / 16; ++nb) o[hh][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    kbase[hh] = a.kp + (((size_t)b * a.Hkv + kv) * a.Lkp + 8 * (c >> 2) + (c & 3)) * 32 + 8 * g;
+    vbase[hh] = a.vt + ((((size_t)b * a.Hkv + kv) * (a.Lkp / 8) + g) * DK + c) * 8;
+    qrow[hh] = a.qp + (((size_t)b * H + h) * a.Lqp + i0 + c) * 32 + 8 * g;
+    srow[hh] = a.scores ? a.scores + (((size_t)b * H + h) * Lq + my_row) * Lk + 8 * g : nullptr;
   }
   // operand registers of the head that stage B handles next, refilled right after use
-  const int h_first = hg0 + wv * HPW;
-  const int key_in_tile = 8 * (c >> 2) + (c & 3);
-  auto q_ptr = [&](int h) { return a.qp + (((size_t)b * H + h) * a.Lqp + i0 + c) * 32 + 8 * g; };
-  auto k_ptr = [&](int h, int tile) {
-    return a.kp + (((size_t)b * a.Hkv + h / group) * a.Lkp + tile * PF_TK + key_in_tile) * 32 + 8 * g;
-  };
-  auto v_ptr = [&](int h, int tile) {
-    return a.vt + ((((size_t)b * a.Hkv + h / group) * (a.Lkp / 8) + tile * (PF_TK / 8) + g) * DK + c) * 8;
-  };
   bf16x8 qop, ka, kb, vop[DK / 16];
-  {
-    qop = *(const bf16x8*)q_ptr(h_first);
-    const bf16_t* kp0 = k_ptr(h_first, 0);
-    ka = *(const bf16x8*)kp0;
-    kb = *(const bf16x8*)(kp0 + 4 * 32);
-    const bf16_t* vp0 = v_ptr(h_first, 0);
+  qop = *(const bf16x8*)qrow[0];
+  ka = *(const bf16x8*)kbase[0];
+  kb = *(const bf16x8*)(kbase[0] + 4 * 32);
 #pragma unroll
-    for (int nb = 0; nb < DK / 16; ++nb) vop[nb] = *(const bf16x8*)(vp0 + nb * 128);
-  }
-  {
-    pf_u32x4 xr[XCH];
-    load_x(0, xr);
-    store_x(xs0, xr);
+  for (int nb = 0; nb < DK / 16; ++nb) vop[nb] = *(const bf16x8*)(vbase[0] + nb * 128);
+
+  // A_{n-1} tile t+1 travels in xr for one whole tile period: loaded at the start of stage B(t-1),
+  // written to LDS at the start of stage B(t)
+  pf_u32x4 xr[XCH];
+  load_x(0, xr);
+  store_x(xs0, xr);
+  load_x(min(1, n_tiles - 1), xr);
+
+  // LDS addresses of stage A (per lane, tile independent)
+  int xrd[KS][2];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    // transposing LDS read: lane s = 4 k' + q4 of a 16-lane group passes the address of head k',
+    // keys 4 q4 .. 4 q4 + 3; it receives key c of heads k' = 0..3.
+    xrd[ks][0] = min(32 * ks + 8 * g + (c >> 2), H - 1) * PF_XS_HEAD + 8 * (c & 3);
+    xrd[ks][1] = min(32 * ks + 8 * g + 4 + (c >> 2), H - 1) * PF_XS_HEAD + 8 * (c & 3);
   }
 
   for (int tile = 0; tile < n_tiles; ++tile) {
     const int j0 = tile * PF_TK;
     unsigned char* xs = xs0 + (tile & 1) * H * PF_XS_HEAD;
-    __syncthreads();                                                     // B1
+    lds_barrier();                                                       // B1
     {
       // ---- stage A: y = FFN(A_{n-1}) for this wave's blocks of 16 positions --------------------
       // the FFN weights live in registers during stage A only (stage B needs the registers for
       // the output accumulators and the operand prefetch)
       Ffn ffn;
       ffn.fetch(w_s);
-#pragma unroll 1
-      for (int nb = wv; nb < 2 * PF_ROWS; nb += NW) {          // block = (row i, key half kh)
-        const int i = nb >> 1, kh = nb & 1;
-        f16x8 x[KS];
+      // two blocks of 16 positions at a time, their MFMA chains interleaved
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          // transposing LDS read: lane s = 4 k' + q4 of a 16-lane group passes the address of head
-          // k', keys 4 q4 .. 4 q4 + 3; it receives key c of heads k' = 0..3.
-          const int hA = min(32 * ks + 8 * g + (c >> 2), H - 1);
-          const int hB = min(32 * ks + 8 * g + 4 + (c >> 2), H - 1);
-          const unsigned char* pa = xs + hA * PF_XS_HEAD + i * 64 + (16 * kh + 4 * (c & 3)) * 2;
-          const unsigned char* pb = xs + hB * PF_XS_HEAD + i * 64 + (16 * kh + 4 * (c & 3)) * 2;
-          const f16x4 lo = __builtin_bit_cast(
-              f16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)pa));
-          const f16x4 hi = __builtin_bit_cast(
-              f16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)pb));
+      for (int q = 0; q < NBW; q += 2) {
+        f16x8 x[2][KS];
+        int yoff[2];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const bool la = 32 * ks + 8 * g + e < H, lb = 32 * ks + 8 * g + 4 + e < H;
-            x[ks][e] = la ? lo[e] : (_Float16)0.f;
-            x[ks][4 + e] = lb ? hi[e] : (_Float16)0.f;
+        for (int n = 0; n < 2; ++n) {
+          // block = (row i, key half kh); a wave with an odd share repeats its last block
+          const int nb = min(wv + (q + n) * NW, 2 * PF_ROWS - 1);
+          const int i = nb >> 1, kh = nb & 1;
+          yoff[n] = i * PF_YS_ROW + (16 * kh + c) * 4;
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) {
+            const f16x4 lo = __builtin_bit_cast(
+                f16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                           (s16x4 __attribute__((address_space(3)))*)(xs + xrd[ks][0] + i * 64 + 32 * kh)));
+            const f16x4 hi = __builtin_bit_cast(
+                f16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                           (s16x4 __attribute__((address_space(3)))*)(xs + xrd[ks][1] + i * 64 + 32 * kh)));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              if (H % 32 == 0) {
+                x[n][ks][e] = lo[e];
+                x[n][ks][4 + e] = hi[e];
+              } else {
+                x[n][ks][e] = 32 * ks + 8 * g + e < H ? lo[e] : (_Float16)0.f;
+                x[n][ks][4 + e] = 32 * ks + 8 * g + 4 + e < H ? hi[e] : (_Float16)0.f;
+              }
+            }
           }
         }
-        f32x4 y[HBO];
-        ffn.apply(x, y);
+        f32x4 y[2][HBO];
+        ffn.template apply<2>(x, y);
 #pragma unroll
-        for (int hb = 0; hb < HBO; ++hb)
+        for (int n = 0; n < 2; ++n)
 #pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            const int hl = 16 * hb + 4 * g + v;
-            if (hl < GH) *(float*)(ys + hl * PF_YS_HEAD + i * PF_YS_ROW + (16 * kh + c) * 4) = y[hb][v];
-          }
+          for (int hb = 0; hb < HBO; ++hb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+              const int hl = 16 * hb + 4 * g + v;
+              if (GH % 16 == 0 || hl < GH) *(float*)(ys + hl * PF_YS_HEAD + yoff[n]) = y[n][hb][v];
+            }
       }
     }
-    __syncthreads();                                                     // B2
+    lds_barrier();                                                       // B2
 
     // ---- stage B: per head scores, softmax, P V ------------------------------------------------
     const int tile_n = min(tile + 1, n_tiles - 1);            // next tile (clamped: loads stay valid)
-    pf_u32x4 xr[XCH];
-    load_x(tile_n, xr);
-    const bool full = j0 + PF_TK <= (a.causal ? min(Lk, i0 + 1 + shift) : Lk) && i0 + PF_ROWS <= Lq;
+    // xs[(tile+1) % 2] was last read in stage A of tile - 1, which every wave left before B2
+    store_x(xs0 + ((tile + 1) & 1) * H * PF_XS_HEAD, xr);
+    load_x(min(tile + 2, n_tiles - 1), xr);
+    const bool full = tile < n_full;                          // workgroup-uniform
+    const int jl = j0 + 8 * g;                                // first of my 8 keys
 #pragma unroll
     for (int hh = 0; hh < HPW; ++hh) {
-      const int h = h_first + hh;
-      const int h_next = hh + 1 < HPW ? h + 1 : h_first;
+      const int hn = hh + 1 < HPW ? hh + 1 : 0;
       const int t_next = hh + 1 < HPW ? tile : tile_n;
       // low-rank scores for keys j0 + 8 g + e of row c
       const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
       const f32x4 s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qop, zero, 0, 0, 0);
       const f32x4 s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb, qop, zero, 0, 0, 0);
       {
-        qop = *(const bf16x8*)q_ptr(h_next);
-        const bf16_t* kpn = k_ptr(h_next, t_next);
+        qop = *(const bf16x8*)qrow[hn];
+        const bf16_t* kpn = kbase[hn] + (size_t)t_next * (PF_TK * 32);
         ka = *(const bf16x8*)kpn;
         kb = *(const bf16x8*)(kpn + 4 * 32);
       }
@@ -277,70 +332,69 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
         an[e] = s0[e] * a.dscale + y0[e];
         an[4 + e] = s1[e] * a.dscale + y1[e];
       }
-      const int jl = j0 + 8 * g;                // first of my 8 keys
-      if (a.scores && i0 + c < Lq) {
-        half_t* sp = a.scores + (((size_t)b * H + h) * Lq + i0 + c) * Lk + jl;
-        if (jl + 8 <= vis_row) {
-          f16x8 hv;
+      f16x8 hv;                                 // A_n for the next layer, stored after the MFMAs
 #pragma unroll
-          for (int e = 0; e < 8; ++e) hv[e] = f32_to_half_sat(an[e]);
-          *(f16x8*)sp = hv;
-        } else {
+      for (int e = 0; e < 8; ++e) hv[e] = f32_to_half_sat(an[e]);
+      // online softmax, statistics of row c kept by all four lanes 16 g + c; exponentials in
+      // base 2: p = 2^(A log2(e) - m log2(e))
+      if (!full) {                              // workgroup-uniform: only diagonal / ragged tiles mask
 #pragma unroll
-          for (int e = 0; e < 8; ++e)
-            if (jl + e < vis_row) sp[e] = f32_to_half_sat(an[e]);
-        }
+        for (int e = 0; e < 8; ++e)
+          if (jl + e >= vis_row) an[e] = -INFINITY;
       }
-      // online softmax (base-2 exponent), statistics of row c kept by all four lanes 16 g + c
-      float mx = -INFINITY;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        if (!full && jl + e >= vis_row) an[e] = -INFINITY;
-        an[e] *= LOG2E;
-        mx = fmaxf(mx, an[e]);
-      }
-      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      float mx = fmaxf(fmaxf(fmaxf(an[0], an[1]), fmaxf(an[2], an[3])),
+                       fmaxf(fmaxf(an[4], an[5]), fmaxf(an[6], an[7])));
+      mx = rows_max(mx);
       const float m_new = fmaxf(m_run[hh], mx);
       // every row sees key 0, so m_new is finite from the first tile on
-      const float alpha = fast_exp2(m_run[hh] - m_new);
+      const float m2 = m_new * LOG2E;
+      const float alpha = fast_exp2(m_run[hh] * LOG2E - m2);
       m_run[hh] = m_new;
       float ps = 0.f;
-      u16x8 pbits;
+      bf16x8 pop;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const float p = fast_exp2(an[e] - m_new);
+        const float p = fast_exp2(__builtin_fmaf(an[e], LOG2E, -m2));
         ps += p;
-        pbits[e] = (unsigned short)f32_to_bf16_bits(p);
+        pop[e] = (__bf16)p;                     // hardware round-to-nearest-even conversion
       }
       l_run[hh] = l_run[hh] * alpha + ps;       // partial sum over my keys; groups merged at the end
-      const bf16x8 pop = bf16x8_from_bits(pbits);
-      const bool rescale = __any(alpha != 1.f);
-      const bf16_t* vpn = v_ptr(h_next, t_next);
+      if (__any(alpha != 1.f)) {                // wave-uniform: the running maximum rarely moves
+#pragma unroll
+        for (int nb = 0; nb < DK / 16; ++nb)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) o[hh][nb][v] *= alpha;
+      }
+      const bf16_t* vpn = vbase[hn] + (size_t)t_next * (PF_TK / 8 * DK * 8);
 #pragma unroll
       for (int nb = 0; nb < DK / 16; ++nb) {
-        f32x4 acc = o[hh][nb];
-        if (rescale) {
-#pragma unroll
-          for (int v = 0; v < 4; ++v) acc[v] *= alpha;
-        }
-        o[hh][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[nb], pop, acc, 0, 0, 0);
+        o[hh][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[nb], pop, o[hh][nb], 0, 0, 0);
         vop[nb] = *(const bf16x8*)(vpn + nb * 128);
       }
+      // stores share the in-order memory counter with loads: issued last, no operand load of
+      // this head has to wait behind them
+      if (a.scores) {
+        half_t* sp = srow[hh] + j0;
+        if (full) {
+          *(f16x8*)sp = hv;
+        } else if (i0 + c < Lq) {
+          if (jl + 8 <= vis_row) {
+            *(f16x8*)sp = hv;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              if (jl + e < vis_row) sp[e] = hv[e];
+          }
+        }
+      }
     }
-    // the other A_{n-1} buffer was last read in stage A of tile - 1, which every wave left
-    // before B2 of this tile
-    store_x(xs0 + ((tile + 1) & 1) * H * PF_XS_HEAD, xr);
   }
 
   // ---- epilogue: O[row][h][d] = o / l ---------------------------------------------------------
 #pragma unroll
   for (int hh = 0; hh < HPW; ++hh) {
     const int h = h_first + hh;
-    float l = l_run[hh];
-    l += __shfl_xor(l, 16, 64);
-    l += __shfl_xor(l, 32, 64);
-    const float inv = 1.f / l;
+    const float inv = 1.f / rows_sum(l_run[hh]);
     if (i0 + c < Lq) {
       const size_t at = (((size_t)b * Lq + i0 + c) * H + h) * DK + 4 * g;
 #pragma unroll

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <cstdlib>
 #include <vector>
 
 #include "kernels_decode.h"
@@ -329,28 +330,28 @@ PrefillWs prefill_fused_ws(const lisa_desc* d) {
   return w;
 }
 
-template <int HB, int FS, int HPW, int NW>
+template <int NG, int FS, int HPW, int NW>
 int launch_prefill_fused_t(const lisa_desc* d, const PrefillArgs& a, hipStream_t st) {
-  constexpr int GH = NW * HPW;
-  typedef MfmaFfn<HB, FS, (GH + 15) / 16> Ffn;
-  const size_t lds = (size_t)d->H * 2 * PF_XS_HEAD + (size_t)GH * PF_YS_HEAD + Ffn::kStageBytes;
-  auto kern = k_lisa_prefill_fused<HB, FS, HPW, NW>;
+  constexpr int GH = NW * HPW, H = NG * GH;
+  typedef MfmaFfn<(H + 15) / 16, FS, (GH + 15) / 16> Ffn;
+  const size_t lds = (size_t)H * 2 * PF_XS_HEAD + (size_t)GH * PF_YS_HEAD + Ffn::kStageBytes;
+  auto kern = k_lisa_prefill_fused<NG, FS, HPW, NW>;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)lds);
   if (e != hipSuccess) return hip_fail(e);
-  dim3 grid(a.Lqp / PF_ROWS, d->B, d->H / GH);
+  dim3 grid(a.Lqp / PF_ROWS, d->B, NG);
   StageScope prof("k_lisa_prefill_fused", st);
   kern<<<grid, NW * 64, lds, st>>>(a);
   return check_launch();
 }
 
-template <int HB, int HPW, int NW>
+template <int NG, int HPW, int NW>
 int launch_prefill_fused_fs(const lisa_desc* d, const PrefillArgs& a, hipStream_t st) {
   switch ((d->F + 31) / 32) {
-    case 1: return launch_prefill_fused_t<HB, 1, HPW, NW>(d, a, st);
-    case 2: return launch_prefill_fused_t<HB, 2, HPW, NW>(d, a, st);
-    case 3: return launch_prefill_fused_t<HB, 3, HPW, NW>(d, a, st);
-    default: return launch_prefill_fused_t<HB, 4, HPW, NW>(d, a, st);
+    case 1: return launch_prefill_fused_t<NG, 1, HPW, NW>(d, a, st);
+    case 2: return launch_prefill_fused_t<NG, 2, HPW, NW>(d, a, st);
+    case 3: return launch_prefill_fused_t<NG, 3, HPW, NW>(d, a, st);
+    default: return launch_prefill_fused_t<NG, 4, HPW, NW>(d, a, st);
   }
 }
 
@@ -392,9 +393,9 @@ int run_prefill_fused(const lisa_desc* d, const void* q_lr, const void* k_lr, co
   switch (d->H) {
     case 8: rc = launch_prefill_fused_fs<1, 1, 8>(d, a, st); break;    // one group of 8 heads
     case 16: rc = launch_prefill_fused_fs<1, 2, 8>(d, a, st); break;   // one group of 16
-    case 24: rc = launch_prefill_fused_fs<2, 3, 8>(d, a, st); break;   // one group of 24
+    case 24: rc = launch_prefill_fused_fs<1, 3, 8>(d, a, st); break;   // one group of 24
     case 32: rc = launch_prefill_fused_fs<2, 2, 8>(d, a, st); break;   // two groups of 16
-    default: rc = launch_prefill_fused_fs<3, 2, 10>(d, a, st); break;  // H = 40: two groups of 20
+    default: rc = launch_prefill_fused_fs<2, 2, 10>(d, a, st); break;  // H = 40: two groups of 20
   }
   if (rc == LISA_OK) g_path = "mfma_fused";
   return rc;

@@ -90,30 +90,44 @@ struct MfmaFfn {
         w2[hb][s] = *(const f16x8*)(lds2 + ((hb * FS + s) * 64 + lane) * 8);
   }
 
-  // x[ks]: B operand of the first product: lane (c, g) holds x[head 32 ks + 8 g + e] of its
-  // position (zero for heads >= H).  y[hb][v] = FFN output of head h_first + 16 hb + 4 g + v.
-  __device__ __forceinline__ void apply(const f16x8 (&x)[KS], f32x4 (&y)[HBO]) const {
-    f16x8 hid[FS];
+  // NBLK independent blocks of 16 positions at once: the MFMAs of the blocks are interleaved so
+  // that none has to wait for the result of the one issued just before it.
+  // x[n][ks]: B operand of the first product of block n: lane (c, g) holds x[head 32 ks + 8 g + e]
+  // of its position (zero for heads >= H).  y[n][hb][v] = FFN output of head h_first + 16 hb + 4 g + v.
+  template <int NBLK>
+  __device__ __forceinline__ void apply(const f16x8 (&x)[NBLK][KS], f32x4 (&y)[NBLK][HBO]) const {
+    f16x8 hid[NBLK][FS];
 #pragma unroll
     for (int s = 0; s < FS; ++s) {
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        f32x4 acc[NBLK];
+#pragma unroll
+        for (int n = 0; n < NBLK; ++n) acc[n] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1[2 * s + half][ks], x[ks], acc, 0, 0, 0);
 #pragma unroll
-        for (int v = 0; v < 4; ++v)
-          hid[s][4 * half + v] = (_Float16)__builtin_amdgcn_fmed3f(acc[v], 0.f, 65504.f);
+          for (int n = 0; n < NBLK; ++n)
+            acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1[2 * s + half][ks], x[n][ks], acc[n], 0, 0, 0);
+#pragma unroll
+        for (int n = 0; n < NBLK; ++n)
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            hid[n][s][4 * half + v] = (_Float16)__builtin_amdgcn_fmed3f(acc[n][v], 0.f, 65504.f);
       }
     }
 #pragma unroll
     for (int hb = 0; hb < HBO; ++hb) {
-      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+      f32x4 acc[NBLK];
+#pragma unroll
+      for (int n = 0; n < NBLK; ++n) acc[n] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int s = 0; s < FS; ++s)
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(w2[hb][s], hid[s], acc, 0, 0, 0);
-      y[hb] = acc;
+#pragma unroll
+        for (int n = 0; n < NBLK; ++n)
+          acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w2[hb][s], hid[n][s], acc[n], 0, 0, 0);
+#pragma unroll
+      for (int n = 0; n < NBLK; ++n) y[n][hb] = acc[n];
     }
   }
 };
