@@ -48,7 +48,15 @@ def stage_algorithmic(stage, cfg, write_scores, out_bytes=4):
         return pos * cfg.H * e + cfg.B * cfg.L * cfg.Hkv * cfg.d_k * e + cfg.B * cfg.L * cfg.H * cfg.d_k * out_bytes
     if stage.endswith("std_scores"):
         return pos * cfg.H * e + cfg.B * cfg.L * (cfg.H + cfg.Hkv) * cfg.d_k * e
+    if stage.endswith("prefill_fused"):
+        # the whole layer in one kernel: A_{n-1} in, A_n out (when emitted), Q_LR, K_LR, V in, O out
+        return lisa_layer_algorithmic(cfg, write_scores, out_bytes)[1]
     return 0
+
+
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this workload,
+# scaled by the same counters of a 1 GiB copy (profiles/lisa_prefill_fused_c2_traffic.md).
+MEASURED_TRAFFIC = {"k_lisa_prefill_fused": 311.6e6 + 168.6e6}
 
 
 def time_steps(fn, steps, warmup):
@@ -157,6 +165,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--decode-steps", type=int, default=3)
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--decode-only", action="store_true",
+                    help="run only the 32-layer decode step (for profiling) and print its record")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=15.0)
     args = ap.parse_args()
@@ -168,6 +178,16 @@ def main():
     from paper_2408_01890_amd import lisa, synth
     assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU path)"
     torch.cuda.set_device(0)
+    # a plain 1 GiB device-to-device copy: the known-size dispatch that counter profiles of
+    # this command are calibrated against (HBM bytes per FETCH_SIZE / WRITE_SIZE unit)
+    cal = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    cal2 = torch.empty_like(cal)
+    cal2.copy_(cal)
+    torch.cuda.synchronize()
+    del cal, cal2
+    if args.decode_only:
+        print(json.dumps(decode_stack(synth.C5, args.decode_steps, 1)), flush=True)
+        return
     dev = "cuda"
     cfg = synth.C2
     n_sets = 4                       # rotate buffer sets so that no step finds its scores in cache
@@ -220,7 +240,8 @@ def main():
     roofline = {
         "bound": "hbm", "kernel": dom, "achieved": dom_bytes / (dom_ms * 1e-3) / 1e9,
         "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": dom_bytes / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+        "frac": dom_bytes / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "traffic": MEASURED_TRAFFIC.get(dom),
         "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms,
     }
     sec_ro = time_steps(step_ro, max(args.steps // 2, 1), 1)

@@ -30,13 +30,13 @@
 // a key chunk contiguous, so the 8 feature blocks of a lane differ by an immediate offset).
 //
 // Software pipeline of one workgroup (tile t = 32 keys):
-//   top of tile t : the A_{n-1} tile t is already in LDS buffer t % 2; barrier B1
-//   stage A(t)    : reads xs[t % 2], writes ys; barrier B2
-//   stage B(t)    : first issues the global loads of the A_{n-1} tile t+1 into registers; then,
-//                   head by head, consumes the K_LR / V operand registers and immediately refills
-//                   them with the operands of the next head (or of the first head of tile t+1), so
-//                   every operand load has one head of work to hide its latency; finally writes
-//                   the A_{n-1} tile t+1 into xs[(t+1) % 2].
+//   top of tile t : the A_{n-1} tile t is already in LDS (xs); barrier B1
+//   stage A(t)    : reads xs, writes ys; barrier B2
+//   stage B(t)    : first writes the A_{n-1} tile t+1 (in registers since stage B(t-1)) into xs and
+//                   issues the global loads of tile t+2; then, head by head, consumes the K_LR / V
+//                   operand registers and immediately refills them with the operands of the next
+//                   head (or of the first head of tile t+1), so every operand load has one head of
+//                   work to hide its latency.
 #pragma once
 #include "kernels_generic.h"
 #include "mfma_ffn.h"
@@ -153,8 +153,8 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
   constexpr int NBW = ((2 * PF_ROWS + NW - 1) / NW + 1) / 2 * 2;   // position blocks per wave in stage A (even)
   extern __shared__ __align__(16) unsigned char pf_lds[];
   const int Lq = a.Lq, Lk = a.Lk;
-  unsigned char* xs0 = pf_lds;                              // A_{n-1} tiles, half, two buffers
-  unsigned char* ys = xs0 + 2 * H * PF_XS_HEAD;             // y tile of the group, float
+  unsigned char* xs = pf_lds;                               // A_{n-1} tile, half
+  unsigned char* ys = xs + H * PF_XS_HEAD;                  // y tile of the group, float
   unsigned short* w_s = (unsigned short*)(ys + GH * PF_YS_HEAD);
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform
@@ -234,7 +234,7 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
   // written to LDS at the start of stage B(t)
   pf_u32x4 xr[XCH];
   load_x(0, xr);
-  store_x(xs0, xr);
+  store_x(xs, xr);
   load_x(min(1, n_tiles - 1), xr);
 
   // LDS addresses of stage A (per lane, tile independent)
@@ -249,7 +249,6 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
 
   for (int tile = 0; tile < n_tiles; ++tile) {
     const int j0 = tile * PF_TK;
-    unsigned char* xs = xs0 + (tile & 1) * H * PF_XS_HEAD;
     lds_barrier();                                                       // B1
     {
       // ---- stage A: y = FFN(A_{n-1}) for this wave's blocks of 16 positions --------------------
@@ -305,8 +304,9 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
 
     // ---- stage B: per head scores, softmax, P V ------------------------------------------------
     const int tile_n = min(tile + 1, n_tiles - 1);            // next tile (clamped: loads stay valid)
-    // xs[(tile+1) % 2] was last read in stage A of tile - 1, which every wave left before B2
-    store_x(xs0 + ((tile + 1) & 1) * H * PF_XS_HEAD, xr);
+    // every wave left stage A(tile), the last reader of xs, before B2; stage A(tile+1) reads the
+    // new tile after B1
+    store_x(xs, xr);
     load_x(min(tile + 2, n_tiles - 1), xr);
     const bool full = tile < n_full;                          // workgroup-uniform
     const int jl = j0 + 8 * g;                                // first of my 8 keys
