@@ -28,7 +28,8 @@
  *     because the softmax that consumes A needs absolute, not relative, precision.
  *   - Visibility: with causal = 1 query row i (0-based, of Lq) sees key j (of Lk) iff
  *     j <= i + (Lk - Lq); with causal = 0 every key is visible.  Score entries of
- *     invisible keys are never read and never written.
+ *     invisible keys are never used and never written (a kernel may load a few of them inside
+ *     an aligned 16-byte chunk of an allocated row and discard them).
  *   - Grouped KV heads: query head h uses KV head h / (H / Hkv).
  */
 #ifndef LISA_H_
