@@ -64,6 +64,9 @@ struct PrefillArgs {
   void* out;              // [B,Lq,H,128] float32 or bf16
   int H, Hkv, Lq, Lk, Lqp, Lkp, F, causal, out_f32;
   float dscale;
+  int split;              // key-range splits per row block (1: the kernel writes `out` itself)
+  float* part_o;          // [split][B][Lqp][H][128] unnormalised partial outputs (split > 1)
+  float* part_ml;         // [split][B][Lqp][H][2]   running maximum, partial sum
 };
 
 // Grid-stride, block 256: zero-pads the Q_LR / K_LR rows from r to 32 elements.
@@ -161,7 +164,8 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
   const int c = lane & 15, g = lane >> 4;
   const int b = blockIdx.y;
   const int hg0 = blockIdx.z * GH;                          // first head of the group
-  const int rb = gridDim.x - 1 - blockIdx.x;                // long row blocks first
+  const int unit = gridDim.x - 1 - blockIdx.x;              // long row blocks first
+  const int rb = unit / a.split, sp = unit % a.split;       // row block, key-range split
   const int i0 = rb * PF_ROWS;
   const int shift = Lk - Lq;                                // key j visible to row i iff j <= i + shift
   const int group = H / a.Hkv;
@@ -169,7 +173,12 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
 
   const int i_last = min(i0 + PF_ROWS - 1, Lq - 1);
   const int n_keys = a.causal ? min(Lk, i_last + 1 + shift) : Lk;
-  const int n_tiles = (n_keys + PF_TK - 1) / PF_TK;
+  const int n_tiles_all = (n_keys + PF_TK - 1) / PF_TK;
+  // this workgroup's share of the key tiles (identical formula in k_prefill_combine)
+  const int per_split = (n_tiles_all + a.split - 1) / a.split;
+  const int t_begin = sp * per_split;
+  const int n_tiles = min(n_tiles_all, t_begin + per_split);   // one past my last tile
+  if (t_begin >= n_tiles) return;                            // empty share (short row block)
   // tiles whose 32 keys are visible to all 16 rows (and all 16 rows exist) need no masking
   const int n_full = (i0 + PF_ROWS <= Lq) ? (a.causal ? min(Lk, i0 + 1 + shift) : Lk) / PF_TK : 0;
 
@@ -217,25 +226,30 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
     l_run[hh] = 0.f;
 #pragma unroll
     for (int nb = 0; nb < DK / 16; ++nb) o[hh][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    kbase[hh] = a.kp + (((size_t)b * a.Hkv + kv) * a.Lkp + 8 * (c >> 2) + (c & 3)) * 32 + 8 * g;
+    kbase[hh] = a.kp + (((size_t)b * a.Hkv + kv) * a.Lkp + 8 * (c >> 2) + (c & 3)) * 32 + 8 * g;   // tile 0
     vbase[hh] = a.vt + ((((size_t)b * a.Hkv + kv) * (a.Lkp / 8) + g) * DK + c) * 8;
     qrow[hh] = a.qp + (((size_t)b * H + h) * a.Lqp + i0 + c) * 32 + 8 * g;
     srow[hh] = a.scores ? a.scores + (((size_t)b * H + h) * Lq + my_row) * Lk + 8 * g : nullptr;
   }
-  // operand registers of the head that stage B handles next, refilled right after use
+  // operand registers of the head that stage B handles next, refilled right after use (keeping
+  // a set per head would give each load a whole tile period but does not fit the register file)
   bf16x8 qop, ka, kb, vop[DK / 16];
   qop = *(const bf16x8*)qrow[0];
-  ka = *(const bf16x8*)kbase[0];
-  kb = *(const bf16x8*)(kbase[0] + 4 * 32);
+  {
+    const bf16_t* kp0 = kbase[0] + (size_t)t_begin * (PF_TK * 32);
+    ka = *(const bf16x8*)kp0;
+    kb = *(const bf16x8*)(kp0 + 4 * 32);
+    const bf16_t* vp0 = vbase[0] + (size_t)t_begin * (PF_TK / 8 * DK * 8);
 #pragma unroll
-  for (int nb = 0; nb < DK / 16; ++nb) vop[nb] = *(const bf16x8*)(vbase[0] + nb * 128);
+    for (int nb = 0; nb < DK / 16; ++nb) vop[nb] = *(const bf16x8*)(vp0 + nb * 128);
+  }
 
   // A_{n-1} tile t+1 travels in xr for one whole tile period: loaded at the start of stage B(t-1),
   // written to LDS at the start of stage B(t)
   pf_u32x4 xr[XCH];
-  load_x(0, xr);
+  load_x(t_begin, xr);
   store_x(xs, xr);
-  load_x(min(1, n_tiles - 1), xr);
+  load_x(min(t_begin + 1, n_tiles - 1), xr);
 
   // LDS addresses of stage A (per lane, tile independent)
   int xrd[KS][2];
@@ -247,7 +261,7 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
     xrd[ks][1] = min(32 * ks + 8 * g + 4 + (c >> 2), H - 1) * PF_XS_HEAD + 8 * (c & 3);
   }
 
-  for (int tile = 0; tile < n_tiles; ++tile) {
+  for (int tile = t_begin; tile < n_tiles; ++tile) {
     const int j0 = tile * PF_TK;
     lds_barrier();                                                       // B1
     {
@@ -390,7 +404,27 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
     }
   }
 
-  // ---- epilogue: O[row][h][d] = o / l ---------------------------------------------------------
+  // ---- epilogue ----------------------------------------------------------------------------------
+  if (a.split > 1) {
+    // unnormalised partial (o, m, l) of this key range; k_prefill_combine merges the ranges
+#pragma unroll
+    for (int hh = 0; hh < HPW; ++hh) {
+      const int h = h_first + hh;
+      const float l = rows_sum(l_run[hh]);
+      const size_t row = (((size_t)sp * gridDim.y + b) * a.Lqp + i0 + c) * H + h;
+      if (g == 0) {
+        a.part_ml[row * 2] = m_run[hh];
+        a.part_ml[row * 2 + 1] = l;
+      }
+#pragma unroll
+      for (int nb = 0; nb < DK / 16; ++nb) {
+        const f32x4 acc = o[hh][nb];
+        *(float4*)(a.part_o + row * DK + nb * 16 + 4 * g) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+      }
+    }
+    return;
+  }
+  // O[row][h][d] = o / l
 #pragma unroll
   for (int hh = 0; hh < HPW; ++hh) {
     const int h = h_first + hh;
@@ -410,6 +444,48 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
           *(uint2*)((bf16_t*)a.out + at + nb * 16) = pk;
         }
       }
+    }
+  }
+}
+
+// Merges the key-range partials of k_lisa_prefill_fused: for every (b, row, h)
+//   O = sum_s e^{m_s - M} o_s / sum_s e^{m_s - M} l_s,   M = max_s m_s   over the non-empty ranges.
+// grid (Lq, B), block 256; thread -> (head, 4 features) pairs.
+__global__ __launch_bounds__(256) void k_prefill_combine(PrefillArgs a) {
+  constexpr int DK = 128;
+  const int i = blockIdx.x, b = blockIdx.y, H = a.H;
+  const int rb = i / PF_ROWS;
+  const int i_last = min(rb * PF_ROWS + PF_ROWS - 1, a.Lq - 1);
+  const int n_keys = a.causal ? min(a.Lk, i_last + 1 + a.Lk - a.Lq) : a.Lk;
+  const int n_tiles_all = (n_keys + PF_TK - 1) / PF_TK;
+  const int per_split = (n_tiles_all + a.split - 1) / a.split;
+  const int n_used = (n_tiles_all + per_split - 1) / per_split;       // non-empty ranges
+  for (int e = threadIdx.x; e < H * (DK / 4); e += 256) {
+    const int h = e / (DK / 4), d4 = e % (DK / 4);
+    float M = -INFINITY;
+    for (int s = 0; s < n_used; ++s)
+      M = fmaxf(M, a.part_ml[((((size_t)s * gridDim.y + b) * a.Lqp + i) * H + h) * 2]);
+    float den = 0.f;
+    float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s = 0; s < n_used; ++s) {
+      const size_t row = (((size_t)s * gridDim.y + b) * a.Lqp + i) * H + h;
+      const float w = __expf(a.part_ml[row * 2] - M);
+      den += w * a.part_ml[row * 2 + 1];
+      const float4 po = *(const float4*)(a.part_o + row * DK + 4 * d4);
+      num.x += w * po.x;
+      num.y += w * po.y;
+      num.z += w * po.z;
+      num.w += w * po.w;
+    }
+    const float inv = 1.f / den;
+    const size_t at = (((size_t)b * a.Lq + i) * H + h) * DK + 4 * d4;
+    if (a.out_f32) {
+      *(float4*)((float*)a.out + at) = make_float4(num.x * inv, num.y * inv, num.z * inv, num.w * inv);
+    } else {
+      uint2 pk;
+      pk.x = f32_to_bf16_bits(num.x * inv) | (f32_to_bf16_bits(num.y * inv) << 16);
+      pk.y = f32_to_bf16_bits(num.z * inv) | (f32_to_bf16_bits(num.w * inv) << 16);
+      *(uint2*)((bf16_t*)a.out + at) = pk;
     }
   }
 }

@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstring>
 #include <cstdlib>
+#include <cstdlib>
 #include <vector>
 
 #include "kernels_decode.h"
@@ -315,9 +316,23 @@ bool prefill_fused_ok(const lisa_desc* d) {
 }
 
 struct PrefillWs {
-  size_t qp, kp, vt, total;   // byte offsets of the packed tensors in the workspace
-  int Lqp, Lkp;
+  size_t qp, kp, vt, part_o, part_ml, total;   // byte offsets in the workspace
+  int Lqp, Lkp, split;
 };
+
+constexpr int kComputeUnits = 256;   // MI355X
+
+// Key-range splits per row block: small problems have too few (row block, head group) units to
+// fill the chip and their longest unit (the last row block) sets the run time.
+int prefill_split(const lisa_desc* d, int Lqp) {
+  const int groups = d->H == 32 || d->H == 40 ? 2 : 1;
+  const long long units = (long long)(Lqp / PF_ROWS) * d->B * groups;
+  const int tiles_max = (d->Lk + PF_TK - 1) / PF_TK;
+  int s = 1;
+  while (s < 4 && units * s < 2 * kComputeUnits && tiles_max / (2 * s) >= 4) s *= 2;
+  if (const char* e = getenv("LISA_PREFILL_SPLIT")) s = atoi(e) > 0 ? atoi(e) : s;
+  return s;
+}
 
 PrefillWs prefill_fused_ws(const lisa_desc* d) {
   PrefillWs w;
@@ -326,7 +341,11 @@ PrefillWs prefill_fused_ws(const lisa_desc* d) {
   w.qp = 0;
   w.kp = w.qp + round_up((size_t)d->B * d->H * w.Lqp * 32 * 2, 256);
   w.vt = w.kp + round_up((size_t)d->B * d->Hkv * w.Lkp * 32 * 2, 256);
-  w.total = w.vt + round_up((size_t)d->B * d->Hkv * d->d_k * w.Lkp * 2, 256);
+  w.part_o = w.vt + round_up((size_t)d->B * d->Hkv * d->d_k * w.Lkp * 2, 256);
+  w.split = prefill_split(d, w.Lqp);
+  const size_t rows = w.split > 1 ? (size_t)w.split * d->B * w.Lqp * d->H : 0;
+  w.part_ml = w.part_o + round_up(rows * d->d_k * sizeof(float), 256);
+  w.total = w.part_ml + round_up(rows * 2 * sizeof(float), 256);
   return w;
 }
 
@@ -339,7 +358,7 @@ int launch_prefill_fused_t(const lisa_desc* d, const PrefillArgs& a, hipStream_t
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)lds);
   if (e != hipSuccess) return hip_fail(e);
-  dim3 grid(a.Lqp / PF_ROWS, d->B, NG);
+  dim3 grid(a.Lqp / PF_ROWS * a.split, d->B, NG);
   StageScope prof("k_lisa_prefill_fused", st);
   kern<<<grid, NW * 64, lds, st>>>(a);
   return check_launch();
@@ -379,6 +398,9 @@ int run_prefill_fused(const lisa_desc* d, const void* q_lr, const void* k_lr, co
   a.causal = d->causal;
   a.out_f32 = d->out_f32;
   a.dscale = pick_scale(d->delta_scale, d->r);
+  a.split = w.split;
+  a.part_o = (float*)(ws + w.part_o);
+  a.part_ml = (float*)(ws + w.part_ml);
   {
     StageScope prof("k_pack_prefill", st);
     k_pack_prefill<<<1024, 256, 0, st>>>((const bf16_t*)q_lr, (const bf16_t*)k_lr, (bf16_t*)(ws + w.qp),
@@ -396,6 +418,12 @@ int run_prefill_fused(const lisa_desc* d, const void* q_lr, const void* k_lr, co
     case 24: rc = launch_prefill_fused_fs<1, 3, 8>(d, a, st); break;   // one group of 24
     case 32: rc = launch_prefill_fused_fs<2, 2, 8>(d, a, st); break;   // two groups of 16
     default: rc = launch_prefill_fused_fs<2, 2, 10>(d, a, st); break;  // H = 40: two groups of 20
+  }
+  if (rc == LISA_OK && a.split > 1) {
+    dim3 grid(d->Lq, d->B);
+    StageScope prof("k_prefill_combine", st);
+    k_prefill_combine<<<grid, 256, 0, st>>>(a);
+    rc = check_launch();
   }
   if (rc == LISA_OK) g_path = "mfma_fused";
   return rc;

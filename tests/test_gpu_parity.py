@@ -137,6 +137,51 @@ def test_lisa_prefill_small_bf16(case, mix, ffn):
     assert torch.all(scores[..., above] == SENTINEL)      # nothing written above the diagonal
 
 
+FUSED_SHAPES = [
+    # name, B, H, Hkv, L (multiple of 8, ragged against the 16-row and 32-key tiles), d_k, r, F
+    ("h8_l264", 2, 8, 8, 264, 128, 11, 32),
+    ("h16_gqa_l296", 1, 16, 4, 296, 128, 22, 64),
+    ("h24_l136", 1, 24, 24, 136, 128, 20, 96),
+    ("h32_gqa_l520", 1, 32, 8, 520, 128, 32, 64),
+    ("h40_l136", 1, 40, 40, 136, 128, 22, 80),
+]
+
+
+@pytest.mark.parametrize("case", FUSED_SHAPES, ids=[c[0] for c in FUSED_SHAPES])
+@pytest.mark.parametrize("causal", [True, False])
+def test_lisa_prefill_fused_kernel_shapes(case, causal):
+    """Every head count the fused MFMA kernel is instantiated for, with ragged tails in both
+    tile directions, key-range splits (small problems split 2- or 4-way) and without the mask."""
+    name, B, H, Hkv, L, dk, r, F = case
+    cfg = synth.LayerShape(name, "bf16", B, H, Hkv, L, 256, dk, r, F)
+    log(f"[case] prefill fused {name} causal={causal}")
+    inp = synth.make_prefill_inputs(cfg, synth.BASE_SEED + 11, DEV, ffn="fan_in")
+    prev, _ = lisa.std_attn_scores(inp["q"], inp["k"], causal=causal)
+    out, scores = lisa.lisa_attn_prefill(inp["q_lr"], inp["k_lr"], inp["v"], prev, inp["w1"],
+                                         inp["w2"], causal=causal)
+    torch.cuda.synchronize()
+    assert lisa.last_path() == "mfma_fused"
+    rows = np.arange(L)
+    tol = hp.TOL[torch.bfloat16]
+    from oracle import cref
+    for b in range(B):
+        prev_rows = hp.gather_score_rows(prev, b, rows)
+        if causal:
+            a_ref, o_ref = hp.oracle_lisa_rows(inp, b, rows, prev_rows)
+        else:   # full visibility = every row is the last row of an L-key decode
+            a_ref = np.empty((L, H, L))
+            o_ref = np.empty((L, H, dk))
+            for i in rows:
+                a1, o1 = cref.lisa_rows(hp.f64(inp["q_lr"][b])[:, i:i + 1], hp.f64(inp["k_lr"][b]),
+                                        hp.f64(inp["v"][b]), hp.f64(inp["w1"]), hp.f64(inp["w2"]), [0],
+                                        prev_rows[i:i + 1])
+                a_ref[i], o_ref[i] = a1[0], o1[0]
+        eo = hp.row_rel_err(hp.gather_out_rows(out, b, rows), o_ref)
+        ea = hp.scores_row_rel_err(hp.gather_score_rows(scores, b, rows), a_ref, rows, L, L, causal)
+        log(f"[parity] {name} causal={causal} b={b}: err_out={eo:.3e} err_scores={ea:.3e}")
+        assert eo <= tol and ea <= tol
+
+
 def test_bf16_output_option_differs_only_by_the_final_rounding():
     cfg = synth.LayerShape("bf16out", "bf16", 1, 32, 32, 200, 256, 128, 22, 64)
     inp = synth.make_prefill_inputs(cfg, 21, DEV, ffn="identity_noise")
