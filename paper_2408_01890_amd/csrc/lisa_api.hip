@@ -14,6 +14,7 @@
 #include "kernels_decode.h"
 #include "kernels_generic.h"
 #include "kernels_prefill.h"
+#include "kernels_std_prefill.h"
 
 using namespace lisa;
 
@@ -429,6 +430,50 @@ int run_prefill_fused(const lisa_desc* d, const void* q_lr, const void* k_lr, co
   return rc;
 }
 
+// ---- standard layer, prefill, MFMA (bf16) ---------------------------------------------
+bool std_prefill_fast_ok(const lisa_desc* d) {
+  return d->dtype == LISA_BF16 && d->d_k == 128 && d->H % 4 == 0 && d->Lk % 8 == 0 && d->Lq > 1;
+}
+
+size_t std_prefill_ws(const lisa_desc* d) {   // V by key chunks
+  const size_t Lkp = (size_t)(d->Lk + 63) / 64 * 64;
+  return round_up((size_t)d->B * d->Hkv * d->d_k * Lkp * 2, 256);
+}
+
+int run_std_prefill_fast(const lisa_desc* d, const void* q, const void* k, const void* v, void* scores,
+                         void* out, void* workspace, hipStream_t st) {
+  StdPrefillArgs a{};
+  a.q = (const bf16_t*)q;
+  a.k = (const bf16_t*)k;
+  a.vt = (const bf16_t*)workspace;
+  a.scores = (half_t*)scores;
+  a.out = out;
+  a.H = d->H;
+  a.Hkv = d->Hkv;
+  a.Lq = d->Lq;
+  a.Lk = d->Lk;
+  a.Lkp = (d->Lk + 63) / 64 * 64;
+  a.causal = d->causal;
+  a.out_f32 = d->out_f32;
+  a.scale = pick_scale(d->std_scale, d->d_k);
+  if (out) {
+    dim3 grid(a.Lkp / 64, d->d_k / 64, d->B * d->Hkv);
+    StageScope prof("k_regroup_v", st);
+    k_regroup_v<<<grid, 256, 0, st>>>((const bf16_t*)v, (bf16_t*)workspace, d->Lk, a.Lkp, d->d_k);
+    int rc = check_launch();
+    if (rc) return rc;
+  }
+  dim3 grid((d->Lq + SP_ROWS - 1) / SP_ROWS, d->H / 4, d->B);
+  StageScope prof("k_std_prefill", st);
+  if (out)
+    k_std_prefill<true><<<grid, 256, 0, st>>>(a);
+  else
+    k_std_prefill<false><<<grid, 256, 0, st>>>(a);
+  int rc = check_launch();
+  if (rc == LISA_OK) g_path = "mfma_std";
+  return rc;
+}
+
 }  // namespace
 
 extern "C" {
@@ -461,6 +506,7 @@ size_t lisa_workspace_bytes(const lisa_desc* desc, int which) {
     case LISA_WS_STD:
       if (check_common(desc) != LISA_OK) return 0;
       // needed only when `out` is requested
+      if (std_prefill_fast_ok(desc)) return std_prefill_ws(desc);
       return decode_fast_ok(desc, false) ? decode_fast_bytes(desc) : exact_bytes(desc);
     default:
       return 0;
@@ -629,6 +675,7 @@ int std_attn_scores(const lisa_desc* desc, const void* q, const void* k, const v
   // With Lq = 1 and Lmax set, K and V are caches of capacity Lmax along the key axis.
   const int cap = (desc->Lq == 1 && desc->Lmax >= desc->Lk) ? desc->Lmax : desc->Lk;
   const KeyStrides ks = dense_keys(desc, cap, desc->d_k);
+  if (std_prefill_fast_ok(desc)) return run_std_prefill_fast(desc, q, k, v, scores_out, out, workspace, st);
   if (out && decode_fast_ok(desc, false)) {
     DecodeArgs a{};
     a.q = (const bf16_t*)q;
