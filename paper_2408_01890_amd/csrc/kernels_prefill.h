@@ -31,12 +31,16 @@
 //
 // Software pipeline of one workgroup (tile t = 32 keys):
 //   top of tile t : the A_{n-1} tile t is already in LDS (xs); barrier B1
-//   stage A(t)    : reads xs, writes ys; barrier B2
-//   stage B(t)    : first writes the A_{n-1} tile t+1 (in registers since stage B(t-1)) into xs and
-//                   issues the global loads of tile t+2; then, head by head, consumes the K_LR / V
-//                   operand registers and immediately refills them with the operands of the next
-//                   head (or of the first head of tile t+1), so every operand load has one head of
-//                   work to hide its latency.
+//   stage A(t)    : reads xs, writes ys; barrier B2.  With two heads per wave the V operands of
+//                   the second head for tile t are loaded here, between the FFN blocks.
+//   stage B(t)    : head by head, consumes the K_LR / V operand registers and refills them right
+//                   away with the same head's operands of tile t+1 (one register set per head when
+//                   the register file allows, else one rotating set refilled for the next head);
+//                   then stores A_n, writes the A_{n-1} tile t+1 (in registers since the end of
+//                   stage B(t-1)) into xs and issues the loads of tile t+2.
+// What bounds it: a compute unit takes in about 75 GB/s of 16-byte loads from the L2 (measured),
+// and a tile moves 192 KB through that pipe (V 128, K_LR 32, A_{n-1} 32); a load that cannot be
+// issued blocks its wave, so the loads are spread over both stages rather than issued in bursts.
 #pragma once
 #include "kernels_generic.h"
 #include "mfma_ffn.h"
@@ -67,49 +71,95 @@ struct PrefillArgs {
   int split;              // key-range splits per row block (1: the kernel writes `out` itself)
   float* part_o;          // [split][B][Lqp][H][128] unnormalised partial outputs (split > 1)
   float* part_ml;         // [split][B][Lqp][H][2]   running maximum, partial sum
+  int pair;               // workgroup x takes the units (last - x) and x
 };
 
-// Grid-stride, block 256: zero-pads the Q_LR / K_LR rows from r to 32 elements.
-__global__ void k_pack_prefill(const bf16_t* __restrict__ q_lr, const bf16_t* __restrict__ k_lr,
-                               bf16_t* __restrict__ qp, bf16_t* __restrict__ kp, int B, int H, int Hkv,
-                               int Lq, int Lk, int Lqp, int Lkp, int r) {
-  const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const size_t nth = (size_t)gridDim.x * blockDim.x;
-  const size_t nq = (size_t)B * H * Lqp * 32, nk = (size_t)B * Hkv * Lkp * 32;
-  bf16_t z;
-  z.bits = 0;
-  for (size_t e = tid; e < nq; e += nth) {
-    const int t = e & 31;
-    const size_t row = e >> 5;
-    const int i = row % Lqp;
-    const size_t bh = row / Lqp;
-    qp[e] = (t < r && i < Lq) ? q_lr[(bh * Lq + i) * r + t] : z;
+typedef unsigned short pf_u16x8 __attribute__((ext_vector_type(8)));
+
+// One 64-key x 64-feature tile of vt[bh][j / 8][d][j % 8] = v[bh][j][d] (zero for j >= Lk)
+// through LDS, 256 threads.  VEC: v is 16-byte aligned and dk % 8 == 0 (row chunks of 8 features
+// are read as one 16-byte load); the output is always written as 16-byte chunks.
+template <bool VEC>
+__device__ __forceinline__ void regroup_v_tile(const bf16_t* __restrict__ v, bf16_t* __restrict__ vt, int Lk,
+                                               int Lkp, int dk, int j0, int d0, size_t bh,
+                                               unsigned short (*tile)[72]) {
+  if (VEC) {
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int id = threadIdx.x + 256 * u, jl = id >> 3, dc = id & 7;
+      pf_u16x8 x = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (j0 + jl < Lk) x = *(const pf_u16x8*)(v + (bh * Lk + j0 + jl) * dk + d0 + 8 * dc);
+      *(pf_u16x8*)&tile[jl][8 * dc] = x;
+    }
+  } else {
+    for (int idx = threadIdx.x; idx < 64 * 64; idx += 256) {
+      const int jl = idx >> 6, dl = idx & 63;
+      tile[jl][dl] = (j0 + jl < Lk) ? v[(bh * Lk + j0 + jl) * dk + d0 + dl].bits : (unsigned short)0;
+    }
   }
-  for (size_t e = tid; e < nk; e += nth) {
-    const int t = e & 31;
-    const size_t row = e >> 5;
-    const int j = row % Lkp;
-    const size_t bh = row / Lkp;
-    kp[e] = (t < r && j < Lk) ? k_lr[(bh * Lk + j) * r + t] : z;
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int id = threadIdx.x + 256 * u, jc = id >> 6, dl = id & 63;
+    pf_u16x8 x;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = tile[8 * jc + e][dl];
+    *(pf_u16x8*)(vt + ((bh * (Lkp / 8) + j0 / 8 + jc) * dk + d0 + dl) * 8) = x;
   }
 }
 
-// vt[bh][j / 8][d][j % 8] = v[bh][j][d] through a 64 x 64 LDS tile (zero for j >= Lk).
 // grid (Lkp / 64, dk / 64, B * Hkv), block 256.
+template <bool VEC>
 __global__ __launch_bounds__(256) void k_regroup_v(const bf16_t* __restrict__ v, bf16_t* __restrict__ vt,
                                                    int Lk, int Lkp, int dk) {
-  __shared__ unsigned short tile[64][66];
-  const int j0 = blockIdx.x * 64, d0 = blockIdx.y * 64;
-  const size_t bh = blockIdx.z;
-  for (int idx = threadIdx.x; idx < 64 * 64; idx += 256) {
-    const int jl = idx >> 6, dl = idx & 63;
-    tile[jl][dl] = (j0 + jl < Lk) ? v[(bh * Lk + j0 + jl) * dk + d0 + dl].bits : (unsigned short)0;
+  __shared__ __align__(16) unsigned short tile[64][72];
+  regroup_v_tile<VEC>(v, vt, Lk, Lkp, dk, blockIdx.x * 64, blockIdx.y * 64, blockIdx.z, tile);
+}
+
+// The repacking of one fused prefill call in one launch, block 256:
+//   blocks [0, n_v):   V tiles as in k_regroup_v (tile index = x + nx (y + ny z))
+//   the rest:          Q_LR and K_LR rows zero-padded from r to 32 elements, one 16-byte chunk of
+//                      a padded row per thread (64 rows per block, Q rows first).
+template <bool VEC>
+__global__ __launch_bounds__(256) void k_prepare_prefill(const bf16_t* __restrict__ q_lr,
+                                                         const bf16_t* __restrict__ k_lr,
+                                                         const bf16_t* __restrict__ v, bf16_t* __restrict__ qp,
+                                                         bf16_t* __restrict__ kp, bf16_t* __restrict__ vt, int B,
+                                                         int H, int Hkv, int Lq, int Lk, int Lqp, int Lkp,
+                                                         int r, int dk) {
+  __shared__ __align__(16) unsigned short tile[64][72];
+  const int nx = Lkp / 64, ny = dk / 64;
+  const int n_v = nx * ny * B * Hkv;
+  int blk = blockIdx.x;
+  if (blk < n_v) {
+    const int x = blk % nx, y = blk / nx % ny, z = blk / (nx * ny);
+    regroup_v_tile<VEC>(v, vt, Lk, Lkp, dk, x * 64, y * 64, z, tile);
+    return;
   }
-  __syncthreads();
-  for (int idx = threadIdx.x; idx < 64 * 64; idx += 256) {
-    const int e = idx & 7, dl = (idx >> 3) & 63, jc = idx >> 9;
-    vt[((bh * (Lkp / 8) + j0 / 8 + jc) * dk + d0 + dl) * 8 + e].bits = tile[8 * jc + e][dl];
+  blk -= n_v;
+  const size_t q_rows = (size_t)B * H * Lqp, k_rows = (size_t)B * Hkv * Lkp;
+  const size_t row = (size_t)blk * 64 + (threadIdx.x >> 2);
+  const int t0 = 8 * (threadIdx.x & 3);
+  const bf16_t* src = nullptr;
+  bf16_t* dst;
+  if (row < q_rows) {
+    const int i = row % Lqp;
+    const size_t bh = row / Lqp;
+    if (i < Lq) src = q_lr + (bh * Lq + i) * r;
+    dst = qp + row * 32 + t0;
+  } else if (row < q_rows + k_rows) {
+    const size_t rk = row - q_rows;
+    const int j = rk % Lkp;
+    const size_t bh = rk / Lkp;
+    if (j < Lk) src = k_lr + (bh * Lk + j) * r;
+    dst = kp + rk * 32 + t0;
+  } else {
+    return;
   }
+  pf_u16x8 x;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) x[e] = (src && t0 + e < r) ? src[t0 + e].bits : (unsigned short)0;
+  *(pf_u16x8*)dst = x;
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -140,8 +190,33 @@ __device__ __forceinline__ float rows_sum(float v) {
   return __uint_as_float(q[0]) + __uint_as_float(q[1]);
 }
 
+// Access at a wave-uniform base plus a per-lane 32-bit byte offset: the form that one global
+// load or store with a scalar base register pair and a vector offset covers, so that no lane
+// keeps 64-bit pointers.
+template <class T>
+__device__ __forceinline__ T ld_uv(const void* ubase, unsigned voff, int imm = 0) {
+  return *(const T*)((const char*)ubase + imm + voff);
+}
+template <class T>
+__device__ __forceinline__ void st_uv(void* ubase, unsigned voff, T v) {
+  *(T*)((char*)ubase + voff) = v;
+}
+// The same for data that is touched once (A_{n-1} in, A_n out): non-temporal, so that the
+// stream does not push the K_LR / V operands, which every row block re-reads, out of the L2.
+template <class T>
+__device__ __forceinline__ T ld_uv_nt(const void* ubase, unsigned voff) {
+  return __builtin_nontemporal_load((const T*)((const char*)ubase + voff));
+}
+template <class T>
+__device__ __forceinline__ void st_uv_nt(void* ubase, unsigned voff, T v) {
+  __builtin_nontemporal_store(v, (T*)((char*)ubase + voff));
+}
+
 // H = NG * NW * HPW heads in NG groups; NW waves per workgroup, HPW heads per wave; FS hidden
-// k-steps of the FFN.  grid (Lqp / 16, B, NG), block NW * 64.  Requires Lk % 8 == 0.
+// k-steps of the FFN.  A unit of work is (row block of 16 rows, key-range split); units are
+// numbered by length.  grid (units or ceil(units / 2), B, NG), block NW * 64: with a.pair the
+// workgroup x takes the units (last - x) and x, a long and a short one, so that all workgroups
+// carry the same number of tiles and stage the FFN weights once.  Requires Lk % 8 == 0.
 template <int NG, int FS, int HPW, int NW>
 __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
   constexpr int DK = 128;
@@ -152,7 +227,7 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
   constexpr int HBO = (GH + 15) / 16;
   typedef MfmaFfn<HB, FS, HBO> Ffn;
   constexpr int KS = Ffn::KS;
-  constexpr int XCH = (H * 64 + THREADS - 1) / THREADS;   // 16-byte chunks of a tile per thread
+  constexpr int XCH = NG * HPW;                      // A_{n-1} chunks per lane: heads wv + NW u
   constexpr int NBW = ((2 * PF_ROWS + NW - 1) / NW + 1) / 2 * 2;   // position blocks per wave in stage A (even)
   extern __shared__ __align__(16) unsigned char pf_lds[];
   const int Lq = a.Lq, Lk = a.Lk;
@@ -164,92 +239,33 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
   const int c = lane & 15, g = lane >> 4;
   const int b = blockIdx.y;
   const int hg0 = blockIdx.z * GH;                          // first head of the group
-  const int unit = gridDim.x - 1 - blockIdx.x;              // long row blocks first
-  const int rb = unit / a.split, sp = unit % a.split;       // row block, key-range split
-  const int i0 = rb * PF_ROWS;
   const int shift = Lk - Lq;                                // key j visible to row i iff j <= i + shift
   const int group = H / a.Hkv;
   const float LOG2E = 1.4426950408889634f;
-
-  const int i_last = min(i0 + PF_ROWS - 1, Lq - 1);
-  const int n_keys = a.causal ? min(Lk, i_last + 1 + shift) : Lk;
-  const int n_tiles_all = (n_keys + PF_TK - 1) / PF_TK;
-  // this workgroup's share of the key tiles (identical formula in k_prefill_combine)
-  const int per_split = (n_tiles_all + a.split - 1) / a.split;
-  const int t_begin = sp * per_split;
-  const int n_tiles = min(n_tiles_all, t_begin + per_split);   // one past my last tile
-  if (t_begin >= n_tiles) return;                            // empty share (short row block)
-  // tiles whose 32 keys are visible to all 16 rows (and all 16 rows exist) need no masking
-  const int n_full = (i0 + PF_ROWS <= Lq) ? (a.causal ? min(Lk, i0 + 1 + shift) : Lk) / PF_TK : 0;
+  const int n_units = a.Lqp / PF_ROWS * a.split;
+  const int h_first = hg0 + wv * HPW;
 
   Ffn::stage(a.w1, a.w2, H, a.F, w_s, tid, THREADS, hg0, GH);
 
-  // ---- A_{n-1} tile: thread -> XCH chunks (head, row, 8 keys) of 16 bytes ------------------------
-  const half_t* xsrc[XCH];       // row start of each chunk's (head, row)
-  int xq4[XCH], xdst[XCH];
-#pragma unroll
-  for (int u = 0; u < XCH; ++u) {
-    const int e = tid + u * THREADS;
-    const int q4 = e & 3, i = (e >> 2) & 15, h = min(e >> 6, H - 1);
-    xsrc[u] = a.prev + (((size_t)b * H + h) * Lq + min(i0 + i, Lq - 1)) * Lk;
-    xq4[u] = 8 * q4;
-    xdst[u] = (e >> 6) < H ? h * PF_XS_HEAD + i * 64 + q4 * 16 : -1;
-  }
-  auto load_x = [&](int tile, pf_u32x4 (&xr)[XCH]) {
-#pragma unroll
-    for (int u = 0; u < XCH; ++u) {
-      // keys >= Lk: any in-bounds chunk will do, those positions are masked in stage B
-      const int jc = min(tile * PF_TK + xq4[u], Lk - 8);
-      xr[u] = *(const pf_u32x4*)(xsrc[u] + jc);
-    }
-  };
-  auto store_x = [&](unsigned char* xs, const pf_u32x4 (&xr)[XCH]) {
-#pragma unroll
-    for (int u = 0; u < XCH; ++u)
-      if (H * 64 % THREADS == 0 || xdst[u] >= 0) *(pf_u32x4*)(xs + xdst[u]) = xr[u];
-  };
-
-  // ---- per-head state of stage B ------------------------------------------------------------------
-  const int my_row = min(i0 + c, Lq - 1);                   // clamped for loads; stores check i0 + c
-  const int vis_row = a.causal ? min(Lk, my_row + 1 + shift) : Lk;   // keys visible to my row
-  f32x4 o[HPW][DK / 16];
-  float m_run[HPW], l_run[HPW];
-  const bf16_t* kbase[HPW];      // K_LR operand rows of this lane, tile 0
-  const bf16_t* vbase[HPW];      // V operand chunk of this lane, tile 0
-  const bf16_t* qrow[HPW];
-  half_t* srow[HPW];             // A_n row of this lane (key 8 g of tile 0)
-  const int h_first = hg0 + wv * HPW;
+  // wave-uniform bases of this wave's heads (scalar registers)
+  const bf16_t* k_base[HPW];     // K_LR rows of the head's key/value head
+  const bf16_t* v_base[HPW];     // V chunks of it
+  half_t* s_base[HPW];           // A_n of the head
 #pragma unroll
   for (int hh = 0; hh < HPW; ++hh) {
     const int h = h_first + hh, kv = h / group;
-    m_run[hh] = -INFINITY;
-    l_run[hh] = 0.f;
-#pragma unroll
-    for (int nb = 0; nb < DK / 16; ++nb) o[hh][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    kbase[hh] = a.kp + (((size_t)b * a.Hkv + kv) * a.Lkp + 8 * (c >> 2) + (c & 3)) * 32 + 8 * g;   // tile 0
-    vbase[hh] = a.vt + ((((size_t)b * a.Hkv + kv) * (a.Lkp / 8) + g) * DK + c) * 8;
-    qrow[hh] = a.qp + (((size_t)b * H + h) * a.Lqp + i0 + c) * 32 + 8 * g;
-    srow[hh] = a.scores ? a.scores + (((size_t)b * H + h) * Lq + my_row) * Lk + 8 * g : nullptr;
+    k_base[hh] = a.kp + ((size_t)b * a.Hkv + kv) * a.Lkp * 32;
+    v_base[hh] = a.vt + ((size_t)b * a.Hkv + kv) * (a.Lkp / 8) * (DK * 8);
+    s_base[hh] = a.scores ? a.scores + ((size_t)b * H + h) * Lq * Lk : nullptr;
   }
-  // operand registers of the head that stage B handles next, refilled right after use (keeping
-  // a set per head would give each load a whole tile period but does not fit the register file)
-  bf16x8 qop, ka, kb, vop[DK / 16];
-  qop = *(const bf16x8*)qrow[0];
-  {
-    const bf16_t* kp0 = kbase[0] + (size_t)t_begin * (PF_TK * 32);
-    ka = *(const bf16x8*)kp0;
-    kb = *(const bf16x8*)(kp0 + 4 * 32);
-    const bf16_t* vp0 = vbase[0] + (size_t)t_begin * (PF_TK / 8 * DK * 8);
+  const half_t* x_base[XCH];     // A_{n-1} of head wv + NW u
 #pragma unroll
-    for (int nb = 0; nb < DK / 16; ++nb) vop[nb] = *(const bf16x8*)(vp0 + nb * 128);
-  }
-
-  // A_{n-1} tile t+1 travels in xr for one whole tile period: loaded at the start of stage B(t-1),
-  // written to LDS at the start of stage B(t)
-  pf_u32x4 xr[XCH];
-  load_x(t_begin, xr);
-  store_x(xs, xr);
-  load_x(min(t_begin + 1, n_tiles - 1), xr);
+  for (int u = 0; u < XCH; ++u) x_base[u] = a.prev + ((size_t)b * H + wv + NW * u) * Lq * Lk;
+  // per-lane byte offsets, the same for every head
+  const unsigned k_off = ((8 * (c >> 2) + (c & 3)) * 32 + 8 * g) * 2;   // MFMA row c -> key 8 (c/4) + c%4 (+4)
+  const unsigned v_off = (g * DK + c) * 16;                             // key chunk g, feature c (+16 nb)
+  const int xq8 = 8 * (lane & 3);                                       // A_{n-1} chunk: row lane/4, 8 keys
+  const int xdst = wv * PF_XS_HEAD + lane * 16;                         // + u NW PF_XS_HEAD
 
   // LDS addresses of stage A (per lane, tile independent)
   int xrd[KS][2];
@@ -261,18 +277,102 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
     xrd[ks][1] = min(32 * ks + 8 * g + 4 + (c >> 2), H - 1) * PF_XS_HEAD + 8 * (c & 3);
   }
 
-  for (int tile = t_begin; tile < n_tiles; ++tile) {
-    const int j0 = tile * PF_TK;
-    lds_barrier();                                                       // B1
-    {
-      // ---- stage A: y = FFN(A_{n-1}) for this wave's blocks of 16 positions --------------------
-      // the FFN weights live in registers during stage A only (stage B needs the registers for
-      // the output accumulators and the operand prefetch)
-      Ffn ffn;
-      ffn.fetch(w_s);
-      // two blocks of 16 positions at a time, their MFMA chains interleaved
+  for (int rep = 0; rep < 2; ++rep) {
+    int unit;
+    if (a.pair) {
+      unit = rep ? (int)blockIdx.x : n_units - 1 - (int)blockIdx.x;
+      if (rep && unit >= n_units - 1 - unit) break;         // the middle unit of an odd count is alone
+    } else {
+      if (rep) break;
+      unit = n_units - 1 - blockIdx.x;                       // long units first
+    }
+    const int rb = unit / a.split, sp = unit % a.split;     // row block, key-range split
+    const int i0 = rb * PF_ROWS;
+    const int i_last = min(i0 + PF_ROWS - 1, Lq - 1);
+    const int n_keys = a.causal ? min(Lk, i_last + 1 + shift) : Lk;
+    const int n_tiles_all = (n_keys + PF_TK - 1) / PF_TK;
+    // this unit's share of the key tiles (identical formula in k_prefill_combine)
+    const int per_split = (n_tiles_all + a.split - 1) / a.split;
+    const int t_begin = sp * per_split;
+    const int n_mine = min(n_tiles_all, t_begin + per_split) - t_begin;
+    if (n_mine <= 0) continue;                                 // empty share (short row block)
+    auto tile_at = [&](int it) { return t_begin + it; };
+    // tiles whose 32 keys are visible to all 16 rows (and all 16 rows exist) need no masking
+    const int n_full = (i0 + PF_ROWS <= Lq) ? (a.causal ? min(Lk, i0 + 1 + shift) : Lk) / PF_TK : 0;
+
+    // ---- A_{n-1} tile: lane -> XCH chunks (head wv + NW u, row lane / 4, 8 keys) of 16 bytes ------
+    const unsigned x_row = (unsigned)min(i0 + (lane >> 2), Lq - 1) * Lk * 2;
+    auto load_x = [&](int tile, pf_u32x4 (&xr)[XCH]) {
+      // keys >= Lk: any in-bounds chunk will do, those positions are masked in stage B
+      const unsigned off = x_row + 2 * min(tile * PF_TK + xq8, Lk - 8);
+#pragma unroll
+      for (int u = 0; u < XCH; ++u) xr[u] = ld_uv_nt<pf_u32x4>(x_base[u], off);
+    };
+    auto store_x = [&](const pf_u32x4 (&xr)[XCH]) {
+#pragma unroll
+      for (int u = 0; u < XCH; ++u) *(pf_u32x4*)(xs + xdst + u * (NW * PF_XS_HEAD)) = xr[u];
+    };
+
+    // ---- per-head state of stage B ------------------------------------------------------------------
+    const int my_row = min(i0 + c, Lq - 1);                   // clamped for loads; stores check i0 + c
+    const int vis_row = a.causal ? min(Lk, my_row + 1 + shift) : Lk;   // keys visible to my row
+    const unsigned s_off = ((unsigned)my_row * Lk + 8 * g) * 2;        // my 8 keys of tile 0 in my row
+    f32x4 o[HPW][DK / 16];
+    float m_run[HPW], l_run[HPW];
+    // PERSIST: every head keeps its own operand registers; each is refilled right after its use
+    // with the same head's next tile, so the load has a whole tile period to arrive.  Otherwise
+    // (register file too small) one rotating set, refilled for the head that stage B handles next.
+    constexpr bool PERSIST = HPW <= 2 && NW <= 8;
+    constexpr int NSET = PERSIST ? HPW : 1;
+    // SPREAD: the V operands of the second head are loaded during stage A of their own tile
+    // instead of right after their use: the compute unit's load pipe, which every wave fills at
+    // the same time in stage B, then also works during stage A.
+    constexpr bool SPREAD = PERSIST && HPW == 2;
+    bf16x8 qop[HPW], ka[NSET], kb[NSET], vop[NSET][DK / 16];
+#pragma unroll
+    for (int hh = 0; hh < HPW; ++hh) {
+      m_run[hh] = -INFINITY;
+      l_run[hh] = 0.f;
+#pragma unroll
+      for (int nb = 0; nb < DK / 16; ++nb) o[hh][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+      qop[hh] = *(const bf16x8*)(a.qp + (((size_t)b * H + h_first + hh) * a.Lqp + i0 + c) * 32 + 8 * g);
+      if (hh >= NSET) continue;
+      const bf16_t* kt = k_base[hh] + (size_t)t_begin * (PF_TK * 32);
+      ka[hh] = ld_uv<bf16x8>(kt, k_off);
+      kb[hh] = ld_uv<bf16x8>(kt, k_off, 4 * 32 * 2);
+      if (SPREAD && hh == 1) continue;
+      const bf16_t* vt = v_base[hh] + (size_t)t_begin * (PF_TK / 8 * DK * 8);
+#pragma unroll
+      for (int nb = 0; nb < DK / 16; ++nb) vop[hh][nb] = ld_uv<bf16x8>(vt, v_off, nb * 256);
+    }
+
+    // the A_{n-1} tile t+2 travels in xr for one whole tile period: loaded at the end of stage
+    // B(t), written to LDS at the end of stage B(t+1)
+    pf_u32x4 xr[XCH];
+    load_x(t_begin, xr);
+    store_x(xr);
+    load_x(tile_at(min(1, n_mine - 1)), xr);
+
+    // Everything loaded so far has arrived before the loop is entered: the wait counts inside the
+    // loop then follow from the loop's own issue order alone (a load pending on entry would cap
+    // them at what the first pass needs and drain the prefetch on every pass).
+    __builtin_amdgcn_s_waitcnt(0x0F70);                       // vmcnt(0), others untouched
+    for (int it = 0; it < n_mine; ++it) {
+      const int tile = tile_at(it);
+      const int j0 = tile * PF_TK;
+      lds_barrier();                                                       // B1
+      // ---- stage A: y = FFN(A_{n-1}) for this wave's blocks of 16 positions ----------------------
+      // two blocks of 16 positions at a time, their MFMA chains interleaved; the weights are read
+      // from LDS as the products need them (stage B keeps the register file)
 #pragma unroll
       for (int q = 0; q < NBW; q += 2) {
+        if (SPREAD) {
+          constexpr int PER = (DK / 16 + NBW / 2 - 1) / (NBW / 2);    // V loads per block pair
+          const bf16_t* vt = v_base[HPW - 1] + (size_t)tile * (PF_TK / 8 * DK * 8);
+#pragma unroll
+          for (int nb = q / 2 * PER; nb < min(q / 2 * PER + PER, DK / 16); ++nb)
+            vop[NSET - 1][nb] = ld_uv<bf16x8>(vt, v_off, nb * 256);
+        }
         f16x8 x[2][KS];
         int yoff[2];
 #pragma unroll
@@ -302,7 +402,7 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
           }
         }
         f32x4 y[2][HBO];
-        ffn.template apply<2>(x, y);
+        Ffn::template apply_lds<2>(w_s, x, y);
 #pragma unroll
         for (int n = 0; n < 2; ++n)
 #pragma unroll
@@ -313,140 +413,145 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
               if (GH % 16 == 0 || hl < GH) *(float*)(ys + hl * PF_YS_HEAD + yoff[n]) = y[n][hb][v];
             }
       }
-    }
-    lds_barrier();                                                       // B2
+      lds_barrier();                                                       // B2
 
-    // ---- stage B: per head scores, softmax, P V ------------------------------------------------
-    const int tile_n = min(tile + 1, n_tiles - 1);            // next tile (clamped: loads stay valid)
-    // every wave left stage A(tile), the last reader of xs, before B2; stage A(tile+1) reads the
-    // new tile after B1
-    store_x(xs, xr);
-    load_x(min(tile + 2, n_tiles - 1), xr);
-    const bool full = tile < n_full;                          // workgroup-uniform
-    const int jl = j0 + 8 * g;                                // first of my 8 keys
+      // ---- stage B: per head scores, softmax, P V ------------------------------------------------
+      const int tile_n = tile_at(min(it + 1, n_mine - 1));      // next tile (clamped: loads stay valid)
+      const bool full = tile < n_full;                          // workgroup-uniform
+      const int jl = j0 + 8 * g;                                // first of my 8 keys
+      f16x8 hv[HPW];
+#pragma unroll
+      for (int hh = 0; hh < HPW; ++hh) {
+        // low-rank scores for keys j0 + 8 g + e of row c
+        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+        const int hs = PERSIST ? hh : 0;                               // operand set in use
+        const int hn = PERSIST ? hh : (hh + 1 < HPW ? hh + 1 : 0);     // head it is refilled for
+        const int t_next = PERSIST || hh + 1 == HPW ? tile_n : tile;
+        const f32x4 s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[hs], qop[hh], zero, 0, 0, 0);
+        const f32x4 s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[hs], qop[hh], zero, 0, 0, 0);
+        {
+          const bf16_t* kt = k_base[hn] + (size_t)t_next * (PF_TK * 32);
+          ka[hs] = ld_uv<bf16x8>(kt, k_off);
+          kb[hs] = ld_uv<bf16x8>(kt, k_off, 4 * 32 * 2);
+        }
+        const float* yp = (const float*)(ys + (wv * HPW + hh) * PF_YS_HEAD + c * PF_YS_ROW + 8 * g * 4);
+        const f32x4 y0 = *(const f32x4*)yp, y1 = *(const f32x4*)(yp + 4);
+        float an[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          an[e] = s0[e] * a.dscale + y0[e];
+          an[4 + e] = s1[e] * a.dscale + y1[e];
+        }
+        // A_n for the next layer, stored at the end of the stage
+#pragma unroll
+        for (int e = 0; e < 8; ++e) hv[hh][e] = f32_to_half_sat(an[e]);
+        // online softmax, statistics of row c kept by all four lanes 16 g + c; exponentials in
+        // base 2: p = 2^(A log2(e) - m log2(e))
+        if (!full) {                              // workgroup-uniform: only diagonal / ragged tiles mask
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (jl + e >= vis_row) an[e] = -INFINITY;
+        }
+        float mx = fmaxf(fmaxf(fmaxf(an[0], an[1]), fmaxf(an[2], an[3])),
+                         fmaxf(fmaxf(an[4], an[5]), fmaxf(an[6], an[7])));
+        mx = rows_max(mx);
+        const float m_new = fmaxf(m_run[hh], mx);
+        // every row sees key 0, so m_new is finite from the first tile on
+        const float m2 = m_new * LOG2E;
+        const float alpha = fast_exp2(m_run[hh] * LOG2E - m2);
+        m_run[hh] = m_new;
+        float ps = 0.f;
+        bf16x8 pop;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float p = fast_exp2(__builtin_fmaf(an[e], LOG2E, -m2));
+          ps += p;
+          pop[e] = (__bf16)p;                     // hardware round-to-nearest-even conversion
+        }
+        l_run[hh] = l_run[hh] * alpha + ps;       // partial sum over my keys; groups merged at the end
+        if (__any(alpha != 1.f)) {                // wave-uniform: the running maximum rarely moves
+#pragma unroll
+          for (int nb = 0; nb < DK / 16; ++nb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) o[hh][nb][v] *= alpha;
+        }
+        const bf16_t* vt = v_base[hn] + (size_t)t_next * (PF_TK / 8 * DK * 8);
+#pragma unroll
+        for (int nb = 0; nb < DK / 16; ++nb) {
+          o[hh][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[hs][nb], pop, o[hh][nb], 0, 0, 0);
+          if (!(SPREAD && hh == 1)) vop[hs][nb] = ld_uv<bf16x8>(vt, v_off, nb * 256);
+        }
+      }
+      // Loads and stores of a wave complete in issue order: the stores of A_n and the loads of the
+      // A_{n-1} tile after next (both HBM traffic) go last, behind every operand load of this tile.
+      if (a.scores) {
+#pragma unroll
+        for (int hh = 0; hh < HPW; ++hh) {
+          half_t* st = s_base[hh] + j0;
+          if (full) {
+            st_uv_nt<f16x8>(st, s_off, hv[hh]);
+          } else if (i0 + c < Lq) {
+            if (jl + 8 <= vis_row) {
+              st_uv_nt<f16x8>(st, s_off, hv[hh]);
+            } else {
+#pragma unroll
+              for (int e = 0; e < 8; ++e)
+                if (jl + e < vis_row) st_uv<_Float16>(st, s_off + 2 * e, hv[hh][e]);
+            }
+          }
+        }
+      }
+      // every wave left stage A(tile), the last reader of xs, before B2; stage A(tile+1) reads the
+      // new tile after B1
+      store_x(xr);
+      load_x(tile_at(min(it + 2, n_mine - 1)), xr);
+    }
+
+    // ---- epilogue ----------------------------------------------------------------------------------
+    if (a.split > 1) {
+      // unnormalised partial (o, m, l) of this key range; k_prefill_combine merges the ranges
+#pragma unroll
+      for (int hh = 0; hh < HPW; ++hh) {
+        const int h = h_first + hh;
+        const float l = rows_sum(l_run[hh]);
+        const size_t row = (((size_t)sp * gridDim.y + b) * a.Lqp + i0 + c) * H + h;
+        if (g == 0) {
+          a.part_ml[row * 2] = m_run[hh];
+          a.part_ml[row * 2 + 1] = l;
+        }
+#pragma unroll
+        for (int nb = 0; nb < DK / 16; ++nb) {
+          const f32x4 acc = o[hh][nb];
+          *(float4*)(a.part_o + row * DK + nb * 16 + 4 * g) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        }
+      }
+      continue;
+    }
+    // O[row][h][d] = o / l
 #pragma unroll
     for (int hh = 0; hh < HPW; ++hh) {
-      const int hn = hh + 1 < HPW ? hh + 1 : 0;
-      const int t_next = hh + 1 < HPW ? tile : tile_n;
-      // low-rank scores for keys j0 + 8 g + e of row c
-      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-      const f32x4 s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qop, zero, 0, 0, 0);
-      const f32x4 s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb, qop, zero, 0, 0, 0);
-      {
-        qop = *(const bf16x8*)qrow[hn];
-        const bf16_t* kpn = kbase[hn] + (size_t)t_next * (PF_TK * 32);
-        ka = *(const bf16x8*)kpn;
-        kb = *(const bf16x8*)(kpn + 4 * 32);
-      }
-      const float* yp = (const float*)(ys + (wv * HPW + hh) * PF_YS_HEAD + c * PF_YS_ROW + 8 * g * 4);
-      const f32x4 y0 = *(const f32x4*)yp, y1 = *(const f32x4*)(yp + 4);
-      float an[8];
+      const int h = h_first + hh;
+      const float inv = 1.f / rows_sum(l_run[hh]);
+      if (i0 + c < Lq) {
+        const size_t at = (((size_t)b * Lq + i0 + c) * H + h) * DK + 4 * g;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        an[e] = s0[e] * a.dscale + y0[e];
-        an[4 + e] = s1[e] * a.dscale + y1[e];
-      }
-      f16x8 hv;                                 // A_n for the next layer, stored after the MFMAs
-#pragma unroll
-      for (int e = 0; e < 8; ++e) hv[e] = f32_to_half_sat(an[e]);
-      // online softmax, statistics of row c kept by all four lanes 16 g + c; exponentials in
-      // base 2: p = 2^(A log2(e) - m log2(e))
-      if (!full) {                              // workgroup-uniform: only diagonal / ragged tiles mask
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-          if (jl + e >= vis_row) an[e] = -INFINITY;
-      }
-      float mx = fmaxf(fmaxf(fmaxf(an[0], an[1]), fmaxf(an[2], an[3])),
-                       fmaxf(fmaxf(an[4], an[5]), fmaxf(an[6], an[7])));
-      mx = rows_max(mx);
-      const float m_new = fmaxf(m_run[hh], mx);
-      // every row sees key 0, so m_new is finite from the first tile on
-      const float m2 = m_new * LOG2E;
-      const float alpha = fast_exp2(m_run[hh] * LOG2E - m2);
-      m_run[hh] = m_new;
-      float ps = 0.f;
-      bf16x8 pop;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float p = fast_exp2(__builtin_fmaf(an[e], LOG2E, -m2));
-        ps += p;
-        pop[e] = (__bf16)p;                     // hardware round-to-nearest-even conversion
-      }
-      l_run[hh] = l_run[hh] * alpha + ps;       // partial sum over my keys; groups merged at the end
-      if (__any(alpha != 1.f)) {                // wave-uniform: the running maximum rarely moves
-#pragma unroll
-        for (int nb = 0; nb < DK / 16; ++nb)
-#pragma unroll
-          for (int v = 0; v < 4; ++v) o[hh][nb][v] *= alpha;
-      }
-      const bf16_t* vpn = vbase[hn] + (size_t)t_next * (PF_TK / 8 * DK * 8);
-#pragma unroll
-      for (int nb = 0; nb < DK / 16; ++nb) {
-        o[hh][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[nb], pop, o[hh][nb], 0, 0, 0);
-        vop[nb] = *(const bf16x8*)(vpn + nb * 128);
-      }
-      // stores share the in-order memory counter with loads: issued last, no operand load of
-      // this head has to wait behind them
-      if (a.scores) {
-        half_t* sp = srow[hh] + j0;
-        if (full) {
-          *(f16x8*)sp = hv;
-        } else if (i0 + c < Lq) {
-          if (jl + 8 <= vis_row) {
-            *(f16x8*)sp = hv;
+        for (int nb = 0; nb < DK / 16; ++nb) {
+          const f32x4 acc = o[hh][nb];
+          if (a.out_f32) {
+            *(float4*)((float*)a.out + at + nb * 16) =
+                make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
           } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-              if (jl + e < vis_row) sp[e] = hv[e];
+            uint2 pk;
+            pk.x = f32_to_bf16_bits(acc[0] * inv) | (f32_to_bf16_bits(acc[1] * inv) << 16);
+            pk.y = f32_to_bf16_bits(acc[2] * inv) | (f32_to_bf16_bits(acc[3] * inv) << 16);
+            *(uint2*)((bf16_t*)a.out + at + nb * 16) = pk;
           }
         }
       }
     }
   }
-
-  // ---- epilogue ----------------------------------------------------------------------------------
-  if (a.split > 1) {
-    // unnormalised partial (o, m, l) of this key range; k_prefill_combine merges the ranges
-#pragma unroll
-    for (int hh = 0; hh < HPW; ++hh) {
-      const int h = h_first + hh;
-      const float l = rows_sum(l_run[hh]);
-      const size_t row = (((size_t)sp * gridDim.y + b) * a.Lqp + i0 + c) * H + h;
-      if (g == 0) {
-        a.part_ml[row * 2] = m_run[hh];
-        a.part_ml[row * 2 + 1] = l;
-      }
-#pragma unroll
-      for (int nb = 0; nb < DK / 16; ++nb) {
-        const f32x4 acc = o[hh][nb];
-        *(float4*)(a.part_o + row * DK + nb * 16 + 4 * g) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-      }
-    }
-    return;
-  }
-  // O[row][h][d] = o / l
-#pragma unroll
-  for (int hh = 0; hh < HPW; ++hh) {
-    const int h = h_first + hh;
-    const float inv = 1.f / rows_sum(l_run[hh]);
-    if (i0 + c < Lq) {
-      const size_t at = (((size_t)b * Lq + i0 + c) * H + h) * DK + 4 * g;
-#pragma unroll
-      for (int nb = 0; nb < DK / 16; ++nb) {
-        const f32x4 acc = o[hh][nb];
-        if (a.out_f32) {
-          *(float4*)((float*)a.out + at + nb * 16) =
-              make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
-        } else {
-          uint2 pk;
-          pk.x = f32_to_bf16_bits(acc[0] * inv) | (f32_to_bf16_bits(acc[1] * inv) << 16);
-          pk.y = f32_to_bf16_bits(acc[2] * inv) | (f32_to_bf16_bits(acc[3] * inv) << 16);
-          *(uint2*)((bf16_t*)a.out + at + nb * 16) = pk;
-        }
-      }
-    }
-  }
 }
+
 
 // Merges the key-range partials of k_lisa_prefill_fused: for every (b, row, h)
 //   O = sum_s e^{m_s - M} o_s / sum_s e^{m_s - M} l_s,   M = max_s m_s   over the non-empty ranges.

@@ -8,8 +8,6 @@
 #include <cstdio>
 #include <cstring>
 #include <cstdlib>
-#include <cstdlib>
-#include <vector>
 
 #include "kernels_decode.h"
 #include "kernels_generic.h"
@@ -335,6 +333,15 @@ int prefill_split(const lisa_desc* d, int Lqp) {
   return s;
 }
 
+// Two units (a long and a short one) per workgroup once that still leaves two workgroups per
+// compute unit: equal work per workgroup, FFN weights staged once for both.
+int prefill_pair(const lisa_desc* d, int Lqp, int split) {
+  const int groups = d->H == 32 || d->H == 40 ? 2 : 1;
+  const long long units = (long long)(Lqp / PF_ROWS) * split * d->B * groups;
+  if (const char* e = getenv("LISA_PREFILL_PAIR")) return atoi(e) != 0;
+  return units >= 2 * kComputeUnits;
+}
+
 PrefillWs prefill_fused_ws(const lisa_desc* d) {
   PrefillWs w;
   w.Lqp = (d->Lq + PF_ROWS - 1) / PF_ROWS * PF_ROWS;
@@ -359,10 +366,12 @@ int launch_prefill_fused_t(const lisa_desc* d, const PrefillArgs& a, hipStream_t
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)lds);
   if (e != hipSuccess) return hip_fail(e);
-  dim3 grid(a.Lqp / PF_ROWS * a.split, d->B, NG);
+  const int units = a.Lqp / PF_ROWS * a.split;
+  dim3 grid(a.pair ? (units + 1) / 2 : units, d->B, NG);
   StageScope prof("k_lisa_prefill_fused", st);
   kern<<<grid, NW * 64, lds, st>>>(a);
   return check_launch();
+
 }
 
 template <int NG, int HPW, int NW>
@@ -400,15 +409,18 @@ int run_prefill_fused(const lisa_desc* d, const void* q_lr, const void* k_lr, co
   a.out_f32 = d->out_f32;
   a.dscale = pick_scale(d->delta_scale, d->r);
   a.split = w.split;
+  a.pair = prefill_pair(d, w.Lqp, w.split);
   a.part_o = (float*)(ws + w.part_o);
   a.part_ml = (float*)(ws + w.part_ml);
   {
-    StageScope prof("k_pack_prefill", st);
-    k_pack_prefill<<<1024, 256, 0, st>>>((const bf16_t*)q_lr, (const bf16_t*)k_lr, (bf16_t*)(ws + w.qp),
-                                         (bf16_t*)(ws + w.kp), d->B, d->H, d->Hkv, d->Lq, d->Lk, w.Lqp,
-                                         w.Lkp, d->r);
-    dim3 grid(w.Lkp / 64, d->d_k / 64, d->B * d->Hkv);
-    k_regroup_v<<<grid, 256, 0, st>>>((const bf16_t*)v, (bf16_t*)(ws + w.vt), d->Lk, w.Lkp, d->d_k);
+    StageScope prof("k_prepare_prefill", st);
+    const size_t rows = (size_t)d->B * d->H * w.Lqp + (size_t)d->B * d->Hkv * w.Lkp;
+    const size_t blocks = (size_t)(w.Lkp / 64) * (d->d_k / 64) * d->B * d->Hkv + (rows + 63) / 64;
+    const bool vec = (uintptr_t)v % 16 == 0;
+    auto kern = vec ? k_prepare_prefill<true> : k_prepare_prefill<false>;
+    kern<<<(unsigned)blocks, 256, 0, st>>>((const bf16_t*)q_lr, (const bf16_t*)k_lr, (const bf16_t*)v,
+                                          (bf16_t*)(ws + w.qp), (bf16_t*)(ws + w.kp), (bf16_t*)(ws + w.vt),
+                                          d->B, d->H, d->Hkv, d->Lq, d->Lk, w.Lqp, w.Lkp, d->r, d->d_k);
     int rc = check_launch();
     if (rc) return rc;
   }
@@ -459,7 +471,10 @@ int run_std_prefill_fast(const lisa_desc* d, const void* q, const void* k, const
   if (out) {
     dim3 grid(a.Lkp / 64, d->d_k / 64, d->B * d->Hkv);
     StageScope prof("k_regroup_v", st);
-    k_regroup_v<<<grid, 256, 0, st>>>((const bf16_t*)v, (bf16_t*)workspace, d->Lk, a.Lkp, d->d_k);
+    if ((uintptr_t)v % 16 == 0)
+      k_regroup_v<true><<<grid, 256, 0, st>>>((const bf16_t*)v, (bf16_t*)workspace, d->Lk, a.Lkp, d->d_k);
+    else
+      k_regroup_v<false><<<grid, 256, 0, st>>>((const bf16_t*)v, (bf16_t*)workspace, d->Lk, a.Lkp, d->d_k);
     int rc = check_launch();
     if (rc) return rc;
   }

@@ -90,6 +90,53 @@ struct MfmaFfn {
         w2[hb][s] = *(const f16x8*)(lds2 + ((hb * FS + s) * 64 + lane) * 8);
   }
 
+  // apply() with the weight operands read from the staged LDS image as the products need them
+  // (no weight registers held by the caller).
+  template <int NBLK>
+  __device__ __forceinline__ static void apply_lds(const unsigned short* lds, const f16x8 (&x)[NBLK][KS],
+                                                   f32x4 (&y)[NBLK][HBO]) {
+    const int lane = threadIdx.x & 63;
+    const unsigned short* l1 = lds + lane * 8;
+    const unsigned short* l2 = l1 + FB * KS * 512;
+    f16x8 hid[NBLK][FS];
+#pragma unroll
+    for (int s = 0; s < FS; ++s) {
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        f32x4 acc[NBLK];
+#pragma unroll
+        for (int n = 0; n < NBLK; ++n) acc[n] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          const f16x8 w = *(const f16x8*)(l1 + ((2 * s + half) * KS + ks) * 512);
+#pragma unroll
+          for (int n = 0; n < NBLK; ++n)
+            acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w, x[n][ks], acc[n], 0, 0, 0);
+        }
+#pragma unroll
+        for (int n = 0; n < NBLK; ++n)
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            hid[n][s][4 * half + v] = (_Float16)__builtin_amdgcn_fmed3f(acc[n][v], 0.f, 65504.f);
+      }
+    }
+#pragma unroll
+    for (int hb = 0; hb < HBO; ++hb) {
+      f32x4 acc[NBLK];
+#pragma unroll
+      for (int n = 0; n < NBLK; ++n) acc[n] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < FS; ++s) {
+        const f16x8 w = *(const f16x8*)(l2 + (hb * FS + s) * 512);
+#pragma unroll
+        for (int n = 0; n < NBLK; ++n)
+          acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w, hid[n][s], acc[n], 0, 0, 0);
+      }
+#pragma unroll
+      for (int n = 0; n < NBLK; ++n) y[n][hb] = acc[n];
+    }
+  }
+
   // NBLK independent blocks of 16 positions at once: the MFMAs of the blocks are interleaved so
   // that none has to wait for the result of the one issued just before it.
   // x[n][ks]: B operand of the first product of block n: lane (c, g) holds x[head 32 ks + 8 g + e]
