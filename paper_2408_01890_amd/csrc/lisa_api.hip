@@ -321,7 +321,7 @@ struct PrefillWs {
 
 constexpr int kComputeUnits = 256;   // MI355X
 
-// Key-range splits per row block: small problems have too few (row block, head group) units to
+// Key splits per row block: small problems have too few (row block, head group) units to
 // fill the chip and their longest unit (the last row block) sets the run time.
 int prefill_split(const lisa_desc* d, int Lqp) {
   const int groups = d->H == 32 || d->H == 40 ? 2 : 1;

@@ -80,6 +80,76 @@ def test_std_attn_scores_small(dtype, B, H, Hkv, Lq, Lk, dk):
         assert hp.row_rel_err(hp.gather_out_rows(o2, b, rows), o_ref) <= tol
 
 
+STD_MFMA_SHAPES = [
+    # name, B, H, Hkv, Lq, Lk (multiple of 8; ragged against the 32-row and 32-key tiles), causal
+    ("mha_l200", 2, 8, 8, 200, 200, True),
+    ("gqa_chunk_96x264", 1, 8, 2, 96, 264, True),
+    ("gqa_full_72x136", 1, 12, 4, 72, 136, False),
+    ("one_tile_24", 1, 4, 4, 24, 24, True),
+]
+
+
+@pytest.mark.parametrize("case", STD_MFMA_SHAPES, ids=[c[0] for c in STD_MFMA_SHAPES])
+def test_std_prefill_mfma_kernel_shapes(case):
+    """The bf16 standard layer on the matrix cores (d_k = 128): scores and output against the
+    oracle in its three call modes, invisible score entries left untouched."""
+    from oracle import cref
+    name, B, H, Hkv, Lq, Lk, causal = case
+    log(f"[case] std mfma {name}")
+    dt = torch.bfloat16
+    g = torch.Generator(device=DEV).manual_seed(23)
+    q = torch.randn((B, H, Lq, 128), generator=g, device=DEV).to(dt)
+    k = torch.randn((B, Hkv, Lk, 128), generator=g, device=DEV).to(dt)
+    v = torch.randn((B, Hkv, Lk, 128), generator=g, device=DEV).to(dt)
+    scores = torch.full((B, H, Lq, Lk), SENTINEL, dtype=lisa.score_dtype(dt), device=DEV)
+    _, out = lisa.std_attn_scores(q, k, v, scores_out=scores, causal=causal)
+    assert lisa.last_path() == "mfma_std"
+    s2, _ = lisa.std_attn_scores(q, k, causal=causal)
+    assert lisa.last_path() == "mfma_std"
+    _, o2 = lisa.std_attn_scores(q, k, v, want_scores=False, causal=causal)
+    assert lisa.last_path() == "mfma_std"
+    torch.cuda.synchronize()
+    rows = np.arange(Lq)
+    tol = hp.TOL[dt]
+    for b in range(B):
+        if causal:
+            ref = hp.oracle_std_rows(q, k, b, rows)
+        else:   # the oracle fills the visible part of a row: ask for each row as a 1-row problem
+            ref = np.concatenate([hp.oracle_std_rows(q[:, :, i:i + 1], k, b, [0]) for i in rows])
+        got = hp.gather_score_rows(scores, b, rows)
+        ea = hp.scores_row_rel_err(got, ref, rows, Lq, Lk, causal)
+        for i in rows:
+            nv = hp.n_visible(int(i), Lq, Lk, causal)
+            assert np.all(got[i, :, nv:] == SENTINEL)
+        assert np.array_equal(got[:, :, :1], hp.gather_score_rows(s2, b, rows)[:, :, :1])
+        if causal:
+            o_ref = cref.softmax_v_rows(hp.f64(v[b]), rows, ref, Lq)
+        else:   # full visibility = every row is the single query row of an Lk-key problem
+            o_ref = np.concatenate([cref.softmax_v_rows(hp.f64(v[b]), [0], ref[i:i + 1], 1) for i in rows])
+        eo = hp.row_rel_err(hp.gather_out_rows(out, b, rows), o_ref)
+        eo2 = hp.row_rel_err(hp.gather_out_rows(o2, b, rows), o_ref)
+        ea2 = hp.scores_row_rel_err(hp.gather_score_rows(s2, b, rows), ref, rows, Lq, Lk, causal)
+        log(f"[parity] std mfma {name} b={b}: err_scores={ea:.3e}/{ea2:.3e} err_out={eo:.3e}/{eo2:.3e}")
+        assert max(ea, ea2, eo, eo2) <= tol
+
+
+def test_std_prefill_c2_full_size_sampled_rows():
+    """The standard layer at the benchmark shape, in the launch configuration the bench times."""
+    from oracle import cref
+    cfg = synth.C2
+    inp = synth.make_prefill_inputs(cfg, synth.BASE_SEED + 7, DEV)
+    scores, out = lisa.std_attn_scores(inp["q"], inp["k"], inp["v"])
+    torch.cuda.synchronize()
+    assert lisa.last_path() == "mfma_std"
+    rows = synth.sample_rows(cfg.L, 96, 9)
+    ref = hp.oracle_std_rows(inp["q"], inp["k"], 0, rows)
+    ea = hp.scores_row_rel_err(hp.gather_score_rows(scores, 0, rows), ref, rows, cfg.L, cfg.L)
+    o_ref = cref.softmax_v_rows(hp.f64(inp["v"][0]), rows, ref, cfg.L)
+    eo = hp.row_rel_err(hp.gather_out_rows(out, 0, rows), o_ref)
+    log(f"[parity] std mfma {cfg.name}: err_scores={ea:.3e} err_out={eo:.3e}")
+    assert max(ea, eo) <= hp.TOL[cfg.torch_dtype]
+
+
 # ---------------------------------------------------------------------------------------
 # LiSA prefill: configuration 1 (fp32) in full, with the stress FFNs and both mix modes
 # ---------------------------------------------------------------------------------------
