@@ -1,15 +1,20 @@
 // Standard attention layer that also emits the shared scores (Sec. 2.1 Eq. 1-2), bf16 on MFMA.
 //
-// One wave = 32 query rows of one head, streaming over 32-key tiles up to the diagonal; no LDS,
-// no barrier.  Both products use the 32x32x16 MFMA and keep the query row on the lane index
+// One workgroup = one head and 128 consecutive query rows, one wave per block of 32 rows,
+// streaming over 32-key tiles up to the diagonal.  The K tile (and the V tile) of a step is
+// loaded once per workgroup into LDS (double buffered, one barrier per tile) and read by the
+// four waves as MFMA operands: a fourth of the global loads of a wave-private stream.
+// Both products use the 32x32x16 MFMA and keep the query row on the lane index
 // (lane = 32 half + r), so the softmax statistics and the probabilities never change lanes:
-//   scores  D[key, row] = sum_t K[key,t] Q[row,t]   A = K rows (read straight from the [L,128]
-//           tensor), B = Q^T (8 operands, resident).  MFMA row m is given key
-//           16 (m/16) + 8 ((m/4)%2) + 4 ((m/8)%2) + m%4 so that lane (r, half) ends with keys
-//           8 half .. 8 half + 7 and 16 + 8 half .. 16 + 8 half + 7: two 16-byte half stores.
+//   scores  D[key, row] = sum_t K[key,t] Q[row,t]   A = K rows, B = Q^T (8 operands, resident).
+//           MFMA row m is given key 16 (m/16) + 8 ((m/4)%2) + 4 ((m/8)%2) + m%4 so that lane
+//           (r, half) ends with keys 8 half .. 8 half + 7 and 16 + 8 half .. 16 + 8 half + 7:
+//           two 16-byte half stores.
 //   output  D[d, row] = sum_key V^T[d,key] P^T[key,row]   A = V by key chunks [L/8][128][8]
 //           (k_regroup_v), B = the lane's probabilities as they are.
 // A = Q K^T * scale is stored as half; the softmax works on the float32 values.
+// A workgroup takes two row groups, the x-th longest and the x-th shortest, so that all
+// workgroups stream the same number of tiles.
 #pragma once
 #include "kernels_prefill.h"
 
@@ -38,167 +43,203 @@ __device__ __forceinline__ float halves_sum(float v) {
   return __uint_as_float(q[0]) + __uint_as_float(q[1]);
 }
 
-constexpr int SP_ROWS = 32;
+constexpr int SP_ROWS = 32;                 // rows per wave
+constexpr int SP_WAVES = 4;
+constexpr int SP_GROUP = SP_ROWS * SP_WAVES;   // rows per workgroup pass
 constexpr int SP_TK = 32;
+constexpr int SP_KROW = 128 * 2 + 16;       // bytes per key row of the K tile in LDS (padded: no bank conflicts)
+constexpr int SP_KTILE = SP_TK * SP_KROW;   // 8704
+constexpr int SP_VTILE = SP_TK * 128 * 2;   // 8192
 
-// grid (ceil(Lq / 32), H / 4, B), block 256: wave w of a workgroup takes head 4 blockIdx.y + w.
-// Requires d_k = 128, H % 4 == 0, Lk % 8 == 0.
+// grid (ceil(n_groups / 2), H, B) with n_groups = ceil(Lq / 128), block 256.
+// Requires d_k = 128, Lk % 8 == 0.
 template <bool WITH_V>
 __global__ __launch_bounds__(256) void k_std_prefill(StdPrefillArgs a) {
   constexpr int DK = 128;
-  const int lane = threadIdx.x & 63;
-  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  __shared__ __align__(16) unsigned char lds[2 * SP_KTILE + (WITH_V ? 2 * SP_VTILE : 0)];
+  unsigned char* ks_ = lds;
+  unsigned char* vs_ = lds + 2 * SP_KTILE;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r = lane & 31, half = lane >> 5;
-  const int b = blockIdx.z, h = blockIdx.y * 4 + wv;
-  const int rb = gridDim.x - 1 - blockIdx.x;               // long row blocks first
-  const int i0 = rb * SP_ROWS;
+  const int b = blockIdx.z, h = blockIdx.y;
   const int Lq = a.Lq, Lk = a.Lk, H = a.H;
   const int shift = Lk - Lq;
   const int kv = h / (H / a.Hkv);
   const float LOG2E = 1.4426950408889634f;
-  const int my_row = min(i0 + r, Lq - 1);
-  const int vis_row = a.causal ? min(Lk, my_row + 1 + shift) : Lk;
-  const int i_last = min(i0 + SP_ROWS - 1, Lq - 1);
-  const int n_keys = a.causal ? min(Lk, i_last + 1 + shift) : Lk;
-  const int n_tiles = (n_keys + SP_TK - 1) / SP_TK;
-  const int n_full = (i0 + SP_ROWS <= Lq) ? (a.causal ? min(Lk, i0 + 1 + shift) : Lk) / SP_TK : 0;
-
-  // B operands of the score product: Q[row][16 ks + 8 half + e]
-  bf16x8 qop[DK / 16];
-  {
-    const bf16_t* qp = a.q + (((size_t)b * H + h) * Lq + my_row) * DK + 8 * half;
-#pragma unroll
-    for (int ks = 0; ks < DK / 16; ++ks) qop[ks] = *(const bf16x8*)(qp + 16 * ks);
-  }
+  const int n_groups = (Lq + SP_GROUP - 1) / SP_GROUP;
   // key of MFMA row m = r (see the header)
   const int key_of_r = 16 * (r >> 4) + 8 * ((r >> 2) & 1) + 4 * ((r >> 3) & 1) + (r & 3);
-  const bf16_t* kbase = a.k + ((size_t)b * a.Hkv + kv) * Lk * DK + 8 * half;
-  const bf16_t* vbase = WITH_V ? a.vt + ((((size_t)b * a.Hkv + kv) * (a.Lkp / 8) + half) * DK + r) * 8 : nullptr;
-  half_t* srow = a.scores ? a.scores + (((size_t)b * H + h) * Lq + my_row) * Lk + 8 * half : nullptr;
+  const bf16_t* kbase = a.k + ((size_t)b * a.Hkv + kv) * Lk * DK;
+  const bf16_t* vbase = WITH_V ? a.vt + ((size_t)b * a.Hkv + kv) * (a.Lkp / 8) * (DK * 8) : nullptr;
+  // cooperative tile loads: thread -> two 16-byte chunks of the K tile (key, 8 features) and two
+  // of the V tile (contiguous 8 KB)
+  const int ck_key = tid >> 4, ck_c = tid & 15;          // chunk u: key ck_key + 16 u
+  // operand addresses in LDS
+  const int k_rd = key_of_r * SP_KROW + half * 16;       // + 32 ks
+  const int v_rd = (half * DK + r) * 16;                 // + (2 s DK + 32 db) 16
 
-  bf16x8 kop[DK / 16], vop[2][DK / 32];
-  auto load_k = [&](int tile) {
-    const bf16_t* kp = kbase + (size_t)min(tile * SP_TK + key_of_r, Lk - 1) * DK;
-#pragma unroll
-    for (int ks = 0; ks < DK / 16; ++ks) kop[ks] = *(const bf16x8*)(kp + 16 * ks);
-  };
-  auto load_v = [&](int tile) {
-    const bf16_t* vp = vbase + (size_t)tile * (SP_TK / 8 * DK * 8);
-#pragma unroll
-    for (int s = 0; s < 2; ++s)
-#pragma unroll
-      for (int db = 0; db < DK / 32; ++db) vop[s][db] = *(const bf16x8*)(vp + (2 * s * DK + 32 * db) * 8);
-  };
-  load_k(0);
-  if (WITH_V) load_v(0);
+  for (int rep = 0; rep < 2; ++rep) {
+    const int grp = rep ? (int)blockIdx.x : n_groups - 1 - (int)blockIdx.x;
+    if (rep && grp >= n_groups - 1 - grp) break;           // the middle group of an odd count is alone
+    const int i0 = grp * SP_GROUP + wv * SP_ROWS;          // first row of this wave
+    const bool have_rows = i0 < Lq;
+    const int my_row = min(i0 + r, Lq - 1);
+    const int vis_row = a.causal ? min(Lk, my_row + 1 + shift) : Lk;
+    const int i_last_w = min(i0 + SP_ROWS - 1, Lq - 1);
+    const int n_tiles_w =
+        have_rows ? ((a.causal ? min(Lk, i_last_w + 1 + shift) : Lk) + SP_TK - 1) / SP_TK : 0;
+    const int i_last_g = min(grp * SP_GROUP + SP_GROUP - 1, Lq - 1);
+    const int n_tiles = ((a.causal ? min(Lk, i_last_g + 1 + shift) : Lk) + SP_TK - 1) / SP_TK;
+    const int n_full =
+        (have_rows && i0 + SP_ROWS <= Lq) ? (a.causal ? min(Lk, i0 + 1 + shift) : Lk) / SP_TK : 0;
 
-  f32x16 o[DK / 32];
+    // B operands of the score product: Q[row][16 ks + 8 half + e]
+    bf16x8 qop[DK / 16];
+    {
+      const bf16_t* qp = a.q + (((size_t)b * H + h) * Lq + my_row) * DK + 8 * half;
 #pragma unroll
-  for (int db = 0; db < DK / 32; ++db)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
+      for (int ks = 0; ks < DK / 16; ++ks) qop[ks] = *(const bf16x8*)(qp + 16 * ks);
+    }
+    half_t* srow = a.scores ? a.scores + (((size_t)b * H + h) * Lq + my_row) * Lk + 8 * half : nullptr;
 
-  for (int tile = 0; tile < n_tiles; ++tile) {
-    const int j0 = tile * SP_TK;
-    const int tile_n = min(tile + 1, n_tiles - 1);
-    f32x16 acc;
+    pf_u32x4 kreg[2], vreg[2];
+    auto load_tile = [&](int tile) {
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < DK / 16; ++ks)
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[ks], qop[ks], acc, 0, 0, 0);
-    load_k(tile_n);
-    // acc[8 u + e] = score of key j0 + 16 u + 8 half + e for row r
-    float an[16];
-#pragma unroll
-    for (int v = 0; v < 16; ++v) an[v] = acc[v] * a.scale;
-    const bool full = tile < n_full;
-    const int jl = j0 + 8 * half;
-    if (a.scores) {
-      f16x8 hv0, hv1;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        hv0[e] = f32_to_half_sat(an[e]);
-        hv1[e] = f32_to_half_sat(an[8 + e]);
+      for (int u = 0; u < 2; ++u) {
+        const int j = min(tile * SP_TK + ck_key + 16 * u, Lk - 1);
+        kreg[u] = *(const pf_u32x4*)(kbase + (size_t)j * DK + 8 * ck_c);
+        if (WITH_V) vreg[u] = *(const pf_u32x4*)(vbase + (size_t)tile * (SP_TK / 8 * DK * 8) + (tid + 256 * u) * 8);
       }
-      half_t* sp = srow + j0;
-      if (full) {
-        *(f16x8*)sp = hv0;
-        *(f16x8*)(sp + 16) = hv1;
-      } else if (i0 + r < Lq) {
+    };
+    auto store_tile = [&](int buf) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          const f16x8 hv = u ? hv1 : hv0;
-          if (jl + 16 * u + 8 <= vis_row) {
-            *(f16x8*)(sp + 16 * u) = hv;
-          } else {
+      for (int u = 0; u < 2; ++u) {
+        *(pf_u32x4*)(ks_ + buf * SP_KTILE + (ck_key + 16 * u) * SP_KROW + ck_c * 16) = kreg[u];
+        if (WITH_V) *(pf_u32x4*)(vs_ + buf * SP_VTILE + (tid + 256 * u) * 16) = vreg[u];
+      }
+    };
+    if (rep) __syncthreads();                              // the first pass is done with both buffers
+    load_tile(0);
+    store_tile(0);
+    load_tile(min(1, n_tiles - 1));
+
+    f32x16 o[DK / 32];
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-              if (jl + 16 * u + e < vis_row) sp[16 * u + e] = hv[e];
+    for (int db = 0; db < DK / 32; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    for (int tile = 0; tile < n_tiles; ++tile) {
+      // tile `tile` is complete in buffer tile & 1, and every wave is done with the other buffer
+      lds_barrier();
+      store_tile((tile + 1) & 1);
+      load_tile(min(tile + 2, n_tiles - 1));
+      if (tile >= n_tiles_w) continue;                     // beyond this wave's diagonal (wave-uniform)
+      const unsigned char* kt = ks_ + (tile & 1) * SP_KTILE;
+      const unsigned char* vtl = vs_ + (tile & 1) * SP_VTILE;
+      const int j0 = tile * SP_TK;
+      f32x16 acc;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < DK / 16; ++ks) {
+        const bf16x8 kop = *(const bf16x8*)(kt + k_rd + 32 * ks);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop, qop[ks], acc, 0, 0, 0);
+      }
+      // acc[8 u + e] = score of key j0 + 16 u + 8 half + e for row r
+      float an[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) an[v] = acc[v] * a.scale;
+      const bool full = tile < n_full;
+      const int jl = j0 + 8 * half;
+      if (a.scores) {
+        f16x8 hv0, hv1;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          hv0[e] = f32_to_half_sat(an[e]);
+          hv1[e] = f32_to_half_sat(an[8 + e]);
+        }
+        half_t* sp = srow + j0;
+        if (full) {
+          *(f16x8*)sp = hv0;
+          *(f16x8*)(sp + 16) = hv1;
+        } else if (i0 + r < Lq) {
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            const f16x8 hv = u ? hv1 : hv0;
+            if (jl + 16 * u + 8 <= vis_row) {
+              *(f16x8*)(sp + 16 * u) = hv;
+            } else {
+#pragma unroll
+              for (int e = 0; e < 8; ++e)
+                if (jl + 16 * u + e < vis_row) sp[16 * u + e] = hv[e];
+            }
           }
         }
       }
+      if (WITH_V) {
+        if (!full) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            if (jl + 16 * (v >> 3) + (v & 7) >= vis_row) an[v] = -INFINITY;
+        }
+        float mx = an[0];
+#pragma unroll
+        for (int v = 1; v < 16; ++v) mx = fmaxf(mx, an[v]);
+        mx = halves_max(mx);
+        const float m_new = fmaxf(m_run, mx);
+        const float m2 = m_new * LOG2E;
+        const float alpha = fast_exp2(m_run * LOG2E - m2);
+        m_run = m_new;
+        float ps = 0.f;
+        bf16x8 pop[2];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float p = fast_exp2(__builtin_fmaf(an[v], LOG2E, -m2));
+          ps += p;
+          pop[v >> 3][v & 7] = (__bf16)p;
+        }
+        l_run = l_run * alpha + ps;
+        if (__any(alpha != 1.f)) {
+#pragma unroll
+          for (int db = 0; db < DK / 32; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+        }
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+          for (int db = 0; db < DK / 32; ++db) {
+            const bf16x8 vop = *(const bf16x8*)(vtl + v_rd + (2 * s * DK + 32 * db) * 16);
+            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pop[s], o[db], 0, 0, 0);
+          }
+      }
     }
+
     if (WITH_V) {
-      if (!full) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-          if (jl + 16 * (v >> 3) + (v & 7) >= vis_row) an[v] = -INFINITY;
-      }
-      float mx = an[0];
-#pragma unroll
-      for (int v = 1; v < 16; ++v) mx = fmaxf(mx, an[v]);
-      mx = halves_max(mx);
-      const float m_new = fmaxf(m_run, mx);
-      const float m2 = m_new * LOG2E;
-      const float alpha = fast_exp2(m_run * LOG2E - m2);
-      m_run = m_new;
-      float ps = 0.f;
-      bf16x8 pop[2];
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const float p = fast_exp2(__builtin_fmaf(an[v], LOG2E, -m2));
-        ps += p;
-        pop[v >> 3][v & 7] = (__bf16)p;
-      }
-      l_run = l_run * alpha + ps;
-      if (__any(alpha != 1.f)) {
+      // O[row][h][32 db + 8 (v/4) + 4 half + v%4] = o[db][v] / l
+      const float inv = 1.f / halves_sum(l_run);
+      if (i0 + r < Lq) {
+        const size_t at = (((size_t)b * Lq + i0 + r) * H + h) * DK + 4 * half;
 #pragma unroll
         for (int db = 0; db < DK / 32; ++db)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
-      }
-#pragma unroll
-      for (int s = 0; s < 2; ++s)
-#pragma unroll
-        for (int db = 0; db < DK / 32; ++db)
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[s][db], pop[s], o[db], 0, 0, 0);
-      load_v(tile_n);
-    }
-  }
-
-  if (WITH_V) {
-    // O[row][h][32 db + 8 (v/4) + 4 half + v%4] = o[db][v] / l
-    const float inv = 1.f / halves_sum(l_run);
-    if (i0 + r < Lq) {
-      const size_t at = (((size_t)b * Lq + i0 + r) * H + h) * DK + 4 * half;
-#pragma unroll
-      for (int db = 0; db < DK / 32; ++db)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          const float x0 = o[db][4 * q4] * inv, x1 = o[db][4 * q4 + 1] * inv;
-          const float x2 = o[db][4 * q4 + 2] * inv, x3 = o[db][4 * q4 + 3] * inv;
-          const size_t d = at + 32 * db + 8 * q4;
-          if (a.out_f32) {
-            *(float4*)((float*)a.out + d) = make_float4(x0, x1, x2, x3);
-          } else {
-            uint2 pk;
-            pk.x = f32_to_bf16_bits(x0) | (f32_to_bf16_bits(x1) << 16);
-            pk.y = f32_to_bf16_bits(x2) | (f32_to_bf16_bits(x3) << 16);
-            *(uint2*)((bf16_t*)a.out + d) = pk;
+          for (int q4 = 0; q4 < 4; ++q4) {
+            const float x0 = o[db][4 * q4] * inv, x1 = o[db][4 * q4 + 1] * inv;
+            const float x2 = o[db][4 * q4 + 2] * inv, x3 = o[db][4 * q4 + 3] * inv;
+            const size_t d = at + 32 * db + 8 * q4;
+            if (a.out_f32) {
+              *(float4*)((float*)a.out + d) = make_float4(x0, x1, x2, x3);
+            } else {
+              uint2 pk;
+              pk.x = f32_to_bf16_bits(x0) | (f32_to_bf16_bits(x1) << 16);
+              pk.y = f32_to_bf16_bits(x2) | (f32_to_bf16_bits(x3) << 16);
+              *(uint2*)((bf16_t*)a.out + d) = pk;
+            }
           }
-        }
+      }
     }
   }
 }

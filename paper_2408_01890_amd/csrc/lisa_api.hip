@@ -444,7 +444,7 @@ int run_prefill_fused(const lisa_desc* d, const void* q_lr, const void* k_lr, co
 
 // ---- standard layer, prefill, MFMA (bf16) ---------------------------------------------
 bool std_prefill_fast_ok(const lisa_desc* d) {
-  return d->dtype == LISA_BF16 && d->d_k == 128 && d->H % 4 == 0 && d->Lk % 8 == 0 && d->Lq > 1;
+  return d->dtype == LISA_BF16 && d->d_k == 128 && d->Lk % 8 == 0 && d->Lq > 1;
 }
 
 size_t std_prefill_ws(const lisa_desc* d) {   // V by key chunks
@@ -478,7 +478,8 @@ int run_std_prefill_fast(const lisa_desc* d, const void* q, const void* k, const
     int rc = check_launch();
     if (rc) return rc;
   }
-  dim3 grid((d->Lq + SP_ROWS - 1) / SP_ROWS, d->H / 4, d->B);
+  const int n_groups = (d->Lq + SP_GROUP - 1) / SP_GROUP;
+  dim3 grid((n_groups + 1) / 2, d->H, d->B);
   StageScope prof("k_std_prefill", st);
   if (out)
     k_std_prefill<true><<<grid, 256, 0, st>>>(a);
