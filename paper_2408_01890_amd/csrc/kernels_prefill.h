@@ -52,6 +52,8 @@ constexpr int PF_TK = 32;         // keys per tile
 constexpr int PF_XS_HEAD = PF_ROWS * PF_TK * 2 + 32;        // bytes per head of the A_{n-1} tile
 constexpr int PF_YS_ROW = PF_TK * 4 + 16;                   // bytes per (head,row) of the y tile
 constexpr int PF_YS_HEAD = PF_ROWS * PF_YS_ROW + 16;
+constexpr int PF_AS_ROW = 2 * PF_TK * 2 + 16;                // bytes per row of the A_n staging tile (64 keys)
+constexpr int PF_AS_HEAD = PF_ROWS * PF_AS_ROW;
 
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -225,6 +227,7 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
   unsigned short* w_s = (unsigned short*)(ys + GH * PF_YS_HEAD);
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform
+  unsigned char* as_ = (unsigned char*)w_s + Ffn::kStageBytes + wv * HPW * PF_AS_HEAD;   // this wave's A_n staging
   const int c = lane & 15, g = lane >> 4;
   const int b = blockIdx.y;
   const int hg0 = blockIdx.z * GH;                          // first head of the group
@@ -313,7 +316,16 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
     // ---- per-head state of stage B ------------------------------------------------------------------
     const int my_row = min(i0 + c, Lq - 1);                   // clamped for loads; stores check i0 + c
     const int vis_row = a.causal ? min(Lk, my_row + 1 + shift) : Lk;   // keys visible to my row
-    const unsigned s_off = ((unsigned)my_row * Lk + 8 * g) * 2;        // my 8 keys of tile 0 in my row
+    // A_n leaves through LDS in whole 128-byte pieces of a row (64 keys = two tiles): lane ->
+    // rows lane / 8 and lane / 8 + 8, keys 8 (lane % 8) .. + 7 of the pair of tiles
+    unsigned a_off[2];
+    int a_vis[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int gi = i0 + (lane >> 3) + 8 * u;
+      a_off[u] = ((unsigned)min(gi, Lq - 1) * Lk + 8 * (lane & 7)) * 2;
+      a_vis[u] = gi < Lq ? (a.causal ? min(Lk, gi + 1 + shift) : Lk) : 0;
+    }
     f32x4 o[HPW][DK / 16];
     float m_run[HPW], l_run[HPW];
     // PERSIST: every head keeps its own operand registers; each is refilled right after its use
@@ -416,7 +428,6 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
       const int tile_n = tile_at(min(it + 1, n_mine - 1));      // next tile (clamped: loads stay valid)
       const bool full = tile < n_full;                          // workgroup-uniform
       const int jl = j0 + 8 * g;                                // first of my 8 keys
-      f16x8 hv[HPW];
 #pragma unroll
       for (int hh = 0; hh < HPW; ++hh) {
         // low-rank scores for keys j0 + 8 g + e of row c
@@ -439,9 +450,13 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
           an[e] = s0[e] * a.dscale + y0[e];
           an[4 + e] = s1[e] * a.dscale + y1[e];
         }
-        // A_n for the next layer, stored at the end of the stage
+        // A_n for the next layer: into this wave's staging tile, stored at the end of the stage
+        if (a.scores) {
+          f16x8 hv;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) hv[hh][e] = f32_to_half_sat(an[e]);
+          for (int e = 0; e < 8; ++e) hv[e] = f32_to_half_sat(an[e]);
+          *(f16x8*)(as_ + hh * PF_AS_HEAD + c * PF_AS_ROW + (tile & 1) * 64 + g * 16) = hv;
+        }
         // online softmax, statistics of row c kept by all four lanes 16 g + c; exponentials in
         // base 2: p = 2^(A log2(e) - m log2(e))
         if (!full) {                              // workgroup-uniform: only diagonal / ragged tiles mask
@@ -481,19 +496,25 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
       }
       // Loads and stores of a wave complete in issue order: the stores of A_n and the loads of the
       // A_{n-1} tile after next (both HBM traffic) go last, behind every operand load of this tile.
-      if (a.scores) {
+      // A_n is written once both tiles of a pair are staged (64-byte pieces of a line reach HBM at
+      // half the rate of whole lines): after the odd tile when walking upwards (or after an even
+      // tile without a partner), after the even tile when walking downwards.
+      if (a.scores && (rep ? (tile & 1) == 0 : ((tile & 1) == 1 || tile + 1 >= n_tiles_all))) {
+        const int jp = (tile >> 1) * (2 * PF_TK);               // first key of the pair
+        const bool pair_full = (tile | 1) < n_full;             // workgroup-uniform
+        const int jc = jp + 8 * (lane & 7);
 #pragma unroll
         for (int hh = 0; hh < HPW; ++hh) {
-          half_t* st = s_base[hh] + j0;
-          if (full) {
-            st_uv<f16x8>(st, s_off, hv[hh]);
-          } else if (i0 + c < Lq) {
-            if (jl + 8 <= vis_row) {
-              st_uv<f16x8>(st, s_off, hv[hh]);
+          half_t* st = s_base[hh] + jp;
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            const f16x8 hv = *(const f16x8*)(as_ + hh * PF_AS_HEAD + ((lane >> 3) + 8 * u) * PF_AS_ROW + (lane & 7) * 16);
+            if (pair_full || jc + 8 <= a_vis[u]) {
+              st_uv<f16x8>(st, a_off[u], hv);
             } else {
 #pragma unroll
               for (int e = 0; e < 8; ++e)
-                if (jl + e < vis_row) st_uv<_Float16>(st, s_off + 2 * e, hv[hh][e]);
+                if (jc + e < a_vis[u]) st_uv<_Float16>(st, a_off[u] + 2 * e, hv[e]);
             }
           }
         }

@@ -361,7 +361,7 @@ template <int NG, int FS, int HPW, int NW>
 int launch_prefill_fused_t(const lisa_desc* d, const PrefillArgs& a, hipStream_t st) {
   constexpr int GH = NW * HPW, H = NG * GH;
   typedef MfmaFfn<(H + 15) / 16, FS, (GH + 15) / 16> Ffn;
-  const size_t lds = (size_t)H * PF_XS_HEAD + (size_t)GH * PF_YS_HEAD + Ffn::kStageBytes;
+  const size_t lds = (size_t)H * PF_XS_HEAD + (size_t)GH * PF_YS_HEAD + Ffn::kStageBytes + (size_t)GH * PF_AS_HEAD;
   auto kern = k_lisa_prefill_fused<NG, FS, HPW, NW>;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)lds);
