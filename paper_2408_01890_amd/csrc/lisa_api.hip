@@ -314,6 +314,9 @@ bool prefill_fused_ok(const lisa_desc* d) {
   return d->H == 8 || d->H == 16 || d->H == 24 || d->H == 32 || d->H == 40;
 }
 
+// Head groups (grid.z) of the instantiation that run_prefill_fused picks for H heads.
+int prefill_groups(int H) { return H == 32 ? 2 : H == 40 ? 5 : 1; }
+
 struct PrefillWs {
   size_t qp, kp, vt, part_o, part_ml, total;   // byte offsets in the workspace
   int Lqp, Lkp, split;
@@ -324,7 +327,7 @@ constexpr int kComputeUnits = 256;   // MI355X
 // Key splits per row block: small problems have too few (row block, head group) units to
 // fill the chip and their longest unit (the last row block) sets the run time.
 int prefill_split(const lisa_desc* d, int Lqp) {
-  const int groups = d->H == 32 || d->H == 40 ? 2 : 1;
+  const int groups = prefill_groups(d->H);
   const long long units = (long long)(Lqp / PF_ROWS) * d->B * groups;
   const int tiles_max = (d->Lk + PF_TK - 1) / PF_TK;
   int s = 1;
@@ -336,7 +339,7 @@ int prefill_split(const lisa_desc* d, int Lqp) {
 // Two units (a long and a short one) per workgroup once that still leaves two workgroups per
 // compute unit: equal work per workgroup, FFN weights staged once for both.
 int prefill_pair(const lisa_desc* d, int Lqp, int split) {
-  const int groups = d->H == 32 || d->H == 40 ? 2 : 1;
+  const int groups = prefill_groups(d->H);
   const long long units = (long long)(Lqp / PF_ROWS) * split * d->B * groups;
   if (const char* e = getenv("LISA_PREFILL_PAIR")) return atoi(e) != 0;
   return units >= 2 * kComputeUnits;
@@ -430,7 +433,7 @@ int run_prefill_fused(const lisa_desc* d, const void* q_lr, const void* k_lr, co
     case 16: rc = launch_prefill_fused_fs<1, 2, 8>(d, a, st); break;   // one group of 16
     case 24: rc = launch_prefill_fused_fs<1, 3, 8>(d, a, st); break;   // one group of 24
     case 32: rc = launch_prefill_fused_fs<2, 2, 8>(d, a, st); break;   // two groups of 16
-    default: rc = launch_prefill_fused_fs<2, 2, 10>(d, a, st); break;  // H = 40: two groups of 20
+    default: rc = launch_prefill_fused_fs<5, 1, 8>(d, a, st); break;   // H = 40: five groups of 8
   }
   if (rc == LISA_OK && a.split > 1) {
     dim3 grid(d->Lq, d->B);
