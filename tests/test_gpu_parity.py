@@ -284,6 +284,44 @@ def test_lisa_prefill_chunked_rows_match_full_prefill():
     assert torch.equal(scores_t[..., vis], scores[:, :, -t:][..., vis])
 
 
+def test_lisa_prefill_fused_paired_units_odd_count():
+    """Enough (row block, head group) units that a workgroup takes two of them (a long one
+    walked upwards, a short one walked downwards), with an odd number of row blocks so that the
+    middle one is taken alone; no key split."""
+    cfg = synth.LayerShape("pair_odd", "bf16", 8, 8, 8, 1040, 1024, 128, 22, 32)
+    inp = synth.make_prefill_inputs(cfg, 31, DEV, ffn="fan_in")
+    prev = std_prev(inp)
+    out, scores = lisa.lisa_attn_prefill(inp["q_lr"], inp["k_lr"], inp["v"], prev, inp["w1"],
+                                         inp["w2"])
+    torch.cuda.synchronize()
+    assert lisa.last_path() == "mfma_fused"
+    rows_by_b = {b: synth.sample_rows(cfg.L, 48, 200 + b) for b in range(cfg.B)}
+    rows_by_b[0] = np.arange(cfg.L)              # one sequence in full: every row block of the pairing
+    check_prefill(cfg, inp, prev, out, scores, rows_by_b)
+
+
+def test_lisa_prefill_fused_chunked_rows_match_full_prefill():
+    """Lq < Lk on the fused kernel: the last 40 query rows against all keys equal the same rows
+    of a full prefill (same tiles, same order of accumulation per row block is not required:
+    compared through the oracle's tolerance and bit-exactly where the tiling coincides)."""
+    cfg = synth.LayerShape("chunk_fused", "bf16", 1, 8, 4, 208, 1024, 128, 22, 32)
+    inp = synth.make_prefill_inputs(cfg, 6, DEV, ffn="fan_in")
+    prev = std_prev(inp)
+    t = 48                                       # 208 - 48 = 160: row blocks of the chunk line up
+    out_t, scores_t = lisa.lisa_attn_prefill(inp["q_lr"][:, :, -t:].contiguous(), inp["k_lr"],
+                                             inp["v"], prev[:, :, -t:].contiguous(), inp["w1"],
+                                             inp["w2"])
+    torch.cuda.synchronize()
+    assert lisa.last_path() == "mfma_fused"
+    rows = np.arange(cfg.L - t, cfg.L)
+    prev_rows = hp.gather_score_rows(prev, 0, rows)
+    a_ref, o_ref = hp.oracle_lisa_rows(inp, 0, rows, prev_rows)
+    tol = hp.TOL[torch.bfloat16]
+    assert hp.row_rel_err(hp.f64(out_t[0]), o_ref) <= tol
+    got = hp.f64(scores_t[0]).transpose(1, 0, 2)
+    assert hp.scores_row_rel_err(got, a_ref, rows, cfg.L, cfg.L) <= tol
+
+
 # ---------------------------------------------------------------------------------------
 # LiSA prefill at the benchmark sizes
 # ---------------------------------------------------------------------------------------
