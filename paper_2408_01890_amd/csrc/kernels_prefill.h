@@ -31,13 +31,14 @@
 //
 // Software pipeline of one workgroup (tile t = 32 keys):
 //   top of tile t : the A_{n-1} tile t is already in LDS (xs); barrier B1
-//   stage A(t)    : reads xs, writes ys; barrier B2.  With two heads per wave the V operands of
-//                   the second head for tile t are loaded here, between the FFN blocks.
-//   stage B(t)    : head by head, consumes the K_LR / V operand registers and refills them right
-//                   away with the same head's operands of tile t+1 (one register set per head when
-//                   the register file allows, else one rotating set refilled for the next head);
-//                   then stores A_n, writes the A_{n-1} tile t+1 (in registers since the end of
-//                   stage B(t-1)) into xs and issues the loads of tile t+2.
+//   stage A(t)    : reads xs, writes ys; barrier B2.  Between the FFN blocks it issues what does not
+//                   depend on this stage: the V operands of the wave's second head for tile t, the
+//                   loads of the A_{n-1} tile t+1 and the stores of the pair of A_n tiles that
+//                   stage B(t-1) completed.
+//   stage B(t)    : head by head, consumes the K_LR / V operand registers and refills them with
+//                   the operands of tile t+1 (one register set per head when the register file
+//                   allows, else one rotating set refilled for the next head); stages A_n in LDS;
+//                   then writes the A_{n-1} tile t+1 into xs.
 // What bounds it: a compute unit takes in about 75 GB/s of 16-byte loads from the L2 (measured),
 // and a tile moves 192 KB through that pipe (V 128, K_LR 32, A_{n-1} 32); a load that cannot be
 // issued blocks its wave, so the loads are spread over both stages rather than issued in bursts.
@@ -355,12 +356,33 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
       for (int nb = 0; nb < DK / 16; ++nb) vop[hh][nb] = ld_uv<bf16x8>(vt, v_off, nb * 256);
     }
 
-    // the A_{n-1} tile t+2 travels in xr for one whole tile period: loaded at the end of stage
-    // B(t), written to LDS at the end of stage B(t+1)
+    // the A_{n-1} tile t+1 travels in xr through stage B(t): loaded during stage A(t), written to
+    // LDS at the end of stage B(t)
     pf_u32x4 xr[XCH];
     load_x(t_begin, xr);
     store_x(xr);
-    load_x(tile_at(min(1, n_mine - 1)), xr);
+    // Stores of a staged pair of A_n tiles (head hh of this wave); `pending` = last tile of a pair
+    // whose stores are still to be issued.  They go out during stage A of the next tile: all
+    // waves of a workgroup run the same stage at the same time, stage B is where the operand loads
+    // crowd the load / store pipe of the compute unit and stage A is where it has room.
+    int pending = -1;
+    auto flush_scores = [&](int tile, int hh) {
+      const int jp = (tile >> 1) * (2 * PF_TK);               // first key of the pair
+      const bool pair_full = (tile | 1) < n_full;             // workgroup-uniform
+      const int jc = jp + 8 * (lane & 7);
+      half_t* st = s_base[hh] + jp;
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const f16x8 hv = *(const f16x8*)(as_ + hh * PF_AS_HEAD + ((lane >> 3) + 8 * u) * PF_AS_ROW + (lane & 7) * 16);
+        if (pair_full || jc + 8 <= a_vis[u]) {
+          st_uv<f16x8>(st, a_off[u], hv);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (jc + e < a_vis[u]) st_uv<_Float16>(st, a_off[u] + 2 * e, hv[e]);
+        }
+      }
+    };
 
     // Everything loaded so far has arrived before the loop is entered: the wait counts inside the
     // loop then follow from the loop's own issue order alone (a load pending on entry would cap
@@ -375,6 +397,12 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
       // from LDS as the products need them (stage B keeps the register file)
 #pragma unroll
       for (int q = 0; q < NBW; q += 2) {
+        if (pending >= 0) {
+          // heads of this wave dealt over the block pairs
+#pragma unroll
+          for (int hh = q / 2; hh < HPW; hh += NBW / 2) flush_scores(pending, hh);
+        }
+        if (q + 2 >= NBW) load_x(tile_at(min(it + 1, n_mine - 1)), xr);
         if (SPREAD) {
           constexpr int PER = (DK / 16 + NBW / 2 - 1) / (NBW / 2);    // V loads per block pair
           const bf16_t* vt = v_base[HPW - 1] + (size_t)tile * (PF_TK / 8 * DK * 8);
@@ -422,6 +450,7 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
               if (GH % 16 == 0 || hl < GH) *(float*)(ys + hl * PF_YS_HEAD + yoff[n]) = y[n][hb][v];
             }
       }
+      pending = -1;
       lds_barrier();                                                       // B2
 
       // ---- stage B: per head scores, softmax, P V ------------------------------------------------
@@ -474,11 +503,16 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
         m_run[hh] = m_new;
         float ps = 0.f;
         bf16x8 pop;
+        // SPREAD: the V operands of the first head for the next tile are loaded here, one load
+        // per exponential of the second head (its registers are free since the first head's P V)
+        const bf16_t* v0n = v_base[0] + (size_t)tile_n * (PF_TK / 8 * DK * 8);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
+          if (SPREAD && hh == 1) vop[0][e] = ld_uv<bf16x8>(v0n, v_off, e * 256);
           const float p = fast_exp2(__builtin_fmaf(an[e], LOG2E, -m2));
           ps += p;
           pop[e] = (__bf16)p;                     // hardware round-to-nearest-even conversion
+          if (SPREAD && hh == 1) __builtin_amdgcn_sched_barrier(0);
         }
         l_run[hh] = l_run[hh] * alpha + ps;       // partial sum over my keys; groups merged at the end
         if (__any(alpha != 1.f)) {                // wave-uniform: the running maximum rarely moves
@@ -491,38 +525,20 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
 #pragma unroll
         for (int nb = 0; nb < DK / 16; ++nb) {
           o[hh][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[hs][nb], pop, o[hh][nb], 0, 0, 0);
-          if (!(SPREAD && hh == 1)) vop[hs][nb] = ld_uv<bf16x8>(vt, v_off, nb * 256);
+          if (!SPREAD) vop[hs][nb] = ld_uv<bf16x8>(vt, v_off, nb * 256);
         }
       }
-      // Loads and stores of a wave complete in issue order: the stores of A_n and the loads of the
-      // A_{n-1} tile after next (both HBM traffic) go last, behind every operand load of this tile.
       // A_n is written once both tiles of a pair are staged (64-byte pieces of a line reach HBM at
       // half the rate of whole lines): after the odd tile when walking upwards (or after an even
       // tile without a partner), after the even tile when walking downwards.
-      if (a.scores && (rep ? (tile & 1) == 0 : ((tile & 1) == 1 || tile + 1 >= n_tiles_all))) {
-        const int jp = (tile >> 1) * (2 * PF_TK);               // first key of the pair
-        const bool pair_full = (tile | 1) < n_full;             // workgroup-uniform
-        const int jc = jp + 8 * (lane & 7);
-#pragma unroll
-        for (int hh = 0; hh < HPW; ++hh) {
-          half_t* st = s_base[hh] + jp;
-#pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            const f16x8 hv = *(const f16x8*)(as_ + hh * PF_AS_HEAD + ((lane >> 3) + 8 * u) * PF_AS_ROW + (lane & 7) * 16);
-            if (pair_full || jc + 8 <= a_vis[u]) {
-              st_uv<f16x8>(st, a_off[u], hv);
-            } else {
-#pragma unroll
-              for (int e = 0; e < 8; ++e)
-                if (jc + e < a_vis[u]) st_uv<_Float16>(st, a_off[u] + 2 * e, hv[e]);
-            }
-          }
-        }
-      }
+      if (a.scores && (rep ? (tile & 1) == 0 : ((tile & 1) == 1 || tile + 1 >= n_tiles_all))) pending = tile;
       // every wave left stage A(tile), the last reader of xs, before B2; stage A(tile+1) reads the
       // new tile after B1
       store_x(xr);
-      load_x(tile_at(min(it + 2, n_mine - 1)), xr);
+    }
+    if (pending >= 0) {
+#pragma unroll
+      for (int hh = 0; hh < HPW; ++hh) flush_scores(pending, hh);
     }
 
     // ---- epilogue ----------------------------------------------------------------------------------
