@@ -50,15 +50,23 @@ constexpr int SP_TK = 32;
 constexpr int SP_KROW = 128 * 2 + 16;       // bytes per key row of the K tile in LDS (padded: no bank conflicts)
 constexpr int SP_KTILE = SP_TK * SP_KROW;   // 8704
 constexpr int SP_VTILE = SP_TK * 128 * 2;   // 8192
+constexpr int SP_SROW = 2 * SP_TK * 2 + 16;  // bytes per row of a wave's score staging tile (64 keys, padded)
+constexpr int SP_STILE = SP_ROWS * SP_SROW;  // 4608
+
+// LDS bytes: two K tiles, the four staging tiles, two V tiles.
+constexpr int std_prefill_head_lds(bool with_v) {
+  return 2 * SP_KTILE + SP_WAVES * SP_STILE + (with_v ? 2 * SP_VTILE : 0);
+}
 
 // grid (ceil(n_groups / 2), H, B) with n_groups = ceil(Lq / 128), block 256.
 // Requires d_k = 128, Lk % 8 == 0.
 template <bool WITH_V>
 __global__ __launch_bounds__(256) void k_std_prefill(StdPrefillArgs a) {
   constexpr int DK = 128;
-  __shared__ __align__(16) unsigned char lds[2 * SP_KTILE + (WITH_V ? 2 * SP_VTILE : 0)];
+  __shared__ __align__(16) unsigned char lds[std_prefill_head_lds(WITH_V)];
   unsigned char* ks_ = lds;
-  unsigned char* vs_ = lds + 2 * SP_KTILE;
+  unsigned char* ss_ = ks_ + 2 * SP_KTILE;              // score staging, one tile per wave
+  unsigned char* vs_ = ss_ + SP_WAVES * SP_STILE;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r = lane & 31, half = lane >> 5;
@@ -101,7 +109,8 @@ __global__ __launch_bounds__(256) void k_std_prefill(StdPrefillArgs a) {
 #pragma unroll
       for (int ks = 0; ks < DK / 16; ++ks) qop[ks] = *(const bf16x8*)(qp + 16 * ks);
     }
-    half_t* srow = a.scores ? a.scores + (((size_t)b * H + h) * Lq + my_row) * Lk + 8 * half : nullptr;
+    half_t* sbase = a.scores ? a.scores + ((size_t)b * H + h) * Lq * Lk : nullptr;
+    unsigned char* stg = ss_ + wv * SP_STILE;
 
     pf_u32x4 kreg[2], vreg[2];
     auto load_tile = [&](int tile) {
@@ -155,26 +164,32 @@ __global__ __launch_bounds__(256) void k_std_prefill(StdPrefillArgs a) {
       const bool full = tile < n_full;
       const int jl = j0 + 8 * half;
       if (a.scores) {
+        // A leaves through the wave's staging tile in whole 128-byte pieces of a row (64 keys =
+        // two tiles): 64-byte pieces reach HBM at about half the rate of whole lines
         f16x8 hv0, hv1;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           hv0[e] = f32_to_half_sat(an[e]);
           hv1[e] = f32_to_half_sat(an[8 + e]);
         }
-        half_t* sp = srow + j0;
-        if (full) {
-          *(f16x8*)sp = hv0;
-          *(f16x8*)(sp + 16) = hv1;
-        } else if (i0 + r < Lq) {
+        unsigned char* sl = stg + r * SP_SROW + (tile & 1) * 64 + 16 * half;
+        *(f16x8*)sl = hv0;
+        *(f16x8*)(sl + 32) = hv1;
+        if ((tile & 1) == 1 || tile == n_tiles_w - 1) {
+          const int jc = (tile >> 1) * (2 * SP_TK) + 8 * (lane & 7);
+          const bool pair_full = (tile | 1) < n_full;
 #pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            const f16x8 hv = u ? hv1 : hv0;
-            if (jl + 16 * u + 8 <= vis_row) {
-              *(f16x8*)(sp + 16 * u) = hv;
+          for (int u = 0; u < 4; ++u) {
+            const int row = 8 * u + (lane >> 3), gi = i0 + row;
+            const f16x8 hv = *(const f16x8*)(stg + row * SP_SROW + (lane & 7) * 16);
+            const int vis = gi < Lq ? (a.causal ? min(Lk, gi + 1 + shift) : Lk) : 0;
+            half_t* sp = sbase + (size_t)min(gi, Lq - 1) * Lk + jc;
+            if (pair_full || jc + 8 <= vis) {
+              *(f16x8*)sp = hv;
             } else {
 #pragma unroll
               for (int e = 0; e < 8; ++e)
-                if (jl + 16 * u + e < vis_row) sp[16 * u + e] = hv[e];
+                if (jc + e < vis) sp[e] = hv[e];
             }
           }
         }
