@@ -142,6 +142,20 @@ int std_attn_scores(const lisa_desc* desc, const void* q, const void* k, const v
                     void* scores_out, void* out, void* workspace, size_t workspace_bytes,
                     void* hip_stream);
 
+/*
+ * lisa_cache_fill -- hand-over from prefill to decode: a LiSA layer keeps K_LR instead of K
+ * for the decoding stage (Sec. 5.2; Sec. 2.2 for the two stages).  Copies the K_LR and V rows of
+ * the first Lk tokens into the caches, in the layouts lisa_attn_decode reads.
+ * Uses dtype, B, Hkv, Lk, r, d_k, kcache_dim_major and Lmax (>= Lk) of the descriptor.
+ *   k_lr        [B,Hkv,Lk,r]     in
+ *   v           [B,Hkv,Lk,d_k]   in
+ *   k_lr_cache  [B,Hkv,Lmax,r] or [B,Hkv,r,Lmax]   out (key indices 0 .. Lk-1 are written)
+ *   v_cache     [B,Hkv,Lmax,d_k]                   out (likewise)
+ * No workspace.  Byte copies: the caches hold exactly the input values.
+ */
+int lisa_cache_fill(const lisa_desc* desc, const void* k_lr, const void* v, void* k_lr_cache,
+                    void* v_cache, void* hip_stream);
+
 /* Host-only helpers (no HIP call). */
 
 /* Scratch bytes the given entry point (lisa_ws_kind) needs for this descriptor. */

@@ -231,4 +231,36 @@ __global__ void k_append(const T* __restrict__ k_new, const T* __restrict__ v_ne
     v_cache[b * vs.b + kvh * vs.h + pos * vs.j + t * vs.t] = v_new[((size_t)b * Hkv + kvh) * dk + t];
 }
 
+// Prefill -> decode hand-over of the K_LR cache in the dimension-major layout:
+// cache[b][kv][t][j] = k_lr[b][kv][j][t] for j < Lk, through a 64-token LDS tile so that both
+// sides move contiguous runs.  grid (ceil(Lk / 64), Hkv, B), block 256; r <= 128.
+template <typename T>
+__global__ __launch_bounds__(256) void k_kcache_fill_dim_major(const T* __restrict__ k_lr, T* __restrict__ cache,
+                                                               int Hkv, int Lk, int r, int Lmax) {
+  __shared__ T tile[64 * 129];
+  const int j0 = blockIdx.x * 64, n = min(64, Lk - j0);
+  const size_t bh = (size_t)blockIdx.z * Hkv + blockIdx.y;
+  const T* src = k_lr + (bh * Lk + j0) * r;              // n * r contiguous elements
+  for (int e = threadIdx.x; e < n * r; e += 256) tile[(e / r) * (r + 1) + e % r] = src[e];
+  __syncthreads();
+  T* dst = cache + bh * r * Lmax + j0;
+  for (int e = threadIdx.x; e < r * 64; e += 256) {
+    const int t = e >> 6, j = e & 63;
+    if (j < n) dst[(size_t)t * Lmax + j] = tile[j * (r + 1) + t];
+  }
+}
+
+// Row copy of n_rows rows of row_elems elements from a dense [B*Hkv][n_rows] tensor into the
+// first rows of a [B*Hkv][Lmax] cache.  grid (ceil(n_rows * row_elems / 1024), B * Hkv), block 256.
+template <typename T>
+__global__ __launch_bounds__(256) void k_cache_fill_rows(const T* __restrict__ src, T* __restrict__ cache,
+                                                         int n_rows, int row_elems, int Lmax) {
+  const size_t bh = blockIdx.y;
+  const size_t n = (size_t)n_rows * row_elems;
+  const T* s = src + bh * n;
+  T* d = cache + bh * (size_t)Lmax * row_elems;
+  for (size_t e = (size_t)blockIdx.x * 1024 + threadIdx.x; e < min(n, ((size_t)blockIdx.x + 1) * 1024); e += 256)
+    d[e] = s[e];
+}
+
 }  // namespace lisa

@@ -497,6 +497,39 @@ int run_std_prefill_fast(const lisa_desc* d, const void* q, const void* k, const
 
 extern "C" {
 
+int lisa_cache_fill(const lisa_desc* d, const void* k_lr, const void* v, void* k_lr_cache, void* v_cache,
+                    void* hip_stream) {
+  if (!d || !k_lr || !v || !k_lr_cache || !v_cache) return LISA_ERR_NULL;
+  if (d->dtype != LISA_F32 && d->dtype != LISA_BF16) return LISA_ERR_UNSUPPORTED;
+  if (d->B < 1 || d->Hkv < 1 || d->Lk < 1 || d->r < 1 || d->d_k < 1 || d->Lmax < d->Lk) return LISA_ERR_SHAPE;
+  if (d->kcache_dim_major != 0 && d->kcache_dim_major != 1) return LISA_ERR_SHAPE;
+  if (d->kcache_dim_major && d->r > 128) return LISA_ERR_UNSUPPORTED;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int rows = d->B * d->Hkv;
+  auto fill_rows = [&](const void* src, void* dst, int row_elems) {
+    dim3 grid((unsigned)(((size_t)d->Lk * row_elems + 1023) / 1024), rows);
+    if (d->dtype == LISA_F32)
+      k_cache_fill_rows<float><<<grid, 256, 0, st>>>((const float*)src, (float*)dst, d->Lk, row_elems, d->Lmax);
+    else
+      k_cache_fill_rows<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)src, (bf16_t*)dst, d->Lk, row_elems, d->Lmax);
+  };
+  if (d->kcache_dim_major) {
+    dim3 grid((d->Lk + 63) / 64, d->Hkv, d->B);
+    if (d->dtype == LISA_F32)
+      k_kcache_fill_dim_major<float><<<grid, 256, 0, st>>>((const float*)k_lr, (float*)k_lr_cache, d->Hkv, d->Lk,
+                                                          d->r, d->Lmax);
+    else
+      k_kcache_fill_dim_major<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)k_lr, (bf16_t*)k_lr_cache, d->Hkv,
+                                                           d->Lk, d->r, d->Lmax);
+  } else {
+    fill_rows(k_lr, k_lr_cache, d->r);
+  }
+  fill_rows(v, v_cache, d->d_k);
+  int rc = check_launch();
+  if (rc == LISA_OK) g_path = "cache_fill";
+  return rc;
+}
+
 size_t lisa_score_elem_bytes(const lisa_desc* desc) {
   if (!desc || (desc->dtype != LISA_F32 && desc->dtype != LISA_BF16)) return 0;
   return score_elem(desc);

@@ -26,7 +26,7 @@ EXPORTS = (
     "lisa_attn_prefill", "lisa_attn_decode", "std_attn_scores", "lisa_workspace_bytes",
     "lisa_scores_bytes", "lisa_score_elem_bytes", "lisa_kcache_saved_bytes", "lisa_supported",
     "lisa_strerror", "lisa_last_hip_error", "lisa_last_path", "lisa_profile_enable",
-    "lisa_profile_collect",
+    "lisa_profile_collect", "lisa_cache_fill",
 )
 
 
@@ -89,6 +89,8 @@ def _lib():
         h.lisa_last_path.restype = C.c_char_p
         h.lisa_profile_enable.argtypes = [C.c_int]
         h.lisa_profile_enable.restype = C.c_int
+        h.lisa_cache_fill.argtypes = [dp] + [vp] * 5
+        h.lisa_cache_fill.restype = C.c_int
         h.lisa_profile_collect.argtypes = [C.POINTER(StageTime), C.c_int]
         h.lisa_profile_collect.restype = C.c_int
         _handle = h
@@ -262,6 +264,24 @@ def lisa_attn_prefill(q_lr, k_lr, v, scores_prev, w1, w2, *, mix=MIX_ADD, write_
     if rc:
         raise LisaError(rc, "lisa_attn_prefill")
     return out, (scores_out if write_scores else None)
+
+
+def lisa_cache_fill(k_lr, v, k_lr_cache, v_cache, *, dim_major=True):
+    """Prefill -> decode hand-over: copies k_lr [B,Hkv,Lk,r] and v [B,Hkv,Lk,d_k] into the first
+    Lk key slots of k_lr_cache ([B,Hkv,r,Lmax] if dim_major else [B,Hkv,Lmax,r]) and
+    v_cache [B,Hkv,Lmax,d_k]."""
+    B, Hkv, Lk, r = k_lr.shape
+    _, _, Lmax, dk = v_cache.shape
+    dt = k_lr.dtype
+    desc = make_desc(dt, B, Hkv, Hkv, 1, Lk, dk, r, kcache_dim_major=int(dim_major), Lmax=Lmax)
+    kshape = (B, Hkv, r, Lmax) if dim_major else (B, Hkv, Lmax, r)
+    rc = _lib().lisa_cache_fill(
+        C.byref(desc), _ptr(k_lr, "k_lr", dtype=dt), _ptr(v, "v", (B, Hkv, Lk, dk), dt),
+        _ptr(k_lr_cache, "k_lr_cache", kshape, dt), _ptr(v_cache, "v_cache", (B, Hkv, Lmax, dk), dt),
+        _stream())
+    if rc:
+        raise LisaError(rc, "lisa_cache_fill")
+    return k_lr_cache, v_cache
 
 
 def lisa_attn_decode(q_lr, k_lr_cache, v_cache, Lk, score_row_prev, w1, w2, *, k_lr_new=None,

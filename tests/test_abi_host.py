@@ -89,6 +89,19 @@ def test_decode_and_std_reject_bad_arguments():
     assert lib.std_attn_scores(C.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, None, 0, None) == -5
 
 
+def test_cache_fill_rejects_bad_arguments():
+    lib = lisa.library()
+    d = lisa.make_desc(lisa.BF16, 2, 8, 2, 1, 100, 128, 22, 0, kcache_dim_major=1, Lmax=128)
+    assert lib.lisa_cache_fill(None, FAKE, FAKE, FAKE, FAKE, None) == -1
+    assert lib.lisa_cache_fill(C.byref(d), FAKE, None, FAKE, FAKE, None) == -1
+    short = lisa.make_desc(lisa.BF16, 2, 8, 2, 1, 100, 128, 22, 0, kcache_dim_major=1, Lmax=64)
+    assert lib.lisa_cache_fill(C.byref(short), FAKE, FAKE, FAKE, FAKE, None) == -2
+    layout = lisa.make_desc(lisa.BF16, 2, 8, 2, 1, 100, 128, 22, 0, kcache_dim_major=3, Lmax=128)
+    assert lib.lisa_cache_fill(C.byref(layout), FAKE, FAKE, FAKE, FAKE, None) == -2
+    wide = lisa.make_desc(lisa.BF16, 2, 8, 2, 1, 100, 256, 200, 0, kcache_dim_major=1, Lmax=128)
+    assert lib.lisa_cache_fill(C.byref(wide), FAKE, FAKE, FAKE, FAKE, None) == -3
+
+
 def test_strerror_is_defined_for_every_status():
     lib = lisa.library()
     seen = set()

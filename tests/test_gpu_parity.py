@@ -403,6 +403,38 @@ def test_lisa_decode_small(dtype, dim_major, append, ffn):
         assert hp.row_rel_err(hp.f64(out[b])[None], o_ref) <= tol
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dim_major", [True, False])
+def test_cache_fill_is_a_byte_copy_and_feeds_decode(dtype, dim_major):
+    """Prefill -> decode hand-over: the caches hold exactly the prefill K_LR / V rows in the decode
+    layout, slots beyond Lk stay untouched, and a decode step on the filled caches equals the last
+    row of the prefill (oracle tolerance)."""
+    cfg = synth.LayerShape("fill", dtype, 2, 8, 4, 150, 512, 64, 11, 32)
+    inp = synth.make_prefill_inputs(cfg, 41, DEV)
+    dt = cfg.torch_dtype
+    L, Lmax = cfg.L, 192
+    kshape = (cfg.B, cfg.Hkv, cfg.r, Lmax) if dim_major else (cfg.B, cfg.Hkv, Lmax, cfg.r)
+    kc = torch.full(kshape, SENTINEL, dtype=dt, device=DEV)
+    vc = torch.full((cfg.B, cfg.Hkv, Lmax, cfg.d_k), SENTINEL, dtype=dt, device=DEV)
+    lisa.lisa_cache_fill(inp["k_lr"], inp["v"], kc, vc, dim_major=dim_major)
+    torch.cuda.synchronize()
+    assert lisa.last_path() == "cache_fill"
+    k_tok = kc.transpose(2, 3) if dim_major else kc              # [B,Hkv,Lmax,r]
+    assert torch.equal(k_tok[:, :, :L], inp["k_lr"]) and torch.all(k_tok[:, :, L:] == SENTINEL)
+    assert torch.equal(vc[:, :, :L], inp["v"]) and torch.all(vc[:, :, L:] == SENTINEL)
+    prev = std_prev(inp)
+    out, scores = lisa.lisa_attn_prefill(inp["q_lr"], inp["k_lr"], inp["v"], prev, inp["w1"], inp["w2"])
+    o_dec, row = lisa.lisa_attn_decode(inp["q_lr"][:, :, -1].contiguous(), kc, vc, L,
+                                       prev[:, :, -1].contiguous(), inp["w1"], inp["w2"],
+                                       dim_major=dim_major)
+    torch.cuda.synchronize()
+    tol = hp.TOL[dt]
+    for b in range(cfg.B):
+        a_ref, o_ref = hp.oracle_lisa_rows(inp, b, [L - 1], hp.gather_score_rows(prev, b, [L - 1]))
+        assert hp.row_rel_err(hp.f64(o_dec[b])[None], o_ref) <= tol
+        assert hp.row_rel_err(hp.f64(row[b])[None], a_ref) <= tol
+
+
 def test_decode_equals_last_prefill_row_on_gpu():
     cfg = synth.LayerShape("pd", "bf16", 2, 8, 8, 97, 128, 64, 12, 32)
     inp = synth.make_prefill_inputs(cfg, 9, DEV)
