@@ -226,21 +226,62 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
 }
 
 // out[b][h][:] = sum_c e^{m_c - M} O_c / sum_c e^{m_c - M} s_c,  M = max_c m_c.
-// grid (H, B), block DK.
+// grid (H, B), block 256: the chunks are dealt to 256 / (DK / 4) groups of DK / 4 lanes (four
+// features per lane, independent 16-byte loads), the groups' sums are merged through LDS.
 template <typename O, int DK>
-__global__ void k_decode_combine(const float* __restrict__ part_o, const float* __restrict__ part_ml,
-                                 O* __restrict__ out, int H, int n_chunk) {
-  const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
-  float M = -INFINITY;
-  for (int c = 0; c < n_chunk; ++c) M = fmaxf(M, part_ml[(((size_t)b * n_chunk + c) * H + h) * 2]);
-  float num = 0.f, den = 0.f;
-  for (int c = 0; c < n_chunk; ++c) {
-    const size_t at = ((size_t)b * n_chunk + c) * H + h;
-    const float w = __expf(part_ml[at * 2] - M);
-    den += w * part_ml[at * 2 + 1];
-    num += w * part_o[at * DK + d];
+__global__ __launch_bounds__(256) void k_decode_combine(const float* __restrict__ part_o,
+                                                        const float* __restrict__ part_ml,
+                                                        O* __restrict__ out, int H, int n_chunk) {
+  constexpr int LPG = DK / 4, NGRP = 256 / LPG;
+  __shared__ float s_max;
+  __shared__ float4 s_num[NGRP][LPG];
+  __shared__ float s_den[NGRP];
+  const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const size_t row0 = (size_t)b * n_chunk * H + h;            // chunk c: row0 + c * H
+  if (tid < 64) {
+    float m = -INFINITY;
+    for (int c = tid; c < n_chunk; c += 64) m = fmaxf(m, part_ml[(row0 + (size_t)c * H) * 2]);
+    m = wave_max(m);
+    if (tid == 0) s_max = m;
   }
-  elem<O>::store(out + ((size_t)b * H + h) * DK + d, num / den);
+  __syncthreads();
+  const float M = s_max;
+  const int grp = tid / LPG, l = tid % LPG;
+  float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+  float den = 0.f;
+  for (int c = grp; c < n_chunk; c += NGRP) {
+    const size_t at = row0 + (size_t)c * H;
+    const float2 ml = *(const float2*)(part_ml + at * 2);
+    const float4 po = *(const float4*)(part_o + at * DK + 4 * l);
+    const float w = __expf(ml.x - M);
+    den += w * ml.y;
+    num.x += w * po.x;
+    num.y += w * po.y;
+    num.z += w * po.z;
+    num.w += w * po.w;
+  }
+  s_num[grp][l] = num;
+  if (l == 0) s_den[grp] = den;
+  __syncthreads();
+  if (tid < LPG) {
+    float4 n = s_num[0][tid];
+    float dsum = s_den[0];
+#pragma unroll
+    for (int gi = 1; gi < NGRP; ++gi) {
+      const float4 x = s_num[gi][tid];
+      n.x += x.x;
+      n.y += x.y;
+      n.z += x.z;
+      n.w += x.w;
+      dsum += s_den[gi];
+    }
+    const float inv = 1.f / dsum;
+    O* o = out + ((size_t)b * H + h) * DK + 4 * tid;
+    elem<O>::store(o, n.x * inv);
+    elem<O>::store(o + 1, n.y * inv);
+    elem<O>::store(o + 2, n.z * inv);
+    elem<O>::store(o + 3, n.w * inv);
+  }
 }
 
 }  // namespace lisa

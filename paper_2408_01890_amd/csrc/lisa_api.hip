@@ -290,14 +290,14 @@ int run_decode_fast(const lisa_desc* d, bool lisa_layer, DecodeArgs a, void* out
     StageScope prof("k_decode_combine", st);
     if (d->d_k == 128) {
       if (d->out_f32)
-        k_decode_combine<float, 128><<<grid, 128, 0, st>>>(a.part_o, a.part_ml, (float*)out, d->H, a.n_chunk);
+        k_decode_combine<float, 128><<<grid, 256, 0, st>>>(a.part_o, a.part_ml, (float*)out, d->H, a.n_chunk);
       else
-        k_decode_combine<bf16_t, 128><<<grid, 128, 0, st>>>(a.part_o, a.part_ml, (bf16_t*)out, d->H, a.n_chunk);
+        k_decode_combine<bf16_t, 128><<<grid, 256, 0, st>>>(a.part_o, a.part_ml, (bf16_t*)out, d->H, a.n_chunk);
     } else {
       if (d->out_f32)
-        k_decode_combine<float, 64><<<grid, 64, 0, st>>>(a.part_o, a.part_ml, (float*)out, d->H, a.n_chunk);
+        k_decode_combine<float, 64><<<grid, 256, 0, st>>>(a.part_o, a.part_ml, (float*)out, d->H, a.n_chunk);
       else
-        k_decode_combine<bf16_t, 64><<<grid, 64, 0, st>>>(a.part_o, a.part_ml, (bf16_t*)out, d->H, a.n_chunk);
+        k_decode_combine<bf16_t, 64><<<grid, 256, 0, st>>>(a.part_o, a.part_ml, (bf16_t*)out, d->H, a.n_chunk);
     }
     rc = check_launch();
   }
