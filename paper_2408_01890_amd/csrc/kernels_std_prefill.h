@@ -61,7 +61,7 @@ constexpr int std_prefill_head_lds(bool with_v) {
 // grid (ceil(n_groups / 2), H, B) with n_groups = ceil(Lq / 128), block 256.
 // Requires d_k = 128, Lk % 8 == 0.
 template <bool WITH_V>
-__global__ __launch_bounds__(256) void k_std_prefill(StdPrefillArgs a) {
+__global__ __launch_bounds__(256, 2) void k_std_prefill(StdPrefillArgs a) {
   constexpr int DK = 128;
   __shared__ __align__(16) unsigned char lds[std_prefill_head_lds(WITH_V)];
   unsigned char* ks_ = lds;
