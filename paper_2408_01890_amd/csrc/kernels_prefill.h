@@ -239,6 +239,14 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
   const int h_first = hg0 + wv * HPW;
 
   Ffn::stage(a.w1, a.w2, H, a.F, w_s, tid, THREADS, hg0, GH);
+  // One head per wave leaves registers for the FFN weights: fetched once per workgroup instead of
+  // read from LDS by every block pair.
+  constexpr bool WREG = HPW == 1 && NW <= 8 && (Ffn::FB * Ffn::KS + HBO * FS) <= 8;
+  Ffn ffn;
+  if (WREG) {
+    __syncthreads();
+    ffn.fetch(w_s);
+  }
 
   // wave-uniform bases of this wave's heads (scalar registers)
   const bf16_t* k_base[HPW];     // K_LR rows of the head's key/value head
@@ -439,7 +447,8 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
           }
         }
         f32x4 y[2][HBO];
-        Ffn::template apply_lds<2>(w_s, x, y);
+        if (WREG) ffn.template apply<2>(x, y);
+        else Ffn::template apply_lds<2>(w_s, x, y);
 #pragma unroll
         for (int n = 0; n < 2; ++n)
 #pragma unroll

@@ -314,20 +314,29 @@ bool prefill_fused_ok(const lisa_desc* d) {
   return d->H == 8 || d->H == 16 || d->H == 24 || d->H == 32 || d->H == 40;
 }
 
-// Head groups (grid.z) of the instantiation that run_prefill_fused picks for H heads.
-int prefill_groups(int H) { return H == 32 ? 2 : H == 40 ? 5 : 1; }
+constexpr int kComputeUnits = 256;   // MI355X
+
+// Head groups (grid.z) of the instantiation that run_prefill_fused picks.  H = 32 runs as two
+// groups of 16 heads (two heads per wave) when that alone gives two units of work per compute
+// unit; smaller problems take four groups of 8 (one head per wave): the first FFN layer is then
+// computed four times, but no key split, partial results or combine pass are needed.
+int prefill_groups(const lisa_desc* d) {
+  if (d->H == 40) return 5;
+  if (d->H != 32) return 1;
+  const long long row_blocks = (long long)((d->Lq + PF_ROWS - 1) / PF_ROWS) * d->B;
+  if (const char* e = getenv("LISA_PREFILL_GROUPS")) return atoi(e) == 4 ? 4 : 2;
+  return row_blocks * 2 >= 2 * kComputeUnits ? 2 : 4;
+}
 
 struct PrefillWs {
   size_t qp, kp, vt, part_o, part_ml, total;   // byte offsets in the workspace
   int Lqp, Lkp, split;
 };
 
-constexpr int kComputeUnits = 256;   // MI355X
-
 // Key splits per row block: small problems have too few (row block, head group) units to
 // fill the chip and their longest unit (the last row block) sets the run time.
 int prefill_split(const lisa_desc* d, int Lqp) {
-  const int groups = prefill_groups(d->H);
+  const int groups = prefill_groups(d);
   const long long units = (long long)(Lqp / PF_ROWS) * d->B * groups;
   const int tiles_max = (d->Lk + PF_TK - 1) / PF_TK;
   int s = 1;
@@ -339,7 +348,7 @@ int prefill_split(const lisa_desc* d, int Lqp) {
 // Two units (a long and a short one) per workgroup once that still leaves two workgroups per
 // compute unit: equal work per workgroup, FFN weights staged once for both.
 int prefill_pair(const lisa_desc* d, int Lqp, int split) {
-  const int groups = prefill_groups(d->H);
+  const int groups = prefill_groups(d);
   const long long units = (long long)(Lqp / PF_ROWS) * split * d->B * groups;
   if (const char* e = getenv("LISA_PREFILL_PAIR")) return atoi(e) != 0;
   return units >= 2 * kComputeUnits;
@@ -432,7 +441,9 @@ int run_prefill_fused(const lisa_desc* d, const void* q_lr, const void* k_lr, co
     case 8: rc = launch_prefill_fused_fs<1, 1, 8>(d, a, st); break;    // one group of 8 heads
     case 16: rc = launch_prefill_fused_fs<1, 2, 8>(d, a, st); break;   // one group of 16
     case 24: rc = launch_prefill_fused_fs<1, 3, 8>(d, a, st); break;   // one group of 24
-    case 32: rc = launch_prefill_fused_fs<2, 2, 8>(d, a, st); break;   // two groups of 16
+    case 32:                                                            // two groups of 16 or four of 8
+      rc = prefill_groups(d) == 4 ? launch_prefill_fused_fs<4, 1, 8>(d, a, st) : launch_prefill_fused_fs<2, 2, 8>(d, a, st);
+      break;
     default: rc = launch_prefill_fused_fs<5, 1, 8>(d, a, st); break;   // H = 40: five groups of 8
   }
   if (rc == LISA_OK && a.split > 1) {

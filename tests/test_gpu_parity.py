@@ -284,6 +284,21 @@ def test_lisa_prefill_chunked_rows_match_full_prefill():
     assert torch.equal(scores_t[..., vis], scores[:, :, -t:][..., vis])
 
 
+@pytest.mark.parametrize("groups", ["2", "4"])
+def test_lisa_prefill_h32_both_head_groupings(groups, monkeypatch):
+    """H = 32 runs as two groups of 16 heads on large problems and as four groups of 8 on small
+    ones; both instantiations on the same ragged problem (key splits and the combine included)."""
+    monkeypatch.setenv("LISA_PREFILL_GROUPS", groups)
+    cfg = synth.LayerShape("h32_groups", "bf16", 1, 32, 8, 328, 4096, 128, 22, 64)
+    inp = synth.make_prefill_inputs(cfg, 51, DEV, ffn="identity_noise")
+    prev = std_prev(inp)
+    out, scores = lisa.lisa_attn_prefill(inp["q_lr"], inp["k_lr"], inp["v"], prev, inp["w1"],
+                                         inp["w2"])
+    torch.cuda.synchronize()
+    assert lisa.last_path() == "mfma_fused"
+    check_prefill(cfg, inp, prev, out, scores, {0: np.arange(cfg.L)}, tag=f"/groups{groups}")
+
+
 def test_lisa_prefill_fused_paired_units_odd_count():
     """Enough (row block, head group) units that a workgroup takes two of them (a long one
     walked upwards, a short one walked downwards), with an odd number of row blocks so that the
