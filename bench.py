@@ -56,7 +56,7 @@ def stage_algorithmic(stage, cfg, write_scores, out_bytes=4):
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this workload,
 # scaled by the same counters of a 1 GiB copy (profiles/lisa_prefill_fused_c2_traffic.md).
-MEASURED_TRAFFIC = {"k_lisa_prefill_fused": 389.6e6 + 224.8e6}
+MEASURED_TRAFFIC = {"k_lisa_prefill_fused": 389.3e6 + 168.9e6}
 
 
 def time_steps(fn, steps, warmup):
