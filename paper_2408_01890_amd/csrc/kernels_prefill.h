@@ -242,6 +242,7 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
   // One head per wave leaves registers for the FFN weights: fetched once per workgroup instead of
   // read from LDS by every block pair.
   constexpr bool WREG = HPW == 1 && NW <= 8 && (Ffn::FB * Ffn::KS + HBO * FS) <= 8;
+  constexpr int NBLK = 2;   // blocks of 16 positions whose MFMA chains are interleaved in stage A
   Ffn ffn;
   if (WREG) {
     __syncthreads();
@@ -404,24 +405,24 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
       // two blocks of 16 positions at a time, their MFMA chains interleaved; the weights are read
       // from LDS as the products need them (stage B keeps the register file)
 #pragma unroll
-      for (int q = 0; q < NBW; q += 2) {
+      for (int q = 0; q < NBW; q += NBLK) {
         if (pending >= 0) {
           // heads of this wave dealt over the block pairs
 #pragma unroll
-          for (int hh = q / 2; hh < HPW; hh += NBW / 2) flush_scores(pending, hh);
+          for (int hh = q / NBLK; hh < HPW; hh += NBW / NBLK) flush_scores(pending, hh);
         }
-        if (q + 2 >= NBW) load_x(tile_at(min(it + 1, n_mine - 1)), xr);
+        if (q + NBLK >= NBW) load_x(tile_at(min(it + 1, n_mine - 1)), xr);
         if (SPREAD) {
-          constexpr int PER = (DK / 16 + NBW / 2 - 1) / (NBW / 2);    // V loads per block pair
+          constexpr int PER = (DK / 16 + NBW / NBLK - 1) / (NBW / NBLK);    // V loads per block group
           const bf16_t* vt = v_base[HPW - 1] + (size_t)tile * (PF_TK / 8 * DK * 8);
 #pragma unroll
-          for (int nb = q / 2 * PER; nb < min(q / 2 * PER + PER, DK / 16); ++nb)
+          for (int nb = q / NBLK * PER; nb < min(q / NBLK * PER + PER, DK / 16); ++nb)
             vop[NSET - 1][nb] = ld_uv<bf16x8>(vt, v_off, nb * 256);
         }
-        f16x8 x[2][KS];
-        int yoff[2];
+        f16x8 x[NBLK][KS];
+        int yoff[NBLK];
 #pragma unroll
-        for (int n = 0; n < 2; ++n) {
+        for (int n = 0; n < NBLK; ++n) {
           // block = (row i, key half kh); a wave with an odd share repeats its last block
           const int nb = min(wv + (q + n) * NW, 2 * PF_ROWS - 1);
           const int i = nb >> 1, kh = nb & 1;
@@ -446,11 +447,11 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
             }
           }
         }
-        f32x4 y[2][HBO];
-        if (WREG) ffn.template apply<2>(x, y);
-        else Ffn::template apply_lds<2>(w_s, x, y);
+        f32x4 y[NBLK][HBO];
+        if (WREG) ffn.template apply<NBLK>(x, y);
+        else Ffn::template apply_lds<NBLK>(w_s, x, y);
 #pragma unroll
-        for (int n = 0; n < 2; ++n)
+        for (int n = 0; n < NBLK; ++n)
 #pragma unroll
           for (int hb = 0; hb < HBO; ++hb)
 #pragma unroll
