@@ -252,6 +252,23 @@ def test_lisa_prefill_fused_kernel_shapes(case, causal):
         assert eo <= tol and ea <= tol
 
 
+@pytest.mark.parametrize("dtype,H,L,dk,r,F", [("f32", 2, 1, 16, 3, 4), ("bf16", 8, 1, 128, 22, 32),
+                                              ("bf16", 8, 2, 128, 22, 32), ("bf16", 8, 8, 128, 22, 32),
+                                              ("bf16", 32, 16, 128, 22, 64), ("f32", 1, 5, 8, 1, 2)])
+def test_lisa_prefill_degenerate_sizes(dtype, H, L, dk, r, F):
+    """One token, one tile, one head: the smallest problems of both the generic and the fused path
+    (row 0 sees a single key, so P = 1 and O = V[0])."""
+    cfg = synth.LayerShape(f"tiny_{dtype}_h{H}_l{L}", dtype, 3, H, H, L, H * dk, dk, r, F)
+    inp = synth.make_prefill_inputs(cfg, 61, DEV, ffn="fan_in")
+    prev = std_prev(inp)
+    out, scores = lisa.lisa_attn_prefill(inp["q_lr"], inp["k_lr"], inp["v"], prev, inp["w1"],
+                                         inp["w2"])
+    torch.cuda.synchronize()
+    check_prefill(cfg, inp, prev, out, scores, {b: np.arange(L) for b in range(cfg.B)})
+    v0 = inp["v"][:, :, 0].float()                              # [B,Hkv,dk]: O of row 0 is V[0]
+    assert torch.allclose(out[:, 0].float(), v0, rtol=1e-6, atol=1e-6)       # float32 rounding of p / l
+
+
 def test_bf16_output_option_differs_only_by_the_final_rounding():
     cfg = synth.LayerShape("bf16out", "bf16", 1, 32, 32, 200, 256, 128, 22, 64)
     inp = synth.make_prefill_inputs(cfg, 21, DEV, ffn="identity_noise")
