@@ -311,6 +311,7 @@ bool prefill_fused_ok(const lisa_desc* d) {
   if (d->dtype != LISA_BF16 || d->d_k != 128) return false;
   if (d->mix != LISA_MIX_ADD || d->act != LISA_ACT_RELU) return false;
   if (d->Lk % 8 != 0 || d->F > 128 || d->r > 32) return false;   // 16-byte aligned score rows
+  if ((long long)d->Lq * d->Lk >= (1LL << 31)) return false;      // 32-bit byte offsets inside one head's scores
   return d->H == 8 || d->H == 16 || d->H == 24 || d->H == 32 || d->H == 40;
 }
 
