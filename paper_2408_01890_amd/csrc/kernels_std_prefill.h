@@ -58,7 +58,10 @@ constexpr int std_prefill_head_lds(bool with_v) {
   return 2 * SP_KTILE + SP_WAVES * SP_STILE + (with_v ? 2 * SP_VTILE : 0);
 }
 
-// grid (ceil(n_groups / 2), H, B) with n_groups = ceil(Lq / 128), block 256.
+// grid (H, ceil(n_groups / 2), B) with n_groups = ceil(Lq / 128), block 256.  The head is the
+// fastest grid index: consecutive workgroups go to different XCDs, so an XCD works on every
+// eighth head and its L2 fetches the K / V of those heads only (they are what every row group
+// of a head re-reads).
 // Requires d_k = 128, Lk % 8 == 0.
 template <bool WITH_V>
 __global__ __launch_bounds__(256, 2) void k_std_prefill(StdPrefillArgs a) {
@@ -70,7 +73,7 @@ __global__ __launch_bounds__(256, 2) void k_std_prefill(StdPrefillArgs a) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r = lane & 31, half = lane >> 5;
-  const int b = blockIdx.z, h = blockIdx.y;
+  const int b = blockIdx.z, h = blockIdx.x;
   const int Lq = a.Lq, Lk = a.Lk, H = a.H;
   const int shift = Lk - Lq;
   const int kv = h / (H / a.Hkv);
@@ -88,7 +91,7 @@ __global__ __launch_bounds__(256, 2) void k_std_prefill(StdPrefillArgs a) {
   const int v_rd = (half * DK + r) * 16;                 // + (2 s DK + 32 db) 16
 
   for (int rep = 0; rep < 2; ++rep) {
-    const int grp = rep ? (int)blockIdx.x : n_groups - 1 - (int)blockIdx.x;
+    const int grp = rep ? (int)blockIdx.y : n_groups - 1 - (int)blockIdx.y;
     if (rep && grp >= n_groups - 1 - grp) break;           // the middle group of an odd count is alone
     const int i0 = grp * SP_GROUP + wv * SP_ROWS;          // first row of this wave
     const bool have_rows = i0 < Lq;

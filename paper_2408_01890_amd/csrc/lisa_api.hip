@@ -494,7 +494,7 @@ int run_std_prefill_fast(const lisa_desc* d, const void* q, const void* k, const
     if (rc) return rc;
   }
   const int n_groups = (d->Lq + SP_GROUP - 1) / SP_GROUP;
-  dim3 grid((n_groups + 1) / 2, d->H, d->B);
+  dim3 grid(d->H, (n_groups + 1) / 2, d->B);
   StageScope prof("k_std_prefill", st);
   if (out)
     k_std_prefill<true><<<grid, 256, 0, st>>>(a);
