@@ -22,7 +22,8 @@
  *   - Tensors are dense, row-major, innermost index last, base pointers 16-byte aligned.
  *   - Element types: `dtype` is the type of Q, K, V, Q_LR, K_LR, W1, W2 and of the
  *     attention output O (float32 instead when out_f32 = 1: the accumulators are float32
- *     and rounding O to bfloat16 alone costs up to 2^-9 of each element).  Score tensors (A_{n-1}, A_n) use the *score type*:
+ *     and rounding O to bfloat16 alone costs up to 2^-9 of each element).  Score tensors
+ *     (A_{n-1}, A_n) use the *score type*:
  *     float32 when dtype = LISA_F32, IEEE binary16 (half) when dtype = LISA_BF16 -- the
  *     2-byte score element assumed by the memory analysis of Sec. 5.2, chosen as half
  *     because the softmax that consumes A needs absolute, not relative, precision.
@@ -175,7 +176,8 @@ const char* lisa_strerror(int status);
 /* hipGetErrorString of the last failed launch seen by this thread ("" if none). */
 const char* lisa_last_hip_error(void);
 /* Name of the kernel family the last successful call on this thread dispatched to
- * ("generic", "mfma", ...); for tests and benchmark reports. */
+ * ("generic", "mfma_fused", "mfma_std", "decode_split", "cache_fill"); for tests and
+ * benchmark reports. */
 const char* lisa_last_path(void);
 
 /*
