@@ -317,16 +317,18 @@ bool prefill_fused_ok(const lisa_desc* d) {
 
 constexpr int kComputeUnits = 256;   // MI355X
 
-// Head groups (grid.z) of the instantiation that run_prefill_fused picks.  H = 32 runs as two
-// groups of 16 heads (two heads per wave) when that alone gives two units of work per compute
-// unit; smaller problems take four groups of 8 (one head per wave): the first FFN layer is then
-// computed four times, but no key split, partial results or combine pass are needed.
+// Head groups (grid.z) of the instantiation that run_prefill_fused picks.  H = 32 (16) runs as
+// two (one) groups of 16 heads, two heads per wave, when that alone gives two units of work per
+// compute unit; smaller problems take groups of 8 (one head per wave): the first FFN layer is
+// then computed once more per extra group, but fewer or no key splits, partial results and
+// combine passes are needed.
 int prefill_groups(const lisa_desc* d) {
   if (d->H == 40) return 5;
-  if (d->H != 32) return 1;
+  if (d->H != 32 && d->H != 16) return 1;
+  const int few = d->H / 16, many = d->H / 8;              // groups of 16 heads or of 8
   const long long row_blocks = (long long)((d->Lq + PF_ROWS - 1) / PF_ROWS) * d->B;
-  if (const char* e = getenv("LISA_PREFILL_GROUPS")) return atoi(e) == 4 ? 4 : 2;
-  return row_blocks * 2 >= 2 * kComputeUnits ? 2 : 4;
+  if (const char* e = getenv("LISA_PREFILL_GROUPS")) return atoi(e) == many ? many : few;
+  return row_blocks * few >= 2 * kComputeUnits ? few : many;
 }
 
 struct PrefillWs {
@@ -440,7 +442,9 @@ int run_prefill_fused(const lisa_desc* d, const void* q_lr, const void* k_lr, co
   int rc;
   switch (d->H) {
     case 8: rc = launch_prefill_fused_fs<1, 1, 8>(d, a, st); break;    // one group of 8 heads
-    case 16: rc = launch_prefill_fused_fs<1, 2, 8>(d, a, st); break;   // one group of 16
+    case 16:                                                            // one group of 16 or two of 8
+      rc = prefill_groups(d) == 2 ? launch_prefill_fused_fs<2, 1, 8>(d, a, st) : launch_prefill_fused_fs<1, 2, 8>(d, a, st);
+      break;
     case 24: rc = launch_prefill_fused_fs<1, 3, 8>(d, a, st); break;   // one group of 24
     case 32:                                                            // two groups of 16 or four of 8
       rc = prefill_groups(d) == 4 ? launch_prefill_fused_fs<4, 1, 8>(d, a, st) : launch_prefill_fused_fs<2, 2, 8>(d, a, st);

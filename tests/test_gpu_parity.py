@@ -301,6 +301,21 @@ def test_lisa_prefill_chunked_rows_match_full_prefill():
     assert torch.equal(scores_t[..., vis], scores[:, :, -t:][..., vis])
 
 
+@pytest.mark.parametrize("groups", ["1", "2"])
+def test_lisa_prefill_h16_both_head_groupings(groups, monkeypatch):
+    """H = 16: one group of 16 heads or two groups of 8, on the same ragged problem."""
+    monkeypatch.setenv("LISA_PREFILL_GROUPS", groups)
+    cfg = synth.LayerShape("h16_groups", "bf16", 2, 16, 4, 200, 2048, 128, 22, 32)
+    inp = synth.make_prefill_inputs(cfg, 52, DEV, ffn="identity_noise")
+    prev = std_prev(inp)
+    out, scores = lisa.lisa_attn_prefill(inp["q_lr"], inp["k_lr"], inp["v"], prev, inp["w1"],
+                                         inp["w2"])
+    torch.cuda.synchronize()
+    assert lisa.last_path() == "mfma_fused"
+    check_prefill(cfg, inp, prev, out, scores, {b: np.arange(cfg.L) for b in range(cfg.B)},
+                  tag=f"/groups{groups}")
+
+
 @pytest.mark.parametrize("groups", ["2", "4"])
 def test_lisa_prefill_h32_both_head_groupings(groups, monkeypatch):
     """H = 32 runs as two groups of 16 heads on large problems and as four groups of 8 on small
