@@ -109,3 +109,27 @@ def lisa_rows(q_lr, k_lr, v, w1, w2, rows, prev_rows, mix=MIX_ADD, delta_scale=N
     if rc:
         raise ValueError("lisa_oracle_lisa_rows: bad shape")
     return (scores, out, probs) if want_probs else (scores, out)
+
+
+def project_rows(x, w, rows, H, Hkv, r, dk, theta=0.0, pos0=0):
+    """Projection front end for the requested token rows of one sequence.
+
+    x [L,D], w [H*r + Hkv*r + Hkv*dk, D] -> q [n,H,r], k [n,Hkv,r], v [n,Hkv,dk]
+    (rotary embedding on q, k when theta > 0).
+    """
+    x, xp = _d(x)
+    w, wp = _d(w)
+    L, D = x.shape
+    assert w.shape == (H * r + Hkv * r + Hkv * dk, D)
+    rows, rp = _rows(rows)
+    n = len(rows)
+    q = np.empty((n, H, r), dtype=np.float64)
+    k = np.empty((n, Hkv, r), dtype=np.float64)
+    v = np.empty((n, Hkv, dk), dtype=np.float64)
+    dp = C.POINTER(C.c_double)
+    rc = lib().lisa_oracle_project_rows(L, D, H, Hkv, r, dk, C.c_double(theta), int(pos0), xp, wp,
+                                        n, rp, q.ctypes.data_as(dp), k.ctypes.data_as(dp),
+                                        v.ctypes.data_as(dp))
+    if rc:
+        raise ValueError("lisa_oracle_project_rows: bad shape")
+    return q, k, v

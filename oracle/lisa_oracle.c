@@ -29,7 +29,9 @@
  * library softmax/matmul; A_delta equals a brute-force triple loop; r = d_k reduces
  * Eq. 3 to Eq. 2; the h = 3 head permutation of Sec. 5.1; uniform and one-hot score
  * closed forms; GQA equals MHA with repeated K/V; prefill row L-1 equals decode; a
- * hand-evaluated 2-head example.
+ * hand-evaluated 2-head example.  Projection front end: without rotation it equals a library
+ * matrix product; unit-vector inputs give (cos, sin) closed forms that fix the pairing, the
+ * sign and the frequency exponent; rotated dot products depend on the position difference only.
  */
 #include <math.h>
 #include <stdlib.h>
@@ -174,6 +176,54 @@ int lisa_oracle_lisa_rows(int H, int Hkv, int Lq, int Lk, int dk, int r, int F, 
   if (rc) return rc;
   return lisa_oracle_softmax_v_rows(H, Hkv, Lq, Lk, dk, v, n_rows, rows, scores_rows,
                                     probs_rows, out_rows);
+}
+
+/* Front end of a LiSA layer for the requested token rows of one sequence:
+ *   Q_LR = X W^Q_LR,  K_LR = X W^K_LR   (the two factors of Eq. 3),   V = X W^V   (Eq. 1),
+ * each split in heads, followed, when theta > 0, by the rotary position embedding of the
+ * LLaMA models of Sec. 6.1 on every Q_LR / K_LR head (r even): with half = r/2 and
+ * angle(pos, t) = pos * theta^(-2t/r), the pair (y[t], y[t+half]) becomes
+ *   (y[t] cos - y[t+half] sin,  y[t] sin + y[t+half] cos),      pos = pos0 + row index.
+ *   x [L][D] hidden states;  w [H*r + Hkv*r + Hkv*dk][D]: one row per output feature, the
+ *   rows of W^Q_LR^T first, then W^K_LR^T, then W^V^T.
+ *   q_rows [n_rows][H][r],  k_rows [n_rows][Hkv][r],  v_rows [n_rows][Hkv][dk].  */
+int lisa_oracle_project_rows(int L, int D, int H, int Hkv, int r, int dk, double theta,
+                             int pos0, const double* x, const double* w, int n_rows,
+                             const int* rows, double* q_rows, double* k_rows,
+                             double* v_rows) {
+  if (L <= 0 || D <= 0 || H <= 0 || Hkv <= 0 || r <= 0 || dk <= 0) return -1;
+  if (theta > 0.0 && r % 2 != 0) return -1;
+  const int nq = H * r, nk = Hkv * r, nv = Hkv * dk;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int n = 0; n < n_rows; ++n) {
+    const int i = rows[n];
+    const double* xi = x + (size_t)i * D;
+    double* y = (double*)malloc(sizeof(double) * (size_t)(nq + nk + nv));
+    for (int f = 0; f < nq + nk + nv; ++f) {
+      double acc = 0.0;
+      for (int c = 0; c < D; ++c) acc += xi[c] * w[(size_t)f * D + c];
+      y[f] = acc;
+    }
+    if (theta > 0.0) {
+      const int half = r / 2;
+      const double pos = (double)(pos0 + i);
+      for (int head = 0; head < H + Hkv; ++head) {
+        double* yh = y + (size_t)head * r;
+        for (int t = 0; t < half; ++t) {
+          const double ang = pos * pow(theta, -2.0 * t / r);
+          const double c = cos(ang), s = sin(ang);
+          const double a = yh[t], b = yh[t + half];
+          yh[t] = a * c - b * s;
+          yh[t + half] = a * s + b * c;
+        }
+      }
+    }
+    memcpy(q_rows + (size_t)n * nq, y, sizeof(double) * (size_t)nq);
+    memcpy(k_rows + (size_t)n * nk, y + nq, sizeof(double) * (size_t)nk);
+    memcpy(v_rows + (size_t)n * nv, y + nq + nk, sizeof(double) * (size_t)nv);
+    free(y);
+  }
+  return 0;
 }
 
 int lisa_oracle_num_threads(void) {

@@ -438,3 +438,88 @@ def test_printed_shapes_fix_per_head_rank_and_gqa_key_heads():
     total = s["llama3_8b_lisa_layers"] * per_layer
     assert round(total / 1e6) == s["llama3_8b_trained_params_millions"]
     assert round(dk / r) == 6                          # "compresses Q, K by 6x"
+
+
+# --------------------------------------------------------------------------------------
+# 9. Projection front end: Q_LR = X W^Q_LR, K_LR = X W^K_LR (factors of Eq. 3), V = X W^V
+#    (Eq. 1), rotary position embedding of the LLaMA models of Sec. 6.1 on Q_LR / K_LR.
+# --------------------------------------------------------------------------------------
+def test_projection_without_rotation_is_a_library_matmul():
+    g = rng(90)
+    L, D, H, Hkv, r, dk = 7, 24, 4, 2, 6, 8
+    x = g.standard_normal((L, D))
+    w = g.standard_normal((H * r + Hkv * r + Hkv * dk, D))
+    q, k, v = cref.project_rows(x, w, all_rows(L), H, Hkv, r, dk)
+    y = x @ w.T
+    np.testing.assert_allclose(q.reshape(L, -1), y[:, :H * r], rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(k.reshape(L, -1), y[:, H * r:(H + Hkv) * r], rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(v.reshape(L, -1), y[:, (H + Hkv) * r:], rtol=1e-12, atol=1e-12)
+    # feature f of head h is row h*r + f of the weight: a one-hot weight picks it out
+    w1 = np.zeros_like(w)
+    w1[2 * r + 3, 5] = 1.0
+    q1, k1, v1 = cref.project_rows(x, w1, all_rows(L), H, Hkv, r, dk)
+    assert np.count_nonzero(k1) == 0 and np.count_nonzero(v1) == 0
+    np.testing.assert_array_equal(q1[:, 2, 3], x[:, 5])
+    assert np.count_nonzero(q1) == np.count_nonzero(x[:, 5])
+
+
+def test_rotary_embedding_unit_vectors_give_cos_and_sin():
+    """r = 4, theta = 10^4: frequencies 1 and 10^-2; identity weights make Q_LR = X.
+    e_0 -> (cos p, 0, sin p, 0); e_2 -> (-sin p, 0, cos p, 0); e_1 -> (0, cos p/100, 0, sin p/100):
+    fixes the pairing (t, t + r/2), the sense of rotation and the exponent -2t/r."""
+    r, dk, L = 4, 2, 6
+    D = r
+    w = np.zeros((r + r + dk, D))
+    w[:r] = np.eye(r)
+    w[r:2 * r] = np.eye(r)
+    for e, expect in (
+        (0, lambda p: [math.cos(p), 0.0, math.sin(p), 0.0]),
+        (2, lambda p: [-math.sin(p), 0.0, math.cos(p), 0.0]),
+        (1, lambda p: [0.0, math.cos(p / 100.0), 0.0, math.sin(p / 100.0)]),
+        (3, lambda p: [0.0, -math.sin(p / 100.0), 0.0, math.cos(p / 100.0)]),
+    ):
+        x = np.zeros((L, D))
+        x[:, e] = 1.0
+        q, k, v = cref.project_rows(x, w, all_rows(L), 1, 1, r, dk, theta=1.0e4, pos0=3)
+        want = np.array([expect(3 + i) for i in range(L)])
+        np.testing.assert_allclose(q[:, 0, :], want, rtol=0, atol=1e-14)
+        np.testing.assert_allclose(k[:, 0, :], want, rtol=0, atol=1e-14)
+        assert np.count_nonzero(v) == 0                      # V is never rotated
+
+
+def test_rotary_embedding_is_a_rotation_that_depends_on_relative_position():
+    g = rng(91)
+    L, D, H, Hkv, r, dk = 12, 10, 4, 2, 6, 4
+    x = np.tile(g.standard_normal((1, D)), (L, 1))           # the same token at every position
+    w = g.standard_normal((H * r + Hkv * r + Hkv * dk, D))
+    q0, k0, v0 = cref.project_rows(x, w, all_rows(L), H, Hkv, r, dk)
+    q, k, v = cref.project_rows(x, w, all_rows(L), H, Hkv, r, dk, theta=500000.0)
+    np.testing.assert_array_equal(v, v0)
+    np.testing.assert_allclose(q[0], q0[0], rtol=0, atol=1e-15)          # position 0: identity
+    np.testing.assert_allclose(np.linalg.norm(q, axis=-1), np.linalg.norm(q0, axis=-1), rtol=1e-13)
+    np.testing.assert_allclose(np.linalg.norm(k, axis=-1), np.linalg.norm(k0, axis=-1), rtol=1e-13)
+    # <q_i, k_j> is a function of i - j
+    s = np.einsum("ihr,jhr->hij", q[:, :Hkv], k)
+    for d in range(-3, 4):
+        diag = np.stack([np.diagonal(s[h], offset=d) for h in range(Hkv)])
+        np.testing.assert_allclose(diag, np.repeat(diag[:, :1], diag.shape[1], axis=1),
+                                   rtol=1e-11, atol=1e-12)
+    assert np.abs(s[0, 0, 0] - s[0, 0, 5]) > 1e-3            # and does depend on it
+    # a position offset shifts the rows
+    q3, k3, _ = cref.project_rows(x, w, all_rows(L - 3), H, Hkv, r, dk, theta=500000.0, pos0=3)
+    np.testing.assert_allclose(q3, q[3:], rtol=0, atol=1e-13)
+    np.testing.assert_allclose(k3, k[3:], rtol=0, atol=1e-13)
+
+
+def test_projection_rows_are_independent_of_the_request_set():
+    g = rng(92)
+    L, D, H, Hkv, r, dk = 9, 16, 2, 1, 4, 8
+    x = g.standard_normal((L, D))
+    w = g.standard_normal((H * r + Hkv * r + Hkv * dk, D))
+    qa, ka, va = cref.project_rows(x, w, all_rows(L), H, Hkv, r, dk, theta=1.0e4, pos0=2)
+    qs, ks, vs = cref.project_rows(x, w, [7, 1], H, Hkv, r, dk, theta=1.0e4, pos0=2)
+    np.testing.assert_array_equal(qs, qa[[7, 1]])
+    np.testing.assert_array_equal(ks, ka[[7, 1]])
+    np.testing.assert_array_equal(vs, va[[7, 1]])
+    with pytest.raises(ValueError):
+        cref.project_rows(x[:, :15], np.zeros((3 + 3 + dk, 15)), [0], 1, 1, 3, dk, theta=1.0e4)
