@@ -157,6 +157,44 @@ int std_attn_scores(const lisa_desc* desc, const void* q, const void* k, const v
 int lisa_cache_fill(const lisa_desc* desc, const void* k_lr, const void* v, void* k_lr_cache,
                     void* v_cache, void* hip_stream);
 
+/* Descriptor of lisa_project_qkv (host memory, plain data, zero-initialise then fill). */
+typedef struct lisa_proj_desc {
+  int32_t dtype;            /* lisa_dtype of X, W and of the three outputs                     */
+  int32_t B;                /* sequences                                                       */
+  int32_t L;                /* new tokens per sequence in this call                            */
+  int32_t d_model;          /* width d of the hidden states                                    */
+  int32_t H;                /* query heads                                                     */
+  int32_t Hkv;              /* key/value heads                                                 */
+  int32_t r;                /* per-head low-rank dimension (Eq. 3); even when rope_theta > 0   */
+  int32_t d_k;              /* head dimension of V                                             */
+  int32_t Lmax;             /* token capacity of k_lr and v, >= pos0 + L; 0 selects pos0 + L   */
+  int32_t pos0;             /* position of the first new token: token l is written at key
+                               index pos0 + l and rotated by the angle of position pos0 + l   */
+  int32_t kcache_dim_major; /* k_lr is [B,Hkv,r,Lmax] (1) or [B,Hkv,Lmax,r] (0)                */
+  float rope_theta;         /* base of the rotary position embedding; 0 = none                 */
+} lisa_proj_desc;
+
+/*
+ * lisa_project_qkv -- front end of a LiSA layer: the low-rank queries and keys
+ * Q_LR = X W^Q_LR, K_LR = X W^K_LR (the two factors of Eq. 3) and the values V = X W^V
+ * (Sec. 2.1 Eq. 1) in one product, split in heads and written where lisa_attn_prefill (dense
+ * tensors: pos0 = 0, Lmax = L or 0, kcache_dim_major = 0) or lisa_attn_decode (the caches,
+ * Sec. 5.2) read them.  The paper's LLaMA models (Sec. 6.1) rotate queries and keys by
+ * position; with rope_theta > 0 every Q_LR / K_LR head y of the token at position p becomes
+ *   (y[t] cos a - y[t+r/2] sin a,  y[t] sin a + y[t+r/2] cos a),  a = p * rope_theta^(-2t/r),
+ * for t < r/2, before it is rounded and stored (the cache holds rotated K_LR).
+ *   x     [B,L,d_model]                          in
+ *   w     [H*r + Hkv*r + Hkv*d_k, d_model]       in   one row per output feature: the columns
+ *                                                     of W^Q_LR (head-major), then of W^K_LR,
+ *                                                     then of W^V
+ *   q_lr  [B,H,L,r]                              out
+ *   k_lr  [B,Hkv,Lmax,r] or [B,Hkv,r,Lmax]       out  key indices pos0 .. pos0+L-1 are written
+ *   v     [B,Hkv,Lmax,d_k]                       out  likewise
+ * No workspace.  Accumulation is float32 (float64 for LISA_F32 inputs).
+ */
+int lisa_project_qkv(const lisa_proj_desc* desc, const void* x, const void* w, void* q_lr,
+                     void* k_lr, void* v, void* hip_stream);
+
 /* Host-only helpers (no HIP call). */
 
 /* Scratch bytes the given entry point (lisa_ws_kind) needs for this descriptor. */
@@ -176,7 +214,8 @@ const char* lisa_strerror(int status);
 /* hipGetErrorString of the last failed launch seen by this thread ("" if none). */
 const char* lisa_last_hip_error(void);
 /* Name of the kernel family the last successful call on this thread dispatched to
- * ("generic", "mfma_fused", "mfma_std", "decode_split", "cache_fill"); for tests and
+ * ("generic", "mfma_fused", "mfma_std", "decode_split", "cache_fill", "project_generic",
+ * "project_mfma"); for tests and
  * benchmark reports. */
 const char* lisa_last_path(void);
 

@@ -1,0 +1,415 @@
+// Projection front end of a LiSA layer: Q_LR = X W^Q_LR, K_LR = X W^K_LR (the two factors of
+// Eq. 3) and V = X W^V (Sec. 2.1 Eq. 1) as one product X W^T over the stacked weight rows, with
+// the rotary position embedding of the LLaMA models (Sec. 6.1) applied to the Q_LR / K_LR heads
+// before they are stored, and the results written where the attention kernels and the decode
+// caches expect them.
+//
+// bf16 kernel (k_project_mfma): a workgroup of 8 waves owns a 256 x 256 tile of the product and
+// streams the reduction axis in steps of 64 through two LDS buffers (one barrier per step: the
+// tile of step k+1 is written right after the barrier that publishes step k, the loads of step
+// k+2 are in flight during the MFMAs of step k).  A CU fetches at most 64 bytes per clock from
+// its vector memory path and its MFMAs eat 2 * 256 * 256 / (256 + 256) = 256 flops per fetched
+// element at this tile size, twice what the fetch path must sustain; a 128 x 128 tile would run at
+// that limit.  Wave (wm, wn) of the 2 x 4 arrangement owns 128 x 64 outputs = 4 x 2 blocks
+// of the 32x32x16 MFMA (A = token rows, B = feature rows, so lane % 32 is the feature).
+//
+// The feature axis of the product is *virtual*: every Q_LR / K_LR head takes 32 columns, of
+// which the first r are real (the others repeat a weight row and are dropped), so that one
+// MFMA block is one head: the two partners of a rotary pair (t, t + r/2) sit in two lanes of
+// the same accumulator register and one lane permute fetches the partner.  With r = 22 this
+// spends 12 % more MFMA work on the LLaMA2-7B shape than the real columns need.
+// LDS rows are 128 bytes (64 reduction elements); the 16-byte chunk c of row m is kept at
+// chunk c ^ ((m / 2) % 8), which makes both the tile writes and the operand reads free of
+// bank conflicts without padding.
+#pragma once
+#include "lisa_types.h"
+
+namespace lisa {
+
+struct ProjectArgs {
+  const void* x;     // [B*L, D]
+  const void* w;     // [H*r + Hkv*r + Hkv*dk, D]
+  void* q_lr;        // [B,H,L,r]
+  void* k_lr;        // [B,Hkv,Lmax,r] or [B,Hkv,r,Lmax]
+  void* v;           // [B,Hkv,Lmax,dk]
+  int B, L, D, H, Hkv, r, dk, Lmax, pos0, k_dim_major;
+  int rope;          // 1: rotate Q_LR / K_LR
+  double freq_log2;  // inverse frequency of pair t = 2^(t * freq_log2), freq_log2 = -2 log2(theta) / r
+  int n_m, n_n, own_n;
+};
+
+// cos and sin of pos * inv_freq.  The angle (up to ~1e5 rad) is formed and reduced to
+// [-pi, pi] in double; the float32 functions then work on a small argument.
+__device__ __forceinline__ void rope_cos_sin(int pos, double inv_freq, float& c, float& s) {
+  const double ang = (double)pos * inv_freq;
+  const double k = rint(ang * 0.15915494309189535);        // 1 / (2 pi)
+  double red = fma(-k, 6.283185307179586, ang);
+  red = fma(-k, 2.4492935982947064e-16, red);              // low part of 2 pi
+  const float rf = (float)red;
+  s = sinf(rf);
+  c = cosf(rf);
+}
+// The same through the hardware sine / cosine (argument in revolutions, absolute error near
+// 1e-6): enough for results that are rounded to bfloat16.
+__device__ __forceinline__ void rope_cos_sin_fast(int pos, double inv_freq_rev, float& c, float& s) {
+  const double rev = (double)pos * inv_freq_rev;           // inv_freq_rev = inv_freq / (2 pi)
+  const float fr = (float)(rev - rint(rev));
+  s = __builtin_amdgcn_sinf(fr);
+  c = __builtin_amdgcn_cosf(fr);
+}
+
+// Where output (token row m, feature n of the stacked weight) goes.  Returns the element index
+// and selects the tensor through `which` (0 Q_LR, 1 K_LR, 2 V).
+__device__ __forceinline__ size_t project_dest(const ProjectArgs& a, int b, int l, int head, int c,
+                                               int& which) {
+  const int pos = a.pos0 + l;
+  if (head < a.H) {
+    which = 0;
+    return (((size_t)b * a.H + head) * a.L + l) * a.r + c;
+  }
+  if (head < a.H + a.Hkv) {
+    which = 1;
+    const int kv = head - a.H;
+    return a.k_dim_major ? (((size_t)b * a.Hkv + kv) * a.r + c) * a.Lmax + pos
+                         : (((size_t)b * a.Hkv + kv) * a.Lmax + pos) * a.r + c;
+  }
+  which = 2;
+  const int kv = head - a.H - a.Hkv;
+  return (((size_t)b * a.Hkv + kv) * a.Lmax + pos) * a.dk + c;
+}
+
+// ---- any dtype, any shape: one thread per output element -------------------------------
+template <typename T, typename AccT>
+__global__ __launch_bounds__(256) void k_project_generic(ProjectArgs a) {
+  const int nqk = (a.H + a.Hkv) * a.r;
+  const int N = nqk + a.Hkv * a.dk;
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (size_t)a.B * a.L * N) return;
+  const int m = (int)(idx / N), f = (int)(idx % N);
+  const int b = m / a.L, l = m % a.L;
+  const T* xr = (const T*)a.x + (size_t)m * a.D;
+  auto dot = [&](int row) {
+    const T* wr = (const T*)a.w + (size_t)row * a.D;
+    AccT acc = 0;
+    for (int c = 0; c < a.D; ++c) acc += (AccT)elem<T>::load(xr + c) * (AccT)elem<T>::load(wr + c);
+    return acc;
+  };
+  int head, c;
+  float y;
+  if (f < nqk) {
+    head = f / a.r;
+    c = f % a.r;
+    const AccT own = dot(f);
+    if (a.rope) {
+      const int half = a.r / 2, t = c < half ? c : c - half;
+      const AccT other = dot(c < half ? f + half : f - half);
+      float cs, sn;
+      rope_cos_sin(a.pos0 + l, exp2((double)t * a.freq_log2), cs, sn);
+      y = c < half ? (float)(own * (AccT)cs - other * (AccT)sn) : (float)(other * (AccT)sn + own * (AccT)cs);
+    } else {
+      y = (float)own;
+    }
+  } else {
+    head = a.H + a.Hkv + (f - nqk) / a.dk;
+    c = (f - nqk) % a.dk;
+    y = (float)dot(f);
+  }
+  int which;
+  const size_t at = project_dest(a, b, l, head, c, which);
+  elem<T>::store((T*)(which == 0 ? a.q_lr : which == 1 ? a.k_lr : a.v) + at, y);
+}
+
+// ---- bf16 on MFMA -----------------------------------------------------------------------
+typedef __bf16 pj_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float pj_f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned pj_u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int PJ_TM = 256, PJ_TN = 256, PJ_TK = 64;
+constexpr int PJ_ROWB = PJ_TK * 2;              // bytes per LDS row
+constexpr int PJ_TILE = PJ_TM * PJ_ROWB;        // one operand tile of one step: 32 KB
+constexpr int PJ_STG_ROW = 64 * 2 + 16;         // bytes per row of a wave's output staging piece (padded)
+constexpr int PJ_STG_WAVE = 128 * PJ_STG_ROW;   // 128 rows x 64 columns per wave
+constexpr int PJ_LDS = 8 * PJ_STG_WAVE;         // the staging space of 8 waves; the main loop uses
+                                                // 4 * PJ_TILE of it: two steps x (X tile, W tile)
+static_assert(PJ_LDS >= 4 * PJ_TILE && PJ_LDS <= 160 * 1024, "LDS budget");
+constexpr int PJ_HEADW = 32;                    // virtual columns of a Q_LR / K_LR head
+
+__device__ __forceinline__ void pj_lds_barrier() {
+  __asm__ volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+__global__ __launch_bounds__(512) void k_project_mfma(ProjectArgs a) {
+  extern __shared__ __align__(16) unsigned char pj_lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int wm = wv >> 2, wn = wv & 3;
+  const int half = lane >> 5, l32 = lane & 31;
+
+  // Workgroup ids go round robin over the 8 XCDs (each with its own L2): an XCD keeps to
+  // its own tiles along one axis of the product so that operand tiles are shared in its L2.
+  int tm, tn;
+  {
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    if (a.own_n) {
+      tn = xcd + 8 * (j / a.n_m);
+      tm = j % a.n_m;
+    } else {
+      tm = xcd + 8 * (j / a.n_n);
+      tn = j % a.n_n;
+    }
+    if (tm >= a.n_m || tn >= a.n_n) return;
+  }
+  const int M = a.B * a.L, D = a.D;
+  const int nheads_qk = a.H + a.Hkv;
+  const int nv_qk = PJ_HEADW * nheads_qk;                   // virtual columns before V
+  const int n_real = nheads_qk * a.r + a.Hkv * a.dk;
+  const int m0 = tm * PJ_TM, n0 = tn * PJ_TN;
+
+  // loader: thread -> 16-byte chunk (row ld_row + 64 i, chunk ld_kc) of both operand tiles
+  const int ld_row = tid >> 3, ld_kc = tid & 7;
+  const bf16_t* xp[4];
+  const bf16_t* wp[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = min(m0 + ld_row + 64 * i, M - 1);
+    xp[i] = (const bf16_t*)a.x + (size_t)row * D + 8 * ld_kc;
+    const int nv = n0 + ld_row + 64 * i;
+    int real;
+    if (nv < nv_qk) {
+      real = (nv >> 5) * a.r + min(nv & 31, a.r - 1);
+    } else {
+      real = nheads_qk * a.r + (nv - nv_qk);
+    }
+    wp[i] = (const bf16_t*)a.w + (size_t)min(real, n_real - 1) * D + 8 * ld_kc;
+  }
+  const int st_off = ld_row * PJ_ROWB + ((ld_kc ^ ((ld_row >> 1) & 7)) << 4);
+  pj_u32x4 rx[4], rw[4];
+  auto load_step = [&](int kt) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      rx[i] = *(const pj_u32x4*)(xp[i] + (size_t)kt * PJ_TK);
+      rw[i] = *(const pj_u32x4*)(wp[i] + (size_t)kt * PJ_TK);
+    }
+  };
+  auto store_step = [&](int buf) {
+    unsigned char* base = pj_lds + buf * (2 * PJ_TILE) + st_off;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      *(pj_u32x4*)(base + i * 64 * PJ_ROWB) = rx[i];
+      *(pj_u32x4*)(base + PJ_TILE + i * 64 * PJ_ROWB) = rw[i];
+    }
+  };
+
+  // operand reads: row (32 blk + l32), chunk 2 ks + half, swizzled by the row
+  const int sw = (l32 >> 1) & 7;
+  int rd_c[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) rd_c[ks] = ((2 * ks + half) ^ sw) << 4;
+  const int rd_a = (wm * 128 + l32) * PJ_ROWB;
+  const int rd_b = PJ_TILE + (wn * 64 + l32) * PJ_ROWB;
+
+  pj_f32x16 acc[4][2];
+#pragma unroll
+  for (int bm = 0; bm < 4; ++bm)
+#pragma unroll
+    for (int bn = 0; bn < 2; ++bn)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[bm][bn][v] = 0.f;
+
+  // Operand registers are double buffered: the reads of sub-step ks + 1 are issued before
+  // the MFMAs of sub-step ks, and the MFMAs of the last sub-step of a step run after the
+  // barrier of the next one, behind its first operand reads and its tile writes, so the
+  // matrix pipe has work while the LDS is busiest.
+  pj_bf16x8 fa[2][4], fb[2][2];
+  auto read_frags = [&](const unsigned char* buf, int ks, int set) {
+#pragma unroll
+    for (int bm = 0; bm < 4; ++bm)
+      fa[set][bm] = *(const pj_bf16x8*)(buf + rd_a + bm * 32 * PJ_ROWB + rd_c[ks]);
+#pragma unroll
+    for (int bn = 0; bn < 2; ++bn)
+      fb[set][bn] = *(const pj_bf16x8*)(buf + rd_b + bn * 32 * PJ_ROWB + rd_c[ks]);
+  };
+  auto mfmas = [&](int set) {
+#pragma unroll
+    for (int bm = 0; bm < 4; ++bm)
+#pragma unroll
+      for (int bn = 0; bn < 2; ++bn)
+        acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][bm], fb[set][bn], acc[bm][bn], 0, 0, 0);
+  };
+
+#ifndef PJ_KNOCK
+#define PJ_KNOCK 0
+#endif
+  const int nk = PJ_KNOCK == 5 ? 1 : D / PJ_TK;
+  load_step(0);
+  store_step(0);
+  if (nk > 1) load_step(1);
+  for (int kt = 0; kt < nk; ++kt) {
+    // step kt is complete in buffer kt & 1 and every wave has read all it needs of the other one
+#ifndef PJ_KNOCK
+#define PJ_KNOCK 0
+#endif
+    if (PJ_KNOCK != 3) pj_lds_barrier();
+    const unsigned char* buf = pj_lds + (kt & 1) * (2 * PJ_TILE);
+    read_frags(buf, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (kt > 0) mfmas(1);                                  // sub-step 3 of step kt - 1
+    __builtin_amdgcn_sched_barrier(0);
+    if (PJ_KNOCK < 2 && kt + 1 < nk) store_step((kt + 1) & 1);
+    if (PJ_KNOCK == 0 && kt + 2 < nk) load_step(kt + 2);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int ks = 0; ks < 3; ++ks) {
+      if (PJ_KNOCK != 4) read_frags(buf, ks + 1, (ks + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfmas(ks & 1);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  mfmas(1);
+
+  // Epilogue.  acc[bm][bn][v]: token row m0 + 128 wm + 32 bm + 8 (v/4) + 4 half + v%4, virtual
+  // column n0 + 64 wn + 32 bn + l32.  Every wave rotates its Q_LR / K_LR blocks in registers
+  // (the partner of a rotary pair is another lane of the same register), rounds to bfloat16 and
+  // lays its 128 x 64 outputs out by rows in its own piece of the LDS, from where whole rows
+  // go to memory: 128-byte pieces of V rows, the 2r-byte rows of Q_LR / K_LR (consecutive
+  // tokens of a head are adjacent in memory), 64-byte runs along the tokens of a
+  // dimension-major K_LR cache.
+  __syncthreads();                                         // the operand tiles are dead: LDS becomes staging space
+  unsigned char* stg = pj_lds + wv * PJ_STG_WAVE;
+  const int mw = m0 + wm * 128;                            // first token row of the wave
+  const int odd = lane & 1;
+#pragma unroll
+  for (int bn = 0; bn < 2; ++bn) {
+    const int nvb = n0 + wn * 64 + bn * 32;                // first virtual column of the block (wave-uniform)
+    const bool rot = a.rope && nvb < nv_qk;
+    const int hr = a.r >> 1;
+    const bool lower = l32 < hr;
+    double inv_freq_rev = 0.0;
+    int partner = lane;
+    if (rot) {
+      const int t = lower ? l32 : l32 - hr;
+      inv_freq_rev = exp2((double)min(t, hr - 1) * a.freq_log2) * 0.15915494309189535;
+      partner = (lane & 32) | (l32 < a.r ? (lower ? l32 + hr : l32 - hr) : l32);
+    }
+#pragma unroll
+    for (int bm = 0; bm < 4; ++bm) {
+      int l0 = 0;
+      if (rot) {
+        const int mb = min(mw + bm * 32 + 4 * half, M - 1);
+        l0 = mb - mb / a.L * a.L;
+      }
+#pragma unroll
+      for (int v = 0; v < 16; v += 2) {
+        float y[2] = {acc[bm][bn][v], acc[bm][bn][v + 1]};
+        if (rot) {
+#pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            int l = l0 + 8 * (v >> 2) + (v & 3) + e;
+            if (l >= a.L) l -= l / a.L * a.L;              // the row block runs into the next sequence(s)
+            const float other = __shfl(y[e], partner, 64);
+            float cs, sn;
+            rope_cos_sin_fast(a.pos0 + l, inv_freq_rev, cs, sn);
+            y[e] = lower ? y[e] * cs - other * sn : other * sn + y[e] * cs;
+          }
+        }
+        // columns c, c + 1 of one row share a 32-bit word: the even lane assembles row v, the odd
+        // lane row v + 1
+        const unsigned u0 = f32_to_bf16_bits(y[0]), u1 = f32_to_bf16_bits(y[1]);
+        const unsigned got = __shfl_xor(odd ? u0 : u1, 1, 64);
+        const unsigned word = odd ? (got | (u1 << 16)) : (u0 | (got << 16));
+        const int row = bm * 32 + 8 * (v >> 2) + 4 * half + (v & 3) + odd;
+        *(unsigned*)(stg + row * PJ_STG_ROW + (bn * 32 + (l32 & ~1)) * 2) = word;
+      }
+    }
+  }
+  // (the staging piece is private to the wave: its own LDS accesses complete in order)
+  int bw, lw;                                              // sequence and token index of row mw
+  {
+    const int mc = min(mw, M - 1);
+    bw = mc / a.L;
+    lw = mc - bw * a.L;
+  }
+  auto locate = [&](int row, int& b, int& l) {             // token row mw + row -> (sequence, token)
+    b = bw;
+    l = lw + row;
+    if (l >= a.L) {
+      const int q = l / a.L;
+      b += q;
+      l -= q * a.L;
+    }
+  };
+  const int nvw = n0 + wn * 64;
+  const int n_vcols = a.Hkv * a.dk;
+  if (nvw >= nv_qk && (nvw - nv_qk) % a.dk + 64 <= a.dk) {
+    // both blocks belong to one V head: 128-byte pieces of rows
+    const int col = nvw - nv_qk;
+    if (col < n_vcols) {
+      const int kv = col / a.dk, cc = col - kv * a.dk;
+#pragma unroll 4
+      for (int pass = 0; pass < 16; ++pass) {
+        const int row = pass * 8 + (lane >> 3), ch = lane & 7;
+        int b, l;
+        locate(row, b, l);
+        if (mw + row < M) {
+          bf16_t* dst = (bf16_t*)a.v + (((size_t)b * a.Hkv + kv) * a.Lmax + a.pos0 + l) * a.dk + cc + 8 * ch;
+          *(pj_u32x4*)dst = *(const pj_u32x4*)(stg + row * PJ_STG_ROW + ch * 16);
+        }
+      }
+    }
+  } else {
+    for (int bn = 0; bn < 2; ++bn) {
+      const int nvb = nvw + bn * 32;
+      const unsigned char* sb = stg + bn * 64;
+      if (nvb >= nv_qk) {
+        // a V block on its own: 64-byte pieces of rows
+        const int col = nvb - nv_qk;
+        if (col >= n_vcols) continue;
+        const int kv = col / a.dk, cc = col - kv * a.dk;
+        for (int pass = 0; pass < 8; ++pass) {
+          const int row = pass * 16 + (lane >> 2), ch = lane & 3;
+          int b, l;
+          locate(row, b, l);
+          if (mw + row < M) {
+            bf16_t* dst = (bf16_t*)a.v + (((size_t)b * a.Hkv + kv) * a.Lmax + a.pos0 + l) * a.dk + cc + 8 * ch;
+            *(pj_u32x4*)dst = *(const pj_u32x4*)(sb + row * PJ_STG_ROW + ch * 16);
+          }
+        }
+        continue;
+      }
+      const int head = nvb >> 5;
+      const bool is_q = head < a.H;
+      const int hh = is_q ? head : head - a.H, nh = is_q ? a.H : a.Hkv;
+      if (!is_q && a.k_dim_major) {
+        // runs along the tokens: lane = (token of a 32-row block, parity of the feature)
+        for (int bm = 0; bm < 4; ++bm) {
+          const int row = bm * 32 + l32;
+          int b, l;
+          locate(row, b, l);
+          if (mw + row >= M) continue;
+          bf16_t* dst = (bf16_t*)a.k_lr + ((size_t)b * a.Hkv + hh) * a.r * a.Lmax + a.pos0 + l;
+          for (int c = half; c < a.r; c += 2)
+            dst[(size_t)c * a.Lmax].bits = *(const uint16_t*)(sb + row * PJ_STG_ROW + 2 * c);
+        }
+        continue;
+      }
+      // rows of r elements; 16 lanes per row, a 32-bit word (or, for odd r, an element) each
+      bf16_t* base = (bf16_t*)(is_q ? a.q_lr : a.k_lr);
+      const int lrow = is_q ? a.L : a.Lmax, p0 = is_q ? 0 : a.pos0;
+      const int j = lane & 15;
+      for (int pass = 0; pass < 32; ++pass) {
+        const int row = pass * 4 + (lane >> 4);
+        int b, l;
+        locate(row, b, l);
+        if (mw + row >= M) continue;
+        bf16_t* dst = base + (((size_t)b * nh + hh) * lrow + p0 + l) * a.r;
+        if ((a.r & 1) == 0) {
+          if (2 * j < a.r) *(unsigned*)(dst + 2 * j) = *(const unsigned*)(sb + row * PJ_STG_ROW + 4 * j);
+        } else {
+          for (int c = j; c < a.r; c += 16) dst[c].bits = *(const uint16_t*)(sb + row * PJ_STG_ROW + 2 * c);
+        }
+      }
+    }
+  }
+}
+
+}  // namespace lisa

@@ -12,6 +12,7 @@
 #include "kernels_decode.h"
 #include "kernels_generic.h"
 #include "kernels_prefill.h"
+#include "kernels_project.h"
 #include "kernels_std_prefill.h"
 
 using namespace lisa;
@@ -543,6 +544,67 @@ int lisa_cache_fill(const lisa_desc* d, const void* k_lr, const void* v, void* k
   fill_rows(v, v_cache, d->d_k);
   int rc = check_launch();
   if (rc == LISA_OK) g_path = "cache_fill";
+  return rc;
+}
+
+int lisa_project_qkv(const lisa_proj_desc* d, const void* x, const void* w, void* q_lr, void* k_lr, void* v,
+                     void* hip_stream) {
+  if (!d || !x || !w || !q_lr || !k_lr || !v) return LISA_ERR_NULL;
+  if (d->dtype != LISA_F32 && d->dtype != LISA_BF16) return LISA_ERR_UNSUPPORTED;
+  if (d->B < 1 || d->L < 1 || d->d_model < 1 || d->H < 1 || d->Hkv < 1 || d->r < 1 || d->d_k < 1 ||
+      d->pos0 < 0)
+    return LISA_ERR_SHAPE;
+  if (d->H % d->Hkv != 0) return LISA_ERR_SHAPE;
+  if (d->kcache_dim_major != 0 && d->kcache_dim_major != 1) return LISA_ERR_SHAPE;
+  if (!(d->rope_theta >= 0.f) || !std::isfinite(d->rope_theta)) return LISA_ERR_SHAPE;
+  if (d->rope_theta > 0.f && d->r % 2 != 0) return LISA_ERR_SHAPE;
+  if ((long long)d->pos0 + d->L > 0x7fffffffLL) return LISA_ERR_SHAPE;
+  const int Lmax = d->Lmax > 0 ? d->Lmax : d->pos0 + d->L;
+  if (Lmax < d->pos0 + d->L) return LISA_ERR_SHAPE;
+  if ((long long)d->B * d->L > 0x7fffffffLL) return LISA_ERR_UNSUPPORTED;
+  if (!aligned16(x) || !aligned16(w) || !aligned16(q_lr) || !aligned16(k_lr) || !aligned16(v))
+    return LISA_ERR_ALIGN;
+  hipStream_t st = (hipStream_t)hip_stream;
+  ProjectArgs a{};
+  a.x = x; a.w = w; a.q_lr = q_lr; a.k_lr = k_lr; a.v = v;
+  a.B = d->B; a.L = d->L; a.D = d->d_model; a.H = d->H; a.Hkv = d->Hkv; a.r = d->r; a.dk = d->d_k;
+  a.Lmax = Lmax; a.pos0 = d->pos0; a.k_dim_major = d->kcache_dim_major;
+  a.rope = d->rope_theta > 0.f;
+  a.freq_log2 = a.rope ? -2.0 * std::log2((double)d->rope_theta) / d->r : 0.0;
+  const long long M = (long long)d->B * d->L;
+  const long long n_real = (long long)(d->H + d->Hkv) * d->r + (long long)d->Hkv * d->d_k;
+  const bool fast = d->dtype == LISA_BF16 && d->d_model % PJ_TK == 0 && d->r <= PJ_HEADW &&
+                    d->d_k % 32 == 0;
+  const char* path;
+  if (fast) {
+    const long long n_virtual = (long long)PJ_HEADW * (d->H + d->Hkv) + (long long)d->Hkv * d->d_k;
+    a.n_m = (int)((M + PJ_TM - 1) / PJ_TM);
+    a.n_n = (int)((n_virtual + PJ_TN - 1) / PJ_TN);
+    // which axis of the tile grid an XCD keeps to: the one that is balanced over 8 XCDs and
+    // re-reads fewer operand bytes
+    const bool n_ok = a.n_n % 8 == 0 || a.n_n >= 40, m_ok = a.n_m % 8 == 0 || a.n_m >= 40;
+    const double xb = (double)M * d->d_model, wb = (double)n_real * d->d_model;
+    a.own_n = n_ok && (!m_ok || wb / 8 + xb <= xb / 8 + wb);
+    const int per_xcd = a.own_n ? (a.n_n + 7) / 8 * a.n_m : (a.n_m + 7) / 8 * a.n_n;
+    hipError_t e = hipFuncSetAttribute((const void*)k_project_mfma,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, PJ_LDS);
+    if (e != hipSuccess) return hip_fail(e);
+    StageScope scope("k_project_mfma", st);
+    k_project_mfma<<<dim3(8 * per_xcd), 512, PJ_LDS, st>>>(a);
+    path = "project_mfma";
+  } else {
+    const long long total = M * n_real;
+    if ((total + 255) / 256 > 0x7fffffffLL) return LISA_ERR_UNSUPPORTED;
+    StageScope scope("k_project_generic", st);
+    dim3 grid((unsigned)((total + 255) / 256));
+    if (d->dtype == LISA_F32)
+      k_project_generic<float, double><<<grid, 256, 0, st>>>(a);
+    else
+      k_project_generic<bf16_t, float><<<grid, 256, 0, st>>>(a);
+    path = "project_generic";
+  }
+  int rc = check_launch();
+  if (rc == LISA_OK) g_path = path;
   return rc;
 }
 

@@ -26,7 +26,7 @@ EXPORTS = (
     "lisa_attn_prefill", "lisa_attn_decode", "std_attn_scores", "lisa_workspace_bytes",
     "lisa_scores_bytes", "lisa_score_elem_bytes", "lisa_kcache_saved_bytes", "lisa_supported",
     "lisa_strerror", "lisa_last_hip_error", "lisa_last_path", "lisa_profile_enable",
-    "lisa_profile_collect", "lisa_cache_fill",
+    "lisa_profile_collect", "lisa_cache_fill", "lisa_project_qkv",
 )
 
 
@@ -47,6 +47,15 @@ class Desc(C.Structure):
         ("delta_scale", C.c_float), ("std_scale", C.c_float), ("causal", C.c_int32),
         ("write_scores", C.c_int32), ("kcache_dim_major", C.c_int32), ("Lmax", C.c_int32),
         ("out_f32", C.c_int32),
+    ]
+
+
+class ProjDesc(C.Structure):
+    _fields_ = [
+        ("dtype", C.c_int32), ("B", C.c_int32), ("L", C.c_int32), ("d_model", C.c_int32),
+        ("H", C.c_int32), ("Hkv", C.c_int32), ("r", C.c_int32), ("d_k", C.c_int32),
+        ("Lmax", C.c_int32), ("pos0", C.c_int32), ("kcache_dim_major", C.c_int32),
+        ("rope_theta", C.c_float),
     ]
 
 
@@ -91,6 +100,8 @@ def _lib():
         h.lisa_profile_enable.restype = C.c_int
         h.lisa_cache_fill.argtypes = [dp] + [vp] * 5
         h.lisa_cache_fill.restype = C.c_int
+        h.lisa_project_qkv.argtypes = [C.POINTER(ProjDesc)] + [vp] * 6
+        h.lisa_project_qkv.restype = C.c_int
         h.lisa_profile_collect.argtypes = [C.POINTER(StageTime), C.c_int]
         h.lisa_profile_collect.restype = C.c_int
         _handle = h
@@ -282,6 +293,35 @@ def lisa_cache_fill(k_lr, v, k_lr_cache, v_cache, *, dim_major=True):
     if rc:
         raise LisaError(rc, "lisa_cache_fill")
     return k_lr_cache, v_cache
+
+
+def lisa_project_qkv(x, w, H, Hkv, r, d_k, *, rope_theta=0.0, pos0=0, q_lr=None, k_lr=None, v=None,
+                     dim_major=False):
+    """Front end of a LiSA layer: x [B,L,d] times the stacked weight rows w [H*r + Hkv*r + Hkv*d_k, d]
+    (W^Q_LR, W^K_LR, W^V, one row per output feature), rotary embedding on Q_LR / K_LR when
+    rope_theta > 0.  Writes q_lr [B,H,L,r] and, at key indices pos0 .. pos0+L-1, k_lr
+    ([B,Hkv,r,Lmax] if dim_major else [B,Hkv,Lmax,r]) and v [B,Hkv,Lmax,d_k]; tensors that are
+    not passed are allocated dense (Lmax = pos0 + L).  Returns (q_lr, k_lr, v)."""
+    B, L, D = x.shape
+    dt = x.dtype
+    dev = x.device
+    Lmax = v.shape[2] if v is not None else pos0 + L
+    kshape = (B, Hkv, r, Lmax) if dim_major else (B, Hkv, Lmax, r)
+    if q_lr is None:
+        q_lr = torch.empty((B, H, L, r), dtype=dt, device=dev)
+    if k_lr is None:
+        k_lr = torch.empty(kshape, dtype=dt, device=dev)
+    if v is None:
+        v = torch.empty((B, Hkv, Lmax, d_k), dtype=dt, device=dev)
+    code = {torch.float32: F32, torch.bfloat16: BF16}[dt]
+    desc = ProjDesc(code, B, L, D, H, Hkv, r, d_k, Lmax, pos0, int(dim_major), float(rope_theta or 0.0))
+    rc = _lib().lisa_project_qkv(
+        C.byref(desc), _ptr(x, "x", dtype=dt), _ptr(w, "w", ((H + Hkv) * r + Hkv * d_k, D), dt),
+        _ptr(q_lr, "q_lr", (B, H, L, r), dt), _ptr(k_lr, "k_lr", kshape, dt),
+        _ptr(v, "v", (B, Hkv, Lmax, d_k), dt), _stream())
+    if rc:
+        raise LisaError(rc, "lisa_project_qkv")
+    return q_lr, k_lr, v
 
 
 def lisa_attn_decode(q_lr, k_lr_cache, v_cache, Lk, score_row_prev, w1, w2, *, k_lr_new=None,

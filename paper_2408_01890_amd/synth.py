@@ -176,6 +176,20 @@ def make_prefill_inputs(cfg: LayerShape, seed: int = BASE_SEED, device="cpu", mi
     return out
 
 
+def make_projection_inputs(cfg: LayerShape, seed: int = BASE_SEED + 9, device="cpu",
+                           L: Optional[int] = None) -> Dict[str, torch.Tensor]:
+    """Operands of the projection front end: hidden states x [B,L,d_model] ~ N(0,1) and the
+    stacked weight rows w [H*r + Hkv*r + Hkv*d_k, d_model] ~ N(0, 0.02^2) (W^Q_LR, W^K_LR, W^V,
+    one row per output feature), rounded to cfg dtype.  Draws only; no product is formed here."""
+    g = _gen(seed, device)
+    dt = cfg.torch_dtype
+    L = cfg.L if L is None else L
+    x = _randn((cfg.B, L, cfg.d_model), g, device).to(dt)
+    n = (cfg.H + cfg.Hkv) * cfg.r + cfg.Hkv * cfg.d_k
+    w = _randn((n, cfg.d_model), g, device, 0.02).to(dt)
+    return {"x": x.contiguous(), "w": w.contiguous()}
+
+
 def make_decode_layer(stk: DecodeStack, layer: int, seed: int = BASE_SEED + 5, device="cpu",
                       mix: str = "add", ffn: str = "paper", dim_major: bool = True,
                       Lmax: Optional[int] = None) -> Dict[str, torch.Tensor]:

@@ -75,3 +75,9 @@ def gather_out_rows(out: torch.Tensor, b: int, rows) -> np.ndarray:
     """out [B,Lq,H,dk] -> float64 [n,H,dk]."""
     idx = torch.as_tensor(np.asarray(rows), device=out.device, dtype=torch.long)
     return f64(out[b].index_select(0, idx))
+
+
+def oracle_project_rows(x, w, b, rows, H, Hkv, r, dk, theta=0.0, pos0=0):
+    """Oracle projection front end for batch element b on the given token rows ->
+    q [n,H,r], k [n,Hkv,r], v [n,Hkv,dk] float64."""
+    return cref.project_rows(f64(x[b]), f64(w), rows, H, Hkv, r, dk, theta=theta or 0.0, pos0=pos0)

@@ -102,6 +102,41 @@ def test_cache_fill_rejects_bad_arguments():
     assert lib.lisa_cache_fill(C.byref(wide), FAKE, FAKE, FAKE, FAKE, None) == -3
 
 
+def test_proj_desc_struct_matches_header_field_order():
+    text = open(os.path.join(ROOT, "include", "lisa.h")).read()
+    body = re.search(r"typedef struct lisa_proj_desc \{(.*?)\} lisa_proj_desc;", text, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"(?:int32_t|float)\s+(\w+);", body)
+    assert fields == [f[0] for f in lisa.ProjDesc._fields_]
+    assert C.sizeof(lisa.ProjDesc) == 4 * len(fields)
+
+
+def test_project_qkv_rejects_bad_arguments():
+    lib = lisa.library()
+
+    def desc(**kw):
+        base = dict(dtype=lisa.BF16, B=2, L=16, d_model=256, H=8, Hkv=2, r=22, d_k=128, Lmax=32,
+                    pos0=4, kcache_dim_major=0, rope_theta=10000.0)
+        base.update(kw)
+        return lisa.ProjDesc(*[base[f[0]] for f in lisa.ProjDesc._fields_])
+
+    def call(d, *ptrs):
+        ptrs = list(ptrs) + [FAKE] * (5 - len(ptrs))
+        return lib.lisa_project_qkv(C.byref(d) if d is not None else None, *ptrs, None)
+
+    assert call(None) == -1
+    assert call(desc(), FAKE, None) == -1
+    assert call(desc(L=0)) == -2
+    assert call(desc(H=8, Hkv=3)) == -2
+    assert call(desc(Lmax=19)) == -2                   # pos0 + L = 20 does not fit
+    assert call(desc(pos0=-1)) == -2
+    assert call(desc(r=21)) == -2                      # rotary pairs need an even r
+    assert call(desc(rope_theta=-1.0)) == -2
+    assert call(desc(kcache_dim_major=2)) == -2
+    assert call(desc(dtype=7)) == -3
+    assert call(desc(), ODD) == -4
+
+
 def test_strerror_is_defined_for_every_status():
     lib = lisa.library()
     seen = set()

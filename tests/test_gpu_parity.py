@@ -547,3 +547,104 @@ def test_error_path_on_gpu_is_reported_not_raised_as_fault():
     with pytest.raises(lisa.LisaError) as e:
         lisa.std_attn_scores(torch.zeros((1, 3, 4, 8), device=DEV, dtype=torch.bfloat16), q)
     assert e.value.status == -2
+
+
+# ---------------------------------------------------------------------------------------
+# projection front end (Q_LR, K_LR, V from the hidden states, rotary embedding)
+# ---------------------------------------------------------------------------------------
+def check_projection(cfg, pin, rows_by_b, theta, pos0, dim_major, Lmax, tag=""):
+    """Runs lisa_project_qkv into sentinel-filled caches and compares the requested token rows
+    with the oracle; also checks that no key slot outside pos0 .. pos0+L-1 was written."""
+    x, w = pin["x"], pin["w"]
+    B, L, _ = x.shape
+    dt = x.dtype
+    H, Hkv, r, dk = cfg.H, cfg.Hkv, cfg.r, cfg.d_k
+    kshape = (B, Hkv, r, Lmax) if dim_major else (B, Hkv, Lmax, r)
+    k_lr = torch.full(kshape, SENTINEL, dtype=dt, device=DEV)
+    v = torch.full((B, Hkv, Lmax, dk), SENTINEL, dtype=dt, device=DEV)
+    q_lr = torch.full((B, H, L, r), SENTINEL, dtype=dt, device=DEV)
+    lisa.lisa_project_qkv(x, w, H, Hkv, r, dk, rope_theta=theta, pos0=pos0, q_lr=q_lr, k_lr=k_lr, v=v,
+                          dim_major=dim_major)
+    torch.cuda.synchronize()
+    path = lisa.last_path()
+    k_rows_major = k_lr.permute(0, 1, 3, 2) if dim_major else k_lr      # [B,Hkv,Lmax,r]
+    tol = hp.TOL[dt]
+    # the outputs are stored in dt: for bfloat16 the rounding of that store is not charged
+    err_fn = hp.row_rel_err_stored_bf16 if dt == torch.bfloat16 else hp.row_rel_err
+    worst = 0.0
+    for b, rows in rows_by_b.items():
+        q_ref, k_ref, v_ref = hp.oracle_project_rows(x, w, b, rows, H, Hkv, r, dk, theta, pos0)
+        idx = torch.as_tensor(np.asarray(rows), device=DEV, dtype=torch.long)
+        q_got = hp.f64(q_lr[b].index_select(1, idx).permute(1, 0, 2))
+        k_got = hp.f64(k_rows_major[b].index_select(1, idx + pos0).permute(1, 0, 2))
+        v_got = hp.f64(v[b].index_select(1, idx + pos0).permute(1, 0, 2))
+        for got, ref in ((q_got, q_ref), (k_got, k_ref), (v_got, v_ref)):
+            worst = max(worst, err_fn(got, ref))
+    log(f"[parity] projection {cfg.name}{tag}: path={path} err={worst:.3e} tol={tol:g}")
+    assert worst <= tol
+    # untouched slots keep the sentinel
+    if pos0 > 0:
+        assert bool((k_rows_major[:, :, :pos0] == SENTINEL).all()) and bool((v[:, :, :pos0] == SENTINEL).all())
+    if pos0 + L < Lmax:
+        assert bool((k_rows_major[:, :, pos0 + L:] == SENTINEL).all())
+        assert bool((v[:, :, pos0 + L:] == SENTINEL).all())
+    assert not bool((q_lr == SENTINEL).any())
+    return path
+
+
+PROJ_SMALL = [
+    # dtype, B, H, Hkv, L, d_model, d_k, r, theta, pos0, dim_major, extra capacity
+    ("f32", 2, 4, 2, 37, 48, 8, 6, 10000.0, 0, False, 0),
+    ("f32", 1, 3, 3, 20, 40, 16, 5, None, 3, True, 4),
+    ("f32", 2, 8, 8, 128, 512, 64, 12, 10000.0, 5, True, 9),
+    ("bf16", 2, 4, 2, 37, 72, 24, 6, 500000.0, 2, False, 3),        # d_model % 64 != 0: generic
+    ("bf16", 1, 2, 1, 9, 64, 32, 34, 10000.0, 0, True, 0),          # r > 32: generic
+]
+
+
+@pytest.mark.parametrize("case", PROJ_SMALL, ids=lambda c: f"{c[0]}-B{c[1]}H{c[2]}-{c[3]}L{c[4]}d{c[5]}r{c[7]}")
+def test_projection_generic_kernel_small(case):
+    dtype, B, H, Hkv, L, D, dk, r, theta, pos0, dim_major, extra = case
+    log(f"[case] projection generic {case}")
+    cfg = synth.LayerShape("proj_small", dtype, B, H, Hkv, L, D, dk, r, 32, theta)
+    pin = synth.make_projection_inputs(cfg, device=DEV)
+    path = check_projection(cfg, pin, {b: np.arange(L) for b in range(B)}, theta, pos0, dim_major,
+                            pos0 + L + extra)
+    assert path == "project_generic"
+
+
+PROJ_MFMA = [
+    # B, H, Hkv, L, d_model, d_k, r, theta, pos0, dim_major, extra capacity
+    (2, 8, 8, 300, 256, 128, 22, 10000.0, 0, False, 0),     # 3 ragged row tiles x 6 column tiles
+    (1, 8, 2, 257, 128, 128, 22, 500000.0, 7, True, 5),     # GQA: a column tile holds K_LR heads and V
+    (3, 4, 4, 50, 64, 32, 8, None, 0, False, 0),            # one reduction step, sequences inside a row block
+    (1, 16, 16, 64, 192, 64, 32, 10000.0, 1000, True, 0),   # r = 32: no padded columns
+    (1, 40, 40, 130, 320, 128, 22, None, 0, False, 2),      # 40 heads
+    (1, 2, 1, 70, 64, 128, 16, 10000.0, 0, False, 0),       # odd head count: V starts inside a wave's columns
+    (2, 4, 4, 40, 64, 96, 10, None, 3, True, 1),            # d_k = 96: V leaves block by block
+    (2, 4, 2, 33, 128, 32, 7, None, 0, False, 0),           # odd r (no rotation): element stores
+]
+
+
+@pytest.mark.parametrize("case", PROJ_MFMA, ids=lambda c: f"B{c[0]}H{c[1]}-{c[2]}L{c[3]}d{c[4]}r{c[6]}")
+def test_projection_mfma_kernel_shapes(case):
+    B, H, Hkv, L, D, dk, r, theta, pos0, dim_major, extra = case
+    log(f"[case] projection mfma {case}")
+    cfg = synth.LayerShape("proj_mfma", "bf16", B, H, Hkv, L, D, dk, r, 64, theta)
+    pin = synth.make_projection_inputs(cfg, device=DEV)
+    path = check_projection(cfg, pin, {b: np.arange(L) for b in range(B)}, theta, pos0, dim_major,
+                            pos0 + L + extra)
+    assert path == "project_mfma"
+
+
+@pytest.mark.parametrize("name", ["c2_llama2_7b_l2048", "c3_llama3_8b_gqa_l8192"])
+def test_projection_full_size_sampled_rows(name):
+    cfg = synth.PREFILL_CONFIGS[name]
+    theta = cfg.rope_theta if cfg.rope_theta is not None else 10000.0
+    log(f"[case] projection full size {name} theta={theta}")
+    pin = synth.make_projection_inputs(cfg, device=DEV)
+    rs = np.random.default_rng(5)
+    rows_by_b = {b: np.unique(np.concatenate([[0, 1, cfg.L - 1], rs.integers(0, cfg.L, 9)]))
+                 for b in (0, cfg.B - 1)}
+    path = check_projection(cfg, pin, rows_by_b, theta, 0, False, cfg.L, tag=" full size")
+    assert path == "project_mfma"
