@@ -134,6 +134,22 @@ constexpr int PJ_LDS = 8 * PJ_STG_WAVE;         // the staging space of 8 waves;
 static_assert(PJ_LDS >= 4 * PJ_TILE && PJ_LDS <= 160 * 1024, "LDS budget");
 constexpr int PJ_HEADW = 32;                    // virtual columns of a Q_LR / K_LR head
 
+// Scheduling request for one sub-step (8 MFMAs, 6 LDS reads, 4 instructions of class `other`:
+// 0x200 LDS writes, 0x020 global loads): the reads early (MFMA, two reads, three times: the
+// next sub-step starts 5 MFMAs after the last of them), then MFMA, two others, twice, 3 MFMAs.
+#define PJ_INTERLEAVE(other)                                  \
+  do {                                                        \
+    _Pragma("unroll") for (int i_ = 0; i_ < 3; ++i_) {        \
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      \
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);      \
+    }                                                         \
+    _Pragma("unroll") for (int i_ = 0; i_ < 2; ++i_) {        \
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      \
+      __builtin_amdgcn_sched_group_barrier(other, 2, 0);      \
+    }                                                         \
+    __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);        \
+  } while (0)
+
 __device__ __forceinline__ void pj_lds_barrier() {
   __asm__ volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
@@ -183,21 +199,23 @@ __global__ __launch_bounds__(512) void k_project_mfma(ProjectArgs a) {
   }
   const int st_off = ld_row * PJ_ROWB + ((ld_kc ^ ((ld_row >> 1) & 7)) << 4);
   pj_u32x4 rx[4], rw[4];
-  auto load_step = [&](int kt) {
+  auto load_part = [&](int kt, int i0, int i1) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = i0; i < i1; ++i) {
       rx[i] = *(const pj_u32x4*)(xp[i] + (size_t)kt * PJ_TK);
       rw[i] = *(const pj_u32x4*)(wp[i] + (size_t)kt * PJ_TK);
     }
   };
-  auto store_step = [&](int buf) {
+  auto store_part = [&](int buf, int i0, int i1) {
     unsigned char* base = pj_lds + buf * (2 * PJ_TILE) + st_off;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = i0; i < i1; ++i) {
       *(pj_u32x4*)(base + i * 64 * PJ_ROWB) = rx[i];
       *(pj_u32x4*)(base + PJ_TILE + i * 64 * PJ_ROWB) = rw[i];
     }
   };
+  auto load_step = [&](int kt) { load_part(kt, 0, 4); };
+  auto store_step = [&](int buf) { store_part(buf, 0, 4); };
 
   // operand reads: row (32 blk + l32), chunk 2 ks + half, swizzled by the row
   const int sw = (l32 >> 1) & 7;
@@ -220,13 +238,14 @@ __global__ __launch_bounds__(512) void k_project_mfma(ProjectArgs a) {
   // barrier of the next one, behind its first operand reads and its tile writes, so the
   // matrix pipe has work while the LDS is busiest.
   pj_bf16x8 fa[2][4], fb[2][2];
+  // (the W operands first: the first MFMAs of a sub-step need both of them and one X operand)
   auto read_frags = [&](const unsigned char* buf, int ks, int set) {
-#pragma unroll
-    for (int bm = 0; bm < 4; ++bm)
-      fa[set][bm] = *(const pj_bf16x8*)(buf + rd_a + bm * 32 * PJ_ROWB + rd_c[ks]);
 #pragma unroll
     for (int bn = 0; bn < 2; ++bn)
       fb[set][bn] = *(const pj_bf16x8*)(buf + rd_b + bn * 32 * PJ_ROWB + rd_c[ks]);
+#pragma unroll
+    for (int bm = 0; bm < 4; ++bm)
+      fa[set][bm] = *(const pj_bf16x8*)(buf + rd_a + bm * 32 * PJ_ROWB + rd_c[ks]);
   };
   auto mfmas = [&](int set) {
 #pragma unroll
@@ -236,30 +255,67 @@ __global__ __launch_bounds__(512) void k_project_mfma(ProjectArgs a) {
         acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][bm], fb[set][bn], acc[bm][bn], 0, 0, 0);
   };
 
-#ifndef PJ_KNOCK
-#define PJ_KNOCK 0
-#endif
-  const int nk = PJ_KNOCK == 5 ? 1 : D / PJ_TK;
+  // Inside a step the MFMAs of a sub-step are interleaved one by one with the LDS reads of the
+  // next sub-step, the LDS writes of the next tile and the global loads of the tile after it
+  // (a wave issues in order: a block of 8 tile writes or 8 loads would leave the matrix pipe of
+  // its SIMD idle, and both waves of a SIMD reach that block together).  The operand sets
+  // start as zeros so that the deferred MFMAs of the first step add nothing.
+#pragma unroll
+  for (int bm = 0; bm < 4; ++bm)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) fa[1][bm][e] = (__bf16)0.f;
+#pragma unroll
+  for (int bn = 0; bn < 2; ++bn)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) fb[1][bn][e] = (__bf16)0.f;
+
+  const int nk = D / PJ_TK;
   load_step(0);
   store_step(0);
   if (nk > 1) load_step(1);
-  for (int kt = 0; kt < nk; ++kt) {
+  int kt = 0;
+  for (; kt + 2 < nk; ++kt) {
     // step kt is complete in buffer kt & 1 and every wave has read all it needs of the other one
-#ifndef PJ_KNOCK
-#define PJ_KNOCK 0
-#endif
-    if (PJ_KNOCK != 3) pj_lds_barrier();
+    pj_lds_barrier();
+    const unsigned char* buf = pj_lds + (kt & 1) * (2 * PJ_TILE);
+    const int nb = (kt + 1) & 1;
+    // sub-step 3 of step kt - 1 | operands of sub-step 0, first half of the tile writes
+    read_frags(buf, 0, 0);
+    store_part(nb, 0, 2);
+    mfmas(1);
+    PJ_INTERLEAVE(0x200);
+    __builtin_amdgcn_sched_barrier(0);
+    // sub-step 0 | operands of sub-step 1, second half of the tile writes
+    read_frags(buf, 1, 1);
+    store_part(nb, 2, 4);
+    mfmas(0);
+    PJ_INTERLEAVE(0x200);
+    __builtin_amdgcn_sched_barrier(0);
+    // sub-step 1 | operands of sub-step 2, first half of the loads of step kt + 2
+    read_frags(buf, 2, 0);
+    load_part(kt + 2, 0, 2);
+    mfmas(1);
+    PJ_INTERLEAVE(0x020);
+    __builtin_amdgcn_sched_barrier(0);
+    // sub-step 2 | operands of sub-step 3, second half of the loads
+    read_frags(buf, 3, 1);
+    load_part(kt + 2, 2, 4);
+    mfmas(0);
+    PJ_INTERLEAVE(0x020);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  for (; kt < nk; ++kt) {                                  // the last two steps: nothing left to load
+    pj_lds_barrier();
     const unsigned char* buf = pj_lds + (kt & 1) * (2 * PJ_TILE);
     read_frags(buf, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
-    if (kt > 0) mfmas(1);                                  // sub-step 3 of step kt - 1
+    mfmas(1);
     __builtin_amdgcn_sched_barrier(0);
-    if (PJ_KNOCK < 2 && kt + 1 < nk) store_step((kt + 1) & 1);
-    if (PJ_KNOCK == 0 && kt + 2 < nk) load_step(kt + 2);
+    if (kt + 1 < nk) store_step((kt + 1) & 1);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int ks = 0; ks < 3; ++ks) {
-      if (PJ_KNOCK != 4) read_frags(buf, ks + 1, (ks + 1) & 1);
+      read_frags(buf, ks + 1, (ks + 1) & 1);
       __builtin_amdgcn_sched_barrier(0);
       mfmas(ks & 1);
       __builtin_amdgcn_sched_barrier(0);
