@@ -273,6 +273,36 @@ def main():
         "paper_context": "end-to-end generation throughput gains on one A800-80GB: +19.5% LLaMA3-8B, "
                          "+32.3% LLaMA2-7B, +40.1% LLaMA2-13B (not this metric)",
     }
+    # the projection front end (hidden states -> rotated Q_LR, K_LR and V) and the layer behind it
+    pin = synth.make_projection_inputs(cfg, device=dev)
+    theta = cfg.rope_theta if cfg.rope_theta is not None else 10000.0
+    pq, pk, pv = lisa.lisa_project_qkv(pin["x"], pin["w"], cfg.H, cfg.Hkv, cfg.r, cfg.d_k, rope_theta=theta)
+
+    def step_proj():
+        lisa.lisa_project_qkv(pin["x"], pin["w"], cfg.H, cfg.Hkv, cfg.r, cfg.d_k, rope_theta=theta,
+                              q_lr=pq, k_lr=pk, v=pv)
+
+    def step_proj_layer():
+        s = sets[counter[0] % n_sets]
+        counter[0] += 1
+        i = s["inp"]
+        step_proj()
+        lisa.lisa_attn_prefill(pq, pk, pv, s["prev"], i["w1"], i["w2"], write_scores=True, out=s["out"],
+                               scores_out=s["a_n"], workspace=ws)
+
+    sec_proj = time_steps(step_proj, max(args.steps // 2, 1), 2)
+    proj_path = lisa.last_path()
+    sec_proj_layer = time_steps(step_proj_layer, max(args.steps // 2, 1), 2)
+    proj_flops = 2.0 * cfg.B * cfg.L * cfg.d_model * ((cfg.H + cfg.Hkv) * cfg.r + cfg.Hkv * cfg.d_k)
+    extra["projection"] = {
+        "path": proj_path, "ms": sec_proj * 1e3, "GFLOP": proj_flops / 1e9,
+        "TFLOP_per_s": proj_flops / sec_proj / 1e12,
+        "mfma_frac": proj_flops / sec_proj / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        "rope_theta": theta,
+        "projection_plus_lisa_layer_ms": sec_proj_layer * 1e3,
+        "projection_plus_lisa_layer_tokens_per_s": cfg.B * cfg.L / sec_proj_layer,
+    }
+    del pin, pq, pk, pv
     cpu = None
     if not args.no_cpu:
         cpu = cpu_baseline(cfg, sets[0]["inp"], sets[0]["prev"], args.cpu_budget)

@@ -64,7 +64,7 @@ typedef enum {
   LISA_ERR_HIP = -6          /* a HIP launch failed; see lisa_last_hip_error()          */
 } lisa_status;
 
-typedef enum { LISA_WS_PREFILL = 0, LISA_WS_DECODE = 1, LISA_WS_STD = 2 } lisa_ws_kind;
+typedef enum { LISA_WS_PREFILL = 0, LISA_WS_DECODE = 1, LISA_WS_STD = 2, LISA_WS_LAYER = 3 } lisa_ws_kind;
 
 /* Problem descriptor (host memory, plain data, zero-initialise then fill). */
 typedef struct lisa_desc {
@@ -195,7 +195,27 @@ typedef struct lisa_proj_desc {
 int lisa_project_qkv(const lisa_proj_desc* desc, const void* x, const void* w, void* q_lr,
                      void* k_lr, void* v, void* hip_stream);
 
+/*
+ * lisa_layer_prefill -- a whole LiSA attention layer from the hidden states: lisa_project_qkv
+ * (Eq. 3's factors H W^Q_LR, H W^K_LR and V = H W^V, rotated by position when rope_theta > 0)
+ * followed by lisa_attn_prefill (Sec. 5.1, Eq. 3-4; Sec. 2.1 Eq. 1-2 without W^O) on the same
+ * stream.  A fresh prefill: requires Lq = Lk; positions 0 .. Lq-1.
+ *   x [B,Lq,d_model], w_qkv [H*r + Hkv*r + Hkv*d_k, d_model]   in   as in lisa_project_qkv
+ *   scores_prev, w1, w2, out, scores_out                        as in lisa_attn_prefill
+ *   workspace   at least lisa_workspace_bytes(desc, LISA_WS_LAYER) bytes: the prefill workspace
+ *               followed by Q_LR, K_LR and V, which can be read there after the call
+ *               (offsets lisa_layer_offsets()).
+ */
+int lisa_layer_prefill(const lisa_desc* desc, int32_t d_model, float rope_theta, const void* x,
+                       const void* w_qkv, const void* scores_prev, const void* w1, const void* w2,
+                       void* out, void* scores_out, void* workspace, size_t workspace_bytes,
+                       void* hip_stream);
+
 /* Host-only helpers (no HIP call). */
+
+/* Byte offsets of Q_LR [B,H,Lq,r], K_LR [B,Hkv,Lq,r] and V [B,Hkv,Lq,d_k] inside the workspace of
+ * lisa_layer_prefill; returns 0 or a negative lisa_status. */
+int lisa_layer_offsets(const lisa_desc* desc, size_t* q_lr_off, size_t* k_lr_off, size_t* v_off);
 
 /* Scratch bytes the given entry point (lisa_ws_kind) needs for this descriptor. */
 size_t lisa_workspace_bytes(const lisa_desc* desc, int which);

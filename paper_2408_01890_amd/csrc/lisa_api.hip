@@ -638,9 +638,56 @@ size_t lisa_workspace_bytes(const lisa_desc* desc, int which) {
       // needed only when `out` is requested
       if (std_prefill_fast_ok(desc)) return std_prefill_ws(desc);
       return decode_fast_ok(desc, false) ? decode_fast_bytes(desc) : exact_bytes(desc);
+    case LISA_WS_LAYER: {
+      size_t q, k, v;
+      if (lisa_layer_offsets(desc, &q, &k, &v) != LISA_OK) return 0;
+      const size_t e = desc->dtype == LISA_F32 ? 4 : 2;
+      return v + round_up((size_t)desc->B * desc->Hkv * desc->Lq * desc->d_k * e, 256);
+    }
     default:
       return 0;
   }
+}
+
+int lisa_layer_offsets(const lisa_desc* desc, size_t* q_lr_off, size_t* k_lr_off, size_t* v_off) {
+  int rc = check_lisa(desc);
+  if (rc) return rc;
+  if (!q_lr_off || !k_lr_off || !v_off) return LISA_ERR_NULL;
+  if (desc->Lq != desc->Lk) return LISA_ERR_SHAPE;
+  const size_t e = desc->dtype == LISA_F32 ? 4 : 2;
+  *q_lr_off = round_up(lisa_workspace_bytes(desc, LISA_WS_PREFILL), 256);
+  *k_lr_off = *q_lr_off + round_up((size_t)desc->B * desc->H * desc->Lq * desc->r * e, 256);
+  *v_off = *k_lr_off + round_up((size_t)desc->B * desc->Hkv * desc->Lq * desc->r * e, 256);
+  return LISA_OK;
+}
+
+int lisa_layer_prefill(const lisa_desc* desc, int32_t d_model, float rope_theta, const void* x,
+                       const void* w_qkv, const void* scores_prev, const void* w1, const void* w2,
+                       void* out, void* scores_out, void* workspace, size_t workspace_bytes,
+                       void* hip_stream) {
+  size_t qo, ko, vo;
+  int rc = lisa_layer_offsets(desc, &qo, &ko, &vo);
+  if (rc) return rc;
+  if (!x || !w_qkv || !scores_prev || !w1 || !w2 || !out) return LISA_ERR_NULL;
+  if (desc->write_scores && !scores_out) return LISA_ERR_NULL;
+  if (!workspace || !aligned16(workspace)) return workspace ? LISA_ERR_ALIGN : LISA_ERR_WORKSPACE;
+  if (workspace_bytes < lisa_workspace_bytes(desc, LISA_WS_LAYER)) return LISA_ERR_WORKSPACE;
+  lisa_proj_desc pd{};
+  pd.dtype = desc->dtype;
+  pd.B = desc->B;
+  pd.L = desc->Lq;
+  pd.d_model = d_model;
+  pd.H = desc->H;
+  pd.Hkv = desc->Hkv;
+  pd.r = desc->r;
+  pd.d_k = desc->d_k;
+  pd.Lmax = desc->Lq;
+  pd.rope_theta = rope_theta;
+  char* ws = (char*)workspace;
+  rc = lisa_project_qkv(&pd, x, w_qkv, ws + qo, ws + ko, ws + vo, hip_stream);
+  if (rc) return rc;
+  return lisa_attn_prefill(desc, ws + qo, ws + ko, ws + vo, scores_prev, w1, w2, out, scores_out, workspace,
+                           qo, hip_stream);
 }
 
 int lisa_supported(const lisa_desc* desc) { return check_lisa(desc); }

@@ -20,13 +20,14 @@ LIB_PATH = os.path.join(_HERE, "liblisa_mi355x.so")
 F32, BF16 = 0, 1
 MIX_ADD, MIX_CONCAT = 0, 1
 ACT_RELU = 0
-WS_PREFILL, WS_DECODE, WS_STD = 0, 1, 2
+WS_PREFILL, WS_DECODE, WS_STD, WS_LAYER = 0, 1, 2, 3
 
 EXPORTS = (
     "lisa_attn_prefill", "lisa_attn_decode", "std_attn_scores", "lisa_workspace_bytes",
     "lisa_scores_bytes", "lisa_score_elem_bytes", "lisa_kcache_saved_bytes", "lisa_supported",
     "lisa_strerror", "lisa_last_hip_error", "lisa_last_path", "lisa_profile_enable",
-    "lisa_profile_collect", "lisa_cache_fill", "lisa_project_qkv",
+    "lisa_profile_collect", "lisa_cache_fill", "lisa_project_qkv", "lisa_layer_prefill",
+    "lisa_layer_offsets",
 )
 
 
@@ -102,6 +103,10 @@ def _lib():
         h.lisa_cache_fill.restype = C.c_int
         h.lisa_project_qkv.argtypes = [C.POINTER(ProjDesc)] + [vp] * 6
         h.lisa_project_qkv.restype = C.c_int
+        h.lisa_layer_prefill.argtypes = [dp, C.c_int32, C.c_float] + [vp] * 8 + [sz, vp]
+        h.lisa_layer_prefill.restype = C.c_int
+        h.lisa_layer_offsets.argtypes = [dp] + [C.POINTER(sz)] * 3
+        h.lisa_layer_offsets.restype = C.c_int
         h.lisa_profile_collect.argtypes = [C.POINTER(StageTime), C.c_int]
         h.lisa_profile_collect.restype = C.c_int
         _handle = h
@@ -322,6 +327,50 @@ def lisa_project_qkv(x, w, H, Hkv, r, d_k, *, rope_theta=0.0, pos0=0, q_lr=None,
     if rc:
         raise LisaError(rc, "lisa_project_qkv")
     return q_lr, k_lr, v
+
+
+def lisa_layer_prefill(x, w_qkv, Hkv, r, d_k, scores_prev, w1, w2, *, rope_theta=0.0, mix=MIX_ADD,
+                       write_scores=True, causal=True, out=None, out_dtype=None, scores_out=None,
+                       workspace=None):
+    """A whole LiSA layer from the hidden states x [B,L,d]: projection front end (see
+    lisa_project_qkv) then lisa_attn_prefill.  Returns (out, scores_out or None, (q_lr, k_lr, v)),
+    the last being views of the workspace."""
+    B, L, D = x.shape
+    H = scores_prev.shape[1]
+    Din, F = w1.shape
+    dt = x.dtype
+    sdt = score_dtype(dt)
+    odt, of32 = _out_dtype(dt, out.dtype if out is not None else out_dtype)
+    desc = make_desc(dt, B, H, Hkv, L, L, d_k, r, F, mix=mix, causal=int(causal),
+                     write_scores=int(write_scores), out_f32=of32)
+    if out is None:
+        out = torch.empty((B, L, H, d_k), dtype=odt, device=x.device)
+    if write_scores and scores_out is None:
+        scores_out = torch.empty((B, H, L, L), dtype=sdt, device=x.device)
+    need = workspace_bytes(desc, WS_LAYER)
+    if need == 0:
+        raise LisaError(supported(desc) or -2, "lisa_layer_prefill")
+    workspace, wp, wb = _workspace(need, x, workspace)
+    rc = _lib().lisa_layer_prefill(
+        C.byref(desc), D, float(rope_theta or 0.0), _ptr(x, "x", dtype=dt),
+        _ptr(w_qkv, "w_qkv", ((H + Hkv) * r + Hkv * d_k, D), dt),
+        _ptr(scores_prev, "scores_prev", (B, H, L, L), sdt), _ptr(w1, "w1", dtype=dt),
+        _ptr(w2, "w2", (F, H), dt), _ptr(out, "out", (B, L, H, d_k), odt),
+        _ptr(scores_out if write_scores else None, "scores_out", (B, H, L, L), sdt), wp, wb, _stream())
+    if rc:
+        raise LisaError(rc, "lisa_layer_prefill")
+    offs = [C.c_size_t() for _ in range(3)]
+    _lib().lisa_layer_offsets(C.byref(desc), *[C.byref(o) for o in offs])
+    es = x.element_size()
+
+    def view(off, shape):
+        n = 1
+        for d in shape:
+            n *= d
+        return workspace[off.value:off.value + n * es].view(dt).view(shape)
+
+    qkv = (view(offs[0], (B, H, L, r)), view(offs[1], (B, Hkv, L, r)), view(offs[2], (B, Hkv, L, d_k)))
+    return out, (scores_out if write_scores else None), qkv
 
 
 def lisa_attn_decode(q_lr, k_lr_cache, v_cache, Lk, score_row_prev, w1, w2, *, k_lr_new=None,

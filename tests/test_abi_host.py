@@ -137,6 +137,25 @@ def test_project_qkv_rejects_bad_arguments():
     assert call(desc(), ODD) == -4
 
 
+def test_layer_prefill_workspace_and_argument_checks():
+    lib = lisa.library()
+    d = lisa.make_desc(lisa.BF16, 2, 32, 8, 256, 256, 128, 22, 64, write_scores=1)
+    sz = C.c_size_t
+    q, k, v = sz(), sz(), sz()
+    assert lib.lisa_layer_offsets(C.byref(d), C.byref(q), C.byref(k), C.byref(v)) == 0
+    pre = lisa.workspace_bytes(d, lisa.WS_PREFILL)
+    assert q.value >= pre and q.value % 256 == 0
+    assert k.value - q.value >= 2 * 32 * 256 * 22 * 2 and v.value - k.value >= 2 * 8 * 256 * 22 * 2
+    total = lisa.workspace_bytes(d, lisa.WS_LAYER)
+    assert total >= v.value + 2 * 8 * 256 * 128 * 2
+    args = [FAKE] * 7
+    assert lib.lisa_layer_prefill(C.byref(d), 4096, 1.0e4, *args, FAKE, total - 1, None) == -5
+    assert lib.lisa_layer_prefill(C.byref(d), 4096, 1.0e4, None, *args[1:], FAKE, total, None) == -1
+    chunk = lisa.make_desc(lisa.BF16, 2, 32, 8, 128, 256, 128, 22, 64)        # Lq != Lk
+    assert lib.lisa_layer_prefill(C.byref(chunk), 4096, 1.0e4, *args, FAKE, 1 << 40, None) == -2
+    assert lisa.workspace_bytes(chunk, lisa.WS_LAYER) == 0
+
+
 def test_strerror_is_defined_for_every_status():
     lib = lisa.library()
     seen = set()

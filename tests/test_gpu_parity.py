@@ -648,3 +648,45 @@ def test_projection_full_size_sampled_rows(name):
                  for b in (0, cfg.B - 1)}
     path = check_projection(cfg, pin, rows_by_b, theta, 0, False, cfg.L, tag=" full size")
     assert path == "project_mfma"
+
+
+LAYER_CASES = [
+    # name, dtype, B, H, Hkv, L, d_model, d_k, r, F, theta
+    ("layer_f32", "f32", 2, 8, 8, 96, 128, 64, 12, 32, 10000.0),
+    ("layer_bf16_gqa", "bf16", 2, 32, 8, 200, 256, 128, 22, 64, 500000.0),
+    ("layer_bf16_mha", "bf16", 1, 32, 32, 333, 512, 128, 22, 64, None),
+]
+
+
+@pytest.mark.parametrize("case", LAYER_CASES, ids=lambda c: c[0])
+def test_layer_prefill_from_hidden_states(case):
+    """lisa_layer_prefill against the oracle chain: oracle projection (float64), rounded once to
+    the dtype as the boundary between the two stages prescribes, then the oracle LiSA layer."""
+    name, dtype, B, H, Hkv, L, D, dk, r, F, theta = case
+    log(f"[case] layer prefill {case}")
+    cfg = synth.LayerShape(name, dtype, B, H, Hkv, L, D, dk, r, F, theta)
+    dt = cfg.torch_dtype
+    pin = synth.make_projection_inputs(cfg, device=DEV)
+    aux = synth.make_prefill_inputs(cfg, device=DEV)          # w1, w2 and the standard layer's q, k
+    prev = std_prev(aux)
+    out, a_n, (q_lr, k_lr, v) = lisa.lisa_layer_prefill(pin["x"], pin["w"], Hkv, r, dk, prev, aux["w1"],
+                                                        aux["w2"], rope_theta=theta)
+    torch.cuda.synchronize()
+    tol = hp.TOL[dt]
+    rows = np.arange(L)
+    worst_o = worst_a = 0.0
+    for b in range(B):
+        q_ref, k_ref, v_ref = hp.oracle_project_rows(pin["x"], pin["w"], b, rows, H, Hkv, r, dk, theta, 0)
+        rounded = {
+            "q_lr": torch.from_numpy(q_ref).to(dt).permute(1, 0, 2)[None],
+            "k_lr": torch.from_numpy(k_ref).to(dt).permute(1, 0, 2)[None],
+            "v": torch.from_numpy(v_ref).to(dt).permute(1, 0, 2)[None],
+            "w1": aux["w1"], "w2": aux["w2"],
+        }
+        prev_rows = hp.gather_score_rows(prev, b, rows)
+        a_ref, o_ref = hp.oracle_lisa_rows(rounded, 0, rows, prev_rows)
+        worst_o = max(worst_o, hp.row_rel_err(hp.gather_out_rows(out, b, rows), o_ref))
+        worst_a = max(worst_a, hp.scores_row_rel_err(hp.gather_score_rows(a_n, b, rows), a_ref, rows, L, L))
+    log(f"[parity] {name}: path={lisa.last_path()} err_out={worst_o:.3e} err_scores={worst_a:.3e} tol={tol:g}")
+    assert worst_o <= tol and worst_a <= tol
+    assert q_lr.shape == (B, H, L, r) and k_lr.shape == (B, Hkv, L, r) and v.shape == (B, Hkv, L, dk)
