@@ -11,6 +11,11 @@ from . import build as _build
 
 MIX_ADD = 0
 MIX_CONCAT = 1
+MIX_PLUS = 2
+MIX_SHARE = 3
+ACT_RELU = 0
+ACT_SILU = 1
+ACT_SINGLE = 2
 
 _lib = None
 
@@ -75,35 +80,48 @@ def softmax_v_rows(v, rows, scores_rows, Lq, want_probs=False):
 
 
 def lisa_rows(q_lr, k_lr, v, w1, w2, rows, prev_rows, mix=MIX_ADD, delta_scale=None,
-              want_probs=False):
+              want_probs=False, act=ACT_RELU, Lq=None):
     """One LiSA layer for the requested query rows.
 
     Returns (scores [n,H,Lk], out [n,H,dk]) and P [n,H,Lk] when ``want_probs``.
+    ``w1`` / ``w2`` may be None for the variants without an FFN (MIX_PLUS, MIX_SHARE), ``w2``
+    for ACT_SINGLE, ``q_lr`` / ``k_lr`` for MIX_SHARE (then pass ``Lq``).
     """
-    q_lr, qp = _d(q_lr)
-    k_lr, kp = _d(k_lr)
     v, vp = _d(v)
-    w1, w1p = _d(w1)
-    w2, w2p = _d(w2)
     prev, pp = _d(prev_rows)
-    H, Lq, r = q_lr.shape
-    Hkv, Lk, r2 = k_lr.shape
-    assert r == r2 and v.shape[:2] == (Hkv, Lk)
-    dk = v.shape[2]
-    Din, F = w1.shape
-    assert w2.shape == (F, H)
-    assert Din == (2 * H if mix == MIX_CONCAT else H)
+    Hkv, Lk, dk = v.shape
     rows, rp = _rows(rows)
     n = len(rows)
+    H = prev.shape[1]
     assert prev.shape == (n, H, Lk)
+    has_ffn = mix in (MIX_ADD, MIX_CONCAT)
+    null = C.POINTER(C.c_double)()
+    if q_lr is not None:
+        q_lr, qp = _d(q_lr)
+        k_lr, kp = _d(k_lr)
+        assert q_lr.shape[0] == H and k_lr.shape[:2] == (Hkv, Lk) and q_lr.shape[2] == k_lr.shape[2]
+        Lq, r = q_lr.shape[1], q_lr.shape[2]
+    else:
+        assert mix == MIX_SHARE and Lq is not None
+        qp = kp = null
+        r = 0
+    F = 0
+    w1p = w2p = null
+    if has_ffn:
+        w1, w1p = _d(w1)
+        Din, F = w1.shape
+        assert Din == (2 * H if mix == MIX_CONCAT else H)
+        if act != ACT_SINGLE:
+            w2, w2p = _d(w2)
+            assert w2.shape == (F, H)
     if delta_scale is None:
-        delta_scale = 1.0 / np.sqrt(r)
+        delta_scale = 1.0 / np.sqrt(r) if r > 0 else 0.0
     scores = np.empty((n, H, Lk), dtype=np.float64)
     out = np.empty((n, H, dk), dtype=np.float64)
     probs = np.empty((n, H, Lk), dtype=np.float64) if want_probs else None
     prp = probs.ctypes.data_as(C.POINTER(C.c_double)) if want_probs else None
-    rc = lib().lisa_oracle_lisa_rows(H, Hkv, Lq, Lk, dk, r, F, int(mix), C.c_double(delta_scale),
-                                     qp, kp, vp, w1p, w2p, n, rp, pp,
+    rc = lib().lisa_oracle_lisa_rows(H, Hkv, Lq, Lk, dk, r, F, int(mix), int(act),
+                                     C.c_double(delta_scale), qp, kp, vp, w1p, w2p, n, rp, pp,
                                      scores.ctypes.data_as(C.POINTER(C.c_double)), prp,
                                      out.ctypes.data_as(C.POINTER(C.c_double)))
     if rc:

@@ -29,7 +29,9 @@
  * library softmax/matmul; A_delta equals a brute-force triple loop; r = d_k reduces
  * Eq. 3 to Eq. 2; the h = 3 head permutation of Sec. 5.1; uniform and one-hot score
  * closed forms; GQA equals MHA with repeated K/V; prefill row L-1 equals decode; a
- * hand-evaluated 2-head example.  Projection front end: without rotation it equals a library
+ * hand-evaluated 2-head example.  Variants: SiLU against a library sigmoid, the single-layer
+ * FFN against a library matmul, LiSA_plus = A_{n-1} + brute-force A_delta, direct sharing =
+ * textbook attention on A_{n-1}.  Projection front end: without rotation it equals a library
  * matrix product; unit-vector inputs give (cos, sin) closed forms that fix the pairing, the
  * sign and the frequency exponent; rotated dot products depend on the position difference only.
  */
@@ -39,6 +41,11 @@
 
 #define LISA_ORACLE_MIX_ADD 0
 #define LISA_ORACLE_MIX_CONCAT 1
+#define LISA_ORACLE_MIX_PLUS 2  /* Sec. 6.3, LiSA_plus: A_n = A_{n-1} + A_delta, no FFN          */
+#define LISA_ORACLE_MIX_SHARE 3 /* Sec. 4, directly sharing (DS): A_n = A_{n-1}                   */
+#define LISA_ORACLE_ACT_RELU 0
+#define LISA_ORACLE_ACT_SILU 1   /* Sec. 6.5, "DL + SiLU": x * sigmoid(x)                          */
+#define LISA_ORACLE_ACT_SINGLE 2 /* Sec. 6.5, "SL": one layer, A_align = W1^T x with W1 [Din][H]  */
 
 static int n_visible(int i, int Lq, int Lk) {
   int n = i + 1 + (Lk - Lq);
@@ -112,16 +119,24 @@ int lisa_oracle_softmax_v_rows(int H, int Hkv, int Lq, int Lk, int dk, const dou
 /* Sec. 5.1: for every visible position (i,j)
  *   a_delta[h] = delta_scale * <Q_LR[h,i,:], K_LR[kv(h),j,:]>                    (Eq. 3)
  *   x = A_{n-1}[:,i,j]                      (ADD)    or [A_{n-1}[:,i,j] ; a_delta] (CONCAT)
- *   hid = ReLU(W1^T x),  y = W2^T hid       (two-layer FFN over the head axis)
+ *   hid = act(W1^T x),  y = W2^T hid        (two-layer FFN over the head axis; act = ReLU or
+ *                                            SiLU)   or   y = W1^T x  (SINGLE, W1 [Din][H])
  *   A_n[:,i,j] = y + a_delta                (ADD, Eq. 4 by addition)  or  y     (CONCAT)
+ * and the two variants without an FFN: A_n = A_{n-1} + a_delta (PLUS), A_n = A_{n-1} (SHARE).
  * scores_rows receives A_n for the requested rows ([n_rows][H][Lk]).  */
-int lisa_oracle_lisa_scores_rows(int H, int Hkv, int Lq, int Lk, int r, int F, int mix,
+int lisa_oracle_lisa_scores_rows(int H, int Hkv, int Lq, int Lk, int r, int F, int mix, int act,
                                  double delta_scale, const double* q_lr, const double* k_lr,
                                  const double* w1, const double* w2, int n_rows,
                                  const int* rows, const double* prev_rows,
                                  double* scores_rows) {
-  if (H <= 0 || Hkv <= 0 || H % Hkv != 0 || Lq <= 0 || Lk < Lq || r <= 0 || F <= 0) return -1;
-  if (mix != LISA_ORACLE_MIX_ADD && mix != LISA_ORACLE_MIX_CONCAT) return -1;
+  if (H <= 0 || Hkv <= 0 || H % Hkv != 0 || Lq <= 0 || Lk < Lq) return -1;
+  if (mix < LISA_ORACLE_MIX_ADD || mix > LISA_ORACLE_MIX_SHARE) return -1;
+  if (act < LISA_ORACLE_ACT_RELU || act > LISA_ORACLE_ACT_SINGLE) return -1;
+  const int has_ffn = mix == LISA_ORACLE_MIX_ADD || mix == LISA_ORACLE_MIX_CONCAT;
+  const int has_delta = mix != LISA_ORACLE_MIX_SHARE;
+  const int single = act == LISA_ORACLE_ACT_SINGLE;
+  if (has_delta && r <= 0) return -1;
+  if (has_ffn && (single ? F != H : F <= 0)) return -1;
   const int group = H / Hkv;
   const int Din = (mix == LISA_ORACLE_MIX_CONCAT) ? 2 * H : H;
 #pragma omp parallel for schedule(dynamic, 1)
@@ -130,7 +145,7 @@ int lisa_oracle_lisa_scores_rows(int H, int Hkv, int Lq, int Lk, int r, int F, i
     const int nv = n_visible(i, Lq, Lk);
     double* ad = (double*)malloc(sizeof(double) * (size_t)H);
     double* x = (double*)malloc(sizeof(double) * (size_t)Din);
-    double* hid = (double*)malloc(sizeof(double) * (size_t)F);
+    double* hid = (double*)malloc(sizeof(double) * (size_t)(F > 0 ? F : 1));
     for (int j = 0; j < Lk; ++j) {
       if (j >= nv) {
         for (int h = 0; h < H; ++h) scores_rows[((size_t)n * H + h) * Lk + j] = 0.0;
@@ -139,21 +154,34 @@ int lisa_oracle_lisa_scores_rows(int H, int Hkv, int Lq, int Lk, int r, int F, i
       for (int h = 0; h < H; ++h) {
         const int kv = h / group;
         double acc = 0.0;
-        for (int t = 0; t < r; ++t)
-          acc += q_lr[((size_t)h * Lq + i) * r + t] * k_lr[((size_t)kv * Lk + j) * r + t];
+        if (has_delta)
+          for (int t = 0; t < r; ++t)
+            acc += q_lr[((size_t)h * Lq + i) * r + t] * k_lr[((size_t)kv * Lk + j) * r + t];
         ad[h] = delta_scale * acc;
       }
       for (int h = 0; h < H; ++h) x[h] = prev_rows[((size_t)n * H + h) * Lk + j];
+      if (!has_ffn) {
+        for (int h = 0; h < H; ++h) scores_rows[((size_t)n * H + h) * Lk + j] = x[h] + ad[h];
+        continue;
+      }
       if (mix == LISA_ORACLE_MIX_CONCAT)
         for (int h = 0; h < H; ++h) x[H + h] = ad[h];
       for (int f = 0; f < F; ++f) {
         double acc = 0.0;
         for (int c = 0; c < Din; ++c) acc += x[c] * w1[(size_t)c * F + f];
-        hid[f] = acc > 0.0 ? acc : 0.0;
+        if (act == LISA_ORACLE_ACT_RELU)
+          hid[f] = acc > 0.0 ? acc : 0.0;
+        else if (act == LISA_ORACLE_ACT_SILU)
+          hid[f] = acc / (1.0 + exp(-acc));
+        else
+          hid[f] = acc;
       }
       for (int h = 0; h < H; ++h) {
         double acc = 0.0;
-        for (int f = 0; f < F; ++f) acc += hid[f] * w2[(size_t)f * H + h];
+        if (single)
+          acc = hid[h];
+        else
+          for (int f = 0; f < F; ++f) acc += hid[f] * w2[(size_t)f * H + h];
         scores_rows[((size_t)n * H + h) * Lk + j] =
             (mix == LISA_ORACLE_MIX_ADD) ? acc + ad[h] : acc;
       }
@@ -166,12 +194,12 @@ int lisa_oracle_lisa_scores_rows(int H, int Hkv, int Lq, int Lk, int r, int F, i
 }
 
 /* The whole LiSA layer for the requested rows: scores (above), then Eq. 1-2. */
-int lisa_oracle_lisa_rows(int H, int Hkv, int Lq, int Lk, int dk, int r, int F, int mix,
+int lisa_oracle_lisa_rows(int H, int Hkv, int Lq, int Lk, int dk, int r, int F, int mix, int act,
                           double delta_scale, const double* q_lr, const double* k_lr,
                           const double* v, const double* w1, const double* w2, int n_rows,
                           const int* rows, const double* prev_rows, double* scores_rows,
                           double* probs_rows, double* out_rows) {
-  int rc = lisa_oracle_lisa_scores_rows(H, Hkv, Lq, Lk, r, F, mix, delta_scale, q_lr, k_lr,
+  int rc = lisa_oracle_lisa_scores_rows(H, Hkv, Lq, Lk, r, F, mix, act, delta_scale, q_lr, k_lr,
                                         w1, w2, n_rows, rows, prev_rows, scores_rows);
   if (rc) return rc;
   return lisa_oracle_softmax_v_rows(H, Hkv, Lq, Lk, dk, v, n_rows, rows, scores_rows,

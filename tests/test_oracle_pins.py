@@ -523,3 +523,112 @@ def test_projection_rows_are_independent_of_the_request_set():
     np.testing.assert_array_equal(vs, va[[7, 1]])
     with pytest.raises(ValueError):
         cref.project_rows(x[:, :15], np.zeros((3 + 3 + dk, 15)), [0], 1, 1, 3, dk, theta=1.0e4)
+
+
+# --------------------------------------------------------------------------------------
+# 10. Variants of the alignment module: SiLU and the single-layer FFN (Sec. 6.5), LiSA_plus
+#     (Sec. 6.3: A_{n-1} + A_delta) and direct sharing (Sec. 4: A_n = A_{n-1}).
+# --------------------------------------------------------------------------------------
+def variant_problem(seed, H=4, Hkv=2, L=6, r=3, dk=5, F=7):
+    g = rng(seed)
+    q_lr = g.standard_normal((H, L, r))
+    k_lr = g.standard_normal((Hkv, L, r))
+    v = g.standard_normal((Hkv, L, dk))
+    prev = g.standard_normal((L, H, L))                   # rows layout [n,H,Lk]
+    return g, q_lr, k_lr, v, prev, H, Hkv, L, r, dk, F
+
+
+def brute_a_delta(q_lr, k_lr, H, Hkv, L, r):
+    ad = np.zeros((L, H, L))
+    for i in range(L):
+        for h in range(H):
+            for j in range(L):
+                ad[i, h, j] = sum(q_lr[h, i, t] * k_lr[h // (H // Hkv), j, t] for t in range(r)) / math.sqrt(r)
+    return ad
+
+
+def causal_mask(L):
+    return np.tril(np.ones((L, L), dtype=bool))[:, None, :]     # [i,1,j]
+
+
+@pytest.mark.parametrize("mix", [cref.MIX_ADD, cref.MIX_CONCAT])
+def test_silu_ffn_matches_library_sigmoid(mix):
+    g, q_lr, k_lr, v, prev, H, Hkv, L, r, dk, F = variant_problem(100)
+    Din = 2 * H if mix == cref.MIX_CONCAT else H
+    w1, w2 = g.standard_normal((Din, F)), g.standard_normal((F, H))
+    a_n, _ = cref.lisa_rows(q_lr, k_lr, v, w1, w2, all_rows(L), prev, mix=mix, act=cref.ACT_SILU)
+    ad = brute_a_delta(q_lr, k_lr, H, Hkv, L, r)
+    x = np.moveaxis(prev, 1, -1)                                  # [i,j,h]
+    if mix == cref.MIX_CONCAT:
+        x = np.concatenate([x, np.moveaxis(ad, 1, -1)], axis=-1)
+    pre = x @ w1
+    y = (pre * scipy.special.expit(pre)) @ w2
+    want = np.moveaxis(y, -1, 1) + (ad if mix == cref.MIX_ADD else 0.0)
+    np.testing.assert_allclose(a_n, np.where(causal_mask(L), want, 0.0), rtol=1e-12, atol=1e-12)
+    # and it is not ReLU: a negative pre-activation leaks through
+    a_relu, _ = cref.lisa_rows(q_lr, k_lr, v, w1, w2, all_rows(L), prev, mix=mix, act=cref.ACT_RELU)
+    assert np.abs(a_relu - a_n).max() > 1e-2
+
+
+def test_silu_limits():
+    """One head, F = 1, unit weights: y = silu(x); silu(0) = 0, silu(40) = 40, silu(-40) = 0 to 1e-15."""
+    L = 3
+    prev = np.zeros((L, 1, L))
+    prev[0, 0, 0], prev[1, 0, 1], prev[2, 0, 2] = 0.0, 40.0, -40.0
+    z = np.zeros((1, L, 2))
+    a_n, _ = cref.lisa_rows(z, z, np.ones((1, L, 1)), np.ones((1, 1)), np.ones((1, 1)), all_rows(L), prev,
+                            act=cref.ACT_SILU)
+    assert a_n[0, 0, 0] == 0.0
+    assert abs(a_n[1, 0, 1] - 40.0) < 1e-12
+    assert abs(a_n[2, 0, 2]) < 1e-12
+
+
+@pytest.mark.parametrize("mix", [cref.MIX_ADD, cref.MIX_CONCAT])
+def test_single_layer_ffn_is_one_library_matmul(mix):
+    g, q_lr, k_lr, v, prev, H, Hkv, L, r, dk, _ = variant_problem(101)
+    Din = 2 * H if mix == cref.MIX_CONCAT else H
+    w1 = g.standard_normal((Din, H))
+    a_n, out = cref.lisa_rows(q_lr, k_lr, v, w1, None, all_rows(L), prev, mix=mix, act=cref.ACT_SINGLE)
+    ad = brute_a_delta(q_lr, k_lr, H, Hkv, L, r)
+    x = np.moveaxis(prev, 1, -1)
+    if mix == cref.MIX_CONCAT:
+        x = np.concatenate([x, np.moveaxis(ad, 1, -1)], axis=-1)
+    want = np.moveaxis(x @ w1, -1, 1) + (ad if mix == cref.MIX_ADD else 0.0)
+    np.testing.assert_allclose(a_n, np.where(causal_mask(L), want, 0.0), rtol=1e-12, atol=1e-12)
+    # a two-layer FFN with an identity second layer and no activation clipping is the same map:
+    # with the [I,-I] / [I;-I] trick the ReLU network reproduces it exactly
+    w1r = np.concatenate([w1, -w1], axis=1)
+    w2r = np.concatenate([np.eye(H), -np.eye(H)], axis=0)
+    a_two, out_two = cref.lisa_rows(q_lr, k_lr, v, w1r, w2r, all_rows(L), prev, mix=mix)
+    np.testing.assert_allclose(a_n, a_two, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(out, out_two, rtol=1e-12, atol=1e-12)
+    with pytest.raises(ValueError):                                # W1 must be [Din, H]
+        cref.lisa_rows(q_lr, k_lr, v, g.standard_normal((Din, H + 1)), None, all_rows(L), prev, mix=mix,
+                       act=cref.ACT_SINGLE)
+
+
+def test_plus_variant_adds_the_brute_force_correction():
+    g, q_lr, k_lr, v, prev, H, Hkv, L, r, dk, _ = variant_problem(102)
+    a_n, out = cref.lisa_rows(q_lr, k_lr, v, None, None, all_rows(L), prev, mix=cref.MIX_PLUS)
+    want = prev + brute_a_delta(q_lr, k_lr, H, Hkv, L, r)
+    np.testing.assert_allclose(a_n, np.where(causal_mask(L), want, 0.0), rtol=1e-12, atol=1e-12)
+    # equals the ADD layer whose FFN is the identity
+    w1, w2 = identity_ffn(H, 2 * H)
+    a_add, out_add = cref.lisa_rows(q_lr, k_lr, v, w1, w2, all_rows(L), prev)
+    np.testing.assert_allclose(a_n, a_add, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(out, out_add, rtol=1e-12, atol=1e-12)
+
+
+def test_direct_sharing_is_textbook_attention_on_the_previous_scores():
+    g, q_lr, k_lr, v, prev, H, Hkv, L, r, dk, _ = variant_problem(103)
+    a_n, out = cref.lisa_rows(None, None, v, None, None, all_rows(L), prev, mix=cref.MIX_SHARE, Lq=L)
+    np.testing.assert_array_equal(a_n, np.where(causal_mask(L), prev, 0.0))
+    masked = np.where(causal_mask(L), prev, -np.inf)
+    p = scipy.special.softmax(masked, axis=-1)                     # [i,h,j]
+    vv = np.repeat(v, H // Hkv, axis=0)                            # [h,j,d]
+    want = np.einsum("ihj,hjd->ihd", p, vv)
+    np.testing.assert_allclose(out, want, rtol=1e-12, atol=1e-12)
+    # passing Q_LR / K_LR changes nothing
+    a2, out2 = cref.lisa_rows(q_lr, k_lr, v, None, None, all_rows(L), prev, mix=cref.MIX_SHARE)
+    np.testing.assert_array_equal(a2, a_n)
+    np.testing.assert_array_equal(out2, out)
