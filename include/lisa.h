@@ -49,10 +49,18 @@ typedef enum { LISA_F32 = 0, LISA_BF16 = 1 } lisa_dtype;
  *                        CONCAT: A_n = FFN([A_{n-1} ; A_delta]), Din = 2H, rows 0..H-1 of W1
  *                                act on A_{n-1} and rows H..2H-1 on A_delta (Sec. 5.1,
  *                                "An overview of LiSA"). */
-typedef enum { LISA_MIX_ADD = 0, LISA_MIX_CONCAT = 1 } lisa_mix;
+/*                        Two variants without the alignment FFN (w1, w2, F are ignored):
+ *                        PLUS:   A_n = A_{n-1} + A_delta (LiSA_plus for models pre-trained with
+ *                                shared attention, Sec. 6.3);
+ *                        SHARE:  A_n = A_{n-1}, the direct sharing the method starts from (DS,
+ *                                Sec. 4; q_lr, k_lr, r are ignored as well).
+ * The MFMA kernels implement ADD with ReLU; every other variant runs on the generic kernels. */
+typedef enum { LISA_MIX_ADD = 0, LISA_MIX_CONCAT = 1, LISA_MIX_PLUS = 2, LISA_MIX_SHARE = 3 } lisa_mix;
 
-/* Activation between the two FFN layers (Sec. 6.1 "Model configuration": ReLU). */
-typedef enum { LISA_ACT_RELU = 0 } lisa_act;
+/* The alignment FFN (Sec. 6.1 "Model configuration": two layers with ReLU; Sec. 6.5 ablates
+ * SiLU, x * sigmoid(x), and a single layer).  SINGLE: A_align = W1^T x with W1 [Din,H]; F must
+ * equal H and w2 is ignored. */
+typedef enum { LISA_ACT_RELU = 0, LISA_ACT_SILU = 1, LISA_ACT_SINGLE = 2 } lisa_act;
 
 typedef enum {
   LISA_OK = 0,
@@ -95,7 +103,8 @@ typedef struct lisa_desc {
  *   k_lr        [B,Hkv,Lk,r]   in   low-rank keys     H W^K_LR
  *   v           [B,Hkv,Lk,d_k] in   values
  *   scores_prev [B,H,Lq,Lk]    in   A_{n-1}, score type
- *   w1 [Din,F], w2 [F,H]       in   FFN weights (no bias), dtype
+ *   w1 [Din,F], w2 [F,H]       in   FFN weights (no bias), dtype; NULL where the variant
+ *                                   (lisa_mix, lisa_act) does not use them
  *   out         [B,Lq,H,d_k]   out  concatenated heads softmax(A_n) V, dtype
  *   scores_out  [B,H,Lq,Lk]    out  A_n, score type; required iff write_scores = 1; must not
  *                                   alias scores_prev

@@ -83,6 +83,9 @@ __global__ __launch_bounds__(256) void k_std_scores(const T* __restrict__ q, con
 // (score type, may be null) and, unrounded, to `exact` (float32, may be null).  Four waves; wave s takes
 // heads / hidden units s, s+4, ...  Dynamic LDS: x[Din][64], hid[F][64], a_delta[H][64].
 // grid (ceil(Lk/64), Lq, B), block 256.
+// `mix`: 0 A_n = FFN(A_{n-1}) + A_delta, 1 A_n = FFN([A_{n-1}; A_delta]) (Sec. 5.1, Eq. 4),
+// 2 A_n = A_{n-1} + A_delta (LiSA_plus, Sec. 6.3), 3 A_n = A_{n-1} (direct sharing, Sec. 4).
+// `act`: 0 ReLU, 1 SiLU, 2 single layer y = W1^T x with F = H (Sec. 6.5).
 // ---------------------------------------------------------------------------------------
 template <typename T, typename S>
 __global__ __launch_bounds__(256) void k_lisa_scores(const T* __restrict__ q_lr,
@@ -92,9 +95,10 @@ __global__ __launch_bounds__(256) void k_lisa_scores(const T* __restrict__ q_lr,
                                                      const T* __restrict__ w2,
                                                      S* __restrict__ scores,
                                                      float* __restrict__ exact, int H, int Hkv,
-                                                     int Lq, int Lk, int r, int F, int concat,
+                                                     int Lq, int Lk, int r, int F, int mix, int act,
                                                      float dscale, int causal) {
   extern __shared__ float sm[];
+  const bool concat = mix == 1, has_ffn = mix <= 1, has_delta = mix != 3;
   const int Din = concat ? 2 * H : H;
   float* xs = sm;
   float* hs = xs + Din * 64;
@@ -109,26 +113,41 @@ __global__ __launch_bounds__(256) void k_lisa_scores(const T* __restrict__ q_lr,
   for (int h = sl; h < H; h += 4) {
     float acc = 0.f, x = 0.f;
     if (live) {
-      const T* qp = q_lr + ((size_t)(b * H + h) * Lq + i) * r;
-      const T* kp = k_lr + b * ks.b + (h / group) * ks.h + j * ks.j;
-      for (int t = 0; t < r; ++t) acc += elem<T>::load(qp + t) * elem<T>::load(kp + t * ks.t);
+      if (has_delta) {
+        const T* qp = q_lr + ((size_t)(b * H + h) * Lq + i) * r;
+        const T* kp = k_lr + b * ks.b + (h / group) * ks.h + j * ks.j;
+        for (int t = 0; t < r; ++t) acc += elem<T>::load(qp + t) * elem<T>::load(kp + t * ks.t);
+      }
       x = elem<S>::load(prev + ((size_t)(b * H + h) * Lq + i) * Lk + j);
     }
     acc *= dscale;
+    if (!has_ffn) {                                        // no alignment module: done with this head
+      if (live) {
+        const size_t at = ((size_t)(b * H + h) * Lq + i) * Lk + j;
+        if (scores) elem<S>::store(scores + at, x + acc);
+        if (exact) exact[at] = x + acc;
+      }
+      continue;
+    }
     ds[h * 64 + pj] = acc;
     xs[h * 64 + pj] = x;
     if (concat) xs[(H + h) * 64 + pj] = acc;
   }
+  if (!has_ffn) return;
   __syncthreads();
   for (int f = sl; f < F; f += 4) {
     float acc = 0.f;
     for (int c = 0; c < Din; ++c) acc += xs[c * 64 + pj] * elem<T>::load(w1 + (size_t)c * F + f);
-    hs[f * 64 + pj] = fmaxf(acc, 0.f);
+    hs[f * 64 + pj] = act == 0 ? fmaxf(acc, 0.f) : act == 1 ? acc / (1.f + expf(-acc)) : acc;
   }
   __syncthreads();
   for (int h = sl; h < H; h += 4) {
     float acc = 0.f;
-    for (int f = 0; f < F; ++f) acc += hs[f * 64 + pj] * elem<T>::load(w2 + (size_t)f * H + h);
+    if (act == 2) {
+      acc = hs[h * 64 + pj];
+    } else {
+      for (int f = 0; f < F; ++f) acc += hs[f * 64 + pj] * elem<T>::load(w2 + (size_t)f * H + h);
+    }
     if (!concat) acc += ds[h * 64 + pj];
     if (live) {
       const size_t at = ((size_t)(b * H + h) * Lq + i) * Lk + j;

@@ -31,6 +31,11 @@ constexpr int kMaxRank = 256;
 constexpr int kMaxFfnRows = 640;      // (Din + F + H) * 64 floats of LDS <= 160 KB
 constexpr int kMaxGridYZ = 65535;
 
+// Which operands a descriptor's variant uses (see lisa_mix / lisa_act).
+inline bool has_ffn(const lisa_desc* d) { return d->mix == LISA_MIX_ADD || d->mix == LISA_MIX_CONCAT; }
+inline bool has_w2(const lisa_desc* d) { return has_ffn(d) && d->act != LISA_ACT_SINGLE; }
+inline bool has_delta(const lisa_desc* d) { return d->mix != LISA_MIX_SHARE; }
+
 int check_common(const lisa_desc* d) {
   if (!d) return LISA_ERR_NULL;
   if (d->dtype != LISA_F32 && d->dtype != LISA_BF16) return LISA_ERR_UNSUPPORTED;
@@ -50,9 +55,11 @@ int check_common(const lisa_desc* d) {
 int check_lisa(const lisa_desc* d) {
   int rc = check_common(d);
   if (rc) return rc;
-  if (d->r <= 0 || d->F <= 0) return LISA_ERR_SHAPE;
-  if (d->mix != LISA_MIX_ADD && d->mix != LISA_MIX_CONCAT) return LISA_ERR_UNSUPPORTED;
-  if (d->act != LISA_ACT_RELU) return LISA_ERR_UNSUPPORTED;
+  if (d->mix < LISA_MIX_ADD || d->mix > LISA_MIX_SHARE) return LISA_ERR_UNSUPPORTED;
+  if (d->act < LISA_ACT_RELU || d->act > LISA_ACT_SINGLE) return LISA_ERR_UNSUPPORTED;
+  if (has_delta(d) && d->r <= 0) return LISA_ERR_SHAPE;
+  if (d->r < 0 || d->F < 0) return LISA_ERR_SHAPE;
+  if (has_ffn(d) && (d->act == LISA_ACT_SINGLE ? d->F != d->H : d->F <= 0)) return LISA_ERR_SHAPE;
   if (d->write_scores != 0 && d->write_scores != 1) return LISA_ERR_SHAPE;
   if (d->delta_scale < 0.f || !std::isfinite(d->delta_scale)) return LISA_ERR_SHAPE;
   if (d->r > kMaxRank) return LISA_ERR_UNSUPPORTED;
@@ -149,9 +156,8 @@ template <typename T, typename S>
 int launch_lisa_scores(const lisa_desc* d, const void* q_lr, const void* k_lr, KeyStrides ks,
                        const void* prev, const void* w1, const void* w2, void* scores,
                        float* exact, hipStream_t st) {
-  const int concat = d->mix == LISA_MIX_CONCAT;
-  const int Din = concat ? 2 * d->H : d->H;
-  const size_t lds = (size_t)(Din + d->F + d->H) * 64 * sizeof(float);
+  const int Din = d->mix == LISA_MIX_CONCAT ? 2 * d->H : d->H;
+  const size_t lds = has_ffn(d) ? (size_t)(Din + d->F + d->H) * 64 * sizeof(float) : 0;
   auto kern = k_lisa_scores<T, S>;
   if (lds > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -162,7 +168,8 @@ int launch_lisa_scores(const lisa_desc* d, const void* q_lr, const void* k_lr, K
   StageScope prof("k_lisa_scores", st);
   kern<<<grid, 256, lds, st>>>((const T*)q_lr, (const T*)k_lr, ks, (const S*)prev, (const T*)w1,
                                (const T*)w2, (S*)scores, exact, d->H, d->Hkv, d->Lq, d->Lk, d->r, d->F,
-                               concat, pick_scale(d->delta_scale, d->r), d->causal);
+                               d->mix, d->act, has_delta(d) ? pick_scale(d->delta_scale, d->r) : 0.f,
+                               d->causal);
   return check_launch();
 }
 
@@ -668,7 +675,8 @@ int lisa_layer_prefill(const lisa_desc* desc, int32_t d_model, float rope_theta,
   size_t qo, ko, vo;
   int rc = lisa_layer_offsets(desc, &qo, &ko, &vo);
   if (rc) return rc;
-  if (!x || !w_qkv || !scores_prev || !w1 || !w2 || !out) return LISA_ERR_NULL;
+  if (!x || !w_qkv || !scores_prev || !out) return LISA_ERR_NULL;
+  if (!has_delta(desc)) return LISA_ERR_UNSUPPORTED;      // nothing to project for: use lisa_attn_prefill
   if (desc->write_scores && !scores_out) return LISA_ERR_NULL;
   if (!workspace || !aligned16(workspace)) return workspace ? LISA_ERR_ALIGN : LISA_ERR_WORKSPACE;
   if (workspace_bytes < lisa_workspace_bytes(desc, LISA_WS_LAYER)) return LISA_ERR_WORKSPACE;
@@ -752,7 +760,9 @@ int lisa_attn_prefill(const lisa_desc* desc, const void* q_lr, const void* k_lr,
                       void* hip_stream) {
   int rc = check_lisa(desc);
   if (rc) return rc;
-  if (!q_lr || !k_lr || !v || !scores_prev || !w1 || !w2 || !out) return LISA_ERR_NULL;
+  if (!v || !scores_prev || !out) return LISA_ERR_NULL;
+  if (has_delta(desc) && (!q_lr || !k_lr)) return LISA_ERR_NULL;
+  if ((has_ffn(desc) && !w1) || (has_w2(desc) && !w2)) return LISA_ERR_NULL;
   if (desc->write_scores && !scores_out) return LISA_ERR_NULL;
   if (desc->write_scores && scores_out == scores_prev) return LISA_ERR_SHAPE;
   const void* ptrs[] = {q_lr, k_lr, v, scores_prev, w1, w2, out, scores_out, workspace};
@@ -781,9 +791,11 @@ int lisa_attn_decode(const lisa_desc* desc, const void* q_lr, const void* k_lr_n
                      void* hip_stream) {
   int rc = check_decode(desc);
   if (rc) return rc;
-  if (!q_lr || !k_lr_cache || !v_cache || !score_row_prev || !w1 || !w2 || !out)
-    return LISA_ERR_NULL;
+  if (!v_cache || !score_row_prev || !out) return LISA_ERR_NULL;
+  if (has_delta(desc) && (!q_lr || !k_lr_cache)) return LISA_ERR_NULL;
+  if ((has_ffn(desc) && !w1) || (has_w2(desc) && !w2)) return LISA_ERR_NULL;
   if ((k_lr_new == nullptr) != (v_new == nullptr)) return LISA_ERR_NULL;
+  if (k_lr_new && !k_lr_cache) return LISA_ERR_NULL;
   if (desc->write_scores && !score_row_out) return LISA_ERR_NULL;
   if (desc->write_scores && score_row_out == score_row_prev) return LISA_ERR_SHAPE;
   const void* ptrs[] = {q_lr, k_lr_new, v_new, k_lr_cache, v_cache, score_row_prev,

@@ -18,8 +18,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblisa_mi355x.so")
 
 F32, BF16 = 0, 1
-MIX_ADD, MIX_CONCAT = 0, 1
-ACT_RELU = 0
+MIX_ADD, MIX_CONCAT, MIX_PLUS, MIX_SHARE = 0, 1, 2, 3
+ACT_RELU, ACT_SILU, ACT_SINGLE = 0, 1, 2
 WS_PREFILL, WS_DECODE, WS_STD, WS_LAYER = 0, 1, 2, 3
 
 EXPORTS = (
@@ -249,32 +249,39 @@ def std_attn_decode(q, k_cache, v_cache, Lk, *, want_scores=True, std_scale=0.0,
     return score_row_out, out
 
 
-def lisa_attn_prefill(q_lr, k_lr, v, scores_prev, w1, w2, *, mix=MIX_ADD, write_scores=True,
-                      causal=True, delta_scale=0.0, out=None, out_dtype=None, scores_out=None,
-                      workspace=None):
+def lisa_attn_prefill(q_lr, k_lr, v, scores_prev, w1, w2, *, mix=MIX_ADD, act=ACT_RELU,
+                      write_scores=True, causal=True, delta_scale=0.0, out=None, out_dtype=None,
+                      scores_out=None, workspace=None):
     """One LiSA layer.  q_lr [B,H,Lq,r], k_lr [B,Hkv,Lk,r], v [B,Hkv,Lk,d_k],
-    scores_prev [B,H,Lq,Lk] (score dtype), w1 [Din,F], w2 [F,H].
+    scores_prev [B,H,Lq,Lk] (score dtype), w1 [Din,F], w2 [F,H].  Operands a variant does not
+    use are None: w1, w2 for MIX_PLUS / MIX_SHARE, w2 for ACT_SINGLE, q_lr, k_lr for MIX_SHARE.
     Returns (out [B,Lq,H,d_k], scores_out [B,H,Lq,Lk] or None)."""
-    B, H, Lq, r = q_lr.shape
-    _, Hkv, Lk, dk = v.shape
-    Din, F = w1.shape
-    dt = q_lr.dtype
+    B, H, Lq, Lk = scores_prev.shape
+    _, Hkv, _, dk = v.shape
+    r = q_lr.shape[3] if q_lr is not None else 0
+    has_ffn = mix in (MIX_ADD, MIX_CONCAT)
+    Din, F = w1.shape if has_ffn else (0, 0)
+    dt = v.dtype
     sdt = score_dtype(dt)
     odt, of32 = _out_dtype(dt, out.dtype if out is not None else out_dtype)
-    desc = make_desc(dt, B, H, Hkv, Lq, Lk, dk, r, F, mix=mix, delta_scale=delta_scale,
+    desc = make_desc(dt, B, H, Hkv, Lq, Lk, dk, r, F, mix=mix, act=act, delta_scale=delta_scale,
                      causal=int(causal), write_scores=int(write_scores), out_f32=of32)
-    if Din != (2 * H if mix == MIX_CONCAT else H):
+    if has_ffn and Din != (2 * H if mix == MIX_CONCAT else H):
         raise ValueError(f"w1 has {Din} rows, expected {2 * H if mix == MIX_CONCAT else H}")
     if out is None:
-        out = torch.empty((B, Lq, H, dk), dtype=odt, device=q_lr.device)
+        out = torch.empty((B, Lq, H, dk), dtype=odt, device=v.device)
     if write_scores and scores_out is None:
-        scores_out = torch.empty((B, H, Lq, Lk), dtype=sdt, device=q_lr.device)
+        scores_out = torch.empty((B, H, Lq, Lk), dtype=sdt, device=v.device)
     need = workspace_bytes(desc, WS_PREFILL)
-    workspace, wp, wb = _workspace(need, q_lr, workspace)
+    if need == 0 and supported(desc) != 0:
+        raise LisaError(supported(desc), "lisa_attn_prefill")
+    workspace, wp, wb = _workspace(need, v, workspace)
     rc = _lib().lisa_attn_prefill(
-        C.byref(desc), _ptr(q_lr, "q_lr", dtype=dt), _ptr(k_lr, "k_lr", (B, Hkv, Lk, r), dt),
+        C.byref(desc), _ptr(q_lr, "q_lr", (B, H, Lq, r), dt), _ptr(k_lr, "k_lr", (B, Hkv, Lk, r), dt),
         _ptr(v, "v", (B, Hkv, Lk, dk), dt), _ptr(scores_prev, "scores_prev", (B, H, Lq, Lk), sdt),
-        _ptr(w1, "w1", (Din, F), dt), _ptr(w2, "w2", (F, H), dt), _ptr(out, "out", (B, Lq, H, dk), odt),
+        _ptr(w1 if has_ffn else None, "w1", (Din, F), dt),
+        _ptr(w2 if has_ffn and act != ACT_SINGLE else None, "w2", (F, H), dt),
+        _ptr(out, "out", (B, Lq, H, dk), odt),
         _ptr(scores_out if write_scores else None, "scores_out", (B, H, Lq, Lk), sdt), wp, wb,
         _stream())
     if rc:
@@ -374,27 +381,33 @@ def lisa_layer_prefill(x, w_qkv, Hkv, r, d_k, scores_prev, w1, w2, *, rope_theta
 
 
 def lisa_attn_decode(q_lr, k_lr_cache, v_cache, Lk, score_row_prev, w1, w2, *, k_lr_new=None,
-                     v_new=None, dim_major=True, mix=MIX_ADD, write_scores=True, delta_scale=0.0,
-                     out=None, out_dtype=None, score_row_out=None, workspace=None):
+                     v_new=None, dim_major=True, mix=MIX_ADD, act=ACT_RELU, write_scores=True,
+                     delta_scale=0.0, out=None, out_dtype=None, score_row_out=None, workspace=None):
     """One LiSA decode step.  q_lr [B,H,r]; k_lr_cache [B,Hkv,r,Lmax] (dim_major) or
     [B,Hkv,Lmax,r]; v_cache [B,Hkv,Lmax,d_k]; score_row_prev [B,H,Lk].
     Returns (out [B,H,d_k], score_row_out [B,H,Lk] or None)."""
-    B, H, r = q_lr.shape
+    B, H, _ = score_row_prev.shape
+    r = q_lr.shape[2] if q_lr is not None else 0
     _, Hkv, Lmax, dk = v_cache.shape
-    Din, F = w1.shape
-    dt = q_lr.dtype
+    has_ffn = mix in (MIX_ADD, MIX_CONCAT)
+    Din, F = w1.shape if has_ffn else (0, 0)
+    if not has_ffn:
+        w1 = w2 = None
+    elif act == ACT_SINGLE:
+        w2 = None
+    dt = v_cache.dtype
     sdt = score_dtype(dt)
     odt, of32 = _out_dtype(dt, out.dtype if out is not None else out_dtype)
-    desc = make_desc(dt, B, H, Hkv, 1, Lk, dk, r, F, mix=mix, delta_scale=delta_scale,
+    desc = make_desc(dt, B, H, Hkv, 1, Lk, dk, r, F, mix=mix, act=act, delta_scale=delta_scale,
                      write_scores=int(write_scores), kcache_dim_major=int(dim_major), Lmax=Lmax,
                      out_f32=of32)
     kshape = (B, Hkv, r, Lmax) if dim_major else (B, Hkv, Lmax, r)
     if out is None:
-        out = torch.empty((B, H, dk), dtype=odt, device=q_lr.device)
+        out = torch.empty((B, H, dk), dtype=odt, device=v_cache.device)
     if write_scores and score_row_out is None:
-        score_row_out = torch.empty((B, H, Lk), dtype=sdt, device=q_lr.device)
+        score_row_out = torch.empty((B, H, Lk), dtype=sdt, device=v_cache.device)
     need = workspace_bytes(desc, WS_DECODE)
-    workspace, wp, wb = _workspace(need, q_lr, workspace)
+    workspace, wp, wb = _workspace(need, v_cache, workspace)
     rc = _lib().lisa_attn_decode(
         C.byref(desc), _ptr(q_lr, "q_lr", dtype=dt), _ptr(k_lr_new, "k_lr_new", (B, Hkv, r), dt),
         _ptr(v_new, "v_new", (B, Hkv, dk), dt), _ptr(k_lr_cache, "k_lr_cache", kshape, dt),

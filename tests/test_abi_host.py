@@ -156,6 +156,25 @@ def test_layer_prefill_workspace_and_argument_checks():
     assert lisa.workspace_bytes(chunk, lisa.WS_LAYER) == 0
 
 
+def test_variant_descriptors_are_validated():
+    ok = lisa.make_desc(lisa.BF16, 1, 32, 32, 64, 64, 128, 22, 64, act=lisa.ACT_SILU)
+    assert lisa.supported(ok) == 0
+    assert lisa.supported(lisa.make_desc(lisa.BF16, 1, 32, 32, 64, 64, 128, 22, 32, act=lisa.ACT_SINGLE)) == 0
+    assert lisa.supported(lisa.make_desc(lisa.BF16, 1, 32, 32, 64, 64, 128, 22, 64, act=lisa.ACT_SINGLE)) == -2
+    assert lisa.supported(lisa.make_desc(lisa.BF16, 1, 32, 32, 64, 64, 128, 22, 0, mix=lisa.MIX_PLUS)) == 0
+    assert lisa.supported(lisa.make_desc(lisa.BF16, 1, 32, 32, 64, 64, 128, 0, 0, mix=lisa.MIX_PLUS)) == -2
+    assert lisa.supported(lisa.make_desc(lisa.BF16, 1, 32, 32, 64, 64, 128, 0, 0, mix=lisa.MIX_SHARE)) == 0
+    assert lisa.supported(lisa.make_desc(lisa.BF16, 1, 32, 32, 64, 64, 128, 22, 64, act=3)) == -3
+    assert lisa.supported(lisa.make_desc(lisa.BF16, 1, 32, 32, 64, 64, 128, 22, 64, mix=4)) == -3
+    lib = lisa.library()
+    plus = lisa.make_desc(lisa.BF16, 1, 32, 32, 64, 64, 128, 22, 0, mix=lisa.MIX_PLUS)
+    big = 1 << 40
+    # the FFN weights may be NULL for LiSA_plus, Q_LR / K_LR may not
+    assert lib.lisa_attn_prefill(C.byref(plus), None, FAKE, FAKE, FAKE, None, None, FAKE, None, FAKE, big, None) == -1
+    relu = lisa.make_desc(lisa.BF16, 1, 32, 32, 64, 64, 128, 22, 64)
+    assert lib.lisa_attn_prefill(C.byref(relu), FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, None, FAKE, big, None) == -1
+
+
 def test_strerror_is_defined_for_every_status():
     lib = lisa.library()
     seen = set()

@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import cref
 from paper_2408_01890_amd import lisa, synth
 from tests import helpers as hp
 
@@ -690,3 +691,85 @@ def test_layer_prefill_from_hidden_states(case):
     log(f"[parity] {name}: path={lisa.last_path()} err_out={worst_o:.3e} err_scores={worst_a:.3e} tol={tol:g}")
     assert worst_o <= tol and worst_a <= tol
     assert q_lr.shape == (B, H, L, r) and k_lr.shape == (B, Hkv, L, r) and v.shape == (B, Hkv, L, dk)
+
+
+# ---------------------------------------------------------------------------------------
+# variants of the alignment module (generic kernels)
+# ---------------------------------------------------------------------------------------
+VARIANTS = [
+    # id, mix, act
+    ("silu_add", lisa.MIX_ADD, lisa.ACT_SILU),
+    ("silu_concat", lisa.MIX_CONCAT, lisa.ACT_SILU),
+    ("single_add", lisa.MIX_ADD, lisa.ACT_SINGLE),
+    ("single_concat", lisa.MIX_CONCAT, lisa.ACT_SINGLE),
+    ("plus", lisa.MIX_PLUS, lisa.ACT_RELU),
+    ("share", lisa.MIX_SHARE, lisa.ACT_RELU),
+]
+
+
+def variant_weights(cfg, mix, act, g):
+    """FFN weights of a variant (fan-in scaled so that the FFN output is of the order of its input)."""
+    H = cfg.H
+    if mix in (lisa.MIX_PLUS, lisa.MIX_SHARE):
+        return None, None
+    Din = 2 * H if mix == lisa.MIX_CONCAT else H
+    F = H if act == lisa.ACT_SINGLE else cfg.F
+    w1 = (torch.randn((Din, F), generator=g, device=DEV) / Din ** 0.5).to(cfg.torch_dtype)
+    if act == lisa.ACT_SINGLE:
+        return w1, None
+    w2 = (torch.randn((F, H), generator=g, device=DEV) / F ** 0.5).to(cfg.torch_dtype)
+    return w1, w2
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("variant", VARIANTS, ids=lambda v: v[0])
+def test_lisa_prefill_and_decode_variants(variant, dtype):
+    name, mix, act = variant
+    log(f"[case] variant {name} {dtype}")
+    cfg = synth.LayerShape("variant_" + name, dtype, 2, 8, 4, 150, 128, 64, 12, 32, 10000.0)
+    dt = cfg.torch_dtype
+    tol = hp.TOL[dt]
+    inp = synth.make_prefill_inputs(cfg, device=DEV)
+    g = torch.Generator(device=DEV).manual_seed(7)
+    w1, w2 = variant_weights(cfg, mix, act, g)
+    prev = std_prev(inp)
+    share = mix == lisa.MIX_SHARE
+    q_lr, k_lr = (None, None) if share else (inp["q_lr"], inp["k_lr"])
+    out, a_n = lisa.lisa_attn_prefill(q_lr, k_lr, inp["v"], prev, w1, w2, mix=mix, act=act)
+    torch.cuda.synchronize()
+    assert lisa.last_path() == "generic"
+    rows = np.arange(cfg.L)
+    worst_o = worst_a = 0.0
+    for b in range(cfg.B):
+        prev_rows = hp.gather_score_rows(prev, b, rows)
+        a_ref, o_ref = cref.lisa_rows(None if share else hp.f64(inp["q_lr"][b]),
+                                      None if share else hp.f64(inp["k_lr"][b]), hp.f64(inp["v"][b]),
+                                      None if w1 is None else hp.f64(w1), None if w2 is None else hp.f64(w2),
+                                      rows, prev_rows, mix=mix, act=act, Lq=cfg.L)
+        worst_o = max(worst_o, hp.row_rel_err(hp.gather_out_rows(out, b, rows), o_ref))
+        worst_a = max(worst_a, hp.scores_row_rel_err(hp.gather_score_rows(a_n, b, rows), a_ref, rows,
+                                                     cfg.L, cfg.L))
+    log(f"[parity] variant {name} {dtype} prefill: err_out={worst_o:.3e} err_scores={worst_a:.3e} tol={tol:g}")
+    assert worst_o <= tol and worst_a <= tol
+    # the decode step of the same variant = the last prefill row, from caches
+    L = cfg.L
+    Lmax = L + 3
+    k_cache = torch.zeros((cfg.B, cfg.Hkv, Lmax, cfg.r), dtype=dt, device=DEV)
+    v_cache = torch.zeros((cfg.B, cfg.Hkv, Lmax, cfg.d_k), dtype=dt, device=DEV)
+    k_cache[:, :, :L] = inp["k_lr"]
+    v_cache[:, :, :L] = inp["v"]
+    row_prev = prev[:, :, L - 1, :].contiguous()
+    q_row = None if share else inp["q_lr"][:, :, L - 1, :].contiguous()
+    o_d, a_d = lisa.lisa_attn_decode(q_row, None if share else k_cache, v_cache, L, row_prev, w1, w2,
+                                     dim_major=False, mix=mix, act=act)
+    torch.cuda.synchronize()
+    worst_o = worst_a = 0.0
+    for b in range(cfg.B):
+        a_ref, o_ref = cref.lisa_rows(None if share else hp.f64(inp["q_lr"][b])[:, L - 1:L],
+                                      None if share else hp.f64(inp["k_lr"][b]), hp.f64(inp["v"][b]),
+                                      None if w1 is None else hp.f64(w1), None if w2 is None else hp.f64(w2),
+                                      [0], hp.f64(row_prev[b])[None], mix=mix, act=act, Lq=1)
+        worst_o = max(worst_o, hp.row_rel_err(hp.f64(o_d[b])[None], o_ref))
+        worst_a = max(worst_a, hp.row_rel_err(hp.f64(a_d[b])[None], a_ref))
+    log(f"[parity] variant {name} {dtype} decode: err_out={worst_o:.3e} err_scores={worst_a:.3e}")
+    assert worst_o <= tol and worst_a <= tol
