@@ -773,3 +773,64 @@ def test_lisa_prefill_and_decode_variants(variant, dtype):
         worst_a = max(worst_a, hp.row_rel_err(hp.f64(a_d[b])[None], a_ref))
     log(f"[parity] variant {name} {dtype} decode: err_out={worst_o:.3e} err_scores={worst_a:.3e}")
     assert worst_o <= tol and worst_a <= tol
+
+
+# ---------------------------------------------------------------------------------------
+# NF decoding strategy (Sec. 5.2): the prefill step of a LiSA layer runs standard attention
+# and stores K_LR (not K) and V in the cache; LiSA takes over at the first decode step.
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dim_major", [True, False])
+def test_nf_strategy_standard_prefill_then_lisa_decode(dim_major):
+    cfg = synth.LayerShape("nf", "bf16", 2, 32, 8, 300, 256, 128, 22, 64, 500000.0)
+    log(f"[case] NF strategy dim_major={dim_major}")
+    B, H, Hkv, L, dk, r = cfg.B, cfg.H, cfg.Hkv, cfg.L, cfg.d_k, cfg.r
+    dt = cfg.torch_dtype
+    tol = hp.TOL[dt]
+    Lmax = L + 20
+    pin = synth.make_projection_inputs(cfg, device=DEV, L=L + 1)          # context + the first new token
+    x_ctx, x_new, w = pin["x"][:, :L].contiguous(), pin["x"][:, L:].contiguous(), pin["w"]
+    aux = synth.make_prefill_inputs(cfg.scaled(L=L + 1), device=DEV)      # w1, w2; q, k of standard layers
+    kshape = (B, Hkv, r, Lmax) if dim_major else (B, Hkv, Lmax, r)
+    k_cache = torch.full(kshape, SENTINEL, dtype=dt, device=DEV)
+    v_cache = torch.full((B, Hkv, Lmax, dk), SENTINEL, dtype=dt, device=DEV)
+
+    # prefill step: K_LR and V of the context go to the caches, attention is the standard one and
+    # emits no score tensor
+    lisa.lisa_project_qkv(x_ctx, w, H, Hkv, r, dk, rope_theta=cfg.rope_theta, k_lr=k_cache, v=v_cache,
+                          dim_major=dim_major)
+    q_ctx, k_ctx = aux["q"][:, :, :L].contiguous(), aux["k"][:, :, :L].contiguous()
+    v_ctx = v_cache[:, :, :L].contiguous()
+    _, o_pre = lisa.std_attn_scores(q_ctx, k_ctx, v_ctx, want_scores=False)
+    torch.cuda.synchronize()
+    rows = np.array([0, 1, 63, 64, 200, L - 1])
+    for b in range(B):
+        s_ref = hp.oracle_std_rows(q_ctx, k_ctx, b, rows)
+        _, _, v_ref = hp.oracle_project_rows(x_ctx, w, b, np.arange(L), H, Hkv, r, dk, cfg.rope_theta, 0)
+        v_rounded = hp.f64(torch.from_numpy(v_ref).to(dt)).transpose(1, 0, 2)
+        o_ref = cref.softmax_v_rows(v_rounded, rows, s_ref, L)
+        err = hp.row_rel_err(hp.gather_out_rows(o_pre, b, rows), o_ref)
+        assert err <= tol, f"NF prefill output error {err}"
+
+    # first decode step: the previous (standard) layer hands over its score row, LiSA reads the caches
+    q_prev_new = aux["q"][:, :, L:L + 1].contiguous()
+    row_prev, _ = lisa.std_attn_scores(q_prev_new, aux["k"])               # [B,H,1,L+1]
+    row_prev = row_prev[:, :, 0, :].contiguous()
+    q_new, _, _ = lisa.lisa_project_qkv(x_new, w, H, Hkv, r, dk, rope_theta=cfg.rope_theta, pos0=L,
+                                        k_lr=k_cache, v=v_cache, dim_major=dim_major)
+    o_d, a_d = lisa.lisa_attn_decode(q_new[:, :, 0, :].contiguous(), k_cache, v_cache, L + 1, row_prev,
+                                     aux["w1"], aux["w2"], dim_major=dim_major)
+    torch.cuda.synchronize()
+    worst_o = worst_a = 0.0
+    for b in range(B):
+        q_ref, k_ref, v_ref = hp.oracle_project_rows(pin["x"], w, b, np.arange(L + 1), H, Hkv, r, dk,
+                                                     cfg.rope_theta, 0)
+        rnd = lambda a: hp.f64(torch.from_numpy(a).to(dt)).transpose(1, 0, 2)   # [heads, L+1, width]
+        a_ref, o_ref = cref.lisa_rows(rnd(q_ref)[:, L:L + 1], rnd(k_ref), rnd(v_ref), hp.f64(aux["w1"]),
+                                      hp.f64(aux["w2"]), [0], hp.f64(row_prev[b])[None])
+        worst_o = max(worst_o, hp.row_rel_err(hp.f64(o_d[b])[None], o_ref))
+        worst_a = max(worst_a, hp.row_rel_err(hp.f64(a_d[b])[None], a_ref))
+    log(f"[parity] NF strategy decode: path={lisa.last_path()} err_out={worst_o:.3e} err_scores={worst_a:.3e}")
+    assert worst_o <= tol and worst_a <= tol
+    # slots beyond the new token are untouched
+    tail = k_cache[..., L + 1:] if dim_major else k_cache[:, :, L + 1:]
+    assert bool((tail == SENTINEL).all()) and bool((v_cache[:, :, L + 1:] == SENTINEL).all())
