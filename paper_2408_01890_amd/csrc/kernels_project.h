@@ -4,7 +4,7 @@
 // before they are stored, and the results written where the attention kernels and the decode
 // caches expect them.
 //
-// bf16 kernel (k_project_mfma): a workgroup of 8 waves owns a 256 x 256 tile of the product and
+// bf16 kernel (k_project_mfma): a workgroup of 8 waves owns a 256 x 256 (or 256 x 192) tile of the product and
 // streams the reduction axis in steps of 64 through two LDS buffers (one barrier per step: the
 // tile of step k+1 is written right after the barrier that publishes step k, the loads of step
 // k+2 are in flight during the MFMAs of step k).  A CU fetches at most 64 bytes per clock from
@@ -124,20 +124,32 @@ typedef __bf16 pj_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float pj_f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned pj_u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int PJ_TM = 256, PJ_TN = 256, PJ_TK = 64;
+constexpr int PJ_TK = 64;                       // reduction elements per step
 constexpr int PJ_ROWB = PJ_TK * 2;              // bytes per LDS row
-constexpr int PJ_TILE = PJ_TM * PJ_ROWB;        // one operand tile of one step: 32 KB
-constexpr int PJ_STG_ROW = 64 * 2 + 16;         // bytes per row of a wave's output staging piece (padded)
-constexpr int PJ_STG_WAVE = 128 * PJ_STG_ROW;   // 128 rows x 64 columns per wave
-constexpr int PJ_LDS = 8 * PJ_STG_WAVE;         // the staging space of 8 waves; the main loop uses
-                                                // 4 * PJ_TILE of it: two steps x (X tile, W tile)
-static_assert(PJ_LDS >= 4 * PJ_TILE && PJ_LDS <= 160 * 1024, "LDS budget");
+
+// Tile geometry: WM x WN waves (8 in all), each BM x BN blocks of 32 x 32 outputs.
+//   <2,4,4,2>  256 x 256 outputs per workgroup, the densest in MFMA work per fetched byte;
+//   <4,2,2,3>  256 x 192, for problems whose 256-wide tiles would leave a quarter of the CUs
+//              idle or add a nearly empty last round of workgroups.
+template <int WM, int WN, int BM, int BN>
+struct ProjTile {
+  static_assert(WM * WN == 8, "8 waves");
+  static constexpr int TM = WM * BM * 32, TN = WN * BN * 32;
+  static constexpr int XN = TM / 64, WNLD = TN / 64;      // 16-byte chunks per thread and step: X, W
+  static constexpr int XTILE = TM * PJ_ROWB, WTILE = TN * PJ_ROWB;
+  static constexpr int STEP = XTILE + WTILE;              // one step of both operands
+  static constexpr int STG_ROW = BN * 64 + 16;            // bytes per row of a wave's output staging piece (padded)
+  static constexpr int STG_WAVE = BM * 32 * STG_ROW;
+  static constexpr int LDS = 2 * STEP > 8 * STG_WAVE ? 2 * STEP : 8 * STG_WAVE;
+  static_assert(TM % 64 == 0 && TN % 64 == 0 && LDS <= 160 * 1024, "tile shape");
+};
 constexpr int PJ_HEADW = 32;                    // virtual columns of a Q_LR / K_LR head
 
-// Scheduling request for one sub-step (8 MFMAs, 6 LDS reads, 4 instructions of class `other`:
-// 0x200 LDS writes, 0x020 global loads): the reads early (MFMA, two reads, three times: the
-// next sub-step starts 5 MFMAs after the last of them), then MFMA, two others, twice, 3 MFMAs.
-#define PJ_INTERLEAVE(other)                                  \
+// Scheduling request for one sub-step (`n_mfma` MFMAs, up to 6 LDS reads, up to 4 instructions of
+// class `other`: 0x200 LDS writes, 0x020 global loads): the reads early (MFMA, two reads, three
+// times: the next sub-step starts several MFMAs after the last of them), then MFMA, two others,
+// twice, then the remaining MFMAs.
+#define PJ_INTERLEAVE(other, n_mfma)                          \
   do {                                                        \
     _Pragma("unroll") for (int i_ = 0; i_ < 3; ++i_) {        \
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      \
@@ -147,17 +159,19 @@ constexpr int PJ_HEADW = 32;                    // virtual columns of a Q_LR / K
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      \
       __builtin_amdgcn_sched_group_barrier(other, 2, 0);      \
     }                                                         \
-    __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);        \
+    __builtin_amdgcn_sched_group_barrier(0x008, (n_mfma) - 5, 0); \
   } while (0)
 
 __device__ __forceinline__ void pj_lds_barrier() {
   __asm__ volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+template <int WM, int WN, int BM, int BN>
 __global__ __launch_bounds__(512) void k_project_mfma(ProjectArgs a) {
+  typedef ProjTile<WM, WN, BM, BN> G;
   extern __shared__ __align__(16) unsigned char pj_lds[];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const int wm = wv >> 2, wn = wv & 3;
+  const int wm = wv / WN, wn = wv % WN;
   const int half = lane >> 5, l32 = lane & 31;
 
   // Workgroup ids go round robin over the 8 XCDs (each with its own L2): an XCD keeps to
@@ -178,16 +192,19 @@ __global__ __launch_bounds__(512) void k_project_mfma(ProjectArgs a) {
   const int nheads_qk = a.H + a.Hkv;
   const int nv_qk = PJ_HEADW * nheads_qk;                   // virtual columns before V
   const int n_real = nheads_qk * a.r + a.Hkv * a.dk;
-  const int m0 = tm * PJ_TM, n0 = tn * PJ_TN;
+  const int m0 = tm * G::TM, n0 = tn * G::TN;
 
   // loader: thread -> 16-byte chunk (row ld_row + 64 i, chunk ld_kc) of both operand tiles
   const int ld_row = tid >> 3, ld_kc = tid & 7;
-  const bf16_t* xp[4];
-  const bf16_t* wp[4];
+  const bf16_t* xp[G::XN];
+  const bf16_t* wp[G::WNLD];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < G::XN; ++i) {
     const int row = min(m0 + ld_row + 64 * i, M - 1);
     xp[i] = (const bf16_t*)a.x + (size_t)row * D + 8 * ld_kc;
+  }
+#pragma unroll
+  for (int i = 0; i < G::WNLD; ++i) {
     const int nv = n0 + ld_row + 64 * i;
     int real;
     if (nv < nv_qk) {
@@ -198,38 +215,42 @@ __global__ __launch_bounds__(512) void k_project_mfma(ProjectArgs a) {
     wp[i] = (const bf16_t*)a.w + (size_t)min(real, n_real - 1) * D + 8 * ld_kc;
   }
   const int st_off = ld_row * PJ_ROWB + ((ld_kc ^ ((ld_row >> 1) & 7)) << 4);
-  pj_u32x4 rx[4], rw[4];
-  auto load_part = [&](int kt, int i0, int i1) {
+  // the chunks of a step travel in two halves (part 0, part 1) so that they can be spread over
+  // the sub-steps
+  pj_u32x4 rx[G::XN], rw[G::WNLD];
+  auto load_part = [&](int kt, int part) {
 #pragma unroll
-    for (int i = i0; i < i1; ++i) {
+    for (int i = part * (G::XN / 2); i < (part ? G::XN : G::XN / 2); ++i)
       rx[i] = *(const pj_u32x4*)(xp[i] + (size_t)kt * PJ_TK);
-      rw[i] = *(const pj_u32x4*)(wp[i] + (size_t)kt * PJ_TK);
-    }
-  };
-  auto store_part = [&](int buf, int i0, int i1) {
-    unsigned char* base = pj_lds + buf * (2 * PJ_TILE) + st_off;
 #pragma unroll
-    for (int i = i0; i < i1; ++i) {
-      *(pj_u32x4*)(base + i * 64 * PJ_ROWB) = rx[i];
-      *(pj_u32x4*)(base + PJ_TILE + i * 64 * PJ_ROWB) = rw[i];
-    }
+    for (int i = part * (G::WNLD / 2); i < (part ? G::WNLD : G::WNLD / 2); ++i)
+      rw[i] = *(const pj_u32x4*)(wp[i] + (size_t)kt * PJ_TK);
   };
-  auto load_step = [&](int kt) { load_part(kt, 0, 4); };
-  auto store_step = [&](int buf) { store_part(buf, 0, 4); };
+  auto store_part = [&](int buf, int part) {
+    unsigned char* base = pj_lds + buf * G::STEP + st_off;
+#pragma unroll
+    for (int i = part * (G::XN / 2); i < (part ? G::XN : G::XN / 2); ++i)
+      *(pj_u32x4*)(base + i * 64 * PJ_ROWB) = rx[i];
+#pragma unroll
+    for (int i = part * (G::WNLD / 2); i < (part ? G::WNLD : G::WNLD / 2); ++i)
+      *(pj_u32x4*)(base + G::XTILE + i * 64 * PJ_ROWB) = rw[i];
+  };
+  auto load_step = [&](int kt) { load_part(kt, 0); load_part(kt, 1); };
+  auto store_step = [&](int buf) { store_part(buf, 0); store_part(buf, 1); };
 
   // operand reads: row (32 blk + l32), chunk 2 ks + half, swizzled by the row
   const int sw = (l32 >> 1) & 7;
   int rd_c[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) rd_c[ks] = ((2 * ks + half) ^ sw) << 4;
-  const int rd_a = (wm * 128 + l32) * PJ_ROWB;
-  const int rd_b = PJ_TILE + (wn * 64 + l32) * PJ_ROWB;
+  const int rd_a = (wm * BM * 32 + l32) * PJ_ROWB;
+  const int rd_b = G::XTILE + (wn * BN * 32 + l32) * PJ_ROWB;
 
-  pj_f32x16 acc[4][2];
+  pj_f32x16 acc[BM][BN];
 #pragma unroll
-  for (int bm = 0; bm < 4; ++bm)
+  for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
-    for (int bn = 0; bn < 2; ++bn)
+    for (int bn = 0; bn < BN; ++bn)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[bm][bn][v] = 0.f;
 
@@ -237,21 +258,21 @@ __global__ __launch_bounds__(512) void k_project_mfma(ProjectArgs a) {
   // the MFMAs of sub-step ks, and the MFMAs of the last sub-step of a step run after the
   // barrier of the next one, behind its first operand reads and its tile writes, so the
   // matrix pipe has work while the LDS is busiest.
-  pj_bf16x8 fa[2][4], fb[2][2];
+  pj_bf16x8 fa[2][BM], fb[2][BN];
   // (the W operands first: the first MFMAs of a sub-step need both of them and one X operand)
   auto read_frags = [&](const unsigned char* buf, int ks, int set) {
 #pragma unroll
-    for (int bn = 0; bn < 2; ++bn)
+    for (int bn = 0; bn < BN; ++bn)
       fb[set][bn] = *(const pj_bf16x8*)(buf + rd_b + bn * 32 * PJ_ROWB + rd_c[ks]);
 #pragma unroll
-    for (int bm = 0; bm < 4; ++bm)
+    for (int bm = 0; bm < BM; ++bm)
       fa[set][bm] = *(const pj_bf16x8*)(buf + rd_a + bm * 32 * PJ_ROWB + rd_c[ks]);
   };
   auto mfmas = [&](int set) {
 #pragma unroll
-    for (int bm = 0; bm < 4; ++bm)
+    for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
-      for (int bn = 0; bn < 2; ++bn)
+      for (int bn = 0; bn < BN; ++bn)
         acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][bm], fb[set][bn], acc[bm][bn], 0, 0, 0);
   };
 
@@ -261,11 +282,11 @@ __global__ __launch_bounds__(512) void k_project_mfma(ProjectArgs a) {
   // its SIMD idle, and both waves of a SIMD reach that block together).  The operand sets
   // start as zeros so that the deferred MFMAs of the first step add nothing.
 #pragma unroll
-  for (int bm = 0; bm < 4; ++bm)
+  for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
     for (int e = 0; e < 8; ++e) fa[1][bm][e] = (__bf16)0.f;
 #pragma unroll
-  for (int bn = 0; bn < 2; ++bn)
+  for (int bn = 0; bn < BN; ++bn)
 #pragma unroll
     for (int e = 0; e < 8; ++e) fb[1][bn][e] = (__bf16)0.f;
 
@@ -277,36 +298,36 @@ __global__ __launch_bounds__(512) void k_project_mfma(ProjectArgs a) {
   for (; kt + 2 < nk; ++kt) {
     // step kt is complete in buffer kt & 1 and every wave has read all it needs of the other one
     pj_lds_barrier();
-    const unsigned char* buf = pj_lds + (kt & 1) * (2 * PJ_TILE);
+    const unsigned char* buf = pj_lds + (kt & 1) * G::STEP;
     const int nb = (kt + 1) & 1;
     // sub-step 3 of step kt - 1 | operands of sub-step 0, first half of the tile writes
     read_frags(buf, 0, 0);
-    store_part(nb, 0, 2);
+    store_part(nb, 0);
     mfmas(1);
-    PJ_INTERLEAVE(0x200);
+    PJ_INTERLEAVE(0x200, BM * BN);
     __builtin_amdgcn_sched_barrier(0);
     // sub-step 0 | operands of sub-step 1, second half of the tile writes
     read_frags(buf, 1, 1);
-    store_part(nb, 2, 4);
+    store_part(nb, 1);
     mfmas(0);
-    PJ_INTERLEAVE(0x200);
+    PJ_INTERLEAVE(0x200, BM * BN);
     __builtin_amdgcn_sched_barrier(0);
     // sub-step 1 | operands of sub-step 2, first half of the loads of step kt + 2
     read_frags(buf, 2, 0);
-    load_part(kt + 2, 0, 2);
+    load_part(kt + 2, 0);
     mfmas(1);
-    PJ_INTERLEAVE(0x020);
+    PJ_INTERLEAVE(0x020, BM * BN);
     __builtin_amdgcn_sched_barrier(0);
     // sub-step 2 | operands of sub-step 3, second half of the loads
     read_frags(buf, 3, 1);
-    load_part(kt + 2, 2, 4);
+    load_part(kt + 2, 1);
     mfmas(0);
-    PJ_INTERLEAVE(0x020);
+    PJ_INTERLEAVE(0x020, BM * BN);
     __builtin_amdgcn_sched_barrier(0);
   }
   for (; kt < nk; ++kt) {                                  // the last two steps: nothing left to load
     pj_lds_barrier();
-    const unsigned char* buf = pj_lds + (kt & 1) * (2 * PJ_TILE);
+    const unsigned char* buf = pj_lds + (kt & 1) * G::STEP;
     read_frags(buf, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
     mfmas(1);
@@ -324,48 +345,75 @@ __global__ __launch_bounds__(512) void k_project_mfma(ProjectArgs a) {
   mfmas(1);
 
   // Epilogue.  acc[bm][bn][v]: token row m0 + 128 wm + 32 bm + 8 (v/4) + 4 half + v%4, virtual
-  // column n0 + 64 wn + 32 bn + l32.  Every wave rotates its Q_LR / K_LR blocks in registers
+  // column n0 + 64 wn + 32 bn + l32 (for the <2,4,4,2> geometry).  Every wave rotates its Q_LR / K_LR blocks in registers
   // (the partner of a rotary pair is another lane of the same register), rounds to bfloat16 and
   // lays its 128 x 64 outputs out by rows in its own piece of the LDS, from where whole rows
   // go to memory: 128-byte pieces of V rows, the 2r-byte rows of Q_LR / K_LR (consecutive
   // tokens of a head are adjacent in memory), 64-byte runs along the tokens of a
   // dimension-major K_LR cache.
   __syncthreads();                                         // the operand tiles are dead: LDS becomes staging space
-  unsigned char* stg = pj_lds + wv * PJ_STG_WAVE;
-  const int mw = m0 + wm * 128;                            // first token row of the wave
+  unsigned char* stg = pj_lds + wv * G::STG_WAVE;
+  const int mw = m0 + wm * (BM * 32);                            // first token row of the wave
   const int odd = lane & 1;
+  // rotary embedding: the lane's frequency, partner lane and side of the pair are the same in
+  // every block (they depend on lane % 32 only)
+  const int nv_first = n0 + wn * (BN * 32);
+  const bool rot_any = a.rope && nv_first < nv_qk;         // (blocks are ordered: Q_LR / K_LR heads first)
+  const int hr = a.r >> 1;
+  const bool lower = l32 < hr;
+  double inv_freq_rev = 0.0;
+  int partner = lane;
+  float c1 = 1.f, s1 = 0.f, c8 = 1.f, s8 = 0.f;            // rotations by 1 and by 8 positions
+  if (rot_any) {
+    const int t = lower ? l32 : l32 - hr;
+    inv_freq_rev = exp2((double)min(t, hr - 1) * a.freq_log2) * 0.15915494309189535;
+    partner = (lane & 32) | (l32 < a.r ? (lower ? l32 + hr : l32 - hr) : l32);
+    rope_cos_sin_fast(1, inv_freq_rev, c1, s1);
+    rope_cos_sin_fast(8, inv_freq_rev, c8, s8);
+  }
 #pragma unroll
-  for (int bn = 0; bn < 2; ++bn) {
-    const int nvb = n0 + wn * 64 + bn * 32;                // first virtual column of the block (wave-uniform)
-    const bool rot = a.rope && nvb < nv_qk;
-    const int hr = a.r >> 1;
-    const bool lower = l32 < hr;
-    double inv_freq_rev = 0.0;
-    int partner = lane;
-    if (rot) {
-      const int t = lower ? l32 : l32 - hr;
-      inv_freq_rev = exp2((double)min(t, hr - 1) * a.freq_log2) * 0.15915494309189535;
-      partner = (lane & 32) | (l32 < a.r ? (lower ? l32 + hr : l32 - hr) : l32);
+  for (int bm = 0; bm < BM; ++bm) {
+    // cos / sin of the lane's 16 rows: row 8 j + i of the lane is position l0 + 8 j + i.  One exact
+    // evaluation, then the angle-addition formulas (float32: the results are rounded to bfloat16);
+    // a block that runs into the next sequence evaluates every row exactly.
+    float cs[16], sn[16];
+    if (rot_any) {
+      const int mb = min(mw + bm * 32 + 4 * half, M - 1);
+      const int l0 = mb - mb / a.L * a.L;
+      if (l0 + 27 < a.L) {
+        rope_cos_sin_fast(a.pos0 + l0, inv_freq_rev, cs[0], sn[0]);
+#pragma unroll
+        for (int jj = 1; jj < 4; ++jj) {
+          cs[4 * jj] = cs[4 * jj - 4] * c8 - sn[4 * jj - 4] * s8;
+          sn[4 * jj] = sn[4 * jj - 4] * c8 + cs[4 * jj - 4] * s8;
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          if ((v & 3) == 0) continue;
+          cs[v] = cs[v - 1] * c1 - sn[v - 1] * s1;
+          sn[v] = sn[v - 1] * c1 + cs[v - 1] * s1;
+        }
+      } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          int l = l0 + 8 * (v >> 2) + (v & 3);
+          if (l >= a.L) l -= l / a.L * a.L;
+          rope_cos_sin_fast(a.pos0 + l, inv_freq_rev, cs[v], sn[v]);
+        }
+      }
     }
 #pragma unroll
-    for (int bm = 0; bm < 4; ++bm) {
-      int l0 = 0;
-      if (rot) {
-        const int mb = min(mw + bm * 32 + 4 * half, M - 1);
-        l0 = mb - mb / a.L * a.L;
-      }
+    for (int bn = 0; bn < BN; ++bn) {
+      const int nvb = nv_first + bn * 32;                  // first virtual column of the block (wave-uniform)
+      const bool rot = a.rope && nvb < nv_qk;
 #pragma unroll
       for (int v = 0; v < 16; v += 2) {
         float y[2] = {acc[bm][bn][v], acc[bm][bn][v + 1]};
         if (rot) {
 #pragma unroll
           for (int e = 0; e < 2; ++e) {
-            int l = l0 + 8 * (v >> 2) + (v & 3) + e;
-            if (l >= a.L) l -= l / a.L * a.L;              // the row block runs into the next sequence(s)
             const float other = __shfl(y[e], partner, 64);
-            float cs, sn;
-            rope_cos_sin_fast(a.pos0 + l, inv_freq_rev, cs, sn);
-            y[e] = lower ? y[e] * cs - other * sn : other * sn + y[e] * cs;
+            y[e] = lower ? y[e] * cs[v + e] - other * sn[v + e] : other * sn[v + e] + y[e] * cs[v + e];
           }
         }
         // columns c, c + 1 of one row share a 32-bit word: the even lane assembles row v, the odd
@@ -374,7 +422,7 @@ __global__ __launch_bounds__(512) void k_project_mfma(ProjectArgs a) {
         const unsigned got = __shfl_xor(odd ? u0 : u1, 1, 64);
         const unsigned word = odd ? (got | (u1 << 16)) : (u0 | (got << 16));
         const int row = bm * 32 + 8 * (v >> 2) + 4 * half + (v & 3) + odd;
-        *(unsigned*)(stg + row * PJ_STG_ROW + (bn * 32 + (l32 & ~1)) * 2) = word;
+        *(unsigned*)(stg + row * G::STG_ROW + (bn * 32 + (l32 & ~1)) * 2) = word;
       }
     }
   }
@@ -394,26 +442,27 @@ __global__ __launch_bounds__(512) void k_project_mfma(ProjectArgs a) {
       l -= q * a.L;
     }
   };
-  const int nvw = n0 + wn * 64;
+  const int nvw = n0 + wn * (BN * 32);
+  constexpr int WCOLS = BN * 32, WROWS = BM * 32, CH = WCOLS / 8;   // columns, rows, 16-byte chunks per row
   const int n_vcols = a.Hkv * a.dk;
-  if (nvw >= nv_qk && (nvw - nv_qk) % a.dk + 64 <= a.dk) {
-    // both blocks belong to one V head: 128-byte pieces of rows
+  if (nvw >= nv_qk && (nvw - nv_qk) % a.dk + WCOLS <= a.dk) {
+    // all blocks belong to one V head: whole pieces of rows (2 * WCOLS bytes)
     const int col = nvw - nv_qk;
     if (col < n_vcols) {
       const int kv = col / a.dk, cc = col - kv * a.dk;
 #pragma unroll 4
-      for (int pass = 0; pass < 16; ++pass) {
-        const int row = pass * 8 + (lane >> 3), ch = lane & 7;
+      for (int idx = lane; idx < WROWS * CH; idx += 64) {
+        const int row = idx / CH, ch = idx - row * CH;
         int b, l;
         locate(row, b, l);
         if (mw + row < M) {
           bf16_t* dst = (bf16_t*)a.v + (((size_t)b * a.Hkv + kv) * a.Lmax + a.pos0 + l) * a.dk + cc + 8 * ch;
-          *(pj_u32x4*)dst = *(const pj_u32x4*)(stg + row * PJ_STG_ROW + ch * 16);
+          *(pj_u32x4*)dst = *(const pj_u32x4*)(stg + row * G::STG_ROW + ch * 16);
         }
       }
     }
   } else {
-    for (int bn = 0; bn < 2; ++bn) {
+    for (int bn = 0; bn < BN; ++bn) {
       const int nvb = nvw + bn * 32;
       const unsigned char* sb = stg + bn * 64;
       if (nvb >= nv_qk) {
@@ -421,13 +470,13 @@ __global__ __launch_bounds__(512) void k_project_mfma(ProjectArgs a) {
         const int col = nvb - nv_qk;
         if (col >= n_vcols) continue;
         const int kv = col / a.dk, cc = col - kv * a.dk;
-        for (int pass = 0; pass < 8; ++pass) {
+        for (int pass = 0; pass < WROWS / 16; ++pass) {
           const int row = pass * 16 + (lane >> 2), ch = lane & 3;
           int b, l;
           locate(row, b, l);
           if (mw + row < M) {
             bf16_t* dst = (bf16_t*)a.v + (((size_t)b * a.Hkv + kv) * a.Lmax + a.pos0 + l) * a.dk + cc + 8 * ch;
-            *(pj_u32x4*)dst = *(const pj_u32x4*)(sb + row * PJ_STG_ROW + ch * 16);
+            *(pj_u32x4*)dst = *(const pj_u32x4*)(sb + row * G::STG_ROW + ch * 16);
           }
         }
         continue;
@@ -437,14 +486,14 @@ __global__ __launch_bounds__(512) void k_project_mfma(ProjectArgs a) {
       const int hh = is_q ? head : head - a.H, nh = is_q ? a.H : a.Hkv;
       if (!is_q && a.k_dim_major) {
         // runs along the tokens: lane = (token of a 32-row block, parity of the feature)
-        for (int bm = 0; bm < 4; ++bm) {
+        for (int bm = 0; bm < BM; ++bm) {
           const int row = bm * 32 + l32;
           int b, l;
           locate(row, b, l);
           if (mw + row >= M) continue;
           bf16_t* dst = (bf16_t*)a.k_lr + ((size_t)b * a.Hkv + hh) * a.r * a.Lmax + a.pos0 + l;
           for (int c = half; c < a.r; c += 2)
-            dst[(size_t)c * a.Lmax].bits = *(const uint16_t*)(sb + row * PJ_STG_ROW + 2 * c);
+            dst[(size_t)c * a.Lmax].bits = *(const uint16_t*)(sb + row * G::STG_ROW + 2 * c);
         }
         continue;
       }
@@ -452,16 +501,16 @@ __global__ __launch_bounds__(512) void k_project_mfma(ProjectArgs a) {
       bf16_t* base = (bf16_t*)(is_q ? a.q_lr : a.k_lr);
       const int lrow = is_q ? a.L : a.Lmax, p0 = is_q ? 0 : a.pos0;
       const int j = lane & 15;
-      for (int pass = 0; pass < 32; ++pass) {
+      for (int pass = 0; pass < WROWS / 4; ++pass) {
         const int row = pass * 4 + (lane >> 4);
         int b, l;
         locate(row, b, l);
         if (mw + row >= M) continue;
         bf16_t* dst = base + (((size_t)b * nh + hh) * lrow + p0 + l) * a.r;
         if ((a.r & 1) == 0) {
-          if (2 * j < a.r) *(unsigned*)(dst + 2 * j) = *(const unsigned*)(sb + row * PJ_STG_ROW + 4 * j);
+          if (2 * j < a.r) *(unsigned*)(dst + 2 * j) = *(const unsigned*)(sb + row * G::STG_ROW + 4 * j);
         } else {
-          for (int c = j; c < a.r; c += 16) dst[c].bits = *(const uint16_t*)(sb + row * PJ_STG_ROW + 2 * c);
+          for (int c = j; c < a.r; c += 16) dst[c].bits = *(const uint16_t*)(sb + row * G::STG_ROW + 2 * c);
         }
       }
     }

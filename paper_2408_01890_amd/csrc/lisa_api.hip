@@ -585,19 +585,40 @@ int lisa_project_qkv(const lisa_proj_desc* d, const void* x, const void* w, void
   const char* path;
   if (fast) {
     const long long n_virtual = (long long)PJ_HEADW * (d->H + d->Hkv) + (long long)d->Hkv * d->d_k;
-    a.n_m = (int)((M + PJ_TM - 1) / PJ_TM);
-    a.n_n = (int)((n_virtual + PJ_TN - 1) / PJ_TN);
+    // tile width: the one whose workgroups fill the 256 CUs in fewer, fuller rounds (a round costs
+    // in proportion to the tile width); the wider tile on a tie
+    auto rounds_cost = [&](int tn) {
+      const long long wgs = ((M + 255) / 256) * ((n_virtual + tn - 1) / tn);
+      return ((wgs + kComputeUnits - 1) / kComputeUnits) * tn;
+    };
+    // (the narrower tile does less MFMA work per fetched byte: it must win by a margin)
+    int tn = rounds_cost(192) * 8 < rounds_cost(256) * 7 ? 192 : 256;
+    if (const char* e = std::getenv("LISA_PROJECT_TN")) {   // tests force either geometry
+      const int v = std::atoi(e);
+      if (v == 192 || v == 256) tn = v;
+    }
+    a.n_m = (int)((M + 255) / 256);
+    a.n_n = (int)((n_virtual + tn - 1) / tn);
     // which axis of the tile grid an XCD keeps to: the one that is balanced over 8 XCDs and
     // re-reads fewer operand bytes
     const bool n_ok = a.n_n % 8 == 0 || a.n_n >= 40, m_ok = a.n_m % 8 == 0 || a.n_m >= 40;
     const double xb = (double)M * d->d_model, wb = (double)n_real * d->d_model;
     a.own_n = n_ok && (!m_ok || wb / 8 + xb <= xb / 8 + wb);
     const int per_xcd = a.own_n ? (a.n_n + 7) / 8 * a.n_m : (a.n_m + 7) / 8 * a.n_n;
-    hipError_t e = hipFuncSetAttribute((const void*)k_project_mfma,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, PJ_LDS);
-    if (e != hipSuccess) return hip_fail(e);
     StageScope scope("k_project_mfma", st);
-    k_project_mfma<<<dim3(8 * per_xcd), 512, PJ_LDS, st>>>(a);
+    if (tn == 256) {
+      auto kern = k_project_mfma<2, 4, 4, 2>;
+      constexpr int lds = ProjTile<2, 4, 4, 2>::LDS;
+      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+      if (e != hipSuccess) return hip_fail(e);
+      kern<<<dim3(8 * per_xcd), 512, lds, st>>>(a);
+    } else {
+      auto kern = k_project_mfma<4, 2, 2, 3>;
+      constexpr int lds = ProjTile<4, 2, 2, 3>::LDS;
+      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+      if (e != hipSuccess) return hip_fail(e);
+      kern<<<dim3(8 * per_xcd), 512, lds, st>>>(a);
+    }
     path = "project_mfma";
   } else {
     const long long total = M * n_real;

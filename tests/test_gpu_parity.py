@@ -627,10 +627,12 @@ PROJ_MFMA = [
 ]
 
 
+@pytest.mark.parametrize("tile_n", [256, 192])
 @pytest.mark.parametrize("case", PROJ_MFMA, ids=lambda c: f"B{c[0]}H{c[1]}-{c[2]}L{c[3]}d{c[4]}r{c[6]}")
-def test_projection_mfma_kernel_shapes(case):
+def test_projection_mfma_kernel_shapes(case, tile_n, monkeypatch):
     B, H, Hkv, L, D, dk, r, theta, pos0, dim_major, extra = case
-    log(f"[case] projection mfma {case}")
+    monkeypatch.setenv("LISA_PROJECT_TN", str(tile_n))       # both tile geometries of the kernel
+    log(f"[case] projection mfma {case} tile_n={tile_n}")
     cfg = synth.LayerShape("proj_mfma", "bf16", B, H, Hkv, L, D, dk, r, 64, theta)
     pin = synth.make_projection_inputs(cfg, device=DEV)
     path = check_projection(cfg, pin, {b: np.arange(L) for b in range(B)}, theta, pos0, dim_major,
