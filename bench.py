@@ -149,6 +149,33 @@ def decode_stack(stk, steps, warmup):
     stages = lisa.profile_collect()
     lisa.profile_enable(False)
     path = lisa.last_path()
+
+    # one layer of each kind alone, for the layer patterns of the paper's models (Sec. 5.1 table of
+    # LiSA configurations: 17, 21 or 27 of 32 layers share attention; this stack is the 27-layer one)
+    def one_std():
+        ly = layers[0]
+        lisa.std_attn_decode(ly["q"], ly["k_cache"], ly["v_cache"], Lk, want_scores=True,
+                             score_row_out=rows[0], out=out, workspace=ws)
+
+    def one_lisa():
+        ly = layers[stk.n_std]
+        lisa.lisa_attn_decode(ly["q_lr"], ly["k_lr_cache"], ly["v_cache"], Lk, rows[0], ly["w1"], ly["w2"],
+                              dim_major=True, write_scores=True, out=out, score_row_out=rows[1],
+                              workspace=ws)
+
+    t_std = time_steps(one_std, 10, 2)
+    t_lisa = time_steps(one_lisa, 10, 2)
+    kv_std = 2 * stk.Hkv * stk.d_k * e                       # cache bytes per token and layer
+    kv_lisa = stk.Hkv * (stk.r + stk.d_k) * e
+    patterns = {}
+    for n_lisa in (17, 21, 27):
+        n_s = stk.n_layers - n_lisa
+        patterns[f"lisa_{n_lisa}_of_{stk.n_layers}"] = {
+            "attention_step_us": (n_s * t_std + n_lisa * t_lisa) * 1e6,
+            "speedup_vs_all_standard_at_equal_batch": stk.n_layers * t_std / (n_s * t_std + n_lisa * t_lisa),
+            "kv_cache_bytes_per_token": n_s * kv_std + n_lisa * kv_lisa,
+            "kv_cache_vs_all_standard": (n_s * kv_std + n_lisa * kv_lisa) / (stk.n_layers * kv_std),
+        }
     del layers
     torch.cuda.empty_cache()
     return {
@@ -159,6 +186,8 @@ def decode_stack(stk, steps, warmup):
         "hbm_GBps": total_bytes / sec / 1e9, "hbm_frac": total_bytes / sec / 1e9 / HBM_PEAK_GBS,
         "tokens_per_s": stk.B / sec,
         "stage_ms_one_step": {k: round(v[1], 4) for k, v in stages.items()},
+        "standard_layer_us": t_std * 1e6, "lisa_layer_us": t_lisa * 1e6,
+        "layer_patterns_attention_only": patterns,
     }
 
 
