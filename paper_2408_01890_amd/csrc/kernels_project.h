@@ -5,9 +5,9 @@
 // caches expect them.
 //
 // bf16 kernel (k_project_mfma): a workgroup of 8 waves owns a 256 x 256 (or 256 x 192) tile of the product and
-// streams the reduction axis in steps of 64 through two LDS buffers (one barrier per step: the
-// tile of step k+1 is written right after the barrier that publishes step k, the loads of step
-// k+2 are in flight during the MFMAs of step k).  A CU fetches at most 64 bytes per clock from
+// streams the reduction axis in steps of 64 through two LDS buffers, filled straight from global
+// memory (global_load_lds_dwordx4), one barrier per step: the loads of step k+1 are issued during
+// the first MFMAs of step k into the buffer that step k-1 used.  A CU fetches at most 64 bytes per clock from
 // its vector memory path and its MFMAs eat 2 * 256 * 256 / (256 + 256) = 256 flops per fetched
 // element at this tile size, twice what the fetch path must sustain; a 128 x 128 tile would run at
 // that limit.  Wave (wm, wn) of the 2 x 4 arrangement owns 128 x 64 outputs = 4 x 2 blocks
@@ -162,8 +162,10 @@ constexpr int PJ_HEADW = 32;                    // virtual columns of a Q_LR / K
     __builtin_amdgcn_sched_group_barrier(0x008, (n_mfma) - 5, 0); \
   } while (0)
 
-__device__ __forceinline__ void pj_lds_barrier() {
-  __asm__ volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+// Barrier that publishes a tile loaded straight into the LDS: the wave's own loads have landed
+// (vmcnt) and its LDS reads are done (lgkmcnt) before it arrives.
+__device__ __forceinline__ void pj_tile_barrier() {
+  __asm__ volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 template <int WM, int WN, int BM, int BN>
@@ -196,12 +198,13 @@ __global__ __launch_bounds__(512) void k_project_mfma(ProjectArgs a) {
 
   // loader: thread -> 16-byte chunk (row ld_row + 64 i, chunk ld_kc) of both operand tiles
   const int ld_row = tid >> 3, ld_kc = tid & 7;
+  const int ld_gc = ld_kc ^ ((ld_row >> 1) & 7);           // chunk of the row that lands at LDS chunk ld_kc
   const bf16_t* xp[G::XN];
   const bf16_t* wp[G::WNLD];
 #pragma unroll
   for (int i = 0; i < G::XN; ++i) {
     const int row = min(m0 + ld_row + 64 * i, M - 1);
-    xp[i] = (const bf16_t*)a.x + (size_t)row * D + 8 * ld_kc;
+    xp[i] = (const bf16_t*)a.x + (size_t)row * D + 8 * ld_gc;
   }
 #pragma unroll
   for (int i = 0; i < G::WNLD; ++i) {
@@ -212,31 +215,27 @@ __global__ __launch_bounds__(512) void k_project_mfma(ProjectArgs a) {
     } else {
       real = nheads_qk * a.r + (nv - nv_qk);
     }
-    wp[i] = (const bf16_t*)a.w + (size_t)min(real, n_real - 1) * D + 8 * ld_kc;
+    wp[i] = (const bf16_t*)a.w + (size_t)min(real, n_real - 1) * D + 8 * ld_gc;
   }
-  const int st_off = ld_row * PJ_ROWB + ((ld_kc ^ ((ld_row >> 1) & 7)) << 4);
-  // the chunks of a step travel in two halves (part 0, part 1) so that they can be spread over
-  // the sub-steps
-  pj_u32x4 rx[G::XN], rw[G::WNLD];
-  auto load_part = [&](int kt, int part) {
+  // The tiles go from global memory straight into the LDS (global_load_lds_dwordx4: lane l of a
+  // wave writes its 16 bytes at the wave's LDS base + 16 l): one instruction of a wave fills 8
+  // consecutive tile rows, so the swizzle is applied on the global side (lane -> which chunk of
+  // the row it fetches).  No staging registers and no LDS write instructions in the loop.
+  // The chunks of a step travel in two halves (part 0, part 1) spread over the first sub-steps.
+  const int lds_wave = __builtin_amdgcn_readfirstlane(wv) * 8 * PJ_ROWB;   // first of the wave's 8 rows
+  auto load_part = [&](int kt, int buf, int part) {
+    unsigned char* base = pj_lds + buf * G::STEP + lds_wave;
 #pragma unroll
     for (int i = part * (G::XN / 2); i < (part ? G::XN : G::XN / 2); ++i)
-      rx[i] = *(const pj_u32x4*)(xp[i] + (size_t)kt * PJ_TK);
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(xp[i] + (size_t)kt * PJ_TK),
+          (__attribute__((address_space(3))) void*)(base + i * 64 * PJ_ROWB), 16, 0, 0);
 #pragma unroll
     for (int i = part * (G::WNLD / 2); i < (part ? G::WNLD : G::WNLD / 2); ++i)
-      rw[i] = *(const pj_u32x4*)(wp[i] + (size_t)kt * PJ_TK);
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(wp[i] + (size_t)kt * PJ_TK),
+          (__attribute__((address_space(3))) void*)(base + G::XTILE + i * 64 * PJ_ROWB), 16, 0, 0);
   };
-  auto store_part = [&](int buf, int part) {
-    unsigned char* base = pj_lds + buf * G::STEP + st_off;
-#pragma unroll
-    for (int i = part * (G::XN / 2); i < (part ? G::XN : G::XN / 2); ++i)
-      *(pj_u32x4*)(base + i * 64 * PJ_ROWB) = rx[i];
-#pragma unroll
-    for (int i = part * (G::WNLD / 2); i < (part ? G::WNLD : G::WNLD / 2); ++i)
-      *(pj_u32x4*)(base + G::XTILE + i * 64 * PJ_ROWB) = rw[i];
-  };
-  auto load_step = [&](int kt) { load_part(kt, 0); load_part(kt, 1); };
-  auto store_step = [&](int buf) { store_part(buf, 0); store_part(buf, 1); };
 
   // operand reads: row (32 blk + l32), chunk 2 ks + half, swizzled by the row
   const int sw = (l32 >> 1) & 7;
@@ -291,48 +290,44 @@ __global__ __launch_bounds__(512) void k_project_mfma(ProjectArgs a) {
     for (int e = 0; e < 8; ++e) fb[1][bn][e] = (__bf16)0.f;
 
   const int nk = D / PJ_TK;
-  load_step(0);
-  store_step(0);
-  if (nk > 1) load_step(1);
+  load_part(0, 0, 0);
+  load_part(0, 0, 1);
   int kt = 0;
-  for (; kt + 2 < nk; ++kt) {
-    // step kt is complete in buffer kt & 1 and every wave has read all it needs of the other one
-    pj_lds_barrier();
+  for (; kt + 1 < nk; ++kt) {
+    // the loads of step kt have landed in buffer kt & 1 and every wave has read all it needs of
+    // the other buffer
+    pj_tile_barrier();
     const unsigned char* buf = pj_lds + (kt & 1) * G::STEP;
     const int nb = (kt + 1) & 1;
-    // sub-step 3 of step kt - 1 | operands of sub-step 0, first half of the tile writes
+    // sub-step 3 of step kt - 1 | operands of sub-step 0, first half of the loads of step kt + 1
     read_frags(buf, 0, 0);
-    store_part(nb, 0);
-    mfmas(1);
-    PJ_INTERLEAVE(0x200, BM * BN);
-    __builtin_amdgcn_sched_barrier(0);
-    // sub-step 0 | operands of sub-step 1, second half of the tile writes
-    read_frags(buf, 1, 1);
-    store_part(nb, 1);
-    mfmas(0);
-    PJ_INTERLEAVE(0x200, BM * BN);
-    __builtin_amdgcn_sched_barrier(0);
-    // sub-step 1 | operands of sub-step 2, first half of the loads of step kt + 2
-    read_frags(buf, 2, 0);
-    load_part(kt + 2, 0);
+    load_part(kt + 1, nb, 0);
     mfmas(1);
     PJ_INTERLEAVE(0x020, BM * BN);
     __builtin_amdgcn_sched_barrier(0);
-    // sub-step 2 | operands of sub-step 3, second half of the loads
+    // sub-step 0 | operands of sub-step 1, second half of the loads
+    read_frags(buf, 1, 1);
+    load_part(kt + 1, nb, 1);
+    mfmas(0);
+    PJ_INTERLEAVE(0x020, BM * BN);
+    __builtin_amdgcn_sched_barrier(0);
+    // sub-step 1 | operands of sub-step 2
+    read_frags(buf, 2, 0);
+    mfmas(1);
+    PJ_INTERLEAVE(0x020, BM * BN);
+    __builtin_amdgcn_sched_barrier(0);
+    // sub-step 2 | operands of sub-step 3
     read_frags(buf, 3, 1);
-    load_part(kt + 2, 1);
     mfmas(0);
     PJ_INTERLEAVE(0x020, BM * BN);
     __builtin_amdgcn_sched_barrier(0);
   }
-  for (; kt < nk; ++kt) {                                  // the last two steps: nothing left to load
-    pj_lds_barrier();
+  {                                                        // the last step: nothing left to load
+    pj_tile_barrier();
     const unsigned char* buf = pj_lds + (kt & 1) * G::STEP;
     read_frags(buf, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
     mfmas(1);
-    __builtin_amdgcn_sched_barrier(0);
-    if (kt + 1 < nk) store_step((kt + 1) & 1);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int ks = 0; ks < 3; ++ks) {
