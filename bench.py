@@ -332,6 +332,37 @@ def main():
         "projection_plus_lisa_layer_tokens_per_s": cfg.B * cfg.L / sec_proj_layer,
     }
     del pin, pq, pk, pv
+
+    # NF decoding strategy (Sec. 5.2): the prefill step of a LiSA layer as standard attention that
+    # emits no score tensor (K_LR and V go to the cache through the projection above)
+    def step_nf():
+        s = sets[counter[0] % n_sets]
+        counter[0] += 1
+        i = s["inp"]
+        lisa.std_attn_scores(i["q"], i["k"], i["v"], want_scores=False, out=s["out"], workspace=ws_std)
+
+    extra["nf_prefill_standard_attention_no_scores_ms"] = time_steps(step_nf, max(args.steps // 2, 1), 1) * 1e3
+
+    # variants of the alignment module (Sec. 6.5 ablation, Sec. 6.3, Sec. 4) on the generic kernels
+    variants = {}
+    s0 = sets[0]
+    i0 = s0["inp"]
+    g = torch.Generator(device=dev).manual_seed(3)
+    w_single = (torch.randn((cfg.H, cfg.H), generator=g, device=dev) / cfg.H ** 0.5).to(cfg.torch_dtype)
+    dv = lisa.make_desc(cfg.torch_dtype, cfg.B, cfg.H, cfg.Hkv, cfg.L, cfg.L, cfg.d_k, cfg.r, cfg.F,
+                        act=lisa.ACT_SILU, write_scores=1, out_f32=1)
+    ws_gen = torch.empty(max(lisa.workspace_bytes(dv, lisa.WS_PREFILL), 256), dtype=torch.uint8, device=dev)
+    for name, kw, w1v, w2v, ql, kl in (
+            ("silu", dict(act=lisa.ACT_SILU), i0["w1"], i0["w2"], i0["q_lr"], i0["k_lr"]),
+            ("single_layer", dict(act=lisa.ACT_SINGLE), w_single, None, i0["q_lr"], i0["k_lr"]),
+            ("plus", dict(mix=lisa.MIX_PLUS), None, None, i0["q_lr"], i0["k_lr"]),
+            ("share", dict(mix=lisa.MIX_SHARE), None, None, None, None)):
+        def step_variant():
+            lisa.lisa_attn_prefill(ql, kl, i0["v"], s0["prev"], w1v, w2v, write_scores=True, out=s0["out"],
+                                   scores_out=s0["a_n"], workspace=ws_gen, **kw)
+        variants[name] = {"ms": time_steps(step_variant, 3, 1) * 1e3, "path": lisa.last_path()}
+    extra["alignment_variants"] = variants
+    del ws_gen
     cpu = None
     if not args.no_cpu:
         cpu = cpu_baseline(cfg, sets[0]["inp"], sets[0]["prev"], args.cpu_budget)
