@@ -14,7 +14,8 @@
 //           (k_regroup_v), B = the lane's probabilities as they are.
 // A = Q K^T * scale is stored as half; the softmax works on the float32 values.
 // A workgroup takes two row groups, the x-th longest and the x-th shortest, so that all
-// workgroups stream the same number of tiles.
+// workgroups stream the same number of tiles (large problems), or one row group (problems with
+// fewer than two such workgroups per compute unit: twice the waves in flight).
 #pragma once
 #include "kernels_prefill.h"
 
@@ -29,6 +30,7 @@ struct StdPrefillArgs {
   half_t* scores;         // [B,H,Lq,Lk] or null
   void* out;              // [B,Lq,H,128] or null
   int H, Hkv, Lq, Lk, Lkp, causal, out_f32;
+  int pair;               // 1: a workgroup takes two row groups (grid.y = ceil(n_groups / 2)), 0: one
   float scale;
 };
 
@@ -58,7 +60,7 @@ constexpr int std_prefill_head_lds(bool with_v) {
   return 2 * SP_KTILE + SP_WAVES * SP_STILE + (with_v ? 2 * SP_VTILE : 0);
 }
 
-// grid (H, ceil(n_groups / 2), B) with n_groups = ceil(Lq / 128), block 256.  The head is the
+// grid (H, pair ? ceil(n_groups / 2) : n_groups, B) with n_groups = ceil(Lq / 128), block 256.  The head is the
 // fastest grid index: consecutive workgroups go to different XCDs, so an XCD works on every
 // eighth head and its L2 fetches the K / V of those heads only (they are what every row group
 // of a head re-reads).
@@ -92,7 +94,7 @@ __global__ __launch_bounds__(256, 2) void k_std_prefill(StdPrefillArgs a) {
 
   for (int rep = 0; rep < 2; ++rep) {
     const int grp = rep ? (int)blockIdx.y : n_groups - 1 - (int)blockIdx.y;
-    if (rep && grp >= n_groups - 1 - grp) break;           // the middle group of an odd count is alone
+    if (rep && (!a.pair || grp >= n_groups - 1 - grp)) break;   // (the middle group of an odd count is alone)
     const int i0 = grp * SP_GROUP + wv * SP_ROWS;          // first row of this wave
     const bool have_rows = i0 < Lq;
     const int my_row = min(i0 + r, Lq - 1);

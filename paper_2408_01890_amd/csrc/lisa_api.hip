@@ -506,7 +506,12 @@ int run_std_prefill_fast(const lisa_desc* d, const void* q, const void* k, const
     if (rc) return rc;
   }
   const int n_groups = (d->Lq + SP_GROUP - 1) / SP_GROUP;
-  dim3 grid(d->H, (n_groups + 1) / 2, d->B);
+  // A workgroup takes the x-th longest and the x-th shortest row group (equal work for all) when
+  // that still leaves two workgroups per compute unit; a smaller problem keeps one row group per
+  // workgroup, long ones first, so that every SIMD has two waves while the short ones last.
+  a.pair = (long long)d->H * ((n_groups + 1) / 2) * d->B >= 2 * kComputeUnits;
+  if (const char* e = std::getenv("LISA_STD_PAIR")) a.pair = std::atoi(e) != 0;   // tests force either
+  dim3 grid(d->H, a.pair ? (n_groups + 1) / 2 : n_groups, d->B);
   StageScope prof("k_std_prefill", st);
   if (out)
     k_std_prefill<true><<<grid, 256, 0, st>>>(a);

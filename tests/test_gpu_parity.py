@@ -90,13 +90,16 @@ STD_MFMA_SHAPES = [
 ]
 
 
+@pytest.mark.parametrize("pair", [1, 0])
 @pytest.mark.parametrize("case", STD_MFMA_SHAPES, ids=[c[0] for c in STD_MFMA_SHAPES])
-def test_std_prefill_mfma_kernel_shapes(case):
+def test_std_prefill_mfma_kernel_shapes(case, pair, monkeypatch):
     """The bf16 standard layer on the matrix cores (d_k = 128): scores and output against the
-    oracle in its three call modes, invisible score entries left untouched."""
+    oracle in its three call modes, invisible score entries left untouched; with one and with
+    two row groups per workgroup."""
     from oracle import cref
     name, B, H, Hkv, Lq, Lk, causal = case
-    log(f"[case] std mfma {name}")
+    monkeypatch.setenv("LISA_STD_PAIR", str(pair))
+    log(f"[case] std mfma {name} pair={pair}")
     dt = torch.bfloat16
     g = torch.Generator(device=DEV).manual_seed(23)
     q = torch.randn((B, H, Lq, 128), generator=g, device=DEV).to(dt)
