@@ -332,6 +332,28 @@ def main():
         "projection_plus_lisa_layer_tokens_per_s": cfg.B * cfg.L / sec_proj_layer,
     }
     del pin, pq, pk, pv
+    # the same front end for one decode step of the decode stack's shape: one new token per sequence,
+    # written into the caches at position ctx (bound by one pass over the 45 MB of weights)
+    dstk = synth.C5
+    dcfg = synth.LayerShape("decode_projection", "bf16", dstk.B, dstk.H, dstk.Hkv, 1, dstk.d_model, dstk.d_k,
+                            dstk.r, dstk.F, theta)
+    dpin = synth.make_projection_inputs(dcfg, device=dev)
+    dLmax = dstk.ctx + 128
+    dk_cache = torch.zeros((dstk.B, dstk.Hkv, dstk.r, dLmax), dtype=torch.bfloat16, device=dev)
+    dv_cache = torch.zeros((dstk.B, dstk.Hkv, dLmax, dstk.d_k), dtype=torch.bfloat16, device=dev)
+    dq = torch.zeros((dstk.B, dstk.H, 1, dstk.r), dtype=torch.bfloat16, device=dev)
+
+    def step_proj_decode():
+        lisa.lisa_project_qkv(dpin["x"], dpin["w"], dstk.H, dstk.Hkv, dstk.r, dstk.d_k, rope_theta=theta,
+                              pos0=dstk.ctx, q_lr=dq, k_lr=dk_cache, v=dv_cache, dim_major=True)
+
+    sec_pd = time_steps(step_proj_decode, max(args.steps, 1), 2)
+    wbytes = dpin["w"].numel() * 2
+    extra["projection"]["decode_step_B64"] = {
+        "path": lisa.last_path(), "us": sec_pd * 1e6, "weight_MB": wbytes / 1e6,
+        "hbm_frac": wbytes / sec_pd / 1e9 / HBM_PEAK_GBS,
+    }
+    del dpin, dk_cache, dv_cache, dq
 
     # NF decoding strategy (Sec. 5.2): the prefill step of a LiSA layer as standard attention that
     # emits no score tensor (K_LR and V go to the cache through the projection above)

@@ -512,4 +512,110 @@ __global__ __launch_bounds__(512) void k_project_mfma(ProjectArgs a) {
   }
 }
 
+// ---- bf16, few token rows (a decode step: one new token per sequence) ---------------------
+// With M = B L <= 128 rows the product is bound by one pass over the weights (HBM), not by the
+// matrix cores.  One workgroup = one block of 32 virtual columns (a Q_LR / K_LR head, or 32
+// features of V) and all rows; its 8 waves split the reduction axis and stream their slices of
+// the weight rows and of X straight into MFMA operand registers (no LDS: nothing is reused),
+// then add their partial sums through the LDS.  Wave mb < MB finishes row block mb: rotation,
+// rounding and element stores (few outputs).
+template <int MB>
+__global__ __launch_bounds__(512) void k_project_skinny(ProjectArgs a) {
+  extern __shared__ __align__(16) unsigned char pj_lds[];
+  float* red = (float*)pj_lds;                              // [8 waves][MB][16][64]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int half = lane >> 5, l32 = lane & 31;
+  const int M = a.B * a.L, D = a.D;
+  const int nheads_qk = a.H + a.Hkv;
+  const int nv_qk = PJ_HEADW * nheads_qk;
+  const int n_real = nheads_qk * a.r + a.Hkv * a.dk;
+  const int nvb = blockIdx.x * 32;                          // first virtual column of the block
+  int real;
+  if (nvb < nv_qk) {
+    real = (nvb >> 5) * a.r + min(l32, a.r - 1);
+  } else {
+    real = nheads_qk * a.r + (nvb - nv_qk) + l32;
+  }
+  const bf16_t* wrow = (const bf16_t*)a.w + (size_t)min(real, n_real - 1) * D + 8 * half;
+  const bf16_t* xrow[MB];
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+    xrow[mb] = (const bf16_t*)a.x + (size_t)min(mb * 32 + l32, M - 1) * D + 8 * half;
+
+  pj_f32x16 acc[MB];
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[mb][v] = 0.f;
+  const int nsteps = D / 16, per = (nsteps + 7) / 8;
+  const int s0 = wv * per, s1 = min(s0 + per, nsteps);
+#pragma unroll 8
+  for (int s = s0; s < s1; ++s) {
+    const pj_bf16x8 bop = *(const pj_bf16x8*)(wrow + 16 * s);
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      const pj_bf16x8 aop = *(const pj_bf16x8*)(xrow[mb] + 16 * s);
+      acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop, bop, acc[mb], 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) red[((wv * MB + mb) * 16 + v) * 64 + lane] = acc[mb][v];
+  __syncthreads();
+  if (wv >= MB) return;
+  const int mb = wv;
+  float y[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    float sum = 0.f;
+#pragma unroll
+    for (int w = 0; w < 8; ++w) sum += red[((w * MB + mb) * 16 + v) * 64 + lane];
+    y[v] = sum;
+  }
+  // acc layout: token row 32 mb + 8 (v/4) + 4 half + v%4, virtual column nvb + l32
+  int head, c;
+  bool valid;
+  if (nvb < nv_qk) {
+    head = nvb >> 5;
+    c = l32;
+    valid = c < a.r;
+  } else {
+    const int col = nvb - nv_qk + l32;
+    head = nheads_qk + col / a.dk;
+    c = col % a.dk;
+    valid = col < a.Hkv * a.dk;
+  }
+  const bool rot = a.rope && nvb < nv_qk;
+  const int hr = a.r >> 1;
+  const bool lower = c < hr;
+  double inv_freq_rev = 0.0;
+  int partner = lane;
+  if (rot) {
+    const int t = lower ? c : c - hr;
+    inv_freq_rev = exp2((double)min(t, hr - 1) * a.freq_log2) * 0.15915494309189535;
+    partner = (lane & 32) | (valid ? (lower ? c + hr : c - hr) : l32);
+  }
+  bf16_t* dst_base = (bf16_t*)(head < a.H ? a.q_lr : head < nheads_qk ? a.k_lr : a.v);
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int m = mb * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+    const int mc = min(m, M - 1);
+    const int b = mc / a.L, l = mc - b * a.L;
+    float out = y[v];
+    if (rot) {
+      const float other = __shfl(out, partner, 64);
+      float cs, sn;
+      rope_cos_sin_fast(a.pos0 + l, inv_freq_rev, cs, sn);
+      out = lower ? out * cs - other * sn : other * sn + out * cs;
+    }
+    if (valid && m < M) {
+      int which;
+      const size_t at = project_dest(a, b, l, head, c, which);
+      dst_base[at].bits = (uint16_t)f32_to_bf16_bits(out);
+    }
+  }
+}
+
 }  // namespace lisa

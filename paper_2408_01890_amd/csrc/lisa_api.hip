@@ -588,7 +588,23 @@ int lisa_project_qkv(const lisa_proj_desc* d, const void* x, const void* w, void
   const bool fast = d->dtype == LISA_BF16 && d->d_model % PJ_TK == 0 && d->r <= PJ_HEADW &&
                     d->d_k % 32 == 0;
   const char* path;
-  if (fast) {
+  if (fast && M <= 128) {
+    // a decode step: few rows, bound by one pass over the weights
+    const long long n_virtual = (long long)PJ_HEADW * (d->H + d->Hkv) + (long long)d->Hkv * d->d_k;
+    const int mb = (int)((M + 31) / 32);
+    const int lds = 8 * mb * 16 * 64 * (int)sizeof(float);
+    StageScope scope("k_project_skinny", st);
+    auto launch = [&](auto kern) -> int {
+      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+      if (e != hipSuccess) return hip_fail(e);
+      kern<<<dim3((unsigned)((n_virtual + 31) / 32)), 512, lds, st>>>(a);
+      return LISA_OK;
+    };
+    int lrc = mb == 1 ? launch(k_project_skinny<1>) : mb == 2 ? launch(k_project_skinny<2>)
+            : mb == 3 ? launch(k_project_skinny<3>) : launch(k_project_skinny<4>);
+    if (lrc) return lrc;
+    path = "project_skinny";
+  } else if (fast) {
     const long long n_virtual = (long long)PJ_HEADW * (d->H + d->Hkv) + (long long)d->Hkv * d->d_k;
     // tile width: the one whose workgroups fill the 256 CUs in fewer, fuller rounds (a round costs
     // in proportion to the tile width); the wider tile on a tie

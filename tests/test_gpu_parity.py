@@ -622,11 +622,22 @@ PROJ_MFMA = [
     (2, 8, 8, 300, 256, 128, 22, 10000.0, 0, False, 0),     # 3 ragged row tiles x 6 column tiles
     (1, 8, 2, 257, 128, 128, 22, 500000.0, 7, True, 5),     # GQA: a column tile holds K_LR heads and V
     (3, 4, 4, 50, 64, 32, 8, None, 0, False, 0),            # one reduction step, sequences inside a row block
-    (1, 16, 16, 64, 192, 64, 32, 10000.0, 1000, True, 0),   # r = 32: no padded columns
+    (1, 16, 16, 160, 192, 64, 32, 10000.0, 1000, True, 0),  # r = 32: no padded columns
     (1, 40, 40, 130, 320, 128, 22, None, 0, False, 2),      # 40 heads
-    (1, 2, 1, 70, 64, 128, 16, 10000.0, 0, False, 0),       # odd head count: V starts inside a wave's columns
-    (2, 4, 4, 40, 64, 96, 10, None, 3, True, 1),            # d_k = 96: V leaves block by block
-    (2, 4, 2, 33, 128, 32, 7, None, 0, False, 0),           # odd r (no rotation): element stores
+    (1, 2, 1, 170, 64, 128, 16, 10000.0, 0, False, 0),      # odd head count: V starts inside a wave's columns
+    (2, 4, 4, 90, 64, 96, 10, None, 3, True, 1),            # d_k = 96: V leaves block by block
+    (2, 4, 2, 97, 128, 32, 7, None, 0, False, 0),           # odd r (no rotation): element stores
+]
+
+# at most 128 token rows (decode steps): the kernel that streams the weights once
+PROJ_SKINNY = [
+    (64, 32, 32, 1, 256, 128, 22, 10000.0, 4096, True, 7),  # one new token per sequence into dimension-major caches
+    (3, 8, 2, 1, 128, 128, 22, 500000.0, 9, False, 2),      # GQA, three rows
+    (1, 16, 16, 64, 192, 64, 32, 10000.0, 1000, True, 0),   # r = 32, two row blocks
+    (1, 2, 1, 70, 64, 128, 16, 10000.0, 0, False, 0),       # odd head count, ragged third row block
+    (2, 4, 4, 40, 64, 96, 10, None, 3, True, 1),            # d_k = 96, sequences inside a row block
+    (2, 4, 2, 33, 128, 32, 7, None, 0, False, 0),           # odd r
+    (1, 8, 8, 128, 2048, 128, 22, 10000.0, 0, False, 0),    # 128 rows (the most), a long reduction axis
 ]
 
 
@@ -641,6 +652,26 @@ def test_projection_mfma_kernel_shapes(case, tile_n, monkeypatch):
     path = check_projection(cfg, pin, {b: np.arange(L) for b in range(B)}, theta, pos0, dim_major,
                             pos0 + L + extra)
     assert path == "project_mfma"
+
+
+@pytest.mark.parametrize("case", PROJ_SKINNY, ids=lambda c: f"B{c[0]}H{c[1]}-{c[2]}L{c[3]}d{c[4]}r{c[6]}")
+def test_projection_skinny_kernel_shapes(case):
+    B, H, Hkv, L, D, dk, r, theta, pos0, dim_major, extra = case
+    log(f"[case] projection skinny {case}")
+    cfg = synth.LayerShape("proj_skinny", "bf16", B, H, Hkv, L, D, dk, r, 64, theta)
+    pin = synth.make_projection_inputs(cfg, device=DEV)
+    path = check_projection(cfg, pin, {b: np.arange(L) for b in range(B)}, theta, pos0, dim_major,
+                            pos0 + L + extra)
+    assert path == "project_skinny"
+
+
+def test_projection_decode_size_full_width():
+    """One new token for each of 64 sequences at the LLaMA2-7B width (d = 4096, 5504 features)."""
+    cfg = synth.LayerShape("proj_decode_c5", "bf16", 64, 32, 32, 1, 4096, 128, 22, 64, 10000.0)
+    log("[case] projection decode size, full width")
+    pin = synth.make_projection_inputs(cfg, device=DEV)
+    path = check_projection(cfg, pin, {b: np.arange(1) for b in (0, 17, 63)}, 10000.0, 4096, True, 4224)
+    assert path == "project_skinny"
 
 
 @pytest.mark.parametrize("name", ["c2_llama2_7b_l2048", "c3_llama3_8b_gqa_l8192"])
