@@ -72,7 +72,9 @@ typedef enum {
   LISA_ERR_HIP = -6          /* a HIP launch failed; see lisa_last_hip_error()          */
 } lisa_status;
 
-typedef enum { LISA_WS_PREFILL = 0, LISA_WS_DECODE = 1, LISA_WS_STD = 2, LISA_WS_LAYER = 3 } lisa_ws_kind;
+typedef enum {
+  LISA_WS_PREFILL = 0, LISA_WS_DECODE = 1, LISA_WS_STD = 2, LISA_WS_LAYER = 3, LISA_WS_LAYER_DECODE = 4
+} lisa_ws_kind;
 
 /* Problem descriptor (host memory, plain data, zero-initialise then fill). */
 typedef struct lisa_desc {
@@ -219,6 +221,22 @@ int lisa_layer_prefill(const lisa_desc* desc, int32_t d_model, float rope_theta,
                        const void* w_qkv, const void* scores_prev, const void* w1, const void* w2,
                        void* out, void* scores_out, void* workspace, size_t workspace_bytes,
                        void* hip_stream);
+
+/*
+ * lisa_layer_decode -- the decode step of a whole LiSA layer from the hidden state of the new
+ * token of every sequence: lisa_project_qkv for one token at position Lk-1 (its rotated K_LR row
+ * and its V row go straight into the caches, Sec. 5.2) followed by lisa_attn_decode.
+ * Requires Lq = 1 and Lk <= Lmax.
+ *   x [B,d_model], w_qkv [H*r + Hkv*r + Hkv*d_k, d_model]     in   as in lisa_project_qkv
+ *   k_lr_cache, v_cache                                        in/out (only index Lk-1 is written)
+ *   score_row_prev, w1, w2, out, score_row_out                 as in lisa_attn_decode
+ *   workspace   at least lisa_workspace_bytes(desc, LISA_WS_LAYER_DECODE) bytes (the decode
+ *               workspace followed by Q_LR [B,H,r])
+ */
+int lisa_layer_decode(const lisa_desc* desc, int32_t d_model, float rope_theta, const void* x,
+                      const void* w_qkv, void* k_lr_cache, void* v_cache, const void* score_row_prev,
+                      const void* w1, const void* w2, void* out, void* score_row_out, void* workspace,
+                      size_t workspace_bytes, void* hip_stream);
 
 /* Host-only helpers (no HIP call). */
 

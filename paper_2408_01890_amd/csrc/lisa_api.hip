@@ -693,9 +693,47 @@ size_t lisa_workspace_bytes(const lisa_desc* desc, int which) {
       const size_t e = desc->dtype == LISA_F32 ? 4 : 2;
       return v + round_up((size_t)desc->B * desc->Hkv * desc->Lq * desc->d_k * e, 256);
     }
+    case LISA_WS_LAYER_DECODE: {
+      if (check_decode(desc) != LISA_OK || !has_delta(desc)) return 0;
+      const size_t e = desc->dtype == LISA_F32 ? 4 : 2;
+      return round_up(lisa_workspace_bytes(desc, LISA_WS_DECODE), 256) +
+             round_up((size_t)desc->B * desc->H * desc->r * e, 256);
+    }
     default:
       return 0;
   }
+}
+
+int lisa_layer_decode(const lisa_desc* desc, int32_t d_model, float rope_theta, const void* x,
+                      const void* w_qkv, void* k_lr_cache, void* v_cache, const void* score_row_prev,
+                      const void* w1, const void* w2, void* out, void* score_row_out, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+  int rc = check_decode(desc);
+  if (rc) return rc;
+  if (!has_delta(desc)) return LISA_ERR_UNSUPPORTED;       // nothing to project for: use lisa_attn_decode
+  if (!x || !w_qkv || !k_lr_cache || !v_cache || !score_row_prev || !out) return LISA_ERR_NULL;
+  if (!workspace) return LISA_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return LISA_ERR_ALIGN;
+  if (workspace_bytes < lisa_workspace_bytes(desc, LISA_WS_LAYER_DECODE)) return LISA_ERR_WORKSPACE;
+  const size_t qo = round_up(lisa_workspace_bytes(desc, LISA_WS_DECODE), 256);
+  lisa_proj_desc pd{};
+  pd.dtype = desc->dtype;
+  pd.B = desc->B;
+  pd.L = 1;
+  pd.d_model = d_model;
+  pd.H = desc->H;
+  pd.Hkv = desc->Hkv;
+  pd.r = desc->r;
+  pd.d_k = desc->d_k;
+  pd.Lmax = desc->Lmax;
+  pd.pos0 = desc->Lk - 1;
+  pd.kcache_dim_major = desc->kcache_dim_major;
+  pd.rope_theta = rope_theta;
+  char* ws = (char*)workspace;
+  rc = lisa_project_qkv(&pd, x, w_qkv, ws + qo, k_lr_cache, v_cache, hip_stream);
+  if (rc) return rc;
+  return lisa_attn_decode(desc, ws + qo, nullptr, nullptr, k_lr_cache, v_cache, score_row_prev, w1, w2, out,
+                          score_row_out, workspace, qo, hip_stream);
 }
 
 int lisa_layer_offsets(const lisa_desc* desc, size_t* q_lr_off, size_t* k_lr_off, size_t* v_off) {

@@ -20,14 +20,14 @@ LIB_PATH = os.path.join(_HERE, "liblisa_mi355x.so")
 F32, BF16 = 0, 1
 MIX_ADD, MIX_CONCAT, MIX_PLUS, MIX_SHARE = 0, 1, 2, 3
 ACT_RELU, ACT_SILU, ACT_SINGLE = 0, 1, 2
-WS_PREFILL, WS_DECODE, WS_STD, WS_LAYER = 0, 1, 2, 3
+WS_PREFILL, WS_DECODE, WS_STD, WS_LAYER, WS_LAYER_DECODE = 0, 1, 2, 3, 4
 
 EXPORTS = (
     "lisa_attn_prefill", "lisa_attn_decode", "std_attn_scores", "lisa_workspace_bytes",
     "lisa_scores_bytes", "lisa_score_elem_bytes", "lisa_kcache_saved_bytes", "lisa_supported",
     "lisa_strerror", "lisa_last_hip_error", "lisa_last_path", "lisa_profile_enable",
     "lisa_profile_collect", "lisa_cache_fill", "lisa_project_qkv", "lisa_layer_prefill",
-    "lisa_layer_offsets",
+    "lisa_layer_offsets", "lisa_layer_decode",
 )
 
 
@@ -105,6 +105,8 @@ def _lib():
         h.lisa_project_qkv.restype = C.c_int
         h.lisa_layer_prefill.argtypes = [dp, C.c_int32, C.c_float] + [vp] * 8 + [sz, vp]
         h.lisa_layer_prefill.restype = C.c_int
+        h.lisa_layer_decode.argtypes = [dp, C.c_int32, C.c_float] + [vp] * 10 + [sz, vp]
+        h.lisa_layer_decode.restype = C.c_int
         h.lisa_layer_offsets.argtypes = [dp] + [C.POINTER(sz)] * 3
         h.lisa_layer_offsets.restype = C.c_int
         h.lisa_profile_collect.argtypes = [C.POINTER(StageTime), C.c_int]
@@ -378,6 +380,47 @@ def lisa_layer_prefill(x, w_qkv, Hkv, r, d_k, scores_prev, w1, w2, *, rope_theta
 
     qkv = (view(offs[0], (B, H, L, r)), view(offs[1], (B, Hkv, L, r)), view(offs[2], (B, Hkv, L, d_k)))
     return out, (scores_out if write_scores else None), qkv
+
+
+def lisa_layer_decode(x, w_qkv, k_lr_cache, v_cache, Lk, score_row_prev, w1, w2, *, rope_theta=0.0,
+                      dim_major=True, mix=MIX_ADD, act=ACT_RELU, write_scores=True, out=None,
+                      out_dtype=None, score_row_out=None, workspace=None):
+    """Decode step of a whole LiSA layer from the hidden states x [B,d] of the new tokens (position
+    Lk-1): projection straight into the caches, then lisa_attn_decode.
+    Returns (out [B,H,d_k], score_row_out [B,H,Lk] or None)."""
+    B, D = x.shape
+    _, H, _ = score_row_prev.shape
+    _, Hkv, Lmax, dk = v_cache.shape
+    r = k_lr_cache.shape[2] if dim_major else k_lr_cache.shape[3]
+    has_ffn = mix in (MIX_ADD, MIX_CONCAT)
+    Din, F = w1.shape if has_ffn else (0, 0)
+    if not has_ffn:
+        w1 = w2 = None
+    elif act == ACT_SINGLE:
+        w2 = None
+    dt = x.dtype
+    sdt = score_dtype(dt)
+    odt, of32 = _out_dtype(dt, out.dtype if out is not None else out_dtype)
+    desc = make_desc(dt, B, H, Hkv, 1, Lk, dk, r, F, mix=mix, act=act, write_scores=int(write_scores),
+                     kcache_dim_major=int(dim_major), Lmax=Lmax, out_f32=of32)
+    kshape = (B, Hkv, r, Lmax) if dim_major else (B, Hkv, Lmax, r)
+    if out is None:
+        out = torch.empty((B, H, dk), dtype=odt, device=x.device)
+    if write_scores and score_row_out is None:
+        score_row_out = torch.empty((B, H, Lk), dtype=sdt, device=x.device)
+    need = workspace_bytes(desc, WS_LAYER_DECODE)
+    if need == 0:
+        raise LisaError(supported(desc) or -2, "lisa_layer_decode")
+    workspace, wp, wb = _workspace(need, x, workspace)
+    rc = _lib().lisa_layer_decode(
+        C.byref(desc), D, float(rope_theta or 0.0), _ptr(x, "x", dtype=dt),
+        _ptr(w_qkv, "w_qkv", ((H + Hkv) * r + Hkv * dk, D), dt), _ptr(k_lr_cache, "k_lr_cache", kshape, dt),
+        _ptr(v_cache, "v_cache", dtype=dt), _ptr(score_row_prev, "score_row_prev", (B, H, Lk), sdt),
+        _ptr(w1, "w1", (Din, F), dt), _ptr(w2, "w2", (F, H), dt), _ptr(out, "out", (B, H, dk), odt),
+        _ptr(score_row_out if write_scores else None, "score_row_out", (B, H, Lk), sdt), wp, wb, _stream())
+    if rc:
+        raise LisaError(rc, "lisa_layer_decode")
+    return out, (score_row_out if write_scores else None)
 
 
 def lisa_attn_decode(q_lr, k_lr_cache, v_cache, Lk, score_row_prev, w1, w2, *, k_lr_new=None,

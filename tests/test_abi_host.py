@@ -175,6 +175,21 @@ def test_variant_descriptors_are_validated():
     assert lib.lisa_attn_prefill(C.byref(relu), FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, None, FAKE, big, None) == -1
 
 
+def test_layer_decode_workspace_and_argument_checks():
+    lib = lisa.library()
+    d = lisa.make_desc(lisa.BF16, 4, 32, 8, 1, 300, 128, 22, 64, write_scores=1, kcache_dim_major=1, Lmax=320)
+    dec = lisa.workspace_bytes(d, lisa.WS_DECODE)
+    total = lisa.workspace_bytes(d, lisa.WS_LAYER_DECODE)
+    assert total >= dec + 4 * 32 * 22 * 2
+    args = [FAKE] * 9
+    assert lib.lisa_layer_decode(C.byref(d), 4096, 1.0e4, *args, FAKE, total - 1, None) == -5
+    assert lib.lisa_layer_decode(C.byref(d), 4096, 1.0e4, FAKE, None, *args[2:], FAKE, total, None) == -1
+    full = lisa.make_desc(lisa.BF16, 4, 32, 8, 1, 400, 128, 22, 64, kcache_dim_major=1, Lmax=320)   # Lk > Lmax
+    assert lib.lisa_layer_decode(C.byref(full), 4096, 1.0e4, *args, FAKE, 1 << 40, None) == -2
+    share = lisa.make_desc(lisa.BF16, 4, 32, 8, 1, 300, 128, 0, 0, mix=lisa.MIX_SHARE, Lmax=320)
+    assert lib.lisa_layer_decode(C.byref(share), 4096, 1.0e4, *args, FAKE, 1 << 40, None) == -3
+
+
 def test_strerror_is_defined_for_every_status():
     lib = lisa.library()
     seen = set()

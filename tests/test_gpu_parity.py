@@ -851,10 +851,8 @@ def test_nf_strategy_standard_prefill_then_lisa_decode(dim_major):
     q_prev_new = aux["q"][:, :, L:L + 1].contiguous()
     row_prev, _ = lisa.std_attn_scores(q_prev_new, aux["k"])               # [B,H,1,L+1]
     row_prev = row_prev[:, :, 0, :].contiguous()
-    q_new, _, _ = lisa.lisa_project_qkv(x_new, w, H, Hkv, r, dk, rope_theta=cfg.rope_theta, pos0=L,
-                                        k_lr=k_cache, v=v_cache, dim_major=dim_major)
-    o_d, a_d = lisa.lisa_attn_decode(q_new[:, :, 0, :].contiguous(), k_cache, v_cache, L + 1, row_prev,
-                                     aux["w1"], aux["w2"], dim_major=dim_major)
+    o_d, a_d = lisa.lisa_layer_decode(x_new[:, 0].contiguous(), w, k_cache, v_cache, L + 1, row_prev,
+                                      aux["w1"], aux["w2"], rope_theta=cfg.rope_theta, dim_major=dim_major)
     torch.cuda.synchronize()
     worst_o = worst_a = 0.0
     for b in range(B):
