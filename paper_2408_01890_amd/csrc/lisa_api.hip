@@ -674,14 +674,52 @@ size_t lisa_kcache_saved_bytes(const lisa_desc* desc, int n_lisa_layers) {
   return (size_t)n_lisa_layers * desc->B * desc->Hkv * desc->Lk * (size_t)(desc->d_k - desc->r) * e;
 }
 
+// The single-layer alignment FFN (y = W^T x) and LiSA_plus (y = x) are two-layer ReLU networks
+// in disguise ([W,-W] then [I;-I]: relu(u) - relu(-u) = u), so they can run on the MFMA kernels,
+// which implement ADD with ReLU: `eq` receives the equivalent descriptor (F = 2H).  The hidden
+// units pass through half precision there, as for the two-layer form.
+bool relu_equivalent(const lisa_desc* d, lisa_desc* eq) {
+  if (d->dtype != LISA_BF16) return false;
+  const bool single = d->mix == LISA_MIX_ADD && d->act == LISA_ACT_SINGLE;
+  if (!single && d->mix != LISA_MIX_PLUS) return false;
+  if (2 * d->H > 128) return false;
+  *eq = *d;
+  eq->mix = LISA_MIX_ADD;
+  eq->act = LISA_ACT_RELU;
+  eq->F = 2 * d->H;
+  return true;
+}
+size_t synth_ffn_bytes(const lisa_desc* d) { return round_up((size_t)4 * d->H * d->H * 2, 256); }
+
+// Writes the equivalent weights behind `offset` bytes of the workspace; returns their addresses.
+int synth_relu_ffn(const lisa_desc* d, const void* w1_user, void* workspace, size_t offset, const void** w1o,
+                   const void** w2o, hipStream_t st) {
+  bf16_t* a = (bf16_t*)((char*)workspace + offset);
+  bf16_t* b = a + (size_t)2 * d->H * d->H;
+  StageScope prof("k_synth_relu_ffn", st);
+  k_synth_relu_ffn<bf16_t><<<(4 * d->H * d->H + 255) / 256, 256, 0, st>>>(
+      d->mix == LISA_MIX_PLUS ? nullptr : (const bf16_t*)w1_user, a, b, d->H);
+  *w1o = a;
+  *w2o = b;
+  return check_launch();
+}
+
 size_t lisa_workspace_bytes(const lisa_desc* desc, int which) {
   switch (which) {
-    case LISA_WS_PREFILL:
+    case LISA_WS_PREFILL: {
       if (check_lisa(desc) != LISA_OK) return 0;
+      lisa_desc eq;
+      if (relu_equivalent(desc, &eq) && prefill_fused_ok(&eq))
+        return round_up(prefill_fused_ws(&eq).total, 256) + synth_ffn_bytes(desc);
       return prefill_fused_ok(desc) ? prefill_fused_ws(desc).total : exact_bytes(desc);
-    case LISA_WS_DECODE:
+    }
+    case LISA_WS_DECODE: {
       if (check_decode(desc) != LISA_OK) return 0;
+      lisa_desc eq;
+      if (relu_equivalent(desc, &eq) && decode_fast_ok(&eq, true))
+        return round_up(decode_fast_bytes(&eq), 256) + synth_ffn_bytes(desc);
       return decode_fast_ok(desc, true) ? decode_fast_bytes(desc) : exact_bytes(desc);
+    }
     case LISA_WS_STD:
       if (check_common(desc) != LISA_OK) return 0;
       // needed only when `out` is requested
@@ -857,6 +895,13 @@ int lisa_attn_prefill(const lisa_desc* desc, const void* q_lr, const void* k_lr,
   const KeyStrides vs = dense_keys(desc, desc->Lk, desc->d_k);
   if (prefill_fused_ok(desc))
     return run_prefill_fused(desc, q_lr, k_lr, v, scores_prev, w1, w2, out, scores, workspace, st);
+  lisa_desc eq;
+  if (relu_equivalent(desc, &eq) && prefill_fused_ok(&eq)) {
+    const void *w1e, *w2e;
+    rc = synth_relu_ffn(desc, w1, workspace, round_up(prefill_fused_ws(&eq).total, 256), &w1e, &w2e, st);
+    if (rc) return rc;
+    return run_prefill_fused(&eq, q_lr, k_lr, v, scores_prev, w1e, w2e, out, scores, workspace, st);
+  }
   if (desc->dtype == LISA_F32)
     return run_lisa<float, float>(desc, q_lr, k_lr, ks, v, vs, scores_prev, w1, w2, out, scores,
                                   exact, st);
@@ -903,7 +948,14 @@ int lisa_attn_decode(const lisa_desc* desc, const void* q_lr, const void* k_lr_n
     rc = check_launch();
     if (rc) return rc;
   }
-  if (decode_fast_ok(desc, true)) {
+  lisa_desc eq;
+  const lisa_desc* eff = desc;                             // the descriptor the fast kernels see
+  if (!decode_fast_ok(desc, true) && relu_equivalent(desc, &eq) && decode_fast_ok(&eq, true)) {
+    rc = synth_relu_ffn(desc, w1, workspace, round_up(decode_fast_bytes(&eq), 256), &w1, &w2, st);
+    if (rc) return rc;
+    eff = &eq;
+  }
+  if (decode_fast_ok(eff, true)) {
     DecodeArgs a{};
     a.q = (const bf16_t*)q_lr;
     a.kc = (const bf16_t*)k_lr_cache;
@@ -914,7 +966,7 @@ int lisa_attn_decode(const lisa_desc* desc, const void* q_lr, const void* k_lr_n
     a.w1 = (const bf16_t*)w1;
     a.w2 = (const bf16_t*)w2;
     a.row_out = (half_t*)scores;
-    return run_decode_fast(desc, true, a, out, workspace, st);
+    return run_decode_fast(eff, true, a, out, workspace, st);
   }
   if (desc->dtype == LISA_F32)
     return run_lisa<float, float>(desc, q_lr, k_lr_cache, ks, v_cache, vs, score_row_prev, w1, w2,
