@@ -305,4 +305,11 @@ __global__ __launch_bounds__(256) void k_synth_relu_ffn(const T* __restrict__ w1
   }
 }
 
+// Zero fill in 16-byte pieces (n16 of them), for scratch operands; a kernel rather than a memset so
+// that callers may capture the launch in a graph.  grid ceil(n16 / 256), block 256.
+__global__ __launch_bounds__(256) void k_zero16(uint4* __restrict__ p, size_t n16) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n16) p[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
 }  // namespace lisa

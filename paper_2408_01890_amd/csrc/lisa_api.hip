@@ -674,33 +674,64 @@ size_t lisa_kcache_saved_bytes(const lisa_desc* desc, int n_lisa_layers) {
   return (size_t)n_lisa_layers * desc->B * desc->Hkv * desc->Lk * (size_t)(desc->d_k - desc->r) * e;
 }
 
-// The single-layer alignment FFN (y = W^T x) and LiSA_plus (y = x) are two-layer ReLU networks
-// in disguise ([W,-W] then [I;-I]: relu(u) - relu(-u) = u), so they can run on the MFMA kernels,
-// which implement ADD with ReLU: `eq` receives the equivalent descriptor (F = 2H).  The hidden
-// units pass through half precision there, as for the two-layer form.
+// The single-layer alignment FFN (y = W^T x), LiSA_plus (y = x) and direct sharing (y = x, no
+// correction) are two-layer ReLU networks in disguise ([W,-W] then [I;-I]: relu(u) - relu(-u) = u),
+// so they can run on the MFMA kernels, which implement ADD with ReLU: `eq` receives the
+// equivalent descriptor (F = 2H).  The hidden units pass through half precision there, as for the
+// two-layer form.  Direct sharing gets all-zero low-rank operands of width kShareRank, built in
+// the workspace, so that its correction is exactly zero.
+constexpr int kShareRank = 8;
 bool relu_equivalent(const lisa_desc* d, lisa_desc* eq) {
   if (d->dtype != LISA_BF16) return false;
   const bool single = d->mix == LISA_MIX_ADD && d->act == LISA_ACT_SINGLE;
-  if (!single && d->mix != LISA_MIX_PLUS) return false;
+  if (!single && d->mix != LISA_MIX_PLUS && d->mix != LISA_MIX_SHARE) return false;
   if (2 * d->H > 128) return false;
   *eq = *d;
   eq->mix = LISA_MIX_ADD;
   eq->act = LISA_ACT_RELU;
   eq->F = 2 * d->H;
+  if (d->mix == LISA_MIX_SHARE) eq->r = kShareRank;
   return true;
 }
-size_t synth_ffn_bytes(const lisa_desc* d) { return round_up((size_t)4 * d->H * d->H * 2, 256); }
+// Scratch behind the kernels' own workspace: the equivalent weights, then (direct sharing) the
+// zero Q_LR [B,H,Lq,r0] and the zero K_LR (Lq > 1: [B,Hkv,Lk,r0]; decode: the cache shape).
+struct SynthWs {
+  size_t w, q0, k0, total;
+};
+SynthWs synth_ws(const lisa_desc* d) {
+  SynthWs s;
+  s.w = 0;
+  s.q0 = round_up((size_t)4 * d->H * d->H * 2, 256);
+  s.k0 = s.q0;
+  s.total = s.q0;
+  if (d->mix == LISA_MIX_SHARE) {
+    const size_t klen = d->Lq == 1 ? (size_t)d->Lmax : (size_t)d->Lk;
+    s.k0 = s.q0 + round_up((size_t)d->B * d->H * d->Lq * kShareRank * 2, 256);
+    s.total = s.k0 + round_up((size_t)d->B * d->Hkv * klen * kShareRank * 2, 256);
+  }
+  return s;
+}
+size_t synth_ffn_bytes(const lisa_desc* d) { return synth_ws(d).total; }
 
-// Writes the equivalent weights behind `offset` bytes of the workspace; returns their addresses.
+// Writes the equivalent operands behind `offset` bytes of the workspace; returns their addresses
+// (q_lr / k_lr are replaced only for direct sharing).
 int synth_relu_ffn(const lisa_desc* d, const void* w1_user, void* workspace, size_t offset, const void** w1o,
-                   const void** w2o, hipStream_t st) {
-  bf16_t* a = (bf16_t*)((char*)workspace + offset);
+                   const void** w2o, const void** q_lr, const void** k_lr, hipStream_t st) {
+  const SynthWs sw = synth_ws(d);
+  char* base = (char*)workspace + offset;
+  bf16_t* a = (bf16_t*)(base + sw.w);
   bf16_t* b = a + (size_t)2 * d->H * d->H;
   StageScope prof("k_synth_relu_ffn", st);
   k_synth_relu_ffn<bf16_t><<<(4 * d->H * d->H + 255) / 256, 256, 0, st>>>(
-      d->mix == LISA_MIX_PLUS ? nullptr : (const bf16_t*)w1_user, a, b, d->H);
+      d->act == LISA_ACT_SINGLE && d->mix == LISA_MIX_ADD ? (const bf16_t*)w1_user : nullptr, a, b, d->H);
   *w1o = a;
   *w2o = b;
+  if (d->mix == LISA_MIX_SHARE) {
+    const size_t n16 = (sw.total - sw.q0) / 16;
+    k_zero16<<<(unsigned)((n16 + 255) / 256), 256, 0, st>>>((uint4*)(base + sw.q0), n16);
+    *q_lr = base + sw.q0;
+    *k_lr = base + sw.k0;
+  }
   return check_launch();
 }
 
@@ -898,7 +929,8 @@ int lisa_attn_prefill(const lisa_desc* desc, const void* q_lr, const void* k_lr,
   lisa_desc eq;
   if (relu_equivalent(desc, &eq) && prefill_fused_ok(&eq)) {
     const void *w1e, *w2e;
-    rc = synth_relu_ffn(desc, w1, workspace, round_up(prefill_fused_ws(&eq).total, 256), &w1e, &w2e, st);
+    rc = synth_relu_ffn(desc, w1, workspace, round_up(prefill_fused_ws(&eq).total, 256), &w1e, &w2e, &q_lr, &k_lr,
+                        st);
     if (rc) return rc;
     return run_prefill_fused(&eq, q_lr, k_lr, v, scores_prev, w1e, w2e, out, scores, workspace, st);
   }
@@ -932,7 +964,7 @@ int lisa_attn_decode(const lisa_desc* desc, const void* q_lr, const void* k_lr_n
   void* scores = desc->write_scores ? score_row_out : nullptr;
   float* exact = (float*)workspace;
   hipStream_t st = (hipStream_t)hip_stream;
-  const KeyStrides ks = desc->kcache_dim_major ? dim_major_keys(desc, desc->Lmax, desc->r)
+  KeyStrides ks = desc->kcache_dim_major ? dim_major_keys(desc, desc->Lmax, desc->r)
                                                : dense_keys(desc, desc->Lmax, desc->r);
   const KeyStrides vs = dense_keys(desc, desc->Lmax, desc->d_k);
   if (k_lr_new) {
@@ -951,9 +983,14 @@ int lisa_attn_decode(const lisa_desc* desc, const void* q_lr, const void* k_lr_n
   lisa_desc eq;
   const lisa_desc* eff = desc;                             // the descriptor the fast kernels see
   if (!decode_fast_ok(desc, true) && relu_equivalent(desc, &eq) && decode_fast_ok(&eq, true)) {
-    rc = synth_relu_ffn(desc, w1, workspace, round_up(decode_fast_bytes(&eq), 256), &w1, &w2, st);
+    const void* k0 = k_lr_cache;
+    rc = synth_relu_ffn(desc, w1, workspace, round_up(decode_fast_bytes(&eq), 256), &w1, &w2, &q_lr, &k0, st);
     if (rc) return rc;
     eff = &eq;
+    if (desc->mix == LISA_MIX_SHARE) {                     // the all-zero K_LR cache of the equivalent layer
+      k_lr_cache = const_cast<void*>(k0);
+      ks = desc->kcache_dim_major ? dim_major_keys(eff, eff->Lmax, eff->r) : dense_keys(eff, eff->Lmax, eff->r);
+    }
   }
   if (decode_fast_ok(eff, true)) {
     DecodeArgs a{};

@@ -870,11 +870,11 @@ def test_nf_strategy_standard_prefill_then_lisa_decode(dim_major):
     assert bool((tail == SENTINEL).all()) and bool((v_cache[:, :, L + 1:] == SENTINEL).all())
 
 
-@pytest.mark.parametrize("variant", [v for v in VARIANTS if v[0] in ("single_add", "plus")], ids=lambda v: v[0])
+@pytest.mark.parametrize("variant", [v for v in VARIANTS if v[0] in ("single_add", "plus", "share")], ids=lambda v: v[0])
 def test_linear_variants_run_on_the_mfma_kernels(variant):
-    """The single-layer FFN and LiSA_plus are exact two-layer ReLU networks ([W,-W] then [I;-I]), so
-    on MFMA-eligible shapes the library runs them on the fused kernels; the reference is the
-    oracle's own single-layer / plus definition."""
+    """The single-layer FFN, LiSA_plus and direct sharing are exact two-layer ReLU networks ([W,-W]
+    then [I;-I]; direct sharing with an all-zero correction), so on MFMA-eligible shapes the library
+    runs them on the fused kernels; the reference is the oracle's own definition of each variant."""
     name, mix, act = variant
     log(f"[case] variant on mfma {name}")
     cfg = synth.LayerShape("variant_mfma_" + name, "bf16", 2, 32, 8, 200, 256, 128, 22, 64, 500000.0)
@@ -884,20 +884,27 @@ def test_linear_variants_run_on_the_mfma_kernels(variant):
     g = torch.Generator(device=DEV).manual_seed(8)
     w1, w2 = variant_weights(cfg, mix, act, g)
     prev = std_prev(inp)
-    out, a_n = lisa.lisa_attn_prefill(inp["q_lr"], inp["k_lr"], inp["v"], prev, w1, w2, mix=mix, act=act)
+    share = mix == lisa.MIX_SHARE
+    q_in, k_in = (None, None) if share else (inp["q_lr"], inp["k_lr"])
+    out, a_n = lisa.lisa_attn_prefill(q_in, k_in, inp["v"], prev, w1, w2, mix=mix, act=act)
     torch.cuda.synchronize()
     assert lisa.last_path() == "mfma_fused"
     rows = np.arange(cfg.L)
     worst_o = worst_a = 0.0
     w1f = None if w1 is None else hp.f64(w1)
     for b in range(cfg.B):
-        a_ref, o_ref = cref.lisa_rows(hp.f64(inp["q_lr"][b]), hp.f64(inp["k_lr"][b]), hp.f64(inp["v"][b]), w1f,
-                                      None, rows, hp.gather_score_rows(prev, b, rows), mix=mix, act=act)
+        a_ref, o_ref = cref.lisa_rows(None if share else hp.f64(inp["q_lr"][b]),
+                                      None if share else hp.f64(inp["k_lr"][b]), hp.f64(inp["v"][b]), w1f,
+                                      None, rows, hp.gather_score_rows(prev, b, rows), mix=mix, act=act,
+                                      Lq=cfg.L)
         worst_o = max(worst_o, hp.row_rel_err(hp.gather_out_rows(out, b, rows), o_ref))
         worst_a = max(worst_a, hp.scores_row_rel_err(hp.gather_score_rows(a_n, b, rows), a_ref, rows,
                                                      cfg.L, cfg.L))
     log(f"[parity] variant {name} on mfma prefill: err_out={worst_o:.3e} err_scores={worst_a:.3e} tol={tol:g}")
     assert worst_o <= tol and worst_a <= tol
+    if share:                                                # the scores pass through unchanged, bit for bit
+        vis = torch.tril(torch.ones((cfg.L, cfg.L), dtype=torch.bool, device=DEV))
+        assert bool((a_n[:, :, vis] == prev[:, :, vis]).all())
     # decode step from caches
     L = cfg.L
     Lmax = L + 8
@@ -905,15 +912,17 @@ def test_linear_variants_run_on_the_mfma_kernels(variant):
     v_cache = torch.zeros((cfg.B, cfg.Hkv, Lmax, cfg.d_k), dtype=dt, device=DEV)
     lisa.lisa_cache_fill(inp["k_lr"], inp["v"], k_cache, v_cache, dim_major=True)
     row_prev = prev[:, :, L - 1, :].contiguous()
-    o_d, a_d = lisa.lisa_attn_decode(inp["q_lr"][:, :, L - 1, :].contiguous(), k_cache, v_cache, L, row_prev,
+    o_d, a_d = lisa.lisa_attn_decode(None if share else inp["q_lr"][:, :, L - 1, :].contiguous(),
+                                     None if share else k_cache, v_cache, L, row_prev,
                                      w1, w2, dim_major=True, mix=mix, act=act)
     torch.cuda.synchronize()
     assert lisa.last_path() == "decode_split"
     worst_o = worst_a = 0.0
     for b in range(cfg.B):
-        a_ref, o_ref = cref.lisa_rows(hp.f64(inp["q_lr"][b])[:, L - 1:L], hp.f64(inp["k_lr"][b]),
+        a_ref, o_ref = cref.lisa_rows(None if share else hp.f64(inp["q_lr"][b])[:, L - 1:L],
+                                      None if share else hp.f64(inp["k_lr"][b]),
                                       hp.f64(inp["v"][b]), w1f, None, [0], hp.f64(row_prev[b])[None],
-                                      mix=mix, act=act)
+                                      mix=mix, act=act, Lq=1)
         worst_o = max(worst_o, hp.row_rel_err(hp.f64(o_d[b])[None], o_ref))
         worst_a = max(worst_a, hp.row_rel_err(hp.f64(a_d[b])[None], a_ref))
     log(f"[parity] variant {name} on mfma decode: err_out={worst_o:.3e} err_scores={worst_a:.3e}")
