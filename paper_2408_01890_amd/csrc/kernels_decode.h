@@ -40,7 +40,7 @@ struct DecodeArgs {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 // LISA_MODE: 1 = LiSA layer, 0 = standard layer.  DK: head dimension (64 or 128).
-template <int LISA_MODE, int HB, int FS, int DK>
+template <int LISA_MODE, int HB, int FS, int DK, int ACT = 0>
 __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
   constexpr int LPK = DK / 8;        // lanes per key in the 16-byte streams
   constexpr int KPW = 64 / LPK;      // keys per wave instruction
@@ -60,7 +60,7 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
   if (LISA_MODE) {
     for (int e = tid; e < H * a.r; e += DEC_THREADS)
       q_s[e] = elem<bf16_t>::load(a.q + (size_t)b * H * a.r + e);
-    MfmaFfn<HB, FS>::stage(a.w1, a.w2, H, a.F, w_s, tid, DEC_THREADS);
+    MfmaFfn<HB, FS, HB, ACT>::stage(a.w1, a.w2, H, a.F, w_s, tid, DEC_THREADS);
     __syncthreads();
     if (a.ks.j == 1 && (a.ks.t & 7) == 0 && (a.ks.h & 7) == 0 && (a.ks.b & 7) == 0) {
       // dimension-major cache with 16-byte aligned rows: 8 keys per lane and load
@@ -135,14 +135,14 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
 
   // ---- S2: A_n = FFN(A_{n-1}) + a_delta ------------------------------------------------
   if (LISA_MODE) {
-    MfmaFfn<HB, FS> ffn;
+    MfmaFfn<HB, FS, HB, ACT> ffn;
     ffn.fetch(w_s);
     const int c = lane & 15, g = lane >> 4;
     for (int nb = wv; nb < DEC_CK / 16; nb += 4) {
       const int pj = nb * 16 + c, j = j0 + pj;
-      f16x8 x[1][MfmaFfn<HB, FS>::KS];
+      f16x8 x[1][MfmaFfn<HB, FS, HB, ACT>::KS];
 #pragma unroll
-      for (int ks = 0; ks < MfmaFfn<HB, FS>::KS; ++ks)
+      for (int ks = 0; ks < MfmaFfn<HB, FS, HB, ACT>::KS; ++ks)
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           const int ch = 32 * ks + 8 * g + e;

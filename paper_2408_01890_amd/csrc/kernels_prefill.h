@@ -209,7 +209,7 @@ __device__ __forceinline__ void st_uv(void* ubase, unsigned voff, T v) {
 // numbered by length.  grid (units or ceil(units / 2), B, NG), block NW * 64: with a.pair the
 // workgroup x takes the units (last - x) and x, a long and a short one, so that all workgroups
 // carry the same number of tiles and stage the FFN weights once.  Requires Lk % 8 == 0.
-template <int NG, int FS, int HPW, int NW>
+template <int NG, int FS, int HPW, int NW, int ACT = 0>
 __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
   constexpr int DK = 128;
   constexpr int THREADS = NW * 64;
@@ -217,7 +217,7 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
   constexpr int H = NG * GH;
   constexpr int HB = (H + 15) / 16;
   constexpr int HBO = (GH + 15) / 16;
-  typedef MfmaFfn<HB, FS, HBO> Ffn;
+  typedef MfmaFfn<HB, FS, HBO, ACT> Ffn;
   constexpr int KS = Ffn::KS;
   constexpr int XCH = NG * HPW;                      // A_{n-1} chunks per lane: heads wv + NW u
   constexpr int NBW = ((2 * PF_ROWS + NW - 1) / NW + 1) / 2 * 2;   // position blocks per wave in stage A (even)

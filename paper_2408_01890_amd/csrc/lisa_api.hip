@@ -227,7 +227,7 @@ bool decode_fast_ok(const lisa_desc* d, bool lisa_layer) {
   if (d->d_k != 64 && d->d_k != 128) return false;
   if (d->H > 64) return false;
   if (lisa_layer) {
-    if (d->mix != LISA_MIX_ADD || d->act != LISA_ACT_RELU) return false;
+    if (d->mix != LISA_MIX_ADD || (d->act != LISA_ACT_RELU && d->act != LISA_ACT_SILU)) return false;
     if (d->F > 128 || d->r > 64) return false;
   }
   return true;
@@ -240,10 +240,10 @@ size_t decode_fast_bytes(const lisa_desc* d) {
   return round_up(units * d->d_k * sizeof(float), 256) + round_up(units * 2 * sizeof(float), 256);
 }
 
-template <int LISA_MODE, int HB, int FS>
+template <int LISA_MODE, int HB, int FS, int ACT = 0>
 int launch_decode_part_dk(const lisa_desc* d, const DecodeArgs& a, size_t lds, hipStream_t st) {
   dim3 grid(a.n_chunk, d->B);
-  auto kern = d->d_k == 128 ? k_decode_part<LISA_MODE, HB, FS, 128> : k_decode_part<LISA_MODE, HB, FS, 64>;
+  auto kern = d->d_k == 128 ? k_decode_part<LISA_MODE, HB, FS, 128, ACT> : k_decode_part<LISA_MODE, HB, FS, 64, ACT>;
   if (lds > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)lds);
@@ -254,14 +254,19 @@ int launch_decode_part_dk(const lisa_desc* d, const DecodeArgs& a, size_t lds, h
   return check_launch();
 }
 
+template <int HB, int ACT>
+int launch_decode_lisa_act(const lisa_desc* d, const DecodeArgs& a, size_t lds, hipStream_t st) {
+  switch ((d->F + 31) / 32) {
+    case 1: return launch_decode_part_dk<1, HB, 1, ACT>(d, a, lds, st);
+    case 2: return launch_decode_part_dk<1, HB, 2, ACT>(d, a, lds, st);
+    case 3: return launch_decode_part_dk<1, HB, 3, ACT>(d, a, lds, st);
+    default: return launch_decode_part_dk<1, HB, 4, ACT>(d, a, lds, st);
+  }
+}
 template <int HB>
 int launch_decode_lisa_fs(const lisa_desc* d, const DecodeArgs& a, size_t lds, hipStream_t st) {
-  switch ((d->F + 31) / 32) {
-    case 1: return launch_decode_part_dk<1, HB, 1>(d, a, lds, st);
-    case 2: return launch_decode_part_dk<1, HB, 2>(d, a, lds, st);
-    case 3: return launch_decode_part_dk<1, HB, 3>(d, a, lds, st);
-    default: return launch_decode_part_dk<1, HB, 4>(d, a, lds, st);
-  }
+  return d->act == LISA_ACT_SILU ? launch_decode_lisa_act<HB, 1>(d, a, lds, st)
+                                 : launch_decode_lisa_act<HB, 0>(d, a, lds, st);
 }
 
 int run_decode_fast(const lisa_desc* d, bool lisa_layer, DecodeArgs a, void* out, void* workspace,
@@ -317,7 +322,7 @@ int run_decode_fast(const lisa_desc* d, bool lisa_layer, DecodeArgs a, void* out
 // Head counts the fused kernel is instantiated for: H -> (waves, heads per wave, head groups).
 bool prefill_fused_ok(const lisa_desc* d) {
   if (d->dtype != LISA_BF16 || d->d_k != 128) return false;
-  if (d->mix != LISA_MIX_ADD || d->act != LISA_ACT_RELU) return false;
+  if (d->mix != LISA_MIX_ADD || (d->act != LISA_ACT_RELU && d->act != LISA_ACT_SILU)) return false;
   if (d->Lk % 8 != 0 || d->F > 128 || d->r > 32) return false;   // 16-byte aligned score rows
   if ((long long)d->Lq * d->Lk >= (1LL << 31)) return false;      // 32-bit byte offsets inside one head's scores
   return d->H == 8 || d->H == 16 || d->H == 24 || d->H == 32 || d->H == 40;
@@ -380,12 +385,12 @@ PrefillWs prefill_fused_ws(const lisa_desc* d) {
   return w;
 }
 
-template <int NG, int FS, int HPW, int NW>
+template <int NG, int FS, int HPW, int NW, int ACT>
 int launch_prefill_fused_t(const lisa_desc* d, const PrefillArgs& a, hipStream_t st) {
   constexpr int GH = NW * HPW, H = NG * GH;
   typedef MfmaFfn<(H + 15) / 16, FS, (GH + 15) / 16> Ffn;
   const size_t lds = (size_t)H * PF_XS_HEAD + (size_t)GH * PF_YS_HEAD + Ffn::kStageBytes + (size_t)GH * PF_AS_HEAD;
-  auto kern = k_lisa_prefill_fused<NG, FS, HPW, NW>;
+  auto kern = k_lisa_prefill_fused<NG, FS, HPW, NW, ACT>;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)lds);
   if (e != hipSuccess) return hip_fail(e);
@@ -397,14 +402,19 @@ int launch_prefill_fused_t(const lisa_desc* d, const PrefillArgs& a, hipStream_t
 
 }
 
+template <int NG, int HPW, int NW, int ACT>
+int launch_prefill_fused_act(const lisa_desc* d, const PrefillArgs& a, hipStream_t st) {
+  switch ((d->F + 31) / 32) {
+    case 1: return launch_prefill_fused_t<NG, 1, HPW, NW, ACT>(d, a, st);
+    case 2: return launch_prefill_fused_t<NG, 2, HPW, NW, ACT>(d, a, st);
+    case 3: return launch_prefill_fused_t<NG, 3, HPW, NW, ACT>(d, a, st);
+    default: return launch_prefill_fused_t<NG, 4, HPW, NW, ACT>(d, a, st);
+  }
+}
 template <int NG, int HPW, int NW>
 int launch_prefill_fused_fs(const lisa_desc* d, const PrefillArgs& a, hipStream_t st) {
-  switch ((d->F + 31) / 32) {
-    case 1: return launch_prefill_fused_t<NG, 1, HPW, NW>(d, a, st);
-    case 2: return launch_prefill_fused_t<NG, 2, HPW, NW>(d, a, st);
-    case 3: return launch_prefill_fused_t<NG, 3, HPW, NW>(d, a, st);
-    default: return launch_prefill_fused_t<NG, 4, HPW, NW>(d, a, st);
-  }
+  return d->act == LISA_ACT_SILU ? launch_prefill_fused_act<NG, HPW, NW, 1>(d, a, st)
+                                 : launch_prefill_fused_act<NG, HPW, NW, 0>(d, a, st);
 }
 
 int run_prefill_fused(const lisa_desc* d, const void* q_lr, const void* k_lr, const void* v,

@@ -20,7 +20,7 @@
 // for |w| >= 2^-14, absolute error < 2^-25 below).  The hidden units are rounded to half, not
 // bfloat16: with an identity-like FFN they carry the scores themselves, and 8 significant bits
 // there would move A_n by up to 2^-9 |A_n|, which the softmax turns into percent-level errors.
-// ReLU and the saturation at the half range are one v_med3.
+// ReLU and the saturation at the half range are one v_med3; SiLU costs an exp2 and a reciprocal.
 #pragma once
 #include "lisa_types.h"
 
@@ -41,10 +41,19 @@ __device__ __forceinline__ unsigned short half_bits(float f) {
 // HB = ceil(H / 16) input head blocks (KS = ceil(H / 32) k-steps of the first product),
 // FS = ceil(F / 32) hidden k-steps (2 FS hidden blocks of 16), HBO = blocks of 16 output heads
 // (the caller may ask for a sub-range of the H output heads: h_first .. h_first + n_out - 1).
-template <int HB, int FS, int HBO = HB>
+// ACT: activation of the hidden units, 0 = ReLU (Sec. 6.1), 1 = SiLU u * sigmoid(u) (ablated in
+// Sec. 6.5); both saturate at the half range.
+template <int HB, int FS, int HBO = HB, int ACT = 0>
 struct MfmaFfn {
   static constexpr int KS = (HB + 1) / 2;
   static constexpr int FB = 2 * FS;
+
+  static __device__ __forceinline__ _Float16 activate(float u) {
+    if (ACT == 0) return (_Float16)__builtin_amdgcn_fmed3f(u, 0.f, 65504.f);
+    // exp2(-u log2 e) overflows to +inf for very negative u: 1 / inf = 0 and the product is -0
+    const float sg = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * u));
+    return (_Float16)fminf(u * sg, 65504.f);
+  }
   f16x8 w1[FB][KS];   // A operands of the first product:  W1^T, rows f, contraction c
   f16x8 w2[HBO][FS];  // A operands of the second product: W2^T, rows h, contraction f
 
@@ -117,7 +126,7 @@ struct MfmaFfn {
         for (int n = 0; n < NBLK; ++n)
 #pragma unroll
           for (int v = 0; v < 4; ++v)
-            hid[n][s][4 * half + v] = (_Float16)__builtin_amdgcn_fmed3f(acc[n][v], 0.f, 65504.f);
+            hid[n][s][4 * half + v] = activate(acc[n][v]);
       }
     }
 #pragma unroll
@@ -160,7 +169,7 @@ struct MfmaFfn {
         for (int n = 0; n < NBLK; ++n)
 #pragma unroll
           for (int v = 0; v < 4; ++v)
-            hid[n][s][4 * half + v] = (_Float16)__builtin_amdgcn_fmed3f(acc[n][v], 0.f, 65504.f);
+            hid[n][s][4 * half + v] = activate(acc[n][v]);
       }
     }
 #pragma unroll

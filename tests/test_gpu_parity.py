@@ -870,11 +870,12 @@ def test_nf_strategy_standard_prefill_then_lisa_decode(dim_major):
     assert bool((tail == SENTINEL).all()) and bool((v_cache[:, :, L + 1:] == SENTINEL).all())
 
 
-@pytest.mark.parametrize("variant", [v for v in VARIANTS if v[0] in ("single_add", "plus", "share")], ids=lambda v: v[0])
-def test_linear_variants_run_on_the_mfma_kernels(variant):
+@pytest.mark.parametrize("variant", [v for v in VARIANTS if v[0] in ("silu_add", "single_add", "plus", "share")], ids=lambda v: v[0])
+def test_variants_that_run_on_the_mfma_kernels(variant):
     """The single-layer FFN, LiSA_plus and direct sharing are exact two-layer ReLU networks ([W,-W]
     then [I;-I]; direct sharing with an all-zero correction), so on MFMA-eligible shapes the library
-    runs them on the fused kernels; the reference is the oracle's own definition of each variant."""
+    runs them on the fused kernels, and so it does the two-layer FFN with SiLU (its own activation in
+    the MFMA FFN); the reference is the oracle's own definition of each variant."""
     name, mix, act = variant
     log(f"[case] variant on mfma {name}")
     cfg = synth.LayerShape("variant_mfma_" + name, "bf16", 2, 32, 8, 200, 256, 128, 22, 64, 500000.0)
@@ -892,10 +893,11 @@ def test_linear_variants_run_on_the_mfma_kernels(variant):
     rows = np.arange(cfg.L)
     worst_o = worst_a = 0.0
     w1f = None if w1 is None else hp.f64(w1)
+    w2f = None if w2 is None else hp.f64(w2)
     for b in range(cfg.B):
         a_ref, o_ref = cref.lisa_rows(None if share else hp.f64(inp["q_lr"][b]),
                                       None if share else hp.f64(inp["k_lr"][b]), hp.f64(inp["v"][b]), w1f,
-                                      None, rows, hp.gather_score_rows(prev, b, rows), mix=mix, act=act,
+                                      w2f, rows, hp.gather_score_rows(prev, b, rows), mix=mix, act=act,
                                       Lq=cfg.L)
         worst_o = max(worst_o, hp.row_rel_err(hp.gather_out_rows(out, b, rows), o_ref))
         worst_a = max(worst_a, hp.scores_row_rel_err(hp.gather_score_rows(a_n, b, rows), a_ref, rows,
@@ -921,7 +923,7 @@ def test_linear_variants_run_on_the_mfma_kernels(variant):
     for b in range(cfg.B):
         a_ref, o_ref = cref.lisa_rows(None if share else hp.f64(inp["q_lr"][b])[:, L - 1:L],
                                       None if share else hp.f64(inp["k_lr"][b]),
-                                      hp.f64(inp["v"][b]), w1f, None, [0], hp.f64(row_prev[b])[None],
+                                      hp.f64(inp["v"][b]), w1f, w2f, [0], hp.f64(row_prev[b])[None],
                                       mix=mix, act=act, Lq=1)
         worst_o = max(worst_o, hp.row_rel_err(hp.f64(o_d[b])[None], o_ref))
         worst_a = max(worst_a, hp.row_rel_err(hp.f64(a_d[b])[None], a_ref))
