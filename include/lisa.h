@@ -264,7 +264,7 @@ const char* lisa_strerror(int status);
 const char* lisa_last_hip_error(void);
 /* Name of the kernel family the last successful call on this thread dispatched to
  * ("generic", "mfma_fused", "mfma_std", "decode_split", "cache_fill", "project_generic",
- * "project_mfma", "project_skinny"); for tests and
+ * "project_mfma", "project_skinny", "mfma_scores"); for tests and
  * benchmark reports. */
 const char* lisa_last_path(void);
 

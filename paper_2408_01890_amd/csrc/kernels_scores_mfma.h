@@ -1,0 +1,208 @@
+// A_n of a LiSA layer in CONCAT form on the matrix cores (bf16 inputs, half scores):
+//   A_n[:,i,j] = W2^T ReLU(W1^T [A_{n-1}[:,i,j] ; A_delta[:,i,j]])      (Sec. 5.1, "An overview of
+// LiSA": the alignment FFN takes the concatenation, 2h -> F -> h; Sec. 6.1: 64 -> 256 -> 32),
+// with A_delta = Q_LR K_LR^T / sqrt(r) (Eq. 3).  The correction goes through the FFN here, so it
+// cannot be added per head after a position-wise stage as in the fused ADD kernel; this kernel
+// produces the score tensor (half, for the next layer) and its unrounded float32 copy, which the
+// softmax / P V kernel of the generic path then consumes.  49 kflop per position at the paper's
+// widths: bound by the matrix cores, not by the 8 + 2 bytes per head and position it moves.
+//
+// One workgroup (8 waves) = 16 query rows x up to SM_CHUNK tiles of 32 keys.  Per tile:
+//   1. the A_{n-1} tile of all heads goes to LDS ([head][row][key], half); wave w computes the
+//      A_delta tile of heads w, w + 8, ... with two 16x16x32 MFMAs each (A = K_LR rows, B = Q_LR
+//      rows, assembled from 4-byte loads: rows of r elements are not 16-byte aligned) and
+//      appends it as heads H .. 2H-1 of the same LDS array;
+//   2. every wave runs the FFN (mfma_ffn.h, weights read from their LDS image) on 4 of the 32
+//      blocks of 16 positions, the 2H input "heads" fetched with transposing LDS reads;
+//   3. the results go to LDS as float32 [head][row][key] (over the input tile) and leave by
+//      heads in whole rows: 128 bytes of float32 and 64 bytes of half per row and tile.
+// Requires Lk % 8 == 0, r even and <= 32, 2H <= 64, F <= 256.
+#pragma once
+#include "kernels_prefill.h"
+
+namespace lisa {
+
+struct ScoresMfmaArgs {
+  const bf16_t* q_lr;   // [B,H,Lq,r]
+  const bf16_t* k_lr;   // [B,Hkv,Lk,r]
+  const half_t* prev;   // [B,H,Lq,Lk]
+  const bf16_t* w1;     // [2H,F]
+  const bf16_t* w2;     // [F,H]
+  half_t* scores;       // [B,H,Lq,Lk] or null
+  float* exact;         // [B,H,Lq,Lk]
+  int H, Hkv, Lq, Lk, r, F, causal;
+  float dscale;
+};
+
+constexpr int SM_CHUNK = 8;       // key tiles per workgroup
+
+// 8 bf16 of a row of r elements starting at element t0 (even), zero beyond r; 4-byte loads.
+__device__ __forceinline__ bf16x8 load_lr_operand(const bf16_t* row, int t0, int r) {
+  unsigned w[4];
+#pragma unroll
+  for (int d = 0; d < 4; ++d) w[d] = t0 + 2 * d + 1 < r ? *(const unsigned*)(row + t0 + 2 * d) : 0u;
+  typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+  u32x4_t v = {w[0], w[1], w[2], w[3]};
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// HBI = ceil(2H / 16) input blocks, FS = ceil(F / 32), HBO = ceil(H / 16).
+// grid (ceil(max tiles / SM_CHUNK), ceil(Lq / 16), B), block 512.
+template <int HBI, int FS, int HBO>
+__global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
+  typedef MfmaFfn<HBI, FS, HBO> Ffn;
+  constexpr int KS = Ffn::KS, NW = 8, NBW = 4;
+  constexpr int NBLK = 2;                                   // blocks per FFN call (they share each weight read)
+  extern __shared__ __align__(16) unsigned char sm_lds[];
+  const int H = a.H, Din = 2 * H, Lq = a.Lq, Lk = a.Lk;
+  // the input tile (2H heads, half) and, later in the same tile, the output tile (H heads, float)
+  const int io_bytes = max(Din * PF_XS_HEAD, H * PF_YS_HEAD);
+  unsigned char* xs = sm_lds;
+  unsigned char* ys = sm_lds;
+  unsigned short* w_s = (unsigned short*)(sm_lds + ((io_bytes + 15) & ~15));
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int c = lane & 15, g = lane >> 4;
+  const int b = blockIdx.z, i0 = blockIdx.y * PF_ROWS;
+  const int shift = Lk - Lq;
+  const int i_last = min(i0 + PF_ROWS - 1, Lq - 1);
+  const int n_keys = a.causal ? min(Lk, i_last + 1 + shift) : Lk;
+  const int n_tiles = (n_keys + PF_TK - 1) / PF_TK;
+  const int t_first = blockIdx.x * SM_CHUNK;
+  if (t_first >= n_tiles) return;                           // beyond the diagonal (whole workgroup)
+  const int t_last = min(t_first + SM_CHUNK, n_tiles);
+  const int group = H / a.Hkv;
+
+  Ffn::stage(a.w1, a.w2, Din, a.F, w_s, tid, NW * 64, 0, H, H);
+
+  // A_delta: B operands (Q_LR rows of this wave's heads), resident
+  constexpr int HPW = (HBO * 16 + NW - 1) / NW;             // heads per wave (upper bound)
+  bf16x8 qop[HPW];
+#pragma unroll
+  for (int u = 0; u < HPW; ++u) {
+    const int h = min(wv + NW * u, H - 1);
+    const bf16_t* qrow = a.q_lr + (((size_t)b * H + h) * Lq + min(i0 + c, Lq - 1)) * a.r;
+    qop[u] = load_lr_operand(qrow, 8 * g, a.r);
+  }
+  // transposing LDS reads of stage 2 (see the fused prefill kernel): lane 4 k' + q4 of a 16-lane
+  // group passes the address of head k', keys 4 q4 .. 4 q4 + 3, and receives key c of heads k' = 0..3
+  int xrd[KS][2];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    xrd[ks][0] = min(32 * ks + 8 * g + (c >> 2), Din - 1) * PF_XS_HEAD + 8 * (c & 3);
+    xrd[ks][1] = min(32 * ks + 8 * g + 4 + (c >> 2), Din - 1) * PF_XS_HEAD + 8 * (c & 3);
+  }
+  const int x_row = min(i0 + (lane >> 2), Lq - 1), xq8 = 8 * (lane & 3);
+
+  for (int tile = t_first; tile < t_last; ++tile) {
+    const int j0 = tile * PF_TK;
+    __syncthreads();                                        // the stores of the previous tile have read ys
+    // ---- 1. input tile -----------------------------------------------------------------------
+    for (int h = wv; h < H; h += NW) {
+      const half_t* src = a.prev + (((size_t)b * H + h) * Lq + x_row) * Lk + min(j0 + xq8, Lk - 8);
+      *(pf_u32x4*)(xs + h * PF_XS_HEAD + lane * 16) = *(const pf_u32x4*)src;
+    }
+#pragma unroll
+    for (int u = 0; u < HPW; ++u) {
+      const int h = wv + NW * u;
+      if (h >= H) break;
+      const bf16_t* kbase = a.k_lr + ((size_t)b * a.Hkv + h / group) * Lk * a.r;
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const int j = min(j0 + 16 * half + c, Lk - 1);
+        const bf16x8 kop = load_lr_operand(kbase + (size_t)j * a.r, 8 * g, a.r);
+        f32x4 d = {0.f, 0.f, 0.f, 0.f};
+        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, qop[u], d, 0, 0, 0);
+        // d[v] = A_delta(row c, key 16 half + 4 g + v) / scale
+        f16x4 hv;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) hv[v] = f32_to_half_sat(d[v] * a.dscale);
+        *(f16x4*)(xs + (H + h) * PF_XS_HEAD + c * 64 + (16 * half + 4 * g) * 2) = hv;
+      }
+    }
+    __syncthreads();
+    // ---- 2. FFN over the wave's 4 blocks of 16 positions ---------------------------------------
+    f32x4 y[NBW][HBO];
+#pragma unroll
+    for (int q = 0; q < NBW; q += NBLK) {
+      f16x8 x[NBLK][KS];
+#pragma unroll
+      for (int n = 0; n < NBLK; ++n) {
+        const int nb = wv + (q + n) * NW;                   // block = (row nb / 2, key half nb % 2)
+        const int i = nb >> 1, kh = nb & 1;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          const f16x4 lo = __builtin_bit_cast(
+              f16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                         (s16x4 __attribute__((address_space(3)))*)(xs + xrd[ks][0] + i * 64 + 32 * kh)));
+          const f16x4 hi = __builtin_bit_cast(
+              f16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                         (s16x4 __attribute__((address_space(3)))*)(xs + xrd[ks][1] + i * 64 + 32 * kh)));
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            x[n][ks][e] = 32 * ks + 8 * g + e < Din ? lo[e] : (_Float16)0.f;
+            x[n][ks][4 + e] = 32 * ks + 8 * g + 4 + e < Din ? hi[e] : (_Float16)0.f;
+          }
+        }
+      }
+      f32x4 yq[NBLK][HBO];
+      Ffn::template apply_lds_lean<NBLK>(w_s, x, yq);
+#pragma unroll
+      for (int n = 0; n < NBLK; ++n)
+#pragma unroll
+        for (int hb = 0; hb < HBO; ++hb) y[q + n][hb] = yq[n][hb];
+    }
+    __syncthreads();                                        // every wave has read the input tile
+    // ---- 3. output tile: float32 [head][row][key] over the input tile, then out by heads ---------
+#pragma unroll
+    for (int qn = 0; qn < NBW; ++qn) {
+      const int nb = wv + qn * NW, i = nb >> 1, kh = nb & 1;
+#pragma unroll
+      for (int hb = 0; hb < HBO; ++hb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int hl = 16 * hb + 4 * g + v;
+          if (hl < H) *(float*)(ys + hl * PF_YS_HEAD + i * PF_YS_ROW + (16 * kh + c) * 4) = y[qn][hb][v];
+        }
+    }
+    __syncthreads();
+    {
+      const int row = lane >> 2, ch = lane & 3;             // 8 keys of a row per lane
+      const int gi = i0 + row, jc = j0 + 8 * ch;
+      const int vis = gi < Lq ? (a.causal ? min(Lk, gi + 1 + shift) : Lk) : 0;
+      for (int h = wv; h < H; h += NW) {
+        const float4 lo = *(const float4*)(ys + h * PF_YS_HEAD + row * PF_YS_ROW + 32 * ch);
+        const float4 hi = *(const float4*)(ys + h * PF_YS_HEAD + row * PF_YS_ROW + 32 * ch + 16);
+        const float vals[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        if (jc >= vis) continue;
+        const size_t at = (((size_t)b * H + h) * Lq + gi) * Lk + jc;
+        if (jc + 8 <= vis) {
+          *(float4*)(a.exact + at) = lo;
+          *(float4*)(a.exact + at + 4) = hi;
+          if (a.scores) {
+            f16x8 hv;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) hv[e] = f32_to_half_sat(vals[e]);
+            *(f16x8*)(a.scores + at) = hv;
+          }
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (jc + e < vis) {
+              a.exact[at + e] = vals[e];
+              if (a.scores) a.scores[at + e] = f32_to_half_sat(vals[e]);
+            }
+        }
+      }
+    }
+  }
+}
+
+// LDS bytes of k_lisa_scores_mfma<HBI, FS, HBO> for H heads.
+template <int HBI, int FS, int HBO>
+constexpr int scores_mfma_lds(int H) {
+  const int io = 2 * H * PF_XS_HEAD > H * PF_YS_HEAD ? 2 * H * PF_XS_HEAD : H * PF_YS_HEAD;
+  return ((io + 15) & ~15) + MfmaFfn<HBI, FS, HBO>::kStageBytes;
+}
+
+}  // namespace lisa

@@ -13,6 +13,7 @@
 #include "kernels_generic.h"
 #include "kernels_prefill.h"
 #include "kernels_project.h"
+#include "kernels_scores_mfma.h"
 #include "kernels_std_prefill.h"
 
 using namespace lisa;
@@ -152,6 +153,50 @@ int launch_std_scores(const lisa_desc* d, const void* q, const void* k, KeyStrid
   return check_launch();
 }
 
+// CONCAT with the two-layer ReLU FFN on the matrix cores (dense prefill tensors only).
+bool scores_mfma_ok(const lisa_desc* d) {
+  if (d->dtype != LISA_BF16 || d->mix != LISA_MIX_CONCAT || d->act != LISA_ACT_RELU) return false;
+  if (d->Lq == 1) return false;                            // decode rows: the generic kernel (strided caches)
+  if (d->H > 32 || d->F > 256 || d->r > 32 || d->r % 2 != 0 || d->Lk % 8 != 0) return false;
+  return (long long)d->Lq * d->Lk < (1LL << 31);
+}
+
+template <int HBI, int FS, int HBO>
+int launch_scores_mfma_t(const lisa_desc* d, const ScoresMfmaArgs& a, hipStream_t st) {
+  const int lds = scores_mfma_lds<HBI, FS, HBO>(d->H);
+  auto kern = k_lisa_scores_mfma<HBI, FS, HBO>;
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e != hipSuccess) return hip_fail(e);
+  const int tiles = (d->Lk + PF_TK - 1) / PF_TK;
+  dim3 grid((tiles + SM_CHUNK - 1) / SM_CHUNK, (d->Lq + PF_ROWS - 1) / PF_ROWS, d->B);
+  StageScope prof("k_lisa_scores_mfma", st);
+  kern<<<grid, 512, lds, st>>>(a);
+  return check_launch();
+}
+
+int launch_scores_mfma(const lisa_desc* d, const void* q_lr, const void* k_lr, const void* prev, const void* w1,
+                       const void* w2, void* scores, float* exact, hipStream_t st) {
+  ScoresMfmaArgs a{};
+  a.q_lr = (const bf16_t*)q_lr;
+  a.k_lr = (const bf16_t*)k_lr;
+  a.prev = (const half_t*)prev;
+  a.w1 = (const bf16_t*)w1;
+  a.w2 = (const bf16_t*)w2;
+  a.scores = (half_t*)scores;
+  a.exact = exact;
+  a.H = d->H;
+  a.Hkv = d->Hkv;
+  a.Lq = d->Lq;
+  a.Lk = d->Lk;
+  a.r = d->r;
+  a.F = d->F;
+  a.causal = d->causal;
+  a.dscale = pick_scale(d->delta_scale, d->r);
+  const bool wide = d->F > 128;
+  if (d->H <= 16) return wide ? launch_scores_mfma_t<2, 8, 1>(d, a, st) : launch_scores_mfma_t<2, 4, 1>(d, a, st);
+  return wide ? launch_scores_mfma_t<4, 8, 2>(d, a, st) : launch_scores_mfma_t<4, 4, 2>(d, a, st);
+}
+
 template <typename T, typename S>
 int launch_lisa_scores(const lisa_desc* d, const void* q_lr, const void* k_lr, KeyStrides ks,
                        const void* prev, const void* w1, const void* w2, void* scores,
@@ -213,10 +258,12 @@ int run_lisa(const lisa_desc* d, const void* q_lr, const void* k_lr, KeyStrides 
              void* scores, float* exact, hipStream_t st) {
   // The softmax reads the unrounded float32 A_n from the workspace: rounding A_n to the
   // 2-byte score type first would move each probability by up to |A_n| 2^-11.
-  int rc = launch_lisa_scores<T, S>(d, q_lr, k_lr, ks, prev, w1, w2, scores, exact, st);
+  const bool mfma = scores_mfma_ok(d);
+  int rc = mfma ? launch_scores_mfma(d, q_lr, k_lr, prev, w1, w2, scores, exact, st)
+                : launch_lisa_scores<T, S>(d, q_lr, k_lr, ks, prev, w1, w2, scores, exact, st);
   if (rc) return rc;
   rc = launch_softmax_v<T>(d, exact, v, vs, out, st);
-  if (rc == LISA_OK) g_path = "generic";
+  if (rc == LISA_OK) g_path = mfma ? "mfma_scores" : "generic";
   return rc;
 }
 

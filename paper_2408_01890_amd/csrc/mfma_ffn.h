@@ -66,7 +66,9 @@ struct MfmaFfn {
   __device__ __forceinline__ static void stage(const bf16_t* __restrict__ w1g,
                                                const bf16_t* __restrict__ w2g, int H, int F,
                                                unsigned short* lds, int tid, int nthreads,
-                                               int h_first = 0, int n_out = 1 << 30) {
+                                               int h_first = 0, int n_out = 1 << 30, int h_total = -1) {
+    // h_total: number of output heads (columns of w2g) when it differs from the input width H
+    const int HO = h_total < 0 ? H : h_total;
     for (int idx = tid; idx < FB * KS * 512; idx += nthreads) {
       const int e = idx & 7, l = (idx >> 3) & 63, o = idx >> 9;
       const int fb = o / KS, ks = o % KS, c = l & 15, g = l >> 4;
@@ -79,7 +81,7 @@ struct MfmaFfn {
       const int e = idx & 7, l = (idx >> 3) & 63, o = idx >> 9;
       const int hb = o / FS, s = o % FS, c = l & 15, g = l >> 4;
       const int hl = 16 * hb + c, h = h_first + hl, f = 16 * (2 * s + e / 4) + 4 * g + e % 4;
-      const float w = (f < F && h < H && hl < n_out) ? elem<bf16_t>::load(w2g + (size_t)f * H + h) : 0.f;
+      const float w = (f < F && h < HO && hl < n_out) ? elem<bf16_t>::load(w2g + (size_t)f * HO + h) : 0.f;
       lds2[idx] = half_bits(w);
     }
   }
@@ -143,6 +145,55 @@ struct MfmaFfn {
       }
 #pragma unroll
       for (int n = 0; n < NBLK; ++n) y[n][hb] = acc[n];
+    }
+  }
+
+  // apply_lds() for wide networks (many weight operands): scheduling fences after every group of
+  // products keep the compiler from hoisting all weight reads to the top, which would need more
+  // registers than a wave has.
+  template <int NBLK>
+  __device__ __forceinline__ static void apply_lds_lean(const unsigned short* lds, const f16x8 (&x)[NBLK][KS],
+                                                        f32x4 (&y)[NBLK][HBO]) {
+    const int lane = threadIdx.x & 63;
+    const unsigned short* l1 = lds + lane * 8;
+    const unsigned short* l2 = l1 + FB * KS * 512;
+    f16x8 hid[NBLK][FS];
+#pragma unroll
+    for (int s = 0; s < FS; ++s) {
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        f32x4 acc[NBLK];
+#pragma unroll
+        for (int n = 0; n < NBLK; ++n) acc[n] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          const f16x8 w = *(const f16x8*)(l1 + ((2 * s + half) * KS + ks) * 512);
+#pragma unroll
+          for (int n = 0; n < NBLK; ++n)
+            acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w, x[n][ks], acc[n], 0, 0, 0);
+        }
+#pragma unroll
+        for (int n = 0; n < NBLK; ++n)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) hid[n][s][4 * half + v] = activate(acc[n][v]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int hb = 0; hb < HBO; ++hb) {
+      f32x4 acc[NBLK];
+#pragma unroll
+      for (int n = 0; n < NBLK; ++n) acc[n] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < FS; ++s) {
+        const f16x8 w = *(const f16x8*)(l2 + (hb * FS + s) * 512);
+#pragma unroll
+        for (int n = 0; n < NBLK; ++n)
+          acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w, hid[n][s], acc[n], 0, 0, 0);
+      }
+#pragma unroll
+      for (int n = 0; n < NBLK; ++n) y[n][hb] = acc[n];
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 

@@ -929,3 +929,75 @@ def test_variants_that_run_on_the_mfma_kernels(variant):
         worst_a = max(worst_a, hp.row_rel_err(hp.f64(a_d[b])[None], a_ref))
     log(f"[parity] variant {name} on mfma decode: err_out={worst_o:.3e} err_scores={worst_a:.3e}")
     assert worst_o <= tol and worst_a <= tol
+
+
+# ---------------------------------------------------------------------------------------
+# CONCAT form (the paper's default: FFN over [A_{n-1}; A_delta], 2h -> F -> h) with the scores
+# computed on the matrix cores
+# ---------------------------------------------------------------------------------------
+CONCAT_MFMA = [
+    # name, B, H, Hkv, L (multiple of 8), d_k, r (even), F
+    ("paper_dims_l200", 1, 32, 32, 200, 128, 20, 256),      # Sec. 6.1: 64 -> 256 -> 32, r = 20
+    ("gqa_l336", 2, 32, 8, 336, 128, 22, 128),
+    ("h16_gqa_l152", 1, 16, 4, 152, 64, 12, 64),
+    ("h8_l264_f200", 1, 8, 8, 264, 128, 32, 200),
+    ("h24_l136", 1, 24, 24, 136, 128, 20, 96),
+]
+
+
+@pytest.mark.parametrize("case", CONCAT_MFMA, ids=[c[0] for c in CONCAT_MFMA])
+@pytest.mark.parametrize("causal,ffn", [(True, "fan_in"), (True, "paper"), (False, "fan_in")])
+def test_lisa_prefill_concat_on_mfma_scores_kernel(case, causal, ffn):
+    name, B, H, Hkv, L, dk, r, F = case
+    cfg = synth.LayerShape(name, "bf16", B, H, Hkv, L, 256, dk, r, F)
+    log(f"[case] prefill concat mfma {name} causal={causal} ffn={ffn}")
+    inp = synth.make_prefill_inputs(cfg, synth.BASE_SEED + 13, DEV, mix="concat", ffn=ffn)
+    prev, _ = lisa.std_attn_scores(inp["q"], inp["k"], causal=causal)
+    sent = torch.full((B, H, L, L), SENTINEL, dtype=torch.float16, device=DEV)
+    out, scores = lisa.lisa_attn_prefill(inp["q_lr"], inp["k_lr"], inp["v"], prev, inp["w1"], inp["w2"],
+                                         mix=lisa.MIX_CONCAT, causal=causal, scores_out=sent)
+    torch.cuda.synchronize()
+    assert lisa.last_path() == "mfma_scores"
+    rows = np.arange(L)
+    tol = hp.TOL[cfg.torch_dtype]
+    worst_o = worst_a = 0.0
+    for b in range(B):
+        if causal:
+            a_ref, o_ref = hp.oracle_lisa_rows(inp, b, rows, hp.gather_score_rows(prev, b, rows), mix=1)
+        else:
+            # the oracle is causal: row i with full visibility is the single row of a 1-row problem
+            refs = [cref.lisa_rows(hp.f64(inp["q_lr"][b])[:, i:i + 1], hp.f64(inp["k_lr"][b]), hp.f64(inp["v"][b]),
+                                   hp.f64(inp["w1"]), hp.f64(inp["w2"]), [0],
+                                   hp.gather_score_rows(prev, b, [i]), mix=1) for i in rows]
+            a_ref = np.concatenate([r[0] for r in refs])
+            o_ref = np.concatenate([r[1] for r in refs])
+        worst_o = max(worst_o, hp.row_rel_err(hp.gather_out_rows(out, b, rows), o_ref))
+        worst_a = max(worst_a, hp.scores_row_rel_err(hp.gather_score_rows(scores, b, rows), a_ref, rows, L, L,
+                                                     causal))
+    log(f"[parity] concat mfma {name} causal={causal} ffn={ffn}: err_out={worst_o:.3e} err_scores={worst_a:.3e}")
+    assert worst_o <= tol and worst_a <= tol
+    if causal:
+        above = torch.ones(L, L, dtype=torch.bool, device=DEV).triu(1)
+        assert torch.all(scores[..., above] == SENTINEL)      # nothing written above the diagonal
+
+
+def test_lisa_prefill_concat_mfma_chunked_rows():
+    """Lq < Lk (a chunk of query rows against a longer key range): the diagonal is shifted."""
+    cfg = synth.LayerShape("concat_chunk", "bf16", 1, 32, 8, 200, 256, 128, 20, 256)
+    log("[case] prefill concat mfma chunked rows")
+    inp = synth.make_prefill_inputs(cfg, synth.BASE_SEED + 14, DEV, mix="concat", ffn="fan_in")
+    prev = std_prev(inp)
+    lo = 120                                                  # rows 120 .. 199 against all 200 keys
+    q_chunk = inp["q_lr"][:, :, lo:].contiguous()
+    prev_chunk = prev[:, :, lo:].contiguous()
+    out, scores = lisa.lisa_attn_prefill(q_chunk, inp["k_lr"], inp["v"], prev_chunk, inp["w1"], inp["w2"],
+                                         mix=lisa.MIX_CONCAT)
+    torch.cuda.synchronize()
+    assert lisa.last_path() == "mfma_scores"
+    rows = np.arange(lo, cfg.L)
+    a_ref, o_ref = hp.oracle_lisa_rows(inp, 0, rows, hp.gather_score_rows(prev, 0, rows), mix=1)
+    local = np.arange(cfg.L - lo)
+    err_o = hp.row_rel_err(hp.gather_out_rows(out, 0, local), o_ref)
+    err_a = hp.scores_row_rel_err(hp.gather_score_rows(scores, 0, local), a_ref, rows, cfg.L, cfg.L)
+    log(f"[parity] concat mfma chunked: err_out={err_o:.3e} err_scores={err_a:.3e}")
+    assert err_o <= hp.TOL[torch.bfloat16] and err_a <= hp.TOL[torch.bfloat16]
