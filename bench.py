@@ -365,26 +365,41 @@ def main():
 
     extra["nf_prefill_standard_attention_no_scores_ms"] = time_steps(step_nf, max(args.steps // 2, 1), 1) * 1e3
 
-    # variants of the alignment module (Sec. 6.5 ablation, Sec. 6.3, Sec. 4) on the generic kernels
+    # variants of the alignment module (Sec. 6.5 ablation, Sec. 6.3, Sec. 4) and the paper's default
+    # CONCAT form at its own widths (Sec. 6.1: FFN 2h -> 256 -> h, r = 20)
     variants = {}
     s0 = sets[0]
     i0 = s0["inp"]
     g = torch.Generator(device=dev).manual_seed(3)
     w_single = (torch.randn((cfg.H, cfg.H), generator=g, device=dev) / cfg.H ** 0.5).to(cfg.torch_dtype)
-    dv = lisa.make_desc(cfg.torch_dtype, cfg.B, cfg.H, cfg.Hkv, cfg.L, cfg.L, cfg.d_k, cfg.r, cfg.F,
-                        act=lisa.ACT_SILU, write_scores=1, out_f32=1)
-    ws_gen = torch.empty(max(lisa.workspace_bytes(dv, lisa.WS_PREFILL), 256), dtype=torch.uint8, device=dev)
-    for name, kw, w1v, w2v, ql, kl in (
-            ("silu", dict(act=lisa.ACT_SILU), i0["w1"], i0["w2"], i0["q_lr"], i0["k_lr"]),
-            ("single_layer", dict(act=lisa.ACT_SINGLE), w_single, None, i0["q_lr"], i0["k_lr"]),
-            ("plus", dict(mix=lisa.MIX_PLUS), None, None, i0["q_lr"], i0["k_lr"]),
-            ("share", dict(mix=lisa.MIX_SHARE), None, None, None, None)):
+    pcfg = cfg.scaled(name="paper_widths", r=20, F=256)
+    pin = synth.make_prefill_inputs(pcfg, synth.BASE_SEED + 3, dev, mix="concat", std_layer=False)
+    for name, kw, w1v, w2v, ql, kl, vv in (
+            ("silu", dict(act=lisa.ACT_SILU), i0["w1"], i0["w2"], i0["q_lr"], i0["k_lr"], i0["v"]),
+            ("single_layer", dict(act=lisa.ACT_SINGLE), w_single, None, i0["q_lr"], i0["k_lr"], i0["v"]),
+            ("plus", dict(mix=lisa.MIX_PLUS), None, None, i0["q_lr"], i0["k_lr"], i0["v"]),
+            ("share", dict(mix=lisa.MIX_SHARE), None, None, None, None, i0["v"]),
+            ("concat_64_256_32_r20", dict(mix=lisa.MIX_CONCAT), pin["w1"], pin["w2"], pin["q_lr"], pin["k_lr"],
+             pin["v"])):
+        dvar = lisa.make_desc(cfg.torch_dtype, cfg.B, cfg.H, cfg.Hkv, cfg.L, cfg.L, cfg.d_k,
+                              ql.shape[3] if ql is not None else 0, w1v.shape[1] if w1v is not None else 0,
+                              write_scores=1, out_f32=1, **kw)
+        ws_var = torch.empty(max(lisa.workspace_bytes(dvar, lisa.WS_PREFILL), 256), dtype=torch.uint8, device=dev)
+
         def step_variant():
-            lisa.lisa_attn_prefill(ql, kl, i0["v"], s0["prev"], w1v, w2v, write_scores=True, out=s0["out"],
-                                   scores_out=s0["a_n"], workspace=ws_gen, **kw)
-        variants[name] = {"ms": time_steps(step_variant, 3, 1) * 1e3, "path": lisa.last_path()}
+            lisa.lisa_attn_prefill(ql, kl, vv, s0["prev"], w1v, w2v, write_scores=True, out=s0["out"],
+                                   scores_out=s0["a_n"], workspace=ws_var, **kw)
+        lisa.profile_enable(False)
+        ms = time_steps(step_variant, 3, 1) * 1e3
+        lisa.profile_enable(True)
+        step_variant()
+        st_v = lisa.profile_collect()
+        lisa.profile_enable(False)
+        variants[name] = {"ms": ms, "path": lisa.last_path(),
+                          "stage_ms": {k: round(v[1] / v[0], 4) for k, v in st_v.items()}}
+        del ws_var
     extra["alignment_variants"] = variants
-    del ws_gen
+    del pin
     cpu = None
     if not args.no_cpu:
         cpu = cpu_baseline(cfg, sets[0]["inp"], sets[0]["prev"], args.cpu_budget)

@@ -94,25 +94,46 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
   }
   const int x_row = min(i0 + (lane >> 2), Lq - 1), xq8 = 8 * (lane & 3);
 
+  // The operands of a tile (this wave's share of the A_{n-1} tile and its K_LR rows) are loaded
+  // into registers one tile ahead, during the FFN of the tile before.
+  constexpr int XCH = (HBO * 16 + NW - 1) / NW;             // A_{n-1} chunks (heads) per wave
+  pf_u32x4 xr[XCH];
+  bf16x8 kop[HPW][2];
+  auto prefetch = [&](int tile) {
+    const int j0 = tile * PF_TK;
+#pragma unroll
+    for (int u = 0; u < XCH; ++u) {
+      const int h = min(wv + NW * u, H - 1);
+      xr[u] = *(const pf_u32x4*)(a.prev + (((size_t)b * H + h) * Lq + x_row) * Lk + min(j0 + xq8, Lk - 8));
+    }
+#pragma unroll
+    for (int u = 0; u < HPW; ++u) {
+      const int h = min(wv + NW * u, H - 1);
+      const bf16_t* kbase = a.k_lr + ((size_t)b * a.Hkv + h / group) * Lk * a.r;
+#pragma unroll
+      for (int half = 0; half < 2; ++half)
+        kop[u][half] = load_lr_operand(kbase + (size_t)min(j0 + 16 * half + c, Lk - 1) * a.r, 8 * g, a.r);
+    }
+  };
+  prefetch(t_first);
+
   for (int tile = t_first; tile < t_last; ++tile) {
     const int j0 = tile * PF_TK;
     __syncthreads();                                        // the stores of the previous tile have read ys
     // ---- 1. input tile -----------------------------------------------------------------------
-    for (int h = wv; h < H; h += NW) {
-      const half_t* src = a.prev + (((size_t)b * H + h) * Lq + x_row) * Lk + min(j0 + xq8, Lk - 8);
-      *(pf_u32x4*)(xs + h * PF_XS_HEAD + lane * 16) = *(const pf_u32x4*)src;
+#pragma unroll
+    for (int u = 0; u < XCH; ++u) {
+      const int h = wv + NW * u;
+      if (h < H) *(pf_u32x4*)(xs + h * PF_XS_HEAD + lane * 16) = xr[u];
     }
 #pragma unroll
     for (int u = 0; u < HPW; ++u) {
       const int h = wv + NW * u;
       if (h >= H) break;
-      const bf16_t* kbase = a.k_lr + ((size_t)b * a.Hkv + h / group) * Lk * a.r;
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
-        const int j = min(j0 + 16 * half + c, Lk - 1);
-        const bf16x8 kop = load_lr_operand(kbase + (size_t)j * a.r, 8 * g, a.r);
         f32x4 d = {0.f, 0.f, 0.f, 0.f};
-        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, qop[u], d, 0, 0, 0);
+        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[u][half], qop[u], d, 0, 0, 0);
         // d[v] = A_delta(row c, key 16 half + 4 g + v) / scale
         f16x4 hv;
 #pragma unroll
@@ -120,6 +141,7 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
         *(f16x4*)(xs + (H + h) * PF_XS_HEAD + c * 64 + (16 * half + 4 * g) * 2) = hv;
       }
     }
+    if (tile + 1 < t_last) prefetch(tile + 1);
     __syncthreads();
     // ---- 2. FFN over the wave's 4 blocks of 16 positions ---------------------------------------
     f32x4 y[NBW][HBO];

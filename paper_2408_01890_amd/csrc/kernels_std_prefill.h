@@ -28,6 +28,7 @@ struct StdPrefillArgs {
   const bf16_t* k;        // [B,Hkv,Lk,128]
   const bf16_t* vt;       // [B,Hkv,Lkp/8,128,8] or null (scores only)
   half_t* scores;         // [B,H,Lq,Lk] or null
+  const float* given;     // GIVEN mode: float32 scores [B,H,Lq,Lk] to take instead of Q K^T (then q, k unused)
   void* out;              // [B,Lq,H,128] or null
   int H, Hkv, Lq, Lk, Lkp, causal, out_f32;
   int pair;               // 1: a workgroup takes two row groups (grid.y = ceil(n_groups / 2)), 0: one
@@ -65,7 +66,9 @@ constexpr int std_prefill_head_lds(bool with_v) {
 // eighth head and its L2 fetches the K / V of those heads only (they are what every row group
 // of a head re-reads).
 // Requires d_k = 128, Lk % 8 == 0.
-template <bool WITH_V>
+// GIVEN: the scores are read from a.given (the unrounded A_n that a LiSA scores kernel left in the
+// workspace) instead of being computed; the rest (masking, online softmax, P V) is the same.
+template <bool WITH_V, bool GIVEN = false>
 __global__ __launch_bounds__(256, 2) void k_std_prefill(StdPrefillArgs a) {
   constexpr int DK = 128;
   __shared__ __align__(16) unsigned char lds[std_prefill_head_lds(WITH_V)];
@@ -83,7 +86,7 @@ __global__ __launch_bounds__(256, 2) void k_std_prefill(StdPrefillArgs a) {
   const int n_groups = (Lq + SP_GROUP - 1) / SP_GROUP;
   // key of MFMA row m = r (see the header)
   const int key_of_r = 16 * (r >> 4) + 8 * ((r >> 2) & 1) + 4 * ((r >> 3) & 1) + (r & 3);
-  const bf16_t* kbase = a.k + ((size_t)b * a.Hkv + kv) * Lk * DK;
+  const bf16_t* kbase = GIVEN ? nullptr : a.k + ((size_t)b * a.Hkv + kv) * Lk * DK;
   const bf16_t* vbase = WITH_V ? a.vt + ((size_t)b * a.Hkv + kv) * (a.Lkp / 8) * (DK * 8) : nullptr;
   // cooperative tile loads: thread -> two 16-byte chunks of the K tile (key, 8 features) and two
   // of the V tile (contiguous 8 KB)
@@ -109,11 +112,12 @@ __global__ __launch_bounds__(256, 2) void k_std_prefill(StdPrefillArgs a) {
 
     // B operands of the score product: Q[row][16 ks + 8 half + e]
     bf16x8 qop[DK / 16];
-    {
+    if (!GIVEN) {
       const bf16_t* qp = a.q + (((size_t)b * H + h) * Lq + my_row) * DK + 8 * half;
 #pragma unroll
       for (int ks = 0; ks < DK / 16; ++ks) qop[ks] = *(const bf16x8*)(qp + 16 * ks);
     }
+    const float* grow = GIVEN ? a.given + (((size_t)b * H + h) * Lq + my_row) * Lk : nullptr;
     half_t* sbase = a.scores ? a.scores + ((size_t)b * H + h) * Lq * Lk : nullptr;
     unsigned char* stg = ss_ + wv * SP_STILE;
 
@@ -122,14 +126,14 @@ __global__ __launch_bounds__(256, 2) void k_std_prefill(StdPrefillArgs a) {
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         const int j = min(tile * SP_TK + ck_key + 16 * u, Lk - 1);
-        kreg[u] = *(const pf_u32x4*)(kbase + (size_t)j * DK + 8 * ck_c);
+        if (!GIVEN) kreg[u] = *(const pf_u32x4*)(kbase + (size_t)j * DK + 8 * ck_c);
         if (WITH_V) vreg[u] = *(const pf_u32x4*)(vbase + (size_t)tile * (SP_TK / 8 * DK * 8) + (tid + 256 * u) * 8);
       }
     };
     auto store_tile = [&](int buf) {
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
-        *(pf_u32x4*)(ks_ + buf * SP_KTILE + (ck_key + 16 * u) * SP_KROW + ck_c * 16) = kreg[u];
+        if (!GIVEN) *(pf_u32x4*)(ks_ + buf * SP_KTILE + (ck_key + 16 * u) * SP_KROW + ck_c * 16) = kreg[u];
         if (WITH_V) *(pf_u32x4*)(vs_ + buf * SP_VTILE + (tid + 256 * u) * 16) = vreg[u];
       }
     };
@@ -154,18 +158,29 @@ __global__ __launch_bounds__(256, 2) void k_std_prefill(StdPrefillArgs a) {
       const unsigned char* kt = ks_ + (tile & 1) * SP_KTILE;
       const unsigned char* vtl = vs_ + (tile & 1) * SP_VTILE;
       const int j0 = tile * SP_TK;
-      f32x16 acc;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < DK / 16; ++ks) {
-        const bf16x8 kop = *(const bf16x8*)(kt + k_rd + 32 * ks);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop, qop[ks], acc, 0, 0, 0);
-      }
-      // acc[8 u + e] = score of key j0 + 16 u + 8 half + e for row r
+      // an[8 u + e] = score of key j0 + 16 u + 8 half + e for row r
       float an[16];
+      if (GIVEN) {
+        // (keys beyond Lk: any in-bounds 8 floats will do, those positions are masked below)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) an[v] = acc[v] * a.scale;
+        for (int u = 0; u < 2; ++u) {
+          const float* gp = grow + min(j0 + 16 * u + 8 * half, Lk - 8);
+          const float4 lo = *(const float4*)gp, hi = *(const float4*)(gp + 4);
+          an[8 * u + 0] = lo.x, an[8 * u + 1] = lo.y, an[8 * u + 2] = lo.z, an[8 * u + 3] = lo.w;
+          an[8 * u + 4] = hi.x, an[8 * u + 5] = hi.y, an[8 * u + 6] = hi.z, an[8 * u + 7] = hi.w;
+        }
+      } else {
+        f32x16 acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < DK / 16; ++ks) {
+          const bf16x8 kop = *(const bf16x8*)(kt + k_rd + 32 * ks);
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop, qop[ks], acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) an[v] = acc[v] * a.scale;
+      }
       const bool full = tile < n_full;
       const int jl = j0 + 8 * half;
       if (a.scores) {

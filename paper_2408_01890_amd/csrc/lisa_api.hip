@@ -252,6 +252,11 @@ KeyStrides dim_major_keys(const lisa_desc* d, int len, int width) {
   return s;
 }
 
+bool std_prefill_fast_ok(const lisa_desc* d);
+size_t std_prefill_ws(const lisa_desc* d);
+int run_softmax_given_fast(const lisa_desc* d, const float* given, const void* v, void* out, void* vt_ws,
+                           hipStream_t st);
+
 template <typename T, typename S>
 int run_lisa(const lisa_desc* d, const void* q_lr, const void* k_lr, KeyStrides ks, const void* v,
              KeyStrides vs, const void* prev, const void* w1, const void* w2, void* out,
@@ -262,7 +267,12 @@ int run_lisa(const lisa_desc* d, const void* q_lr, const void* k_lr, KeyStrides 
   int rc = mfma ? launch_scores_mfma(d, q_lr, k_lr, prev, w1, w2, scores, exact, st)
                 : launch_lisa_scores<T, S>(d, q_lr, k_lr, ks, prev, w1, w2, scores, exact, st);
   if (rc) return rc;
-  rc = launch_softmax_v<T>(d, exact, v, vs, out, st);
+  // softmax and P V from the float32 scores: on the matrix cores where the standard layer's kernel
+  // fits (it then reads the scores instead of computing Q K^T), else the generic kernel
+  if (std_prefill_fast_ok(d))
+    rc = run_softmax_given_fast(d, exact, v, out, (char*)exact + exact_bytes(d), st);
+  else
+    rc = launch_softmax_v<T>(d, exact, v, vs, out, st);
   if (rc == LISA_OK) g_path = mfma ? "mfma_scores" : "generic";
   return rc;
 }
@@ -536,6 +546,39 @@ size_t std_prefill_ws(const lisa_desc* d) {   // V by key chunks
   return round_up((size_t)d->B * d->Hkv * d->d_k * Lkp * 2, 256);
 }
 
+// softmax(A) V for float32 scores A that are already in memory (k_std_prefill in GIVEN mode).
+int run_softmax_given_fast(const lisa_desc* d, const float* given, const void* v, void* out, void* vt_ws,
+                           hipStream_t st) {
+  StdPrefillArgs a{};
+  a.vt = (const bf16_t*)vt_ws;
+  a.given = given;
+  a.out = out;
+  a.H = d->H;
+  a.Hkv = d->Hkv;
+  a.Lq = d->Lq;
+  a.Lk = d->Lk;
+  a.Lkp = (d->Lk + 63) / 64 * 64;
+  a.causal = d->causal;
+  a.out_f32 = d->out_f32;
+  a.scale = 1.f;
+  {
+    dim3 grid(a.Lkp / 64, d->d_k / 64, d->B * d->Hkv);
+    StageScope prof("k_regroup_v", st);
+    if ((uintptr_t)v % 16 == 0)
+      k_regroup_v<true><<<grid, 256, 0, st>>>((const bf16_t*)v, (bf16_t*)vt_ws, d->Lk, a.Lkp, d->d_k);
+    else
+      k_regroup_v<false><<<grid, 256, 0, st>>>((const bf16_t*)v, (bf16_t*)vt_ws, d->Lk, a.Lkp, d->d_k);
+    int rc = check_launch();
+    if (rc) return rc;
+  }
+  const int n_groups = (d->Lq + SP_GROUP - 1) / SP_GROUP;
+  a.pair = (long long)d->H * ((n_groups + 1) / 2) * d->B >= 2 * kComputeUnits;
+  dim3 grid(d->H, a.pair ? (n_groups + 1) / 2 : n_groups, d->B);
+  StageScope prof("k_softmax_v_mfma", st);
+  k_std_prefill<true, true><<<grid, 256, 0, st>>>(a);
+  return check_launch();
+}
+
 int run_std_prefill_fast(const lisa_desc* d, const void* q, const void* k, const void* v, void* scores,
                          void* out, void* workspace, hipStream_t st) {
   StdPrefillArgs a{};
@@ -799,7 +842,8 @@ size_t lisa_workspace_bytes(const lisa_desc* desc, int which) {
       lisa_desc eq;
       if (relu_equivalent(desc, &eq) && prefill_fused_ok(&eq))
         return round_up(prefill_fused_ws(&eq).total, 256) + synth_ffn_bytes(desc);
-      return prefill_fused_ok(desc) ? prefill_fused_ws(desc).total : exact_bytes(desc);
+      if (prefill_fused_ok(desc)) return prefill_fused_ws(desc).total;
+      return exact_bytes(desc) + (std_prefill_fast_ok(desc) ? std_prefill_ws(desc) : 0);
     }
     case LISA_WS_DECODE: {
       if (check_decode(desc) != LISA_OK) return 0;
