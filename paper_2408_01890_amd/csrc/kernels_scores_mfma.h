@@ -34,7 +34,7 @@ struct ScoresMfmaArgs {
   float dscale;
 };
 
-constexpr int SM_CHUNK = 8;       // key tiles per workgroup
+constexpr int SM_CHUNK = 16;      // key tiles per workgroup
 
 // 8 bf16 of a row of r elements starting at element t0 (even), zero beyond r; 4-byte loads.
 __device__ __forceinline__ bf16x8 load_lr_operand(const bf16_t* row, int t0, int r) {
