@@ -5,7 +5,8 @@
 // alignment FFN couples the heads of a position, Sec. 5.1).  Stages:
 //   S1  scores of the chunk into LDS:   LiSA  a_delta[h][j] = scale <q_lr[h], K_LR[kv][j]>  (Eq. 3)
 //                                       std   a[h][j]       = scale <q[h],    K[kv][j]>     (Eq. 2)
-//   S2  (LiSA) A_n = FFN(A_{n-1}) + a_delta on the matrix cores, 16 positions per MFMA block
+//   S2  (LiSA) A_n = FFN(A_{n-1}) + a_delta, or A_n = FFN([A_{n-1}; a_delta]) in CONCAT form, on
+//       the matrix cores, 16 positions per MFMA block
 //   S3  per head: chunk maximum, p = exp(a - max), chunk sum; the score row is stored here
 //   S4  per head: partial O = sum_j p[j] V[kv][j][:]  -- the HBM stream that dominates
 // k_decode_combine merges the per-chunk (max, sum, O) triples of each (sequence, head).
@@ -39,7 +40,9 @@ struct DecodeArgs {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-// LISA_MODE: 1 = LiSA layer, 0 = standard layer.  DK: head dimension (64 or 128).
+// LISA_MODE: 0 = standard layer, 1 = LiSA layer in ADD form (HB = blocks of 16 heads), 2 = LiSA
+// layer in CONCAT form (HB = blocks of 16 FFN inputs, 2H of them; (HB + 1) / 2 output blocks; the
+// FFN weights stay in LDS).  DK: head dimension (64 or 128).
 template <int LISA_MODE, int HB, int FS, int DK, int ACT = 0>
 __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
   constexpr int LPK = DK / 8;        // lanes per key in the 16-byte streams
@@ -60,7 +63,10 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
   if (LISA_MODE) {
     for (int e = tid; e < H * a.r; e += DEC_THREADS)
       q_s[e] = elem<bf16_t>::load(a.q + (size_t)b * H * a.r + e);
-    MfmaFfn<HB, FS, HB, ACT>::stage(a.w1, a.w2, H, a.F, w_s, tid, DEC_THREADS);
+    if (LISA_MODE == 2)
+      MfmaFfn<HB, FS, (HB + 1) / 2, ACT>::stage(a.w1, a.w2, 2 * H, a.F, w_s, tid, DEC_THREADS, 0, H, H);
+    else
+      MfmaFfn<HB, FS, HB, ACT>::stage(a.w1, a.w2, H, a.F, w_s, tid, DEC_THREADS);
     __syncthreads();
     if (a.ks.j == 1 && (a.ks.t & 7) == 0 && (a.ks.h & 7) == 0 && (a.ks.b & 7) == 0) {
       // dimension-major cache with 16-byte aligned rows: 8 keys per lane and load
@@ -133,8 +139,38 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
   }
   __syncthreads();
 
-  // ---- S2: A_n = FFN(A_{n-1}) + a_delta ------------------------------------------------
-  if (LISA_MODE) {
+  // ---- S2: A_n = FFN(A_{n-1}) + a_delta, or FFN([A_{n-1}; a_delta]) ---------------------------
+  if (LISA_MODE == 2) {
+    typedef MfmaFfn<HB, FS, (HB + 1) / 2, ACT> Ffn;
+    const int c = lane & 15, g = lane >> 4;
+    for (int nb = wv; nb < DEC_CK / 16; nb += 4) {
+      // a wave owns its 16 positions: it reads their a_delta of all heads, then overwrites them
+      const int pj = nb * 16 + c, j = j0 + pj;
+      f16x8 x[1][Ffn::KS];
+#pragma unroll
+      for (int ks = 0; ks < Ffn::KS; ++ks)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int ch = 32 * ks + 8 * g + e;
+          _Float16 xv = (_Float16)0.f;
+          if (j < Lk) {
+            if (ch < H) xv = a.prev[((size_t)b * H + ch) * Lk + j];
+            else if (ch < 2 * H) xv = f32_to_half_sat(a_s[(ch - H) * DEC_CK + pj]);
+          }
+          x[0][ks][e] = xv;
+        }
+      f32x4 y[1][(HB + 1) / 2];
+      Ffn::template apply_lds_lean<1>(w_s, x, y);
+#pragma unroll
+      for (int hb = 0; hb < (HB + 1) / 2; ++hb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int h = 16 * hb + 4 * g + v;
+          if (h < H) a_s[h * DEC_CK + pj] = y[0][hb][v];
+        }
+    }
+    __syncthreads();
+  } else if (LISA_MODE) {
     MfmaFfn<HB, FS, HB, ACT> ffn;
     ffn.fetch(w_s);
     const int c = lane & 15, g = lane >> 4;

@@ -284,6 +284,8 @@ bool decode_fast_ok(const lisa_desc* d, bool lisa_layer) {
   if (d->d_k != 64 && d->d_k != 128) return false;
   if (d->H > 64) return false;
   if (lisa_layer) {
+    if (d->mix == LISA_MIX_CONCAT)                         // the instantiated CONCAT shapes
+      return d->act == LISA_ACT_RELU && d->H <= 32 && d->F <= 256 && d->r <= 64;
     if (d->mix != LISA_MIX_ADD || (d->act != LISA_ACT_RELU && d->act != LISA_ACT_SILU)) return false;
     if (d->F > 128 || d->r > 64) return false;
   }
@@ -309,6 +311,14 @@ int launch_decode_part_dk(const lisa_desc* d, const DecodeArgs& a, size_t lds, h
   StageScope prof(LISA_MODE ? "k_decode_part_lisa" : "k_decode_part_std", st);
   kern<<<grid, DEC_THREADS, lds, st>>>(a);
   return check_launch();
+}
+
+// CONCAT form: HBI blocks of 16 FFN inputs (2H of them), hidden width by thirds of the range
+template <int HBI>
+int launch_decode_concat_fs(const lisa_desc* d, const DecodeArgs& a, size_t lds, hipStream_t st) {
+  if (d->F <= 64) return launch_decode_part_dk<2, HBI, 2>(d, a, lds, st);
+  if (d->F <= 128) return launch_decode_part_dk<2, HBI, 4>(d, a, lds, st);
+  return launch_decode_part_dk<2, HBI, 8>(d, a, lds, st);
 }
 
 template <int HB, int ACT>
@@ -339,7 +349,13 @@ int run_decode_fast(const lisa_desc* d, bool lisa_layer, DecodeArgs a, void* out
   a.n_chunk = decode_chunks(d);
   size_t lds = (size_t)d->H * DEC_CK * sizeof(float);
   int rc;
-  if (lisa_layer) {
+  if (lisa_layer && d->mix == LISA_MIX_CONCAT) {
+    const int hbi = d->H <= 16 ? 2 : 4, fs = d->F <= 64 ? 2 : d->F <= 128 ? 4 : 8;
+    const int ks1 = (hbi + 1) / 2, hbo = (hbi + 1) / 2;
+    lds += (size_t)((d->H * d->r + 3) & ~3) * sizeof(float) + (size_t)(2 * fs * ks1 + hbo * fs) * 1024;
+    a.scale = pick_scale(d->delta_scale, d->r);
+    rc = hbi == 2 ? launch_decode_concat_fs<2>(d, a, lds, st) : launch_decode_concat_fs<4>(d, a, lds, st);
+  } else if (lisa_layer) {
     // + q_lr [H][r] as float + the FFN weights in MFMA operand order (mfma_ffn.h: kStageBytes)
     const int hb = (d->H + 15) / 16, fs = (d->F + 31) / 32, ks1 = (hb + 1) / 2;
     lds += (size_t)((d->H * d->r + 3) & ~3) * sizeof(float) + (size_t)(2 * fs * ks1 + hb * fs) * 1024;

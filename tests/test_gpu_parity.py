@@ -979,6 +979,27 @@ def test_lisa_prefill_concat_on_mfma_scores_kernel(case, causal, ffn):
     if causal:
         above = torch.ones(L, L, dtype=torch.bool, device=DEV).triu(1)
         assert torch.all(scores[..., above] == SENTINEL)      # nothing written above the diagonal
+    if not causal:
+        return
+    # the decode step of the same layer (split-context kernel in CONCAT form) = the last prefill row
+    Lmax = L + 8
+    k_cache = torch.zeros((B, Hkv, r, Lmax), dtype=cfg.torch_dtype, device=DEV)
+    v_cache = torch.zeros((B, Hkv, Lmax, dk), dtype=cfg.torch_dtype, device=DEV)
+    lisa.lisa_cache_fill(inp["k_lr"], inp["v"], k_cache, v_cache, dim_major=True)
+    row_prev = prev[:, :, L - 1, :].contiguous()
+    o_d, a_d = lisa.lisa_attn_decode(inp["q_lr"][:, :, L - 1, :].contiguous(), k_cache, v_cache, L, row_prev,
+                                     inp["w1"], inp["w2"], dim_major=True, mix=lisa.MIX_CONCAT)
+    torch.cuda.synchronize()
+    assert lisa.last_path() == "decode_split"
+    worst_o = worst_a = 0.0
+    for b in range(B):
+        a_ref, o_ref = cref.lisa_rows(hp.f64(inp["q_lr"][b])[:, L - 1:L], hp.f64(inp["k_lr"][b]),
+                                      hp.f64(inp["v"][b]), hp.f64(inp["w1"]), hp.f64(inp["w2"]), [0],
+                                      hp.f64(row_prev[b])[None], mix=1)
+        worst_o = max(worst_o, hp.row_rel_err(hp.f64(o_d[b])[None], o_ref))
+        worst_a = max(worst_a, hp.row_rel_err(hp.f64(a_d[b])[None], a_ref))
+    log(f"[parity] concat mfma {name} decode: err_out={worst_o:.3e} err_scores={worst_a:.3e}")
+    assert worst_o <= tol and worst_a <= tol
 
 
 def test_lisa_prefill_concat_mfma_chunked_rows():
