@@ -374,13 +374,17 @@ def main():
     w_single = (torch.randn((cfg.H, cfg.H), generator=g, device=dev) / cfg.H ** 0.5).to(cfg.torch_dtype)
     pcfg = cfg.scaled(name="paper_widths", r=20, F=256)
     pin = synth.make_prefill_inputs(pcfg, synth.BASE_SEED + 3, dev, mix="concat", std_layer=False)
+    slin = synth.make_prefill_inputs(cfg.scaled(name="lisa_sl", r=32), synth.BASE_SEED + 4, dev, std_layer=False)
+    w_sl = (torch.randn((2 * cfg.H, cfg.H), generator=g, device=dev) / (2 * cfg.H) ** 0.5).to(cfg.torch_dtype)
     for name, kw, w1v, w2v, ql, kl, vv in (
             ("silu", dict(act=lisa.ACT_SILU), i0["w1"], i0["w2"], i0["q_lr"], i0["k_lr"], i0["v"]),
             ("single_layer", dict(act=lisa.ACT_SINGLE), w_single, None, i0["q_lr"], i0["k_lr"], i0["v"]),
             ("plus", dict(mix=lisa.MIX_PLUS), None, None, i0["q_lr"], i0["k_lr"], i0["v"]),
             ("share", dict(mix=lisa.MIX_SHARE), None, None, None, None, i0["v"]),
             ("concat_64_256_32_r20", dict(mix=lisa.MIX_CONCAT), pin["w1"], pin["w2"], pin["q_lr"], pin["k_lr"],
-             pin["v"])):
+             pin["v"]),
+            ("lisa_sl_concat_64x32_r32", dict(mix=lisa.MIX_CONCAT, act=lisa.ACT_SINGLE), w_sl, None, slin["q_lr"],
+             slin["k_lr"], slin["v"])):
         dvar = lisa.make_desc(cfg.torch_dtype, cfg.B, cfg.H, cfg.Hkv, cfg.L, cfg.L, cfg.d_k,
                               ql.shape[3] if ql is not None else 0, w1v.shape[1] if w1v is not None else 0,
                               write_scores=1, out_f32=1, **kw)
@@ -399,7 +403,7 @@ def main():
                           "stage_ms": {k: round(v[1] / v[0], 4) for k, v in st_v.items()}}
         del ws_var
     extra["alignment_variants"] = variants
-    del pin
+    del pin, slin
     cpu = None
     if not args.no_cpu:
         cpu = cpu_baseline(cfg, sets[0]["inp"], sets[0]["prev"], args.cpu_budget)

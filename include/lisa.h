@@ -54,9 +54,11 @@ typedef enum { LISA_F32 = 0, LISA_BF16 = 1 } lisa_dtype;
  *                                shared attention, Sec. 6.3);
  *                        SHARE:  A_n = A_{n-1}, the direct sharing the method starts from (DS,
  *                                Sec. 4; q_lr, k_lr, r are ignored as well).
- * The MFMA kernels implement ADD with ReLU or SiLU.  ADD with a single layer, PLUS and SHARE are
- * served by them too (y = W^T x equals the two-layer ReLU network [W,-W] then [I;-I], built in
- * the workspace; SHARE with an all-zero correction); CONCAT runs on the generic kernels. */
+ * MFMA kernels exist for ADD with ReLU or SiLU (fused prefill, split-context decode) and for
+ * CONCAT with ReLU (scores kernel + softmax / P V kernel in prefill, split-context decode).  A
+ * single layer, PLUS and SHARE are served by them too (y = W^T x equals the two-layer ReLU
+ * network [W,-W] then [I;-I], built in the workspace; SHARE with an all-zero correction).  Other
+ * combinations and shapes run on the generic kernels. */
 typedef enum { LISA_MIX_ADD = 0, LISA_MIX_CONCAT = 1, LISA_MIX_PLUS = 2, LISA_MIX_SHARE = 3 } lisa_mix;
 
 /* The alignment FFN (Sec. 6.1 "Model configuration": two layers with ReLU; Sec. 6.5 ablates

@@ -284,23 +284,24 @@ __global__ __launch_bounds__(256) void k_cache_fill_rows(const T* __restrict__ s
 
 // ---------------------------------------------------------------------------------------
 // Two-layer ReLU network that equals a linear map exactly: relu(u) - relu(-u) = u.
-//   w1o [H][2H] = [W, -W],  w2o [2H][H] = [I; -I]     (W = w1_user [H][H], or the identity when
-// w1_user is null).  Lets the single-layer alignment FFN (Sec. 6.5) and LiSA_plus (Sec. 6.3: no
-// FFN, i.e. the identity) run on the kernels built for the two-layer ReLU form.
-// grid ceil(4 H H / 256), block 256.
+//   w1o [Din][2H] = [W, -W],  w2o [2H][H] = [I; -I]     (W = w1_user [Din][H], or the identity when
+// w1_user is null, Din = H).  Lets the single-layer alignment FFN (Sec. 6.5; LiSA_SL: 2h x h on the
+// concatenation) and LiSA_plus (Sec. 6.3: no FFN, i.e. the identity) run on the kernels built for
+// the two-layer ReLU form.
+// grid ceil((2 Din H + 2 H H) / 256), block 256.
 // ---------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void k_synth_relu_ffn(const T* __restrict__ w1_user, T* __restrict__ w1o,
-                                                        T* __restrict__ w2o, int H) {
+                                                        T* __restrict__ w2o, int Din, int H) {
   const int idx = blockIdx.x * 256 + threadIdx.x;
-  const int n = 2 * H * H;
-  if (idx < n) {
+  const int n1 = 2 * Din * H, n2 = 2 * H * H;
+  if (idx < n1) {
     const int c = idx / (2 * H), f = idx % (2 * H);        // w1o[c][f]
     const int fo = f < H ? f : f - H;
     const float w = w1_user ? elem<T>::load(w1_user + (size_t)c * H + fo) : (c == fo ? 1.f : 0.f);
     elem<T>::store(w1o + idx, f < H ? w : -w);
-  } else if (idx < 2 * n) {
-    const int j = idx - n, f = j / H, h = j % H;           // w2o[f][h]
+  } else if (idx < n1 + n2) {
+    const int j = idx - n1, f = j / H, h = j % H;          // w2o[f][h]
     elem<T>::store(w2o + j, f == h ? 1.f : (f == H + h ? -1.f : 0.f));
   }
 }

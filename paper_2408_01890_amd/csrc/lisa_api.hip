@@ -799,11 +799,11 @@ size_t lisa_kcache_saved_bytes(const lisa_desc* desc, int n_lisa_layers) {
 constexpr int kShareRank = 8;
 bool relu_equivalent(const lisa_desc* d, lisa_desc* eq) {
   if (d->dtype != LISA_BF16) return false;
-  const bool single = d->mix == LISA_MIX_ADD && d->act == LISA_ACT_SINGLE;
-  if (!single && d->mix != LISA_MIX_PLUS && d->mix != LISA_MIX_SHARE) return false;
+  const bool ffn = d->mix == LISA_MIX_ADD || d->mix == LISA_MIX_CONCAT;
+  if (ffn && d->act != LISA_ACT_SINGLE) return false;      // two-layer forms run as they are
   if (2 * d->H > 128) return false;
   *eq = *d;
-  eq->mix = LISA_MIX_ADD;
+  eq->mix = d->mix == LISA_MIX_CONCAT ? LISA_MIX_CONCAT : LISA_MIX_ADD;
   eq->act = LISA_ACT_RELU;
   eq->F = 2 * d->H;
   if (d->mix == LISA_MIX_SHARE) eq->r = kShareRank;
@@ -817,7 +817,8 @@ struct SynthWs {
 SynthWs synth_ws(const lisa_desc* d) {
   SynthWs s;
   s.w = 0;
-  s.q0 = round_up((size_t)4 * d->H * d->H * 2, 256);
+  const size_t Din = d->mix == LISA_MIX_CONCAT ? 2 * d->H : d->H;
+  s.q0 = round_up((2 * Din * d->H + (size_t)2 * d->H * d->H) * 2, 256);
   s.k0 = s.q0;
   s.total = s.q0;
   if (d->mix == LISA_MIX_SHARE) {
@@ -835,11 +836,13 @@ int synth_relu_ffn(const lisa_desc* d, const void* w1_user, void* workspace, siz
                    const void** w2o, const void** q_lr, const void** k_lr, hipStream_t st) {
   const SynthWs sw = synth_ws(d);
   char* base = (char*)workspace + offset;
+  const int Din = d->mix == LISA_MIX_CONCAT ? 2 * d->H : d->H;
+  const bool ffn = d->mix == LISA_MIX_ADD || d->mix == LISA_MIX_CONCAT;
   bf16_t* a = (bf16_t*)(base + sw.w);
-  bf16_t* b = a + (size_t)2 * d->H * d->H;
+  bf16_t* b = a + (size_t)2 * Din * d->H;
   StageScope prof("k_synth_relu_ffn", st);
-  k_synth_relu_ffn<bf16_t><<<(4 * d->H * d->H + 255) / 256, 256, 0, st>>>(
-      d->act == LISA_ACT_SINGLE && d->mix == LISA_MIX_ADD ? (const bf16_t*)w1_user : nullptr, a, b, d->H);
+  k_synth_relu_ffn<bf16_t><<<(2 * Din * d->H + 2 * d->H * d->H + 255) / 256, 256, 0, st>>>(
+      ffn ? (const bf16_t*)w1_user : nullptr, a, b, Din, d->H);
   *w1o = a;
   *w2o = b;
   if (d->mix == LISA_MIX_SHARE) {
@@ -859,7 +862,9 @@ size_t lisa_workspace_bytes(const lisa_desc* desc, int which) {
       if (relu_equivalent(desc, &eq) && prefill_fused_ok(&eq))
         return round_up(prefill_fused_ws(&eq).total, 256) + synth_ffn_bytes(desc);
       if (prefill_fused_ok(desc)) return prefill_fused_ws(desc).total;
-      return exact_bytes(desc) + (std_prefill_fast_ok(desc) ? std_prefill_ws(desc) : 0);
+      const size_t generic = exact_bytes(desc) + (std_prefill_fast_ok(desc) ? std_prefill_ws(desc) : 0);
+      if (relu_equivalent(desc, &eq) && scores_mfma_ok(&eq)) return round_up(generic, 256) + synth_ffn_bytes(desc);
+      return generic;
     }
     case LISA_WS_DECODE: {
       if (check_decode(desc) != LISA_OK) return 0;
@@ -1050,6 +1055,13 @@ int lisa_attn_prefill(const lisa_desc* desc, const void* q_lr, const void* k_lr,
                         st);
     if (rc) return rc;
     return run_prefill_fused(&eq, q_lr, k_lr, v, scores_prev, w1e, w2e, out, scores, workspace, st);
+  }
+  if (relu_equivalent(desc, &eq) && scores_mfma_ok(&eq)) {   // the single layer over the concatenation
+    const size_t generic = exact_bytes(desc) + (std_prefill_fast_ok(desc) ? std_prefill_ws(desc) : 0);
+    const void *w1e, *w2e;
+    rc = synth_relu_ffn(desc, w1, workspace, round_up(generic, 256), &w1e, &w2e, &q_lr, &k_lr, st);
+    if (rc) return rc;
+    return run_lisa<bf16_t, half_t>(&eq, q_lr, k_lr, ks, v, vs, scores_prev, w1e, w2e, out, scores, exact, st);
   }
   if (desc->dtype == LISA_F32)
     return run_lisa<float, float>(desc, q_lr, k_lr, ks, v, vs, scores_prev, w1, w2, out, scores,
