@@ -54,8 +54,8 @@ typedef enum { LISA_F32 = 0, LISA_BF16 = 1 } lisa_dtype;
  *                                shared attention, Sec. 6.3);
  *                        SHARE:  A_n = A_{n-1}, the direct sharing the method starts from (DS,
  *                                Sec. 4; q_lr, k_lr, r are ignored as well).
- * MFMA kernels exist for ADD with ReLU or SiLU (fused prefill, split-context decode) and for
- * CONCAT with ReLU (scores kernel + softmax / P V kernel in prefill, split-context decode).  A
+ * MFMA kernels exist for ADD (fused prefill, split-context decode) and for CONCAT (scores kernel
+ * + softmax / P V kernel in prefill, split-context decode), each with ReLU or SiLU.  A
  * single layer, PLUS and SHARE are served by them too (y = W^T x equals the two-layer ReLU
  * network [W,-W] then [I;-I], built in the workspace; SHARE with an all-zero correction).  Other
  * combinations and shapes run on the generic kernels. */

@@ -46,11 +46,11 @@ __device__ __forceinline__ bf16x8 load_lr_operand(const bf16_t* row, int t0, int
   return __builtin_bit_cast(bf16x8, v);
 }
 
-// HBI = ceil(2H / 16) input blocks, FS = ceil(F / 32), HBO = ceil(H / 16).
+// HBI = ceil(2H / 16) input blocks, FS = ceil(F / 32), HBO = ceil(H / 16), ACT: 0 ReLU, 1 SiLU.
 // grid (ceil(max tiles / SM_CHUNK), ceil(Lq / 16), B), block 512.
-template <int HBI, int FS, int HBO>
+template <int HBI, int FS, int HBO, int ACT = 0>
 __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
-  typedef MfmaFfn<HBI, FS, HBO> Ffn;
+  typedef MfmaFfn<HBI, FS, HBO, ACT> Ffn;
   constexpr int KS = Ffn::KS, NW = 8, NBW = 4;
   constexpr int NBLK = 2;                                   // blocks per FFN call (they share each weight read)
   extern __shared__ __align__(16) unsigned char sm_lds[];

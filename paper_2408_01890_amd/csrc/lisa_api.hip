@@ -155,7 +155,8 @@ int launch_std_scores(const lisa_desc* d, const void* q, const void* k, KeyStrid
 
 // CONCAT with the two-layer ReLU FFN on the matrix cores (dense prefill tensors only).
 bool scores_mfma_ok(const lisa_desc* d) {
-  if (d->dtype != LISA_BF16 || d->mix != LISA_MIX_CONCAT || d->act != LISA_ACT_RELU) return false;
+  if (d->dtype != LISA_BF16 || d->mix != LISA_MIX_CONCAT) return false;
+  if (d->act != LISA_ACT_RELU && d->act != LISA_ACT_SILU) return false;
   if (d->Lq == 1) return false;                            // decode rows: the generic kernel (strided caches)
   if (d->H > 32 || d->F > 256 || d->r > 32 || d->r % 2 != 0 || d->Lk % 8 != 0) return false;
   return (long long)d->Lq * d->Lk < (1LL << 31);
@@ -164,7 +165,7 @@ bool scores_mfma_ok(const lisa_desc* d) {
 template <int HBI, int FS, int HBO>
 int launch_scores_mfma_t(const lisa_desc* d, const ScoresMfmaArgs& a, hipStream_t st) {
   const int lds = scores_mfma_lds<HBI, FS, HBO>(d->H);
-  auto kern = k_lisa_scores_mfma<HBI, FS, HBO>;
+  auto kern = d->act == LISA_ACT_SILU ? k_lisa_scores_mfma<HBI, FS, HBO, 1> : k_lisa_scores_mfma<HBI, FS, HBO, 0>;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e != hipSuccess) return hip_fail(e);
   const int tiles = (d->Lk + PF_TK - 1) / PF_TK;
@@ -285,7 +286,7 @@ bool decode_fast_ok(const lisa_desc* d, bool lisa_layer) {
   if (d->H > 64) return false;
   if (lisa_layer) {
     if (d->mix == LISA_MIX_CONCAT)                         // the instantiated CONCAT shapes
-      return d->act == LISA_ACT_RELU && d->H <= 32 && d->F <= 256 && d->r <= 64;
+      return (d->act == LISA_ACT_RELU || d->act == LISA_ACT_SILU) && d->H <= 32 && d->F <= 256 && d->r <= 64;
     if (d->mix != LISA_MIX_ADD || (d->act != LISA_ACT_RELU && d->act != LISA_ACT_SILU)) return false;
     if (d->F > 128 || d->r > 64) return false;
   }
@@ -314,11 +315,16 @@ int launch_decode_part_dk(const lisa_desc* d, const DecodeArgs& a, size_t lds, h
 }
 
 // CONCAT form: HBI blocks of 16 FFN inputs (2H of them), hidden width by thirds of the range
+template <int HBI, int ACT>
+int launch_decode_concat_act(const lisa_desc* d, const DecodeArgs& a, size_t lds, hipStream_t st) {
+  if (d->F <= 64) return launch_decode_part_dk<2, HBI, 2, ACT>(d, a, lds, st);
+  if (d->F <= 128) return launch_decode_part_dk<2, HBI, 4, ACT>(d, a, lds, st);
+  return launch_decode_part_dk<2, HBI, 8, ACT>(d, a, lds, st);
+}
 template <int HBI>
 int launch_decode_concat_fs(const lisa_desc* d, const DecodeArgs& a, size_t lds, hipStream_t st) {
-  if (d->F <= 64) return launch_decode_part_dk<2, HBI, 2>(d, a, lds, st);
-  if (d->F <= 128) return launch_decode_part_dk<2, HBI, 4>(d, a, lds, st);
-  return launch_decode_part_dk<2, HBI, 8>(d, a, lds, st);
+  return d->act == LISA_ACT_SILU ? launch_decode_concat_act<HBI, 1>(d, a, lds, st)
+                                 : launch_decode_concat_act<HBI, 0>(d, a, lds, st);
 }
 
 template <int HB, int ACT>

@@ -870,7 +870,7 @@ def test_nf_strategy_standard_prefill_then_lisa_decode(dim_major):
     assert bool((tail == SENTINEL).all()) and bool((v_cache[:, :, L + 1:] == SENTINEL).all())
 
 
-@pytest.mark.parametrize("variant", [v for v in VARIANTS if v[0] in ("silu_add", "single_add", "single_concat", "plus", "share")], ids=lambda v: v[0])
+@pytest.mark.parametrize("variant", [v for v in VARIANTS if v[0] in ("silu_add", "silu_concat", "single_add", "single_concat", "plus", "share")], ids=lambda v: v[0])
 def test_variants_that_run_on_the_mfma_kernels(variant):
     """The single-layer FFN, LiSA_plus and direct sharing are exact two-layer ReLU networks ([W,-W]
     then [I;-I]; direct sharing with an all-zero correction), so on MFMA-eligible shapes the library
