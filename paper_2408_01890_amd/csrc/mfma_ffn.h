@@ -148,9 +148,10 @@ struct MfmaFfn {
     }
   }
 
-  // apply_lds() for wide networks (many weight operands): scheduling fences after every group of
-  // products keep the compiler from hoisting all weight reads to the top, which would need more
-  // registers than a wave has.
+  // apply_lds() for wide networks (many weight operands): the weight operands of the next group
+  // of products are read while the current group runs, and scheduling fences between the groups
+  // keep the compiler from hoisting all weight reads to the top, which would need more registers
+  // than a wave has.
   template <int NBLK>
   __device__ __forceinline__ static void apply_lds_lean(const unsigned short* lds, const f16x8 (&x)[NBLK][KS],
                                                         f32x4 (&y)[NBLK][HBO]) {
@@ -158,27 +159,33 @@ struct MfmaFfn {
     const unsigned short* l1 = lds + lane * 8;
     const unsigned short* l2 = l1 + FB * KS * 512;
     f16x8 hid[NBLK][FS];
+    f16x8 wn[KS];
 #pragma unroll
-    for (int s = 0; s < FS; ++s) {
+    for (int ks = 0; ks < KS; ++ks) wn[ks] = *(const f16x8*)(l1 + ks * 512);
 #pragma unroll
-      for (int half = 0; half < 2; ++half) {
-        f32x4 acc[NBLK];
+    for (int fb = 0; fb < FB; ++fb) {                       // hidden block fb = 2 s + half
+      f16x8 w[KS];
 #pragma unroll
-        for (int n = 0; n < NBLK; ++n) acc[n] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int ks = 0; ks < KS; ++ks) w[ks] = wn[ks];
+      if (fb + 1 < FB) {
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          const f16x8 w = *(const f16x8*)(l1 + ((2 * s + half) * KS + ks) * 512);
+        for (int ks = 0; ks < KS; ++ks) wn[ks] = *(const f16x8*)(l1 + ((fb + 1) * KS + ks) * 512);
+      }
+      f32x4 acc[NBLK];
 #pragma unroll
-          for (int n = 0; n < NBLK; ++n)
-            acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w, x[n][ks], acc[n], 0, 0, 0);
-        }
+      for (int n = 0; n < NBLK; ++n) acc[n] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
         for (int n = 0; n < NBLK; ++n)
+          acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w[ks], x[n][ks], acc[n], 0, 0, 0);
 #pragma unroll
-          for (int v = 0; v < 4; ++v) hid[n][s][4 * half + v] = activate(acc[n][v]);
-      }
+      for (int n = 0; n < NBLK; ++n)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) hid[n][fb >> 1][4 * (fb & 1) + v] = activate(acc[n][v]);
       __builtin_amdgcn_sched_barrier(0);
     }
+    f16x8 vn = *(const f16x8*)l2;
 #pragma unroll
     for (int hb = 0; hb < HBO; ++hb) {
       f32x4 acc[NBLK];
@@ -186,14 +193,15 @@ struct MfmaFfn {
       for (int n = 0; n < NBLK; ++n) acc[n] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int s = 0; s < FS; ++s) {
-        const f16x8 w = *(const f16x8*)(l2 + (hb * FS + s) * 512);
+        const f16x8 w = vn;
+        if (hb * FS + s + 1 < HBO * FS) vn = *(const f16x8*)(l2 + (hb * FS + s + 1) * 512);
 #pragma unroll
         for (int n = 0; n < NBLK; ++n)
           acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w, hid[n][s], acc[n], 0, 0, 0);
+        if ((s & 1) == 1) __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
       for (int n = 0; n < NBLK; ++n) y[n][hb] = acc[n];
-      __builtin_amdgcn_sched_barrier(0);
     }
   }
 
