@@ -116,10 +116,12 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
     }
   };
   prefetch(t_first);
+  // (the barriers of the tile loop order LDS traffic only: __syncthreads() would also wait for the
+  // global stores of the previous tile and for the prefetch)
 
   for (int tile = t_first; tile < t_last; ++tile) {
     const int j0 = tile * PF_TK;
-    __syncthreads();                                        // the stores of the previous tile have read ys
+    lds_barrier();                                           // the stores of the previous tile have read ys
     // ---- 1. input tile -----------------------------------------------------------------------
 #pragma unroll
     for (int u = 0; u < XCH; ++u) {
@@ -142,7 +144,7 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
       }
     }
     if (tile + 1 < t_last) prefetch(tile + 1);
-    __syncthreads();
+    lds_barrier();   
     // ---- 2. FFN over the wave's 4 blocks of 16 positions ---------------------------------------
     f32x4 y[NBW][HBO];
 #pragma unroll
@@ -174,7 +176,7 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
 #pragma unroll
         for (int hb = 0; hb < HBO; ++hb) y[q + n][hb] = yq[n][hb];
     }
-    __syncthreads();                                        // every wave has read the input tile
+    lds_barrier();                                           // every wave has read the input tile
     // ---- 3. output tile: float32 [head][row][key] over the input tile, then out by heads ---------
 #pragma unroll
     for (int qn = 0; qn < NBW; ++qn) {
@@ -187,7 +189,7 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
           if (hl < H) *(float*)(ys + hl * PF_YS_HEAD + i * PF_YS_ROW + (16 * kh + c) * 4) = y[qn][hb][v];
         }
     }
-    __syncthreads();
+    lds_barrier();   
     {
       const int row = lane >> 2, ch = lane & 3;             // 8 keys of a row per lane
       const int gi = i0 + row, jc = j0 + 8 * ch;
