@@ -10,41 +10,31 @@
 // One workgroup (8 waves) = 16 query rows x up to SM_CHUNK tiles of 32 keys.  Per tile:
 //   1. the A_{n-1} tile of all heads goes to LDS ([head][row][key], half); wave w computes the
 //      A_delta tile of heads w, w + 8, ... with two 16x16x32 MFMAs each (A = K_LR rows, B = Q_LR
-//      rows, assembled from 4-byte loads: rows of r elements are not 16-byte aligned) and
+//      rows, both read from copies zero-padded to 32 elements per row: k_prepare_prefill) and
 //      appends it as heads H .. 2H-1 of the same LDS array;
 //   2. every wave runs the FFN (mfma_ffn.h, weights read from their LDS image) on 4 of the 32
 //      blocks of 16 positions, the 2H input "heads" fetched with transposing LDS reads;
 //   3. the results go to LDS as float32 [head][row][key] (over the input tile) and leave by
 //      heads in whole rows: 128 bytes of float32 and 64 bytes of half per row and tile.
-// Requires Lk % 8 == 0, r even and <= 32, 2H <= 64, F <= 256.
+// Requires Lk % 8 == 0, r <= 32, 2H <= 64, F <= 256.
 #pragma once
 #include "kernels_prefill.h"
 
 namespace lisa {
 
 struct ScoresMfmaArgs {
-  const bf16_t* q_lr;   // [B,H,Lq,r]
-  const bf16_t* k_lr;   // [B,Hkv,Lk,r]
+  const bf16_t* qp;     // [B,H,Lqp,32]   Q_LR rows zero-padded to 32 elements
+  const bf16_t* kp;     // [B,Hkv,Lkp,32] K_LR rows likewise
   const half_t* prev;   // [B,H,Lq,Lk]
   const bf16_t* w1;     // [2H,F]
   const bf16_t* w2;     // [F,H]
   half_t* scores;       // [B,H,Lq,Lk] or null
   float* exact;         // [B,H,Lq,Lk]
-  int H, Hkv, Lq, Lk, r, F, causal;
+  int H, Hkv, Lq, Lk, Lqp, Lkp, F, causal;
   float dscale;
 };
 
 constexpr int SM_CHUNK = 16;      // key tiles per workgroup
-
-// 8 bf16 of a row of r elements starting at element t0 (even), zero beyond r; 4-byte loads.
-__device__ __forceinline__ bf16x8 load_lr_operand(const bf16_t* row, int t0, int r) {
-  unsigned w[4];
-#pragma unroll
-  for (int d = 0; d < 4; ++d) w[d] = t0 + 2 * d + 1 < r ? *(const unsigned*)(row + t0 + 2 * d) : 0u;
-  typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
-  u32x4_t v = {w[0], w[1], w[2], w[3]};
-  return __builtin_bit_cast(bf16x8, v);
-}
 
 // HBI = ceil(2H / 16) input blocks, FS = ceil(F / 32), HBO = ceil(H / 16), ACT: 0 ReLU, 1 SiLU.
 // grid (ceil(max tiles / SM_CHUNK), ceil(Lq / 16), B), block 512.
@@ -81,8 +71,7 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
 #pragma unroll
   for (int u = 0; u < HPW; ++u) {
     const int h = min(wv + NW * u, H - 1);
-    const bf16_t* qrow = a.q_lr + (((size_t)b * H + h) * Lq + min(i0 + c, Lq - 1)) * a.r;
-    qop[u] = load_lr_operand(qrow, 8 * g, a.r);
+    qop[u] = *(const bf16x8*)(a.qp + (((size_t)b * H + h) * a.Lqp + min(i0 + c, Lq - 1)) * 32 + 8 * g);
   }
   // transposing LDS reads of stage 2 (see the fused prefill kernel): lane 4 k' + q4 of a 16-lane
   // group passes the address of head k', keys 4 q4 .. 4 q4 + 3, and receives key c of heads k' = 0..3
@@ -109,10 +98,10 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
 #pragma unroll
     for (int u = 0; u < HPW; ++u) {
       const int h = min(wv + NW * u, H - 1);
-      const bf16_t* kbase = a.k_lr + ((size_t)b * a.Hkv + h / group) * Lk * a.r;
+      const bf16_t* kbase = a.kp + ((size_t)b * a.Hkv + h / group) * a.Lkp * 32 + 8 * g;
 #pragma unroll
       for (int half = 0; half < 2; ++half)
-        kop[u][half] = load_lr_operand(kbase + (size_t)min(j0 + 16 * half + c, Lk - 1) * a.r, 8 * g, a.r);
+        kop[u][half] = *(const bf16x8*)(kbase + (size_t)min(j0 + 16 * half + c, Lk - 1) * 32);
     }
   };
   prefetch(t_first);

@@ -158,7 +158,7 @@ bool scores_mfma_ok(const lisa_desc* d) {
   if (d->dtype != LISA_BF16 || d->mix != LISA_MIX_CONCAT) return false;
   if (d->act != LISA_ACT_RELU && d->act != LISA_ACT_SILU) return false;
   if (d->Lq == 1) return false;                            // decode rows: the generic kernel (strided caches)
-  if (d->H > 32 || d->F > 256 || d->r > 32 || d->r % 2 != 0 || d->Lk % 8 != 0) return false;
+  if (d->H > 32 || d->F > 256 || d->r > 32 || d->Lk % 8 != 0) return false;
   return (long long)d->Lq * d->Lk < (1LL << 31);
 }
 
@@ -175,11 +175,46 @@ int launch_scores_mfma_t(const lisa_desc* d, const ScoresMfmaArgs& a, hipStream_
   return check_launch();
 }
 
-int launch_scores_mfma(const lisa_desc* d, const void* q_lr, const void* k_lr, const void* prev, const void* w1,
-                       const void* w2, void* scores, float* exact, hipStream_t st) {
+// Workspace of the CONCAT path behind the float32 scores: Q_LR / K_LR rows padded to 32 elements
+// and V by key chunks (k_prepare_prefill), the latter only where the MFMA softmax kernel runs.
+struct ConcatWs {
+  size_t qp, kp, vt, total;
+  int Lqp, Lkp;
+};
+bool std_prefill_fast_ok(const lisa_desc* d);
+ConcatWs concat_ws(const lisa_desc* d) {
+  ConcatWs w;
+  w.Lqp = (d->Lq + PF_ROWS - 1) / PF_ROWS * PF_ROWS;
+  w.Lkp = (d->Lk + 63) / 64 * 64;
+  w.qp = exact_bytes(d);
+  w.kp = w.qp + round_up((size_t)d->B * d->H * w.Lqp * 32 * 2, 256);
+  w.vt = w.kp + round_up((size_t)d->B * d->Hkv * w.Lkp * 32 * 2, 256);
+  w.total = w.vt + (std_prefill_fast_ok(d) ? round_up((size_t)d->B * d->Hkv * d->d_k * w.Lkp * 2, 256) : 0);
+  return w;
+}
+
+int launch_scores_mfma(const lisa_desc* d, const void* q_lr, const void* k_lr, const void* v, const void* prev,
+                       const void* w1, const void* w2, void* scores, float* exact, hipStream_t st) {
+  const ConcatWs w = concat_ws(d);
+  char* ws = (char*)exact;
+  {
+    // V is regrouped in the same launch when the MFMA softmax kernel follows (d_k = 128)
+    const bool with_v = std_prefill_fast_ok(d);
+    const int dk = with_v ? d->d_k : 0;
+    StageScope prof("k_prepare_prefill", st);
+    const size_t rows = (size_t)d->B * d->H * w.Lqp + (size_t)d->B * d->Hkv * w.Lkp;
+    const size_t blocks = (size_t)(w.Lkp / 64) * (dk / 64) * d->B * d->Hkv + (rows + 63) / 64;
+    const bool vec = (uintptr_t)v % 16 == 0;
+    auto kern = vec ? k_prepare_prefill<true> : k_prepare_prefill<false>;
+    kern<<<(unsigned)blocks, 256, 0, st>>>((const bf16_t*)q_lr, (const bf16_t*)k_lr, (const bf16_t*)v,
+                                          (bf16_t*)(ws + w.qp), (bf16_t*)(ws + w.kp), (bf16_t*)(ws + w.vt),
+                                          d->B, d->H, d->Hkv, d->Lq, d->Lk, w.Lqp, w.Lkp, d->r, dk);
+    int rc = check_launch();
+    if (rc) return rc;
+  }
   ScoresMfmaArgs a{};
-  a.q_lr = (const bf16_t*)q_lr;
-  a.k_lr = (const bf16_t*)k_lr;
+  a.qp = (const bf16_t*)(ws + w.qp);
+  a.kp = (const bf16_t*)(ws + w.kp);
   a.prev = (const half_t*)prev;
   a.w1 = (const bf16_t*)w1;
   a.w2 = (const bf16_t*)w2;
@@ -189,7 +224,8 @@ int launch_scores_mfma(const lisa_desc* d, const void* q_lr, const void* k_lr, c
   a.Hkv = d->Hkv;
   a.Lq = d->Lq;
   a.Lk = d->Lk;
-  a.r = d->r;
+  a.Lqp = w.Lqp;
+  a.Lkp = w.Lkp;
   a.F = d->F;
   a.causal = d->causal;
   a.dscale = pick_scale(d->delta_scale, d->r);
@@ -265,13 +301,14 @@ int run_lisa(const lisa_desc* d, const void* q_lr, const void* k_lr, KeyStrides 
   // The softmax reads the unrounded float32 A_n from the workspace: rounding A_n to the
   // 2-byte score type first would move each probability by up to |A_n| 2^-11.
   const bool mfma = scores_mfma_ok(d);
-  int rc = mfma ? launch_scores_mfma(d, q_lr, k_lr, prev, w1, w2, scores, exact, st)
+  int rc = mfma ? launch_scores_mfma(d, q_lr, k_lr, v, prev, w1, w2, scores, exact, st)
                 : launch_lisa_scores<T, S>(d, q_lr, k_lr, ks, prev, w1, w2, scores, exact, st);
   if (rc) return rc;
   // softmax and P V from the float32 scores: on the matrix cores where the standard layer's kernel
   // fits (it then reads the scores instead of computing Q K^T), else the generic kernel
   if (std_prefill_fast_ok(d))
-    rc = run_softmax_given_fast(d, exact, v, out, (char*)exact + exact_bytes(d), st);
+    rc = run_softmax_given_fast(d, exact, mfma ? nullptr : v, out,
+                                (char*)exact + (mfma ? concat_ws(d).vt : exact_bytes(d)), st);
   else
     rc = launch_softmax_v<T>(d, exact, v, vs, out, st);
   if (rc == LISA_OK) g_path = mfma ? "mfma_scores" : "generic";
@@ -583,7 +620,7 @@ int run_softmax_given_fast(const lisa_desc* d, const float* given, const void* v
   a.causal = d->causal;
   a.out_f32 = d->out_f32;
   a.scale = 1.f;
-  {
+  if (v) {                                                   // (null: vt_ws already holds the regrouped V)
     dim3 grid(a.Lkp / 64, d->d_k / 64, d->B * d->Hkv);
     StageScope prof("k_regroup_v", st);
     if ((uintptr_t)v % 16 == 0)
@@ -868,9 +905,10 @@ size_t lisa_workspace_bytes(const lisa_desc* desc, int which) {
       if (relu_equivalent(desc, &eq) && prefill_fused_ok(&eq))
         return round_up(prefill_fused_ws(&eq).total, 256) + synth_ffn_bytes(desc);
       if (prefill_fused_ok(desc)) return prefill_fused_ws(desc).total;
-      const size_t generic = exact_bytes(desc) + (std_prefill_fast_ok(desc) ? std_prefill_ws(desc) : 0);
-      if (relu_equivalent(desc, &eq) && scores_mfma_ok(&eq)) return round_up(generic, 256) + synth_ffn_bytes(desc);
-      return generic;
+      if (scores_mfma_ok(desc)) return concat_ws(desc).total;
+      if (relu_equivalent(desc, &eq) && scores_mfma_ok(&eq))
+        return round_up(concat_ws(&eq).total, 256) + synth_ffn_bytes(desc);
+      return exact_bytes(desc) + (std_prefill_fast_ok(desc) ? std_prefill_ws(desc) : 0);
     }
     case LISA_WS_DECODE: {
       if (check_decode(desc) != LISA_OK) return 0;
@@ -1063,9 +1101,8 @@ int lisa_attn_prefill(const lisa_desc* desc, const void* q_lr, const void* k_lr,
     return run_prefill_fused(&eq, q_lr, k_lr, v, scores_prev, w1e, w2e, out, scores, workspace, st);
   }
   if (relu_equivalent(desc, &eq) && scores_mfma_ok(&eq)) {   // the single layer over the concatenation
-    const size_t generic = exact_bytes(desc) + (std_prefill_fast_ok(desc) ? std_prefill_ws(desc) : 0);
     const void *w1e, *w2e;
-    rc = synth_relu_ffn(desc, w1, workspace, round_up(generic, 256), &w1e, &w2e, &q_lr, &k_lr, st);
+    rc = synth_relu_ffn(desc, w1, workspace, round_up(concat_ws(&eq).total, 256), &w1e, &w2e, &q_lr, &k_lr, st);
     if (rc) return rc;
     return run_lisa<bf16_t, half_t>(&eq, q_lr, k_lr, ks, v, vs, scores_prev, w1e, w2e, out, scores, exact, st);
   }
