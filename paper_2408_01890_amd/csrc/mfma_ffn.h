@@ -148,7 +148,7 @@ struct MfmaFfn {
     }
   }
 
-  // apply_lds() for wide networks (many weight operands): the weight operands of the next group
+  // apply_lds() for wide networks (many weight operands): the weight operands of the next groups
   // of products are read while the current group runs, and scheduling fences between the groups
   // keep the compiler from hoisting all weight reads to the top, which would need more registers
   // than a wave has.
@@ -159,17 +159,21 @@ struct MfmaFfn {
     const unsigned short* l1 = lds + lane * 8;
     const unsigned short* l2 = l1 + FB * KS * 512;
     f16x8 hid[NBLK][FS];
-    f16x8 wn[KS];
+    constexpr int PD = 3;                                   // groups of weight operands in flight
+    f16x8 wq[PD][KS];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) wn[ks] = *(const f16x8*)(l1 + ks * 512);
+    for (int p = 0; p < PD; ++p)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        if (p < FB) wq[p][ks] = *(const f16x8*)(l1 + (p * KS + ks) * 512);
 #pragma unroll
     for (int fb = 0; fb < FB; ++fb) {                       // hidden block fb = 2 s + half
       f16x8 w[KS];
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) w[ks] = wn[ks];
-      if (fb + 1 < FB) {
+      for (int ks = 0; ks < KS; ++ks) w[ks] = wq[fb % PD][ks];
+      if (fb + PD < FB) {
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) wn[ks] = *(const f16x8*)(l1 + ((fb + 1) * KS + ks) * 512);
+        for (int ks = 0; ks < KS; ++ks) wq[fb % PD][ks] = *(const f16x8*)(l1 + ((fb + PD) * KS + ks) * 512);
       }
       f32x4 acc[NBLK];
 #pragma unroll
@@ -185,7 +189,11 @@ struct MfmaFfn {
         for (int v = 0; v < 4; ++v) hid[n][fb >> 1][4 * (fb & 1) + v] = activate(acc[n][v]);
       __builtin_amdgcn_sched_barrier(0);
     }
-    f16x8 vn = *(const f16x8*)l2;
+    constexpr int N2 = HBO * FS, PD2 = 4;
+    f16x8 vq[PD2];
+#pragma unroll
+    for (int p = 0; p < PD2; ++p)
+      if (p < N2) vq[p] = *(const f16x8*)(l2 + p * 512);
 #pragma unroll
     for (int hb = 0; hb < HBO; ++hb) {
       f32x4 acc[NBLK];
@@ -193,8 +201,9 @@ struct MfmaFfn {
       for (int n = 0; n < NBLK; ++n) acc[n] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int s = 0; s < FS; ++s) {
-        const f16x8 w = vn;
-        if (hb * FS + s + 1 < HBO * FS) vn = *(const f16x8*)(l2 + (hb * FS + s + 1) * 512);
+        const int o = hb * FS + s;
+        const f16x8 w = vq[o % PD2];
+        if (o + PD2 < N2) vq[o % PD2] = *(const f16x8*)(l2 + (o + PD2) * 512);
 #pragma unroll
         for (int n = 0; n < NBLK; ++n)
           acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w, hid[n][s], acc[n], 0, 0, 0);
