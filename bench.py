@@ -165,6 +165,21 @@ def decode_stack(stk, steps, warmup):
 
     t_std = time_steps(one_std, 10, 2)
     t_lisa = time_steps(one_lisa, 10, 2)
+    # the same LiSA layer with the paper's own module: FFN over the concatenation, 2h -> 256 -> h, r = 20
+    pstk = stk.scaled(name=stk.name + "_paper_widths", r=20, F=256)
+    ply = synth.make_decode_layer(pstk, stk.n_std, device=dev, mix="concat", dim_major=True, Lmax=Lmax)
+    pd = lisa.make_desc(pstk.torch_dtype, pstk.B, pstk.H, pstk.Hkv, 1, Lk, pstk.d_k, pstk.r, pstk.F,
+                        mix=lisa.MIX_CONCAT, write_scores=1, kcache_dim_major=1, Lmax=Lmax, out_f32=1)
+    pws = torch.empty(max(lisa.workspace_bytes(pd, lisa.WS_DECODE), 256), dtype=torch.uint8, device=dev)
+
+    def one_concat():
+        lisa.lisa_attn_decode(ply["q_lr"], ply["k_lr_cache"], ply["v_cache"], Lk, rows[0], ply["w1"], ply["w2"],
+                              dim_major=True, mix=lisa.MIX_CONCAT, write_scores=True, out=out,
+                              score_row_out=rows[1], workspace=pws)
+
+    t_concat = time_steps(one_concat, 10, 2)
+    concat_path = lisa.last_path()
+    del ply, pws
     kv_std = 2 * stk.Hkv * stk.d_k * e                       # cache bytes per token and layer
     kv_lisa = stk.Hkv * (stk.r + stk.d_k) * e
     patterns = {}
@@ -187,6 +202,7 @@ def decode_stack(stk, steps, warmup):
         "tokens_per_s": stk.B / sec,
         "stage_ms_one_step": {k: round(v[1], 4) for k, v in stages.items()},
         "standard_layer_us": t_std * 1e6, "lisa_layer_us": t_lisa * 1e6,
+        "lisa_layer_concat_64_256_32_r20_us": t_concat * 1e6, "lisa_layer_concat_path": concat_path,
         "layer_patterns_attention_only": patterns,
     }
 
