@@ -16,7 +16,7 @@
 //      blocks of 16 positions, the 2H input "heads" fetched with transposing LDS reads;
 //   3. the results go to LDS as float32 [head][row][key] (over the input tile) and leave by
 //      heads in whole rows: 128 bytes of float32 and 64 bytes of half per row and tile.
-// Requires Lk % 8 == 0, r <= 32, 2H <= 64, F <= 256.
+// Requires Lk % 8 == 0, r <= 32, H <= 48, F <= 256.
 #pragma once
 #include "kernels_prefill.h"
 
@@ -35,6 +35,8 @@ struct ScoresMfmaArgs {
 };
 
 constexpr int SM_CHUNK = 16;      // key tiles per workgroup
+constexpr int SM_YS_ROW = PF_TK * 4;              // bytes per (head,row) of the output tile (float32, unpadded:
+constexpr int SM_YS_HEAD = PF_ROWS * SM_YS_ROW;   // with 40 heads the padded form would not fit the LDS)
 
 // HBI = ceil(2H / 16) input blocks, FS = ceil(F / 32), HBO = ceil(H / 16), ACT: 0 ReLU, 1 SiLU.
 // grid (ceil(max tiles / SM_CHUNK), ceil(Lq / 16), B), block 512.
@@ -42,11 +44,13 @@ template <int HBI, int FS, int HBO, int ACT = 0>
 __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
   typedef MfmaFfn<HBI, FS, HBO, ACT> Ffn;
   constexpr int KS = Ffn::KS, NW = 8, NBW = 4;
-  constexpr int NBLK = 2;                                   // blocks per FFN call (they share each weight read)
+  // blocks per FFN call (they share each weight read); one for the widest form, whose hidden
+  // units and operands of two blocks do not fit the register file
+  constexpr int NBLK = (HBI > 4 && FS > 4) ? 1 : 2;
   extern __shared__ __align__(16) unsigned char sm_lds[];
   const int H = a.H, Din = 2 * H, Lq = a.Lq, Lk = a.Lk;
   // the input tile (2H heads, half) and, later in the same tile, the output tile (H heads, float)
-  const int io_bytes = max(Din * PF_XS_HEAD, H * PF_YS_HEAD);
+  const int io_bytes = max(Din * PF_XS_HEAD, H * SM_YS_HEAD);
   unsigned char* xs = sm_lds;
   unsigned char* ys = sm_lds;
   unsigned short* w_s = (unsigned short*)(sm_lds + ((io_bytes + 15) & ~15));
@@ -175,7 +179,7 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           const int hl = 16 * hb + 4 * g + v;
-          if (hl < H) *(float*)(ys + hl * PF_YS_HEAD + i * PF_YS_ROW + (16 * kh + c) * 4) = y[qn][hb][v];
+          if (hl < H) *(float*)(ys + hl * SM_YS_HEAD + i * SM_YS_ROW + (16 * kh + c) * 4) = y[qn][hb][v];
         }
     }
     lds_barrier();   
@@ -184,8 +188,8 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
       const int gi = i0 + row, jc = j0 + 8 * ch;
       const int vis = gi < Lq ? (a.causal ? min(Lk, gi + 1 + shift) : Lk) : 0;
       for (int h = wv; h < H; h += NW) {
-        const float4 lo = *(const float4*)(ys + h * PF_YS_HEAD + row * PF_YS_ROW + 32 * ch);
-        const float4 hi = *(const float4*)(ys + h * PF_YS_HEAD + row * PF_YS_ROW + 32 * ch + 16);
+        const float4 lo = *(const float4*)(ys + h * SM_YS_HEAD + row * SM_YS_ROW + 32 * ch);
+        const float4 hi = *(const float4*)(ys + h * SM_YS_HEAD + row * SM_YS_ROW + 32 * ch + 16);
         const float vals[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
         if (jc >= vis) continue;
         const size_t at = (((size_t)b * H + h) * Lq + gi) * Lk + jc;
@@ -214,7 +218,7 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
 // LDS bytes of k_lisa_scores_mfma<HBI, FS, HBO> for H heads.
 template <int HBI, int FS, int HBO>
 constexpr int scores_mfma_lds(int H) {
-  const int io = 2 * H * PF_XS_HEAD > H * PF_YS_HEAD ? 2 * H * PF_XS_HEAD : H * PF_YS_HEAD;
+  const int io = 2 * H * PF_XS_HEAD > H * SM_YS_HEAD ? 2 * H * PF_XS_HEAD : H * SM_YS_HEAD;
   return ((io + 15) & ~15) + MfmaFfn<HBI, FS, HBO>::kStageBytes;
 }
 

@@ -158,7 +158,7 @@ bool scores_mfma_ok(const lisa_desc* d) {
   if (d->dtype != LISA_BF16 || d->mix != LISA_MIX_CONCAT) return false;
   if (d->act != LISA_ACT_RELU && d->act != LISA_ACT_SILU) return false;
   if (d->Lq == 1) return false;                            // decode rows: the generic kernel (strided caches)
-  if (d->H > 32 || d->F > 256 || d->r > 32 || d->Lk % 8 != 0) return false;
+  if (d->H > 48 || d->F > 256 || d->r > 32 || d->Lk % 8 != 0) return false;
   return (long long)d->Lq * d->Lk < (1LL << 31);
 }
 
@@ -231,7 +231,8 @@ int launch_scores_mfma(const lisa_desc* d, const void* q_lr, const void* k_lr, c
   a.dscale = pick_scale(d->delta_scale, d->r);
   const bool wide = d->F > 128;
   if (d->H <= 16) return wide ? launch_scores_mfma_t<2, 8, 1>(d, a, st) : launch_scores_mfma_t<2, 4, 1>(d, a, st);
-  return wide ? launch_scores_mfma_t<4, 8, 2>(d, a, st) : launch_scores_mfma_t<4, 4, 2>(d, a, st);
+  if (d->H <= 32) return wide ? launch_scores_mfma_t<4, 8, 2>(d, a, st) : launch_scores_mfma_t<4, 4, 2>(d, a, st);
+  return wide ? launch_scores_mfma_t<6, 8, 3>(d, a, st) : launch_scores_mfma_t<6, 4, 3>(d, a, st);
 }
 
 template <typename T, typename S>
@@ -323,7 +324,7 @@ bool decode_fast_ok(const lisa_desc* d, bool lisa_layer) {
   if (d->H > 64) return false;
   if (lisa_layer) {
     if (d->mix == LISA_MIX_CONCAT)                         // the instantiated CONCAT shapes
-      return (d->act == LISA_ACT_RELU || d->act == LISA_ACT_SILU) && d->H <= 32 && d->F <= 256 && d->r <= 64;
+      return (d->act == LISA_ACT_RELU || d->act == LISA_ACT_SILU) && d->H <= 48 && d->F <= 256 && d->r <= 64;
     if (d->mix != LISA_MIX_ADD || (d->act != LISA_ACT_RELU && d->act != LISA_ACT_SILU)) return false;
     if (d->F > 128 || d->r > 64) return false;
   }
@@ -393,11 +394,13 @@ int run_decode_fast(const lisa_desc* d, bool lisa_layer, DecodeArgs a, void* out
   size_t lds = (size_t)d->H * DEC_CK * sizeof(float);
   int rc;
   if (lisa_layer && d->mix == LISA_MIX_CONCAT) {
-    const int hbi = d->H <= 16 ? 2 : 4, fs = d->F <= 64 ? 2 : d->F <= 128 ? 4 : 8;
+    const int hbi = d->H <= 16 ? 2 : d->H <= 32 ? 4 : 6, fs = d->F <= 64 ? 2 : d->F <= 128 ? 4 : 8;
     const int ks1 = (hbi + 1) / 2, hbo = (hbi + 1) / 2;
     lds += (size_t)((d->H * d->r + 3) & ~3) * sizeof(float) + (size_t)(2 * fs * ks1 + hbo * fs) * 1024;
     a.scale = pick_scale(d->delta_scale, d->r);
-    rc = hbi == 2 ? launch_decode_concat_fs<2>(d, a, lds, st) : launch_decode_concat_fs<4>(d, a, lds, st);
+    rc = hbi == 2   ? launch_decode_concat_fs<2>(d, a, lds, st)
+         : hbi == 4 ? launch_decode_concat_fs<4>(d, a, lds, st)
+                    : launch_decode_concat_fs<6>(d, a, lds, st);
   } else if (lisa_layer) {
     // + q_lr [H][r] as float + the FFN weights in MFMA operand order (mfma_ffn.h: kStageBytes)
     const int hb = (d->H + 15) / 16, fs = (d->F + 31) / 32, ks1 = (hb + 1) / 2;

@@ -942,6 +942,7 @@ CONCAT_MFMA = [
     ("h16_gqa_l152", 1, 16, 4, 152, 64, 12, 64),
     ("h8_l264_f200", 1, 8, 8, 264, 128, 32, 200),
     ("h24_l136", 1, 24, 24, 136, 128, 20, 96),
+    ("llama13b_paper_dims_l136", 1, 40, 40, 136, 128, 20, 256),   # 80 -> 256 -> 40
 ]
 
 
