@@ -3,11 +3,12 @@
 // LiSA": the alignment FFN takes the concatenation, 2h -> F -> h; Sec. 6.1: 64 -> 256 -> 32),
 // with A_delta = Q_LR K_LR^T / sqrt(r) (Eq. 3).  The correction goes through the FFN here, so it
 // cannot be added per head after a position-wise stage as in the fused ADD kernel; this kernel
-// produces the score tensor (half, for the next layer) and its unrounded float32 copy, which the
-// softmax / P V kernel of the generic path then consumes.  49 kflop per position at the paper's
-// widths: bound by the matrix cores, not by the 8 + 2 bytes per head and position it moves.
+// produces the score tensor (half), which the next layer shares and which the softmax / P V
+// kernel that follows reads.  49 kflop per position at the paper's widths against 2 + 2 bytes per
+// head and position.
 //
-// One workgroup (8 waves) = 16 query rows x up to SM_CHUNK tiles of 32 keys.  Per tile:
+// One workgroup (8 waves) works on tiles of 16 query rows x 32 keys, a run of them (see the
+// kernel).  Per tile:
 //   1. the A_{n-1} tile of all heads goes to LDS ([head][row][key], half); wave w computes the
 //      A_delta tile of heads w, w + 8, ... with two 16x16x32 MFMAs each (A = K_LR rows, B = Q_LR
 //      rows, both read from copies zero-padded to 32 elements per row: k_prepare_prefill) and
@@ -15,7 +16,7 @@
 //   2. every wave runs the FFN (mfma_ffn.h, weights read from their LDS image) on 4 of the 32
 //      blocks of 16 positions, the 2H input "heads" fetched with transposing LDS reads;
 //   3. the results go to LDS as float32 [head][row][key] (over the input tile) and leave by
-//      heads in whole rows: 128 bytes of float32 and 64 bytes of half per row and tile.
+//      heads in whole rows, 64 bytes of half per row and tile.
 // Requires Lk % 8 == 0, r <= 32, H <= 48, F <= 256.
 #pragma once
 #include "kernels_prefill.h"
@@ -28,25 +29,33 @@ struct ScoresMfmaArgs {
   const half_t* prev;   // [B,H,Lq,Lk]
   const bf16_t* w1;     // [2H,F]
   const bf16_t* w2;     // [F,H]
-  half_t* scores;       // [B,H,Lq,Lk] or null
-  float* exact;         // [B,H,Lq,Lk]
-  int H, Hkv, Lq, Lk, Lqp, Lkp, F, causal;
+  half_t* scores;       // [B,H,Lq,Lk]: A_n, which the softmax kernel that follows reads as well
+  int B, H, Hkv, Lq, Lk, Lqp, Lkp, F, causal;
+  long long tiles_b;    // tiles of one batch element: sum over the row groups of scores_mfma_tiles()
   float dscale;
 };
 
-constexpr int SM_CHUNK = 16;      // key tiles per workgroup
 constexpr int SM_YS_ROW = PF_TK * 4;              // bytes per (head,row) of the output tile (float32, unpadded:
 constexpr int SM_YS_HEAD = PF_ROWS * SM_YS_ROW;   // with 40 heads the padded form would not fit the LDS)
 
+// Key tiles (PF_TK keys) that hold visible keys of row group rg (PF_ROWS query rows).
+__host__ __device__ inline int scores_mfma_tiles(int rg, int Lq, int Lk, int causal) {
+  const int i_last = min(rg * PF_ROWS + PF_ROWS - 1, Lq - 1);
+  const int n_keys = causal ? min(Lk, i_last + 1 + (Lk - Lq)) : Lk;
+  return (n_keys + PF_TK - 1) / PF_TK;
+}
+
 // HBI = ceil(2H / 16) input blocks, FS = ceil(F / 32), HBO = ceil(H / 16), ACT: 0 ReLU, 1 SiLU.
-// grid (ceil(max tiles / SM_CHUNK), ceil(Lq / 16), B), block 512.
+// grid (G), block 512, one workgroup per compute unit: the tiles of the causal triangle, in the
+// order (batch, row group, key tile), are cut into G equal runs, so that every workgroup has the
+// same number of tiles whatever the shape of the triangle (whole row groups or chunks of them
+// leave the last workgroups of a grid with up to twice the average), and stages the weights once.
 template <int HBI, int FS, int HBO, int ACT = 0>
 __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
   typedef MfmaFfn<HBI, FS, HBO, ACT> Ffn;
   constexpr int KS = Ffn::KS, NW = 8, NBW = 4;
-  // blocks per FFN call (they share each weight read); one for the widest form, whose hidden
-  // units and operands of two blocks do not fit the register file
-  constexpr int NBLK = (HBI > 4 && FS > 4) ? 1 : 2;
+  // hidden k-steps alive at a time in the FFN call (4 blocks x SC x 4 registers)
+  constexpr int SC = (HBI > 4 || FS % 2 != 0) ? 1 : 2;
   extern __shared__ __align__(16) unsigned char sm_lds[];
   const int H = a.H, Din = 2 * H, Lq = a.Lq, Lk = a.Lk;
   // the input tile (2H heads, half) and, later in the same tile, the output tile (H heads, float)
@@ -57,26 +66,20 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int c = lane & 15, g = lane >> 4;
-  const int b = blockIdx.z, i0 = blockIdx.y * PF_ROWS;
   const int shift = Lk - Lq;
-  const int i_last = min(i0 + PF_ROWS - 1, Lq - 1);
-  const int n_keys = a.causal ? min(Lk, i_last + 1 + shift) : Lk;
-  const int n_tiles = (n_keys + PF_TK - 1) / PF_TK;
-  const int t_first = blockIdx.x * SM_CHUNK;
-  if (t_first >= n_tiles) return;                           // beyond the diagonal (whole workgroup)
-  const int t_last = min(t_first + SM_CHUNK, n_tiles);
   const int group = H / a.Hkv;
+  const int n_rg = (Lq + PF_ROWS - 1) / PF_ROWS;
+  // this workgroup's run of tiles [pos, hi) and where it starts
+  const long long total = a.tiles_b * a.B;
+  long long pos = total * blockIdx.x / gridDim.x;
+  const long long hi = total * (blockIdx.x + 1) / gridDim.x;
+  if (pos >= hi) return;
+  int b = (int)(pos / a.tiles_b), rg = 0;
+  int tile0 = (int)(pos - b * a.tiles_b);
+  for (int nt; tile0 >= (nt = scores_mfma_tiles(rg, Lq, Lk, a.causal)); ++rg) tile0 -= nt;
 
   Ffn::stage(a.w1, a.w2, Din, a.F, w_s, tid, NW * 64, 0, H, H);
 
-  // A_delta: B operands (Q_LR rows of this wave's heads), resident
-  constexpr int HPW = (HBO * 16 + NW - 1) / NW;             // heads per wave (upper bound)
-  bf16x8 qop[HPW];
-#pragma unroll
-  for (int u = 0; u < HPW; ++u) {
-    const int h = min(wv + NW * u, H - 1);
-    qop[u] = *(const bf16x8*)(a.qp + (((size_t)b * H + h) * a.Lqp + min(i0 + c, Lq - 1)) * 32 + 8 * g);
-  }
   // transposing LDS reads of stage 2 (see the fused prefill kernel): lane 4 k' + q4 of a 16-lane
   // group passes the address of head k', keys 4 q4 .. 4 q4 + 3, and receives key c of heads k' = 0..3
   int xrd[KS][2];
@@ -84,6 +87,19 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
   for (int ks = 0; ks < KS; ++ks) {
     xrd[ks][0] = min(32 * ks + 8 * g + (c >> 2), Din - 1) * PF_XS_HEAD + 8 * (c & 3);
     xrd[ks][1] = min(32 * ks + 8 * g + 4 + (c >> 2), Din - 1) * PF_XS_HEAD + 8 * (c & 3);
+  }
+  while (pos < hi) {
+  // ---- one row group: tiles [t_first, t_last) of its key tiles -----------------------------------
+  const int i0 = rg * PF_ROWS;
+  const int t_first = tile0;
+  const int t_last = (int)min((long long)scores_mfma_tiles(rg, Lq, Lk, a.causal), tile0 + (hi - pos));
+  // A_delta: B operands (Q_LR rows of this wave's heads), resident
+  constexpr int HPW = (HBO * 16 + NW - 1) / NW;             // heads per wave (upper bound)
+  bf16x8 qop[HPW];
+#pragma unroll
+  for (int u = 0; u < HPW; ++u) {
+    const int h = min(wv + NW * u, H - 1);
+    qop[u] = *(const bf16x8*)(a.qp + (((size_t)b * H + h) * a.Lqp + min(i0 + c, Lq - 1)) * 32 + 8 * g);
   }
   const int x_row = min(i0 + (lane >> 2), Lq - 1), xq8 = 8 * (lane & 3);
 
@@ -138,14 +154,13 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
     }
     if (tile + 1 < t_last) prefetch(tile + 1);
     lds_barrier();   
-    // ---- 2. FFN over the wave's 4 blocks of 16 positions ---------------------------------------
+    // ---- 2. FFN over the wave's 4 blocks of 16 positions, all in one call ----------------------
     f32x4 y[NBW][HBO];
+    {
+      f16x8 x[NBW][KS];
 #pragma unroll
-    for (int q = 0; q < NBW; q += NBLK) {
-      f16x8 x[NBLK][KS];
-#pragma unroll
-      for (int n = 0; n < NBLK; ++n) {
-        const int nb = wv + (q + n) * NW;                   // block = (row nb / 2, key half nb % 2)
+      for (int n = 0; n < NBW; ++n) {
+        const int nb = wv + n * NW;                         // block = (row nb / 2, key half nb % 2)
         const int i = nb >> 1, kh = nb & 1;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
@@ -162,12 +177,7 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
           }
         }
       }
-      f32x4 yq[NBLK][HBO];
-      Ffn::template apply_lds_lean<NBLK>(w_s, x, yq);
-#pragma unroll
-      for (int n = 0; n < NBLK; ++n)
-#pragma unroll
-        for (int hb = 0; hb < HBO; ++hb) y[q + n][hb] = yq[n][hb];
+      Ffn::template apply_lds_chunked<NBW, SC>(w_s, x, y);
     }
     lds_barrier();                                           // every wave has read the input tile
     // ---- 3. output tile: float32 [head][row][key] over the input tile, then out by heads ---------
@@ -193,25 +203,22 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
         const float vals[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
         if (jc >= vis) continue;
         const size_t at = (((size_t)b * H + h) * Lq + gi) * Lk + jc;
-        if (jc + 8 <= vis) {
-          *(float4*)(a.exact + at) = lo;
-          *(float4*)(a.exact + at + 4) = hi;
-          if (a.scores) {
-            f16x8 hv;
+        f16x8 hv;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) hv[e] = f32_to_half_sat(vals[e]);
-            *(f16x8*)(a.scores + at) = hv;
-          }
+        for (int e = 0; e < 8; ++e) hv[e] = f32_to_half_sat(vals[e]);
+        if (jc + 8 <= vis) {
+          *(f16x8*)(a.scores + at) = hv;
         } else {
 #pragma unroll
           for (int e = 0; e < 8; ++e)
-            if (jc + e < vis) {
-              a.exact[at + e] = vals[e];
-              if (a.scores) a.scores[at + e] = f32_to_half_sat(vals[e]);
-            }
+            if (jc + e < vis) a.scores[at + e] = hv[e];
         }
       }
     }
+  }
+  pos += t_last - t_first;
+  tile0 = 0;
+  if (++rg == n_rg) rg = 0, ++b;
   }
 }
 

@@ -28,7 +28,8 @@ struct StdPrefillArgs {
   const bf16_t* k;        // [B,Hkv,Lk,128]
   const bf16_t* vt;       // [B,Hkv,Lkp/8,128,8] or null (scores only)
   half_t* scores;         // [B,H,Lq,Lk] or null
-  const float* given;     // GIVEN mode: float32 scores [B,H,Lq,Lk] to take instead of Q K^T (then q, k unused)
+  const void* given;      // GIVEN mode: scores [B,H,Lq,Lk] to take instead of Q K^T (then q, k unused):
+                          // float32 (GIVEN = 1) or IEEE half (GIVEN = 2)
   void* out;              // [B,Lq,H,128] or null
   int H, Hkv, Lq, Lk, Lkp, causal, out_f32;
   int pair;               // 1: a workgroup takes two row groups (grid.y = ceil(n_groups / 2)), 0: one
@@ -66,9 +67,9 @@ constexpr int std_prefill_head_lds(bool with_v) {
 // eighth head and its L2 fetches the K / V of those heads only (they are what every row group
 // of a head re-reads).
 // Requires d_k = 128, Lk % 8 == 0.
-// GIVEN: the scores are read from a.given (the unrounded A_n that a LiSA scores kernel left in the
-// workspace) instead of being computed; the rest (masking, online softmax, P V) is the same.
-template <bool WITH_V, bool GIVEN = false>
+// GIVEN: the scores are read from a.given (the A_n that a LiSA scores kernel left there) instead
+// of being computed; the rest (masking, online softmax, P V) is the same.
+template <bool WITH_V, int GIVEN = 0>
 __global__ __launch_bounds__(256, 2) void k_std_prefill(StdPrefillArgs a) {
   constexpr int DK = 128;
   __shared__ __align__(16) unsigned char lds[std_prefill_head_lds(WITH_V)];
@@ -117,7 +118,9 @@ __global__ __launch_bounds__(256, 2) void k_std_prefill(StdPrefillArgs a) {
 #pragma unroll
       for (int ks = 0; ks < DK / 16; ++ks) qop[ks] = *(const bf16x8*)(qp + 16 * ks);
     }
-    const float* grow = GIVEN ? a.given + (((size_t)b * H + h) * Lq + my_row) * Lk : nullptr;
+    const size_t grow_at = (((size_t)b * H + h) * Lq + my_row) * Lk;
+    const float* grow = GIVEN == 1 ? (const float*)a.given + grow_at : nullptr;
+    const half_t* grow_h = GIVEN == 2 ? (const half_t*)a.given + grow_at : nullptr;
     half_t* sbase = a.scores ? a.scores + ((size_t)b * H + h) * Lq * Lk : nullptr;
     unsigned char* stg = ss_ + wv * SP_STILE;
 
@@ -137,10 +140,22 @@ __global__ __launch_bounds__(256, 2) void k_std_prefill(StdPrefillArgs a) {
         if (WITH_V) *(pf_u32x4*)(vs_ + buf * SP_VTILE + (tid + 256 * u) * 16) = vreg[u];
       }
     };
+    // GIVEN = 2: the wave's scores of a tile are loaded two tiles ahead (nothing else hides the
+    // latency of these loads: there is no score product to wait behind)
+    f16x8 gq[2][2];
+    auto load_scores = [&](int tile, f16x8 (&dst)[2]) {
+#pragma unroll
+      for (int u = 0; u < 2; ++u)    // (keys beyond Lk: any in-bounds 8 scores will do, those positions are masked)
+        dst[u] = *(const f16x8*)(grow_h + min(tile * SP_TK + 16 * u + 8 * half, Lk - 8));
+    };
     if (rep) __syncthreads();                              // the first pass is done with both buffers
     load_tile(0);
     store_tile(0);
     load_tile(min(1, n_tiles - 1));
+    if (GIVEN == 2) {
+      load_scores(0, gq[0]);
+      load_scores(min(1, n_tiles - 1), gq[1]);
+    }
 
     f32x16 o[DK / 32];
 #pragma unroll
@@ -160,8 +175,15 @@ __global__ __launch_bounds__(256, 2) void k_std_prefill(StdPrefillArgs a) {
       const int j0 = tile * SP_TK;
       // an[8 u + e] = score of key j0 + 16 u + 8 half + e for row r
       float an[16];
-      if (GIVEN) {
-        // (keys beyond Lk: any in-bounds 8 floats will do, those positions are masked below)
+      if (GIVEN == 2) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) an[8 * u + e] = (float)gq[0][u][e];
+          gq[0][u] = gq[1][u];
+        }
+        load_scores(min(tile + 2, n_tiles - 1), gq[1]);
+      } else if (GIVEN == 1) {
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
           const float* gp = grow + min(j0 + 16 * u + 8 * half, Lk - 8);

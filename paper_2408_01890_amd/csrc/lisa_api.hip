@@ -154,6 +154,8 @@ int launch_std_scores(const lisa_desc* d, const void* q, const void* k, KeyStrid
 }
 
 // CONCAT with the two-layer ReLU FFN on the matrix cores (dense prefill tensors only).
+constexpr int kComputeUnits = 256;   // MI355X
+
 bool scores_mfma_ok(const lisa_desc* d) {
   if (d->dtype != LISA_BF16 || d->mix != LISA_MIX_CONCAT) return false;
   if (d->act != LISA_ACT_RELU && d->act != LISA_ACT_SILU) return false;
@@ -168,15 +170,16 @@ int launch_scores_mfma_t(const lisa_desc* d, const ScoresMfmaArgs& a, hipStream_
   auto kern = d->act == LISA_ACT_SILU ? k_lisa_scores_mfma<HBI, FS, HBO, 1> : k_lisa_scores_mfma<HBI, FS, HBO, 0>;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e != hipSuccess) return hip_fail(e);
-  const int tiles = (d->Lk + PF_TK - 1) / PF_TK;
-  dim3 grid((tiles + SM_CHUNK - 1) / SM_CHUNK, (d->Lq + PF_ROWS - 1) / PF_ROWS, d->B);
+  // one workgroup per compute unit, each with an equal run of the tiles
+  const long long total = a.tiles_b * a.B;
+  dim3 grid((unsigned)std::min<long long>(total, kComputeUnits));
   StageScope prof("k_lisa_scores_mfma", st);
   kern<<<grid, 512, lds, st>>>(a);
   return check_launch();
 }
 
-// Workspace of the CONCAT path behind the float32 scores: Q_LR / K_LR rows padded to 32 elements
-// and V by key chunks (k_prepare_prefill), the latter only where the MFMA softmax kernel runs.
+// Workspace of the CONCAT pipeline: A_n in the score type when the caller does not ask for it (the
+// softmax kernel reads it from there), the padded low-rank operands, V by key chunks.
 struct ConcatWs {
   size_t qp, kp, vt, total;
   int Lqp, Lkp;
@@ -186,7 +189,7 @@ ConcatWs concat_ws(const lisa_desc* d) {
   ConcatWs w;
   w.Lqp = (d->Lq + PF_ROWS - 1) / PF_ROWS * PF_ROWS;
   w.Lkp = (d->Lk + 63) / 64 * 64;
-  w.qp = exact_bytes(d);
+  w.qp = round_up((size_t)d->B * d->H * d->Lq * d->Lk * 2, 256);
   w.kp = w.qp + round_up((size_t)d->B * d->H * w.Lqp * 32 * 2, 256);
   w.vt = w.kp + round_up((size_t)d->B * d->Hkv * w.Lkp * 32 * 2, 256);
   w.total = w.vt + (std_prefill_fast_ok(d) ? round_up((size_t)d->B * d->Hkv * d->d_k * w.Lkp * 2, 256) : 0);
@@ -194,9 +197,9 @@ ConcatWs concat_ws(const lisa_desc* d) {
 }
 
 int launch_scores_mfma(const lisa_desc* d, const void* q_lr, const void* k_lr, const void* v, const void* prev,
-                       const void* w1, const void* w2, void* scores, float* exact, hipStream_t st) {
+                       const void* w1, const void* w2, void* scores, void* workspace, hipStream_t st) {
   const ConcatWs w = concat_ws(d);
-  char* ws = (char*)exact;
+  char* ws = (char*)workspace;
   {
     // V is regrouped in the same launch when the MFMA softmax kernel follows (d_k = 128)
     const bool with_v = std_prefill_fast_ok(d);
@@ -219,11 +222,14 @@ int launch_scores_mfma(const lisa_desc* d, const void* q_lr, const void* k_lr, c
   a.w1 = (const bf16_t*)w1;
   a.w2 = (const bf16_t*)w2;
   a.scores = (half_t*)scores;
-  a.exact = exact;
+  a.B = d->B;
   a.H = d->H;
   a.Hkv = d->Hkv;
   a.Lq = d->Lq;
   a.Lk = d->Lk;
+  a.tiles_b = 0;
+  for (int rg = 0; rg < (d->Lq + PF_ROWS - 1) / PF_ROWS; ++rg)
+    a.tiles_b += scores_mfma_tiles(rg, d->Lq, d->Lk, d->causal);
   a.Lqp = w.Lqp;
   a.Lkp = w.Lkp;
   a.F = d->F;
@@ -256,19 +262,18 @@ int launch_lisa_scores(const lisa_desc* d, const void* q_lr, const void* k_lr, K
   return check_launch();
 }
 
-template <typename T>
-int launch_softmax_v(const lisa_desc* d, const float* scores, const void* v, KeyStrides vs, void* out,
+template <typename T, typename S = float>
+int launch_softmax_v(const lisa_desc* d, const S* scores, const void* v, KeyStrides vs, void* out,
                      hipStream_t st) {
   dim3 grid((d->Lq + 7) / 8, d->H, d->B);
   const long long sh = d->d_k, si = (long long)d->H * d->d_k, sb = si * d->Lq;
   StageScope prof("k_softmax_v", st);
   if (d->out_f32)
-    k_softmax_v<T, float, float><<<grid, 256, 0, st>>>(scores, (const T*)v, vs, (float*)out, sb, si,
-                                                       sh, d->H, d->Hkv, d->Lq, d->Lk, d->d_k,
-                                                       d->causal);
+    k_softmax_v<T, S, float><<<grid, 256, 0, st>>>(scores, (const T*)v, vs, (float*)out, sb, si, sh, d->H,
+                                                   d->Hkv, d->Lq, d->Lk, d->d_k, d->causal);
   else
-    k_softmax_v<T, float, T><<<grid, 256, 0, st>>>(scores, (const T*)v, vs, (T*)out, sb, si, sh,
-                                                   d->H, d->Hkv, d->Lq, d->Lk, d->d_k, d->causal);
+    k_softmax_v<T, S, T><<<grid, 256, 0, st>>>(scores, (const T*)v, vs, (T*)out, sb, si, sh, d->H, d->Hkv,
+                                               d->Lq, d->Lk, d->d_k, d->causal);
   return check_launch();
 }
 
@@ -292,27 +297,39 @@ KeyStrides dim_major_keys(const lisa_desc* d, int len, int width) {
 
 bool std_prefill_fast_ok(const lisa_desc* d);
 size_t std_prefill_ws(const lisa_desc* d);
-int run_softmax_given_fast(const lisa_desc* d, const float* given, const void* v, void* out, void* vt_ws,
-                           hipStream_t st);
+int run_softmax_given_fast(const lisa_desc* d, const void* given, bool given_half, const void* v, void* out,
+                           void* vt_ws, hipStream_t st);
 
 template <typename T, typename S>
 int run_lisa(const lisa_desc* d, const void* q_lr, const void* k_lr, KeyStrides ks, const void* v,
              KeyStrides vs, const void* prev, const void* w1, const void* w2, void* out,
              void* scores, float* exact, hipStream_t st) {
-  // The softmax reads the unrounded float32 A_n from the workspace: rounding A_n to the
-  // 2-byte score type first would move each probability by up to |A_n| 2^-11.
   const bool mfma = scores_mfma_ok(d);
-  int rc = mfma ? launch_scores_mfma(d, q_lr, k_lr, v, prev, w1, w2, scores, exact, st)
-                : launch_lisa_scores<T, S>(d, q_lr, k_lr, ks, prev, w1, w2, scores, exact, st);
+  if (mfma) {
+    // A_n exists as the IEEE-half tensor that the next layer shares, and the softmax reads that
+    // tensor: a float32 copy would triple the bytes this pipeline writes.  The rounding, |A_n| 2^-11,
+    // is the size of what the module's inputs already carry (A_{n-1} is stored as half, and A_delta
+    // enters the FFN as a half MFMA operand).
+    void* an = scores ? scores : (void*)exact;
+    int rc = launch_scores_mfma(d, q_lr, k_lr, v, prev, w1, w2, an, exact, st);
+    if (rc) return rc;
+    if (std_prefill_fast_ok(d))
+      rc = run_softmax_given_fast(d, an, true, nullptr, out, (char*)exact + concat_ws(d).vt, st);
+    else
+      rc = launch_softmax_v<T, half_t>(d, (const half_t*)an, v, vs, out, st);
+    if (rc == LISA_OK) g_path = "mfma_scores";
+    return rc;
+  }
+  // Generic kernels: the softmax reads the unrounded float32 A_n from the workspace.
+  int rc = launch_lisa_scores<T, S>(d, q_lr, k_lr, ks, prev, w1, w2, scores, exact, st);
   if (rc) return rc;
   // softmax and P V from the float32 scores: on the matrix cores where the standard layer's kernel
   // fits (it then reads the scores instead of computing Q K^T), else the generic kernel
   if (std_prefill_fast_ok(d))
-    rc = run_softmax_given_fast(d, exact, mfma ? nullptr : v, out,
-                                (char*)exact + (mfma ? concat_ws(d).vt : exact_bytes(d)), st);
+    rc = run_softmax_given_fast(d, exact, false, v, out, (char*)exact + exact_bytes(d), st);
   else
     rc = launch_softmax_v<T>(d, exact, v, vs, out, st);
-  if (rc == LISA_OK) g_path = mfma ? "mfma_scores" : "generic";
+  if (rc == LISA_OK) g_path = "generic";
   return rc;
 }
 
@@ -447,7 +464,6 @@ bool prefill_fused_ok(const lisa_desc* d) {
   return d->H == 8 || d->H == 16 || d->H == 24 || d->H == 32 || d->H == 40;
 }
 
-constexpr int kComputeUnits = 256;   // MI355X
 
 // Head groups (grid.z) of the instantiation that run_prefill_fused picks.  H = 32 (16) runs as
 // two (one) groups of 16 heads, two heads per wave, when that alone gives two units of work per
@@ -608,9 +624,10 @@ size_t std_prefill_ws(const lisa_desc* d) {   // V by key chunks
   return round_up((size_t)d->B * d->Hkv * d->d_k * Lkp * 2, 256);
 }
 
-// softmax(A) V for float32 scores A that are already in memory (k_std_prefill in GIVEN mode).
-int run_softmax_given_fast(const lisa_desc* d, const float* given, const void* v, void* out, void* vt_ws,
-                           hipStream_t st) {
+// softmax(A) V for scores A that are already in memory, float32 or IEEE half (k_std_prefill in
+// GIVEN mode).
+int run_softmax_given_fast(const lisa_desc* d, const void* given, bool given_half, const void* v, void* out,
+                           void* vt_ws, hipStream_t st) {
   StdPrefillArgs a{};
   a.vt = (const bf16_t*)vt_ws;
   a.given = given;
@@ -637,7 +654,10 @@ int run_softmax_given_fast(const lisa_desc* d, const float* given, const void* v
   a.pair = (long long)d->H * ((n_groups + 1) / 2) * d->B >= 2 * kComputeUnits;
   dim3 grid(d->H, a.pair ? (n_groups + 1) / 2 : n_groups, d->B);
   StageScope prof("k_softmax_v_mfma", st);
-  k_std_prefill<true, true><<<grid, 256, 0, st>>>(a);
+  if (given_half)
+    k_std_prefill<true, 2><<<grid, 256, 0, st>>>(a);
+  else
+    k_std_prefill<true, 1><<<grid, 256, 0, st>>>(a);
   return check_launch();
 }
 

@@ -214,6 +214,71 @@ struct MfmaFfn {
     }
   }
 
+  // The same network with the hidden units taken SC k-steps (32 SC units) at a time: the second
+  // product is linear in the hidden units, so their chunks are folded into its accumulators one
+  // after the other and only one chunk is alive.  That leaves registers for more blocks per call,
+  // and every weight operand is read from LDS once per call: with all blocks of a wave in one
+  // call the weight traffic, which is what a wide FFN costs, is the least possible.
+  template <int NBLK, int SC>
+  __device__ __forceinline__ static void apply_lds_chunked(const unsigned short* lds,
+                                                           const f16x8 (&x)[NBLK][KS], f32x4 (&y)[NBLK][HBO]) {
+    static_assert(FS % SC == 0, "chunk size");
+    const int lane = threadIdx.x & 63;
+    const unsigned short* l1 = lds + lane * 8;
+    const unsigned short* l2 = l1 + FB * KS * 512;
+#pragma unroll
+    for (int n = 0; n < NBLK; ++n)
+#pragma unroll
+      for (int hb = 0; hb < HBO; ++hb) y[n][hb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // the operands of a group of MFMAs are read while the group before it runs
+    f16x8 wa[2][KS], wb[2][SC];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) wa[0][ks] = *(const f16x8*)(l1 + ks * 512);
+#pragma unroll
+    for (int s0 = 0; s0 < FS; s0 += SC) {
+      f16x8 hid[NBLK][SC];
+#pragma unroll
+      for (int fb = 2 * s0; fb < 2 * (s0 + SC); ++fb) {     // hidden block fb = 2 s + half
+        if (fb + 1 < 2 * (s0 + SC)) {
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) wa[(fb + 1) & 1][ks] = *(const f16x8*)(l1 + ((fb + 1) * KS + ks) * 512);
+        } else {
+#pragma unroll
+          for (int s = 0; s < SC; ++s) wb[0][s] = *(const f16x8*)(l2 + (s0 + s) * 512);
+        }
+        f32x4 acc[NBLK];
+#pragma unroll
+        for (int n = 0; n < NBLK; ++n) acc[n] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+          for (int n = 0; n < NBLK; ++n)
+            acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wa[fb & 1][ks], x[n][ks], acc[n], 0, 0, 0);
+#pragma unroll
+        for (int n = 0; n < NBLK; ++n)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) hid[n][(fb >> 1) - s0][4 * (fb & 1) + v] = activate(acc[n][v]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int hb = 0; hb < HBO; ++hb) {
+        if (hb + 1 < HBO) {
+#pragma unroll
+          for (int s = 0; s < SC; ++s) wb[(hb + 1) & 1][s] = *(const f16x8*)(l2 + ((hb + 1) * FS + s0 + s) * 512);
+        } else if (s0 + SC < FS) {
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) wa[0][ks] = *(const f16x8*)(l1 + (2 * (s0 + SC) * KS + ks) * 512);
+        }
+#pragma unroll
+        for (int s = 0; s < SC; ++s)
+#pragma unroll
+          for (int n = 0; n < NBLK; ++n)
+            y[n][hb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wb[hb & 1][s], hid[n][s], y[n][hb], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  }
+
   // NBLK independent blocks of 16 positions at once: the MFMAs of the blocks are interleaved so
   // that none has to wait for the result of the one issued just before it.
   // x[n][ks]: B operand of the first product of block n: lane (c, g) holds x[head 32 ks + 8 g + e]

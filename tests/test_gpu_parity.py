@@ -980,6 +980,11 @@ def test_lisa_prefill_concat_on_mfma_scores_kernel(case, causal, ffn):
     if causal:
         above = torch.ones(L, L, dtype=torch.bool, device=DEV).triu(1)
         assert torch.all(scores[..., above] == SENTINEL)      # nothing written above the diagonal
+    # without the score output A_n stays in the workspace: same kernels, same bits
+    out2, none = lisa.lisa_attn_prefill(inp["q_lr"], inp["k_lr"], inp["v"], prev, inp["w1"], inp["w2"],
+                                        mix=lisa.MIX_CONCAT, causal=causal, write_scores=False)
+    torch.cuda.synchronize()
+    assert none is None and torch.equal(out2, out)
     if not causal:
         return
     # the decode step of the same layer (split-context kernel in CONCAT form) = the last prefill row
