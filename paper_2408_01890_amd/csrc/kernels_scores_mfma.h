@@ -35,8 +35,13 @@ struct ScoresMfmaArgs {
   float dscale;
 };
 
-constexpr int SM_YS_ROW = PF_TK * 4;              // bytes per (head,row) of the output tile (float32, unpadded:
-constexpr int SM_YS_HEAD = PF_ROWS * SM_YS_ROW;   // with 40 heads the padded form would not fit the LDS)
+constexpr int SM_YS_ROW = PF_TK * 4;                    // bytes per (head,row) of the output tile (float32)
+// bytes per head: 16 more than its rows, so that the four heads 4 apart that the lane groups of a
+// wave write at once fall into different banks (the tile still fits under the input tile, 2 x 1056
+// bytes per head)
+constexpr int SM_YS_HEAD = PF_ROWS * SM_YS_ROW + 16;
+// the output tile as half in an array of its own (up to 32 heads, see the kernel), padded likewise
+constexpr int SM_YH_HEAD = PF_ROWS * PF_TK * 2 + 16;
 
 // Key tiles (PF_TK keys) that hold visible keys of row group rg (PF_ROWS query rows).
 __host__ __device__ inline int scores_mfma_tiles(int rg, int Lq, int Lk, int causal) {
@@ -54,14 +59,19 @@ template <int HBI, int FS, int HBO, int ACT = 0>
 __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
   typedef MfmaFfn<HBI, FS, HBO, ACT> Ffn;
   constexpr int KS = Ffn::KS, NW = 8, NBW = 4;
-  // hidden k-steps alive at a time in the FFN call (4 blocks x SC x 4 registers)
-  constexpr int SC = (HBI > 4 || FS % 2 != 0) ? 1 : 2;
+  // hidden k-steps alive at a time in the FFN call (4 blocks x SC x 4 registers; two only where
+  // the register file has room)
+  constexpr int SC = (HBI >= 4 || FS % 2 != 0) ? 1 : 2;
   extern __shared__ __align__(16) unsigned char sm_lds[];
   const int H = a.H, Din = 2 * H, Lq = a.Lq, Lk = a.Lk;
-  // the input tile (2H heads, half) and, later in the same tile, the output tile (H heads, float)
-  const int io_bytes = max(Din * PF_XS_HEAD, H * SM_YS_HEAD);
+  // PIPE (up to 32 heads, where the LDS has room): the output tile (H heads, half) has an array of
+  // its own and leaves during the FFN of the next tile.  Otherwise it takes the place of the input
+  // tile (2H heads, half) as float32 and leaves before the next tile is staged.
+  constexpr bool PIPE = HBI <= 4;
+  const int io_bytes = PIPE ? Din * PF_XS_HEAD + H * SM_YH_HEAD : max(Din * PF_XS_HEAD, H * SM_YS_HEAD);
   unsigned char* xs = sm_lds;
   unsigned char* ys = sm_lds;
+  unsigned char* yh = sm_lds + Din * PF_XS_HEAD;
   unsigned short* w_s = (unsigned short*)(sm_lds + ((io_bytes + 15) & ~15));
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -128,6 +138,147 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
   // (the barriers of the tile loop order LDS traffic only: __syncthreads() would also wait for the
   // global stores of the previous tile and for the prefetch)
 
+  auto stage_tile = [&]() {
+#pragma unroll
+    for (int u = 0; u < XCH; ++u) {
+      const int h = wv + NW * u;
+      if (h < H) *(pf_u32x4*)(xs + h * PF_XS_HEAD + lane * 16) = xr[u];
+    }
+#pragma unroll
+    for (int u = 0; u < HPW; ++u) {
+      const int h = wv + NW * u;
+      if (h >= H) break;
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        f32x4 d = {0.f, 0.f, 0.f, 0.f};
+        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[u][half], qop[u], d, 0, 0, 0);
+        // d[v] = A_delta(row c, key 16 half + 4 g + v) / scale
+        f16x4 hv;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) hv[v] = f32_to_half_sat(d[v] * a.dscale);
+        *(f16x4*)(xs + (H + h) * PF_XS_HEAD + c * 64 + (16 * half + 4 * g) * 2) = hv;
+      }
+    }
+  };
+  auto read_x = [&](f16x8 (&x)[NBW][KS]) {
+#pragma unroll
+    for (int n = 0; n < NBW; ++n) {
+      const int nb = wv + n * NW;                           // block = (row nb / 2, key half nb % 2)
+      const int i = nb >> 1, kh = nb & 1;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const f16x4 lo = __builtin_bit_cast(
+            f16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                       (s16x4 __attribute__((address_space(3)))*)(xs + xrd[ks][0] + i * 64 + 32 * kh)));
+        const f16x4 hi = __builtin_bit_cast(
+            f16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                       (s16x4 __attribute__((address_space(3)))*)(xs + xrd[ks][1] + i * 64 + 32 * kh)));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          x[n][ks][e] = 32 * ks + 8 * g + e < Din ? lo[e] : (_Float16)0.f;
+          x[n][ks][4 + e] = 32 * ks + 8 * g + 4 + e < Din ? hi[e] : (_Float16)0.f;
+        }
+      }
+    }
+  };
+
+  if constexpr (PIPE) {
+    // Two barriers per tile.  Between A and B: the FFN of tile t, and in the shadow of its MFMA
+    // groups the loads of tile t + 1 and the stores of A_n of tile t - 1 (from yh).  Between B and
+    // A: tile t + 1 goes into xs and the result of tile t into yh.
+    const int orow = lane >> 2, och = lane & 3;             // output: 8 keys of a row per lane
+    const int gi = i0 + orow;
+    const int vis = gi < Lq ? (a.causal ? min(Lk, gi + 1 + shift) : Lk) : 0;
+    half_t* const obase = a.scores + (((size_t)b * H + wv) * Lq + min(gi, Lq - 1)) * Lk + 8 * och;
+    const size_t ohead = (size_t)NW * Lq * Lk;              // from a head of this wave to its next
+    const unsigned char* const yrd = yh + wv * SM_YH_HEAD + orow * (PF_TK * 2) + 16 * och;
+    const half_t* const pbase = a.prev + ((size_t)b * H * Lq + x_row) * Lk;
+    const size_t phead = (size_t)Lq * Lk;
+    f32x4 y[NBW][HBO];
+    f16x8 held;
+    auto out_read = [&](int u) {
+      if (wv + NW * u < H) held = *(const f16x8*)(yrd + u * NW * SM_YH_HEAD);
+    };
+    auto out_store = [&](int u, int jc) {                   // jc: first of the lane's 8 keys
+      if (wv + NW * u >= H || jc >= vis) return;
+      half_t* sp = obase + u * ohead + jc - 8 * och;
+      if (jc + 8 <= vis) {
+        *(f16x8*)sp = held;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (jc + e < vis) sp[e] = held[e];
+      }
+    };
+    // The result leaves the registers as dwords of two keys: a lane holds one key of the four heads
+    // 4 g + v; the lanes of a pair (keys c, c ^ 1) swap halves, after which the even lane has both
+    // keys of heads v = 0, 1 and the odd lane those of v = 2, 3 (2-byte LDS writes cost about three
+    // times as much).
+    const bool odd = c & 1;
+    auto write_y = [&]() {
+#pragma unroll
+      for (int qn = 0; qn < NBW; ++qn) {
+        const int nb = wv + qn * NW, i = nb >> 1, kh = nb & 1;
+#pragma unroll
+        for (int hb = 0; hb < HBO; ++hb) {
+          f16x4 hv;
+#pragma unroll
+          for (int v = 0; v < 4; ++v) hv[v] = f32_to_half_sat(y[qn][hb][v]);
+          const uint2 pq = __builtin_bit_cast(uint2, hv);   // (heads v = 0, 1), (heads v = 2, 3) of key c
+          const unsigned keep = odd ? pq.y : pq.x;
+          const unsigned got = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(odd ? pq.x : pq.y), 0xB1, 0xF, 0xF, true);
+          const unsigned first = odd ? got : keep, second = odd ? keep : got;   // keys c & ~1, c | 1
+          const int hl = 16 * hb + 4 * g + 2 * (c & 1);
+          unsigned char* yp = yh + hl * SM_YH_HEAD + i * (PF_TK * 2) + (16 * kh + (c & ~1)) * 2;
+          if (hl < H) *(unsigned*)yp = (first & 0xffffu) | (second << 16);
+          if (hl + 1 < H) *(unsigned*)(yp + SM_YH_HEAD) = (first >> 16) | (second & 0xffff0000u);
+        }
+      }
+    };
+    constexpr int N_OPS = XCH + 2 * HPW + XCH + 1;          // loads of a tile, then read / store pairs
+    constexpr int N_GROUPS = (FS / SC) * (2 * SC + HBO);
+    constexpr int OPG = (N_OPS + N_GROUPS - 1) / N_GROUPS;
+    for (int tile = t_first; tile < t_last; ++tile) {
+      const bool pending = tile > t_first;
+      stage_tile();
+      if (pending) write_y();
+      lds_barrier();                                         // A: xs and yh are complete
+      f16x8 x[NBW][KS];
+      read_x(x);
+      const int jn = (tile + 1) * PF_TK, jo = (tile - 1) * PF_TK + 8 * och;
+      const int xoff = min(jn + xq8, Lk - 8);
+      int koff[2];
+#pragma unroll
+      for (int half = 0; half < 2; ++half) koff[half] = min(jn + 16 * half + c, Lk - 1) * 32 + 8 * g;
+      // (the loads are not conditional on a next tile: its clamped addresses are in bounds, and a
+      // branch around a load makes the compiler wait for every earlier one)
+      Ffn::template apply_lds_chunked<NBW, SC>(w_s, x, y, [&](int gidx) {
+#pragma unroll
+        for (int k = gidx * OPG; k < (gidx + 1) * OPG && k < N_OPS; ++k) {
+          if (k < XCH) {
+            xr[k] = *(const pf_u32x4*)(pbase + min(wv + NW * k, H - 1) * phead + xoff);
+          } else if (k < XCH + 2 * HPW) {
+            const int u = (k - XCH) >> 1, half = (k - XCH) & 1;
+            const int h = min(wv + NW * u, H - 1);
+            kop[u][half] = *(const bf16x8*)(a.kp + ((size_t)b * a.Hkv + h / group) * a.Lkp * 32 + koff[half]);
+          } else if (pending) {
+            const int sidx = k - XCH - 2 * HPW;
+            if (sidx > 0) out_store(sidx - 1, jo);
+            if (sidx < XCH) out_read(sidx);
+          }
+        }
+      });
+      lds_barrier();                                         // B: xs and yh have been read
+    }
+    // the result of the last tile of the run
+    write_y();
+    lds_barrier();
+#pragma unroll
+    for (int u = 0; u < XCH; ++u) {
+      out_read(u);
+      out_store(u, (t_last - 1) * PF_TK + 8 * och);
+    }
+  } else
   for (int tile = t_first; tile < t_last; ++tile) {
     const int j0 = tile * PF_TK;
     lds_barrier();                                           // the stores of the previous tile have read ys
@@ -177,7 +328,7 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
           }
         }
       }
-      Ffn::template apply_lds_chunked<NBW, SC>(w_s, x, y);
+      Ffn::template apply_lds_chunked<NBW, SC>(w_s, x, y, [](int) {});
     }
     lds_barrier();                                           // every wave has read the input tile
     // ---- 3. output tile: float32 [head][row][key] over the input tile, then out by heads ---------
@@ -225,7 +376,8 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
 // LDS bytes of k_lisa_scores_mfma<HBI, FS, HBO> for H heads.
 template <int HBI, int FS, int HBO>
 constexpr int scores_mfma_lds(int H) {
-  const int io = 2 * H * PF_XS_HEAD > H * SM_YS_HEAD ? 2 * H * PF_XS_HEAD : H * SM_YS_HEAD;
+  const int io = HBI <= 4 ? 2 * H * PF_XS_HEAD + H * SM_YH_HEAD
+                          : (2 * H * PF_XS_HEAD > H * SM_YS_HEAD ? 2 * H * PF_XS_HEAD : H * SM_YS_HEAD);
   return ((io + 15) & ~15) + MfmaFfn<HBI, FS, HBO>::kStageBytes;
 }
 

@@ -219,10 +219,15 @@ struct MfmaFfn {
   // after the other and only one chunk is alive.  That leaves registers for more blocks per call,
   // and every weight operand is read from LDS once per call: with all blocks of a wave in one
   // call the weight traffic, which is what a wide FFN costs, is the least possible.
-  template <int NBLK, int SC>
+  // `between(gi)` is called at the head of MFMA group gi = 0 .. (FS / SC) (2 SC + HBO) - 1 (a group =
+  // the MFMAs of one hidden block, or of one output block and chunk): the caller's memory operations
+  // placed there run in the shadow of the matrix cores.
+  template <int NBLK, int SC, class Between>
   __device__ __forceinline__ static void apply_lds_chunked(const unsigned short* lds,
-                                                           const f16x8 (&x)[NBLK][KS], f32x4 (&y)[NBLK][HBO]) {
+                                                           const f16x8 (&x)[NBLK][KS], f32x4 (&y)[NBLK][HBO],
+                                                           Between&& between) {
     static_assert(FS % SC == 0, "chunk size");
+    constexpr int GPC = 2 * SC + HBO;                       // groups per chunk
     const int lane = threadIdx.x & 63;
     const unsigned short* l1 = lds + lane * 8;
     const unsigned short* l2 = l1 + FB * KS * 512;
@@ -239,6 +244,7 @@ struct MfmaFfn {
       f16x8 hid[NBLK][SC];
 #pragma unroll
       for (int fb = 2 * s0; fb < 2 * (s0 + SC); ++fb) {     // hidden block fb = 2 s + half
+        between((s0 / SC) * GPC + fb - 2 * s0);
         if (fb + 1 < 2 * (s0 + SC)) {
 #pragma unroll
           for (int ks = 0; ks < KS; ++ks) wa[(fb + 1) & 1][ks] = *(const f16x8*)(l1 + ((fb + 1) * KS + ks) * 512);
@@ -262,6 +268,7 @@ struct MfmaFfn {
       }
 #pragma unroll
       for (int hb = 0; hb < HBO; ++hb) {
+        between((s0 / SC) * GPC + 2 * SC + hb);
         if (hb + 1 < HBO) {
 #pragma unroll
           for (int s = 0; s < SC; ++s) wb[(hb + 1) & 1][s] = *(const f16x8*)(l2 + ((hb + 1) * FS + s0 + s) * 512);
