@@ -1008,6 +1008,21 @@ def test_lisa_prefill_concat_on_mfma_scores_kernel(case, causal, ffn):
     assert worst_o <= tol and worst_a <= tol
 
 
+@pytest.mark.parametrize("ffn", ["paper", "identity_noise", "fan_in"])
+def test_lisa_prefill_concat_full_size_sampled_rows(ffn):
+    # the benchmark shape with the paper's module (Sec. 6.1: 64 -> 256 -> 32, r = 20), as bench.py times it
+    cfg = synth.LayerShape("c2_concat_64_256_32_r20", "bf16", 1, 32, 32, 2048, 4096, 128, 20, 256)
+    log(f"[case] prefill {cfg.name} ffn={ffn} sampled")
+    inp = synth.make_prefill_inputs(cfg, synth.BASE_SEED + 21, DEV, mix="concat", ffn=ffn)
+    prev = std_prev(inp)
+    out, scores = lisa.lisa_attn_prefill(inp["q_lr"], inp["k_lr"], inp["v"], prev, inp["w1"], inp["w2"],
+                                         mix=lisa.MIX_CONCAT)
+    torch.cuda.synchronize()
+    assert lisa.last_path() == "mfma_scores"
+    rows = synth.sample_rows(cfg.L, 280, 121)
+    check_prefill(cfg, inp, prev, out, scores, {0: rows}, mix=1, tag=f"/{ffn}")
+
+
 def test_lisa_prefill_concat_mfma_chunked_rows():
     """Lq < Lk (a chunk of query rows against a longer key range): the diagonal is shifted."""
     cfg = synth.LayerShape("concat_chunk", "bf16", 1, 32, 8, 200, 256, 128, 20, 256)
