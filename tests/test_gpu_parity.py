@@ -943,6 +943,8 @@ CONCAT_MFMA = [
     ("h8_l264_f200", 1, 8, 8, 264, 128, 32, 200),
     ("h24_l136", 1, 24, 24, 136, 128, 20, 96),
     ("llama13b_paper_dims_l136", 1, 40, 40, 136, 128, 20, 256),   # 80 -> 256 -> 40
+    ("one_tile_l8", 1, 8, 8, 8, 128, 20, 64),                     # a grid of one workgroup, one tile
+    ("b3_h8_l520", 3, 8, 4, 520, 128, 24, 96),                    # runs of 3-4 tiles that cross row groups and batch elements
 ]
 
 
