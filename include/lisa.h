@@ -116,8 +116,10 @@ typedef struct lisa_desc {
  *                                   alias scores_prev
  *   workspace                  scratch of at least lisa_workspace_bytes(desc, LISA_WS_PREFILL)
  *                              bytes (may be NULL when that is 0); contents undefined after.
- *                              The softmax never reads the rounded 2-byte A_n: kernels that
- *                              cannot keep A_n in registers stage it here as float32.
+ *                              The fused kernels keep A_n in float32 registers up to the
+ *                              softmax and the generic kernels stage it here as float32; the
+ *                              matrix-core kernels of the CONCAT form pass it between their two
+ *                              launches in the score type (the rounding its inputs carry).
  */
 int lisa_attn_prefill(const lisa_desc* desc, const void* q_lr, const void* k_lr, const void* v,
                       const void* scores_prev, const void* w1, const void* w2, void* out,
