@@ -305,13 +305,15 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
     }
     if (tile + 1 < t_last) prefetch(tile + 1);
     lds_barrier();   
-    // ---- 2. FFN over the wave's 4 blocks of 16 positions, all in one call ----------------------
+    // ---- 2. FFN over the wave's 4 blocks of 16 positions, two at a time (the operands of four do
+    //         not fit the register file next to those of 40 - 48 heads) ---------------------------
     f32x4 y[NBW][HBO];
-    {
-      f16x8 x[NBW][KS];
 #pragma unroll
-      for (int n = 0; n < NBW; ++n) {
-        const int nb = wv + n * NW;                         // block = (row nb / 2, key half nb % 2)
+    for (int q = 0; q < NBW; q += 2) {
+      f16x8 x[2][KS];
+#pragma unroll
+      for (int n = 0; n < 2; ++n) {
+        const int nb = wv + (q + n) * NW;                   // block = (row nb / 2, key half nb % 2)
         const int i = nb >> 1, kh = nb & 1;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
@@ -328,7 +330,12 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
           }
         }
       }
-      Ffn::template apply_lds_chunked<NBW, SC>(w_s, x, y, [](int) {});
+      f32x4 yq[2][HBO];
+      Ffn::template apply_lds_chunked<2, SC>(w_s, x, yq, [](int) {});
+#pragma unroll
+      for (int n = 0; n < 2; ++n)
+#pragma unroll
+        for (int hb = 0; hb < HBO; ++hb) y[q + n][hb] = yq[n][hb];
     }
     lds_barrier();                                           // every wave has read the input tile
     // ---- 3. output tile: float32 [head][row][key] over the input tile, then out by heads ---------
