@@ -191,8 +191,40 @@ def decode_stack(stk, steps, warmup):
             "kv_cache_bytes_per_token": n_s * kv_std + n_lisa * kv_lisa,
             "kv_cache_vs_all_standard": (n_s * kv_std + n_lisa * kv_lisa) / (stk.n_layers * kv_std),
         }
-    del layers
+    del layers, rows, out, ws
     torch.cuda.empty_cache()
+    # The paper's throughput table (Sec. 5.4) is taken at the largest batch that fits the memory:
+    # a LiSA layer caches r + d_k instead of 2 d_k values per key and head, so the same cache
+    # memory holds a larger batch.  Attention layers only (no projections, no MLP): the batch of
+    # the all-standard model is this stack's, the LiSA patterns get the batch that fills the same
+    # cache bytes, and one layer of each kind is timed at that batch.
+    for n_lisa in (17, 21, 27):
+        pat = patterns[f"lisa_{n_lisa}_of_{stk.n_layers}"]
+        b_eq = int(stk.B / pat["kv_cache_vs_all_standard"])
+        bstk = stk.scaled(B=b_eq)
+        brows = [torch.empty((b_eq, stk.H, Lk), dtype=sdt, device=dev) for _ in range(2)]
+        bout = torch.empty((b_eq, stk.H, stk.d_k), dtype=torch.float32, device=dev)
+        bd = lisa.make_desc(stk.torch_dtype, b_eq, stk.H, stk.Hkv, 1, Lk, stk.d_k, stk.r, stk.F,
+                            write_scores=1, kcache_dim_major=1, Lmax=Lmax, out_f32=1)
+        bws = torch.empty(max(lisa.workspace_bytes(bd, lisa.WS_DECODE), lisa.workspace_bytes(bd, lisa.WS_STD), 256),
+                          dtype=torch.uint8, device=dev)
+        ly = synth.make_decode_layer(bstk, 0, device=dev, dim_major=True, Lmax=Lmax)
+        tb_std = time_steps(lambda: lisa.std_attn_decode(ly["q"], ly["k_cache"], ly["v_cache"], Lk, want_scores=True,
+                                                         score_row_out=brows[0], out=bout, workspace=bws), 6, 2)
+        del ly
+        ly = synth.make_decode_layer(bstk, stk.n_std, device=dev, dim_major=True, Lmax=Lmax)
+        tb_lisa = time_steps(lambda: lisa.lisa_attn_decode(ly["q_lr"], ly["k_lr_cache"], ly["v_cache"], Lk, brows[0],
+                                                           ly["w1"], ly["w2"], dim_major=True, write_scores=True,
+                                                           out=bout, score_row_out=brows[1], workspace=bws), 6, 2)
+        del ly, brows, bout, bws
+        torch.cuda.empty_cache()
+        n_s = stk.n_layers - n_lisa
+        step_eq = n_s * tb_std + n_lisa * tb_lisa
+        pat["equal_cache_memory"] = {
+            "batch": b_eq, "batch_all_standard": stk.B, "attention_step_us": step_eq * 1e6,
+            "tokens_per_s": b_eq / step_eq, "tokens_per_s_all_standard": stk.B / (stk.n_layers * t_std),
+            "throughput_vs_all_standard": (b_eq / step_eq) / (stk.B / (stk.n_layers * t_std)),
+        }
     return {
         "workload": f"{stk.name}: B{stk.B} ctx{stk.ctx}+1 H{stk.H} dk{stk.d_k} r{stk.r} F{stk.F}, "
                     f"{stk.n_std} standard + {stk.n_layers - stk.n_std} LiSA layers",
@@ -381,8 +413,8 @@ def main():
 
     extra["nf_prefill_standard_attention_no_scores_ms"] = time_steps(step_nf, max(args.steps // 2, 1), 1) * 1e3
 
-    # variants of the alignment module (Sec. 6.5 ablation, Sec. 6.3, Sec. 4) and the paper's default
-    # CONCAT form at its own widths (Sec. 6.1: FFN 2h -> 256 -> h, r = 20)
+    # variants of the alignment module (Sec. 5.7 ablation, Sec. 5.5, Sec. 4) and the paper's default
+    # CONCAT form at its own widths (Sec. 5.3: FFN 2h -> 256 -> h, r = 20)
     variants = {}
     s0 = sets[0]
     i0 = s0["inp"]

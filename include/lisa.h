@@ -51,7 +51,7 @@ typedef enum { LISA_F32 = 0, LISA_BF16 = 1 } lisa_dtype;
  *                                "An overview of LiSA"). */
 /*                        Two variants without the alignment FFN (w1, w2, F are ignored):
  *                        PLUS:   A_n = A_{n-1} + A_delta (LiSA_plus for models pre-trained with
- *                                shared attention, Sec. 6.3);
+ *                                shared attention, Sec. 5.5);
  *                        SHARE:  A_n = A_{n-1}, the direct sharing the method starts from (DS,
  *                                Sec. 4; q_lr, k_lr, r are ignored as well).
  * MFMA kernels exist for ADD (fused prefill, split-context decode) and for CONCAT (scores kernel
@@ -61,7 +61,7 @@ typedef enum { LISA_F32 = 0, LISA_BF16 = 1 } lisa_dtype;
  * combinations and shapes run on the generic kernels. */
 typedef enum { LISA_MIX_ADD = 0, LISA_MIX_CONCAT = 1, LISA_MIX_PLUS = 2, LISA_MIX_SHARE = 3 } lisa_mix;
 
-/* The alignment FFN (Sec. 6.1 "Model configuration": two layers with ReLU; Sec. 6.5 ablates
+/* The alignment FFN (Sec. 5.3 "Model configuration": two layers with ReLU; Sec. 5.7 ablates
  * SiLU, x * sigmoid(x), and a single layer).  SINGLE: A_align = W1^T x with W1 [Din,H]; F must
  * equal H and w2 is ignored. */
 typedef enum { LISA_ACT_RELU = 0, LISA_ACT_SILU = 1, LISA_ACT_SINGLE = 2 } lisa_act;
@@ -196,7 +196,7 @@ typedef struct lisa_proj_desc {
  * Q_LR = X W^Q_LR, K_LR = X W^K_LR (the two factors of Eq. 3) and the values V = X W^V
  * (Sec. 2.1 Eq. 1) in one product, split in heads and written where lisa_attn_prefill (dense
  * tensors: pos0 = 0, Lmax = L or 0, kcache_dim_major = 0) or lisa_attn_decode (the caches,
- * Sec. 5.2) read them.  The paper's LLaMA models (Sec. 6.1) rotate queries and keys by
+ * Sec. 5.2) read them.  The paper's LLaMA models (Sec. 5.3) rotate queries and keys by
  * position; with rope_theta > 0 every Q_LR / K_LR head y of the token at position p becomes
  *   (y[t] cos a - y[t+r/2] sin a,  y[t] sin a + y[t+r/2] cos a),  a = p * rope_theta^(-2t/r),
  * for t < r/2, before it is rounded and stored (the cache holds rotated K_LR).

@@ -41,11 +41,11 @@
 
 #define LISA_ORACLE_MIX_ADD 0
 #define LISA_ORACLE_MIX_CONCAT 1
-#define LISA_ORACLE_MIX_PLUS 2  /* Sec. 6.3, LiSA_plus: A_n = A_{n-1} + A_delta, no FFN          */
+#define LISA_ORACLE_MIX_PLUS 2  /* Sec. 5.5, LiSA_plus: A_n = A_{n-1} + A_delta, no FFN          */
 #define LISA_ORACLE_MIX_SHARE 3 /* Sec. 4, directly sharing (DS): A_n = A_{n-1}                   */
 #define LISA_ORACLE_ACT_RELU 0
-#define LISA_ORACLE_ACT_SILU 1   /* Sec. 6.5, "DL + SiLU": x * sigmoid(x)                          */
-#define LISA_ORACLE_ACT_SINGLE 2 /* Sec. 6.5, "SL": one layer, A_align = W1^T x with W1 [Din][H]  */
+#define LISA_ORACLE_ACT_SILU 1   /* Sec. 5.7, "DL + SiLU": x * sigmoid(x)                          */
+#define LISA_ORACLE_ACT_SINGLE 2 /* Sec. 5.7, "SL": one layer, A_align = W1^T x with W1 [Din][H]  */
 
 static int n_visible(int i, int Lq, int Lk) {
   int n = i + 1 + (Lk - Lq);
@@ -209,7 +209,7 @@ int lisa_oracle_lisa_rows(int H, int Hkv, int Lq, int Lk, int dk, int r, int F, 
 /* Front end of a LiSA layer for the requested token rows of one sequence:
  *   Q_LR = X W^Q_LR,  K_LR = X W^K_LR   (the two factors of Eq. 3),   V = X W^V   (Eq. 1),
  * each split in heads, followed, when theta > 0, by the rotary position embedding of the
- * LLaMA models of Sec. 6.1 on every Q_LR / K_LR head (r even): with half = r/2 and
+ * LLaMA models of Sec. 5.3 on every Q_LR / K_LR head (r even): with half = r/2 and
  * angle(pos, t) = pos * theta^(-2t/r), the pair (y[t], y[t+half]) becomes
  *   (y[t] cos - y[t+half] sin,  y[t] sin + y[t+half] cos),      pos = pos0 + row index.
  *   x [L][D] hidden states;  w [H*r + Hkv*r + Hkv*dk][D]: one row per output feature, the

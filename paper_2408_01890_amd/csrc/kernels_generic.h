@@ -84,8 +84,8 @@ __global__ __launch_bounds__(256) void k_std_scores(const T* __restrict__ q, con
 // heads / hidden units s, s+4, ...  Dynamic LDS: x[Din][64], hid[F][64], a_delta[H][64].
 // grid (ceil(Lk/64), Lq, B), block 256.
 // `mix`: 0 A_n = FFN(A_{n-1}) + A_delta, 1 A_n = FFN([A_{n-1}; A_delta]) (Sec. 5.1, Eq. 4),
-// 2 A_n = A_{n-1} + A_delta (LiSA_plus, Sec. 6.3), 3 A_n = A_{n-1} (direct sharing, Sec. 4).
-// `act`: 0 ReLU, 1 SiLU, 2 single layer y = W1^T x with F = H (Sec. 6.5).
+// 2 A_n = A_{n-1} + A_delta (LiSA_plus, Sec. 5.5), 3 A_n = A_{n-1} (direct sharing, Sec. 4).
+// `act`: 0 ReLU, 1 SiLU, 2 single layer y = W1^T x with F = H (Sec. 5.7).
 // ---------------------------------------------------------------------------------------
 template <typename T, typename S>
 __global__ __launch_bounds__(256) void k_lisa_scores(const T* __restrict__ q_lr,
@@ -285,8 +285,8 @@ __global__ __launch_bounds__(256) void k_cache_fill_rows(const T* __restrict__ s
 // ---------------------------------------------------------------------------------------
 // Two-layer ReLU network that equals a linear map exactly: relu(u) - relu(-u) = u.
 //   w1o [Din][2H] = [W, -W],  w2o [2H][H] = [I; -I]     (W = w1_user [Din][H], or the identity when
-// w1_user is null, Din = H).  Lets the single-layer alignment FFN (Sec. 6.5; LiSA_SL: 2h x h on the
-// concatenation) and LiSA_plus (Sec. 6.3: no FFN, i.e. the identity) run on the kernels built for
+// w1_user is null, Din = H).  Lets the single-layer alignment FFN (Sec. 5.7; LiSA_SL: 2h x h on the
+// concatenation) and LiSA_plus (Sec. 5.5: no FFN, i.e. the identity) run on the kernels built for
 // the two-layer ReLU form.
 // grid ceil((2 Din H + 2 H H) / 256), block 256.
 // ---------------------------------------------------------------------------------------

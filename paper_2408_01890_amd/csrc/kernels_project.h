@@ -1,6 +1,6 @@
 // Projection front end of a LiSA layer: Q_LR = X W^Q_LR, K_LR = X W^K_LR (the two factors of
 // Eq. 3) and V = X W^V (Sec. 2.1 Eq. 1) as one product X W^T over the stacked weight rows, with
-// the rotary position embedding of the LLaMA models (Sec. 6.1) applied to the Q_LR / K_LR heads
+// the rotary position embedding of the LLaMA models (Sec. 5.3) applied to the Q_LR / K_LR heads
 // before they are stored, and the results written where the attention kernels and the decode
 // caches expect them.
 //

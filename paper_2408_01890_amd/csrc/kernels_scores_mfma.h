@@ -1,6 +1,6 @@
 // A_n of a LiSA layer in CONCAT form on the matrix cores (bf16 inputs, half scores):
 //   A_n[:,i,j] = W2^T ReLU(W1^T [A_{n-1}[:,i,j] ; A_delta[:,i,j]])      (Sec. 5.1, "An overview of
-// LiSA": the alignment FFN takes the concatenation, 2h -> F -> h; Sec. 6.1: 64 -> 256 -> 32),
+// LiSA": the alignment FFN takes the concatenation, 2h -> F -> h; Sec. 5.3: 64 -> 256 -> 32),
 // with A_delta = Q_LR K_LR^T / sqrt(r) (Eq. 3).  The correction goes through the FFN here, so it
 // cannot be added per head after a position-wise stage as in the fused ADD kernel; this kernel
 // produces the score tensor (half), which the next layer shares and which the softmax / P V

@@ -41,8 +41,8 @@ __device__ __forceinline__ unsigned short half_bits(float f) {
 // HB = ceil(H / 16) input head blocks (KS = ceil(H / 32) k-steps of the first product),
 // FS = ceil(F / 32) hidden k-steps (2 FS hidden blocks of 16), HBO = blocks of 16 output heads
 // (the caller may ask for a sub-range of the H output heads: h_first .. h_first + n_out - 1).
-// ACT: activation of the hidden units, 0 = ReLU (Sec. 6.1), 1 = SiLU u * sigmoid(u) (ablated in
-// Sec. 6.5); both saturate at the half range.
+// ACT: activation of the hidden units, 0 = ReLU (Sec. 5.3), 1 = SiLU u * sigmoid(u) (ablated in
+// Sec. 5.7); both saturate at the half range.
 template <int HB, int FS, int HBO = HB, int ACT = 0>
 struct MfmaFfn {
   static constexpr int KS = (HB + 1) / 2;

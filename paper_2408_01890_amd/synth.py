@@ -4,7 +4,7 @@ This module only *draws and prepares inputs*; it contains none of the LiSA layer
 arithmetic (no scores, no alignment FFN, no softmax).  Both the HIP library and the CPU
 oracle are fed the arrays produced here, already rounded to the configuration's dtype.
 
-Recipe (stands in for the trained LLaMA2-7B / LLaMA3-8B / LLaMA2-13B layers of Sec. 6.1
+Recipe (stands in for the trained LLaMA2-7B / LLaMA3-8B / LLaMA2-13B layers of Sec. 5.3
 and App. C.1, whose weights are not available): hidden states X ~ N(0,1); projection and FFN
 weights ~ N(0, 0.02^2); Q_LR = X W^Q_LR, K_LR = X W^K_LR, V = X W^V by one library matmul
 (input preparation outside the library boundary; Eq. 3's `H W_LR` factor); optional rotary

@@ -937,7 +937,7 @@ def test_variants_that_run_on_the_mfma_kernels(variant):
 # ---------------------------------------------------------------------------------------
 CONCAT_MFMA = [
     # name, B, H, Hkv, L (multiple of 8), d_k, r (even), F
-    ("paper_dims_l200", 1, 32, 32, 200, 128, 20, 256),      # Sec. 6.1: 64 -> 256 -> 32, r = 20
+    ("paper_dims_l200", 1, 32, 32, 200, 128, 20, 256),      # Sec. 5.3: 64 -> 256 -> 32, r = 20
     ("gqa_l336", 2, 32, 8, 336, 128, 22, 128),
     ("h16_gqa_l152", 1, 16, 4, 152, 64, 12, 64),
     ("h8_l264_f200", 1, 8, 8, 264, 128, 32, 200),
@@ -1012,7 +1012,7 @@ def test_lisa_prefill_concat_on_mfma_scores_kernel(case, causal, ffn):
 
 @pytest.mark.parametrize("ffn", ["paper", "identity_noise", "fan_in"])
 def test_lisa_prefill_concat_full_size_sampled_rows(ffn):
-    # the benchmark shape with the paper's module (Sec. 6.1: 64 -> 256 -> 32, r = 20), as bench.py times it
+    # the benchmark shape with the paper's module (Sec. 5.3: 64 -> 256 -> 32, r = 20), as bench.py times it
     cfg = synth.LayerShape("c2_concat_64_256_32_r20", "bf16", 1, 32, 32, 2048, 4096, 128, 20, 256)
     log(f"[case] prefill {cfg.name} ffn={ffn} sampled")
     inp = synth.make_prefill_inputs(cfg, synth.BASE_SEED + 21, DEV, mix="concat", ffn=ffn)

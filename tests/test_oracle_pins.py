@@ -442,7 +442,7 @@ def test_printed_shapes_fix_per_head_rank_and_gqa_key_heads():
 
 # --------------------------------------------------------------------------------------
 # 9. Projection front end: Q_LR = X W^Q_LR, K_LR = X W^K_LR (factors of Eq. 3), V = X W^V
-#    (Eq. 1), rotary position embedding of the LLaMA models of Sec. 6.1 on Q_LR / K_LR.
+#    (Eq. 1), rotary position embedding of the LLaMA models of Sec. 5.3 on Q_LR / K_LR.
 # --------------------------------------------------------------------------------------
 def test_projection_without_rotation_is_a_library_matmul():
     g = rng(90)
@@ -526,8 +526,8 @@ def test_projection_rows_are_independent_of_the_request_set():
 
 
 # --------------------------------------------------------------------------------------
-# 10. Variants of the alignment module: SiLU and the single-layer FFN (Sec. 6.5), LiSA_plus
-#     (Sec. 6.3: A_{n-1} + A_delta) and direct sharing (Sec. 4: A_n = A_{n-1}).
+# 10. Variants of the alignment module: SiLU and the single-layer FFN (Sec. 5.7), LiSA_plus
+#     (Sec. 5.5: A_{n-1} + A_delta) and direct sharing (Sec. 4: A_n = A_{n-1}).
 # --------------------------------------------------------------------------------------
 def variant_problem(seed, H=4, Hkv=2, L=6, r=3, dk=5, F=7):
     g = rng(seed)
