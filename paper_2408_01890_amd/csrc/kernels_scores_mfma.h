@@ -235,7 +235,7 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
         }
       }
     };
-    constexpr int N_OPS = XCH + 2 * HPW + XCH + 1;          // loads of a tile, then read / store pairs
+    constexpr int N_OPS = XCH + 1 + XCH + 2 * HPW;          // read / store pairs of a tile, then the loads of the next
     constexpr int N_GROUPS = (FS / SC) * (2 * SC + HBO);
     constexpr int OPG = (N_OPS + N_GROUPS - 1) / N_GROUPS;
     for (int tile = t_first; tile < t_last; ++tile) {
@@ -255,16 +255,18 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
       Ffn::template apply_lds_chunked<NBW, SC>(w_s, x, y, [&](int gidx) {
 #pragma unroll
         for (int k = gidx * OPG; k < (gidx + 1) * OPG && k < N_OPS; ++k) {
-          if (k < XCH) {
-            xr[k] = *(const pf_u32x4*)(pbase + min(wv + NW * k, H - 1) * phead + xoff);
-          } else if (k < XCH + 2 * HPW) {
-            const int u = (k - XCH) >> 1, half = (k - XCH) & 1;
+          if (k <= XCH) {                                    // stores first: the wait for the loads, at the
+            if (pending) {                                   // next staging, also waits for them
+              if (k > 0) out_store(k - 1, jo);
+              if (k < XCH) out_read(k);
+            }
+          } else if (k <= 2 * XCH) {
+            const int u = k - XCH - 1;
+            xr[u] = *(const pf_u32x4*)(pbase + min(wv + NW * u, H - 1) * phead + xoff);
+          } else {
+            const int u = (k - 2 * XCH - 1) >> 1, half = (k - 2 * XCH - 1) & 1;
             const int h = min(wv + NW * u, H - 1);
             kop[u][half] = *(const bf16x8*)(a.kp + ((size_t)b * a.Hkv + h / group) * a.Lkp * 32 + koff[half]);
-          } else if (pending) {
-            const int sidx = k - XCH - 2 * HPW;
-            if (sidx > 0) out_store(sidx - 1, jo);
-            if (sidx < XCH) out_read(sidx);
           }
         }
       });
