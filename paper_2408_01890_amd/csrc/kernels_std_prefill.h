@@ -124,20 +124,27 @@ __global__ __launch_bounds__(256, 2) void k_std_prefill(StdPrefillArgs a) {
     half_t* sbase = a.scores ? a.scores + ((size_t)b * H + h) * Lq * Lk : nullptr;
     unsigned char* stg = ss_ + wv * SP_STILE;
 
-    pf_u32x4 kreg[2], vreg[2];
-    auto load_tile = [&](int tile) {
+    // The K / V tile of a step travels through registers: loaded three tiles ahead into one of two
+    // register sets, written to LDS one tile ahead.  Two sets rather than one because loads and
+    // stores complete in one order behind one counter, and the score stores below are conditional
+    // (uncountable for the compiler): with one set the wait for the tile loads at the top of a step
+    // was a wait for everything, the score stores of the step before included; with two the loads
+    // of the other set lie between, and only what is older than those has to be complete.
+    typedef pf_u32x4 TileRegs[2][2];                       // [K, V][chunk]
+    TileRegs regs_a, regs_b;
+    auto load_tile = [&](int tile, TileRegs& tr) {
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         const int j = min(tile * SP_TK + ck_key + 16 * u, Lk - 1);
-        if (!GIVEN) kreg[u] = *(const pf_u32x4*)(kbase + (size_t)j * DK + 8 * ck_c);
-        if (WITH_V) vreg[u] = *(const pf_u32x4*)(vbase + (size_t)tile * (SP_TK / 8 * DK * 8) + (tid + 256 * u) * 8);
+        if (!GIVEN) tr[0][u] = *(const pf_u32x4*)(kbase + (size_t)j * DK + 8 * ck_c);
+        if (WITH_V) tr[1][u] = *(const pf_u32x4*)(vbase + (size_t)tile * (SP_TK / 8 * DK * 8) + (tid + 256 * u) * 8);
       }
     };
-    auto store_tile = [&](int buf) {
+    auto store_tile = [&](int buf, const TileRegs& tr) {
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
-        if (!GIVEN) *(pf_u32x4*)(ks_ + buf * SP_KTILE + (ck_key + 16 * u) * SP_KROW + ck_c * 16) = kreg[u];
-        if (WITH_V) *(pf_u32x4*)(vs_ + buf * SP_VTILE + (tid + 256 * u) * 16) = vreg[u];
+        if (!GIVEN) *(pf_u32x4*)(ks_ + buf * SP_KTILE + (ck_key + 16 * u) * SP_KROW + ck_c * 16) = tr[0][u];
+        if (WITH_V) *(pf_u32x4*)(vs_ + buf * SP_VTILE + (tid + 256 * u) * 16) = tr[1][u];
       }
     };
     // GIVEN = 2: the wave's scores of a tile are loaded two tiles ahead (nothing else hides the
@@ -149,9 +156,10 @@ __global__ __launch_bounds__(256, 2) void k_std_prefill(StdPrefillArgs a) {
         dst[u] = *(const f16x8*)(grow_h + min(tile * SP_TK + 16 * u + 8 * half, Lk - 8));
     };
     if (rep) __syncthreads();                              // the first pass is done with both buffers
-    load_tile(0);
-    store_tile(0);
-    load_tile(min(1, n_tiles - 1));
+    load_tile(0, regs_a);
+    store_tile(0, regs_a);
+    load_tile(min(1, n_tiles - 1), regs_a);                // set a: odd tiles, set b: even tiles
+    load_tile(min(2, n_tiles - 1), regs_b);
     if (GIVEN == 2) {
       load_scores(0, gq[0]);
       load_scores(min(1, n_tiles - 1), gq[1]);
@@ -164,12 +172,12 @@ __global__ __launch_bounds__(256, 2) void k_std_prefill(StdPrefillArgs a) {
       for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    for (int tile = 0; tile < n_tiles; ++tile) {
+    auto step = [&](int tile, TileRegs& tr) {              // tr holds tile + 1
       // tile `tile` is complete in buffer tile & 1, and every wave is done with the other buffer
       lds_barrier();
-      store_tile((tile + 1) & 1);
-      load_tile(min(tile + 2, n_tiles - 1));
-      if (tile >= n_tiles_w) continue;                     // beyond this wave's diagonal (wave-uniform)
+      store_tile((tile + 1) & 1, tr);
+      load_tile(min(tile + 3, n_tiles - 1), tr);
+      if (tile >= n_tiles_w) return;                       // beyond this wave's diagonal (wave-uniform)
       const unsigned char* kt = ks_ + (tile & 1) * SP_KTILE;
       const unsigned char* vtl = vs_ + (tile & 1) * SP_VTILE;
       const int j0 = tile * SP_TK;
@@ -273,7 +281,16 @@ __global__ __launch_bounds__(256, 2) void k_std_prefill(StdPrefillArgs a) {
             o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pop[s], o[db], 0, 0, 0);
           }
       }
+    };
+    // (everything loaded so far has arrived before the loop is entered: the wait counts inside the
+    // loop then follow from the loop's own issue order, not from that of the prologue)
+    __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0), others untouched
+    int tile = 0;
+    for (; tile + 1 < n_tiles; tile += 2) {                // (both steps on every path round the loop)
+      step(tile, regs_a);
+      step(tile + 1, regs_b);
     }
+    if (tile < n_tiles) step(tile, regs_a);
 
     if (WITH_V) {
       // O[row][h][32 db + 8 (v/4) + 4 half + v%4] = o[db][v] / l

@@ -654,8 +654,8 @@ int run_softmax_given_fast(const lisa_desc* d, const void* given, bool given_hal
     if (rc) return rc;
   }
   const int n_groups = (d->Lq + SP_GROUP - 1) / SP_GROUP;
-  a.pair = (long long)d->H * ((n_groups + 1) / 2) * d->B >= 2 * kComputeUnits;
-  dim3 grid(d->H, a.pair ? (n_groups + 1) / 2 : n_groups, d->B);
+  a.pair = 0;
+  dim3 grid(d->H, n_groups, d->B);
   StageScope prof("k_softmax_v_mfma", st);
   if (given_half)
     k_std_prefill<true, 2><<<grid, 256, 0, st>>>(a);
@@ -691,10 +691,11 @@ int run_std_prefill_fast(const lisa_desc* d, const void* q, const void* k, const
     if (rc) return rc;
   }
   const int n_groups = (d->Lq + SP_GROUP - 1) / SP_GROUP;
-  // A workgroup takes the x-th longest and the x-th shortest row group (equal work for all) when
-  // that still leaves two workgroups per compute unit; a smaller problem keeps one row group per
-  // workgroup, long ones first, so that every SIMD has two waves while the short ones last.
-  a.pair = (long long)d->H * ((n_groups + 1) / 2) * d->B >= 2 * kComputeUnits;
+  // One row group per workgroup, long ones first: the dispatcher evens out the rest.  (The kernel
+  // can also take the x-th longest and the x-th shortest row group in one workgroup, equal work
+  // for all; measured equal on the LLaMA2-13B shape at L = 4096, 3 - 7 % slower at L = 8192 with
+  // grouped keys and 10 % slower at L = 2048, where it leaves one workgroup per compute unit.)
+  a.pair = 0;
   if (const char* e = std::getenv("LISA_STD_PAIR")) a.pair = std::atoi(e) != 0;   // tests force either
   dim3 grid(d->H, a.pair ? (n_groups + 1) / 2 : n_groups, d->B);
   StageScope prof("k_std_prefill", st);
