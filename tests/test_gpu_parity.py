@@ -87,6 +87,7 @@ STD_MFMA_SHAPES = [
     ("gqa_chunk_96x264", 1, 8, 2, 96, 264, True),
     ("gqa_full_72x136", 1, 12, 4, 72, 136, False),
     ("one_tile_24", 1, 4, 4, 24, 24, True),
+    ("mha_l520", 1, 4, 4, 520, 520, True),                 # five row groups of 4 .. 17 key tiles
 ]
 
 
