@@ -224,3 +224,16 @@ def test_binding_refuses_cpu_tensors():
     x = torch.zeros(1, 2, 4, 8)
     with pytest.raises(ValueError, match="GPU tensor"):
         lisa.std_attn_scores(x, x)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU: any other count ends with a message and a non-zero status
+    before anything touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    for argv, env in ((["--gpus", "2"], {}), ([], {"WORLD_SIZE": "2"})):
+        p = subprocess.run([sys.executable, os.path.join(root, "bench.py")] + argv, capture_output=True, text=True,
+                           env={**os.environ, **env}, timeout=120)
+        assert p.returncode != 0
+        assert "one GPU" in p.stderr and p.stdout.strip() == ""
