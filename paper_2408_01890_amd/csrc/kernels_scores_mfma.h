@@ -15,8 +15,10 @@
 //      appends it as heads H .. 2H-1 of the same LDS array;
 //   2. every wave runs the FFN (mfma_ffn.h, weights read from their LDS image) on 4 of the 32
 //      blocks of 16 positions, the 2H input "heads" fetched with transposing LDS reads;
-//   3. the results go to LDS as float32 [head][row][key] (over the input tile) and leave by
-//      heads in whole rows, 64 bytes of half per row and tile.
+//   3. the results go to LDS [head][row][key] and leave by heads in whole rows, 64 bytes of half
+//      per row and tile: up to 32 heads as half in an array of their own, stored during the FFN of
+//      the next tile (two barriers per tile); wider forms as float32 over the input tile, stored
+//      before the next tile is staged (four barriers).
 // Requires Lk % 8 == 0, r <= 32, H <= 48, F <= 256.
 #pragma once
 #include "kernels_prefill.h"
