@@ -239,6 +239,61 @@ def decode_stack(stk, steps, warmup):
     }
 
 
+def graph_replay(steps, warmup):
+    """The timed step (k_prepare_prefill + k_lisa_prefill_fused, A_n emitted) captured once per
+    buffer set into a HIP graph and replayed: what the step costs without the host's launch path.
+    Every replay is checked against the eager result of the same set, with eager work between."""
+    import torch
+    from paper_2408_01890_amd import lisa, synth
+    torch.cuda.set_device(0)
+    dev, cfg = "cuda", synth.C2
+    sets = []
+    for s in range(4):
+        inp = synth.make_prefill_inputs(cfg, synth.BASE_SEED + 2 + 100 * s, dev)
+        prev, _ = lisa.std_attn_scores(inp["q"], inp["k"])
+        sets.append(dict(inp=inp, prev=prev,
+                         out=torch.empty((cfg.B, cfg.L, cfg.H, cfg.d_k), dtype=torch.float32, device=dev),
+                         a_n=torch.empty_like(prev)))
+    d0 = lisa.make_desc(cfg.torch_dtype, cfg.B, cfg.H, cfg.Hkv, cfg.L, cfg.L, cfg.d_k, cfg.r, cfg.F,
+                        write_scores=1, out_f32=1)
+    ws = torch.empty(max(lisa.workspace_bytes(d0, lisa.WS_PREFILL), 256), dtype=torch.uint8, device=dev)
+
+    def run(s):
+        i = s["inp"]
+        lisa.lisa_attn_prefill(i["q_lr"], i["k_lr"], i["v"], s["prev"], i["w1"], i["w2"],
+                               write_scores=True, out=s["out"], scores_out=s["a_n"], workspace=ws)
+
+    ref = []
+    for s in sets:                                           # eager results (and warm-up)
+        s["a_n"].fill_(7.0)                                  # (entries above the diagonal are never written)
+        run(s)
+        torch.cuda.synchronize()
+        ref.append((s["out"].clone(), s["a_n"].clone()))
+    graphs = []
+    for s in sets:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            run(s)
+        graphs.append(g)
+    ok = True
+    for rnd in range(3):
+        for s, g, (o_ref, a_ref) in zip(sets, graphs, ref):
+            s["out"].zero_()                                 # eager work between the replays
+            s["a_n"].fill_(7.0)
+            g.replay()
+            torch.cuda.synchronize()
+            ok = ok and torch.equal(s["out"], o_ref) and torch.equal(s["a_n"], a_ref)
+    n = [0]
+
+    def step():
+        graphs[n[0] % 4].replay()
+        n[0] += 1
+
+    sec = time_steps(step, steps, warmup)
+    return {"ms_per_step": sec * 1e3, "tokens_per_s": cfg.B * cfg.L / sec, "replays_equal_eager": bool(ok),
+            "steps": steps}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -249,6 +304,9 @@ def main():
     ap.add_argument("--decode-only", action="store_true",
                     help="run only the 32-layer decode step (for profiling) and print its record")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--graph-only", action="store_true",
+                    help="run only the HIP-graph replay of the timed step and print its record")
     ap.add_argument("--cpu-budget", type=float, default=15.0)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -259,6 +317,9 @@ def main():
     from paper_2408_01890_amd import lisa, synth
     assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU path)"
     torch.cuda.set_device(0)
+    if args.graph_only:
+        print(json.dumps(graph_replay(args.steps, args.warmup)), flush=True)
+        return
     # a plain 1 GiB device-to-device copy: the known-size dispatch that counter profiles of
     # this command are calibrated against (HBM bytes per FETCH_SIZE / WRITE_SIZE unit)
     cal = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
@@ -459,6 +520,17 @@ def main():
     torch.cuda.empty_cache()
     if not args.no_decode:
         extra["decode"] = decode_stack(synth.C5, args.decode_steps, 1)
+    if not args.no_graph:
+        # in a process of its own: a capture that fails must not take this record with it
+        import subprocess
+        try:
+            p = subprocess.run([sys.executable, os.path.abspath(__file__), "--graph-only", "--steps", str(args.steps),
+                                "--warmup", str(args.warmup)], capture_output=True, text=True, timeout=180)
+            rec = [ln for ln in p.stdout.splitlines() if ln.startswith("{")]
+            extra["hip_graph_replay"] = json.loads(rec[-1]) if p.returncode == 0 and rec else {
+                "error": (p.stderr.strip().splitlines() or ["no output"])[-1][:200]}
+        except Exception as e:                               # noqa: BLE001 (reported, not fatal)
+            extra["hip_graph_replay"] = {"error": repr(e)[:200]}
     line = {
         "metric": "LiSA-layer prefill tokens/s", "value": cfg.B * cfg.L / sec, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3,
