@@ -521,14 +521,8 @@ def main():
     if not args.no_decode:
         extra["decode"] = decode_stack(synth.C5, args.decode_steps, 1)
     if not args.no_graph:
-        # in a process of its own: a capture that fails must not take this record with it
-        import subprocess
         try:
-            p = subprocess.run([sys.executable, os.path.abspath(__file__), "--graph-only", "--steps", str(args.steps),
-                                "--warmup", str(args.warmup)], capture_output=True, text=True, timeout=180)
-            rec = [ln for ln in p.stdout.splitlines() if ln.startswith("{")]
-            extra["hip_graph_replay"] = json.loads(rec[-1]) if p.returncode == 0 and rec else {
-                "error": (p.stderr.strip().splitlines() or ["no output"])[-1][:200]}
+            extra["hip_graph_replay"] = graph_replay(args.steps, args.warmup)
         except Exception as e:                               # noqa: BLE001 (reported, not fatal)
             extra["hip_graph_replay"] = {"error": repr(e)[:200]}
     line = {
