@@ -1046,3 +1046,89 @@ def test_lisa_prefill_concat_mfma_chunked_rows():
     err_a = hp.scores_row_rel_err(hp.gather_score_rows(scores, 0, local), a_ref, rows, cfg.L, cfg.L)
     log(f"[parity] concat mfma chunked: err_out={err_o:.3e} err_scores={err_a:.3e}")
     assert err_o <= hp.TOL[torch.bfloat16] and err_a <= hp.TOL[torch.bfloat16]
+
+
+# ---------------------------------------------------------------------------------------
+# seeded random shapes (the fixed lists above were chosen with the tilings in mind; these were not)
+# ---------------------------------------------------------------------------------------
+def _rand_rows(Lq, seed):
+    return np.unique(np.concatenate([np.arange(min(Lq, 2)), np.random.RandomState(seed).randint(0, Lq, 8), [Lq - 1]]))
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_std_prefill_mfma_random_shapes(seed):
+    import random
+    from oracle import cref
+    rnd = random.Random(1100 + seed)
+    H = rnd.choice([2, 4, 8, 12, 32])
+    Hkv = H // rnd.choice([g for g in (1, 2, 4) if H % g == 0])
+    B = rnd.choice([1, 2])
+    Lk = 8 * rnd.randint(1, 90)
+    Lq = Lk if rnd.random() < 0.6 else 8 * rnd.randint(1, Lk // 8)
+    causal = rnd.random() < 0.8
+    log(f"[case] std random {seed}: B{B} H{H}/{Hkv} Lq{Lq} Lk{Lk} causal={causal}")
+    dt = torch.bfloat16
+    g = torch.Generator(device=DEV).manual_seed(100 + seed)
+    q = torch.randn((B, H, Lq, 128), generator=g, device=DEV).to(dt)
+    k = torch.randn((B, Hkv, Lk, 128), generator=g, device=DEV).to(dt)
+    v = torch.randn((B, Hkv, Lk, 128), generator=g, device=DEV).to(dt)
+    sent = torch.full((B, H, Lq, Lk), SENTINEL, dtype=torch.float16, device=DEV)
+    _, out = lisa.std_attn_scores(q, k, v, scores_out=sent, causal=causal)
+    assert lisa.last_path() == "mfma_std"
+    _, o2 = lisa.std_attn_scores(q, k, v, want_scores=False, causal=causal)
+    torch.cuda.synchronize()
+    eo = ea = 0.0
+    for b in range(B):
+        for i in _rand_rows(Lq, seed):
+            nv = hp.n_visible(int(i), Lq, Lk, causal)
+            # a row and its visible keys as a one-row problem with full visibility
+            ref = hp.oracle_std_rows(q[:, :, i:i + 1], k[:, :, :nv], b, [0])
+            o_ref = cref.softmax_v_rows(hp.f64(v[b])[:, :nv], [0], ref, 1)
+            ea = max(ea, hp.row_rel_err(sent[b, :, i, :nv].double().cpu().numpy()[None], ref))
+            for o in (out, o2):
+                eo = max(eo, hp.row_rel_err(o[b, i].double().cpu().numpy()[None], o_ref))
+            assert torch.all(sent[b, :, i, nv:] == SENTINEL)
+    log(f"[parity] std random {seed}: err_out={eo:.3e} err_scores={ea:.3e}")
+    assert max(eo, ea) <= hp.TOL[dt]
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_lisa_prefill_concat_mfma_random_shapes(seed):
+    import random
+    from oracle import cref
+    rnd = random.Random(2100 + seed)
+    H = rnd.choice([8, 12, 16, 20, 24, 32, 40, 48])
+    Hkv = H // rnd.choice([g for g in (1, 2, 4) if H % g == 0])
+    B = rnd.choice([1, 2, 3])
+    Lk = 8 * rnd.randint(2, 70)
+    Lq = Lk if rnd.random() < 0.6 else 8 * rnd.randint(1, Lk // 8)
+    dk = rnd.choice([64, 128])
+    r = rnd.choice([8, 12, 16, 20, 22, 32])
+    F = rnd.choice([32, 64, 96, 128, 200, 256])
+    if H > 40:
+        F = min(F, 128)                                      # (48 heads with 256 hidden units exceed the LDS)
+    causal = rnd.random() < 0.8
+    act = rnd.choice([lisa.ACT_RELU, lisa.ACT_SILU])
+    log(f"[case] concat random {seed}: B{B} H{H}/{Hkv} Lq{Lq} Lk{Lk} dk{dk} r{r} F{F} causal={causal} act={act}")
+    cfg = synth.LayerShape(f"rand{seed}", "bf16", B, H, Hkv, Lk, 256, dk, r, F)
+    inp = synth.make_prefill_inputs(cfg, 3000 + seed, DEV, mix="concat", ffn=rnd.choice(["paper", "fan_in"]))
+    prev_full, _ = lisa.std_attn_scores(inp["q"], inp["k"], causal=causal)
+    q_lr = inp["q_lr"][:, :, Lk - Lq:].contiguous()           # the last Lq positions as a chunk
+    prev = prev_full[:, :, Lk - Lq:].contiguous()
+    sent = torch.full((B, H, Lq, Lk), SENTINEL, dtype=torch.float16, device=DEV)
+    out, sc = lisa.lisa_attn_prefill(q_lr, inp["k_lr"], inp["v"], prev, inp["w1"], inp["w2"], mix=lisa.MIX_CONCAT,
+                                     act=act, causal=causal, scores_out=sent)
+    torch.cuda.synchronize()
+    assert lisa.last_path() == "mfma_scores"
+    eo = ea = 0.0
+    for b in range(B):
+        for i in _rand_rows(Lq, seed):
+            nv = hp.n_visible(int(i), Lq, Lk, causal)
+            a_ref, o_ref = cref.lisa_rows(hp.f64(q_lr[b])[:, i:i + 1], hp.f64(inp["k_lr"][b])[:, :nv],
+                                          hp.f64(inp["v"][b])[:, :nv], hp.f64(inp["w1"]), hp.f64(inp["w2"]), [0],
+                                          hp.gather_score_rows(prev, b, [i])[:, :, :nv], mix=1, act=act)
+            eo = max(eo, hp.row_rel_err(out[b, i].double().cpu().numpy()[None], o_ref))
+            ea = max(ea, hp.row_rel_err(sc[b, :, i, :nv].double().cpu().numpy()[None], a_ref[:, :, :nv]))
+            assert torch.all(sc[b, :, i, nv:] == SENTINEL)
+    log(f"[parity] concat random {seed}: err_out={eo:.3e} err_scores={ea:.3e}")
+    assert max(eo, ea) <= hp.TOL[torch.bfloat16]
