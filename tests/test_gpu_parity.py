@@ -1132,3 +1132,92 @@ def test_lisa_prefill_concat_mfma_random_shapes(seed):
             assert torch.all(sc[b, :, i, nv:] == SENTINEL)
     log(f"[parity] concat random {seed}: err_out={eo:.3e} err_scores={ea:.3e}")
     assert max(eo, ea) <= hp.TOL[torch.bfloat16]
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_lisa_prefill_fused_random_shapes(seed):
+    """The fused ADD kernel (H in 8, 16, 24, 32, 40; d_k = 128; F <= 128; r <= 32) on random
+    lengths, batch sizes, key groupings and chunked rows."""
+    import random
+    from oracle import cref
+    rnd = random.Random(4100 + seed)
+    H = rnd.choice([8, 16, 24, 32, 40])
+    Hkv = H // rnd.choice([g for g in (1, 2, 4, 8) if H % g == 0])
+    B = rnd.choice([1, 2, 3])
+    Lk = 8 * rnd.randint(2, 80)
+    Lq = Lk if rnd.random() < 0.6 else 8 * rnd.randint(1, Lk // 8)
+    r = rnd.choice([8, 11, 16, 22, 32])
+    F = rnd.choice([16, 32, 64, 80, 128])
+    causal = rnd.random() < 0.8
+    ffn = rnd.choice(["paper", "fan_in"])
+    log(f"[case] fused random {seed}: B{B} H{H}/{Hkv} Lq{Lq} Lk{Lk} r{r} F{F} causal={causal} ffn={ffn}")
+    cfg = synth.LayerShape(f"rand{seed}", "bf16", B, H, Hkv, Lk, 256, 128, r, F)
+    inp = synth.make_prefill_inputs(cfg, 5000 + seed, DEV, ffn=ffn)
+    prev_full, _ = lisa.std_attn_scores(inp["q"], inp["k"], causal=causal)
+    q_lr = inp["q_lr"][:, :, Lk - Lq:].contiguous()
+    prev = prev_full[:, :, Lk - Lq:].contiguous()
+    sent = torch.full((B, H, Lq, Lk), SENTINEL, dtype=torch.float16, device=DEV)
+    out, sc = lisa.lisa_attn_prefill(q_lr, inp["k_lr"], inp["v"], prev, inp["w1"], inp["w2"], causal=causal,
+                                     scores_out=sent, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert lisa.last_path() == "mfma_fused"
+    eo = ea = 0.0
+    for b in range(B):
+        for i in _rand_rows(Lq, seed):
+            nv = hp.n_visible(int(i), Lq, Lk, causal)
+            a_ref, o_ref = cref.lisa_rows(hp.f64(q_lr[b])[:, i:i + 1], hp.f64(inp["k_lr"][b])[:, :nv],
+                                          hp.f64(inp["v"][b])[:, :nv], hp.f64(inp["w1"]), hp.f64(inp["w2"]), [0],
+                                          hp.gather_score_rows(prev, b, [i])[:, :, :nv])
+            eo = max(eo, hp.row_rel_err(out[b, i].double().cpu().numpy()[None], o_ref))
+            ea = max(ea, hp.row_rel_err(sc[b, :, i, :nv].double().cpu().numpy()[None], a_ref[:, :, :nv]))
+            assert torch.all(sc[b, :, i, nv:] == SENTINEL)
+    log(f"[parity] fused random {seed}: err_out={eo:.3e} err_scores={ea:.3e}")
+    assert max(eo, ea) <= hp.TOL[torch.bfloat16]
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_decode_split_random_shapes(seed):
+    """The split-context decode kernels (LiSA layer in ADD and CONCAT form, standard layer) on
+    random batch sizes, context lengths, head counts and cache capacities."""
+    import random
+    from oracle import cref
+    rnd = random.Random(6100 + seed)
+    H = rnd.choice([8, 16, 24, 32, 40])
+    Hkv = H // (1, 2, 4)[seed % 3]                           # (every key grouping and both head widths occur)
+    B = (1, 2, 5)[(seed // 2) % 3]
+    ctx = rnd.randint(1, 700)
+    dk = (64, 128)[seed % 2]
+    r = rnd.choice([8, 11, 16, 22, 32])
+    concat = (seed // 2) % 2 == 0
+    F = rnd.choice([32, 64, 128, 256] if concat else [16, 32, 64, 128])
+    dim_major = seed % 4 != 3
+    Lk, Lmax = ctx + 1, ctx + 1 + rnd.randint(0, 40)
+    stk = synth.DecodeStack(f"rand{seed}", "bf16", B, H, Hkv, ctx, 256, dk, r, F, 2, 1)
+    log(f"[case] decode random {seed}: B{B} H{H}/{Hkv} ctx{ctx} Lmax{Lmax} dk{dk} r{r} F{F} concat={concat} "
+        f"dim_major={dim_major}")
+    tol = hp.TOL[torch.bfloat16]
+    # standard layer
+    ly = synth.make_decode_layer(stk, 0, device=DEV, dim_major=dim_major, Lmax=Lmax)
+    row, out = lisa.std_attn_decode(ly["q"], ly["k_cache"], ly["v_cache"], Lk)
+    torch.cuda.synchronize()
+    assert lisa.last_path() == "decode_split"
+    for b in range(B):
+        ref = hp.oracle_std_rows(ly["q"][:, :, None, :], ly["k_cache"][:, :, :Lk], b, [0])
+        o_ref = cref.softmax_v_rows(hp.f64(ly["v_cache"][b])[:, :Lk], [0], ref, 1)
+        assert hp.row_rel_err(hp.f64(row[b])[None], ref) <= tol
+        assert hp.row_rel_err(hp.f64(out[b])[None], o_ref) <= tol
+    # LiSA layer on the score row of the standard layer
+    ly = synth.make_decode_layer(stk, 1, device=DEV, mix="concat" if concat else "add", dim_major=dim_major,
+                                 Lmax=Lmax, ffn=rnd.choice(["paper", "fan_in"]))
+    mix = lisa.MIX_CONCAT if concat else lisa.MIX_ADD
+    out, row2 = lisa.lisa_attn_decode(ly["q_lr"], ly["k_lr_cache"], ly["v_cache"], Lk, row, ly["w1"], ly["w2"],
+                                      dim_major=dim_major, mix=mix)
+    torch.cuda.synchronize()
+    assert lisa.last_path() == "decode_split"
+    eo = ea = 0.0
+    for b in range(B):
+        a_ref, o_ref = oracle_decode_lisa(ly, b, Lk, hp.f64(row[b]), dim_major, mix=1 if concat else 0)
+        ea = max(ea, hp.row_rel_err(hp.f64(row2[b])[None], a_ref))
+        eo = max(eo, hp.row_rel_err(hp.f64(out[b])[None], o_ref))
+    log(f"[parity] decode random {seed}: err_out={eo:.3e} err_scores={ea:.3e}")
+    assert max(eo, ea) <= tol
