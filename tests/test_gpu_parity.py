@@ -1221,3 +1221,29 @@ def test_decode_split_random_shapes(seed):
         eo = max(eo, hp.row_rel_err(hp.f64(out[b])[None], o_ref))
     log(f"[parity] decode random {seed}: err_out={eo:.3e} err_scores={ea:.3e}")
     assert max(eo, ea) <= tol
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_projection_random_shapes(seed):
+    """The bf16 projection kernels (tiled and few-row form) on random widths, lengths, head
+    counts, positions and cache layouts."""
+    rs = np.random.RandomState(7100 + seed)
+    H = int(rs.choice([2, 4, 8, 12, 16, 32, 40]))
+    Hkv = H // (1, 2, 4)[seed % 3] if H % (1, 2, 4)[seed % 3] == 0 else H
+    dk = (128, 64, 32, 96)[seed % 4]
+    theta = (10000.0, 500000.0, None)[seed % 3]
+    r = int(rs.choice([r for r in (6, 7, 8, 11, 16, 22, 32) if r <= dk and (theta is None or r % 2 == 0)]))
+    D = 64 * int(rs.randint(1, 9))                           # (the rotary embedding pairs the elements of a head)
+    few_rows = seed % 2 == 1
+    B = int(rs.randint(1, 4))
+    L = int(rs.randint(1, 128 // B + 1)) if few_rows else int(rs.randint(128 // B + 1, 400))
+    pos0 = int(rs.randint(0, 50)) if seed % 2 else 0
+    dim_major = seed % 4 < 2
+    extra = int(rs.randint(0, 9))
+    log(f"[case] projection random {seed}: B{B} H{H}/{Hkv} L{L} d{D} dk{dk} r{r} theta={theta} pos0={pos0} "
+        f"dim_major={dim_major}")
+    cfg = synth.LayerShape(f"proj_rand{seed}", "bf16", B, H, Hkv, L, D, dk, r, 64, theta)
+    pin = synth.make_projection_inputs(cfg, seed=8100 + seed, device=DEV)
+    rows = {b: np.unique(np.concatenate([np.arange(min(L, 3)), rs.randint(0, L, 24), [L - 1]])) for b in range(B)}
+    path = check_projection(cfg, pin, rows, theta, pos0, dim_major, pos0 + L + extra)
+    assert path == ("project_skinny" if B * L <= 128 else "project_mfma")
