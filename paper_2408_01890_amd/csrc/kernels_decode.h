@@ -78,13 +78,20 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
         for (int e = 0; e < 8; ++e) acc[e] = 0.f;
         if (jb < Lk) {      // the cache holds Lmax >= 8 ceil(Lk / 8) keys per row (ks.t % 8 == 0)
           const bf16_t* kp = a.kc + b * a.ks.b + (h / group) * a.ks.h + jb;
-          for (int t = 0; t < a.r; ++t) {
-            const u32x4 kvv = *(const u32x4*)(kp + (size_t)t * a.ks.t);
-            const float qt = q_s[h * a.r + t];
+          // UN rows of the rank axis per batch of independent loads (a row past the rank repeats
+          // the last one with a zero factor)
+          for (int t0 = 0; t0 < a.r; t0 += UN) {
+            u32x4 kvv[UN];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              acc[2 * e] += qt * bf16_bits_to_f32(kvv[e] & 0xffffu);
-              acc[2 * e + 1] += qt * bf16_bits_to_f32(kvv[e] >> 16);
+            for (int u = 0; u < UN; ++u) kvv[u] = *(const u32x4*)(kp + (size_t)min(t0 + u, a.r - 1) * a.ks.t);
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+              const float qt = t0 + u < a.r ? q_s[h * a.r + t0 + u] : 0.f;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                acc[2 * e] += qt * bf16_bits_to_f32(kvv[u][e] & 0xffffu);
+                acc[2 * e + 1] += qt * bf16_bits_to_f32(kvv[u][e] >> 16);
+              }
             }
           }
         }
@@ -105,35 +112,52 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
       }
     }
   } else {
+    // (items and two register sets as in S4 below)
+    constexpr int NBATCH = DEC_CK / KPW / UN;
     const int js = lane / LPK, dc = lane % LPK;
-    for (int h = wv; h < H; h += 4) {
-      float qf[8];
-      const u32x4 qv = *(const u32x4*)(a.q + ((size_t)b * H + h) * DK + dc * 8);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        qf[2 * e] = bf16_bits_to_f32(qv[e] & 0xffffu);
-        qf[2 * e + 1] = bf16_bits_to_f32(qv[e] >> 16);
-      }
+    const int n_items = ((H - wv + 3) / 4) * NBATCH;
+    auto issue = [&](int item, u32x4 (&kvv)[UN]) {
+      item = min(item, n_items - 1);
+      const int h = wv + 4 * (item / NBATCH), it = (item % NBATCH) * UN;
       const bf16_t* kb = a.kc + b * a.ks.b + (h / group) * a.ks.h + dc * 8;
-      for (int it = 0; it < DEC_CK / KPW; it += UN) {
-        u32x4 kvv[UN];
 #pragma unroll
-        for (int u = 0; u < UN; ++u) {
-          const int jc = min(js + (it + u) * KPW, n_here - 1);     // clamped, result unused
-          kvv[u] = *(const u32x4*)(kb + (size_t)(j0 + jc) * a.ks.j);
+      for (int u = 0; u < UN; ++u) {
+        const int jc = min(js + (it + u) * KPW, n_here - 1);     // clamped, result unused
+        kvv[u] = *(const u32x4*)(kb + (size_t)(j0 + jc) * a.ks.j);
+      }
+    };
+    float qf[8];
+    auto consume = [&](int item, const u32x4 (&kvv)[UN]) {
+      const int h = wv + 4 * (item / NBATCH), bt = item % NBATCH, it = bt * UN;
+      if (bt == 0) {
+        const u32x4 qv = *(const u32x4*)(a.q + ((size_t)b * H + h) * DK + dc * 8);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          qf[2 * e] = bf16_bits_to_f32(qv[e] & 0xffffu);
+          qf[2 * e + 1] = bf16_bits_to_f32(qv[e] >> 16);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < UN; ++u) {
+        float acc = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          acc += qf[2 * e] * bf16_bits_to_f32(kvv[u][e] & 0xffffu);
+          acc += qf[2 * e + 1] * bf16_bits_to_f32(kvv[u][e] >> 16);
         }
 #pragma unroll
-        for (int u = 0; u < UN; ++u) {
-          float acc = 0.f;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            acc += qf[2 * e] * bf16_bits_to_f32(kvv[u][e] & 0xffffu);
-            acc += qf[2 * e + 1] * bf16_bits_to_f32(kvv[u][e] >> 16);
-          }
-#pragma unroll
-          for (int o = LPK / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-          if (dc == 0) a_s[h * DEC_CK + js + (it + u) * KPW] = acc * a.scale;
-        }
+        for (int o = LPK / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+        if (dc == 0) a_s[h * DEC_CK + js + (it + u) * KPW] = acc * a.scale;
+      }
+    };
+    u32x4 ka[UN], kb2[UN];
+    if (n_items > 0) {
+      issue(0, ka);
+      for (int item = 0; item < n_items; item += 2) {
+        issue(item + 1, kb2);
+        consume(item, ka);
+        issue(item + 2, ka);
+        consume(item + 1, kb2);
       }
     }
   }
@@ -222,40 +246,63 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
 
   // ---- S4: partial O ---------------------------------------------------------------------
   {
+    // The wave's heads and their batches of UN independent 16-byte loads form one sequence of
+    // items; the loads of item i + 1 are issued before item i is consumed (two register sets), so
+    // that a wave keeps loads in flight while it computes.  Keys past the end of the chunk are
+    // clamped to its last key and carry probability 0 (set in S3), so no lane branches on
+    // validity; the item after the last is clamped to the last (a load around a branch would make
+    // the compiler wait for every earlier one).
+    constexpr int NBATCH = DEC_CK / KPW / UN;
+    static_assert(NBATCH % 2 == 0, "items are taken in pairs");
     const int js = lane / LPK, dc = lane % LPK;
-    for (int h = wv; h < H; h += 4) {
+    const int n_items = ((H - wv + 3) / 4) * NBATCH;
+    auto issue = [&](int item, u32x4 (&vv)[UN]) {
+      item = min(item, n_items - 1);
+      const int h = wv + 4 * (item / NBATCH), it = (item % NBATCH) * UN;
       const bf16_t* vb = a.vc + b * a.vs.b + (h / group) * a.vs.h + dc * 8;
+#pragma unroll
+      for (int u = 0; u < UN; ++u) {
+        const int jc = min(js + (it + u) * KPW, n_here - 1);
+        vv[u] = *(const u32x4*)(vb + (size_t)(j0 + jc) * a.vs.j);
+      }
+    };
+    float acc[8];
+    auto consume = [&](int item, const u32x4 (&vv)[UN]) {
+      const int h = wv + 4 * (item / NBATCH), bt = item % NBATCH, it = bt * UN;
       const float* p = a_s + h * DEC_CK;
-      float acc[8];
+      if (bt == 0) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-      // Batches of UN independent 16-byte loads; keys past the end of the chunk are clamped to
-      // its last key and carry probability 0 (set in S3), so no lane branches on validity.
-      for (int it = 0; it < DEC_CK / KPW; it += UN) {
-        u32x4 vv[UN];
-#pragma unroll
-        for (int u = 0; u < UN; ++u) {
-          const int jc = min(js + (it + u) * KPW, n_here - 1);
-          vv[u] = *(const u32x4*)(vb + (size_t)(j0 + jc) * a.vs.j);
-        }
-#pragma unroll
-        for (int u = 0; u < UN; ++u) {
-          const float pj = p[js + (it + u) * KPW];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            acc[2 * e] += pj * bf16_bits_to_f32(vv[u][e] & 0xffffu);
-            acc[2 * e + 1] += pj * bf16_bits_to_f32(vv[u][e] >> 16);
-          }
-        }
+        for (int e = 0; e < 8; ++e) acc[e] = 0.f;
       }
 #pragma unroll
-      for (int e = 0; e < 8; ++e)
+      for (int u = 0; u < UN; ++u) {
+        const float pj = p[js + (it + u) * KPW];
 #pragma unroll
-        for (int o = LPK; o < 64; o <<= 1) acc[e] += __shfl_xor(acc[e], o, 64);
-      if (js == 0) {
-        float* po = a.part_o + (((size_t)b * a.n_chunk + chunk) * H + h) * DK + dc * 8;
-        *(float4*)po = make_float4(acc[0], acc[1], acc[2], acc[3]);
-        *(float4*)(po + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+        for (int e = 0; e < 4; ++e) {
+          acc[2 * e] += pj * bf16_bits_to_f32(vv[u][e] & 0xffffu);
+          acc[2 * e + 1] += pj * bf16_bits_to_f32(vv[u][e] >> 16);
+        }
+      }
+      if (bt == NBATCH - 1) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+#pragma unroll
+          for (int o = LPK; o < 64; o <<= 1) acc[e] += __shfl_xor(acc[e], o, 64);
+        if (js == 0) {
+          float* po = a.part_o + (((size_t)b * a.n_chunk + chunk) * H + h) * DK + dc * 8;
+          *(float4*)po = make_float4(acc[0], acc[1], acc[2], acc[3]);
+          *(float4*)(po + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+        }
+      }
+    };
+    u32x4 va[UN], vb2[UN];
+    if (n_items > 0) {
+      issue(0, va);
+      for (int item = 0; item < n_items; item += 2) {
+        issue(item + 1, vb2);
+        consume(item, va);
+        issue(item + 2, va);
+        consume(item + 1, vb2);
       }
     }
   }
