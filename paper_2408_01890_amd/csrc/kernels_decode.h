@@ -59,6 +59,26 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
   const int group = H / a.Hkv;
   const int n_here = min(DEC_CK, Lk - j0);    // keys of this chunk that exist (>= 1)
 
+  // ---- S4's stream starts here ------------------------------------------------------------
+  // The addresses of the V stream do not depend on the scores: the first batch of every wave is
+  // in flight while S1 - S3 run.
+  constexpr int V_NBATCH = DEC_CK / KPW / UN;
+  static_assert(V_NBATCH % 2 == 0, "items are taken in pairs");
+  const int v_js = lane / LPK, v_dc = lane % LPK;
+  const int v_items = ((H - wv + 3) / 4) * V_NBATCH;
+  auto v_issue = [&](int item, u32x4 (&vv)[UN]) {
+    item = min(item, v_items - 1);
+    const int h = wv + 4 * (item / V_NBATCH), it = (item % V_NBATCH) * UN;
+    const bf16_t* vb = a.vc + b * a.vs.b + (h / group) * a.vs.h + v_dc * 8;
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int jc = min(v_js + (it + u) * KPW, n_here - 1);
+      vv[u] = *(const u32x4*)(vb + (size_t)(j0 + jc) * a.vs.j);
+    }
+  };
+  u32x4 va[UN];
+  if (v_items > 0) v_issue(0, va);
+
   // ---- S1 ------------------------------------------------------------------------------
   if (LISA_MODE) {
     for (int e = tid; e < H * a.r; e += DEC_THREADS)
@@ -252,20 +272,8 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
     // clamped to its last key and carry probability 0 (set in S3), so no lane branches on
     // validity; the item after the last is clamped to the last (a load around a branch would make
     // the compiler wait for every earlier one).
-    constexpr int NBATCH = DEC_CK / KPW / UN;
-    static_assert(NBATCH % 2 == 0, "items are taken in pairs");
-    const int js = lane / LPK, dc = lane % LPK;
-    const int n_items = ((H - wv + 3) / 4) * NBATCH;
-    auto issue = [&](int item, u32x4 (&vv)[UN]) {
-      item = min(item, n_items - 1);
-      const int h = wv + 4 * (item / NBATCH), it = (item % NBATCH) * UN;
-      const bf16_t* vb = a.vc + b * a.vs.b + (h / group) * a.vs.h + dc * 8;
-#pragma unroll
-      for (int u = 0; u < UN; ++u) {
-        const int jc = min(js + (it + u) * KPW, n_here - 1);
-        vv[u] = *(const u32x4*)(vb + (size_t)(j0 + jc) * a.vs.j);
-      }
-    };
+    constexpr int NBATCH = V_NBATCH;
+    const int js = v_js, dc = v_dc, n_items = v_items;
     float acc[8];
     auto consume = [&](int item, const u32x4 (&vv)[UN]) {
       const int h = wv + 4 * (item / NBATCH), bt = item % NBATCH, it = bt * UN;
@@ -295,13 +303,12 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
         }
       }
     };
-    u32x4 va[UN], vb2[UN];
+    u32x4 vb2[UN];
     if (n_items > 0) {
-      issue(0, va);
       for (int item = 0; item < n_items; item += 2) {
-        issue(item + 1, vb2);
+        v_issue(item + 1, vb2);
         consume(item, va);
-        issue(item + 2, va);
+        v_issue(item + 2, va);
         consume(item + 1, vb2);
       }
     }
