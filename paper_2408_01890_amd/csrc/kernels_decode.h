@@ -78,6 +78,22 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
   };
   u32x4 va[UN];
   if (v_items > 0) v_issue(0, va);
+  // ADD form: the A_{n-1} operands of this wave's FFN blocks do not depend on S1 either (clamped
+  // addresses; what lies past the heads or the context is zeroed where it is used)
+  constexpr int XKS = LISA_MODE == 1 ? MfmaFfn<HB, FS, HB, ACT>::KS : 1;
+  constexpr int XNB = DEC_CK / 16 / 4;                     // blocks of 16 positions per wave
+  f16x8 xpre[XNB][XKS];
+  if (LISA_MODE == 1) {
+    const int c = lane & 15, g = lane >> 4;
+#pragma unroll
+    for (int q = 0; q < XNB; ++q)
+#pragma unroll
+      for (int ks = 0; ks < XKS; ++ks)
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          xpre[q][ks][e] = a.prev[((size_t)b * H + min(32 * ks + 8 * g + e, H - 1)) * Lk +
+                                  min(j0 + (wv + 4 * q) * 16 + c, Lk - 1)];
+  }
 
   // ---- S1 ------------------------------------------------------------------------------
   if (LISA_MODE) {
@@ -218,7 +234,9 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
     MfmaFfn<HB, FS, HB, ACT> ffn;
     ffn.fetch(w_s);
     const int c = lane & 15, g = lane >> 4;
-    for (int nb = wv; nb < DEC_CK / 16; nb += 4) {
+#pragma unroll
+    for (int q = 0; q < XNB; ++q) {
+      const int nb = wv + 4 * q;
       const int pj = nb * 16 + c, j = j0 + pj;
       f16x8 x[1][MfmaFfn<HB, FS, HB, ACT>::KS];
 #pragma unroll
@@ -226,7 +244,7 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           const int ch = 32 * ks + 8 * g + e;
-          x[0][ks][e] = (ch < H && j < Lk) ? a.prev[((size_t)b * H + ch) * Lk + j] : (_Float16)0.f;
+          x[0][ks][e] = (ch < H && j < Lk) ? xpre[q][ks][e] : (_Float16)0.f;
         }
       f32x4 y[1][HB];
       ffn.template apply<1>(x, y);
