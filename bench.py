@@ -2,12 +2,15 @@
 """Benchmark of the LiSA attention path on one MI355X.
 
 A step is one LiSA prefill layer (low-rank scores, head-alignment FFN, Integrate, causal
-softmax, P V; scores A_n emitted for the next layer) on the LLaMA2-7B-shaped workload
-(batch 1, 2048 tokens, 32 heads of 128, r = 22, FFN 32->64->32, bf16).  Inputs are synthetic
-and resident in HBM before the timed region.  One JSON line is printed:
+softmax, P V; scores A_n emitted for the next layer) on the largest prefill workload of the
+benchmark definition, the LLaMA3-8B-shaped layer with grouped KV heads (batch 4, 8192 tokens,
+32 query / 8 KV heads of 128, r = 22, FFN 32->64->32, rope theta 500000, bf16).  Inputs are
+synthetic and resident in HBM before the timed region.  One JSON line is printed:
 value = tokens/s of that layer; `roofline` describes the kernel that took most of the time;
 `cpu_baseline` is the float64 oracle timed on this host on a bounded sample of the same
-workload; `extra` holds the standard layer, the read-only mode and the 32-layer decode step.
+workload; `extra` holds the same record for the LLaMA2-7B (L = 2048) and LLaMA2-13B (L = 4096)
+shaped layers, the standard layer, the read-only mode, the projection front end, the variants
+of the alignment module and the 32-layer decode step.
 """
 import argparse
 import json
@@ -54,9 +57,13 @@ def stage_algorithmic(stage, cfg, write_scores, out_bytes=4):
     return 0
 
 
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this workload,
-# scaled by the same counters of a 1 GiB copy (profiles/lisa_prefill_fused_c2_traffic.md).
-MEASURED_TRAFFIC = {"k_lisa_prefill_fused": 389.3e6 + 168.9e6}
+# HBM bytes per launch of the dominant kernel, measured with rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE on `bench.py --only <config>` and scaled by what the same counters read for the
+# 1 GiB copy at the start of that run.  Recorded constants: each names the summary under
+# profiles/ it was taken from (a counter run cannot share a process with the timed run).
+MEASURED_TRAFFIC = {
+    ("c2_llama2_7b_l2048", "k_lisa_prefill_fused"): (389.3e6 + 168.9e6, "profiles/lisa_prefill_fused_c2_traffic.md"),
+}
 
 
 def time_steps(fn, steps, warmup):
@@ -294,54 +301,37 @@ def graph_replay(steps, warmup):
             "steps": steps}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--decode-steps", type=int, default=3)
-    ap.add_argument("--no-decode", action="store_true")
-    ap.add_argument("--decode-only", action="store_true",
-                    help="run only the 32-layer decode step (for profiling) and print its record")
-    ap.add_argument("--no-cpu", action="store_true")
-    ap.add_argument("--no-graph", action="store_true")
-    ap.add_argument("--graph-only", action="store_true",
-                    help="run only the HIP-graph replay of the timed step and print its record")
-    ap.add_argument("--cpu-budget", type=float, default=15.0)
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures one GPU only; run with --gpus 1", file=sys.stderr)
-        sys.exit(2)
+def time_each(fn, steps):
+    """Per-step durations (ms) from events on torch's current stream, which is the stream the
+    binding hands to the library."""
+    import torch
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, b in evs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    return sorted(a.elapsed_time(b) for a, b in evs)
 
+
+def prefill_layer(cfg, seed_idx, steps, warmup, n_sets, cpu_budget, want_cpu):
+    """Times `steps` LiSA prefill layers (A_n emitted) on one configuration and returns
+    (seconds per step, record, buffer sets).  The record carries the roofline of the dominant
+    kernel and the oracle timed on a bounded sample of the same inputs."""
     import torch
     from paper_2408_01890_amd import lisa, synth
-    assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU path)"
-    torch.cuda.set_device(0)
-    if args.graph_only:
-        print(json.dumps(graph_replay(args.steps, args.warmup)), flush=True)
-        return
-    # a plain 1 GiB device-to-device copy: the known-size dispatch that counter profiles of
-    # this command are calibrated against (HBM bytes per FETCH_SIZE / WRITE_SIZE unit)
-    cal = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
-    cal2 = torch.empty_like(cal)
-    cal2.copy_(cal)
-    torch.cuda.synchronize()
-    del cal, cal2
-    if args.decode_only:
-        print(json.dumps(decode_stack(synth.C5, args.decode_steps, 1)), flush=True)
-        return
     dev = "cuda"
-    cfg = synth.C2
-    n_sets = 4                       # rotate buffer sets so that no step finds its scores in cache
     sets = []
-    for s in range(n_sets):
-        inp = synth.make_prefill_inputs(cfg, synth.BASE_SEED + 2 + 100 * s, dev)
+    for s in range(n_sets):       # rotating sets: no step finds its scores in a cache
+        inp = synth.make_prefill_inputs(cfg, synth.BASE_SEED + seed_idx + 100 * s, dev)
         prev, _ = lisa.std_attn_scores(inp["q"], inp["k"])
+        if n_sets == 1:
+            del inp["q"], inp["k"]
         sets.append(dict(inp=inp, prev=prev,
                          out=torch.empty((cfg.B, cfg.L, cfg.H, cfg.d_k), dtype=torch.float32, device=dev),
                          a_n=torch.empty_like(prev)))
     d0 = lisa.make_desc(cfg.torch_dtype, cfg.B, cfg.H, cfg.Hkv, cfg.L, cfg.L, cfg.d_k, cfg.r, cfg.F,
-                        write_scores=0, out_f32=1)
+                        write_scores=1, out_f32=1)
     ws = torch.empty(max(lisa.workspace_bytes(d0, lisa.WS_PREFILL), 256), dtype=torch.uint8, device=dev)
     counter = [0]
 
@@ -359,6 +349,64 @@ def main():
         lisa.lisa_attn_prefill(i["q_lr"], i["k_lr"], i["v"], s["prev"], i["w1"], i["w2"],
                                write_scores=False, out=s["out"], workspace=ws)
 
+    # ---- the timed region: exactly `steps` LiSA layers ------------------------------------
+    lisa.profile_enable(False)
+    sec = time_steps(step_rw, steps, warmup)
+    path = lisa.last_path()
+    each = time_each(step_rw, max(steps, 50))
+    # per-kernel durations with HIP events on the launch stream, over the same kind of steps
+    lisa.profile_enable(True)
+    for _ in range(steps):
+        step_rw()
+    stages = lisa.profile_collect()
+    lisa.profile_enable(False)
+    dom = max(stages, key=lambda k: stages[k][1])
+    dom_ms = stages[dom][1] / stages[dom][0]
+    dom_bytes = stage_algorithmic(dom, cfg, True)
+    pos, layer_bytes, layer_flops = lisa_layer_algorithmic(cfg, True)
+    traffic = MEASURED_TRAFFIC.get((cfg.name, dom))
+    roofline = {
+        "bound": "hbm", "kernel": dom, "achieved": dom_bytes / (dom_ms * 1e-3) / 1e9,
+        "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": dom_bytes / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "traffic": traffic[0] if traffic else None,
+        "traffic_source": traffic[1] if traffic else None,
+        "traffic_over_algorithmic": traffic[0] / dom_bytes if traffic else None,
+        "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms,
+        "mfma_frac_of_bf16_peak": layer_flops / (dom_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+    }
+    sec_ro = time_steps(step_ro, max(steps // 2, 1), 1)
+    rec = {
+        "workload": workload_name(cfg), "tokens_per_s": cfg.B * cfg.L / sec, "ms_per_step": sec * 1e3,
+        "ms_per_step_median": each[len(each) // 2], "ms_per_step_min": each[0], "timed_iterations": len(each),
+        "path": path, "stage_ms_per_step": {k: round(v[1] / steps, 4) for k, v in stages.items()},
+        "roofline": roofline,
+        "layer_algorithmic_GB": layer_bytes / 1e9, "layer_GFLOP": layer_flops / 1e9,
+        "layer_hbm_frac": layer_bytes / sec / 1e9 / HBM_PEAK_GBS,
+        "layer_mfma_frac": layer_flops / sec / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        "lisa_layer_no_score_write_ms": sec_ro * 1e3,
+        "lisa_layer_no_score_write_tokens_per_s": cfg.B * cfg.L / sec_ro,
+    }
+    if want_cpu:
+        rec["cpu_baseline"] = cpu_baseline(cfg, sets[0]["inp"], sets[0]["prev"], cpu_budget)
+    return sec, rec, sets, ws
+
+
+def workload_name(cfg):
+    return (f"{cfg.name}: B{cfg.B} L{cfg.L} d{cfg.d_model} H{cfg.H}/{cfg.Hkv} dk{cfg.d_k} r{cfg.r} "
+            f"FFN {cfg.H}->{cfg.F}->{cfg.H} ReLU, Integrate=add, causal, A_n emitted, fp16 scores, fp32 O")
+
+
+def c2_extras(cfg, sets, ws, steps):
+    """The other measurements on the LLaMA2-7B shape: the standard layer, the projection front
+    end, the NF prefill step and the variants of the alignment module."""
+    import torch
+    from paper_2408_01890_amd import lisa, synth
+    dev = "cuda"
+    n_sets = len(sets)
+    counter = [0]
+    extra = {}
+
     def step_std():
         s = sets[counter[0] % n_sets]
         counter[0] += 1
@@ -374,43 +422,9 @@ def main():
         i = s["inp"]
         lisa.std_attn_scores(i["q"], i["k"], i["v"], scores_out=s["prev"], out=s["out"], workspace=ws_std)
 
-    # ---- the timed region: exactly `steps` LiSA layers ------------------------------------
-    lisa.profile_enable(False)
-    sec = time_steps(step_rw, args.steps, args.warmup)
-    path = lisa.last_path()
-    # per-kernel durations with HIP events on the launch stream, over the same kind of steps
-    lisa.profile_enable(True)
-    for _ in range(args.steps):
-        step_rw()
-    stages = lisa.profile_collect()
-    lisa.profile_enable(False)
-    dom = max(stages, key=lambda k: stages[k][1])
-    dom_ms = stages[dom][1] / stages[dom][0]
-    dom_bytes = stage_algorithmic(dom, cfg, True)
-    pos, layer_bytes, layer_flops = lisa_layer_algorithmic(cfg, True)
-    roofline = {
-        "bound": "hbm", "kernel": dom, "achieved": dom_bytes / (dom_ms * 1e-3) / 1e9,
-        "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": dom_bytes / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "traffic": MEASURED_TRAFFIC.get(dom),
-        "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms,
-    }
-    sec_ro = time_steps(step_ro, max(args.steps // 2, 1), 1)
-    sec_std = time_steps(step_std, max(args.steps // 2, 1), 1)
-    sec_std_full = time_steps(step_std_full, max(args.steps // 2, 1), 1)
-    extra = {
-        "path": path,
-        "stage_ms_per_step": {k: round(v[1] / args.steps, 4) for k, v in stages.items()},
-        "layer_algorithmic_GB": layer_bytes / 1e9, "layer_GFLOP": layer_flops / 1e9,
-        "layer_hbm_frac_if_fused": layer_bytes / sec / 1e9 / HBM_PEAK_GBS,
-        "layer_mfma_frac": layer_flops / sec / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-        "lisa_layer_no_score_write_ms": sec_ro * 1e3,
-        "lisa_layer_no_score_write_tokens_per_s": cfg.B * cfg.L / sec_ro,
-        "std_scores_layer_ms": sec_std * 1e3,
-        "std_layer_scores_and_output_ms": sec_std_full * 1e3,
-        "paper_context": "end-to-end generation throughput gains on one A800-80GB: +19.5% LLaMA3-8B, "
-                         "+32.3% LLaMA2-7B, +40.1% LLaMA2-13B (not this metric)",
-    }
+    # (the standard layer overwrites `prev` with the same values: the sets stay valid)
+    extra["std_scores_layer_ms"] = time_steps(step_std, max(steps // 2, 1), 1) * 1e3
+    extra["std_layer_scores_and_output_ms"] = time_steps(step_std_full, max(steps // 2, 1), 1) * 1e3
     # the projection front end (hidden states -> rotated Q_LR, K_LR and V) and the layer behind it
     pin = synth.make_projection_inputs(cfg, device=dev)
     theta = cfg.rope_theta if cfg.rope_theta is not None else 10000.0
@@ -428,9 +442,9 @@ def main():
         lisa.lisa_attn_prefill(pq, pk, pv, s["prev"], i["w1"], i["w2"], write_scores=True, out=s["out"],
                                scores_out=s["a_n"], workspace=ws)
 
-    sec_proj = time_steps(step_proj, max(args.steps // 2, 1), 2)
+    sec_proj = time_steps(step_proj, max(steps // 2, 1), 2)
     proj_path = lisa.last_path()
-    sec_proj_layer = time_steps(step_proj_layer, max(args.steps // 2, 1), 2)
+    sec_proj_layer = time_steps(step_proj_layer, max(steps // 2, 1), 2)
     proj_flops = 2.0 * cfg.B * cfg.L * cfg.d_model * ((cfg.H + cfg.Hkv) * cfg.r + cfg.Hkv * cfg.d_k)
     extra["projection"] = {
         "path": proj_path, "ms": sec_proj * 1e3, "GFLOP": proj_flops / 1e9,
@@ -456,7 +470,7 @@ def main():
         lisa.lisa_project_qkv(dpin["x"], dpin["w"], dstk.H, dstk.Hkv, dstk.r, dstk.d_k, rope_theta=theta,
                               pos0=dstk.ctx, q_lr=dq, k_lr=dk_cache, v=dv_cache, dim_major=True)
 
-    sec_pd = time_steps(step_proj_decode, max(args.steps, 1), 2)
+    sec_pd = time_steps(step_proj_decode, max(steps, 1), 2)
     wbytes = dpin["w"].numel() * 2
     extra["projection"]["decode_step_B64"] = {
         "path": lisa.last_path(), "us": sec_pd * 1e6, "weight_MB": wbytes / 1e6,
@@ -472,7 +486,7 @@ def main():
         i = s["inp"]
         lisa.std_attn_scores(i["q"], i["k"], i["v"], want_scores=False, out=s["out"], workspace=ws_std)
 
-    extra["nf_prefill_standard_attention_no_scores_ms"] = time_steps(step_nf, max(args.steps // 2, 1), 1) * 1e3
+    extra["nf_prefill_standard_attention_no_scores_ms"] = time_steps(step_nf, max(steps // 2, 1), 1) * 1e3
 
     # variants of the alignment module (Sec. 5.7 ablation, Sec. 5.5, Sec. 4) and the paper's default
     # CONCAT form at its own widths (Sec. 5.3: FFN 2h -> 256 -> h, r = 20)
@@ -512,28 +526,94 @@ def main():
                           "stage_ms": {k: round(v[1] / v[0], 4) for k, v in st_v.items()}}
         del ws_var
     extra["alignment_variants"] = variants
-    del pin, slin
-    cpu = None
-    if not args.no_cpu:
-        cpu = cpu_baseline(cfg, sets[0]["inp"], sets[0]["prev"], args.cpu_budget)
-    del sets
+    return extra
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--decode-steps", type=int, default=3)
+    ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--decode-only", action="store_true",
+                    help="run only the 32-layer decode step (for profiling) and print its record")
+    ap.add_argument("--only", choices=["c2", "c3", "c4"], default=None,
+                    help="run only the timed LiSA prefill layers of one configuration (for profiling) "
+                         "and print its record")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--graph-only", action="store_true",
+                    help="run only the HIP-graph replay of the timed step and print its record")
+    ap.add_argument("--cpu-budget", type=float, default=15.0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2408_01890_amd import lisa, synth
+    assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU path)"
+    torch.cuda.set_device(0)
+    if args.graph_only:
+        print(json.dumps(graph_replay(args.steps, args.warmup)), flush=True)
+        return
+    # a plain 1 GiB device-to-device copy: the known-size dispatch that counter profiles of
+    # this command are calibrated against (HBM bytes per FETCH_SIZE / WRITE_SIZE unit)
+    cal = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    cal2 = torch.empty_like(cal)
+    cal2.copy_(cal)
+    torch.cuda.synchronize()
+    del cal, cal2
+    if args.decode_only:
+        print(json.dumps(decode_stack(synth.C5, args.decode_steps, 1)), flush=True)
+        return
+    # (configuration, seed index, rotating buffer sets): the score tensors of the two large
+    # configurations (17 and 11 GB) cannot stay in any cache, one set is enough there
+    plans = {"c2": (synth.C2, 2, 4), "c3": (synth.C3, 3, 1), "c4": (synth.C4, 4, 1)}
+    if args.only:
+        cfg, idx, n_sets = plans[args.only]
+        _, rec, _, _ = prefill_layer(cfg, idx, args.steps, args.warmup, n_sets, args.cpu_budget, False)
+        print(json.dumps(rec), flush=True)
+        return
+
+    # ---- headline: the largest prefill configuration that fits one GPU -------------------------
+    cfg, idx, n_sets = plans["c3"]
+    sec, head, sets, ws = prefill_layer(cfg, idx, args.steps, args.warmup, n_sets, args.cpu_budget,
+                                        not args.no_cpu)
+    del sets, ws
+    torch.cuda.empty_cache()
+    extra = {k: head[k] for k in head if k not in ("roofline", "cpu_baseline", "workload", "tokens_per_s",
+                                                   "ms_per_step")}
+    extra["paper_context"] = ("end-to-end generation throughput gains on one A800-80GB: +19.5% LLaMA3-8B, "
+                              "+32.3% LLaMA2-7B, +40.1% LLaMA2-13B (not this metric)")
+    # ---- the other two bf16 prefill configurations, each with its own roofline and baseline -----
+    small_steps = max(args.steps, 1)
+    c4cfg, c4idx, c4sets = plans["c4"]
+    _, extra["c4"], sets, ws = prefill_layer(c4cfg, c4idx, small_steps, args.warmup, c4sets,
+                                             min(args.cpu_budget, 6.0), not args.no_cpu)
+    del sets, ws
+    torch.cuda.empty_cache()
+    c2cfg, c2idx, c2sets = plans["c2"]
+    _, extra["c2"], sets, ws = prefill_layer(c2cfg, c2idx, small_steps, args.warmup, c2sets,
+                                             min(args.cpu_budget, 6.0), not args.no_cpu)
+    extra["c2"].update(c2_extras(c2cfg, sets, ws, small_steps))
+    del sets, ws
     torch.cuda.empty_cache()
     if not args.no_decode:
         extra["decode"] = decode_stack(synth.C5, args.decode_steps, 1)
     if not args.no_graph:
         try:
-            extra["hip_graph_replay"] = graph_replay(args.steps, args.warmup)
+            extra["c2"]["hip_graph_replay"] = graph_replay(args.steps, args.warmup)
         except Exception as e:                               # noqa: BLE001 (reported, not fatal)
-            extra["hip_graph_replay"] = {"error": repr(e)[:200]}
+            extra["c2"]["hip_graph_replay"] = {"error": repr(e)[:200]}
     line = {
         "metric": "LiSA-layer prefill tokens/s", "value": cfg.B * cfg.L / sec, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: B{cfg.B} L{cfg.L} d{cfg.d_model} H{cfg.H} dk{cfg.d_k} "
-                               f"r{cfg.r} FFN {cfg.H}->{cfg.F}->{cfg.H} ReLU, Integrate=add, causal, "
-                               f"A_n emitted, fp16 scores, fp32 O"},
-        "roofline": roofline, "cpu_baseline": cpu, "extra": extra,
+        "config": {"workload": workload_name(cfg)},
+        "roofline": head["roofline"], "cpu_baseline": head.get("cpu_baseline"), "extra": extra,
     }
     print(json.dumps(line), flush=True)
 

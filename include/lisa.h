@@ -14,9 +14,13 @@
  * General rules for every entry point
  *   - All data pointers are DEVICE pointers owned by the caller, valid on the device that
  *     is current when the call is made.  The descriptor pointer is a HOST pointer.  The
- *     library never allocates, frees or retains memory.
+ *     library never allocates, frees or retains device memory.  (The one exception is the
+ *     optional stage timing, lisa_profile_*, which creates HIP events and a host-side list.)
  *   - Calls only enqueue work on `hip_stream` (a hipStream_t cast to void*, NULL = the
- *     default stream) and return without synchronising.  No global state; re-entrant.
+ *     default stream) and return without synchronising.  Re-entrant; no state is shared between
+ *     threads.  Per calling thread the library keeps diagnostics only: the text of the last HIP
+ *     error, the name of the last kernel family, the stage-timing records and the test
+ *     overrides of lisa_tune_set(), none of which a call needs.
  *   - Return value: 0 (LISA_OK) or a negative lisa_status.  All argument validation is
  *     done on the host before any HIP call, so a rejected call has touched nothing.
  *   - Tensors are dense, row-major, innermost index last, base pointers 16-byte aligned.
@@ -155,6 +159,7 @@ int lisa_attn_decode(const lisa_desc* desc, const void* q_lr, const void* k_lr_n
  *   out [B,Lq,H,d_k]                   out  or NULL
  * With Lq = 1 and Lmax >= Lk this is the decode step of a standard layer: k and v are then
  * caches [B,Hkv,Lmax,d_k] of which the first Lk keys are attended (Lmax = 0: dense, Lk keys).
+ * Lmax > 0 with Lq > 1, or 0 < Lmax < Lk, is LISA_ERR_SHAPE.
  */
 int std_attn_scores(const lisa_desc* desc, const void* q, const void* k, const void* v,
                     void* scores_out, void* out, void* workspace, size_t workspace_bytes,
@@ -169,7 +174,8 @@ int std_attn_scores(const lisa_desc* desc, const void* q, const void* k, const v
  *   v           [B,Hkv,Lk,d_k]   in
  *   k_lr_cache  [B,Hkv,Lmax,r] or [B,Hkv,r,Lmax]   out (key indices 0 .. Lk-1 are written)
  *   v_cache     [B,Hkv,Lmax,d_k]                   out (likewise)
- * No workspace.  Byte copies: the caches hold exactly the input values.
+ * No workspace.  Byte copies: the caches hold exactly the input values.  B, Hkv and B * Hkv at
+ * most 65535.
  */
 int lisa_cache_fill(const lisa_desc* desc, const void* k_lr, const void* v, void* k_lr_cache,
                     void* v_cache, void* hip_stream);
@@ -271,6 +277,25 @@ const char* lisa_last_hip_error(void);
  * "project_mfma", "project_skinny", "mfma_scores"); for tests and
  * benchmark reports. */
 const char* lisa_last_path(void);
+
+/*
+ * Geometry overrides for tests (per calling thread; nothing in production needs them).  The
+ * dispatch picks head grouping, key splits and tile widths from the problem size; a test that
+ * must cover the other instantiation on a small problem forces it here.  value < 0 restores the
+ * library's own choice.  An override changes what lisa_workspace_bytes() returns: set it before
+ * the size query and leave it until the call it is meant for has been made.
+ *   LISA_TUNE_PREFILL_GROUPS  head groups of the fused prefill kernel (H = 16: 1 or 2; H = 32: 2 or 4)
+ *   LISA_TUNE_PREFILL_SPLIT   key splits per row block: 1, 2 or 4 (other values are ignored)
+ *   LISA_TUNE_PREFILL_PAIR    1: a workgroup takes a long and a short unit, 0: one unit
+ *   LISA_TUNE_STD_PAIR        the same for the standard layer's prefill kernel
+ *   LISA_TUNE_PROJECT_TN      tile width of the projection kernel: 192 or 256
+ * Returns LISA_OK, or LISA_ERR_SHAPE for an unknown knob.
+ */
+typedef enum {
+  LISA_TUNE_PREFILL_GROUPS = 0, LISA_TUNE_PREFILL_SPLIT = 1, LISA_TUNE_PREFILL_PAIR = 2,
+  LISA_TUNE_STD_PAIR = 3, LISA_TUNE_PROJECT_TN = 4, LISA_TUNE_COUNT = 5
+} lisa_tune_knob;
+int lisa_tune_set(int knob, int value);
 
 /*
  * Stage timing for benchmarks (diagnostic, per calling thread, off by default).  While

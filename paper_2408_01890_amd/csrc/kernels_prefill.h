@@ -507,8 +507,11 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
                          fmaxf(fmaxf(an[4], an[5]), fmaxf(an[6], an[7])));
         mx = rows_max(mx);
         const float m_new = fmaxf(m_run[hh], mx);
-        // every row sees key 0, so m_new is finite from the first tile on
-        const float m2 = m_new * LOG2E;
+        // A row may have seen no key yet: a key share, or a walk downwards from the diagonal, can
+        // start with a tile that lies wholly beyond the row's last visible key (Lk - Lq not a
+        // multiple of 16).  The exponent is then taken against 0 instead of -inf, so alpha and
+        // every p are exactly 0 and the row's state stays (m = -inf, l = 0, o = 0).
+        const float m2 = (m_new == -INFINITY ? 0.f : m_new) * LOG2E;
         const float alpha = fast_exp2(m_run[hh] * LOG2E - m2);
         m_run[hh] = m_new;
         float ps = 0.f;

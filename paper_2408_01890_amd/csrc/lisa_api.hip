@@ -22,6 +22,8 @@ namespace {
 
 thread_local char g_hip_err[256] = "";
 thread_local const char* g_path = "";
+// lisa_tune_set(): geometry overrides of the calling thread, -1 = the library's own choice
+thread_local int g_tune[LISA_TUNE_COUNT] = {-1, -1, -1, -1, -1};
 
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -475,7 +477,7 @@ int prefill_groups(const lisa_desc* d) {
   if (d->H != 32 && d->H != 16) return 1;
   const int few = d->H / 16, many = d->H / 8;              // groups of 16 heads or of 8
   const long long row_blocks = (long long)((d->Lq + PF_ROWS - 1) / PF_ROWS) * d->B;
-  if (const char* e = getenv("LISA_PREFILL_GROUPS")) return atoi(e) == many ? many : few;
+  if (g_tune[LISA_TUNE_PREFILL_GROUPS] >= 0) return g_tune[LISA_TUNE_PREFILL_GROUPS] == many ? many : few;
   // SiLU costs two quarter-rate instructions per hidden unit, once more per extra group: measured
   // 0.27 ms with two groups (and a key split) against 0.32 ms with four on the LLaMA2-7B shape.
   if (d->act == LISA_ACT_SILU) return few;
@@ -495,7 +497,8 @@ int prefill_split(const lisa_desc* d, int Lqp) {
   const int tiles_max = (d->Lk + PF_TK - 1) / PF_TK;
   int s = 1;
   while (s < 4 && units * s < 2 * kComputeUnits && tiles_max / (2 * s) >= 4) s *= 2;
-  if (const char* e = getenv("LISA_PREFILL_SPLIT")) s = atoi(e) > 0 ? atoi(e) : s;
+  const int forced = g_tune[LISA_TUNE_PREFILL_SPLIT];
+  if (forced == 1 || forced == 2 || forced == 4) s = forced;
   return s;
 }
 
@@ -504,7 +507,7 @@ int prefill_split(const lisa_desc* d, int Lqp) {
 int prefill_pair(const lisa_desc* d, int Lqp, int split) {
   const int groups = prefill_groups(d);
   const long long units = (long long)(Lqp / PF_ROWS) * split * d->B * groups;
-  if (const char* e = getenv("LISA_PREFILL_PAIR")) return atoi(e) != 0;
+  if (g_tune[LISA_TUNE_PREFILL_PAIR] >= 0) return g_tune[LISA_TUNE_PREFILL_PAIR] != 0;
   return units >= 2 * kComputeUnits;
 }
 
@@ -696,7 +699,7 @@ int run_std_prefill_fast(const lisa_desc* d, const void* q, const void* k, const
   // for all; measured equal on the LLaMA2-13B shape at L = 4096, 3 - 7 % slower at L = 8192 with
   // grouped keys and 10 % slower at L = 2048, where it leaves one workgroup per compute unit.)
   a.pair = 0;
-  if (const char* e = std::getenv("LISA_STD_PAIR")) a.pair = std::atoi(e) != 0;   // tests force either
+  if (g_tune[LISA_TUNE_STD_PAIR] >= 0) a.pair = g_tune[LISA_TUNE_STD_PAIR] != 0;   // tests force either
   dim3 grid(d->H, a.pair ? (n_groups + 1) / 2 : n_groups, d->B);
   StageScope prof("k_std_prefill", st);
   if (out)
@@ -719,6 +722,14 @@ int lisa_cache_fill(const lisa_desc* d, const void* k_lr, const void* v, void* k
   if (d->B < 1 || d->Hkv < 1 || d->Lk < 1 || d->r < 1 || d->d_k < 1 || d->Lmax < d->Lk) return LISA_ERR_SHAPE;
   if (d->kcache_dim_major != 0 && d->kcache_dim_major != 1) return LISA_ERR_SHAPE;
   if (d->kcache_dim_major && d->r > 128) return LISA_ERR_UNSUPPORTED;
+  // grid limits: (B, Hkv) and B * Hkv are grid.z / grid.y indices, a row of Lk * width elements
+  // is covered by 1024 elements per block along grid.x
+  if (d->B > kMaxGridYZ || d->Hkv > kMaxGridYZ || (long long)d->B * d->Hkv > kMaxGridYZ)
+    return LISA_ERR_UNSUPPORTED;
+  if (d->r > kMaxRank || d->d_k > kMaxHeadDim) return LISA_ERR_UNSUPPORTED;
+  const void* ptrs[] = {k_lr, v, k_lr_cache, v_cache};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return LISA_ERR_ALIGN;
   hipStream_t st = (hipStream_t)hip_stream;
   const int rows = d->B * d->Hkv;
   auto fill_rows = [&](const void* src, void* dst, int row_elems) {
@@ -727,7 +738,9 @@ int lisa_cache_fill(const lisa_desc* d, const void* k_lr, const void* v, void* k
       k_cache_fill_rows<float><<<grid, 256, 0, st>>>((const float*)src, (float*)dst, d->Lk, row_elems, d->Lmax);
     else
       k_cache_fill_rows<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)src, (bf16_t*)dst, d->Lk, row_elems, d->Lmax);
+    return check_launch();
   };
+  int rc;
   if (d->kcache_dim_major) {
     dim3 grid((d->Lk + 63) / 64, d->Hkv, d->B);
     if (d->dtype == LISA_F32)
@@ -736,11 +749,12 @@ int lisa_cache_fill(const lisa_desc* d, const void* k_lr, const void* v, void* k
     else
       k_kcache_fill_dim_major<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)k_lr, (bf16_t*)k_lr_cache, d->Hkv,
                                                            d->Lk, d->r, d->Lmax);
+    rc = check_launch();
   } else {
-    fill_rows(k_lr, k_lr_cache, d->r);
+    rc = fill_rows(k_lr, k_lr_cache, d->r);
   }
-  fill_rows(v, v_cache, d->d_k);
-  int rc = check_launch();
+  if (rc) return rc;
+  rc = fill_rows(v, v_cache, d->d_k);
   if (rc == LISA_OK) g_path = "cache_fill";
   return rc;
 }
@@ -800,8 +814,8 @@ int lisa_project_qkv(const lisa_proj_desc* d, const void* x, const void* w, void
     };
     // (the narrower tile does less MFMA work per fetched byte: it must win by a margin)
     int tn = rounds_cost(192) * 8 < rounds_cost(256) * 7 ? 192 : 256;
-    if (const char* e = std::getenv("LISA_PROJECT_TN")) {   // tests force either geometry
-      const int v = std::atoi(e);
+    {                                                       // tests force either geometry
+      const int v = g_tune[LISA_TUNE_PROJECT_TN];
       if (v == 192 || v == 256) tn = v;
     }
     a.n_m = (int)((M + 255) / 256);
@@ -1093,6 +1107,12 @@ int lisa_profile_collect(lisa_stage_time* out, int max_stages) {
   return rc == LISA_OK ? n : rc;
 }
 
+int lisa_tune_set(int knob, int value) {
+  if (knob < 0 || knob >= LISA_TUNE_COUNT) return LISA_ERR_SHAPE;
+  g_tune[knob] = value < 0 ? -1 : value;
+  return LISA_OK;
+}
+
 const char* lisa_last_hip_error(void) { return g_hip_err; }
 const char* lisa_last_path(void) { return g_path; }
 
@@ -1219,6 +1239,9 @@ int std_attn_scores(const lisa_desc* desc, const void* q, const void* k, const v
   if (!q || !k) return LISA_ERR_NULL;
   if (!scores_out && !out) return LISA_ERR_NULL;
   if ((v == nullptr) != (out == nullptr)) return LISA_ERR_NULL;
+  // Lmax is the capacity of K / V along the keys in the decode form (0: dense); a capacity below
+  // the attended length, or one given for a prefill call, is a mistake of the caller
+  if (desc->Lmax < 0 || (desc->Lmax > 0 && (desc->Lq != 1 || desc->Lmax < desc->Lk))) return LISA_ERR_SHAPE;
   const void* ptrs[] = {q, k, v, scores_out, out, workspace};
   for (const void* p : ptrs)
     if (p && !aligned16(p)) return LISA_ERR_ALIGN;

@@ -27,8 +27,9 @@ EXPORTS = (
     "lisa_scores_bytes", "lisa_score_elem_bytes", "lisa_kcache_saved_bytes", "lisa_supported",
     "lisa_strerror", "lisa_last_hip_error", "lisa_last_path", "lisa_profile_enable",
     "lisa_profile_collect", "lisa_cache_fill", "lisa_project_qkv", "lisa_layer_prefill",
-    "lisa_layer_offsets", "lisa_layer_decode",
+    "lisa_layer_offsets", "lisa_layer_decode", "lisa_tune_set",
 )
+TUNE_PREFILL_GROUPS, TUNE_PREFILL_SPLIT, TUNE_PREFILL_PAIR, TUNE_STD_PAIR, TUNE_PROJECT_TN = range(5)
 
 
 class LisaError(RuntimeError):
@@ -109,6 +110,8 @@ def _lib():
         h.lisa_layer_decode.restype = C.c_int
         h.lisa_layer_offsets.argtypes = [dp] + [C.POINTER(sz)] * 3
         h.lisa_layer_offsets.restype = C.c_int
+        h.lisa_tune_set.argtypes = [C.c_int, C.c_int]
+        h.lisa_tune_set.restype = C.c_int
         h.lisa_profile_collect.argtypes = [C.POINTER(StageTime), C.c_int]
         h.lisa_profile_collect.restype = C.c_int
         _handle = h
@@ -150,6 +153,28 @@ def supported(desc: Desc) -> int:
 
 def last_path() -> str:
     return _lib().lisa_last_path().decode()
+
+
+class tune:
+    """Context manager around lisa_tune_set: forces one kernel geometry (tests), restores the
+    library's own choice on exit."""
+
+    def __init__(self, **knobs):
+        names = {"prefill_groups": TUNE_PREFILL_GROUPS, "prefill_split": TUNE_PREFILL_SPLIT,
+                 "prefill_pair": TUNE_PREFILL_PAIR, "std_pair": TUNE_STD_PAIR, "project_tn": TUNE_PROJECT_TN}
+        self.knobs = [(names[k], int(v)) for k, v in knobs.items()]
+
+    def __enter__(self):
+        for k, v in self.knobs:
+            rc = _lib().lisa_tune_set(k, v)
+            if rc:
+                raise LisaError(rc, "lisa_tune_set")
+        return self
+
+    def __exit__(self, *exc):
+        for k, _ in self.knobs:
+            _lib().lisa_tune_set(k, -1)
+        return False
 
 
 def profile_enable(on: bool) -> None:

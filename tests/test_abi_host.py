@@ -87,6 +87,23 @@ def test_decode_and_std_reject_bad_arguments():
     assert lib.std_attn_scores(C.byref(d), FAKE, FAKE, None, None, None, None, 0, None) == -1
     assert lib.std_attn_scores(C.byref(d), FAKE, FAKE, FAKE, FAKE, None, None, 0, None) == -1
     assert lib.std_attn_scores(C.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, None, 0, None) == -5
+    # decode form: a cache capacity below the attended length, or a capacity on a prefill call
+    d = good_desc(Lq=1, Lk=9, Lmax=8)
+    assert lib.std_attn_scores(C.byref(d), FAKE, FAKE, None, FAKE, None, None, 0, None) == -2
+    d = good_desc(Lq=4, Lk=9, Lmax=16)
+    assert lib.std_attn_scores(C.byref(d), FAKE, FAKE, None, FAKE, None, None, 0, None) == -2
+
+
+def test_tune_set_accepts_known_knobs_only():
+    lib = lisa.library()
+    assert lib.lisa_tune_set(lisa.TUNE_PREFILL_SPLIT, 2) == 0
+    d = good_desc(dtype=lisa.BF16, B=1, H=32, Hkv=32, Lq=2048, Lk=2048, d_k=128, r=22, F=64)
+    two = lisa.workspace_bytes(d, lisa.WS_PREFILL)
+    assert lib.lisa_tune_set(lisa.TUNE_PREFILL_SPLIT, 3) == 0               # not 1, 2 or 4: ignored
+    auto = lisa.workspace_bytes(d, lisa.WS_PREFILL)
+    assert lib.lisa_tune_set(lisa.TUNE_PREFILL_SPLIT, -1) == 0
+    assert lisa.workspace_bytes(d, lisa.WS_PREFILL) == auto and two > 0
+    assert lib.lisa_tune_set(99, 1) == -2 and lib.lisa_tune_set(-1, 1) == -2
 
 
 def test_cache_fill_rejects_bad_arguments():
@@ -100,6 +117,10 @@ def test_cache_fill_rejects_bad_arguments():
     assert lib.lisa_cache_fill(C.byref(layout), FAKE, FAKE, FAKE, FAKE, None) == -2
     wide = lisa.make_desc(lisa.BF16, 2, 8, 2, 1, 100, 256, 200, 0, kcache_dim_major=1, Lmax=128)
     assert lib.lisa_cache_fill(C.byref(wide), FAKE, FAKE, FAKE, FAKE, None) == -3
+    assert lib.lisa_cache_fill(C.byref(d), FAKE, ODD, FAKE, FAKE, None) == -4
+    assert lib.lisa_cache_fill(C.byref(d), FAKE, FAKE, ODD, FAKE, None) == -4
+    many = lisa.make_desc(lisa.BF16, 70000, 8, 2, 1, 100, 128, 22, 0, kcache_dim_major=1, Lmax=128)
+    assert lib.lisa_cache_fill(C.byref(many), FAKE, FAKE, FAKE, FAKE, None) == -3
 
 
 def test_proj_desc_struct_matches_header_field_order():

@@ -18,19 +18,38 @@ def log(*a):
     print(*a, flush=True)
 
 
+@pytest.fixture
+def tuned():
+    """Forces kernel geometries through lisa_tune_set for one test; restored afterwards."""
+    import contextlib
+    with contextlib.ExitStack() as stack:
+        yield lambda **knobs: stack.enter_context(lisa.tune(**knobs))
+
+
 def check_prefill(cfg, inp, prev, out, scores, rows_by_b, mix=0, causal=True, tag=""):
     tol = hp.TOL[cfg.torch_dtype]
     worst_o = worst_a = 0.0
     Lq, Lk = inp["q_lr"].shape[2], inp["k_lr"].shape[2]
+    # the other reading of the tolerance, one RMS over all compared rows: logged, not asserted
+    o_max = o_sq = o_n = a_max = a_sq = a_n = 0.0
     for b, rows in rows_by_b.items():
         prev_rows = hp.gather_score_rows(prev, b, rows)
         a_ref, o_ref = hp.oracle_lisa_rows(inp, b, rows, prev_rows, mix=mix)
-        worst_o = max(worst_o, hp.row_rel_err(hp.gather_out_rows(out, b, rows), o_ref))
+        o_got = hp.gather_out_rows(out, b, rows)
+        worst_o = max(worst_o, hp.row_rel_err(o_got, o_ref))
+        o_max, o_sq, o_n = max(o_max, float(np.abs(o_got - o_ref).max())), o_sq + float((o_ref ** 2).sum()), o_n + o_ref.size
         if scores is not None:
-            worst_a = max(worst_a, hp.scores_row_rel_err(hp.gather_score_rows(scores, b, rows), a_ref,
-                                                         rows, Lq, Lk, causal))
+            a_got = hp.gather_score_rows(scores, b, rows)
+            worst_a = max(worst_a, hp.scores_row_rel_err(a_got, a_ref, rows, Lq, Lk, causal))
+            for n, i in enumerate(rows):
+                nv = hp.n_visible(int(i), Lq, Lk, causal)
+                a_max = max(a_max, float(np.abs(a_got[n, :, :nv] - a_ref[n, :, :nv]).max()))
+                a_sq, a_n = a_sq + float((a_ref[n, :, :nv] ** 2).sum()), a_n + a_ref[n, :, :nv].size
+    glob_o = o_max / np.sqrt(o_sq / o_n)
+    glob_a = a_max / np.sqrt(a_sq / a_n) if a_n else 0.0
     log(f"[parity] {cfg.name}{tag}: path={lisa.last_path()} err_out={worst_o:.3e} "
-        f"err_scores={worst_a:.3e} tol={tol:g}")
+        f"err_scores={worst_a:.3e} tol={tol:g} (per query row, asserted); one RMS over all compared "
+        f"rows: err_out={glob_o:.3e} err_scores={glob_a:.3e} (logged only)")
     assert worst_o <= tol, f"O error {worst_o} > {tol}"
     assert worst_a <= tol, f"A_n error {worst_a} > {tol}"
 
@@ -93,13 +112,13 @@ STD_MFMA_SHAPES = [
 
 @pytest.mark.parametrize("pair", [1, 0])
 @pytest.mark.parametrize("case", STD_MFMA_SHAPES, ids=[c[0] for c in STD_MFMA_SHAPES])
-def test_std_prefill_mfma_kernel_shapes(case, pair, monkeypatch):
+def test_std_prefill_mfma_kernel_shapes(case, pair, tuned):
     """The bf16 standard layer on the matrix cores (d_k = 128): scores and output against the
     oracle in its three call modes, invisible score entries left untouched; with one and with
     two row groups per workgroup."""
     from oracle import cref
     name, B, H, Hkv, Lq, Lk, causal = case
-    monkeypatch.setenv("LISA_STD_PAIR", str(pair))
+    tuned(std_pair=pair)
     log(f"[case] std mfma {name} pair={pair}")
     dt = torch.bfloat16
     g = torch.Generator(device=DEV).manual_seed(23)
@@ -286,7 +305,15 @@ def test_bf16_output_option_differs_only_by_the_final_rounding():
     assert torch.equal(o32.to(torch.bfloat16), o16)          # same accumulators, one rounding
     rows = np.arange(cfg.L)
     _, o_ref = hp.oracle_lisa_rows(inp, 0, rows, hp.gather_score_rows(prev, 0, rows))
-    assert hp.row_rel_err_stored_bf16(hp.gather_out_rows(o16, 0, rows), o_ref) <= hp.TOL[torch.bfloat16]
+    # the float32 output meets the tolerance as it stands; the bfloat16 one is that result rounded
+    # once, so every stored element is the oracle's value rounded to bfloat16 or its neighbour
+    assert hp.row_rel_err(hp.gather_out_rows(o32, 0, rows), o_ref) <= hp.TOL[torch.bfloat16]
+    assert hp.bf16_ulps_off(hp.gather_out_rows(o16, 0, rows), o_ref) <= 1.0
+    # Rounding the oracle's own float64 output to bfloat16 already moves the worst row of this
+    # problem by 2.05e-2 of its RMS (a head with one dominant key keeps |O| ~ |V| while the row's
+    # RMS is set by the heads that average many keys), so the plain figure is logged, not asserted.
+    log(f"[parity] bf16out: stored-bf16 O err_out={hp.row_rel_err(hp.gather_out_rows(o16, 0, rows), o_ref):.3e} "
+        f"(plain metric, logged only; float32 O is the graded output)")
 
 
 def test_lisa_prefill_chunked_rows_match_full_prefill():
@@ -307,9 +334,9 @@ def test_lisa_prefill_chunked_rows_match_full_prefill():
 
 
 @pytest.mark.parametrize("groups", ["1", "2"])
-def test_lisa_prefill_h16_both_head_groupings(groups, monkeypatch):
+def test_lisa_prefill_h16_both_head_groupings(groups, tuned):
     """H = 16: one group of 16 heads or two groups of 8, on the same ragged problem."""
-    monkeypatch.setenv("LISA_PREFILL_GROUPS", groups)
+    tuned(prefill_groups=int(groups))
     cfg = synth.LayerShape("h16_groups", "bf16", 2, 16, 4, 200, 2048, 128, 22, 32)
     inp = synth.make_prefill_inputs(cfg, 52, DEV, ffn="identity_noise")
     prev = std_prev(inp)
@@ -322,10 +349,10 @@ def test_lisa_prefill_h16_both_head_groupings(groups, monkeypatch):
 
 
 @pytest.mark.parametrize("groups", ["2", "4"])
-def test_lisa_prefill_h32_both_head_groupings(groups, monkeypatch):
+def test_lisa_prefill_h32_both_head_groupings(groups, tuned):
     """H = 32 runs as two groups of 16 heads on large problems and as four groups of 8 on small
     ones; both instantiations on the same ragged problem (key splits and the combine included)."""
-    monkeypatch.setenv("LISA_PREFILL_GROUPS", groups)
+    tuned(prefill_groups=int(groups))
     cfg = synth.LayerShape("h32_groups", "bf16", 1, 32, 8, 328, 4096, 128, 22, 64)
     inp = synth.make_prefill_inputs(cfg, 51, DEV, ffn="identity_noise")
     prev = std_prev(inp)
@@ -372,6 +399,28 @@ def test_lisa_prefill_fused_chunked_rows_match_full_prefill():
     assert hp.row_rel_err(hp.f64(out_t[0]), o_ref) <= tol
     got = hp.f64(scores_t[0]).transpose(1, 0, 2)
     assert hp.scores_row_rel_err(got, a_ref, rows, cfg.L, cfg.L) <= tol
+
+
+@pytest.mark.parametrize("mode", [dict(prefill_pair=1, prefill_split=1), dict(prefill_pair=0, prefill_split=2),
+                                  dict(prefill_pair=0, prefill_split=4), dict(prefill_pair=1, prefill_split=2)],
+                         ids=["pair", "split2", "split4", "pair_split2"])
+@pytest.mark.parametrize("shift", [8, 24])
+@pytest.mark.parametrize("H,Hkv,Lk", [(8, 4, 256), (32, 8, 544)])
+def test_lisa_prefill_fused_chunked_rows_unaligned_shift(H, Hkv, Lk, shift, mode, tuned):
+    """Chunked prefill (Lq < Lk, Sec. 2.2) whose offset Lk - Lq is not a multiple of the row
+    block: a key share, or the downward walk of a paired unit, then starts with a tile in which
+    the first rows of the block see no key at all.  Every row is compared."""
+    tuned(**mode)
+    Lq = Lk - shift
+    cfg = synth.LayerShape(f"unaligned_H{H}_Lk{Lk}_shift{shift}", "bf16", 1, H, Hkv, Lk, 1024, 128, 22, 2 * H)
+    inp = synth.make_prefill_inputs(cfg, 77 + shift, DEV, ffn="identity_noise")
+    prev = std_prev(inp)[:, :, shift:].contiguous()
+    inp["q_lr"] = inp["q_lr"][:, :, shift:].contiguous()
+    out, scores = lisa.lisa_attn_prefill(inp["q_lr"], inp["k_lr"], inp["v"], prev, inp["w1"], inp["w2"])
+    torch.cuda.synchronize()
+    assert lisa.last_path() == "mfma_fused"
+    assert bool(torch.isfinite(out).all())
+    check_prefill(cfg, inp, prev, out, scores, {0: np.arange(Lq)}, tag=f"/{mode}")
 
 
 # ---------------------------------------------------------------------------------------
@@ -503,12 +552,16 @@ def test_decode_equals_last_prefill_row_on_gpu():
     assert hp.row_rel_err(hp.f64(o_d), hp.f64(out[:, L - 1])) <= tol
 
 
-def test_decode_stack_c5_shape_sampled_sequences():
-    """Configuration 5 at its real per-layer shape (B=64, ctx=4096), chained through the score
-    row: 2 standard layers then 4 LiSA layers (the full 32-layer stack is what bench.py runs;
-    every layer here has the shape and launch configuration of a layer there)."""
-    stk = synth.C5.scaled(n_layers=6, n_std=2)
-    log(f"[case] decode stack {stk.name} layers={stk.n_layers}")
+@pytest.mark.parametrize("n_layers,n_std", [(6, 2), (synth.C5.n_layers, synth.C5.n_std)],
+                         ids=["6_layers", "full_32_layers"])
+def test_decode_stack_c5_shape_sampled_sequences(n_layers, n_std):
+    """Configuration 5 at its real shape (B=64, ctx=4096), chained through the score row: a short
+    stack of 2 standard + 4 LiSA layers, and the whole stack the decode-step metric is quoted
+    on, 5 standard + 27 LiSA layers, in the launch configuration bench.py times.  Three sampled
+    sequences are compared with the oracle at every layer; the oracle of a LiSA layer consumes
+    exactly the (rounded) score row that the library's previous layer emitted."""
+    stk = synth.C5.scaled(n_layers=n_layers, n_std=n_std)
+    log(f"[case] decode stack {stk.name} layers={stk.n_layers} std={stk.n_std}")
     Lk = stk.ctx + 1
     from oracle import cref
     sample_b = [0, 17, 63]
@@ -574,9 +627,7 @@ def check_projection(cfg, pin, rows_by_b, theta, pos0, dim_major, Lmax, tag=""):
     path = lisa.last_path()
     k_rows_major = k_lr.permute(0, 1, 3, 2) if dim_major else k_lr      # [B,Hkv,Lmax,r]
     tol = hp.TOL[dt]
-    # the outputs are stored in dt: for bfloat16 the rounding of that store is not charged
-    err_fn = hp.row_rel_err_stored_bf16 if dt == torch.bfloat16 else hp.row_rel_err
-    worst = 0.0
+    worst = ulps = 0.0
     for b, rows in rows_by_b.items():
         q_ref, k_ref, v_ref = hp.oracle_project_rows(x, w, b, rows, H, Hkv, r, dk, theta, pos0)
         idx = torch.as_tensor(np.asarray(rows), device=DEV, dtype=torch.long)
@@ -584,9 +635,12 @@ def check_projection(cfg, pin, rows_by_b, theta, pos0, dim_major, Lmax, tag=""):
         k_got = hp.f64(k_rows_major[b].index_select(1, idx + pos0).permute(1, 0, 2))
         v_got = hp.f64(v[b].index_select(1, idx + pos0).permute(1, 0, 2))
         for got, ref in ((q_got, q_ref), (k_got, k_ref), (v_got, v_ref)):
-            worst = max(worst, err_fn(got, ref))
-    log(f"[parity] projection {cfg.name}{tag}: path={path} err={worst:.3e} tol={tol:g}")
+            worst = max(worst, hp.row_rel_err(got, ref))
+            if dt == torch.bfloat16:
+                ulps = max(ulps, hp.bf16_ulps_off(got, ref))
+    log(f"[parity] projection {cfg.name}{tag}: path={path} err={worst:.3e} tol={tol:g} bf16_ulps_off={ulps:.2f}")
     assert worst <= tol
+    assert ulps <= 1.0                       # the stored value is the oracle's, rounded once, or its neighbour
     # untouched slots keep the sentinel
     if pos0 > 0:
         assert bool((k_rows_major[:, :, :pos0] == SENTINEL).all()) and bool((v[:, :, :pos0] == SENTINEL).all())
@@ -644,9 +698,9 @@ PROJ_SKINNY = [
 
 @pytest.mark.parametrize("tile_n", [256, 192])
 @pytest.mark.parametrize("case", PROJ_MFMA, ids=lambda c: f"B{c[0]}H{c[1]}-{c[2]}L{c[3]}d{c[4]}r{c[6]}")
-def test_projection_mfma_kernel_shapes(case, tile_n, monkeypatch):
+def test_projection_mfma_kernel_shapes(case, tile_n, tuned):
     B, H, Hkv, L, D, dk, r, theta, pos0, dim_major, extra = case
-    monkeypatch.setenv("LISA_PROJECT_TN", str(tile_n))       # both tile geometries of the kernel
+    tuned(project_tn=tile_n)       # both tile geometries of the kernel
     log(f"[case] projection mfma {case} tile_n={tile_n}")
     cfg = synth.LayerShape("proj_mfma", "bf16", B, H, Hkv, L, D, dk, r, 64, theta)
     pin = synth.make_projection_inputs(cfg, device=DEV)
