@@ -77,7 +77,8 @@ typedef enum {
   LISA_ERR_UNSUPPORTED = -3, /* valid request outside what the kernels implement        */
   LISA_ERR_ALIGN = -4,       /* a base pointer is not 16-byte aligned                   */
   LISA_ERR_WORKSPACE = -5,   /* workspace missing or smaller than lisa_workspace_bytes  */
-  LISA_ERR_HIP = -6          /* a HIP launch failed; see lisa_last_hip_error()          */
+  LISA_ERR_HIP = -6,         /* a HIP launch failed; see lisa_last_hip_error()          */
+  LISA_ERR_SCRATCH = -7      /* lisa_attn_decode_static: needs more than the static scratch */
 } lisa_status;
 
 typedef enum {
@@ -149,6 +150,30 @@ int lisa_attn_decode(const lisa_desc* desc, const void* q_lr, const void* k_lr_n
                      const void* score_row_prev, const void* w1, const void* w2, void* out,
                      void* score_row_out, void* workspace, size_t workspace_bytes,
                      void* hip_stream);
+
+/*
+ * lisa_attn_decode_static -- lisa_attn_decode for callers that cannot allocate device memory and
+ * have no workspace to hand over: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, same kernels and same results as lisa_attn_decode,
+ * without the workspace: the partial results of the split-context kernels (and the operands that
+ * the variants without a two-layer FFN synthesise) live in a buffer of LISA_STATIC_SCRATCH_BYTES
+ * bytes that is part of the library's code object, one copy per GPU, held until the process ends.
+ *   - The call makes no hipMalloc / hipFree and uses no allocating library routine; stage timing
+ *     (lisa_profile_*) is off inside it.  The first call on a device resolves the address of that
+ *     device's copy of the buffer (hipGetSymbolAddress); make that first call outside any capture.
+ *   - A problem whose lisa_workspace_bytes(desc, LISA_WS_DECODE) exceeds LISA_STATIC_SCRATCH_BYTES
+ *     is rejected with LISA_ERR_SCRATCH before any HIP call (B * ceil(Lk / 128) * H <= 32263 units
+ *     at d_k = 128: e.g. 30 sequences of 32 heads at 4097 keys).
+ *   - All calls on one GPU share that GPU's buffer and it keeps the last call's contents; every
+ *     kernel writes what it later reads, so nothing needs clearing between calls.  Calls that can
+ *     overlap on one GPU (different streams, or graphs replayed concurrently) race on it: the
+ *     caller orders them.
+ */
+#define LISA_STATIC_SCRATCH_BYTES (16u << 20)
+int lisa_attn_decode_static(const lisa_desc* desc, const void* q_lr, const void* k_lr_new,
+                            const void* v_new, void* k_lr_cache, void* v_cache,
+                            const void* score_row_prev, const void* w1, const void* w2, void* out,
+                            void* score_row_out, void* hip_stream);
 
 /*
  * std_attn_scores -- standard scaled dot-product attention (Sec. 2.1 Eq. 1-2) that also

@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstring>
 #include <cstdlib>
+#include <mutex>
 
 #include "kernels_decode.h"
 #include "kernels_generic.h"
@@ -24,6 +25,35 @@ thread_local char g_hip_err[256] = "";
 thread_local const char* g_path = "";
 // lisa_tune_set(): geometry overrides of the calling thread, -1 = the library's own choice
 thread_local int g_tune[LISA_TUNE_COUNT] = {-1, -1, -1, -1, -1};
+
+// ---- static scratch of lisa_attn_decode_static ------------------------------------------
+// Device memory that exists from the moment the code object is loaded on a GPU until the process
+// ends: one copy per GPU, each at its own address.  In host code the array's name is only a
+// handle for hipGetSymbolAddress; kernels receive the resolved address as an ordinary argument.
+static __device__ __align__(256) unsigned char scratch[LISA_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Address of this GPU's copy of `scratch` (resolved once per device, with that device current).
+int static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return LISA_ERR_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return LISA_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      snprintf(g_hip_err, sizeof(g_hip_err), "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+      return LISA_ERR_HIP;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return LISA_OK;
+}
 
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -1065,6 +1095,8 @@ const char* lisa_strerror(int status) {
     case LISA_ERR_ALIGN: return "a base pointer is not 16-byte aligned";
     case LISA_ERR_WORKSPACE: return "workspace missing or too small";
     case LISA_ERR_HIP: return "a HIP call failed (see lisa_last_hip_error)";
+    case LISA_ERR_SCRATCH:
+      return "the problem needs more scratch than the static buffer of lisa_attn_decode_static holds";
     default: return "unknown status";
   }
 }
@@ -1160,11 +1192,10 @@ int lisa_attn_prefill(const lisa_desc* desc, const void* q_lr, const void* k_lr,
                                   exact, st);
 }
 
-int lisa_attn_decode(const lisa_desc* desc, const void* q_lr, const void* k_lr_new,
-                     const void* v_new, void* k_lr_cache, void* v_cache,
-                     const void* score_row_prev, const void* w1, const void* w2, void* out,
-                     void* score_row_out, void* workspace, size_t workspace_bytes,
-                     void* hip_stream) {
+// Argument checks of the decode step that need no workspace (host only).
+static int check_decode_args(const lisa_desc* desc, const void* q_lr, const void* k_lr_new, const void* v_new,
+                             void* k_lr_cache, void* v_cache, const void* score_row_prev, const void* w1,
+                             const void* w2, void* out, void* score_row_out) {
   int rc = check_decode(desc);
   if (rc) return rc;
   if (!v_cache || !score_row_prev || !out) return LISA_ERR_NULL;
@@ -1174,15 +1205,20 @@ int lisa_attn_decode(const lisa_desc* desc, const void* q_lr, const void* k_lr_n
   if (k_lr_new && !k_lr_cache) return LISA_ERR_NULL;
   if (desc->write_scores && !score_row_out) return LISA_ERR_NULL;
   if (desc->write_scores && score_row_out == score_row_prev) return LISA_ERR_SHAPE;
-  const void* ptrs[] = {q_lr, k_lr_new, v_new, k_lr_cache, v_cache, score_row_prev,
-                        w1,   w2,       out,   score_row_out, workspace};
+  const void* ptrs[] = {q_lr, k_lr_new, v_new, k_lr_cache, v_cache, score_row_prev, w1, w2, out, score_row_out};
   for (const void* p : ptrs)
     if (p && !aligned16(p)) return LISA_ERR_ALIGN;
-  if (!workspace || workspace_bytes < lisa_workspace_bytes(desc, LISA_WS_DECODE))
-    return LISA_ERR_WORKSPACE;
+  return LISA_OK;
+}
+
+// The decode step itself: arguments already checked, `workspace` holds at least
+// lisa_workspace_bytes(desc, LISA_WS_DECODE) bytes.
+static int run_attn_decode(const lisa_desc* desc, const void* q_lr, const void* k_lr_new, const void* v_new,
+                           void* k_lr_cache, void* v_cache, const void* score_row_prev, const void* w1,
+                           const void* w2, void* out, void* score_row_out, void* workspace, hipStream_t st) {
+  int rc;
   void* scores = desc->write_scores ? score_row_out : nullptr;
   float* exact = (float*)workspace;
-  hipStream_t st = (hipStream_t)hip_stream;
   KeyStrides ks = desc->kcache_dim_major ? dim_major_keys(desc, desc->Lmax, desc->r)
                                                : dense_keys(desc, desc->Lmax, desc->r);
   const KeyStrides vs = dense_keys(desc, desc->Lmax, desc->d_k);
@@ -1229,6 +1265,41 @@ int lisa_attn_decode(const lisa_desc* desc, const void* q_lr, const void* k_lr_n
                                   out, scores, exact, st);
   return run_lisa<bf16_t, half_t>(desc, q_lr, k_lr_cache, ks, v_cache, vs, score_row_prev, w1, w2,
                                   out, scores, exact, st);
+}
+
+int lisa_attn_decode(const lisa_desc* desc, const void* q_lr, const void* k_lr_new,
+                     const void* v_new, void* k_lr_cache, void* v_cache,
+                     const void* score_row_prev, const void* w1, const void* w2, void* out,
+                     void* score_row_out, void* workspace, size_t workspace_bytes,
+                     void* hip_stream) {
+  int rc = check_decode_args(desc, q_lr, k_lr_new, v_new, k_lr_cache, v_cache, score_row_prev, w1, w2, out,
+                             score_row_out);
+  if (rc) return rc;
+  if (workspace && !aligned16(workspace)) return LISA_ERR_ALIGN;
+  if (!workspace || workspace_bytes < lisa_workspace_bytes(desc, LISA_WS_DECODE))
+    return LISA_ERR_WORKSPACE;
+  return run_attn_decode(desc, q_lr, k_lr_new, v_new, k_lr_cache, v_cache, score_row_prev, w1, w2, out,
+                         score_row_out, workspace, (hipStream_t)hip_stream);
+}
+
+int lisa_attn_decode_static(const lisa_desc* desc, const void* q_lr, const void* k_lr_new,
+                            const void* v_new, void* k_lr_cache, void* v_cache,
+                            const void* score_row_prev, const void* w1, const void* w2, void* out,
+                            void* score_row_out, void* hip_stream) {
+  int rc = check_decode_args(desc, q_lr, k_lr_new, v_new, k_lr_cache, v_cache, score_row_prev, w1, w2, out,
+                             score_row_out);
+  if (rc) return rc;
+  if (lisa_workspace_bytes(desc, LISA_WS_DECODE) > (size_t)LISA_STATIC_SCRATCH_BYTES) return LISA_ERR_SCRATCH;
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc) return rc;
+  // stage timing creates HIP events: not in a call that promises to allocate nothing
+  const bool prof = g_prof_on;
+  g_prof_on = false;
+  rc = run_attn_decode(desc, q_lr, k_lr_new, v_new, k_lr_cache, v_cache, score_row_prev, w1, w2, out,
+                       score_row_out, ws, (hipStream_t)hip_stream);
+  g_prof_on = prof;
+  return rc;
 }
 
 int std_attn_scores(const lisa_desc* desc, const void* q, const void* k, const void* v,

@@ -27,7 +27,7 @@ EXPORTS = (
     "lisa_scores_bytes", "lisa_score_elem_bytes", "lisa_kcache_saved_bytes", "lisa_supported",
     "lisa_strerror", "lisa_last_hip_error", "lisa_last_path", "lisa_profile_enable",
     "lisa_profile_collect", "lisa_cache_fill", "lisa_project_qkv", "lisa_layer_prefill",
-    "lisa_layer_offsets", "lisa_layer_decode", "lisa_tune_set",
+    "lisa_layer_offsets", "lisa_layer_decode", "lisa_tune_set", "lisa_attn_decode_static",
 )
 TUNE_PREFILL_GROUPS, TUNE_PREFILL_SPLIT, TUNE_PREFILL_PAIR, TUNE_STD_PAIR, TUNE_PROJECT_TN = range(5)
 
@@ -36,7 +36,7 @@ class LisaError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
         msg = _lib().lisa_strerror(status).decode()
-        if status == -6:
+        if status in (-6,):
             msg += ": " + _lib().lisa_last_hip_error().decode()
         super().__init__(f"{where}: {msg} (status {status})")
 
@@ -82,6 +82,8 @@ def _lib():
         h.lisa_attn_prefill.restype = C.c_int
         h.lisa_attn_decode.argtypes = [dp] + [vp] * 11 + [sz, vp]
         h.lisa_attn_decode.restype = C.c_int
+        h.lisa_attn_decode_static.argtypes = [dp] + [vp] * 11
+        h.lisa_attn_decode_static.restype = C.c_int
         h.std_attn_scores.argtypes = [dp] + [vp] * 6 + [sz, vp]
         h.std_attn_scores.restype = C.c_int
         h.lisa_workspace_bytes.argtypes = [dp, C.c_int]
@@ -450,9 +452,12 @@ def lisa_layer_decode(x, w_qkv, k_lr_cache, v_cache, Lk, score_row_prev, w1, w2,
 
 def lisa_attn_decode(q_lr, k_lr_cache, v_cache, Lk, score_row_prev, w1, w2, *, k_lr_new=None,
                      v_new=None, dim_major=True, mix=MIX_ADD, act=ACT_RELU, write_scores=True,
-                     delta_scale=0.0, out=None, out_dtype=None, score_row_out=None, workspace=None):
+                     delta_scale=0.0, out=None, out_dtype=None, score_row_out=None, workspace=None,
+                     static_scratch=False):
     """One LiSA decode step.  q_lr [B,H,r]; k_lr_cache [B,Hkv,r,Lmax] (dim_major) or
     [B,Hkv,Lmax,r]; v_cache [B,Hkv,Lmax,d_k]; score_row_prev [B,H,Lk].
+    static_scratch: call lisa_attn_decode_static (no workspace; pass `out` and `score_row_out`
+    if the call itself must not allocate).
     Returns (out [B,H,d_k], score_row_out [B,H,Lk] or None)."""
     B, H, _ = score_row_prev.shape
     r = q_lr.shape[2] if q_lr is not None else 0
@@ -474,15 +479,17 @@ def lisa_attn_decode(q_lr, k_lr_cache, v_cache, Lk, score_row_prev, w1, w2, *, k
         out = torch.empty((B, H, dk), dtype=odt, device=v_cache.device)
     if write_scores and score_row_out is None:
         score_row_out = torch.empty((B, H, Lk), dtype=sdt, device=v_cache.device)
-    need = workspace_bytes(desc, WS_DECODE)
-    workspace, wp, wb = _workspace(need, v_cache, workspace)
-    rc = _lib().lisa_attn_decode(
-        C.byref(desc), _ptr(q_lr, "q_lr", dtype=dt), _ptr(k_lr_new, "k_lr_new", (B, Hkv, r), dt),
-        _ptr(v_new, "v_new", (B, Hkv, dk), dt), _ptr(k_lr_cache, "k_lr_cache", kshape, dt),
-        _ptr(v_cache, "v_cache", dtype=dt), _ptr(score_row_prev, "score_row_prev", (B, H, Lk), sdt),
-        _ptr(w1, "w1", (Din, F), dt), _ptr(w2, "w2", (F, H), dt), _ptr(out, "out", (B, H, dk), odt),
-        _ptr(score_row_out if write_scores else None, "score_row_out", (B, H, Lk), sdt), wp, wb,
-        _stream())
+    args = [C.byref(desc), _ptr(q_lr, "q_lr", dtype=dt), _ptr(k_lr_new, "k_lr_new", (B, Hkv, r), dt),
+            _ptr(v_new, "v_new", (B, Hkv, dk), dt), _ptr(k_lr_cache, "k_lr_cache", kshape, dt),
+            _ptr(v_cache, "v_cache", dtype=dt), _ptr(score_row_prev, "score_row_prev", (B, H, Lk), sdt),
+            _ptr(w1, "w1", (Din, F), dt), _ptr(w2, "w2", (F, H), dt), _ptr(out, "out", (B, H, dk), odt),
+            _ptr(score_row_out if write_scores else None, "score_row_out", (B, H, Lk), sdt)]
+    if static_scratch:
+        rc = _lib().lisa_attn_decode_static(*args, _stream())
+    else:
+        need = workspace_bytes(desc, WS_DECODE)
+        workspace, wp, wb = _workspace(need, v_cache, workspace)
+        rc = _lib().lisa_attn_decode(*args, wp, wb, _stream())
     if rc:
-        raise LisaError(rc, "lisa_attn_decode")
+        raise LisaError(rc, "lisa_attn_decode_static" if static_scratch else "lisa_attn_decode")
     return out, (score_row_out if write_scores else None)

@@ -94,6 +94,24 @@ def test_decode_and_std_reject_bad_arguments():
     assert lib.std_attn_scores(C.byref(d), FAKE, FAKE, None, FAKE, None, None, 0, None) == -2
 
 
+def test_static_scratch_decode_rejects_what_does_not_fit_before_any_launch():
+    B, H, Lk = 64, 32, 4097
+    d = lisa.make_desc(lisa.BF16, B, H, H, 1, Lk, 128, 22, 64, write_scores=1, kcache_dim_major=1, Lmax=Lk)
+    assert lisa.workspace_bytes(d, lisa.WS_DECODE) > (16 << 20)
+    lib = lisa.library()
+    ptrs = [C.c_void_p(0x10000 + 0x100 * i) for i in range(10)]             # distinct: no aliasing
+    assert lib.lisa_attn_decode_static(C.byref(d), *ptrs, None) == -7
+    assert "static" in lib.lisa_strerror(-7).decode()
+    fits = lisa.make_desc(lisa.BF16, 30, H, H, 1, Lk, 128, 22, 64, write_scores=1, kcache_dim_major=1, Lmax=Lk)
+    assert lisa.workspace_bytes(fits, lisa.WS_DECODE) <= (16 << 20)
+    a = list(ptrs)
+    a[5] = None                                                             # score_row_prev
+    assert lib.lisa_attn_decode_static(C.byref(fits), *a, None) == -1       # other checks come first
+    a = list(ptrs)
+    a[4] = ODD
+    assert lib.lisa_attn_decode_static(C.byref(fits), *a, None) == -4
+
+
 def test_tune_set_accepts_known_knobs_only():
     lib = lisa.library()
     assert lib.lisa_tune_set(lisa.TUNE_PREFILL_SPLIT, 2) == 0
