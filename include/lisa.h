@@ -176,6 +176,45 @@ int lisa_attn_decode_static(const lisa_desc* desc, const void* q_lr, const void*
                             void* score_row_out, void* hip_stream);
 
 /*
+ * lisa_decode_stack -- one decode step through the attention layers of a model in which some
+ * layers share attention (Sec. 5.1, "Selecting layers to implement LiSA" and its table of
+ * configurations; Sec. 4 for direct sharing): every layer is a standard layer, a LiSA layer or a
+ * direct-sharing layer.  A sharing layer takes A_{n-1} from the layer in front of it, so the first
+ * layer must be standard.  The score row travels from layer to layer inside the workspace; a
+ * layer emits its row only if the next layer shares it (or the caller gives it a place).
+ *   desc     the LiSA layers' descriptor (Lq = 1, Lk, Lmax, r, F, mix, act, kcache_dim_major, ...);
+ *            standard layers use its B, H, Hkv, Lk, Lmax, d_k, std_scale, out_f32; write_scores is
+ *            ignored.  mix must not be LISA_MIX_SHARE.
+ *   layers   HOST array of n_layers entries, in layer order; device pointers inside:
+ *     kind       LISA_LAYER_STD | LISA_LAYER_LISA | LISA_LAYER_SHARE
+ *     q          STD: q [B,H,d_k]; LISA: q_lr [B,H,r]; SHARE: unused
+ *     k_cache    STD: K cache [B,Hkv,Lmax,d_k]; LISA: K_LR cache (layout as in lisa_attn_decode);
+ *                SHARE: unused.  The caches already hold the new token (index Lk-1).
+ *     v_cache    [B,Hkv,Lmax,d_k]
+ *     w1, w2     LISA: FFN weights as in lisa_attn_decode
+ *     out        [B,H,d_k]  out  the layer's attention output
+ *     score_row  [B,H,Lk]   out  or NULL: where to keep this layer's A_n (score type)
+ *   workspace    at least lisa_stack_workspace_bytes(desc) bytes
+ * All layers are enqueued on hip_stream in order; the call returns after the last launch.
+ */
+typedef enum { LISA_LAYER_STD = 0, LISA_LAYER_LISA = 1, LISA_LAYER_SHARE = 2 } lisa_layer_kind;
+typedef struct lisa_stack_layer {
+  int32_t kind;      /* lisa_layer_kind */
+  int32_t reserved;  /* 0 */
+  const void* q;
+  void* k_cache;
+  void* v_cache;
+  const void* w1;
+  const void* w2;
+  void* out;
+  void* score_row;
+} lisa_stack_layer;
+int lisa_decode_stack(const lisa_desc* desc, const lisa_stack_layer* layers, int32_t n_layers,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+/* Scratch bytes of lisa_decode_stack for this descriptor (two score rows + the largest layer). */
+size_t lisa_stack_workspace_bytes(const lisa_desc* desc);
+
+/*
  * std_attn_scores -- standard scaled dot-product attention (Sec. 2.1 Eq. 1-2) that also
  * emits the pre-softmax scores A = Q K^T * std_scale shared with the following LiSA layer.
  *   q [B,H,Lq,d_k], k [B,Hkv,Lk,d_k]   in
@@ -314,11 +353,13 @@ const char* lisa_last_path(void);
  *   LISA_TUNE_PREFILL_PAIR    1: a workgroup takes a long and a short unit, 0: one unit
  *   LISA_TUNE_STD_PAIR        the same for the standard layer's prefill kernel
  *   LISA_TUNE_PROJECT_TN      tile width of the projection kernel: 192 or 256
+ *   LISA_TUNE_PREFILL_SLICES  slices of 16 query rows per workgroup of the fused prefill kernel:
+ *                             1, 2 or 4 (where the shape has them: ReLU, 33..96 hidden units)
  * Returns LISA_OK, or LISA_ERR_SHAPE for an unknown knob.
  */
 typedef enum {
   LISA_TUNE_PREFILL_GROUPS = 0, LISA_TUNE_PREFILL_SPLIT = 1, LISA_TUNE_PREFILL_PAIR = 2,
-  LISA_TUNE_STD_PAIR = 3, LISA_TUNE_PROJECT_TN = 4, LISA_TUNE_COUNT = 5
+  LISA_TUNE_STD_PAIR = 3, LISA_TUNE_PROJECT_TN = 4, LISA_TUNE_PREFILL_SLICES = 5, LISA_TUNE_COUNT = 6
 } lisa_tune_knob;
 int lisa_tune_set(int knob, int value);
 

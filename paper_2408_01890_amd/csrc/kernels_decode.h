@@ -5,6 +5,7 @@
 // alignment FFN couples the heads of a position, Sec. 5.1).  Stages:
 //   S1  scores of the chunk into LDS:   LiSA  a_delta[h][j] = scale <q_lr[h], K_LR[kv][j]>  (Eq. 3)
 //                                       std   a[h][j]       = scale <q[h],    K[kv][j]>     (Eq. 2)
+//                                       direct sharing (Sec. 4): a[h][j] = A_{n-1}[h][j], no key cache
 //   S2  (LiSA) A_n = FFN(A_{n-1}) + a_delta, or A_n = FFN([A_{n-1}; a_delta]) in CONCAT form, on
 //       the matrix cores, 16 positions per MFMA block
 //   S3  per head: chunk maximum, p = exp(a - max), chunk sum; the score row is stored here
@@ -42,7 +43,8 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 // LISA_MODE: 0 = standard layer, 1 = LiSA layer in ADD form (HB = blocks of 16 heads), 2 = LiSA
 // layer in CONCAT form (HB = blocks of 16 FFN inputs, 2H of them; (HB + 1) / 2 output blocks; the
-// FFN weights stay in LDS).  DK: head dimension (64 or 128).
+// FFN weights stay in LDS), 3 = direct sharing: the scores are the previous layer's row as it
+// stands (no key-side operand, no FFN; HB, FS unused).  DK: head dimension (64 or 128).
 template <int LISA_MODE, int HB, int FS, int DK, int ACT = 0>
 __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
   constexpr int LPK = DK / 8;        // lanes per key in the 16-byte streams
@@ -96,7 +98,12 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
   }
 
   // ---- S1 ------------------------------------------------------------------------------
-  if (LISA_MODE) {
+  if (LISA_MODE == 3) {
+    for (int e = tid; e < H * DEC_CK; e += DEC_THREADS) {
+      const int h = e / DEC_CK, pj = e % DEC_CK;
+      a_s[e] = pj < n_here ? (float)a.prev[((size_t)b * H + h) * Lk + j0 + pj] : 0.f;
+    }
+  } else if (LISA_MODE) {
     for (int e = tid; e < H * a.r; e += DEC_THREADS)
       q_s[e] = elem<bf16_t>::load(a.q + (size_t)b * H * a.r + e);
     if (LISA_MODE == 2)
@@ -230,7 +237,7 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
         }
     }
     __syncthreads();
-  } else if (LISA_MODE) {
+  } else if (LISA_MODE == 1) {
     MfmaFfn<HB, FS, HB, ACT> ffn;
     ffn.fetch(w_s);
     const int c = lane & 15, g = lane >> 4;

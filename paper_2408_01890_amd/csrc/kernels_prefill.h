@@ -75,6 +75,7 @@ struct PrefillArgs {
   float* part_o;          // [split][B][Lqp][H][128] unnormalised partial outputs (split > 1)
   float* part_ml;         // [split][B][Lqp][H][2]   running maximum, partial sum
   int pair;               // workgroup x takes the units (last - x) and x
+  int B;                  // sequences
 };
 
 typedef unsigned short pf_u16x8 __attribute__((ext_vector_type(8)));
@@ -205,16 +206,49 @@ __device__ __forceinline__ void st_uv(void* ubase, unsigned voff, T v) {
   *(T*)((char*)ubase + voff) = v;
 }
 // H = NG * NW * HPW heads in NG groups; NW waves per workgroup, HPW heads per wave; FS hidden
-// k-steps of the FFN.  A unit of work is (row block of 16 rows, key split); units are
-// numbered by length.  grid (units or ceil(units / 2), B, NG), block NW * 64: with a.pair the
-// workgroup x takes the units (last - x) and x, a long and a short one, so that all workgroups
-// carry the same number of tiles and stage the FFN weights once.  Requires Lk % 8 == 0.
-template <int NG, int FS, int HPW, int NW, int ACT = 0>
+// k-steps of the FFN; RS slices of 16 query rows per workgroup (RS > 1 needs HPW = 1).
+//
+// Row slices.  A workgroup owns R = 16 RS query rows.  The K_LR / V operands of a tile of 32 keys
+// are loaded once and used for all RS slices, one slice per step: a step is what the pipeline
+// above calls a tile (stage A on the A_{n-1} piece of 16 rows x 32 keys, stage B for the same
+// rows), and the steps of a tile run through its slices in order.  What a compute unit fetches
+// per position for K_LR and V falls with 1 / RS, and so does what leaves the L2: row blocks do not
+// share their K_LR / V tiles in the L2 in practice (the streams of A_{n-1} and A_n flush it within
+// a few tiles; measured fetch = one K_LR / V tile per workgroup and tile), so HBM traffic is
+// Hkv * 320 / R bytes per position on top of the 4 H bytes of the two score tensors.
+// A slice is skipped in the tiles that none of its rows can see (beyond its own diagonal).
+//
+// A unit of work is (row block of R rows, key split); units are numbered by length.
+// Grid: one dimension.  Workgroup ids go round robin over the 8 XCDs, each with its own L2 and 32
+// compute units.  The ids of one XCD are dealt in chunks of 8 neighbouring units of one sequence
+// times NG head groups: 32 workgroups that start together and carry nearly the same number of
+// tiles, so they walk the keys side by side.  The NG head groups of a row block then find the
+// A_{n-1} tile, and the 8 row blocks of a head group the K_LR / V tiles, in the L2 after the first
+// of them has fetched it from HBM.  With a.pair the workgroup takes the units (last - x) and x, a
+// long and a short one, so that all workgroups carry the same number of tiles and stage the FFN
+// weights once.
+// Requires Lk % 8 == 0.
+// SHG > 0: every SHG consecutive heads of a wave share one key/value head (grouped KV heads, H / Hkv
+// a multiple of SHG, HPW a multiple of SHG): one set of K_LR / V operands per tile serves all of
+// them, and every such set is refilled behind its last head with the next tile's operands.  With
+// NG = 1 and 32 heads (XSTG below) the whole layer of a row block runs in one workgroup: the FFN is
+// computed once, the A_{n-1} tile is read once, and a wave issues 10 operand loads per tile and
+// key/value head for four query heads.
+template <int NG, int FS, int HPW, int NW, int ACT = 0, int RS = 1, int SHG = 0>
 __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
+  static_assert(RS == 1 || HPW == 1, "row slices: one head per wave");
+  // XSTG: the A_{n-1} piece is double buffered by tile parity and the buffers double as the staging
+  // tiles of A_n (a wave loads the A_{n-1} rows of its own heads, so it alone touches those parts
+  // between the barriers): the 32 heads' own staging tiles would not fit the LDS.
+  constexpr bool SHKV = SHG > 0;
+  static_assert(!SHKV || HPW % SHG == 0, "whole key/value head groups per wave");
+  constexpr bool XSTG = NG == 1 && HPW * NW == 32;
+  static_assert(!XSTG || RS == 1, "one row slice with all heads in one workgroup");
   constexpr int DK = 128;
   constexpr int THREADS = NW * 64;
   constexpr int GH = NW * HPW;                       // heads of this workgroup's group
   constexpr int H = NG * GH;
+  constexpr int R = PF_ROWS * RS;                    // query rows of this workgroup
   constexpr int HB = (H + 15) / 16;
   constexpr int HBO = (GH + 15) / 16;
   typedef MfmaFfn<HB, FS, HBO, ACT> Ffn;
@@ -223,26 +257,41 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
   constexpr int NBW = ((2 * PF_ROWS + NW - 1) / NW + 1) / 2 * 2;   // position blocks per wave in stage A (even)
   extern __shared__ __align__(16) unsigned char pf_lds[];
   const int Lq = a.Lq, Lk = a.Lk;
-  unsigned char* xs = pf_lds;                               // A_{n-1} tile, half
-  unsigned char* ys = xs + H * PF_XS_HEAD;                  // y tile of the group, float
+  unsigned char* xs = pf_lds;                               // A_{n-1} piece, half
+  unsigned char* ys = xs + (XSTG ? 2 : 1) * H * PF_XS_HEAD; // y piece of the group, float
   unsigned short* w_s = (unsigned short*)(ys + GH * PF_YS_HEAD);
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform
-  unsigned char* as_ = (unsigned char*)w_s + Ffn::kStageBytes + wv * HPW * PF_AS_HEAD;   // this wave's A_n staging
+  unsigned char* as_ = (unsigned char*)w_s + Ffn::kStageBytes + wv * (HPW * RS) * PF_AS_HEAD;   // this wave's A_n staging
   const int c = lane & 15, g = lane >> 4;
-  const int b = blockIdx.y;
-  const int hg0 = blockIdx.z * GH;                          // first head of the group
   const int shift = Lk - Lq;                                // key j visible to row i iff j <= i + shift
   const int group = H / a.Hkv;
   const float LOG2E = 1.4426950408889634f;
-  const int n_units = a.Lqp / PF_ROWS * a.split;
+  const int n_units = (Lq + R - 1) / R * a.split;
+  // workgroup id -> (XCD, chunk of 8 neighbouring slots of one sequence, slot in the chunk, head group)
+  const int n_slots = a.pair ? (n_units + 1) / 2 : n_units;
+  int slot, b, grp;
+  {
+    const int i = blockIdx.x, x = i & 7, j = i >> 3;
+    grp = j % NG;
+    const int jj = j / NG;                                   // position among this XCD's workgroups
+    const int chunk = (jj >> 3) * 8 + x;                     // chunks go round robin over the XCDs, long first
+    const int n_chunks = (n_slots + 7) / 8;
+    if (chunk >= n_chunks * a.B) return;
+    b = chunk % a.B;
+    slot = (chunk / a.B) * 8 + (jj & 7);
+    if (slot >= n_slots) return;
+  }
+  const int hg0 = grp * GH;                                 // first head of the group
   const int h_first = hg0 + wv * HPW;
 
   Ffn::stage(a.w1, a.w2, H, a.F, w_s, tid, THREADS, hg0, GH);
   // One head per wave leaves registers for the FFN weights: fetched once per workgroup instead of
   // read from LDS by every block pair.
-  constexpr bool WREG = HPW == 1 && NW <= 8 && (Ffn::FB * Ffn::KS + HBO * FS) <= 8;
-  constexpr int NBLK = 2;   // blocks of 16 positions whose MFMA chains are interleaved in stage A
+  constexpr bool WREG = HPW == 1 && NW <= 8 && RS == 1 && (Ffn::FB * Ffn::KS + HBO * FS) <= 8;
+  // blocks of 16 positions whose MFMA chains are interleaved in stage A (one at a time where the
+  // accumulators of four row slices leave no registers for a second chain)
+  constexpr int NBLK = RS >= 4 ? 1 : 2;
   Ffn ffn;
   if (WREG) {
     __syncthreads();
@@ -260,16 +309,16 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
     v_base[hh] = a.vt + ((size_t)b * a.Hkv + kv) * (a.Lkp / 8) * (DK * 8);
     s_base[hh] = a.scores ? a.scores + ((size_t)b * H + h) * Lq * Lk : nullptr;
   }
-  const half_t* x_base[XCH];     // A_{n-1} of head wv + NW u
+  const half_t* x_base[XCH];     // A_{n-1} of head wv + NW u (XSTG: of the wave's own heads)
 #pragma unroll
-  for (int u = 0; u < XCH; ++u) x_base[u] = a.prev + ((size_t)b * H + wv + NW * u) * Lq * Lk;
+  for (int u = 0; u < XCH; ++u) x_base[u] = a.prev + ((size_t)b * H + (XSTG ? wv * HPW + u : wv + NW * u)) * Lq * Lk;
   // per-lane byte offsets, the same for every head
   const unsigned k_off = ((8 * (c >> 2) + (c & 3)) * 32 + 8 * g) * 2;   // MFMA row c -> key 8 (c/4) + c%4 (+4)
   const unsigned v_off = (g * DK + c) * 16;                             // key chunk g, feature c (+16 nb)
   const int xq8 = 8 * (lane & 3);                                       // A_{n-1} chunk: row lane/4, 8 keys
-  const int xdst = wv * PF_XS_HEAD + lane * 16;                         // + u NW PF_XS_HEAD
+  const int xdst = (XSTG ? wv * HPW : wv) * PF_XS_HEAD + lane * 16;     // + u NW PF_XS_HEAD (XSTG: + u PF_XS_HEAD)
 
-  // LDS addresses of stage A (per lane, tile independent)
+  // LDS addresses of stage A (per lane, step independent)
   int xrd[KS][2];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
@@ -282,113 +331,149 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
   for (int rep = 0; rep < 2; ++rep) {
     int unit;
     if (a.pair) {
-      unit = rep ? (int)blockIdx.x : n_units - 1 - (int)blockIdx.x;
+      unit = rep ? slot : n_units - 1 - slot;
       if (rep && unit >= n_units - 1 - unit) break;         // the middle unit of an odd count is alone
     } else {
       if (rep) break;
-      unit = n_units - 1 - blockIdx.x;                       // long units first
+      unit = n_units - 1 - slot;                             // long units first
     }
     // Row block and key split.  The key tiles are dealt in pairs (64 keys = one 128-byte line of a
     // score row): split sp takes the pairs sp, sp + split, ...; the longer share comes later in
     // the unit numbering.
     const int rb = unit / a.split, sp = a.split - 1 - unit % a.split;
-    const int i0 = rb * PF_ROWS;
-    const int i_last = min(i0 + PF_ROWS - 1, Lq - 1);
+    const int i0 = rb * R;
+    const int i_last = min(i0 + R - 1, Lq - 1);
+    // (a slice without rows, in the last row block of a ragged Lq, runs on copies of row Lq - 1 and
+    // stores nothing: "last slice of a tile" stays a compile-time property, and with it the place
+    // where the tile's operands are refilled -- a load behind a run-time branch would make every
+    // later wait for an older load a wait for everything)
+    constexpr int rs_last = RS - 1;
     const int n_keys = a.causal ? min(Lk, i_last + 1 + shift) : Lk;
     const int n_tiles_all = (n_keys + PF_TK - 1) / PF_TK;
     const int n_mine = n_tiles_all / (2 * a.split) * 2 + min(max(n_tiles_all % (2 * a.split) - 2 * sp, 0), 2);
     if (n_mine == 0) continue;                                 // empty share (short row block)
-    // The first unit of a workgroup walks its tiles upwards, the second one downwards.  All
-    // workgroups start together and carry about the same number of tiles, so at any time the chip
-    // works on two narrow fronts of keys and the K_LR / V tiles, which every row block re-reads,
-    // are served by the L2 (measured: 2.5 times less HBM fetch than with contiguous key ranges).
+    // The first unit of a workgroup walks its tiles upwards, the second one downwards.
     auto tile_at = [&](int it) {
       const int k = rep ? n_mine - 1 - it : it;
       return 2 * (sp + a.split * (k >> 1)) + (k & 1);
     };
     const int t_begin = tile_at(0);
-    // tiles whose 32 keys are visible to all 16 rows (and all 16 rows exist) need no masking
-    const int n_full = (i0 + PF_ROWS <= Lq) ? (a.causal ? min(Lk, i0 + 1 + shift) : Lk) / PF_TK : 0;
+    // first slice of which some row sees a key of the tile (the slices after it do too)
+    auto rs_min = [&](int tile) {
+      int r0 = 0;
+      if (RS > 1 && a.causal) {
+#pragma unroll
+        for (int rs = 0; rs + 1 < RS; ++rs)
+          if (tile * PF_TK > min(i0 + PF_ROWS * rs + PF_ROWS - 1, Lq - 1) + shift) r0 = rs + 1;
+      }
+      return min(r0, rs_last);
+    };
+    // tiles of slice rs whose 32 keys are visible to all its 16 rows (and all 16 rows exist) need no masking
+    auto n_full_of = [&](int rs) {
+      const int f = i0 + PF_ROWS * rs;
+      return (f + PF_ROWS <= Lq) ? (a.causal ? min(Lk, f + 1 + shift) : Lk) / PF_TK : 0;
+    };
+    // last tile that slice rs takes part in
+    auto last_tile_of = [&](int rs) {
+      const int l = min(i0 + PF_ROWS * rs + PF_ROWS - 1, Lq - 1);
+      return (a.causal ? min(Lk, l + 1 + shift) - 1 : Lk - 1) / PF_TK;
+    };
 
-    // ---- A_{n-1} tile: lane -> XCH chunks (head wv + NW u, row lane / 4, 8 keys) of 16 bytes ------
-    const unsigned x_row = (unsigned)min(i0 + (lane >> 2), Lq - 1) * Lk * 2;
-    auto load_x = [&](int tile, pf_u32x4 (&xr)[XCH]) {
+    // ---- A_{n-1} piece: lane -> XCH chunks (head wv + NW u, row lane / 4, 8 keys) of 16 bytes ------
+    auto load_x = [&](int tile, int rs, pf_u32x4 (&xr)[XCH]) {
+      const unsigned x_row = (unsigned)min(i0 + PF_ROWS * rs + (lane >> 2), Lq - 1) * Lk * 2;
       // keys >= Lk: any in-bounds chunk will do, those positions are masked in stage B
       const unsigned off = x_row + 2 * min(tile * PF_TK + xq8, Lk - 8);
 #pragma unroll
       for (int u = 0; u < XCH; ++u) xr[u] = ld_uv<pf_u32x4>(x_base[u], off);
     };
-    auto store_x = [&](const pf_u32x4 (&xr)[XCH]) {
+    auto store_x = [&](const pf_u32x4 (&xr)[XCH], int tile) {   // XSTG: into the buffer of the tile's parity
+      unsigned char* dst = xs + (XSTG ? (tile & 1) * (H * PF_XS_HEAD) : 0) + xdst;
 #pragma unroll
-      for (int u = 0; u < XCH; ++u) *(pf_u32x4*)(xs + xdst + u * (NW * PF_XS_HEAD)) = xr[u];
+      for (int u = 0; u < XCH; ++u) *(pf_u32x4*)(dst + u * ((XSTG ? 1 : NW) * PF_XS_HEAD)) = xr[u];
     };
 
-    // ---- per-head state of stage B ------------------------------------------------------------------
-    const int my_row = min(i0 + c, Lq - 1);                   // clamped for loads; stores check i0 + c
-    const int vis_row = a.causal ? min(Lk, my_row + 1 + shift) : Lk;   // keys visible to my row
+    // ---- per-head, per-slice state of stage B ---------------------------------------------------------
     // A_n leaves through LDS in whole 128-byte pieces of a row (64 keys = two tiles): lane ->
-    // rows lane / 8 and lane / 8 + 8, keys 8 (lane % 8) .. + 7 of the pair of tiles
-    unsigned a_off[2];
-    int a_vis[2];
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const int gi = i0 + (lane >> 3) + 8 * u;
-      a_off[u] = ((unsigned)min(gi, Lq - 1) * Lk + 8 * (lane & 7)) * 2;
-      a_vis[u] = gi < Lq ? (a.causal ? min(Lk, gi + 1 + shift) : Lk) : 0;
-    }
-    f32x4 o[HPW][DK / 16];
-    float m_run[HPW], l_run[HPW];
+    // rows lane / 8 and lane / 8 + 8 of the slice, keys 8 (lane % 8) .. + 7 of the pair of tiles
+    f32x4 o[HPW * RS][DK / 16];
+    float m_run[HPW * RS], l_run[HPW * RS];
     // PERSIST: every head keeps its own operand registers; each is refilled right after its use
     // with the same head's next tile, so the load has a whole tile period to arrive.  Otherwise
     // (register file too small) one rotating set, refilled for the head that stage B handles next.
-    constexpr bool PERSIST = HPW <= 2 && NW <= 8;
-    constexpr int NSET = PERSIST ? HPW : 1;
+    constexpr bool PERSIST = (HPW <= 2 && NW <= 8) || SHKV;
+    constexpr int SH = SHKV ? SHG : 1;                         // heads per operand set
+    constexpr int NSET = PERSIST ? HPW / SH : 1;
     // SPREAD: the V operands of the second head are loaded during stage A of their own tile
     // instead of right after their use: the compute unit's load pipe, which every wave fills at
     // the same time in stage B, then also works during stage A.
-    constexpr bool SPREAD = PERSIST && HPW == 2;
-    bf16x8 qop[HPW], ka[NSET], kb[NSET], vop[NSET][DK / 16];
+    constexpr bool SPREAD = PERSIST && HPW == 2 && !SHKV;
+    // QRES: the Q_LR operands of all slices stay in registers; with many slices the accumulators
+    // need that room and the operand of a step is loaded at the start of its stage A instead
+    constexpr bool QRES = RS <= 2;
+    bf16x8 qop[QRES ? HPW * RS : HPW], ka[NSET], kb[NSET], vop[NSET][DK / 16];
+    const bf16_t* q_head = a.qp + ((size_t)b * H + h_first) * a.Lqp * 32;   // + hh Lqp 32
 #pragma unroll
     for (int hh = 0; hh < HPW; ++hh) {
-      m_run[hh] = -INFINITY;
-      l_run[hh] = 0.f;
 #pragma unroll
-      for (int nb = 0; nb < DK / 16; ++nb) o[hh][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
-      qop[hh] = *(const bf16x8*)(a.qp + (((size_t)b * H + h_first + hh) * a.Lqp + i0 + c) * 32 + 8 * g);
-      if (hh >= NSET) continue;
-      const bf16_t* kt = k_base[hh] + (size_t)t_begin * (PF_TK * 32);
+      for (int rs = 0; rs < RS; ++rs) {
+        m_run[hh * RS + rs] = -INFINITY;
+        l_run[hh * RS + rs] = 0.f;
+#pragma unroll
+        for (int nb = 0; nb < DK / 16; ++nb) o[hh * RS + rs][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        const int qrow = min(i0 + PF_ROWS * rs + c, a.Lqp - 1);
+        if (QRES) qop[hh * RS + rs] = *(const bf16x8*)(q_head + ((size_t)hh * a.Lqp + qrow) * 32 + 8 * g);
+      }
+      if (hh >= NSET) continue;                                // (hh here numbers the operand sets)
+      const bf16_t* kt = k_base[hh * SH] + (size_t)t_begin * (PF_TK * 32);
       ka[hh] = ld_uv<bf16x8>(kt, k_off);
       kb[hh] = ld_uv<bf16x8>(kt, k_off, 4 * 32 * 2);
       if (SPREAD && hh == 1) continue;
-      const bf16_t* vt = v_base[hh] + (size_t)t_begin * (PF_TK / 8 * DK * 8);
+      const bf16_t* vt = v_base[hh * SH] + (size_t)t_begin * (PF_TK / 8 * DK * 8);
 #pragma unroll
       for (int nb = 0; nb < DK / 16; ++nb) vop[hh][nb] = ld_uv<bf16x8>(vt, v_off, nb * 256);
     }
 
-    // the A_{n-1} tile t+1 travels in xr through stage B(t): loaded during stage A(t), written to
-    // LDS at the end of stage B(t)
+    // the A_{n-1} piece of the next step travels in xr through stage B: loaded during stage A,
+    // written to LDS at the end of stage B
     pf_u32x4 xr[XCH];
-    load_x(t_begin, xr);
-    store_x(xr);
-    // Stores of a staged pair of A_n tiles (head hh of this wave); `pending` = last tile of a pair
-    // whose stores are still to be issued.  They go out during stage A of the next tile: all
-    // waves of a workgroup run the same stage at the same time, stage B is where the operand loads
-    // crowd the load / store pipe of the compute unit and stage A is where it has room.
-    int pending = -1;
-    auto flush_scores = [&](int tile, int hh) {
+    load_x(t_begin, rs_min(t_begin), xr);
+    store_x(xr, t_begin);
+    // Stores of a staged pair of A_n tiles (head hh, slice rs of this wave); pending[rs] = last
+    // tile of a pair whose stores are still to be issued.  They go out during stage A of the
+    // slice's next step: all waves of a workgroup run the same stage at the same time, stage B is
+    // where the operand loads crowd the load / store pipe of the compute unit and stage A is where
+    // it has room.
+    int pending[RS];
+#pragma unroll
+    for (int rs = 0; rs < RS; ++rs) pending[rs] = -1;
+    auto flush_scores = [&](int tile, int hh, int rs) {
       const int jp = (tile >> 1) * (2 * PF_TK);               // first key of the pair
-      const bool pair_full = (tile | 1) < n_full;             // workgroup-uniform
+      const bool pair_full = (tile | 1) < n_full_of(rs);      // workgroup-uniform
       const int jc = jp + 8 * (lane & 7);
       half_t* st = s_base[hh] + jp;
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
-        const f16x8 hv = *(const f16x8*)(as_ + hh * PF_AS_HEAD + ((lane >> 3) + 8 * u) * PF_AS_ROW + (lane & 7) * 16);
-        if (pair_full || jc + 8 <= a_vis[u]) {
-          st_uv<f16x8>(st, a_off[u], hv);
-        } else {
+        const int gi = i0 + PF_ROWS * rs + (lane >> 3) + 8 * u;
+        const unsigned a_off = ((unsigned)min(gi, Lq - 1) * Lk + 8 * (lane & 7)) * 2;
+        const int a_vis = gi < Lq ? (a.causal ? min(Lk, gi + 1 + shift) : Lk) : 0;
+        // XSTG: keys 0..31 of the pair lie in the even buffer, 32..63 in the odd one
+        const unsigned char* sp =
+            XSTG ? xs + ((lane >> 2) & 1) * (H * PF_XS_HEAD) + (wv * HPW + hh) * PF_XS_HEAD +
+                       ((lane >> 3) + 8 * u) * (2 * PF_TK) + (lane & 3) * 16
+                 : as_ + (hh * RS + rs) * PF_AS_HEAD + ((lane >> 3) + 8 * u) * PF_AS_ROW + (lane & 7) * 16;
+        if (pair_full || jc + 8 <= a_vis) {
+          st_uv<f16x8>(st, a_off, *(const f16x8*)sp);
+        } else if (jc < a_vis) {
+          // a piece that straddles the row's last visible key (diagonal tiles only): the entries
+          // beyond it keep what memory holds -- read, merge, write back; every piece has one writer.
+          // (Element-wise stores kept eight addresses per piece alive across the whole tile loop.)
+          const f16x8 old = ld_uv<f16x8>(st, a_off);
+          f16x8 hv = *(const f16x8*)sp;
 #pragma unroll
-          for (int e = 0; e < 8; ++e)
-            if (jc + e < a_vis[u]) st_uv<_Float16>(st, a_off[u] + 2 * e, hv[e]);
+          for (int e = 1; e < 8; ++e)
+            if (jc + e >= a_vis) hv[e] = old[e];
+          st_uv<f16x8>(st, a_off, hv);
         }
       }
     };
@@ -400,18 +485,32 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
     for (int it = 0; it < n_mine; ++it) {
       const int tile = tile_at(it);
       const int j0 = tile * PF_TK;
+      const int tile_n = tile_at(min(it + 1, n_mine - 1));      // next tile (clamped: loads stay valid)
+      const int rs_first = rs_min(tile), rs_first_n = rs_min(tile_n);
+#pragma unroll
+      for (int rs = 0; rs < RS; ++rs) {
+      if (RS > 1 && rs < rs_first) continue;                   // workgroup-uniform: no row of the slice sees the tile
+      const bool last_slice = RS == 1 || rs == rs_last;        // the tile's operands are used up after this step
+      // the step after this one: the next slice of the tile, else the first slice of the next tile
+      const int x_tile = last_slice ? tile_n : tile, x_rs = last_slice ? rs_first_n : rs + 1;
+      unsigned char* xs_t = xs + (XSTG ? (tile & 1) * (H * PF_XS_HEAD) : 0);   // this tile's A_{n-1} buffer
       lds_barrier();                                                       // B1
+      if (!QRES) {
+        const unsigned qoff = ((unsigned)min(i0 + PF_ROWS * rs + c, a.Lqp - 1) * 32 + 8 * g) * 2;
+#pragma unroll
+        for (int hh = 0; hh < HPW; ++hh) qop[hh] = ld_uv<bf16x8>(q_head + (size_t)hh * a.Lqp * 32, qoff);
+      }
       // ---- stage A: y = FFN(A_{n-1}) for this wave's blocks of 16 positions ----------------------
       // two blocks of 16 positions at a time, their MFMA chains interleaved; the weights are read
       // from LDS as the products need them (stage B keeps the register file)
 #pragma unroll
       for (int q = 0; q < NBW; q += NBLK) {
-        if (pending >= 0) {
+        if (!XSTG && pending[rs] >= 0) {
           // heads of this wave dealt over the block pairs
 #pragma unroll
-          for (int hh = q / NBLK; hh < HPW; hh += NBW / NBLK) flush_scores(pending, hh);
+          for (int hh = q / NBLK; hh < HPW; hh += NBW / NBLK) flush_scores(pending[rs], hh, rs);
         }
-        if (q + NBLK >= NBW) load_x(tile_at(min(it + 1, n_mine - 1)), xr);
+        if (q + NBLK >= NBW) load_x(x_tile, x_rs, xr);
         if (SPREAD) {
           constexpr int PER = (DK / 16 + NBW / NBLK - 1) / (NBW / NBLK);    // V loads per block group
           const bf16_t* vt = v_base[HPW - 1] + (size_t)tile * (PF_TK / 8 * DK * 8);
@@ -431,10 +530,10 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
           for (int ks = 0; ks < KS; ++ks) {
             const f16x4 lo = __builtin_bit_cast(
                 f16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                           (s16x4 __attribute__((address_space(3)))*)(xs + xrd[ks][0] + i * 64 + 32 * kh)));
+                           (s16x4 __attribute__((address_space(3)))*)(xs_t + xrd[ks][0] + i * 64 + 32 * kh)));
             const f16x4 hi = __builtin_bit_cast(
                 f16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                           (s16x4 __attribute__((address_space(3)))*)(xs + xrd[ks][1] + i * 64 + 32 * kh)));
+                           (s16x4 __attribute__((address_space(3)))*)(xs_t + xrd[ks][1] + i * 64 + 32 * kh)));
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
               if (H % 32 == 0) {
@@ -460,23 +559,29 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
               if (GH % 16 == 0 || hl < GH) *(float*)(ys + hl * PF_YS_HEAD + yoff[n]) = y[n][hb][v];
             }
       }
-      pending = -1;
+      pending[rs] = -1;
       lds_barrier();                                                       // B2
 
       // ---- stage B: per head scores, softmax, P V ------------------------------------------------
-      const int tile_n = tile_at(min(it + 1, n_mine - 1));      // next tile (clamped: loads stay valid)
-      const bool full = tile < n_full;                          // workgroup-uniform
+      const bool full = tile < n_full_of(rs);                   // workgroup-uniform
       const int jl = j0 + 8 * g;                                // first of my 8 keys
+      const int my_row = min(i0 + PF_ROWS * rs + c, Lq - 1);    // clamped; stores check the row itself
+      const int vis_row = a.causal ? min(Lk, my_row + 1 + shift) : Lk;   // keys visible to my row
 #pragma unroll
       for (int hh = 0; hh < HPW; ++hh) {
+        const int sl = hh * RS + rs;                                   // accumulator slot
+        if (HPW * RS > 2) __builtin_amdgcn_sched_barrier(0);           // keep the heads' chains apart: registers
         // low-rank scores for keys j0 + 8 g + e of row c
         const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-        const int hs = PERSIST ? hh : 0;                               // operand set in use
-        const int hn = PERSIST ? hh : (hh + 1 < HPW ? hh + 1 : 0);     // head it is refilled for
+        const int hs = PERSIST ? hh / SH : 0;                          // operand set in use
+        const int hn = PERSIST ? hh / SH * SH : (hh + 1 < HPW ? hh + 1 : 0);   // head it is refilled for
         const int t_next = PERSIST || hh + 1 == HPW ? tile_n : tile;
-        const f32x4 s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[hs], qop[hh], zero, 0, 0, 0);
-        const f32x4 s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[hs], qop[hh], zero, 0, 0, 0);
-        {
+        // (shared operands are refilled behind the last head that uses them)
+        const bool refill = (RS == 1 || last_slice) && (hh + 1) % SH == 0;   // compile time
+        const bf16x8 qo = qop[QRES ? sl : hh];
+        const f32x4 s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[hs], qo, zero, 0, 0, 0);
+        const f32x4 s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[hs], qo, zero, 0, 0, 0);
+        if (refill) {
           const bf16_t* kt = k_base[hn] + (size_t)t_next * (PF_TK * 32);
           ka[hs] = ld_uv<bf16x8>(kt, k_off);
           kb[hs] = ld_uv<bf16x8>(kt, k_off, 4 * 32 * 2);
@@ -494,7 +599,8 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
           f16x8 hv;
 #pragma unroll
           for (int e = 0; e < 8; ++e) hv[e] = f32_to_half_sat(an[e]);
-          *(f16x8*)(as_ + hh * PF_AS_HEAD + c * PF_AS_ROW + (tile & 1) * 64 + g * 16) = hv;
+          if (XSTG) *(f16x8*)(xs_t + (wv * HPW + hh) * PF_XS_HEAD + c * (2 * PF_TK) + g * 16) = hv;
+          else *(f16x8*)(as_ + sl * PF_AS_HEAD + c * PF_AS_ROW + (tile & 1) * 64 + g * 16) = hv;
         }
         // online softmax, statistics of row c kept by all four lanes 16 g + c; exponentials in
         // base 2: p = 2^(A log2(e) - m log2(e))
@@ -506,14 +612,14 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
         float mx = fmaxf(fmaxf(fmaxf(an[0], an[1]), fmaxf(an[2], an[3])),
                          fmaxf(fmaxf(an[4], an[5]), fmaxf(an[6], an[7])));
         mx = rows_max(mx);
-        const float m_new = fmaxf(m_run[hh], mx);
-        // A row may have seen no key yet: a key share, or a walk downwards from the diagonal, can
-        // start with a tile that lies wholly beyond the row's last visible key (Lk - Lq not a
-        // multiple of 16).  The exponent is then taken against 0 instead of -inf, so alpha and
-        // every p are exactly 0 and the row's state stays (m = -inf, l = 0, o = 0).
+        const float m_new = fmaxf(m_run[sl], mx);
+        // A row may have seen no key yet: a key share, a walk downwards from the diagonal, or a
+        // slice at its own diagonal can meet a tile that lies wholly beyond the row's last visible
+        // key.  The exponent is then taken against 0 instead of -inf, so alpha and every p are
+        // exactly 0 and the row's state stays (m = -inf, l = 0, o = 0).
         const float m2 = (m_new == -INFINITY ? 0.f : m_new) * LOG2E;
-        const float alpha = fast_exp2(m_run[hh] * LOG2E - m2);
-        m_run[hh] = m_new;
+        const float alpha = fast_exp2(m_run[sl] * LOG2E - m2);
+        m_run[sl] = m_new;
         float ps = 0.f;
         bf16x8 pop;
         // SPREAD: the V operands of the first head for the next tile are loaded here, one load
@@ -527,48 +633,59 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
           pop[e] = (__bf16)p;                     // hardware round-to-nearest-even conversion
           if (SPREAD && hh == 1) __builtin_amdgcn_sched_barrier(0);
         }
-        l_run[hh] = l_run[hh] * alpha + ps;       // partial sum over my keys; groups merged at the end
+        l_run[sl] = l_run[sl] * alpha + ps;       // partial sum over my keys; groups merged at the end
         if (__any(alpha != 1.f)) {                // wave-uniform: the running maximum rarely moves
 #pragma unroll
           for (int nb = 0; nb < DK / 16; ++nb)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) o[hh][nb][v] *= alpha;
+            for (int v = 0; v < 4; ++v) o[sl][nb][v] *= alpha;
         }
         const bf16_t* vt = v_base[hn] + (size_t)t_next * (PF_TK / 8 * DK * 8);
 #pragma unroll
         for (int nb = 0; nb < DK / 16; ++nb) {
-          o[hh][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[hs][nb], pop, o[hh][nb], 0, 0, 0);
-          if (!SPREAD) vop[hs][nb] = ld_uv<bf16x8>(vt, v_off, nb * 256);
+          o[sl][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[hs][nb], pop, o[sl][nb], 0, 0, 0);
+          if (!SPREAD && refill) vop[hs][nb] = ld_uv<bf16x8>(vt, v_off, nb * 256);
         }
       }
       // A_n is written once both tiles of a pair are staged (64-byte pieces of a line reach HBM at
-      // half the rate of whole lines): after the odd tile when walking upwards (or after an even
-      // tile without a partner), after the even tile when walking downwards.
-      if (a.scores && (rep ? (tile & 1) == 0 : ((tile & 1) == 1 || tile + 1 >= n_tiles_all))) pending = tile;
-      // every wave left stage A(tile), the last reader of xs, before B2; stage A(tile+1) reads the
-      // new tile after B1
-      store_x(xr);
-    }
-    if (pending >= 0) {
+      // half the rate of whole lines): after the odd tile when walking upwards (or after the
+      // slice's last tile, which may have no partner), after the even tile when walking downwards.
+      if (a.scores && (rep ? (tile & 1) == 0 : ((tile & 1) == 1 || tile >= last_tile_of(rs)))) pending[rs] = tile;
+      if (XSTG && pending[rs] >= 0) {
+        // the pair sits in the two A_{n-1} buffers, which the next pieces are about to overwrite
 #pragma unroll
-      for (int hh = 0; hh < HPW; ++hh) flush_scores(pending, hh);
+        for (int hh = 0; hh < HPW; ++hh) flush_scores(pending[rs], hh, rs);
+        pending[rs] = -1;
+      }
+      // every wave left stage A of this step, the last reader of xs, before B2; stage A of the
+      // next step reads the new piece after B1
+      store_x(xr, x_tile);
+      }
+    }
+#pragma unroll
+    for (int rs = 0; rs < RS; ++rs) {
+      if (pending[rs] >= 0) {
+#pragma unroll
+        for (int hh = 0; hh < HPW; ++hh) flush_scores(pending[rs], hh, rs);
+      }
     }
 
     // ---- epilogue ----------------------------------------------------------------------------------
     if (a.split > 1) {
       // unnormalised partial (o, m, l) of this key share; k_prefill_combine merges the shares
+      // (RS = 1 only: the host never splits the keys of wider row blocks)
 #pragma unroll
       for (int hh = 0; hh < HPW; ++hh) {
         const int h = h_first + hh;
-        const float l = rows_sum(l_run[hh]);
-        const size_t row = (((size_t)sp * gridDim.y + b) * a.Lqp + i0 + c) * H + h;
+        const float l = rows_sum(l_run[hh * RS]);
+        const size_t row = (((size_t)sp * a.B + b) * a.Lqp + i0 + c) * H + h;
         if (g == 0) {
-          a.part_ml[row * 2] = m_run[hh];
+          a.part_ml[row * 2] = m_run[hh * RS];
           a.part_ml[row * 2 + 1] = l;
         }
 #pragma unroll
         for (int nb = 0; nb < DK / 16; ++nb) {
-          const f32x4 acc = o[hh][nb];
+          const f32x4 acc = o[hh * RS][nb];
           *(float4*)(a.part_o + row * DK + nb * 16 + 4 * g) = make_float4(acc[0], acc[1], acc[2], acc[3]);
         }
       }
@@ -577,21 +694,25 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
     // O[row][h][d] = o / l
 #pragma unroll
     for (int hh = 0; hh < HPW; ++hh) {
-      const int h = h_first + hh;
-      const float inv = 1.f / rows_sum(l_run[hh]);
-      if (i0 + c < Lq) {
-        const size_t at = (((size_t)b * Lq + i0 + c) * H + h) * DK + 4 * g;
 #pragma unroll
-        for (int nb = 0; nb < DK / 16; ++nb) {
-          const f32x4 acc = o[hh][nb];
-          if (a.out_f32) {
-            *(float4*)((float*)a.out + at + nb * 16) =
-                make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
-          } else {
-            uint2 pk;
-            pk.x = f32_to_bf16_bits(acc[0] * inv) | (f32_to_bf16_bits(acc[1] * inv) << 16);
-            pk.y = f32_to_bf16_bits(acc[2] * inv) | (f32_to_bf16_bits(acc[3] * inv) << 16);
-            *(uint2*)((bf16_t*)a.out + at + nb * 16) = pk;
+      for (int rs = 0; rs < RS; ++rs) {
+        const int h = h_first + hh, sl = hh * RS + rs;
+        const float inv = 1.f / rows_sum(l_run[sl]);
+        const int row = i0 + PF_ROWS * rs + c;
+        if (row < Lq) {
+          const size_t at = (((size_t)b * Lq + row) * H + h) * DK + 4 * g;
+#pragma unroll
+          for (int nb = 0; nb < DK / 16; ++nb) {
+            const f32x4 acc = o[sl][nb];
+            if (a.out_f32) {
+              *(float4*)((float*)a.out + at + nb * 16) =
+                  make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
+            } else {
+              uint2 pk;
+              pk.x = f32_to_bf16_bits(acc[0] * inv) | (f32_to_bf16_bits(acc[1] * inv) << 16);
+              pk.y = f32_to_bf16_bits(acc[2] * inv) | (f32_to_bf16_bits(acc[3] * inv) << 16);
+              *(uint2*)((bf16_t*)a.out + at + nb * 16) = pk;
+            }
           }
         }
       }

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -24,7 +25,7 @@ namespace {
 thread_local char g_hip_err[256] = "";
 thread_local const char* g_path = "";
 // lisa_tune_set(): geometry overrides of the calling thread, -1 = the library's own choice
-thread_local int g_tune[LISA_TUNE_COUNT] = {-1, -1, -1, -1, -1};
+thread_local int g_tune[LISA_TUNE_COUNT] = {-1, -1, -1, -1, -1, -1};
 
 // ---- static scratch of lisa_attn_decode_static ------------------------------------------
 // Device memory that exists from the moment the code object is loaded on a GPU until the process
@@ -372,6 +373,7 @@ bool decode_fast_ok(const lisa_desc* d, bool lisa_layer) {
   if (d->d_k != 64 && d->d_k != 128) return false;
   if (d->H > 64) return false;
   if (lisa_layer) {
+    if (d->mix == LISA_MIX_SHARE) return true;             // direct sharing: the previous row as it stands
     if (d->mix == LISA_MIX_CONCAT)                         // the instantiated CONCAT shapes
       return (d->act == LISA_ACT_RELU || d->act == LISA_ACT_SILU) && d->H <= 48 && d->F <= 256 && d->r <= 64;
     if (d->mix != LISA_MIX_ADD || (d->act != LISA_ACT_RELU && d->act != LISA_ACT_SILU)) return false;
@@ -396,7 +398,7 @@ int launch_decode_part_dk(const lisa_desc* d, const DecodeArgs& a, size_t lds, h
                                        (int)lds);
     if (e != hipSuccess) return hip_fail(e);
   }
-  StageScope prof(LISA_MODE ? "k_decode_part_lisa" : "k_decode_part_std", st);
+  StageScope prof(LISA_MODE == 3 ? "k_decode_part_share" : LISA_MODE ? "k_decode_part_lisa" : "k_decode_part_std", st);
   kern<<<grid, DEC_THREADS, lds, st>>>(a);
   return check_launch();
 }
@@ -442,7 +444,10 @@ int run_decode_fast(const lisa_desc* d, bool lisa_layer, DecodeArgs a, void* out
   a.n_chunk = decode_chunks(d);
   size_t lds = (size_t)d->H * DEC_CK * sizeof(float);
   int rc;
-  if (lisa_layer && d->mix == LISA_MIX_CONCAT) {
+  if (lisa_layer && d->mix == LISA_MIX_SHARE) {
+    a.scale = 0.f;
+    rc = launch_decode_part_dk<3, 1, 1>(d, a, lds, st);
+  } else if (lisa_layer && d->mix == LISA_MIX_CONCAT) {
     const int hbi = d->H <= 16 ? 2 : d->H <= 32 ? 4 : 6, fs = d->F <= 64 ? 2 : d->F <= 128 ? 4 : 8;
     const int ks1 = (hbi + 1) / 2, hbo = (hbi + 1) / 2;
     lds += (size_t)((d->H * d->r + 3) & ~3) * sizeof(float) + (size_t)(2 * fs * ks1 + hbo * fs) * 1024;
@@ -497,49 +502,76 @@ bool prefill_fused_ok(const lisa_desc* d) {
 }
 
 
-// Head groups (grid.z) of the instantiation that run_prefill_fused picks.  H = 32 (16) runs as
-// two (one) groups of 16 heads, two heads per wave, when that alone gives two units of work per
-// compute unit; smaller problems take groups of 8 (one head per wave): the first FFN layer is
-// then computed once more per extra group, but fewer or no key splits, partial results and
-// combine passes are needed.
-int prefill_groups(const lisa_desc* d) {
-  if (d->H == 40) return 5;
-  if (d->H != 32 && d->H != 16) return 1;
-  const int few = d->H / 16, many = d->H / 8;              // groups of 16 heads or of 8
-  const long long row_blocks = (long long)((d->Lq + PF_ROWS - 1) / PF_ROWS) * d->B;
-  if (g_tune[LISA_TUNE_PREFILL_GROUPS] >= 0) return g_tune[LISA_TUNE_PREFILL_GROUPS] == many ? many : few;
+// Geometry of the fused prefill launch: row slices per workgroup (R = 16 * slices query rows), head
+// groups, key splits, paired units.
+//   slices  A workgroup of R rows fetches each K_LR / V tile once for all its rows: 4 slices where
+//           the problem still gives every compute unit several units of work (>= 1024 units), which
+//           needs one head per wave (groups of 8 heads); ReLU layers with 33..96 hidden units.
+//   groups  H = 32 (16) runs as two (one) groups of 16 heads, two heads per wave, or as four (two)
+//           groups of 8, one head per wave: the first FFN layer is computed once more per extra
+//           group, but there are more units (no key splits, partial results and combine passes on
+//           small problems) and row slices become possible.
+//   split   small problems have too few units to fill the chip and their longest unit (the last
+//           row block) sets the run time: the key tiles of a row block are dealt to 2 or 4 units.
+//   pair    two units (a long and a short one) per workgroup once that still leaves two workgroups
+//           per compute unit: equal work per workgroup, FFN weights staged once for both.
+struct PrefillGeom {
+  int slices, groups, split, pair;
+};
+
+bool prefill_slices_ok(const lisa_desc* d) {
+  return d->act == LISA_ACT_RELU && d->F > 32 && d->F <= 96 && (d->H == 8 || d->H == 16 || d->H == 32 || d->H == 40);
+}
+
+PrefillGeom prefill_geom(const lisa_desc* d) {
+  PrefillGeom g{1, 1, 1, 0};
+  const long long blocks16 = (long long)((d->Lq + PF_ROWS - 1) / PF_ROWS) * d->B;
+  const int few = d->H == 40 ? 5 : d->H == 32 ? 2 : 1;      // groups of 16 heads (H = 40, 8: of 8)
+  const int many = d->H / 8;
+  const bool two_forms = d->H == 32 || d->H == 16;
+  // H = 32 with key/value heads shared by (a multiple of) four query heads can keep the whole layer
+  // of a row block in one workgroup, a wave per group of four heads.  It is correct and tested but
+  // never chosen: its 128 accumulator registers per lane leave the compiler 50 short (spills), and
+  // it measured 11.8 ms against 7.6 ms for two groups of 16 on the LLaMA3-8B shape at L = 8192.
+  const bool whole_ok = d->H == 32 && (d->H / d->Hkv) % 4 == 0;
+  const bool large = blocks16 * few >= 2 * kComputeUnits;
+  if (prefill_slices_ok(d)) {
+    // two slices where the problem still gives every compute unit several units of work; not where
+    // groups of 16 heads, two per wave, are the alternative (measured with two slices against two
+    // groups: 10.2 / 7.6 ms on the LLaMA3-8B shape, where the pair of heads shares its operands;
+    // 2.8 / 2.5 ms on LLaMA2-7B heads at B = 4, L = 4096; on the LLaMA2-13B shape, which has no
+    // such form, 8.5 ms with two slices against 9.3 ms with one).  Four slices exist and are
+    // tested, but their 128 accumulators spill: 16 - 20 ms on the same shapes.
+    if (!(two_forms && large) && (long long)((d->Lq + 31) / 32) * d->B * many >= 4 * kComputeUnits) g.slices = 2;
+    const int forced = g_tune[LISA_TUNE_PREFILL_SLICES];
+    if (forced == 1 || forced == 2 || forced == 4) g.slices = forced;
+  }
+  const int want = g_tune[LISA_TUNE_PREFILL_GROUPS];
+  if (d->H == 24) g.groups = 1;
+  else if (whole_ok && g.slices == 1 && want == 1) g.groups = 1;
+  else if (!two_forms || g.slices > 1) g.groups = many;
+  else if (want >= 0) g.groups = want == many ? many : few;
   // SiLU costs two quarter-rate instructions per hidden unit, once more per extra group: measured
   // 0.27 ms with two groups (and a key split) against 0.32 ms with four on the LLaMA2-7B shape.
-  if (d->act == LISA_ACT_SILU) return few;
-  return row_blocks * few >= 2 * kComputeUnits ? few : many;
+  else if (d->act == LISA_ACT_SILU) g.groups = few;
+  else g.groups = large ? few : many;
+  const long long units = (long long)((d->Lq + 16 * g.slices - 1) / (16 * g.slices)) * d->B * g.groups;
+  if (g.slices == 1) {
+    const int tiles_max = (d->Lk + PF_TK - 1) / PF_TK;
+    while (g.split < 4 && units * g.split < 2 * kComputeUnits && tiles_max / (2 * g.split) >= 4) g.split *= 2;
+    const int forced = g_tune[LISA_TUNE_PREFILL_SPLIT];
+    if (forced == 1 || forced == 2 || forced == 4) g.split = forced;
+  }
+  g.pair = units * g.split >= 2 * kComputeUnits;
+  if (g_tune[LISA_TUNE_PREFILL_PAIR] >= 0) g.pair = g_tune[LISA_TUNE_PREFILL_PAIR] != 0;
+  return g;
 }
 
 struct PrefillWs {
   size_t qp, kp, vt, part_o, part_ml, total;   // byte offsets in the workspace
-  int Lqp, Lkp, split;
+  int Lqp, Lkp;
+  PrefillGeom geom;
 };
-
-// Key splits per row block: small problems have too few (row block, head group) units to
-// fill the chip and their longest unit (the last row block) sets the run time.
-int prefill_split(const lisa_desc* d, int Lqp) {
-  const int groups = prefill_groups(d);
-  const long long units = (long long)(Lqp / PF_ROWS) * d->B * groups;
-  const int tiles_max = (d->Lk + PF_TK - 1) / PF_TK;
-  int s = 1;
-  while (s < 4 && units * s < 2 * kComputeUnits && tiles_max / (2 * s) >= 4) s *= 2;
-  const int forced = g_tune[LISA_TUNE_PREFILL_SPLIT];
-  if (forced == 1 || forced == 2 || forced == 4) s = forced;
-  return s;
-}
-
-// Two units (a long and a short one) per workgroup once that still leaves two workgroups per
-// compute unit: equal work per workgroup, FFN weights staged once for both.
-int prefill_pair(const lisa_desc* d, int Lqp, int split) {
-  const int groups = prefill_groups(d);
-  const long long units = (long long)(Lqp / PF_ROWS) * split * d->B * groups;
-  if (g_tune[LISA_TUNE_PREFILL_PAIR] >= 0) return g_tune[LISA_TUNE_PREFILL_PAIR] != 0;
-  return units >= 2 * kComputeUnits;
-}
 
 PrefillWs prefill_fused_ws(const lisa_desc* d) {
   PrefillWs w;
@@ -549,49 +581,66 @@ PrefillWs prefill_fused_ws(const lisa_desc* d) {
   w.kp = w.qp + round_up((size_t)d->B * d->H * w.Lqp * 32 * 2, 256);
   w.vt = w.kp + round_up((size_t)d->B * d->Hkv * w.Lkp * 32 * 2, 256);
   w.part_o = w.vt + round_up((size_t)d->B * d->Hkv * d->d_k * w.Lkp * 2, 256);
-  w.split = prefill_split(d, w.Lqp);
-  const size_t rows = w.split > 1 ? (size_t)w.split * d->B * w.Lqp * d->H : 0;
+  w.geom = prefill_geom(d);
+  const size_t rows = w.geom.split > 1 ? (size_t)w.geom.split * d->B * w.Lqp * d->H : 0;
   w.part_ml = w.part_o + round_up(rows * d->d_k * sizeof(float), 256);
   w.total = w.part_ml + round_up(rows * 2 * sizeof(float), 256);
   return w;
 }
 
-template <int NG, int FS, int HPW, int NW, int ACT>
+template <int NG, int FS, int HPW, int NW, int ACT, int RS, int SHG = 0>
 int launch_prefill_fused_t(const lisa_desc* d, const PrefillArgs& a, hipStream_t st) {
   constexpr int GH = NW * HPW, H = NG * GH;
   typedef MfmaFfn<(H + 15) / 16, FS, (GH + 15) / 16> Ffn;
-  const size_t lds = (size_t)H * PF_XS_HEAD + (size_t)GH * PF_YS_HEAD + Ffn::kStageBytes + (size_t)GH * PF_AS_HEAD;
-  auto kern = k_lisa_prefill_fused<NG, FS, HPW, NW, ACT>;
+  // (all heads in one workgroup: the A_{n-1} piece is double buffered and doubles as A_n staging)
+  constexpr bool XSTG = NG == 1 && HPW == 4;
+  constexpr size_t lds = XSTG ? (size_t)2 * H * PF_XS_HEAD + (size_t)GH * PF_YS_HEAD + Ffn::kStageBytes
+                              : (size_t)H * PF_XS_HEAD + (size_t)GH * PF_YS_HEAD + Ffn::kStageBytes +
+                                    (size_t)GH * RS * PF_AS_HEAD;
+  static_assert(lds <= 160 * 1024, "LDS of one compute unit");
+  auto kern = k_lisa_prefill_fused<NG, FS, HPW, NW, ACT, RS, SHG>;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)lds);
   if (e != hipSuccess) return hip_fail(e);
-  const int units = a.Lqp / PF_ROWS * a.split;
-  dim3 grid(a.pair ? (units + 1) / 2 : units, d->B, NG);
+  const long long units = (long long)((a.Lq + PF_ROWS * RS - 1) / (PF_ROWS * RS)) * a.split;
+  const long long chunks = ((a.pair ? (units + 1) / 2 : units) + 7) / 8 * a.B;   // 8 neighbouring units each
+  const long long wgs = (chunks + 7) / 8 * 8 * 8 * NG;
+  if (wgs > 0x7fffffffLL) return LISA_ERR_UNSUPPORTED;
   StageScope prof("k_lisa_prefill_fused", st);
-  kern<<<grid, NW * 64, lds, st>>>(a);
+  kern<<<dim3((unsigned)wgs), NW * 64, lds, st>>>(a);
   return check_launch();
-
 }
 
-template <int NG, int HPW, int NW, int ACT>
+template <int NG, int HPW, int NW, int ACT, int RS, int SHG = 0>
 int launch_prefill_fused_act(const lisa_desc* d, const PrefillArgs& a, hipStream_t st) {
+  if (RS > 1)                                                // row slices: 33..96 hidden units (prefill_slices_ok)
+    return (d->F + 31) / 32 == 2 ? launch_prefill_fused_t<NG, 2, HPW, NW, ACT, RS, SHG>(d, a, st)
+                                 : launch_prefill_fused_t<NG, 3, HPW, NW, ACT, RS, SHG>(d, a, st);
   switch ((d->F + 31) / 32) {
-    case 1: return launch_prefill_fused_t<NG, 1, HPW, NW, ACT>(d, a, st);
-    case 2: return launch_prefill_fused_t<NG, 2, HPW, NW, ACT>(d, a, st);
-    case 3: return launch_prefill_fused_t<NG, 3, HPW, NW, ACT>(d, a, st);
-    default: return launch_prefill_fused_t<NG, 4, HPW, NW, ACT>(d, a, st);
+    case 1: return launch_prefill_fused_t<NG, 1, HPW, NW, ACT, 1, SHG>(d, a, st);
+    case 2: return launch_prefill_fused_t<NG, 2, HPW, NW, ACT, 1, SHG>(d, a, st);
+    case 3: return launch_prefill_fused_t<NG, 3, HPW, NW, ACT, 1, SHG>(d, a, st);
+    default: return launch_prefill_fused_t<NG, 4, HPW, NW, ACT, 1, SHG>(d, a, st);
   }
 }
 template <int NG, int HPW, int NW>
-int launch_prefill_fused_fs(const lisa_desc* d, const PrefillArgs& a, hipStream_t st) {
-  return d->act == LISA_ACT_SILU ? launch_prefill_fused_act<NG, HPW, NW, 1>(d, a, st)
-                                 : launch_prefill_fused_act<NG, HPW, NW, 0>(d, a, st);
+int launch_prefill_fused_fs(const lisa_desc* d, const PrefillArgs& a, int slices, hipStream_t st) {
+  if (HPW == 1 && slices == 4) return launch_prefill_fused_act<NG, 1, NW, 0, 4>(d, a, st);
+  if (HPW == 1 && slices == 2) return launch_prefill_fused_act<NG, 1, NW, 0, 2>(d, a, st);
+  // the heads of a wave share their key/value head: one operand set for all of them
+  constexpr int HS = HPW == 3 ? 2 : HPW;                     // (no shared form of the 24-head kernel)
+  if (HPW > 1 && HPW != 3 && (d->H / d->Hkv) % HPW == 0)
+    return d->act == LISA_ACT_SILU ? launch_prefill_fused_act<NG, HS, NW, 1, 1, HS>(d, a, st)
+                                   : launch_prefill_fused_act<NG, HS, NW, 0, 1, HS>(d, a, st);
+  return d->act == LISA_ACT_SILU ? launch_prefill_fused_act<NG, HPW, NW, 1, 1>(d, a, st)
+                                 : launch_prefill_fused_act<NG, HPW, NW, 0, 1>(d, a, st);
 }
 
 int run_prefill_fused(const lisa_desc* d, const void* q_lr, const void* k_lr, const void* v,
                       const void* prev, const void* w1, const void* w2, void* out, void* scores,
                       void* workspace, hipStream_t st) {
   const PrefillWs w = prefill_fused_ws(d);
+  const PrefillGeom& geo = w.geom;
   char* ws = (char*)workspace;
   PrefillArgs a{};
   a.qp = (const bf16_t*)(ws + w.qp);
@@ -602,6 +651,7 @@ int run_prefill_fused(const lisa_desc* d, const void* q_lr, const void* k_lr, co
   a.w2 = (const bf16_t*)w2;
   a.scores = (half_t*)scores;
   a.out = out;
+  a.B = d->B;
   a.H = d->H;
   a.Hkv = d->Hkv;
   a.Lq = d->Lq;
@@ -612,8 +662,8 @@ int run_prefill_fused(const lisa_desc* d, const void* q_lr, const void* k_lr, co
   a.causal = d->causal;
   a.out_f32 = d->out_f32;
   a.dscale = pick_scale(d->delta_scale, d->r);
-  a.split = w.split;
-  a.pair = prefill_pair(d, w.Lqp, w.split);
+  a.split = geo.split;
+  a.pair = geo.pair;
   a.part_o = (float*)(ws + w.part_o);
   a.part_ml = (float*)(ws + w.part_ml);
   {
@@ -630,15 +680,18 @@ int run_prefill_fused(const lisa_desc* d, const void* q_lr, const void* k_lr, co
   }
   int rc;
   switch (d->H) {
-    case 8: rc = launch_prefill_fused_fs<1, 1, 8>(d, a, st); break;    // one group of 8 heads
+    case 8: rc = launch_prefill_fused_fs<1, 1, 8>(d, a, geo.slices, st); break;    // one group of 8 heads
     case 16:                                                            // one group of 16 or two of 8
-      rc = prefill_groups(d) == 2 ? launch_prefill_fused_fs<2, 1, 8>(d, a, st) : launch_prefill_fused_fs<1, 2, 8>(d, a, st);
+      rc = geo.groups == 2 ? launch_prefill_fused_fs<2, 1, 8>(d, a, geo.slices, st)
+                           : launch_prefill_fused_fs<1, 2, 8>(d, a, 1, st);
       break;
-    case 24: rc = launch_prefill_fused_fs<1, 3, 8>(d, a, st); break;   // one group of 24
-    case 32:                                                            // two groups of 16 or four of 8
-      rc = prefill_groups(d) == 4 ? launch_prefill_fused_fs<4, 1, 8>(d, a, st) : launch_prefill_fused_fs<2, 2, 8>(d, a, st);
+    case 24: rc = launch_prefill_fused_fs<1, 3, 8>(d, a, 1, st); break;   // one group of 24
+    case 32:                                                   // two groups of 16, four of 8, or all 32 heads
+      rc = geo.groups == 4   ? launch_prefill_fused_fs<4, 1, 8>(d, a, geo.slices, st)
+           : geo.groups == 1 ? launch_prefill_fused_fs<1, 4, 8>(d, a, 1, st)
+                             : launch_prefill_fused_fs<2, 2, 8>(d, a, 1, st);
       break;
-    default: rc = launch_prefill_fused_fs<5, 1, 8>(d, a, st); break;   // H = 40: five groups of 8
+    default: rc = launch_prefill_fused_fs<5, 1, 8>(d, a, geo.slices, st); break;   // H = 40: five groups of 8
   }
   if (rc == LISA_OK && a.split > 1) {
     dim3 grid(d->Lq, d->B);
@@ -984,9 +1037,10 @@ size_t lisa_workspace_bytes(const lisa_desc* desc, int which) {
     case LISA_WS_DECODE: {
       if (check_decode(desc) != LISA_OK) return 0;
       lisa_desc eq;
+      if (decode_fast_ok(desc, true)) return decode_fast_bytes(desc);
       if (relu_equivalent(desc, &eq) && decode_fast_ok(&eq, true))
         return round_up(decode_fast_bytes(&eq), 256) + synth_ffn_bytes(desc);
-      return decode_fast_ok(desc, true) ? decode_fast_bytes(desc) : exact_bytes(desc);
+      return exact_bytes(desc);
     }
     case LISA_WS_STD:
       if (check_common(desc) != LISA_OK) return 0;
@@ -1300,6 +1354,99 @@ int lisa_attn_decode_static(const lisa_desc* desc, const void* q_lr, const void*
                        score_row_out, ws, (hipStream_t)hip_stream);
   g_prof_on = prof;
   return rc;
+}
+
+// ---- a decode step through a stack of layers (Sec. 5.1: which layers share attention) -------------
+namespace {
+struct StackWs {
+  size_t rows, layer, total;      // byte offsets: two score rows, then the per-layer workspace
+};
+// Descriptors of the three kinds of layer, derived from the LiSA layer's.
+void stack_descs(const lisa_desc* d, lisa_desc* std_d, lisa_desc* share_d) {
+  *std_d = *d;
+  std_d->mix = LISA_MIX_ADD;
+  std_d->act = LISA_ACT_RELU;
+  std_d->r = 0;
+  std_d->F = 0;
+  std_d->write_scores = 0;
+  std_d->kcache_dim_major = 0;
+  *share_d = *d;
+  share_d->mix = LISA_MIX_SHARE;
+}
+StackWs stack_ws(const lisa_desc* d) {
+  lisa_desc sd, hd;
+  stack_descs(d, &sd, &hd);
+  StackWs w;
+  w.rows = 0;
+  w.layer = round_up(2 * scores_bytes(d), 256);
+  const size_t a = lisa_workspace_bytes(d, LISA_WS_DECODE), b = lisa_workspace_bytes(&hd, LISA_WS_DECODE),
+               c = lisa_workspace_bytes(&sd, LISA_WS_STD);
+  w.total = w.layer + round_up(std::max(a, std::max(b, c)), 256);
+  return w;
+}
+}  // namespace
+
+size_t lisa_stack_workspace_bytes(const lisa_desc* desc) {
+  if (check_decode(desc) != LISA_OK) return 0;
+  return stack_ws(desc).total;
+}
+
+int lisa_decode_stack(const lisa_desc* desc, const lisa_stack_layer* layers, int32_t n_layers, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+  int rc = check_decode(desc);
+  if (rc) return rc;
+  if (!layers) return LISA_ERR_NULL;
+  if (n_layers < 1) return LISA_ERR_SHAPE;
+  if (desc->mix == LISA_MIX_SHARE) return LISA_ERR_SHAPE;   // (direct sharing is a kind of layer, not of stack)
+  // the whole stack is checked on the host before the first launch
+  for (int n = 0; n < n_layers; ++n) {
+    const lisa_stack_layer& ly = layers[n];
+    if (ly.kind < LISA_LAYER_STD || ly.kind > LISA_LAYER_SHARE) return LISA_ERR_SHAPE;
+    if (n == 0 && ly.kind != LISA_LAYER_STD) return LISA_ERR_SHAPE;   // a sharing layer needs a front layer
+    if (!ly.v_cache || !ly.out) return LISA_ERR_NULL;
+    if (ly.kind != LISA_LAYER_SHARE && (!ly.q || !ly.k_cache)) return LISA_ERR_NULL;
+    if (ly.kind == LISA_LAYER_LISA && ((has_ffn(desc) && !ly.w1) || (has_w2(desc) && !ly.w2))) return LISA_ERR_NULL;
+    const void* ptrs[] = {ly.q, ly.k_cache, ly.v_cache, ly.w1, ly.w2, ly.out, ly.score_row};
+    for (const void* p : ptrs)
+      if (p && !aligned16(p)) return LISA_ERR_ALIGN;
+  }
+  if (!workspace) return LISA_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return LISA_ERR_ALIGN;
+  const StackWs w = stack_ws(desc);
+  if (workspace_bytes < w.total) return LISA_ERR_WORKSPACE;
+  lisa_desc std_d, share_d;
+  stack_descs(desc, &std_d, &share_d);
+  char* ws = (char*)workspace;
+  void* own[2] = {ws + w.rows, ws + w.rows + scores_bytes(desc)};
+  void* lws = ws + w.layer;
+  const size_t lws_bytes = w.total - w.layer;
+  const void* cur = nullptr;                                 // the row A_{n-1} that the next layer may share
+  for (int n = 0; n < n_layers; ++n) {
+    const lisa_stack_layer& ly = layers[n];
+    const bool next_shares = n + 1 < n_layers && layers[n + 1].kind != LISA_LAYER_STD;
+    void* dst = ly.score_row ? ly.score_row : (cur == own[0] ? own[1] : own[0]);
+    if (ly.kind == LISA_LAYER_STD) {
+      // its row is emitted only if somebody reads it
+      const bool emit = next_shares || ly.score_row;
+      rc = std_attn_scores(&std_d, ly.q, ly.k_cache, ly.v_cache, emit ? dst : nullptr, ly.out, lws, lws_bytes,
+                           hip_stream);
+      cur = emit ? dst : nullptr;
+    } else if (ly.kind == LISA_LAYER_LISA) {
+      lisa_desc d = *desc;
+      d.write_scores = next_shares || ly.score_row;
+      rc = lisa_attn_decode(&d, ly.q, nullptr, nullptr, ly.k_cache, ly.v_cache, cur, ly.w1, ly.w2, ly.out,
+                            d.write_scores ? dst : nullptr, lws, lws_bytes, hip_stream);
+      cur = d.write_scores ? dst : nullptr;
+    } else {
+      // direct sharing: A_n = A_{n-1}; the row passes through untouched unless the caller wants a copy
+      share_d.write_scores = ly.score_row != nullptr;
+      rc = lisa_attn_decode(&share_d, nullptr, nullptr, nullptr, nullptr, ly.v_cache, cur, nullptr, nullptr, ly.out,
+                            share_d.write_scores ? dst : nullptr, lws, lws_bytes, hip_stream);
+      if (share_d.write_scores) cur = dst;
+    }
+    if (rc) return rc;
+  }
+  return LISA_OK;
 }
 
 int std_attn_scores(const lisa_desc* desc, const void* q, const void* k, const void* v,

@@ -28,8 +28,9 @@ EXPORTS = (
     "lisa_strerror", "lisa_last_hip_error", "lisa_last_path", "lisa_profile_enable",
     "lisa_profile_collect", "lisa_cache_fill", "lisa_project_qkv", "lisa_layer_prefill",
     "lisa_layer_offsets", "lisa_layer_decode", "lisa_tune_set", "lisa_attn_decode_static",
+    "lisa_decode_stack", "lisa_stack_workspace_bytes",
 )
-TUNE_PREFILL_GROUPS, TUNE_PREFILL_SPLIT, TUNE_PREFILL_PAIR, TUNE_STD_PAIR, TUNE_PROJECT_TN = range(5)
+TUNE_PREFILL_GROUPS, TUNE_PREFILL_SPLIT, TUNE_PREFILL_PAIR, TUNE_STD_PAIR, TUNE_PROJECT_TN, TUNE_PREFILL_SLICES = range(6)
 
 
 class LisaError(RuntimeError):
@@ -59,6 +60,15 @@ class ProjDesc(C.Structure):
         ("Lmax", C.c_int32), ("pos0", C.c_int32), ("kcache_dim_major", C.c_int32),
         ("rope_theta", C.c_float),
     ]
+
+
+LAYER_STD, LAYER_LISA, LAYER_SHARE = 0, 1, 2
+
+
+class StackLayer(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("reserved", C.c_int32), ("q", C.c_void_p), ("k_cache", C.c_void_p),
+                ("v_cache", C.c_void_p), ("w1", C.c_void_p), ("w2", C.c_void_p), ("out", C.c_void_p),
+                ("score_row", C.c_void_p)]
 
 
 class StageTime(C.Structure):
@@ -112,6 +122,10 @@ def _lib():
         h.lisa_layer_decode.restype = C.c_int
         h.lisa_layer_offsets.argtypes = [dp] + [C.POINTER(sz)] * 3
         h.lisa_layer_offsets.restype = C.c_int
+        h.lisa_decode_stack.argtypes = [dp, C.POINTER(StackLayer), C.c_int32, vp, sz, vp]
+        h.lisa_decode_stack.restype = C.c_int
+        h.lisa_stack_workspace_bytes.argtypes = [dp]
+        h.lisa_stack_workspace_bytes.restype = sz
         h.lisa_tune_set.argtypes = [C.c_int, C.c_int]
         h.lisa_tune_set.restype = C.c_int
         h.lisa_profile_collect.argtypes = [C.POINTER(StageTime), C.c_int]
@@ -163,7 +177,8 @@ class tune:
 
     def __init__(self, **knobs):
         names = {"prefill_groups": TUNE_PREFILL_GROUPS, "prefill_split": TUNE_PREFILL_SPLIT,
-                 "prefill_pair": TUNE_PREFILL_PAIR, "std_pair": TUNE_STD_PAIR, "project_tn": TUNE_PROJECT_TN}
+                 "prefill_pair": TUNE_PREFILL_PAIR, "std_pair": TUNE_STD_PAIR, "project_tn": TUNE_PROJECT_TN,
+                 "prefill_slices": TUNE_PREFILL_SLICES}
         self.knobs = [(names[k], int(v)) for k, v in knobs.items()]
 
     def __enter__(self):
@@ -493,3 +508,65 @@ def lisa_attn_decode(q_lr, k_lr_cache, v_cache, Lk, score_row_prev, w1, w2, *, k
     if rc:
         raise LisaError(rc, "lisa_attn_decode_static" if static_scratch else "lisa_attn_decode")
     return out, (score_row_out if write_scores else None)
+
+
+def stack_workspace_bytes(desc: Desc) -> int:
+    return int(_lib().lisa_stack_workspace_bytes(C.byref(desc)))
+
+
+class DecodeStack:
+    """Marshals one decode step through a stack of attention layers (lisa_decode_stack).
+
+    `layers`: list of dicts with key "kind" (LAYER_STD | LAYER_LISA | LAYER_SHARE) and tensors
+    "q" (STD: q [B,H,d_k]; LISA: q_lr [B,H,r]), "k_cache" (STD: K cache; LISA: K_LR cache),
+    "v_cache" [B,Hkv,Lmax,d_k], "w1", "w2" (LISA), optional "out" [B,H,d_k] float32 and
+    "score_row" [B,H,Lk].  The array of layer records is built once; step() only makes the call."""
+
+    def __init__(self, layers, Lk, *, r, F, dim_major=True, mix=MIX_ADD, act=ACT_RELU, keep_rows=False):
+        v0 = layers[0]["v_cache"]
+        B, Hkv, Lmax, dk = v0.shape
+        H = layers[0]["q"].shape[1]
+        dt = v0.dtype
+        self.sdt = score_dtype(dt)
+        self.desc = make_desc(dt, B, H, Hkv, 1, Lk, dk, r, F, mix=mix, act=act, kcache_dim_major=int(dim_major),
+                              Lmax=Lmax, out_f32=1)
+        self.outs, self.rows, self._keep = [], [], []
+        arr = (StackLayer * len(layers))()
+        for n, ly in enumerate(layers):
+            out = ly.get("out")
+            if out is None:
+                out = torch.empty((B, H, dk), dtype=torch.float32, device=v0.device)
+            row = ly.get("score_row")
+            if row is None and keep_rows:
+                row = torch.empty((B, H, Lk), dtype=self.sdt, device=v0.device)
+            kind = ly["kind"]
+            kshape = None
+            if kind == LAYER_STD:
+                kshape = (B, Hkv, Lmax, dk)
+            elif kind == LAYER_LISA:
+                kshape = (B, Hkv, r, Lmax) if dim_major else (B, Hkv, Lmax, r)
+            share = kind == LAYER_SHARE
+            arr[n] = StackLayer(
+                kind, 0,
+                None if share else _ptr(ly["q"], "q", (B, H, dk if kind == LAYER_STD else r), dt),
+                None if share else _ptr(ly["k_cache"], "k_cache", kshape, dt),
+                _ptr(ly["v_cache"], "v_cache", (B, Hkv, Lmax, dk), dt),
+                _ptr(ly.get("w1"), "w1", dtype=dt) if kind == LAYER_LISA else None,
+                _ptr(ly.get("w2"), "w2", dtype=dt) if kind == LAYER_LISA else None,
+                _ptr(out, "out", (B, H, dk), torch.float32),
+                _ptr(row, "score_row", (B, H, Lk), self.sdt))
+            self.outs.append(out)
+            self.rows.append(row)
+            self._keep.append(ly)
+        self.arr = arr
+        need = stack_workspace_bytes(self.desc)
+        if need == 0:
+            raise LisaError(supported(self.desc) or -2, "lisa_decode_stack")
+        self.ws = torch.empty(need, dtype=torch.uint8, device=v0.device)
+
+    def step(self):
+        rc = _lib().lisa_decode_stack(C.byref(self.desc), self.arr, len(self.arr), C.c_void_p(self.ws.data_ptr()),
+                                      self.ws.numel(), _stream())
+        if rc:
+            raise LisaError(rc, "lisa_decode_stack")
+        return self.outs

@@ -192,7 +192,7 @@ def make_projection_inputs(cfg: LayerShape, seed: int = BASE_SEED + 9, device="c
 
 def make_decode_layer(stk: DecodeStack, layer: int, seed: int = BASE_SEED + 5, device="cpu",
                       mix: str = "add", ffn: str = "paper", dim_major: bool = True,
-                      Lmax: Optional[int] = None) -> Dict[str, torch.Tensor]:
+                      Lmax: Optional[int] = None, kind: Optional[str] = None) -> Dict[str, torch.Tensor]:
     """Caches and the new token's projections of one layer of the decode stack.
 
     Caches are filled with N(0,1) values up to and including the new token (index ctx), so
@@ -201,6 +201,8 @@ def make_decode_layer(stk: DecodeStack, layer: int, seed: int = BASE_SEED + 5, d
     Standard layers (layer < n_std): q [B,H,d_k], k_cache [B,Hkv,Lmax,d_k], v_cache.
     LiSA layers: q_lr [B,H,r], k_lr_cache ([B,Hkv,r,Lmax] if dim_major else [B,Hkv,Lmax,r]),
     v_cache [B,Hkv,Lmax,d_k], w1, w2.
+    kind: "std" | "lisa" | "share" overrides the stack's own split (layer < n_std is standard);
+    a direct-sharing layer ("share") has a V cache only.
     """
     g = _gen(seed * 1000 + layer, device)
     dt = stk.torch_dtype
@@ -216,7 +218,11 @@ def make_decode_layer(stk: DecodeStack, layer: int, seed: int = BASE_SEED + 5, d
 
     out["v_cache"] = cache(stk.d_k)
     out["v_new"] = out["v_cache"][:, :, Lk - 1].contiguous()
-    if layer < stk.n_std:
+    if kind is None:
+        kind = "std" if layer < stk.n_std else "lisa"
+    if kind == "share":
+        return out
+    if kind == "std":
         out["q"] = _randn((stk.B, stk.H, stk.d_k), g, device).to(dt)
         out["k_cache"] = cache(stk.d_k)
     else:

@@ -276,3 +276,55 @@ def test_bench_refuses_more_than_one_gpu():
                            env={**os.environ, **env}, timeout=120)
         assert p.returncode != 0
         assert "one GPU" in p.stderr and p.stdout.strip() == ""
+
+
+def test_sharing_patterns_match_the_printed_table():
+    """Counts and proportions of the paper's layer-sharing configurations (Sec. 5.1 table), the
+    split of the single-layer models into LiSA and direct-sharing layers, and the rule that a
+    sharing layer always has a layer in front of it."""
+    from paper_2408_01890_amd import patterns
+    rows = [l.split() for l in open(os.path.join(ROOT, "tests", "golden", "sharing_patterns.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 12
+    for name, total, sharing, pct in rows:
+        p = patterns.PATTERNS[name]
+        assert len(p) == int(total) and patterns.sharing_layers(p) == int(sharing)
+        assert f"{100.0 * int(sharing) / int(total) + 1e-9:.2f}" == pct
+        assert p[0] == patterns.STD and p[1] == patterns.STD and p[2] == patterns.STD
+    sl = patterns.PATTERNS["lisa_sl_7_10_of_32"]
+    assert (sl.count(patterns.LISA), sl.count(patterns.SHARE)) == (7, 10)        # "LiSA_SL (7+10)"
+    sl = patterns.PATTERNS["lisa_sl_10_12_of_40"]
+    assert (sl.count(patterns.LISA), sl.count(patterns.SHARE)) == (10, 12)       # "LiSA_SL (10+12)"
+    # LiSA (27) shares in 27 consecutive layers, numbers 4..30 (1-based)
+    p = patterns.PATTERNS["lisa_27_of_32"]
+    assert all(k == patterns.LISA for k in p[3:30]) and p[30] == patterns.STD and p[31] == patterns.STD
+    # the sharing layers of a LiSA model and of the DS model of the same size coincide
+    for a, b in (("lisa_17_of_32", "ds_17_of_32"), ("lisa_21_of_32", "ds_21_of_32"), ("lisa_26_of_40", "ds_26_of_40")):
+        assert [k != patterns.STD for k in patterns.PATTERNS[a]] == [k != patterns.STD for k in patterns.PATTERNS[b]]
+
+
+def test_decode_stack_rejects_bad_stacks_before_any_launch():
+    lib = lisa.library()
+    d = lisa.make_desc(lisa.BF16, 2, 8, 4, 1, 100, 128, 22, 32, kcache_dim_major=1, Lmax=128)
+    assert lisa.stack_workspace_bytes(d) > 2 * 2 * 8 * 100 * 2
+    P = [C.c_void_p(0x10000 + 0x100 * i) for i in range(8)]
+
+    def layer(kind, **kw):
+        f = dict(q=P[0], k_cache=P[1], v_cache=P[2], w1=P[3], w2=P[4], out=P[5], score_row=None)
+        f.update(kw)
+        return lisa.StackLayer(kind, 0, f["q"], f["k_cache"], f["v_cache"], f["w1"], f["w2"], f["out"], f["score_row"])
+
+    def call(layers, ws=P[6], wsb=1 << 40, desc=d):
+        arr = (lisa.StackLayer * len(layers))(*layers)
+        return lib.lisa_decode_stack(C.byref(desc), arr, len(layers), ws, wsb, None)
+
+    assert call([layer(lisa.LAYER_LISA)]) == -2                             # no front layer to share with
+    assert call([layer(lisa.LAYER_STD), layer(7)]) == -2                    # unknown kind
+    assert call([layer(lisa.LAYER_STD), layer(lisa.LAYER_LISA, w1=None)]) == -1
+    assert call([layer(lisa.LAYER_STD, v_cache=None)]) == -1
+    assert call([layer(lisa.LAYER_STD), layer(lisa.LAYER_SHARE, out=ODD)]) == -4
+    assert call([layer(lisa.LAYER_STD)], ws=None) == -5
+    assert call([layer(lisa.LAYER_STD)], wsb=64) == -5
+    assert lib.lisa_decode_stack(C.byref(d), None, 1, P[6], 1 << 40, None) == -1
+    bad = lisa.make_desc(lisa.BF16, 2, 8, 4, 1, 100, 128, 22, 32, mix=lisa.MIX_SHARE, kcache_dim_major=1, Lmax=128)
+    assert call([layer(lisa.LAYER_STD)], desc=bad) == -2

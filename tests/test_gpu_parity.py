@@ -347,10 +347,34 @@ def test_lisa_prefill_h16_both_head_groupings(groups, tuned):
                   tag=f"/groups{groups}")
 
 
-@pytest.mark.parametrize("groups", ["2", "4"])
+@pytest.mark.parametrize("pair", [0, 1])
+@pytest.mark.parametrize("shift", [0, 24, 160])
+def test_lisa_prefill_h32_all_heads_in_one_workgroup(shift, pair, tuned):
+    """H = 32 with four query heads per key/value head: the instantiation that keeps all heads of
+    a row block in one workgroup (a wave per key/value head, the A_{n-1} buffers doubling as the
+    staging tiles of A_n), on ragged and chunked problems, units singly and in pairs."""
+    tuned(prefill_groups=1, prefill_pair=pair)
+    Lk = 360
+    cfg = synth.LayerShape(f"h32_whole_shift{shift}", "bf16", 2, 32, 8, Lk, 1024, 128, 22, 64)
+    inp = synth.make_prefill_inputs(cfg, 61 + shift, DEV, ffn="identity_noise")
+    Lq = Lk - shift
+    prev = std_prev(inp)[:, :, shift:].contiguous()
+    inp["q_lr"] = inp["q_lr"][:, :, shift:].contiguous()
+    sent = torch.full((cfg.B, 32, Lq, Lk), SENTINEL, dtype=torch.float16, device=DEV)
+    out, scores = lisa.lisa_attn_prefill(inp["q_lr"], inp["k_lr"], inp["v"], prev, inp["w1"], inp["w2"],
+                                         scores_out=sent)
+    torch.cuda.synchronize()
+    assert lisa.last_path() == "mfma_fused"
+    check_prefill(cfg, inp, prev, out, scores, {b: np.arange(Lq) for b in range(cfg.B)}, tag=f"/pair{pair}")
+    above = torch.ones(Lq, Lk, dtype=torch.bool, device=DEV).triu(shift + 1)
+    assert torch.all(scores[..., above] == SENTINEL)
+
+
+@pytest.mark.parametrize("groups", ["1", "2", "4"])
 def test_lisa_prefill_h32_both_head_groupings(groups, tuned):
-    """H = 32 runs as two groups of 16 heads on large problems and as four groups of 8 on small
-    ones; both instantiations on the same ragged problem (key splits and the combine included)."""
+    """H = 32 runs as one workgroup of all heads (grouped KV heads), as two groups of 16 heads or as
+    four groups of 8, by problem size; all instantiations on the same ragged problem (key splits
+    and the combine included)."""
     tuned(prefill_groups=int(groups))
     cfg = synth.LayerShape("h32_groups", "bf16", 1, 32, 8, 328, 4096, 128, 22, 64)
     inp = synth.make_prefill_inputs(cfg, 51, DEV, ffn="identity_noise")
@@ -420,6 +444,42 @@ def test_lisa_prefill_fused_chunked_rows_unaligned_shift(H, Hkv, Lk, shift, mode
     assert lisa.last_path() == "mfma_fused"
     assert bool(torch.isfinite(out).all())
     check_prefill(cfg, inp, prev, out, scores, {0: np.arange(Lq)}, tag=f"/{mode}")
+
+
+SLICE_SHAPES = [
+    # name, B, H, Hkv, Lq, Lk (multiple of 8; ragged against 16, 32, 64-row blocks and 32-key tiles), r, F
+    ("h32_gqa", 2, 32, 8, 520, 520, 22, 64),
+    ("h40", 1, 40, 40, 200, 200, 22, 80),
+    ("h8_chunk_shift128", 2, 8, 4, 136, 264, 11, 64),
+    ("h16_f40", 1, 16, 16, 296, 296, 22, 40),
+    ("h32_shift24", 1, 32, 32, 248, 272, 22, 64),
+]
+
+
+@pytest.mark.parametrize("pair", [0, 1])
+@pytest.mark.parametrize("slices", [2, 4])
+@pytest.mark.parametrize("case", SLICE_SHAPES, ids=[c[0] for c in SLICE_SHAPES])
+def test_lisa_prefill_fused_row_slices(case, slices, pair, tuned):
+    """Workgroups of 2 and 4 slices of 16 query rows (the K_LR / V tile of a step serves all
+    slices): every row compared, nothing written above the diagonal; ragged last row blocks,
+    slices that skip the tiles beyond their own diagonal, chunked rows with aligned and
+    unaligned offsets, units taken singly and in long + short pairs."""
+    name, B, H, Hkv, Lq, Lk, r, F = case
+    tuned(prefill_slices=slices, prefill_pair=pair)
+    cfg = synth.LayerShape(f"{name}_s{slices}", "bf16", B, H, Hkv, Lk, 512, 128, r, F)
+    inp = synth.make_prefill_inputs(cfg, 300 + slices, DEV, ffn="fan_in")
+    shift = Lk - Lq
+    prev = std_prev(inp)[:, :, shift:].contiguous()
+    inp["q_lr"] = inp["q_lr"][:, :, shift:].contiguous()
+    sent = torch.full((B, H, Lq, Lk), SENTINEL, dtype=torch.float16, device=DEV)
+    out, scores = lisa.lisa_attn_prefill(inp["q_lr"], inp["k_lr"], inp["v"], prev, inp["w1"], inp["w2"],
+                                         scores_out=sent)
+    torch.cuda.synchronize()
+    assert lisa.last_path() == "mfma_fused"
+    assert bool(torch.isfinite(out).all())
+    check_prefill(cfg, inp, prev, out, scores, {b: np.arange(Lq) for b in range(B)}, tag=f"/pair{pair}")
+    above = torch.ones(Lq, Lk, dtype=torch.bool, device=DEV).triu(shift + 1)
+    assert torch.all(scores[..., above] == SENTINEL)      # nothing written beyond a row's last visible key
 
 
 # ---------------------------------------------------------------------------------------
@@ -595,6 +655,78 @@ def test_decode_stack_c5_shape_sampled_sequences(n_layers, n_std):
         if n >= stk.n_std:
             row = row_new
         del layer
+
+
+def run_pattern_stack(stk, kinds, sample_b, dim_major=True, Lmax=None):
+    """One decode step of lisa_decode_stack over the given layer kinds; every layer's output and
+    score row are compared with the oracle on the sampled sequences (the oracle of a sharing layer
+    consumes the row the library's front layer emitted), and the same step without kept rows (rows
+    travelling inside the workspace, emitted only where a next layer shares them) must give the
+    same outputs bit for bit."""
+    from oracle import cref
+    from paper_2408_01890_amd import patterns
+    Lk = stk.ctx + 1
+    code = {patterns.STD: lisa.LAYER_STD, patterns.LISA: lisa.LAYER_LISA, patterns.SHARE: lisa.LAYER_SHARE}
+    layers = []
+    for n, kind in enumerate(kinds):
+        ly = synth.make_decode_layer(stk, n, device=DEV, dim_major=dim_major, Lmax=Lmax, kind=kind,
+                                     ffn=("paper", "identity_noise", "fan_in")[n % 3])
+        rec = dict(kind=code[kind], v_cache=ly["v_cache"])
+        if kind == patterns.STD:
+            rec.update(q=ly["q"], k_cache=ly["k_cache"])
+        elif kind == patterns.LISA:
+            rec.update(q=ly["q_lr"], k_cache=ly["k_lr_cache"], w1=ly["w1"], w2=ly["w2"])
+        layers.append(rec)
+    kept = lisa.DecodeStack(layers, Lk, r=stk.r, F=stk.F, dim_major=dim_major, keep_rows=True)
+    lean = lisa.DecodeStack(layers, Lk, r=stk.r, F=stk.F, dim_major=dim_major, keep_rows=False)
+    outs_k = kept.step()
+    outs_l = lean.step()
+    torch.cuda.synchronize()
+    tol = hp.TOL[stk.torch_dtype]
+    worst = 0.0
+    for n, kind in enumerate(kinds):
+        assert torch.equal(outs_k[n], outs_l[n]), f"layer {n}: kept and workspace rows differ"
+        ly = layers[n]
+        for b in sample_b:
+            v = hp.f64(ly["v_cache"][b][:, :Lk])
+            if kind == patterns.STD:
+                a_ref = cref.std_scores_rows(hp.f64(ly["q"][b])[:, None, :], hp.f64(ly["k_cache"][b][:, :Lk]), [0])
+                o_ref = cref.softmax_v_rows(v, [0], a_ref, 1)
+            else:
+                prev_row = hp.f64(kept.rows[n - 1][b])[None]
+                if kind == patterns.LISA:
+                    kc = ly["k_cache"][b]
+                    kc = kc.permute(0, 2, 1) if dim_major else kc
+                    a_ref, o_ref = cref.lisa_rows(hp.f64(ly["q"][b])[:, None, :], hp.f64(kc[:, :Lk]), v,
+                                                  hp.f64(ly["w1"]), hp.f64(ly["w2"]), [0], prev_row)
+                else:
+                    a_ref, o_ref = cref.lisa_rows(None, None, v, None, None, [0], prev_row, mix=cref.MIX_SHARE, Lq=1)
+                    assert torch.equal(kept.rows[n][b], kept.rows[n - 1][b])     # A_n = A_{n-1} bit for bit
+            ea = hp.row_rel_err(hp.f64(kept.rows[n][b])[None], a_ref)
+            eo = hp.row_rel_err(hp.f64(outs_k[n][b])[None], o_ref)
+            worst = max(worst, ea, eo)
+            assert ea <= tol and eo <= tol, f"layer {n} ({kind}) b={b}: err_row={ea} err_out={eo}"
+    log(f"[parity] decode stack {stk.name} {len(kinds)} layers: worst error {worst:.3e} tol={tol:g}")
+
+
+def test_decode_stack_driver_small_mixed_pattern():
+    """lisa_decode_stack on a small stack that has every hand-over: standard -> LiSA, LiSA ->
+    LiSA, LiSA -> direct sharing, sharing -> sharing, sharing -> standard, standard -> standard."""
+    from paper_2408_01890_amd import patterns as pt
+    stk = synth.DecodeStack("stack_small", "bf16", 3, 8, 4, 300, 512, 128, 12, 16, 10, 1)
+    kinds = (pt.STD, pt.LISA, pt.SHARE, pt.STD, pt.STD, pt.LISA, pt.LISA, pt.SHARE, pt.SHARE, pt.STD)
+    run_pattern_stack(stk, kinds, [0, 1, 2], Lmax=304)
+
+
+@pytest.mark.parametrize("name", ["lisa_21_of_32", "lisa_sl_7_10_of_32"])
+def test_decode_stack_paper_patterns_full_size(name):
+    """The paper's layer patterns (Sec. 5.1 table of configurations) at the shape of the decode
+    benchmark (B = 64, 4096 cached tokens, 32 heads of 128, r = 22, F = 64): LiSA (21), whose
+    sharing layers alternate with standard ones, and LiSA_SL (7+10), whose deep layers share
+    directly.  Three sampled sequences at every layer."""
+    from paper_2408_01890_amd import patterns as pt
+    stk = synth.C5
+    run_pattern_stack(stk, pt.PATTERNS[name], [0, 31, 63], Lmax=(stk.ctx + 1 + 127) // 128 * 128)
 
 
 def test_error_path_on_gpu_is_reported_not_raised_as_fault():
@@ -1187,12 +1319,16 @@ def test_lisa_prefill_concat_mfma_random_shapes(seed):
     assert max(eo, ea) <= hp.TOL[torch.bfloat16]
 
 
+@pytest.mark.parametrize("slices", [0, 2, 4])
 @pytest.mark.parametrize("seed", range(8))
-def test_lisa_prefill_fused_random_shapes(seed):
+def test_lisa_prefill_fused_random_shapes(seed, slices, tuned):
     """The fused ADD kernel (H in 8, 16, 24, 32, 40; d_k = 128; F <= 128; r <= 32) on random
-    lengths, batch sizes, key groupings and chunked rows."""
+    lengths, batch sizes, key groupings and chunked rows; with the library's own geometry and
+    with 2 and 4 row slices per workgroup forced (where the shape has them)."""
     import random
     from oracle import cref
+    if slices:
+        tuned(prefill_slices=slices, prefill_pair=seed % 2)
     rnd = random.Random(4100 + seed)
     H = rnd.choice([8, 16, 24, 32, 40])
     Hkv = H // rnd.choice([g for g in (1, 2, 4, 8) if H % g == 0])
@@ -1203,7 +1339,12 @@ def test_lisa_prefill_fused_random_shapes(seed):
     F = rnd.choice([16, 32, 64, 80, 128])
     causal = rnd.random() < 0.8
     ffn = rnd.choice(["paper", "fan_in"])
-    log(f"[case] fused random {seed}: B{B} H{H}/{Hkv} Lq{Lq} Lk{Lk} r{r} F{F} causal={causal} ffn={ffn}")
+    if slices:                       # shapes that have sliced instantiations: ReLU, 33..96 hidden units
+        F = rnd.choice([40, 64, 80, 96])
+        H = rnd.choice([8, 16, 32, 40])
+        Hkv = H // rnd.choice([g for g in (1, 2, 4, 8) if H % g == 0])
+    log(f"[case] fused random {seed}: B{B} H{H}/{Hkv} Lq{Lq} Lk{Lk} r{r} F{F} causal={causal} ffn={ffn} "
+        f"slices={slices or 'auto'}")
     cfg = synth.LayerShape(f"rand{seed}", "bf16", B, H, Hkv, Lk, 256, 128, r, F)
     inp = synth.make_prefill_inputs(cfg, 5000 + seed, DEV, ffn=ffn)
     prev_full, _ = lisa.std_attn_scores(inp["q"], inp["k"], causal=causal)
