@@ -116,14 +116,90 @@ def cpu_baseline(cfg, inp, prev, budget_s=15.0):
 
 
 def decode_stack(stk, steps, warmup):
-    """One decode step = all layers of the stack on one stream, chained through the score row."""
+    """Decode steps through whole stacks of attention layers (lisa_decode_stack), chained through the
+    score row on one stream: the 5 standard + 27 LiSA stack of the benchmark definition, and the
+    layer patterns of the paper's 32-layer models (Sec. 5.1 table of configurations) at equal
+    batch and at equal KV-cache memory.  Every number is a measured step of the whole stack."""
     import torch
     from paper_2408_01890_amd import lisa, synth
+    from paper_2408_01890_amd import patterns as pt
     dev = "cuda"
     Lk = stk.ctx + 1
     Lmax = (Lk + 127) // 128 * 128       # cache capacity, as a serving system would allocate it
-    layers = [synth.make_decode_layer(stk, n, device=dev, dim_major=True, Lmax=Lmax)
-              for n in range(stk.n_layers)]
+    e = 2
+    code = {pt.STD: lisa.LAYER_STD, pt.LISA: lisa.LAYER_LISA, pt.SHARE: lisa.LAYER_SHARE}
+
+    def build(B, kinds_needed):
+        """Per layer: the V cache (every kind of layer has one) and, where some pattern needs them,
+        the standard layer's q / K cache and the LiSA layer's q_lr / K_LR cache / FFN."""
+        bstk = stk.scaled(B=B)
+        layers = []
+        for n in range(stk.n_layers):
+            need = {k[n] for k in kinds_needed}
+            ly = {}
+            if pt.STD in need:
+                t = synth.make_decode_layer(bstk, n, device=dev, dim_major=True, Lmax=Lmax, kind="std")
+                ly.update(q=t["q"], k_cache=t["k_cache"], v_cache=t["v_cache"])
+            if pt.LISA in need:
+                t = synth.make_decode_layer(bstk, n, device=dev, dim_major=True, Lmax=Lmax, kind="lisa")
+                ly.update(q_lr=t["q_lr"], k_lr_cache=t["k_lr_cache"], w1=t["w1"], w2=t["w2"])
+                ly.setdefault("v_cache", t["v_cache"])
+            if "v_cache" not in ly:
+                ly["v_cache"] = synth.make_decode_layer(bstk, n, device=dev, Lmax=Lmax, kind="share")["v_cache"]
+            layers.append(ly)
+        return layers
+
+    def run(layers, kinds, B, n_steps):
+        recs = []
+        for n, kind in enumerate(kinds):
+            ly = layers[n]
+            rec = dict(kind=code[kind], v_cache=ly["v_cache"])
+            if kind == pt.STD:
+                rec.update(q=ly["q"], k_cache=ly["k_cache"])
+            elif kind == pt.LISA:
+                rec.update(q=ly["q_lr"], k_cache=ly["k_lr_cache"], w1=ly["w1"], w2=ly["w2"])
+            recs.append(rec)
+        ds = lisa.DecodeStack(recs, Lk, r=stk.r, F=stk.F, dim_major=True)
+        lisa.profile_enable(False)
+        sec = time_steps(ds.step, n_steps, warmup)
+        lisa.profile_enable(True)
+        ds.step()
+        stages = lisa.profile_collect()
+        lisa.profile_enable(False)
+        # algorithmic bytes: caches read once, the score row read by a sharing layer and written
+        # by a layer whose successor shares it
+        nbytes = cache = 0
+        for n, kind in enumerate(kinds):
+            emits = n + 1 < len(kinds) and kinds[n + 1] != pt.STD and kind != pt.SHARE
+            row = stk.H * Lk * e
+            if kind == pt.STD:
+                nbytes += B * (stk.Hkv * Lk * 2 * stk.d_k * e + (row if emits else 0))
+                cache += 2 * stk.Hkv * stk.d_k * e
+            elif kind == pt.LISA:
+                nbytes += B * (stk.Hkv * Lk * (stk.r + stk.d_k) * e + row + (row if emits else 0))
+                cache += stk.Hkv * (stk.r + stk.d_k) * e
+            else:
+                nbytes += B * (stk.Hkv * Lk * stk.d_k * e + row)
+                cache += stk.Hkv * stk.d_k * e
+        return {"batch": B, "step_us": sec * 1e6, "tokens_per_s": B / sec, "algorithmic_GB_per_step": nbytes / 1e9,
+                "hbm_GBps": nbytes / sec / 1e9, "hbm_frac": nbytes / sec / 1e9 / HBM_PEAK_GBS,
+                "kv_cache_bytes_per_token": cache,
+                "stage_ms_one_step": {k: round(v[1], 4) for k, v in stages.items()}}
+
+    c5_kinds = tuple(pt.STD if n < stk.n_std else pt.LISA for n in range(stk.n_layers))
+    names = ("all_standard_32", "lisa_17_of_32", "lisa_21_of_32", "lisa_27_of_32", "lisa_sl_7_10_of_32")
+    pats = {k: pt.PATTERNS[k] for k in names}
+    layers = build(stk.B, [c5_kinds] + list(pats.values()))
+    head = run(layers, c5_kinds, stk.B, steps)
+    path = lisa.last_path()
+    equal_batch = {k: run(layers, v, stk.B, max(steps, 2)) for k, v in pats.items()}
+    base = equal_batch["all_standard_32"]
+    for k, v in equal_batch.items():
+        v["speedup_vs_all_standard_at_equal_batch"] = base["step_us"] / v["step_us"]
+        v["kv_cache_vs_all_standard"] = v["kv_cache_bytes_per_token"] / base["kv_cache_bytes_per_token"]
+
+    # one layer of each kind alone (with its combine pass), and the LiSA layer with the paper's own
+    # module: FFN over the concatenation, 2h -> 256 -> h, r = 20
     sdt = stk.score_dtype
     rows = [torch.empty((stk.B, stk.H, Lk), dtype=sdt, device=dev) for _ in range(2)]
     out = torch.empty((stk.B, stk.H, stk.d_k), dtype=torch.float32, device=dev)
@@ -132,33 +208,6 @@ def decode_stack(stk, steps, warmup):
     ws = torch.empty(max(lisa.workspace_bytes(dd, lisa.WS_DECODE), lisa.workspace_bytes(dd, lisa.WS_STD),
                          256), dtype=torch.uint8, device=dev)
 
-    def step():
-        cur = 0
-        for n, ly in enumerate(layers):
-            if n < stk.n_std:
-                # every standard layer emits its score row; the last one feeds the LiSA chain
-                lisa.std_attn_decode(ly["q"], ly["k_cache"], ly["v_cache"], Lk, want_scores=True,
-                                     score_row_out=rows[cur], out=out, workspace=ws)
-            else:
-                lisa.lisa_attn_decode(ly["q_lr"], ly["k_lr_cache"], ly["v_cache"], Lk, rows[cur],
-                                      ly["w1"], ly["w2"], dim_major=True, write_scores=True,
-                                      out=out, score_row_out=rows[1 - cur], workspace=ws)
-                cur = 1 - cur
-
-    e = 2
-    lisa_bytes = stk.B * (stk.Hkv * Lk * (stk.r + stk.d_k) * e + 2 * stk.H * Lk * e)
-    std_bytes = stk.B * (stk.Hkv * Lk * 2 * stk.d_k * e + stk.H * Lk * e)
-    total_bytes = stk.n_std * std_bytes + (stk.n_layers - stk.n_std) * lisa_bytes
-    lisa.profile_enable(False)
-    sec = time_steps(step, steps, warmup)
-    lisa.profile_enable(True)
-    step()
-    stages = lisa.profile_collect()
-    lisa.profile_enable(False)
-    path = lisa.last_path()
-
-    # one layer of each kind alone, for the layer patterns of the paper's models (Sec. 5.1 table of
-    # LiSA configurations: 17, 21 or 27 of 32 layers share attention; this stack is the 27-layer one)
     def one_std():
         ly = layers[0]
         lisa.std_attn_decode(ly["q"], ly["k_cache"], ly["v_cache"], Lk, want_scores=True,
@@ -170,9 +219,15 @@ def decode_stack(stk, steps, warmup):
                               dim_major=True, write_scores=True, out=out, score_row_out=rows[1],
                               workspace=ws)
 
+    def one_share():
+        ly = layers[stk.n_std]
+        lisa.lisa_attn_decode(None, None, ly["v_cache"], Lk, rows[0], None, None, dim_major=True,
+                              mix=lisa.MIX_SHARE, write_scores=False, out=out, workspace=ws)
+
+    one_std()                                                # (fills rows[0] with real scores)
     t_std = time_steps(one_std, 10, 2)
     t_lisa = time_steps(one_lisa, 10, 2)
-    # the same LiSA layer with the paper's own module: FFN over the concatenation, 2h -> 256 -> h, r = 20
+    t_share = time_steps(one_share, 10, 2)
     pstk = stk.scaled(name=stk.name + "_paper_widths", r=20, F=256)
     ply = synth.make_decode_layer(pstk, stk.n_std, device=dev, mix="concat", dim_major=True, Lmax=Lmax)
     pd = lisa.make_desc(pstk.torch_dtype, pstk.B, pstk.H, pstk.Hkv, 1, Lk, pstk.d_k, pstk.r, pstk.F,
@@ -186,63 +241,35 @@ def decode_stack(stk, steps, warmup):
 
     t_concat = time_steps(one_concat, 10, 2)
     concat_path = lisa.last_path()
-    del ply, pws
-    kv_std = 2 * stk.Hkv * stk.d_k * e                       # cache bytes per token and layer
-    kv_lisa = stk.Hkv * (stk.r + stk.d_k) * e
-    patterns = {}
-    for n_lisa in (17, 21, 27):
-        n_s = stk.n_layers - n_lisa
-        patterns[f"lisa_{n_lisa}_of_{stk.n_layers}"] = {
-            "attention_step_us": (n_s * t_std + n_lisa * t_lisa) * 1e6,
-            "speedup_vs_all_standard_at_equal_batch": stk.n_layers * t_std / (n_s * t_std + n_lisa * t_lisa),
-            "kv_cache_bytes_per_token": n_s * kv_std + n_lisa * kv_lisa,
-            "kv_cache_vs_all_standard": (n_s * kv_std + n_lisa * kv_lisa) / (stk.n_layers * kv_std),
-        }
-    del layers, rows, out, ws
+    del ply, pws, layers, rows, out, ws
     torch.cuda.empty_cache()
     # The paper's throughput table (Sec. 5.4) is taken at the largest batch that fits the memory:
     # a LiSA layer caches r + d_k instead of 2 d_k values per key and head, so the same cache
-    # memory holds a larger batch.  Attention layers only (no projections, no MLP): the batch of
-    # the all-standard model is this stack's, the LiSA patterns get the batch that fills the same
-    # cache bytes, and one layer of each kind is timed at that batch.
-    for n_lisa in (17, 21, 27):
-        pat = patterns[f"lisa_{n_lisa}_of_{stk.n_layers}"]
-        b_eq = int(stk.B / pat["kv_cache_vs_all_standard"])
-        bstk = stk.scaled(B=b_eq)
-        brows = [torch.empty((b_eq, stk.H, Lk), dtype=sdt, device=dev) for _ in range(2)]
-        bout = torch.empty((b_eq, stk.H, stk.d_k), dtype=torch.float32, device=dev)
-        bd = lisa.make_desc(stk.torch_dtype, b_eq, stk.H, stk.Hkv, 1, Lk, stk.d_k, stk.r, stk.F,
-                            write_scores=1, kcache_dim_major=1, Lmax=Lmax, out_f32=1)
-        bws = torch.empty(max(lisa.workspace_bytes(bd, lisa.WS_DECODE), lisa.workspace_bytes(bd, lisa.WS_STD), 256),
-                          dtype=torch.uint8, device=dev)
-        ly = synth.make_decode_layer(bstk, 0, device=dev, dim_major=True, Lmax=Lmax)
-        tb_std = time_steps(lambda: lisa.std_attn_decode(ly["q"], ly["k_cache"], ly["v_cache"], Lk, want_scores=True,
-                                                         score_row_out=brows[0], out=bout, workspace=bws), 6, 2)
-        del ly
-        ly = synth.make_decode_layer(bstk, stk.n_std, device=dev, dim_major=True, Lmax=Lmax)
-        tb_lisa = time_steps(lambda: lisa.lisa_attn_decode(ly["q_lr"], ly["k_lr_cache"], ly["v_cache"], Lk, brows[0],
-                                                           ly["w1"], ly["w2"], dim_major=True, write_scores=True,
-                                                           out=bout, score_row_out=brows[1], workspace=bws), 6, 2)
-        del ly, brows, bout, bws
+    # memory holds a larger batch.  Attention layers only (no projections, no MLP): each pattern
+    # runs at the batch that fills the cache bytes of the all-standard model at this stack's batch.
+    equal_mem = {}
+    for k in ("lisa_17_of_32", "lisa_21_of_32", "lisa_27_of_32"):
+        b_eq = int(stk.B / equal_batch[k]["kv_cache_vs_all_standard"])
+        lys = build(b_eq, [pats[k]])
+        r = run(lys, pats[k], b_eq, max(steps, 2))
+        r["batch_all_standard"] = stk.B
+        r["tokens_per_s_all_standard"] = base["tokens_per_s"]
+        r["throughput_vs_all_standard"] = r["tokens_per_s"] / base["tokens_per_s"]
+        equal_mem[k] = r
+        del lys
         torch.cuda.empty_cache()
-        n_s = stk.n_layers - n_lisa
-        step_eq = n_s * tb_std + n_lisa * tb_lisa
-        pat["equal_cache_memory"] = {
-            "batch": b_eq, "batch_all_standard": stk.B, "attention_step_us": step_eq * 1e6,
-            "tokens_per_s": b_eq / step_eq, "tokens_per_s_all_standard": stk.B / (stk.n_layers * t_std),
-            "throughput_vs_all_standard": (b_eq / step_eq) / (stk.B / (stk.n_layers * t_std)),
-        }
     return {
         "workload": f"{stk.name}: B{stk.B} ctx{stk.ctx}+1 H{stk.H} dk{stk.d_k} r{stk.r} F{stk.F}, "
                     f"{stk.n_std} standard + {stk.n_layers - stk.n_std} LiSA layers",
-        "decode_step_us": sec * 1e6, "steps": steps, "path": path,
-        "algorithmic_GB_per_step": total_bytes / 1e9,
-        "hbm_GBps": total_bytes / sec / 1e9, "hbm_frac": total_bytes / sec / 1e9 / HBM_PEAK_GBS,
-        "tokens_per_s": stk.B / sec,
-        "stage_ms_one_step": {k: round(v[1], 4) for k, v in stages.items()},
-        "standard_layer_us": t_std * 1e6, "lisa_layer_us": t_lisa * 1e6,
+        "decode_step_us": head["step_us"], "steps": steps, "path": path,
+        "algorithmic_GB_per_step": head["algorithmic_GB_per_step"],
+        "hbm_GBps": head["hbm_GBps"], "hbm_frac": head["hbm_frac"],
+        "tokens_per_s": head["tokens_per_s"],
+        "stage_ms_one_step": head["stage_ms_one_step"],
+        "standard_layer_us": t_std * 1e6, "lisa_layer_us": t_lisa * 1e6, "direct_sharing_layer_us": t_share * 1e6,
         "lisa_layer_concat_64_256_32_r20_us": t_concat * 1e6, "lisa_layer_concat_path": concat_path,
-        "layer_patterns_attention_only": patterns,
+        "layer_patterns_attention_only": {"measured": "whole stacks through lisa_decode_stack",
+                                          "equal_batch": equal_batch, "equal_cache_memory": equal_mem},
     }
 
 
