@@ -49,6 +49,9 @@
 namespace lisa {
 
 constexpr int PF_ROWS = 16;       // query rows per workgroup
+// Neighbouring units of work per chunk: a chunk times the NG head groups fills the 32 compute
+// units of one XCD (see the grid of k_lisa_prefill_fused).
+constexpr int pf_chunk_units(int ng) { return 32 / ng > 0 ? 32 / ng : 1; }
 constexpr int PF_TK = 32;         // keys per tile
 constexpr int PF_XS_HEAD = PF_ROWS * PF_TK * 2 + 32;        // bytes per head of the A_{n-1} tile
 constexpr int PF_YS_ROW = PF_TK * 4 + 16;                   // bytes per (head,row) of the y tile
@@ -205,6 +208,18 @@ template <class T>
 __device__ __forceinline__ void st_uv(void* ubase, unsigned voff, T v) {
   *(T*)((char*)ubase + voff) = v;
 }
+// The same for the A_{n-1} and A_n streams, kept apart because cache hints were tried on them:
+// non-temporal loads stop the head groups of a row block from sharing the A_{n-1} tile in the L2
+// (fetch 36.9 GB instead of 22.9 GB on the LLaMA3-8B shape), non-temporal stores change nothing
+// (21.4 GB, same time); plain accesses are what is used.
+template <class T>
+__device__ __forceinline__ T ld_uv_stream(const void* ubase, unsigned voff) {
+  return *(const T*)((const char*)ubase + voff);
+}
+template <class T>
+__device__ __forceinline__ void st_uv_stream(void* ubase, unsigned voff, T v) {
+  *(T*)((char*)ubase + voff) = v;
+}
 // H = NG * NW * HPW heads in NG groups; NW waves per workgroup, HPW heads per wave; FS hidden
 // k-steps of the FFN; RS slices of 16 query rows per workgroup (RS > 1 needs HPW = 1).
 //
@@ -220,11 +235,11 @@ __device__ __forceinline__ void st_uv(void* ubase, unsigned voff, T v) {
 //
 // A unit of work is (row block of R rows, key split); units are numbered by length.
 // Grid: one dimension.  Workgroup ids go round robin over the 8 XCDs, each with its own L2 and 32
-// compute units.  The ids of one XCD are dealt in chunks of 8 neighbouring units of one sequence
-// times NG head groups: 32 workgroups that start together and carry nearly the same number of
-// tiles, so they walk the keys side by side.  The NG head groups of a row block then find the
-// A_{n-1} tile, and the 8 row blocks of a head group the K_LR / V tiles, in the L2 after the first
-// of them has fetched it from HBM.  With a.pair the workgroup takes the units (last - x) and x, a
+// compute units.  The ids of one XCD are dealt in chunks of 32 / NG neighbouring units of one
+// sequence times NG head groups: the workgroups that fill one XCD start together and carry nearly
+// the same number of tiles, so they walk the keys side by side.  The NG head groups of a row block
+// then find the A_{n-1} tile, and the row blocks of a head group the K_LR / V tiles, in the L2
+// after the first of them has fetched it from HBM.  With a.pair the workgroup takes the units (last - x) and x, a
 // long and a short one, so that all workgroups carry the same number of tiles and stage the FFN
 // weights once.
 // Requires Lk % 8 == 0.
@@ -268,18 +283,19 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
   const int group = H / a.Hkv;
   const float LOG2E = 1.4426950408889634f;
   const int n_units = (Lq + R - 1) / R * a.split;
-  // workgroup id -> (XCD, chunk of 8 neighbouring slots of one sequence, slot in the chunk, head group)
+  // workgroup id -> (XCD, chunk of PF_CHUNK(NG) neighbouring slots of one sequence, slot in the chunk, head group)
   const int n_slots = a.pair ? (n_units + 1) / 2 : n_units;
   int slot, b, grp;
   {
+    constexpr int CHU = pf_chunk_units(NG);
     const int i = blockIdx.x, x = i & 7, j = i >> 3;
     grp = j % NG;
     const int jj = j / NG;                                   // position among this XCD's workgroups
-    const int chunk = (jj >> 3) * 8 + x;                     // chunks go round robin over the XCDs, long first
-    const int n_chunks = (n_slots + 7) / 8;
+    const int chunk = (jj / CHU) * 8 + x;                    // chunks go round robin over the XCDs, long first
+    const int n_chunks = (n_slots + CHU - 1) / CHU;
     if (chunk >= n_chunks * a.B) return;
     b = chunk % a.B;
-    slot = (chunk / a.B) * 8 + (jj & 7);
+    slot = (chunk / a.B) * CHU + jj % CHU;
     if (slot >= n_slots) return;
   }
   const int hg0 = grp * GH;                                 // first head of the group
@@ -287,8 +303,9 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
 
   Ffn::stage(a.w1, a.w2, H, a.F, w_s, tid, THREADS, hg0, GH);
   // One head per wave leaves registers for the FFN weights: fetched once per workgroup instead of
-  // read from LDS by every block pair.
-  constexpr bool WREG = HPW == 1 && NW <= 8 && RS == 1 && (Ffn::FB * Ffn::KS + HBO * FS) <= 8;
+  // read from LDS by every block pair.  (Two heads with shared operands would have the room too:
+  // measured, no gain.)
+  constexpr bool WREG = HPW == 1 && RS == 1 && NW <= 8 && (Ffn::FB * Ffn::KS + HBO * FS) <= 8;
   // blocks of 16 positions whose MFMA chains are interleaved in stage A (one at a time where the
   // accumulators of four row slices leave no registers for a second chain)
   constexpr int NBLK = RS >= 4 ? 1 : 2;
@@ -385,7 +402,7 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
       // keys >= Lk: any in-bounds chunk will do, those positions are masked in stage B
       const unsigned off = x_row + 2 * min(tile * PF_TK + xq8, Lk - 8);
 #pragma unroll
-      for (int u = 0; u < XCH; ++u) xr[u] = ld_uv<pf_u32x4>(x_base[u], off);
+      for (int u = 0; u < XCH; ++u) xr[u] = ld_uv_stream<pf_u32x4>(x_base[u], off);
     };
     auto store_x = [&](const pf_u32x4 (&xr)[XCH], int tile) {   // XSTG: into the buffer of the tile's parity
       unsigned char* dst = xs + (XSTG ? (tile & 1) * (H * PF_XS_HEAD) : 0) + xdst;
@@ -434,8 +451,12 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
       for (int nb = 0; nb < DK / 16; ++nb) vop[hh][nb] = ld_uv<bf16x8>(vt, v_off, nb * 256);
     }
 
-    // the A_{n-1} piece of the next step travels in xr through stage B: loaded during stage A,
-    // written to LDS at the end of stage B
+    // The A_{n-1} piece of the next step travels in xr through stage B: loaded during stage A,
+    // written to LDS at the end of stage B.  (With the tile already in the L2 the layer runs 8 %
+    // faster at L = 8192 and 20 % faster at L = 2048, so the load from HBM is not fully covered;
+    // a second register set, loaded two tiles ahead, gained 4 % with one head per wave and cost
+    // more than that in spilled registers with two: loads complete in order, so the younger
+    // K_LR / V loads wait for it anyway.)
     pf_u32x4 xr[XCH];
     load_x(t_begin, rs_min(t_begin), xr);
     store_x(xr, t_begin);
@@ -463,7 +484,7 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
                        ((lane >> 3) + 8 * u) * (2 * PF_TK) + (lane & 3) * 16
                  : as_ + (hh * RS + rs) * PF_AS_HEAD + ((lane >> 3) + 8 * u) * PF_AS_ROW + (lane & 7) * 16;
         if (pair_full || jc + 8 <= a_vis) {
-          st_uv<f16x8>(st, a_off, *(const f16x8*)sp);
+          st_uv_stream<f16x8>(st, a_off, *(const f16x8*)sp);
         } else if (jc < a_vis) {
           // a piece that straddles the row's last visible key (diagonal tiles only): the entries
           // beyond it keep what memory holds -- read, merge, write back; every piece has one writer.

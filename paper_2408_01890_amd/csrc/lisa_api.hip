@@ -603,8 +603,9 @@ int launch_prefill_fused_t(const lisa_desc* d, const PrefillArgs& a, hipStream_t
                                      (int)lds);
   if (e != hipSuccess) return hip_fail(e);
   const long long units = (long long)((a.Lq + PF_ROWS * RS - 1) / (PF_ROWS * RS)) * a.split;
-  const long long chunks = ((a.pair ? (units + 1) / 2 : units) + 7) / 8 * a.B;   // 8 neighbouring units each
-  const long long wgs = (chunks + 7) / 8 * 8 * 8 * NG;
+  constexpr int CHU = pf_chunk_units(NG);                    // neighbouring units per chunk
+  const long long chunks = ((a.pair ? (units + 1) / 2 : units) + CHU - 1) / CHU * a.B;
+  const long long wgs = (chunks + 7) / 8 * 8 * CHU * NG;
   if (wgs > 0x7fffffffLL) return LISA_ERR_UNSUPPORTED;
   StageScope prof("k_lisa_prefill_fused", st);
   kern<<<dim3((unsigned)wgs), NW * 64, lds, st>>>(a);
