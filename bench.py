@@ -62,7 +62,12 @@ def stage_algorithmic(stage, cfg, write_scores, out_bytes=4):
 # 1 GiB copy at the start of that run.  Recorded constants: each names the summary under
 # profiles/ it was taken from (a counter run cannot share a process with the timed run).
 MEASURED_TRAFFIC = {
-    ("c2_llama2_7b_l2048", "k_lisa_prefill_fused"): (389.3e6 + 168.9e6, "profiles/lisa_prefill_fused_c2_traffic.md"),
+    ("c3_llama3_8b_gqa_l8192", "k_lisa_prefill_fused"):
+        (24.96e9 + 9.16e9, "profiles/lisa_prefill_fused_c3_kernel_trace_and_counters.md"),
+    ("c4_llama2_13b_l4096", "k_lisa_prefill_fused"):
+        (15.75e9 + 6.06e9, "profiles/lisa_prefill_fused_c4_kernel_trace_and_counters.md"),
+    ("c2_llama2_7b_l2048", "k_lisa_prefill_fused"):
+        (328.3e6 + 169.0e6, "profiles/lisa_prefill_fused_c2_kernel_trace_and_counters.md"),
 }
 
 
