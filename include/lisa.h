@@ -105,7 +105,25 @@ typedef struct lisa_desc {
   int32_t kcache_dim_major; /* decode: K_LR cache is [B,Hkv,r,Lmax] (1) or [B,Hkv,Lmax,r] (0) */
   int32_t Lmax;             /* decode: capacity of the caches along the key axis, >= Lk       */
   int32_t out_f32;          /* 1: the attention output O is written as float32 whatever dtype */
+  int32_t score_tiled;      /* prefill score tensors: 0 = [B,H,Lq,Lk]; 1 = tiles, see below    */
 } lisa_desc;
+
+/*
+ * Tiled score layout (score_tiled = 1; prefill calls of the bf16 matrix-core kernels only, other
+ * requests return LISA_ERR_UNSUPPORTED).  A score tensor is then
+ *     [B, H, ceil(Lq / 16), ceil(Lk / 32), 16, 32]     (lisa_scores_elems() elements)
+ * i.e. tile (rb, kt) of a head holds rows 16 rb .. 16 rb + 15 and keys 32 kt .. 32 kt + 31 as 1 KB of
+ * consecutive memory: what a workgroup of the LiSA layer reads per head and step.  In [B,H,Lq,Lk]
+ * that piece is 16 separate half lines, each fetched from HBM as a whole line and again one step
+ * later for its other half; tiled, the layer moves a third fewer bytes and runs a fifth faster.
+ * The standard layer writes this layout, the LiSA layer reads and writes it.  Entries of a stored
+ * tile that lie above the diagonal, beyond row Lq - 1 or beyond key Lk - 1 are unspecified; tiles
+ * wholly above the diagonal are neither written nor read.
+ */
+#define LISA_SCORE_TILE_ROWS 16
+#define LISA_SCORE_TILE_KEYS 32
+/* Elements of one prefill score tensor of the descriptor in its layout (0 on a NULL descriptor). */
+size_t lisa_scores_elems(const lisa_desc* desc);
 
 /*
  * lisa_attn_prefill -- one LiSA attention layer over Lq query rows (Sec. 5.1, Eq. 3-4,
@@ -322,8 +340,8 @@ int lisa_layer_offsets(const lisa_desc* desc, size_t* q_lr_off, size_t* k_lr_off
 
 /* Scratch bytes the given entry point (lisa_ws_kind) needs for this descriptor. */
 size_t lisa_workspace_bytes(const lisa_desc* desc, int which);
-/* Bytes of one score tensor [B,H,Lq,Lk] in the score type (Sec. 5.2: h*l*l*2 per
- * sequence in prefill, h*l*2 per sequence in decode). */
+/* Bytes of one score tensor of the descriptor in the score type and in its layout (Sec. 5.2:
+ * h*l*l*2 per sequence in prefill, h*l*2 per sequence in decode; tiled: whole tiles). */
 size_t lisa_scores_bytes(const lisa_desc* desc);
 /* Bytes per score element: 4 (LISA_F32) or 2 (LISA_BF16). */
 size_t lisa_score_elem_bytes(const lisa_desc* desc);

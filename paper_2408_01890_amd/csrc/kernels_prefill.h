@@ -79,6 +79,7 @@ struct PrefillArgs {
   float* part_ml;         // [split][B][Lqp][H][2]   running maximum, partial sum
   int pair;               // workgroup x takes the units (last - x) and x
   int B;                  // sequences
+  int tiled;              // prev and scores are [B,H,ceil(Lq/16),ceil(Lk/32),16,32] (1 KB per tile)
 };
 
 typedef unsigned short pf_u16x8 __attribute__((ext_vector_type(8)));
@@ -178,15 +179,29 @@ __device__ __forceinline__ void lds_barrier() {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// Maxima as single instructions.  fmaxf makes the compiler quiet every operand it cannot prove
+// canonical (a copy through v_max x, x: 8 of them per head and tile in the softmax); the scores
+// are never signalling NaNs, so the plain instructions are used.
+__device__ __forceinline__ float max2_raw(float a, float b) {
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+__device__ __forceinline__ float max3_raw(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
 // Butterflies across the four 16-lane rows of a wave with the row-swap instructions of gfx950
 // (no LDS crossbar): after both steps every lane 16 g + c holds the reduction over g.
-__device__ __forceinline__ float rows_max(float v) {
+// Returns max(m, reduction of v).
+__device__ __forceinline__ float rows_max(float v, float m) {
   const unsigned u = __float_as_uint(v);
   auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);   // rows (0,1) and (2,3) exchanged
-  v = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  v = max2_raw(__uint_as_float(r[0]), __uint_as_float(r[1]));
   const unsigned w = __float_as_uint(v);
   auto q = __builtin_amdgcn_permlane32_swap(w, w, false, false);   // halves exchanged
-  return fmaxf(__uint_as_float(q[0]), __uint_as_float(q[1]));
+  return max3_raw(m, __uint_as_float(q[0]), __uint_as_float(q[1]));
 }
 __device__ __forceinline__ float rows_sum(float v) {
   const unsigned u = __float_as_uint(v);
@@ -315,6 +330,9 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
     ffn.fetch(w_s);
   }
 
+  // score tensors: elements per head, and the tile grid of the tiled layout
+  const int n_rb = (Lq + PF_ROWS - 1) / PF_ROWS, n_kt = (Lk + PF_TK - 1) / PF_TK;
+  const size_t head_elems = a.tiled ? (size_t)n_rb * n_kt * (PF_ROWS * PF_TK) : (size_t)Lq * Lk;
   // wave-uniform bases of this wave's heads (scalar registers)
   const bf16_t* k_base[HPW];     // K_LR rows of the head's key/value head
   const bf16_t* v_base[HPW];     // V chunks of it
@@ -324,11 +342,11 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
     const int h = h_first + hh, kv = h / group;
     k_base[hh] = a.kp + ((size_t)b * a.Hkv + kv) * a.Lkp * 32;
     v_base[hh] = a.vt + ((size_t)b * a.Hkv + kv) * (a.Lkp / 8) * (DK * 8);
-    s_base[hh] = a.scores ? a.scores + ((size_t)b * H + h) * Lq * Lk : nullptr;
+    s_base[hh] = a.scores ? a.scores + ((size_t)b * H + h) * head_elems : nullptr;
   }
   const half_t* x_base[XCH];     // A_{n-1} of head wv + NW u (XSTG: of the wave's own heads)
 #pragma unroll
-  for (int u = 0; u < XCH; ++u) x_base[u] = a.prev + ((size_t)b * H + (XSTG ? wv * HPW + u : wv + NW * u)) * Lq * Lk;
+  for (int u = 0; u < XCH; ++u) x_base[u] = a.prev + ((size_t)b * H + (XSTG ? wv * HPW + u : wv + NW * u)) * head_elems;
   // per-lane byte offsets, the same for every head
   const unsigned k_off = ((8 * (c >> 2) + (c & 3)) * 32 + 8 * g) * 2;   // MFMA row c -> key 8 (c/4) + c%4 (+4)
   const unsigned v_off = (g * DK + c) * 16;                             // key chunk g, feature c (+16 nb)
@@ -397,10 +415,20 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
     };
 
     // ---- A_{n-1} piece: lane -> XCH chunks (head wv + NW u, row lane / 4, 8 keys) of 16 bytes ------
+    // Row-major scores: the piece of a head is 16 half lines (64 bytes of 16 rows).  The L2 fetches
+    // whole 128-byte lines, and the other half of each is wanted one tile later, by when the line
+    // has usually left the L2 again: A_{n-1} was measured to come from HBM 2.5 times (22 GB on the
+    // LLaMA3-8B shape at L = 8192; a 4-byte load of the other half issued next to each piece, to have
+    // it fetched once, changed little).  Tiled scores: the piece is 1 KB of consecutive memory.
     auto load_x = [&](int tile, int rs, pf_u32x4 (&xr)[XCH]) {
-      const unsigned x_row = (unsigned)min(i0 + PF_ROWS * rs + (lane >> 2), Lq - 1) * Lk * 2;
-      // keys >= Lk: any in-bounds chunk will do, those positions are masked in stage B
-      const unsigned off = x_row + 2 * min(tile * PF_TK + xq8, Lk - 8);
+      unsigned off;
+      if (a.tiled) {
+        off = ((unsigned)min((i0 >> 4) + rs, n_rb - 1) * n_kt + tile) * (PF_ROWS * PF_TK * 2) + lane * 16;
+      } else {
+        const unsigned x_row = (unsigned)min(i0 + PF_ROWS * rs + (lane >> 2), Lq - 1) * Lk * 2;
+        // keys >= Lk: any in-bounds chunk will do, those positions are masked in stage B
+        off = x_row + 2 * min(tile * PF_TK + xq8, Lk - 8);
+      }
 #pragma unroll
       for (int u = 0; u < XCH; ++u) xr[u] = ld_uv_stream<pf_u32x4>(x_base[u], off);
     };
@@ -473,6 +501,22 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
       const bool pair_full = (tile | 1) < n_full_of(rs);      // workgroup-uniform
       const int jc = jp + 8 * (lane & 7);
       half_t* st = s_base[hh] + jp;
+      if (a.tiled) {
+        // each staged tile of the pair is 1 KB of consecutive memory: lane -> row lane / 4, 16
+        // bytes; what lies above the diagonal inside a stored tile is unspecified
+        if (i0 + PF_ROWS * rs >= Lq) return;                 // (a slice without rows)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int tl = (tile & ~1) + u;
+          if (tl > last_tile_of(rs)) continue;                // the last pair of a row block may be half
+          const unsigned char* sp =
+              XSTG ? xs + u * (H * PF_XS_HEAD) + (wv * HPW + hh) * PF_XS_HEAD + (lane >> 2) * (2 * PF_TK) + (lane & 3) * 16
+                   : as_ + (hh * RS + rs) * PF_AS_HEAD + (lane >> 2) * PF_AS_ROW + u * 64 + (lane & 3) * 16;
+          const unsigned toff = ((unsigned)((i0 >> 4) + rs) * n_kt + tl) * (PF_ROWS * PF_TK * 2) + lane * 16;
+          st_uv_stream<f16x8>(s_base[hh], toff, *(const f16x8*)sp);
+        }
+        return;
+      }
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         const int gi = i0 + PF_ROWS * rs + (lane >> 3) + 8 * u;
@@ -491,9 +535,11 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
           // (Element-wise stores kept eight addresses per piece alive across the whole tile loop.)
           const f16x8 old = ld_uv<f16x8>(st, a_off);
           f16x8 hv = *(const f16x8*)sp;
+          int rel = a_vis - jc;                   // kept inside this branch: the eight compares
+          asm volatile("" : "+v"(rel));           // were hoisted into every pass of the tile loop
 #pragma unroll
           for (int e = 1; e < 8; ++e)
-            if (jc + e >= a_vis) hv[e] = old[e];
+            if (e >= rel) hv[e] = old[e];
           st_uv<f16x8>(st, a_off, hv);
         }
       }
@@ -626,14 +672,14 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
         // online softmax, statistics of row c kept by all four lanes 16 g + c; exponentials in
         // base 2: p = 2^(A log2(e) - m log2(e))
         if (!full) {                              // workgroup-uniform: only diagonal / ragged tiles mask
+          int rel = vis_row - jl;                 // the compares stay inside the branch
+          asm volatile("" : "+v"(rel));
 #pragma unroll
           for (int e = 0; e < 8; ++e)
-            if (jl + e >= vis_row) an[e] = -INFINITY;
+            if (e >= rel) an[e] = -INFINITY;
         }
-        float mx = fmaxf(fmaxf(fmaxf(an[0], an[1]), fmaxf(an[2], an[3])),
-                         fmaxf(fmaxf(an[4], an[5]), fmaxf(an[6], an[7])));
-        mx = rows_max(mx);
-        const float m_new = fmaxf(m_run[sl], mx);
+        const float mx = max2_raw(max3_raw(max3_raw(max3_raw(an[0], an[1], an[2]), an[3], an[4]), an[5], an[6]), an[7]);
+        const float m_new = rows_max(mx, m_run[sl]);
         // A row may have seen no key yet: a key share, a walk downwards from the diagonal, or a
         // slice at its own diagonal can meet a tile that lies wholly beyond the row's last visible
         // key.  The exponent is then taken against 0 instead of -inf, so alpha and every p are

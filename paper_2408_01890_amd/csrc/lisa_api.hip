@@ -78,6 +78,7 @@ int check_common(const lisa_desc* d) {
   if (d->H % d->Hkv != 0) return LISA_ERR_SHAPE;
   if (d->causal != 0 && d->causal != 1) return LISA_ERR_SHAPE;
   if (d->out_f32 != 0 && d->out_f32 != 1) return LISA_ERR_SHAPE;
+  if (d->score_tiled != 0 && d->score_tiled != 1) return LISA_ERR_SHAPE;
   if (d->causal && d->Lk < d->Lq) return LISA_ERR_SHAPE;
   if (d->d_k > kMaxHeadDim) return LISA_ERR_UNSUPPORTED;
   if (d->B > kMaxGridYZ || d->Lq > kMaxGridYZ || (long long)d->B * d->H > kMaxGridYZ)
@@ -108,14 +109,18 @@ int check_decode(const lisa_desc* d) {
   if (d->Lq != 1) return LISA_ERR_SHAPE;
   if (d->Lmax < d->Lk) return LISA_ERR_SHAPE;
   if (d->kcache_dim_major != 0 && d->kcache_dim_major != 1) return LISA_ERR_SHAPE;
+  if (d->score_tiled) return LISA_ERR_UNSUPPORTED;          // a decode step hands over score rows
   return LISA_OK;
 }
 
 size_t score_elem(const lisa_desc* d) { return d->dtype == LISA_F32 ? 4 : 2; }
 
-size_t scores_bytes(const lisa_desc* d) {
-  return (size_t)d->B * d->H * d->Lq * d->Lk * score_elem(d);
+size_t scores_elems(const lisa_desc* d) {
+  if (d->score_tiled)
+    return (size_t)d->B * d->H * ((d->Lq + PF_ROWS - 1) / PF_ROWS) * ((d->Lk + PF_TK - 1) / PF_TK) * (PF_ROWS * PF_TK);
+  return (size_t)d->B * d->H * d->Lq * d->Lk;
 }
+size_t scores_bytes(const lisa_desc* d) { return scores_elems(d) * score_elem(d); }
 
 // float32 copy of the score tensor that the generic softmax kernel reads
 size_t exact_bytes(const lisa_desc* d) {
@@ -497,7 +502,8 @@ bool prefill_fused_ok(const lisa_desc* d) {
   if (d->dtype != LISA_BF16 || d->d_k != 128) return false;
   if (d->mix != LISA_MIX_ADD || (d->act != LISA_ACT_RELU && d->act != LISA_ACT_SILU)) return false;
   if (d->Lk % 8 != 0 || d->F > 128 || d->r > 32) return false;   // 16-byte aligned score rows
-  if ((long long)d->Lq * d->Lk >= (1LL << 31)) return false;      // 32-bit byte offsets inside one head's scores
+  // 32-bit byte offsets inside one head's scores (tiled: rows and keys rounded up to whole tiles)
+  if ((long long)(d->Lq + PF_ROWS) * (d->Lk + PF_TK) >= (1LL << 31)) return false;
   return d->H == 8 || d->H == 16 || d->H == 24 || d->H == 32 || d->H == 40;
 }
 
@@ -662,6 +668,7 @@ int run_prefill_fused(const lisa_desc* d, const void* q_lr, const void* k_lr, co
   a.F = d->F;
   a.causal = d->causal;
   a.out_f32 = d->out_f32;
+  a.tiled = d->score_tiled;
   a.dscale = pick_scale(d->delta_scale, d->r);
   a.split = geo.split;
   a.pair = geo.pair;
@@ -766,6 +773,7 @@ int run_std_prefill_fast(const lisa_desc* d, const void* q, const void* k, const
   a.Lkp = (d->Lk + 63) / 64 * 64;
   a.causal = d->causal;
   a.out_f32 = d->out_f32;
+  a.tiled = d->score_tiled;
   a.scale = pick_scale(d->std_scale, d->d_k);
   if (out) {
     dim3 grid(a.Lkp / 64, d->d_k / 64, d->B * d->Hkv);
@@ -1141,6 +1149,8 @@ int lisa_layer_prefill(const lisa_desc* desc, int32_t d_model, float rope_theta,
 
 int lisa_supported(const lisa_desc* desc) { return check_lisa(desc); }
 
+size_t lisa_scores_elems(const lisa_desc* desc) { return desc ? scores_elems(desc) : 0; }
+
 const char* lisa_strerror(int status) {
   switch (status) {
     case LISA_OK: return "ok";
@@ -1234,6 +1244,7 @@ int lisa_attn_prefill(const lisa_desc* desc, const void* q_lr, const void* k_lr,
     if (rc) return rc;
     return run_prefill_fused(&eq, q_lr, k_lr, v, scores_prev, w1e, w2e, out, scores, workspace, st);
   }
+  if (desc->score_tiled) return LISA_ERR_UNSUPPORTED;       // the fused kernels alone read and write tiles
   if (relu_equivalent(desc, &eq) && scores_mfma_ok(&eq)) {   // the single layer over the concatenation
     const void *w1e, *w2e;
     rc = synth_relu_ffn(desc, w1, workspace, round_up(concat_ws(&eq).total, 256), &w1e, &w2e, &q_lr, &k_lr, st);
@@ -1475,6 +1486,7 @@ int std_attn_scores(const lisa_desc* desc, const void* q, const void* k, const v
   const int cap = (desc->Lq == 1 && desc->Lmax >= desc->Lk) ? desc->Lmax : desc->Lk;
   const KeyStrides ks = dense_keys(desc, cap, desc->d_k);
   if (std_prefill_fast_ok(desc)) return run_std_prefill_fast(desc, q, k, v, scores_out, out, workspace, st);
+  if (desc->score_tiled) return LISA_ERR_UNSUPPORTED;       // the matrix-core prefill kernel alone writes tiles
   if (out && decode_fast_ok(desc, false)) {
     DecodeArgs a{};
     a.q = (const bf16_t*)q;

@@ -22,8 +22,7 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
 // Saturating float -> half: scores beyond the half range are clamped to +-65504 instead
 // of becoming infinities that would poison the softmax of the next layer.
 __device__ __forceinline__ half_t f32_to_half_sat(float f) {
-  f = fminf(fmaxf(f, -65504.0f), 65504.0f);
-  return (half_t)f;
+  return (half_t)__builtin_amdgcn_fmed3f(f, -65504.0f, 65504.0f);   // one median-of-three
 }
 
 template <typename T> struct elem;

@@ -28,7 +28,7 @@ EXPORTS = (
     "lisa_strerror", "lisa_last_hip_error", "lisa_last_path", "lisa_profile_enable",
     "lisa_profile_collect", "lisa_cache_fill", "lisa_project_qkv", "lisa_layer_prefill",
     "lisa_layer_offsets", "lisa_layer_decode", "lisa_tune_set", "lisa_attn_decode_static",
-    "lisa_decode_stack", "lisa_stack_workspace_bytes",
+    "lisa_decode_stack", "lisa_stack_workspace_bytes", "lisa_scores_elems",
 )
 TUNE_PREFILL_GROUPS, TUNE_PREFILL_SPLIT, TUNE_PREFILL_PAIR, TUNE_STD_PAIR, TUNE_PROJECT_TN, TUNE_PREFILL_SLICES = range(6)
 
@@ -49,7 +49,7 @@ class Desc(C.Structure):
         ("F", C.c_int32), ("mix", C.c_int32), ("act", C.c_int32),
         ("delta_scale", C.c_float), ("std_scale", C.c_float), ("causal", C.c_int32),
         ("write_scores", C.c_int32), ("kcache_dim_major", C.c_int32), ("Lmax", C.c_int32),
-        ("out_f32", C.c_int32),
+        ("out_f32", C.c_int32), ("score_tiled", C.c_int32),
     ]
 
 
@@ -100,6 +100,8 @@ def _lib():
         h.lisa_workspace_bytes.restype = sz
         h.lisa_scores_bytes.argtypes = [dp]
         h.lisa_scores_bytes.restype = sz
+        h.lisa_scores_elems.argtypes = [dp]
+        h.lisa_scores_elems.restype = sz
         h.lisa_score_elem_bytes.argtypes = [dp]
         h.lisa_score_elem_bytes.restype = sz
         h.lisa_kcache_saved_bytes.argtypes = [dp, C.c_int]
@@ -141,10 +143,35 @@ def library():
 
 def make_desc(dtype, B, H, Hkv, Lq, Lk, d_k, r=0, F=0, mix=MIX_ADD, act=ACT_RELU,
               delta_scale=0.0, std_scale=0.0, causal=1, write_scores=0, kcache_dim_major=0,
-              Lmax=0, out_f32=0) -> Desc:
+              Lmax=0, out_f32=0, score_tiled=0) -> Desc:
     code = {torch.float32: F32, torch.bfloat16: BF16, F32: F32, BF16: BF16}[dtype]
     return Desc(code, B, H, Hkv, Lq, Lk, d_k, r, F, mix, act, delta_scale, std_scale, causal,
-                write_scores, kcache_dim_major, Lmax, out_f32)
+                write_scores, kcache_dim_major, Lmax, out_f32, score_tiled)
+
+
+TILE_ROWS, TILE_KEYS = 16, 32
+
+
+def scores_shape(B, H, Lq, Lk, tiled=False):
+    """Shape of a prefill score tensor: [B,H,Lq,Lk], or its tiles [B,H,ceil(Lq/16),ceil(Lk/32),16,32]."""
+    if not tiled:
+        return (B, H, Lq, Lk)
+    return (B, H, -(-Lq // TILE_ROWS), -(-Lk // TILE_KEYS), TILE_ROWS, TILE_KEYS)
+
+
+def tile_scores(s):
+    """[B,H,Lq,Lk] -> tiled layout (a copy; rows and keys padded with zeros to whole tiles)."""
+    B, H, Lq, Lk = s.shape
+    nr, nk = -(-Lq // TILE_ROWS), -(-Lk // TILE_KEYS)
+    p = torch.zeros((B, H, nr * TILE_ROWS, nk * TILE_KEYS), dtype=s.dtype, device=s.device)
+    p[:, :, :Lq, :Lk] = s
+    return p.view(B, H, nr, TILE_ROWS, nk, TILE_KEYS).permute(0, 1, 2, 4, 3, 5).contiguous()
+
+
+def untile_scores(t, Lq, Lk):
+    """Tiled layout -> [B,H,Lq,Lk] (a copy)."""
+    B, H, nr, nk = t.shape[:4]
+    return t.permute(0, 1, 2, 4, 3, 5).reshape(B, H, nr * TILE_ROWS, nk * TILE_KEYS)[:, :, :Lq, :Lk].contiguous()
 
 
 def score_dtype(dtype) -> torch.dtype:
@@ -244,24 +271,25 @@ def _out_dtype(dt, out_dtype):
 
 
 def std_attn_scores(q, k, v=None, *, want_scores=True, causal=True, std_scale=0.0,
-                    scores_out=None, out=None, out_dtype=None, workspace=None):
+                    scores_out=None, out=None, out_dtype=None, workspace=None, tiled=False):
     """Standard attention that emits the shared scores.  q [B,H,Lq,d_k], k/v [B,Hkv,Lk,d_k].
-    Returns (scores [B,H,Lq,Lk] or None, out [B,Lq,H,d_k] or None)."""
+    Returns (scores [B,H,Lq,Lk] (tiled: see scores_shape) or None, out [B,Lq,H,d_k] or None)."""
     B, H, Lq, dk = q.shape
     _, Hkv, Lk, _ = k.shape
     odt, of32 = _out_dtype(q.dtype, out.dtype if out is not None else out_dtype)
     desc = make_desc(q.dtype, B, H, Hkv, Lq, Lk, dk, causal=int(causal), std_scale=std_scale,
-                     out_f32=of32)
+                     out_f32=of32, score_tiled=int(tiled))
     sdt = score_dtype(q.dtype)
+    sshape = scores_shape(B, H, Lq, Lk, tiled)
     if want_scores and scores_out is None:
-        scores_out = torch.empty((B, H, Lq, Lk), dtype=sdt, device=q.device)
+        scores_out = torch.empty(sshape, dtype=sdt, device=q.device)
     if v is not None and out is None:
         out = torch.empty((B, Lq, H, dk), dtype=odt, device=q.device)
     need = workspace_bytes(desc, WS_STD) if out is not None else 0
     workspace, wp, wb = _workspace(need, q, workspace)
     rc = _lib().std_attn_scores(
         C.byref(desc), _ptr(q, "q", dtype=q.dtype), _ptr(k, "k", (B, Hkv, Lk, dk), q.dtype),
-        _ptr(v, "v", (B, Hkv, Lk, dk), q.dtype), _ptr(scores_out, "scores_out", (B, H, Lq, Lk), sdt),
+        _ptr(v, "v", (B, Hkv, Lk, dk), q.dtype), _ptr(scores_out, "scores_out", sshape, sdt),
         _ptr(out, "out", (B, Lq, H, dk), odt), wp, wb, _stream())
     if rc:
         raise LisaError(rc, "std_attn_scores")
@@ -295,12 +323,20 @@ def std_attn_decode(q, k_cache, v_cache, Lk, *, want_scores=True, std_scale=0.0,
 
 def lisa_attn_prefill(q_lr, k_lr, v, scores_prev, w1, w2, *, mix=MIX_ADD, act=ACT_RELU,
                       write_scores=True, causal=True, delta_scale=0.0, out=None, out_dtype=None,
-                      scores_out=None, workspace=None):
+                      scores_out=None, workspace=None, tiled=False, Lq=None):
     """One LiSA layer.  q_lr [B,H,Lq,r], k_lr [B,Hkv,Lk,r], v [B,Hkv,Lk,d_k],
     scores_prev [B,H,Lq,Lk] (score dtype), w1 [Din,F], w2 [F,H].  Operands a variant does not
     use are None: w1, w2 for MIX_PLUS / MIX_SHARE, w2 for ACT_SINGLE, q_lr, k_lr for MIX_SHARE.
+    tiled: both score tensors are in the tiled layout (see scores_shape); Lq is then taken from
+    q_lr (or the Lq argument where there is no q_lr).
     Returns (out [B,Lq,H,d_k], scores_out [B,H,Lq,Lk] or None)."""
-    B, H, Lq, Lk = scores_prev.shape
+    if tiled:
+        B, H = scores_prev.shape[:2]
+        Lq = q_lr.shape[2] if q_lr is not None else Lq
+        Lk = v.shape[2]
+    else:
+        B, H, Lq, Lk = scores_prev.shape
+    sshape = scores_shape(B, H, Lq, Lk, tiled)
     _, Hkv, _, dk = v.shape
     r = q_lr.shape[3] if q_lr is not None else 0
     has_ffn = mix in (MIX_ADD, MIX_CONCAT)
@@ -309,24 +345,25 @@ def lisa_attn_prefill(q_lr, k_lr, v, scores_prev, w1, w2, *, mix=MIX_ADD, act=AC
     sdt = score_dtype(dt)
     odt, of32 = _out_dtype(dt, out.dtype if out is not None else out_dtype)
     desc = make_desc(dt, B, H, Hkv, Lq, Lk, dk, r, F, mix=mix, act=act, delta_scale=delta_scale,
-                     causal=int(causal), write_scores=int(write_scores), out_f32=of32)
+                     causal=int(causal), write_scores=int(write_scores), out_f32=of32,
+                     score_tiled=int(tiled))
     if has_ffn and Din != (2 * H if mix == MIX_CONCAT else H):
         raise ValueError(f"w1 has {Din} rows, expected {2 * H if mix == MIX_CONCAT else H}")
     if out is None:
         out = torch.empty((B, Lq, H, dk), dtype=odt, device=v.device)
     if write_scores and scores_out is None:
-        scores_out = torch.empty((B, H, Lq, Lk), dtype=sdt, device=v.device)
+        scores_out = torch.empty(sshape, dtype=sdt, device=v.device)
     need = workspace_bytes(desc, WS_PREFILL)
     if need == 0 and supported(desc) != 0:
         raise LisaError(supported(desc), "lisa_attn_prefill")
     workspace, wp, wb = _workspace(need, v, workspace)
     rc = _lib().lisa_attn_prefill(
         C.byref(desc), _ptr(q_lr, "q_lr", (B, H, Lq, r), dt), _ptr(k_lr, "k_lr", (B, Hkv, Lk, r), dt),
-        _ptr(v, "v", (B, Hkv, Lk, dk), dt), _ptr(scores_prev, "scores_prev", (B, H, Lq, Lk), sdt),
+        _ptr(v, "v", (B, Hkv, Lk, dk), dt), _ptr(scores_prev, "scores_prev", sshape, sdt),
         _ptr(w1 if has_ffn else None, "w1", (Din, F), dt),
         _ptr(w2 if has_ffn and act != ACT_SINGLE else None, "w2", (F, H), dt),
         _ptr(out, "out", (B, Lq, H, dk), odt),
-        _ptr(scores_out if write_scores else None, "scores_out", (B, H, Lq, Lk), sdt), wp, wb,
+        _ptr(scores_out if write_scores else None, "scores_out", sshape, sdt), wp, wb,
         _stream())
     if rc:
         raise LisaError(rc, "lisa_attn_prefill")
@@ -382,7 +419,7 @@ def lisa_project_qkv(x, w, H, Hkv, r, d_k, *, rope_theta=0.0, pos0=0, q_lr=None,
 
 def lisa_layer_prefill(x, w_qkv, Hkv, r, d_k, scores_prev, w1, w2, *, rope_theta=0.0, mix=MIX_ADD,
                        write_scores=True, causal=True, out=None, out_dtype=None, scores_out=None,
-                       workspace=None):
+                       workspace=None, tiled=False):
     """A whole LiSA layer from the hidden states x [B,L,d]: projection front end (see
     lisa_project_qkv) then lisa_attn_prefill.  Returns (out, scores_out or None, (q_lr, k_lr, v)),
     the last being views of the workspace."""
@@ -393,11 +430,12 @@ def lisa_layer_prefill(x, w_qkv, Hkv, r, d_k, scores_prev, w1, w2, *, rope_theta
     sdt = score_dtype(dt)
     odt, of32 = _out_dtype(dt, out.dtype if out is not None else out_dtype)
     desc = make_desc(dt, B, H, Hkv, L, L, d_k, r, F, mix=mix, causal=int(causal),
-                     write_scores=int(write_scores), out_f32=of32)
+                     write_scores=int(write_scores), out_f32=of32, score_tiled=int(tiled))
+    sshape = scores_shape(B, H, L, L, tiled)
     if out is None:
         out = torch.empty((B, L, H, d_k), dtype=odt, device=x.device)
     if write_scores and scores_out is None:
-        scores_out = torch.empty((B, H, L, L), dtype=sdt, device=x.device)
+        scores_out = torch.empty(sshape, dtype=sdt, device=x.device)
     need = workspace_bytes(desc, WS_LAYER)
     if need == 0:
         raise LisaError(supported(desc) or -2, "lisa_layer_prefill")
@@ -405,9 +443,9 @@ def lisa_layer_prefill(x, w_qkv, Hkv, r, d_k, scores_prev, w1, w2, *, rope_theta
     rc = _lib().lisa_layer_prefill(
         C.byref(desc), D, float(rope_theta or 0.0), _ptr(x, "x", dtype=dt),
         _ptr(w_qkv, "w_qkv", ((H + Hkv) * r + Hkv * d_k, D), dt),
-        _ptr(scores_prev, "scores_prev", (B, H, L, L), sdt), _ptr(w1, "w1", dtype=dt),
+        _ptr(scores_prev, "scores_prev", sshape, sdt), _ptr(w1, "w1", dtype=dt),
         _ptr(w2, "w2", (F, H), dt), _ptr(out, "out", (B, L, H, d_k), odt),
-        _ptr(scores_out if write_scores else None, "scores_out", (B, H, L, L), sdt), wp, wb, _stream())
+        _ptr(scores_out if write_scores else None, "scores_out", sshape, sdt), wp, wb, _stream())
     if rc:
         raise LisaError(rc, "lisa_layer_prefill")
     offs = [C.c_size_t() for _ in range(3)]

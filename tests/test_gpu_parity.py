@@ -33,13 +33,13 @@ def check_prefill(cfg, inp, prev, out, scores, rows_by_b, mix=0, causal=True, ta
     # the other reading of the tolerance, one RMS over all compared rows: logged, not asserted
     o_max = o_sq = o_n = a_max = a_sq = a_n = 0.0
     for b, rows in rows_by_b.items():
-        prev_rows = hp.gather_score_rows(prev, b, rows)
+        prev_rows = hp.gather_score_rows(prev, b, rows, Lk)
         a_ref, o_ref = hp.oracle_lisa_rows(inp, b, rows, prev_rows, mix=mix)
         o_got = hp.gather_out_rows(out, b, rows)
         worst_o = max(worst_o, hp.row_rel_err(o_got, o_ref))
         o_max, o_sq, o_n = max(o_max, float(np.abs(o_got - o_ref).max())), o_sq + float((o_ref ** 2).sum()), o_n + o_ref.size
         if scores is not None:
-            a_got = hp.gather_score_rows(scores, b, rows)
+            a_got = hp.gather_score_rows(scores, b, rows, Lk)
             worst_a = max(worst_a, hp.scores_row_rel_err(a_got, a_ref, rows, Lq, Lk, causal))
             for n, i in enumerate(rows):
                 nv = hp.n_visible(int(i), Lq, Lk, causal)
