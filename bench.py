@@ -61,13 +61,16 @@ def stage_algorithmic(stage, cfg, write_scores, out_bytes=4):
 # WRITE_SIZE on `bench.py --only <config>` and scaled by what the same counters read for the
 # 1 GiB copy at the start of that run.  Recorded constants: each names the summary under
 # profiles/ it was taken from (a counter run cannot share a process with the timed run).
+# Prefill score tensors in the tiled layout of include/lisa.h (the row-major time is reported beside it).
+TILED = True
+
 MEASURED_TRAFFIC = {
     ("c3_llama3_8b_gqa_l8192", "k_lisa_prefill_fused"):
-        (24.96e9 + 9.16e9, "profiles/lisa_prefill_fused_c3_kernel_trace_and_counters.md"),
+        (10.08e9 + 9.16e9, "profiles/lisa_prefill_fused_c3_kernel_trace_and_counters.md"),
     ("c4_llama2_13b_l4096", "k_lisa_prefill_fused"):
-        (15.75e9 + 6.06e9, "profiles/lisa_prefill_fused_c4_kernel_trace_and_counters.md"),
+        (10.60e9 + 6.08e9, "profiles/lisa_prefill_fused_c4_kernel_trace_and_counters.md"),
     ("c2_llama2_7b_l2048", "k_lisa_prefill_fused"):
-        (328.3e6 + 169.0e6, "profiles/lisa_prefill_fused_c2_kernel_trace_and_counters.md"),
+        (322.0e6 + 169.0e6, "profiles/lisa_prefill_fused_c2_kernel_trace_and_counters.md"),
 }
 
 
@@ -95,7 +98,7 @@ def cpu_baseline(cfg, inp, prev, budget_s=15.0):
     total_pos = cfg.B * L * (L + 1) // 2
 
     def run(rows):
-        prev_rows = hp.gather_score_rows(prev, 0, rows)
+        prev_rows = hp.gather_score_rows(prev, 0, rows, L)
         t0 = time.perf_counter()
         cref.lisa_rows(q_lr, k_lr, v, w1, w2, rows, prev_rows)
         return time.perf_counter() - t0
@@ -289,18 +292,18 @@ def graph_replay(steps, warmup):
     sets = []
     for s in range(4):
         inp = synth.make_prefill_inputs(cfg, synth.BASE_SEED + 2 + 100 * s, dev)
-        prev, _ = lisa.std_attn_scores(inp["q"], inp["k"])
+        prev, _ = lisa.std_attn_scores(inp["q"], inp["k"], tiled=TILED)
         sets.append(dict(inp=inp, prev=prev,
                          out=torch.empty((cfg.B, cfg.L, cfg.H, cfg.d_k), dtype=torch.float32, device=dev),
                          a_n=torch.empty_like(prev)))
     d0 = lisa.make_desc(cfg.torch_dtype, cfg.B, cfg.H, cfg.Hkv, cfg.L, cfg.L, cfg.d_k, cfg.r, cfg.F,
-                        write_scores=1, out_f32=1)
+                        write_scores=1, out_f32=1, score_tiled=int(TILED))
     ws = torch.empty(max(lisa.workspace_bytes(d0, lisa.WS_PREFILL), 256), dtype=torch.uint8, device=dev)
 
     def run(s):
         i = s["inp"]
         lisa.lisa_attn_prefill(i["q_lr"], i["k_lr"], i["v"], s["prev"], i["w1"], i["w2"],
-                               write_scores=True, out=s["out"], scores_out=s["a_n"], workspace=ws)
+                               write_scores=True, out=s["out"], scores_out=s["a_n"], workspace=ws, tiled=TILED)
 
     ref = []
     for s in sets:                                           # eager results (and warm-up)
@@ -356,14 +359,14 @@ def prefill_layer(cfg, seed_idx, steps, warmup, n_sets, cpu_budget, want_cpu):
     sets = []
     for s in range(n_sets):       # rotating sets: no step finds its scores in a cache
         inp = synth.make_prefill_inputs(cfg, synth.BASE_SEED + seed_idx + 100 * s, dev)
-        prev, _ = lisa.std_attn_scores(inp["q"], inp["k"])
+        prev, _ = lisa.std_attn_scores(inp["q"], inp["k"], tiled=TILED)
         if n_sets == 1:
             del inp["q"], inp["k"]
         sets.append(dict(inp=inp, prev=prev,
                          out=torch.empty((cfg.B, cfg.L, cfg.H, cfg.d_k), dtype=torch.float32, device=dev),
                          a_n=torch.empty_like(prev)))
     d0 = lisa.make_desc(cfg.torch_dtype, cfg.B, cfg.H, cfg.Hkv, cfg.L, cfg.L, cfg.d_k, cfg.r, cfg.F,
-                        write_scores=1, out_f32=1)
+                        write_scores=1, out_f32=1, score_tiled=int(TILED))
     ws = torch.empty(max(lisa.workspace_bytes(d0, lisa.WS_PREFILL), 256), dtype=torch.uint8, device=dev)
     counter = [0]
 
@@ -372,14 +375,14 @@ def prefill_layer(cfg, seed_idx, steps, warmup, n_sets, cpu_budget, want_cpu):
         counter[0] += 1
         i = s["inp"]
         lisa.lisa_attn_prefill(i["q_lr"], i["k_lr"], i["v"], s["prev"], i["w1"], i["w2"],
-                               write_scores=True, out=s["out"], scores_out=s["a_n"], workspace=ws)
+                               write_scores=True, out=s["out"], scores_out=s["a_n"], workspace=ws, tiled=TILED)
 
     def step_ro():
         s = sets[counter[0] % n_sets]
         counter[0] += 1
         i = s["inp"]
         lisa.lisa_attn_prefill(i["q_lr"], i["k_lr"], i["v"], s["prev"], i["w1"], i["w2"],
-                               write_scores=False, out=s["out"], workspace=ws)
+                               write_scores=False, out=s["out"], workspace=ws, tiled=TILED)
 
     # ---- the timed region: exactly `steps` LiSA layers ------------------------------------
     lisa.profile_enable(False)
@@ -408,6 +411,18 @@ def prefill_layer(cfg, seed_idx, steps, warmup, n_sets, cpu_budget, want_cpu):
         "mfma_frac_of_bf16_peak": layer_flops / (dom_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
     }
     sec_ro = time_steps(step_ro, max(steps // 2, 1), 1)
+    # the same layer on row-major score tensors [B,H,L,L] (one buffer set; the layout is the caller's choice)
+    s0 = sets[0]
+    prev_rm = lisa.untile_scores(s0["prev"], cfg.L, cfg.L) if TILED else s0["prev"]
+    a_rm = torch.empty_like(prev_rm)
+
+    def step_rm():
+        i = s0["inp"]
+        lisa.lisa_attn_prefill(i["q_lr"], i["k_lr"], i["v"], prev_rm, i["w1"], i["w2"],
+                               write_scores=True, out=s0["out"], scores_out=a_rm, workspace=ws)
+
+    sec_rm = time_steps(step_rm, max(steps // 4, 2), 1)
+    del prev_rm, a_rm
     rec = {
         "workload": workload_name(cfg), "tokens_per_s": cfg.B * cfg.L / sec, "ms_per_step": sec * 1e3,
         "ms_per_step_median": each[len(each) // 2], "ms_per_step_min": each[0], "timed_iterations": len(each),
@@ -418,6 +433,8 @@ def prefill_layer(cfg, seed_idx, steps, warmup, n_sets, cpu_budget, want_cpu):
         "layer_mfma_frac": layer_flops / sec / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         "lisa_layer_no_score_write_ms": sec_ro * 1e3,
         "lisa_layer_no_score_write_tokens_per_s": cfg.B * cfg.L / sec_ro,
+        "score_layout": "tiles of 16 rows x 32 keys" if TILED else "row-major",
+        "lisa_layer_row_major_scores_ms": sec_rm * 1e3,
     }
     if want_cpu:
         rec["cpu_baseline"] = cpu_baseline(cfg, sets[0]["inp"], sets[0]["prev"], cpu_budget)
@@ -426,7 +443,8 @@ def prefill_layer(cfg, seed_idx, steps, warmup, n_sets, cpu_budget, want_cpu):
 
 def workload_name(cfg):
     return (f"{cfg.name}: B{cfg.B} L{cfg.L} d{cfg.d_model} H{cfg.H}/{cfg.Hkv} dk{cfg.d_k} r{cfg.r} "
-            f"FFN {cfg.H}->{cfg.F}->{cfg.H} ReLU, Integrate=add, causal, A_n emitted, fp16 scores, fp32 O")
+            f"FFN {cfg.H}->{cfg.F}->{cfg.H} ReLU, Integrate=add, causal, A_n emitted, fp16 scores"
+            f"{' in 16x32 tiles' if TILED else ''}, fp32 O")
 
 
 def c2_extras(cfg, sets, ws, steps):
@@ -443,7 +461,7 @@ def c2_extras(cfg, sets, ws, steps):
         s = sets[counter[0] % n_sets]
         counter[0] += 1
         i = s["inp"]
-        lisa.std_attn_scores(i["q"], i["k"], scores_out=s["prev"])
+        lisa.std_attn_scores(i["q"], i["k"], scores_out=s["prev"], tiled=TILED)
 
     ds = lisa.make_desc(cfg.torch_dtype, cfg.B, cfg.H, cfg.Hkv, cfg.L, cfg.L, cfg.d_k, out_f32=1)
     ws_std = torch.empty(max(lisa.workspace_bytes(ds, lisa.WS_STD), 256), dtype=torch.uint8, device=dev)
@@ -452,7 +470,8 @@ def c2_extras(cfg, sets, ws, steps):
         s = sets[counter[0] % n_sets]
         counter[0] += 1
         i = s["inp"]
-        lisa.std_attn_scores(i["q"], i["k"], i["v"], scores_out=s["prev"], out=s["out"], workspace=ws_std)
+        lisa.std_attn_scores(i["q"], i["k"], i["v"], scores_out=s["prev"], out=s["out"], workspace=ws_std,
+                             tiled=TILED)
 
     # (the standard layer overwrites `prev` with the same values: the sets stay valid)
     extra["std_scores_layer_ms"] = time_steps(step_std, max(steps // 2, 1), 1) * 1e3
@@ -472,7 +491,7 @@ def c2_extras(cfg, sets, ws, steps):
         i = s["inp"]
         step_proj()
         lisa.lisa_attn_prefill(pq, pk, pv, s["prev"], i["w1"], i["w2"], write_scores=True, out=s["out"],
-                               scores_out=s["a_n"], workspace=ws)
+                               scores_out=s["a_n"], workspace=ws, tiled=TILED)
 
     sec_proj = time_steps(step_proj, max(steps // 2, 1), 2)
     proj_path = lisa.last_path()
@@ -527,6 +546,8 @@ def c2_extras(cfg, sets, ws, steps):
     i0 = s0["inp"]
     g = torch.Generator(device=dev).manual_seed(3)
     w_single = (torch.randn((cfg.H, cfg.H), generator=g, device=dev) / cfg.H ** 0.5).to(cfg.torch_dtype)
+    prev_rm = lisa.untile_scores(s0["prev"], cfg.L, cfg.L) if TILED else None
+    a_rm = torch.empty_like(prev_rm) if TILED else None
     pcfg = cfg.scaled(name="paper_widths", r=20, F=256)
     pin = synth.make_prefill_inputs(pcfg, synth.BASE_SEED + 3, dev, mix="concat", std_layer=False)
     slin = synth.make_prefill_inputs(cfg.scaled(name="lisa_sl", r=32), synth.BASE_SEED + 4, dev, std_layer=False)
@@ -540,14 +561,17 @@ def c2_extras(cfg, sets, ws, steps):
              pin["v"]),
             ("lisa_sl_concat_64x32_r32", dict(mix=lisa.MIX_CONCAT, act=lisa.ACT_SINGLE), w_sl, None, slin["q_lr"],
              slin["k_lr"], slin["v"])):
+        # the CONCAT kernels take row-major scores
+        tl = TILED and kw.get("mix") != lisa.MIX_CONCAT
         dvar = lisa.make_desc(cfg.torch_dtype, cfg.B, cfg.H, cfg.Hkv, cfg.L, cfg.L, cfg.d_k,
                               ql.shape[3] if ql is not None else 0, w1v.shape[1] if w1v is not None else 0,
-                              write_scores=1, out_f32=1, **kw)
+                              write_scores=1, out_f32=1, score_tiled=int(tl), **kw)
         ws_var = torch.empty(max(lisa.workspace_bytes(dvar, lisa.WS_PREFILL), 256), dtype=torch.uint8, device=dev)
+        prev_v, a_v = (s0["prev"], s0["a_n"]) if tl or not TILED else (prev_rm, a_rm)
 
         def step_variant():
-            lisa.lisa_attn_prefill(ql, kl, vv, s0["prev"], w1v, w2v, write_scores=True, out=s0["out"],
-                                   scores_out=s0["a_n"], workspace=ws_var, **kw)
+            lisa.lisa_attn_prefill(ql, kl, vv, prev_v, w1v, w2v, write_scores=True, out=s0["out"],
+                                   scores_out=a_v, workspace=ws_var, tiled=tl, Lq=cfg.L, **kw)
         lisa.profile_enable(False)
         ms = time_steps(step_variant, 3, 1) * 1e3
         lisa.profile_enable(True)

@@ -328,3 +328,32 @@ def test_decode_stack_rejects_bad_stacks_before_any_launch():
     assert lib.lisa_decode_stack(C.byref(d), None, 1, P[6], 1 << 40, None) == -1
     bad = lisa.make_desc(lisa.BF16, 2, 8, 4, 1, 100, 128, 22, 32, mix=lisa.MIX_SHARE, kcache_dim_major=1, Lmax=128)
     assert call([layer(lisa.LAYER_STD)], desc=bad) == -2
+
+
+def test_tiled_score_layout_is_validated_and_sized_on_the_host():
+    """score_tiled: a flag of the prefill calls of the bf16 matrix-core kernels (tiles of 16 rows x 32
+    keys, 1 KB each); sizes count whole tiles; other values, decode steps and shapes outside those
+    kernels are refused before any HIP call."""
+    lib = lisa.library()
+    d = lisa.make_desc(lisa.BF16, 2, 32, 8, 100, 200, 128, 22, 64, write_scores=1, score_tiled=1)
+    assert lib.lisa_scores_elems(C.byref(d)) == 2 * 32 * 7 * 7 * 512          # ceil(100/16) x ceil(200/32) tiles
+    assert lisa.scores_bytes(d) == 2 * 32 * 7 * 7 * 512 * 2
+    rm = lisa.make_desc(lisa.BF16, 2, 32, 8, 100, 200, 128, 22, 64, write_scores=1)
+    assert lib.lisa_scores_elems(C.byref(rm)) == 2 * 32 * 100 * 200
+    assert lisa.scores_shape(2, 32, 100, 200, True) == (2, 32, 7, 7, 16, 32)
+    assert lib.lisa_scores_elems(None) == 0
+    big = 1 << 40
+    bad = lisa.make_desc(lisa.BF16, 2, 32, 8, 100, 200, 128, 22, 64, write_scores=1, score_tiled=2)
+    assert lib.lisa_attn_prefill(C.byref(bad), *([FAKE] * 6), FAKE, C.c_void_p(0x20000), FAKE, big, None) == -2
+    # a decode step hands over score rows, not tiles
+    dec = lisa.make_desc(lisa.BF16, 2, 32, 8, 1, 200, 128, 22, 64, write_scores=1, Lmax=256, score_tiled=1)
+    ptrs = [C.c_void_p(0x10000 + 0x1000 * i) for i in range(11)]
+    assert lib.lisa_attn_decode(C.byref(dec), *ptrs, big, None) == -3
+    # shapes that run on the generic kernels (fp32; F beyond the fused kernel; the CONCAT form)
+    f32 = lisa.make_desc(lisa.F32, 1, 4, 4, 64, 64, 64, 8, 16, write_scores=1, score_tiled=1)
+    wide = lisa.make_desc(lisa.BF16, 1, 32, 32, 64, 64, 128, 20, 256, write_scores=1, score_tiled=1)
+    cat = lisa.make_desc(lisa.BF16, 1, 32, 32, 64, 64, 128, 20, 256, mix=lisa.MIX_CONCAT, write_scores=1,
+                         score_tiled=1)
+    for desc in (f32, wide, cat):
+        assert lib.lisa_attn_prefill(C.byref(desc), *([FAKE] * 6), FAKE, C.c_void_p(0x20000), FAKE, big, None) == -3
+    assert lib.std_attn_scores(C.byref(f32), FAKE, FAKE, None, FAKE, None, None, 0, None) == -3
