@@ -111,11 +111,13 @@ typedef struct lisa_desc {
 /*
  * Tiled score layout (score_tiled = 1; prefill calls of the bf16 matrix-core kernels only, other
  * requests return LISA_ERR_UNSUPPORTED).  A score tensor is then
- *     [B, H, ceil(Lq / 16), ceil(Lk / 32), 16, 32]     (lisa_scores_elems() elements)
- * i.e. tile (rb, kt) of a head holds rows 16 rb .. 16 rb + 15 and keys 32 kt .. 32 kt + 31 as 1 KB of
- * consecutive memory: what a workgroup of the LiSA layer reads per head and step.  In [B,H,Lq,Lk]
- * that piece is 16 separate half lines, each fetched from HBM as a whole line and again one step
- * later for its other half; tiled, the layer moves a third fewer bytes and runs a fifth faster.
+ *     [B, ceil(Lq / 16), ceil(Lk / 32), H, 16, 32]     (lisa_scores_elems() elements)
+ * i.e. tile (rb, kt) holds, head after head, rows 16 rb .. 16 rb + 15 and keys 32 kt .. 32 kt + 31 of
+ * every head as 1 KB of consecutive memory each: what a workgroup of the LiSA layer reads per
+ * step is one run of H KB.  In [B,H,Lq,Lk] the piece of a head is 16 separate half lines, each
+ * fetched from HBM as a whole line and again one step later for its other half, and the pieces of
+ * the H heads lie in H pages of the address translation; tiled, the layer moves a third fewer
+ * bytes.
  * The standard layer writes this layout, the LiSA layer reads and writes it.  Entries of a stored
  * tile that lie above the diagonal, beyond row Lq - 1 or beyond key Lk - 1 are unspecified; tiles
  * wholly above the diagonal are neither written nor read.

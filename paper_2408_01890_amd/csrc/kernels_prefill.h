@@ -79,7 +79,7 @@ struct PrefillArgs {
   float* part_ml;         // [split][B][Lqp][H][2]   running maximum, partial sum
   int pair;               // workgroup x takes the units (last - x) and x
   int B;                  // sequences
-  int tiled;              // prev and scores are [B,H,ceil(Lq/16),ceil(Lk/32),16,32] (1 KB per tile)
+  int tiled;              // prev and scores are [B,ceil(Lq/16),ceil(Lk/32),H,16,32] (1 KB per head and tile)
 };
 
 typedef unsigned short pf_u16x8 __attribute__((ext_vector_type(8)));
@@ -317,10 +317,11 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
   const int h_first = hg0 + wv * HPW;
 
   Ffn::stage(a.w1, a.w2, H, a.F, w_s, tid, THREADS, hg0, GH);
-  // One head per wave leaves registers for the FFN weights: fetched once per workgroup instead of
-  // read from LDS by every block pair.  (Two heads with shared operands would have the room too:
-  // measured, no gain.)
-  constexpr bool WREG = HPW == 1 && RS == 1 && NW <= 8 && (Ffn::FB * Ffn::KS + HBO * FS) <= 8;
+  // One head per wave, or two with shared operands, leave registers for the FFN weights: fetched
+  // once per workgroup instead of read from LDS, each read followed by a wait, by every block
+  // pair (5 % on the LLaMA3-8B shape once the score tensors are tiled; nothing before that, when
+  // the layer waited for HBM).
+  constexpr bool WREG = (HPW == 1 || (SHKV && HPW == 2)) && RS == 1 && NW <= 8 && (Ffn::FB * Ffn::KS + HBO * FS) <= 8;
   // blocks of 16 positions whose MFMA chains are interleaved in stage A (one at a time where the
   // accumulators of four row slices leave no registers for a second chain)
   constexpr int NBLK = RS >= 4 ? 1 : 2;
@@ -330,9 +331,16 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
     ffn.fetch(w_s);
   }
 
-  // score tensors: elements per head, and the tile grid of the tiled layout
+  // score tensors.  Row-major: head h of sequence b starts at (b H + h) Lq Lk.  Tiled: tile (rb, kt)
+  // of sequence b holds the H pieces of 16 rows x 32 keys one after the other, 1 KB each -- what a
+  // workgroup reads per step is one run of H KB, in one page of the address translation (with a
+  // tensor per head the 32 + 16 pieces of a step lay in as many pages and every step missed in the
+  // translation cache of the compute unit for most of them: 36 misses per step).
   const int n_rb = (Lq + PF_ROWS - 1) / PF_ROWS, n_kt = (Lk + PF_TK - 1) / PF_TK;
-  const size_t head_elems = a.tiled ? (size_t)n_rb * n_kt * (PF_ROWS * PF_TK) : (size_t)Lq * Lk;
+  constexpr int TILE_ELEMS = PF_ROWS * PF_TK;
+  const size_t head_elems = a.tiled ? (size_t)TILE_ELEMS : (size_t)Lq * Lk;                 // head stride
+  const size_t seq_elems = a.tiled ? (size_t)n_rb * n_kt * H * TILE_ELEMS : (size_t)H * Lq * Lk;
+  const size_t tile_stride = (size_t)H * TILE_ELEMS;        // tiled: elements from one (rb, kt) to the next
   // wave-uniform bases of this wave's heads (scalar registers)
   const bf16_t* k_base[HPW];     // K_LR rows of the head's key/value head
   const bf16_t* v_base[HPW];     // V chunks of it
@@ -342,11 +350,12 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
     const int h = h_first + hh, kv = h / group;
     k_base[hh] = a.kp + ((size_t)b * a.Hkv + kv) * a.Lkp * 32;
     v_base[hh] = a.vt + ((size_t)b * a.Hkv + kv) * (a.Lkp / 8) * (DK * 8);
-    s_base[hh] = a.scores ? a.scores + ((size_t)b * H + h) * head_elems : nullptr;
+    s_base[hh] = a.scores ? a.scores + (size_t)b * seq_elems + (size_t)h * head_elems : nullptr;
   }
   const half_t* x_base[XCH];     // A_{n-1} of head wv + NW u (XSTG: of the wave's own heads)
 #pragma unroll
-  for (int u = 0; u < XCH; ++u) x_base[u] = a.prev + ((size_t)b * H + (XSTG ? wv * HPW + u : wv + NW * u)) * head_elems;
+  for (int u = 0; u < XCH; ++u)
+    x_base[u] = a.prev + (size_t)b * seq_elems + (size_t)(XSTG ? wv * HPW + u : wv + NW * u) * head_elems;
   // per-lane byte offsets, the same for every head
   const unsigned k_off = ((8 * (c >> 2) + (c & 3)) * 32 + 8 * g) * 2;   // MFMA row c -> key 8 (c/4) + c%4 (+4)
   const unsigned v_off = (g * DK + c) * 16;                             // key chunk g, feature c (+16 nb)
@@ -422,15 +431,17 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
     // it fetched once, changed little).  Tiled scores: the piece is 1 KB of consecutive memory.
     auto load_x = [&](int tile, int rs, pf_u32x4 (&xr)[XCH]) {
       unsigned off;
+      size_t at = 0;                                          // wave-uniform element offset of the tile
       if (a.tiled) {
-        off = ((unsigned)min((i0 >> 4) + rs, n_rb - 1) * n_kt + tile) * (PF_ROWS * PF_TK * 2) + lane * 16;
+        at = ((size_t)min((i0 >> 4) + rs, n_rb - 1) * n_kt + tile) * tile_stride;
+        off = lane * 16;
       } else {
         const unsigned x_row = (unsigned)min(i0 + PF_ROWS * rs + (lane >> 2), Lq - 1) * Lk * 2;
         // keys >= Lk: any in-bounds chunk will do, those positions are masked in stage B
         off = x_row + 2 * min(tile * PF_TK + xq8, Lk - 8);
       }
 #pragma unroll
-      for (int u = 0; u < XCH; ++u) xr[u] = ld_uv_stream<pf_u32x4>(x_base[u], off);
+      for (int u = 0; u < XCH; ++u) xr[u] = ld_uv_stream<pf_u32x4>(x_base[u] + at, off);
     };
     auto store_x = [&](const pf_u32x4 (&xr)[XCH], int tile) {   // XSTG: into the buffer of the tile's parity
       unsigned char* dst = xs + (XSTG ? (tile & 1) * (H * PF_XS_HEAD) : 0) + xdst;
@@ -512,8 +523,8 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
           const unsigned char* sp =
               XSTG ? xs + u * (H * PF_XS_HEAD) + (wv * HPW + hh) * PF_XS_HEAD + (lane >> 2) * (2 * PF_TK) + (lane & 3) * 16
                    : as_ + (hh * RS + rs) * PF_AS_HEAD + (lane >> 2) * PF_AS_ROW + u * 64 + (lane & 3) * 16;
-          const unsigned toff = ((unsigned)((i0 >> 4) + rs) * n_kt + tl) * (PF_ROWS * PF_TK * 2) + lane * 16;
-          st_uv_stream<f16x8>(s_base[hh], toff, *(const f16x8*)sp);
+          const size_t at = ((size_t)((i0 >> 4) + rs) * n_kt + tl) * tile_stride;   // wave-uniform
+          st_uv_stream<f16x8>(s_base[hh] + at, lane * 16, *(const f16x8*)sp);
         }
         return;
       }

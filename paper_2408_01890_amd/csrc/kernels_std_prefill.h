@@ -34,7 +34,7 @@ struct StdPrefillArgs {
   int H, Hkv, Lq, Lk, Lkp, causal, out_f32;
   int pair;               // 1: a workgroup takes two row groups (grid.y = ceil(n_groups / 2)), 0: one
   float scale;
-  int tiled;              // scores are written as [B,H,ceil(Lq/16),ceil(Lk/32),16,32] (not with GIVEN)
+  int tiled;              // scores are written as [B,ceil(Lq/16),ceil(Lk/32),H,16,32] (not with GIVEN)
 };
 
 __device__ __forceinline__ float halves_max(float v) {
@@ -123,8 +123,10 @@ __global__ __launch_bounds__(256, 2) void k_std_prefill(StdPrefillArgs a) {
     const float* grow = GIVEN == 1 ? (const float*)a.given + grow_at : nullptr;
     const half_t* grow_h = GIVEN == 2 ? (const half_t*)a.given + grow_at : nullptr;
     const int n_kt = (Lk + SP_TK - 1) / SP_TK;               // tile grid of the tiled score layout
-    const size_t head_elems = a.tiled ? (size_t)((Lq + 15) / 16) * n_kt * (16 * SP_TK) : (size_t)Lq * Lk;
-    half_t* sbase = a.scores ? a.scores + ((size_t)b * H + h) * head_elems : nullptr;
+    // (tiled: the H pieces of a tile follow each other, 1 KB each; see k_lisa_prefill_fused)
+    const size_t seq_elems = a.tiled ? (size_t)((Lq + 15) / 16) * n_kt * H * (16 * SP_TK) : (size_t)H * Lq * Lk;
+    half_t* sbase = a.scores ? a.scores + (size_t)b * seq_elems + (size_t)h * (a.tiled ? (size_t)16 * SP_TK : (size_t)Lq * Lk)
+                             : nullptr;
     unsigned char* stg = ss_ + wv * SP_STILE;
 
     // The K / V tile of a step travels through registers: loaded three tiles ahead into one of two
@@ -236,7 +238,7 @@ __global__ __launch_bounds__(256, 2) void k_std_prefill(StdPrefillArgs a) {
             if (16 * rbq >= Lq) continue;                      // (wave-uniform)
             const f16x8 hv =
                 *(const f16x8*)(stg + (16 * q + (lane >> 2)) * SP_SROW + (tile & 1) * 64 + (lane & 3) * 16);
-            *(f16x8*)((char*)sbase + ((size_t)rbq * n_kt + tile) * (16 * SP_TK * 2) + lane * 16) = hv;
+            *(f16x8*)((char*)sbase + ((size_t)rbq * n_kt + tile) * H * (16 * SP_TK * 2) + lane * 16) = hv;
           }
         } else if ((tile & 1) == 1 || tile == n_tiles_w - 1) {
           const int jc = (tile >> 1) * (2 * SP_TK) + 8 * (lane & 7);

@@ -153,10 +153,10 @@ TILE_ROWS, TILE_KEYS = 16, 32
 
 
 def scores_shape(B, H, Lq, Lk, tiled=False):
-    """Shape of a prefill score tensor: [B,H,Lq,Lk], or its tiles [B,H,ceil(Lq/16),ceil(Lk/32),16,32]."""
+    """Shape of a prefill score tensor: [B,H,Lq,Lk], or its tiles [B,ceil(Lq/16),ceil(Lk/32),H,16,32]."""
     if not tiled:
         return (B, H, Lq, Lk)
-    return (B, H, -(-Lq // TILE_ROWS), -(-Lk // TILE_KEYS), TILE_ROWS, TILE_KEYS)
+    return (B, -(-Lq // TILE_ROWS), -(-Lk // TILE_KEYS), H, TILE_ROWS, TILE_KEYS)
 
 
 def tile_scores(s):
@@ -165,13 +165,13 @@ def tile_scores(s):
     nr, nk = -(-Lq // TILE_ROWS), -(-Lk // TILE_KEYS)
     p = torch.zeros((B, H, nr * TILE_ROWS, nk * TILE_KEYS), dtype=s.dtype, device=s.device)
     p[:, :, :Lq, :Lk] = s
-    return p.view(B, H, nr, TILE_ROWS, nk, TILE_KEYS).permute(0, 1, 2, 4, 3, 5).contiguous()
+    return p.view(B, H, nr, TILE_ROWS, nk, TILE_KEYS).permute(0, 2, 4, 1, 3, 5).contiguous()
 
 
 def untile_scores(t, Lq, Lk):
     """Tiled layout -> [B,H,Lq,Lk] (a copy)."""
-    B, H, nr, nk = t.shape[:4]
-    return t.permute(0, 1, 2, 4, 3, 5).reshape(B, H, nr * TILE_ROWS, nk * TILE_KEYS)[:, :, :Lq, :Lk].contiguous()
+    B, nr, nk, H = t.shape[:4]
+    return t.permute(0, 3, 1, 4, 2, 5).reshape(B, H, nr * TILE_ROWS, nk * TILE_KEYS)[:, :, :Lq, :Lk].contiguous()
 
 
 def score_dtype(dtype) -> torch.dtype:
@@ -331,7 +331,7 @@ def lisa_attn_prefill(q_lr, k_lr, v, scores_prev, w1, w2, *, mix=MIX_ADD, act=AC
     q_lr (or the Lq argument where there is no q_lr).
     Returns (out [B,Lq,H,d_k], scores_out [B,H,Lq,Lk] or None)."""
     if tiled:
-        B, H = scores_prev.shape[:2]
+        B, H = scores_prev.shape[0], scores_prev.shape[3]
         Lq = q_lr.shape[2] if q_lr is not None else Lq
         Lk = v.shape[2]
     else:
@@ -424,7 +424,7 @@ def lisa_layer_prefill(x, w_qkv, Hkv, r, d_k, scores_prev, w1, w2, *, rope_theta
     lisa_project_qkv) then lisa_attn_prefill.  Returns (out, scores_out or None, (q_lr, k_lr, v)),
     the last being views of the workspace."""
     B, L, D = x.shape
-    H = scores_prev.shape[1]
+    H = scores_prev.shape[3] if tiled else scores_prev.shape[1]
     Din, F = w1.shape
     dt = x.dtype
     sdt = score_dtype(dt)

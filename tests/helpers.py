@@ -79,11 +79,12 @@ def oracle_lisa_rows(inp, b, rows, prev_rows, mix=0, delta_scale=None):
 
 def gather_score_rows(scores: torch.Tensor, b: int, rows, Lk=None) -> np.ndarray:
     """scores [B,H,Lq,Lk] (device) -> float64 [n,H,Lk] for batch b, rows.  A 6-dimensional tensor is
-    the tiled layout [B,H,Lq/16,Lk/32,16,32]; its rows are cut to Lk keys when Lk is given."""
+    the tiled layout [B,Lq/16,Lk/32,H,16,32]; its rows are cut to Lk keys when Lk is given."""
     idx = torch.as_tensor(np.asarray(rows), device=scores.device, dtype=torch.long)
     if scores.dim() == 6:
-        s = scores[b]                                            # [H, nr, nk, 16, 32]
-        got = s[:, idx // 16, :, idx % 16, :]                    # [n, H, nk, 32]
+        s = scores[b]                                            # [nr, nk, H, 16, 32]
+        got = s[idx // 16, :, :, idx % 16, :]                    # [n, nk, H, 32]
+        got = got.permute(0, 2, 1, 3)                            # [n, H, nk, 32]
         got = got.reshape(got.shape[0], got.shape[1], -1)
         return f64(got if Lk is None else got[:, :, :Lk])
     return f64(scores[b].index_select(1, idx).permute(1, 0, 2))

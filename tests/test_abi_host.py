@@ -340,7 +340,7 @@ def test_tiled_score_layout_is_validated_and_sized_on_the_host():
     assert lisa.scores_bytes(d) == 2 * 32 * 7 * 7 * 512 * 2
     rm = lisa.make_desc(lisa.BF16, 2, 32, 8, 100, 200, 128, 22, 64, write_scores=1)
     assert lib.lisa_scores_elems(C.byref(rm)) == 2 * 32 * 100 * 200
-    assert lisa.scores_shape(2, 32, 100, 200, True) == (2, 32, 7, 7, 16, 32)
+    assert lisa.scores_shape(2, 32, 100, 200, True) == (2, 7, 7, 32, 16, 32)
     assert lib.lisa_scores_elems(None) == 0
     big = 1 << 40
     bad = lisa.make_desc(lisa.BF16, 2, 32, 8, 100, 200, 128, 22, 64, write_scores=1, score_tiled=2)

@@ -1,4 +1,4 @@
-"""The tiled score layout ([B,H,Lq/16,Lk/32,16,32], 1 KB per tile): the standard layer writes it, the
+"""The tiled score layout ([B,Lq/16,Lk/32,H,16,32], 1 KB per head and tile): the standard layer writes it, the
 LiSA layer reads and writes it.  The row-major path is checked against the oracle elsewhere; here
 the tiled path must give the same bits (same arithmetic, other addresses) on shapes that cover every
 instantiation and launch geometry of the fused kernel, and is checked against the oracle directly
