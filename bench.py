@@ -66,11 +66,11 @@ TILED = True
 
 MEASURED_TRAFFIC = {
     ("c3_llama3_8b_gqa_l8192", "k_lisa_prefill_fused"):
-        (10.08e9 + 9.16e9, "profiles/lisa_prefill_fused_c3_kernel_trace_and_counters.md"),
+        (10.07e9 + 9.16e9, "profiles/lisa_prefill_fused_c3_kernel_trace_and_counters.md"),
     ("c4_llama2_13b_l4096", "k_lisa_prefill_fused"):
         (10.60e9 + 6.08e9, "profiles/lisa_prefill_fused_c4_kernel_trace_and_counters.md"),
     ("c2_llama2_7b_l2048", "k_lisa_prefill_fused"):
-        (322.0e6 + 169.0e6, "profiles/lisa_prefill_fused_c2_kernel_trace_and_counters.md"),
+        (318.6e6 + 169.9e6, "profiles/lisa_prefill_fused_c2_kernel_trace_and_counters.md"),
 }
 
 
