@@ -73,3 +73,23 @@ def lisa_layer(q_lr, k_lr, v, w1, w2, prev, mix=MIX_ADD, delta_scale=None):
     a_n = lisa_scores(q_lr, k_lr, w1, w2, prev, mix, delta_scale)
     o, p = softmax_v(a_n, v)
     return a_n, o, p
+
+
+def huber(a, b, delta=1.0):
+    """App. C.1 "Huber loss function": elementwise L_delta(a, b) = (a - b)^2 / 2 where |a - b| <= delta,
+    delta (|a - b| - delta / 2) otherwise."""
+    d = np.abs(np.asarray(a, np.float64) - np.asarray(b, np.float64))
+    return np.where(d <= delta, 0.5 * d * d, delta * (d - 0.5 * delta))
+
+
+def kd_loss(scores, teacher, delta=1.0, causal=True):
+    """Sec. 5.1 "Training strategy": the regression term of one LiSA layer, L_delta(A_n, A_n^*), for
+    score tensors [..., Lq, Lk]: the mean of the elementwise Huber loss over the entries a query
+    row can see (the paper gives no reduction; the mean is the reading taken, that of the usual
+    library routine).  L_KD is the mean of this over the layers of S."""
+    scores = np.asarray(scores, np.float64)
+    teacher = np.asarray(teacher, np.float64)
+    Lq, Lk = scores.shape[-2:]
+    vis = visible(Lq, Lk) if causal else np.ones((Lq, Lk), bool)
+    el = huber(scores, teacher, delta)
+    return float(el[..., vis].mean())

@@ -632,3 +632,52 @@ def test_direct_sharing_is_textbook_attention_on_the_previous_scores():
     a2, out2 = cref.lisa_rows(q_lr, k_lr, v, None, None, all_rows(L), prev, mix=cref.MIX_SHARE)
     np.testing.assert_array_equal(a2, a_n)
     np.testing.assert_array_equal(out2, out)
+
+
+# ---------------------------------------------------------------------------------------
+# knowledge-distillation regression term (Sec. 5.1 "Training strategy", App. C.1 Huber loss)
+# ---------------------------------------------------------------------------------------
+def test_huber_loss_values_worked_by_hand():
+    """delta = 1: differences 0.5, -0.5, 1, 2, -3 give 1/8, 1/8, 1/2 (both branches agree at
+    |d| = delta), 3/2, 5/2; delta = 2: a difference of 3 gives 2 (3 - 1) = 4."""
+    from oracle import npref
+    a = np.array([0.5, 1.0, 3.0, 5.0, -1.0])
+    b = np.array([0.0, 1.5, 2.0, 3.0, 2.0])
+    assert np.allclose(npref.huber(a, b, 1.0), [0.125, 0.125, 0.5, 1.5, 2.5], rtol=0, atol=1e-15)
+    assert npref.huber(3.0, 0.0, 2.0) == 4.0
+    assert npref.huber(1.25, 1.25, 1.0) == 0.0
+
+
+def test_huber_loss_matches_the_library_routine_and_its_two_regimes():
+    from scipy.special import huber as sp_huber
+    from oracle import npref
+    rng = np.random.default_rng(5)
+    a, b = rng.normal(size=4000) * 2, rng.normal(size=4000) * 2
+    for delta in (0.5, 1.0, 3.0):
+        assert np.allclose(npref.huber(a, b, delta), sp_huber(delta, a - b), rtol=1e-14, atol=0)
+    small = np.abs(a - b) <= 1.0                            # quadratic regime = half the squared error
+    assert np.allclose(npref.huber(a, b)[small], 0.5 * (a - b)[small] ** 2)
+    assert np.allclose(npref.huber(a, b)[~small], np.abs(a - b)[~small] - 0.5)   # linear regime, delta = 1
+    assert np.array_equal(npref.huber(a, b), npref.huber(b, a))                  # symmetric
+    # L_delta(d) = delta^2 L_1(d / delta)
+    assert np.allclose(npref.huber(a, b, 3.0), 9.0 * npref.huber(a / 3.0, b / 3.0, 1.0))
+
+
+def test_kd_loss_is_the_mean_over_visible_entries_only():
+    from oracle import npref
+    rng = np.random.default_rng(6)
+    H, Lq, Lk = 3, 5, 7
+    s, t = rng.normal(size=(2, H, Lq, Lk)), rng.normal(size=(2, H, Lq, Lk))
+    vis = npref.visible(Lq, Lk)
+    want = np.mean([npref.huber(s[b, h, i, j], t[b, h, i, j]) for b in range(2) for h in range(H)
+                    for i in range(Lq) for j in range(Lk) if j <= i + Lk - Lq])
+    assert abs(npref.kd_loss(s, t) - want) < 1e-15
+    s2 = s.copy()
+    s2[..., ~vis] = 1e9                                     # what a row cannot see does not count
+    assert npref.kd_loss(s2, t) == npref.kd_loss(s, t)
+    assert npref.kd_loss(s, s) == 0.0
+    full = npref.kd_loss(s, t, causal=False)
+    assert abs(full - npref.huber(s, t).mean()) < 1e-15
+    # differences all below delta: half the mean squared error; all above: mean absolute error - 1/2
+    assert abs(npref.kd_loss(t + 0.25, t) - 0.03125) < 1e-15
+    assert abs(npref.kd_loss(t + 4.0, t) - 3.5) < 1e-12
