@@ -423,6 +423,15 @@ def prefill_layer(cfg, seed_idx, steps, warmup, n_sets, cpu_budget, want_cpu):
 
     sec_rm = time_steps(step_rm, max(steps // 4, 2), 1)
     del prev_rm, a_rm
+    # the regression term of the distillation loss (Sec. 5.1 training strategy) between the layer's
+    # A_n and another score tensor of the same shape (here A_{n-1}: two reads of the visible entries)
+    kd_out = torch.zeros(2, dtype=torch.float64, device=dev)
+
+    def step_kd():
+        lisa.lisa_kd_huber(s0["a_n"], s0["prev"], Lq=cfg.L, Lk=cfg.L, tiled=TILED, out=kd_out)
+
+    sec_kd = time_steps(step_kd, max(steps // 4, 2), 1)
+    kd_bytes = 2.0 * pos * cfg.H * 2
     rec = {
         "workload": workload_name(cfg), "tokens_per_s": cfg.B * cfg.L / sec, "ms_per_step": sec * 1e3,
         "ms_per_step_median": each[len(each) // 2], "ms_per_step_min": each[0], "timed_iterations": len(each),
@@ -435,6 +444,7 @@ def prefill_layer(cfg, seed_idx, steps, warmup, n_sets, cpu_budget, want_cpu):
         "lisa_layer_no_score_write_tokens_per_s": cfg.B * cfg.L / sec_ro,
         "score_layout": "tiles of 16 rows x 32 keys" if TILED else "row-major",
         "lisa_layer_row_major_scores_ms": sec_rm * 1e3,
+        "kd_huber_loss_ms": sec_kd * 1e3, "kd_huber_hbm_frac": kd_bytes / sec_kd / 1e9 / HBM_PEAK_GBS,
     }
     if want_cpu:
         rec["cpu_baseline"] = cpu_baseline(cfg, sets[0]["inp"], sets[0]["prev"], cpu_budget)

@@ -82,7 +82,8 @@ typedef enum {
 } lisa_status;
 
 typedef enum {
-  LISA_WS_PREFILL = 0, LISA_WS_DECODE = 1, LISA_WS_STD = 2, LISA_WS_LAYER = 3, LISA_WS_LAYER_DECODE = 4
+  LISA_WS_PREFILL = 0, LISA_WS_DECODE = 1, LISA_WS_STD = 2, LISA_WS_LAYER = 3, LISA_WS_LAYER_DECODE = 4,
+  LISA_WS_KD = 5
 } lisa_ws_kind;
 
 /* Problem descriptor (host memory, plain data, zero-initialise then fill). */
@@ -339,6 +340,28 @@ int lisa_layer_decode(const lisa_desc* desc, int32_t d_model, float rope_theta, 
 /* Byte offsets of Q_LR [B,H,Lq,r], K_LR [B,Hkv,Lq,r] and V [B,Hkv,Lq,d_k] inside the workspace of
  * lisa_layer_prefill; returns 0 or a negative lisa_status. */
 int lisa_layer_offsets(const lisa_desc* desc, size_t* q_lr_off, size_t* k_lr_off, size_t* v_off);
+
+/*
+ * lisa_kd_huber -- regression term of the knowledge-distillation loss for one LiSA layer
+ * (Sec. 5.1 "Training strategy": L_KD = 1/|S| sum_{n in S} L_delta(A_n, A_n^*); App. C.1 "Huber
+ * loss function": L_delta(a, b) = (a - b)^2 / 2 where |a - b| <= delta, delta (|a - b| - delta / 2)
+ * otherwise).  The paper states no reduction over the entries; this library takes the mean over
+ * the entries a query row can see (all entries when causal = 0), of all heads and sequences.
+ *   scores   in   A_n of the student, score type, [B,H,Lq,Lk] or tiled (desc->score_tiled)
+ *   teacher  in   A_n^* of the teacher, same type and layout
+ *   delta         threshold of the loss, > 0 (the paper uses 1)
+ *   weight, accumulate   out[0] = (accumulate ? out[0] : 0) + weight * mean: the |S| layers of a
+ *                 model are |S| calls with weight 1 / |S|, the first with accumulate = 0
+ *   out      out  2 doubles on the device: out[0] as above, out[1] = this layer's mean
+ *   workspace     at least lisa_workspace_bytes(desc, LISA_WS_KD) bytes (partial sums, added in a
+ *                 fixed order: the result does not depend on scheduling)
+ * Uses dtype, B, H, Lq, Lk, causal and score_tiled of the descriptor (tiled: LISA_BF16 only).
+ * Errors: LISA_ERR_NULL, LISA_ERR_SHAPE (delta <= 0 or not finite, weight not finite, bad
+ * dimensions), LISA_ERR_ALIGN (16-byte), LISA_ERR_WORKSPACE, LISA_ERR_UNSUPPORTED, LISA_ERR_HIP.
+ */
+int lisa_kd_huber(const lisa_desc* desc, const void* scores, const void* teacher, float delta,
+                  float weight, int accumulate, double* out, void* workspace,
+                  size_t workspace_bytes, void* hip_stream);
 
 /* Scratch bytes the given entry point (lisa_ws_kind) needs for this descriptor. */
 size_t lisa_workspace_bytes(const lisa_desc* desc, int which);

@@ -12,6 +12,7 @@
 #include <mutex>
 
 #include "kernels_decode.h"
+#include "kernels_kd.h"
 #include "kernels_generic.h"
 #include "kernels_prefill.h"
 #include "kernels_project.h"
@@ -1030,6 +1031,67 @@ int synth_relu_ffn(const lisa_desc* d, const void* w1_user, void* workspace, siz
   return check_launch();
 }
 
+// Workgroups of the loss kernel: four score rows each per pass, at most eight per compute unit.
+int kd_blocks(const lisa_desc* d) {
+  const long long rows = (long long)d->B * d->H * d->Lq;
+  return (int)std::min<long long>((rows + 3) / 4, 2048);
+}
+
+int lisa_kd_huber(const lisa_desc* desc, const void* scores, const void* teacher, float delta,
+                  float weight, int accumulate, double* out, void* workspace,
+                  size_t workspace_bytes, void* hip_stream) {
+  int rc = check_common(desc);
+  if (rc) return rc;
+  if (!scores || !teacher || !out) return LISA_ERR_NULL;
+  if (!(delta > 0.f) || !std::isfinite(delta) || !std::isfinite(weight)) return LISA_ERR_SHAPE;
+  if (accumulate != 0 && accumulate != 1) return LISA_ERR_SHAPE;
+  if (desc->score_tiled && desc->dtype != LISA_BF16) return LISA_ERR_UNSUPPORTED;
+  if (!aligned16(scores) || !aligned16(teacher) || !aligned16(out) || (workspace && !aligned16(workspace)))
+    return LISA_ERR_ALIGN;
+  const int n_blocks = kd_blocks(desc);
+  if (!workspace || workspace_bytes < (size_t)n_blocks * sizeof(double)) return LISA_ERR_WORKSPACE;
+  KdArgs g{};
+  g.a = scores;
+  g.t = teacher;
+  g.part = (double*)workspace;
+  g.out = out;
+  g.B = desc->B;
+  g.H = desc->H;
+  g.Lq = desc->Lq;
+  g.Lk = desc->Lk;
+  g.causal = desc->causal;
+  g.tiled = desc->score_tiled;
+  g.delta = delta;
+  g.weight = weight;
+  g.accumulate = accumulate;
+  g.n_blocks = n_blocks;
+  g.n_rows = (long long)desc->B * desc->H * desc->Lq;
+  // visible entries: row i sees min(Lk, i + 1 + Lk - Lq) keys (causal needs Lk >= Lq, checked above)
+  double per_head = 0.0;
+  if (desc->causal) {
+    const double first = (double)desc->Lk - desc->Lq + 1, last = (double)desc->Lk;
+    per_head = 0.5 * (first + last) * desc->Lq;
+  } else {
+    per_head = (double)desc->Lq * desc->Lk;
+  }
+  g.count = per_head * desc->B * desc->H;
+  hipStream_t st = (hipStream_t)hip_stream;
+  {
+    StageScope prof("k_kd_huber_part", st);
+    if (desc->dtype == LISA_F32)
+      k_kd_huber_part<float><<<n_blocks, 256, 0, st>>>(g);
+    else
+      k_kd_huber_part<half_t><<<n_blocks, 256, 0, st>>>(g);
+    rc = check_launch();
+    if (rc) return rc;
+  }
+  StageScope prof("k_kd_huber_finish", st);
+  k_kd_huber_finish<<<1, 256, 0, st>>>(g);
+  rc = check_launch();
+  if (rc == LISA_OK) g_path = "kd_huber";
+  return rc;
+}
+
 size_t lisa_workspace_bytes(const lisa_desc* desc, int which) {
   switch (which) {
     case LISA_WS_PREFILL: {
@@ -1068,6 +1130,9 @@ size_t lisa_workspace_bytes(const lisa_desc* desc, int which) {
       return round_up(lisa_workspace_bytes(desc, LISA_WS_DECODE), 256) +
              round_up((size_t)desc->B * desc->H * desc->r * e, 256);
     }
+    case LISA_WS_KD:
+      if (check_common(desc) != LISA_OK) return 0;
+      return (size_t)kd_blocks(desc) * sizeof(double);
     default:
       return 0;
   }

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "liblisa_mi355x.so")
 F32, BF16 = 0, 1
 MIX_ADD, MIX_CONCAT, MIX_PLUS, MIX_SHARE = 0, 1, 2, 3
 ACT_RELU, ACT_SILU, ACT_SINGLE = 0, 1, 2
-WS_PREFILL, WS_DECODE, WS_STD, WS_LAYER, WS_LAYER_DECODE = 0, 1, 2, 3, 4
+WS_PREFILL, WS_DECODE, WS_STD, WS_LAYER, WS_LAYER_DECODE, WS_KD = 0, 1, 2, 3, 4, 5
 
 EXPORTS = (
     "lisa_attn_prefill", "lisa_attn_decode", "std_attn_scores", "lisa_workspace_bytes",
@@ -28,7 +28,7 @@ EXPORTS = (
     "lisa_strerror", "lisa_last_hip_error", "lisa_last_path", "lisa_profile_enable",
     "lisa_profile_collect", "lisa_cache_fill", "lisa_project_qkv", "lisa_layer_prefill",
     "lisa_layer_offsets", "lisa_layer_decode", "lisa_tune_set", "lisa_attn_decode_static",
-    "lisa_decode_stack", "lisa_stack_workspace_bytes", "lisa_scores_elems",
+    "lisa_decode_stack", "lisa_stack_workspace_bytes", "lisa_scores_elems", "lisa_kd_huber",
 )
 TUNE_PREFILL_GROUPS, TUNE_PREFILL_SPLIT, TUNE_PREFILL_PAIR, TUNE_STD_PAIR, TUNE_PROJECT_TN, TUNE_PREFILL_SLICES = range(6)
 
@@ -102,6 +102,8 @@ def _lib():
         h.lisa_scores_bytes.restype = sz
         h.lisa_scores_elems.argtypes = [dp]
         h.lisa_scores_elems.restype = sz
+        h.lisa_kd_huber.argtypes = [dp, vp, vp, C.c_float, C.c_float, C.c_int, vp, vp, sz, vp]
+        h.lisa_kd_huber.restype = C.c_int
         h.lisa_score_elem_bytes.argtypes = [dp]
         h.lisa_score_elem_bytes.restype = sz
         h.lisa_kcache_saved_bytes.argtypes = [dp, C.c_int]
@@ -368,6 +370,30 @@ def lisa_attn_prefill(q_lr, k_lr, v, scores_prev, w1, w2, *, mix=MIX_ADD, act=AC
     if rc:
         raise LisaError(rc, "lisa_attn_prefill")
     return out, (scores_out if write_scores else None)
+
+
+def lisa_kd_huber(scores, teacher, *, Lq=None, Lk=None, delta=1.0, weight=1.0, accumulate=False, causal=True,
+                  tiled=False, out=None, workspace=None):
+    """Huber regression term of the distillation loss for one layer (see include/lisa.h): mean over
+    the visible entries of L_delta(scores, teacher).  scores, teacher: [B,H,Lq,Lk], or tiled (then
+    Lq and Lk are given).  Returns the device tensor out (2 float64: accumulated loss, this mean)."""
+    if tiled:
+        B, H = scores.shape[0], scores.shape[3]
+    else:
+        B, H, Lq, Lk = scores.shape
+    dt = torch.float32 if scores.dtype == torch.float32 else torch.bfloat16
+    desc = make_desc(dt, B, H, H, Lq, Lk, 1, causal=int(causal), score_tiled=int(tiled))
+    sshape = scores_shape(B, H, Lq, Lk, tiled)
+    if out is None:
+        out = torch.zeros(2, dtype=torch.float64, device=scores.device)
+    need = workspace_bytes(desc, WS_KD)
+    workspace, wp, wb = _workspace(need, scores, workspace)
+    rc = _lib().lisa_kd_huber(C.byref(desc), _ptr(scores, "scores", sshape, scores.dtype),
+                              _ptr(teacher, "teacher", sshape, scores.dtype), float(delta), float(weight),
+                              int(bool(accumulate)), _ptr(out, "out", (2,), torch.float64), wp, wb, _stream())
+    if rc:
+        raise LisaError(rc, "lisa_kd_huber")
+    return out
 
 
 def lisa_cache_fill(k_lr, v, k_lr_cache, v_cache, *, dim_major=True):

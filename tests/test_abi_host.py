@@ -357,3 +357,20 @@ def test_tiled_score_layout_is_validated_and_sized_on_the_host():
     for desc in (f32, wide, cat):
         assert lib.lisa_attn_prefill(C.byref(desc), *([FAKE] * 6), FAKE, C.c_void_p(0x20000), FAKE, big, None) == -3
     assert lib.std_attn_scores(C.byref(f32), FAKE, FAKE, None, FAKE, None, None, 0, None) == -3
+
+
+def test_kd_huber_rejects_bad_arguments_before_any_launch():
+    lib = lisa.library()
+    d = lisa.make_desc(lisa.BF16, 2, 8, 8, 64, 64, 1)
+    need = lisa.workspace_bytes(d, lisa.WS_KD)
+    assert need == min((2 * 8 * 64 + 3) // 4, 2048) * 8
+    out = C.c_void_p(0x30000)
+    assert lib.lisa_kd_huber(C.byref(d), None, FAKE, 1.0, 1.0, 0, out, FAKE, need, None) == -1
+    assert lib.lisa_kd_huber(C.byref(d), FAKE, FAKE, 0.0, 1.0, 0, out, FAKE, need, None) == -2
+    assert lib.lisa_kd_huber(C.byref(d), FAKE, FAKE, 1.0, float("inf"), 0, out, FAKE, need, None) == -2
+    assert lib.lisa_kd_huber(C.byref(d), FAKE, FAKE, 1.0, 1.0, 2, out, FAKE, need, None) == -2
+    assert lib.lisa_kd_huber(C.byref(d), FAKE, ODD, 1.0, 1.0, 0, out, FAKE, need, None) == -4
+    assert lib.lisa_kd_huber(C.byref(d), FAKE, FAKE, 1.0, 1.0, 0, out, FAKE, need - 1, None) == -5
+    assert lib.lisa_kd_huber(C.byref(d), FAKE, FAKE, 1.0, 1.0, 0, out, None, 0, None) == -5
+    f32t = lisa.make_desc(lisa.F32, 2, 8, 8, 64, 64, 1, score_tiled=1)
+    assert lib.lisa_kd_huber(C.byref(f32t), FAKE, FAKE, 1.0, 1.0, 0, out, FAKE, 1 << 20, None) == -3
