@@ -556,8 +556,6 @@ def c2_extras(cfg, sets, ws, steps):
     i0 = s0["inp"]
     g = torch.Generator(device=dev).manual_seed(3)
     w_single = (torch.randn((cfg.H, cfg.H), generator=g, device=dev) / cfg.H ** 0.5).to(cfg.torch_dtype)
-    prev_rm = lisa.untile_scores(s0["prev"], cfg.L, cfg.L) if TILED else None
-    a_rm = torch.empty_like(prev_rm) if TILED else None
     pcfg = cfg.scaled(name="paper_widths", r=20, F=256)
     pin = synth.make_prefill_inputs(pcfg, synth.BASE_SEED + 3, dev, mix="concat", std_layer=False)
     slin = synth.make_prefill_inputs(cfg.scaled(name="lisa_sl", r=32), synth.BASE_SEED + 4, dev, std_layer=False)
@@ -571,13 +569,12 @@ def c2_extras(cfg, sets, ws, steps):
              pin["v"]),
             ("lisa_sl_concat_64x32_r32", dict(mix=lisa.MIX_CONCAT, act=lisa.ACT_SINGLE), w_sl, None, slin["q_lr"],
              slin["k_lr"], slin["v"])):
-        # the CONCAT kernels take row-major scores
-        tl = TILED and kw.get("mix") != lisa.MIX_CONCAT
+        tl = TILED
         dvar = lisa.make_desc(cfg.torch_dtype, cfg.B, cfg.H, cfg.Hkv, cfg.L, cfg.L, cfg.d_k,
                               ql.shape[3] if ql is not None else 0, w1v.shape[1] if w1v is not None else 0,
                               write_scores=1, out_f32=1, score_tiled=int(tl), **kw)
         ws_var = torch.empty(max(lisa.workspace_bytes(dvar, lisa.WS_PREFILL), 256), dtype=torch.uint8, device=dev)
-        prev_v, a_v = (s0["prev"], s0["a_n"]) if tl or not TILED else (prev_rm, a_rm)
+        prev_v, a_v = s0["prev"], s0["a_n"]
 
         def step_variant():
             lisa.lisa_attn_prefill(ql, kl, vv, prev_v, w1v, w2v, write_scores=True, out=s0["out"],

@@ -119,7 +119,9 @@ typedef struct lisa_desc {
  * fetched from HBM as a whole line and again one step later for its other half, and the pieces of
  * the H heads lie in H pages of the address translation; tiled, the layer moves a third fewer
  * bytes.
- * The standard layer writes this layout, the LiSA layer reads and writes it.  Entries of a stored
+ * The standard layer writes this layout, the LiSA layer reads and writes it: the fused ADD kernels,
+ * and the CONCAT form on the matrix cores up to 32 heads with d_k = 128 (its scores kernel reads
+ * and writes tiles, the softmax / P V kernel behind it reads them).  Entries of a stored
  * tile that lie above the diagonal, beyond row Lq - 1 or beyond key Lk - 1 are unspecified; tiles
  * wholly above the diagonal are neither written nor read.
  */

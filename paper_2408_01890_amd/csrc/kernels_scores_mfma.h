@@ -21,6 +21,7 @@
 //      before the next tile is staged (four barriers).
 // Requires Lk % 8 == 0, r <= 32, H <= 48, F <= 256.
 #pragma once
+#include <type_traits>
 #include "kernels_prefill.h"
 
 namespace lisa {
@@ -28,11 +29,12 @@ namespace lisa {
 struct ScoresMfmaArgs {
   const bf16_t* qp;     // [B,H,Lqp,32]   Q_LR rows zero-padded to 32 elements
   const bf16_t* kp;     // [B,Hkv,Lkp,32] K_LR rows likewise
-  const half_t* prev;   // [B,H,Lq,Lk]
+  const half_t* prev;   // [B,H,Lq,Lk] (or tiled, see below)
   const bf16_t* w1;     // [2H,F]
   const bf16_t* w2;     // [F,H]
   half_t* scores;       // [B,H,Lq,Lk]: A_n, which the softmax kernel that follows reads as well
   int B, H, Hkv, Lq, Lk, Lqp, Lkp, F, causal;
+  int tiled;            // prev and scores are [B,ceil(Lq/16),ceil(Lk/32),H,16,32] (TILED kernels only)
   long long tiles_b;    // tiles of one batch element: sum over the row groups of scores_mfma_tiles()
   float dscale;
 };
@@ -57,8 +59,12 @@ __host__ __device__ inline int scores_mfma_tiles(int rg, int Lq, int Lk, int cau
 // order (batch, row group, key tile), are cut into G equal runs, so that every workgroup has the
 // same number of tiles whatever the shape of the triangle (whole row groups or chunks of them
 // leave the last workgroups of a grid with up to twice the average), and stages the weights once.
-template <int HBI, int FS, int HBO, int ACT = 0>
+// TILED (up to 32 heads): A_{n-1} and A_n in the tiled score layout, where the tile of a head is one
+// contiguous KB (whole lines instead of 16 half lines) and leaves without a visibility test: the
+// entries above the diagonal of a tile are unspecified there.
+template <int HBI, int FS, int HBO, int ACT = 0, bool TILED = false>
 __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
+  static_assert(!TILED || HBI <= 4, "tiled scores: the pipelined form only");
   typedef MfmaFfn<HBI, FS, HBO, ACT> Ffn;
   constexpr int KS = Ffn::KS, NW = 8, NBW = 4;
   // hidden k-steps alive at a time in the FFN call (4 blocks x SC x 4 registers; two only where
@@ -120,12 +126,20 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
   constexpr int XCH = (HBO * 16 + NW - 1) / NW;             // A_{n-1} chunks (heads) per wave
   pf_u32x4 xr[XCH];
   bf16x8 kop[HPW][2];
+  // tiled layout: tile (rg, t) of head h at ((b n_rg + rg) n_kt + t) H + h KB, a lane's 16 bytes at
+  // 16 lane (row lane / 4, keys 8 (lane % 4) .. + 7: the same share as in the row-major form)
+  const int n_kt = (Lk + PF_TK - 1) / PF_TK;
+  const size_t tile_stride = (size_t)H * (PF_ROWS * PF_TK);
+  const size_t trow = ((size_t)b * n_rg + rg) * n_kt * tile_stride + lane * 8;   // + t tile_stride + h 512
   auto prefetch = [&](int tile) {
     const int j0 = tile * PF_TK;
 #pragma unroll
     for (int u = 0; u < XCH; ++u) {
       const int h = min(wv + NW * u, H - 1);
-      xr[u] = *(const pf_u32x4*)(a.prev + (((size_t)b * H + h) * Lq + x_row) * Lk + min(j0 + xq8, Lk - 8));
+      if (TILED)
+        xr[u] = *(const pf_u32x4*)(a.prev + trow + min(tile, n_kt - 1) * tile_stride + h * (PF_ROWS * PF_TK));
+      else
+        xr[u] = *(const pf_u32x4*)(a.prev + (((size_t)b * H + h) * Lq + x_row) * Lk + min(j0 + xq8, Lk - 8));
     }
 #pragma unroll
     for (int u = 0; u < HPW; ++u) {
@@ -162,7 +176,7 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
       }
     }
   };
-  auto read_x = [&](f16x8 (&x)[NBW][KS]) {
+  auto read_x = [&](f16x8 (&x)[NBW][KS], bool x_all) {     // x_all: 2H fills the k-steps, nothing to zero
 #pragma unroll
     for (int n = 0; n < NBW; ++n) {
       const int nb = wv + n * NW;                           // block = (row nb / 2, key half nb % 2)
@@ -177,8 +191,8 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
                        (s16x4 __attribute__((address_space(3)))*)(xs + xrd[ks][1] + i * 64 + 32 * kh)));
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          x[n][ks][e] = 32 * ks + 8 * g + e < Din ? lo[e] : (_Float16)0.f;
-          x[n][ks][4 + e] = 32 * ks + 8 * g + 4 + e < Din ? hi[e] : (_Float16)0.f;
+          x[n][ks][e] = (x_all || 32 * ks + 8 * g + e < Din) ? lo[e] : (_Float16)0.f;
+          x[n][ks][4 + e] = (x_all || 32 * ks + 8 * g + 4 + e < Din) ? hi[e] : (_Float16)0.f;
         }
       }
     }
@@ -201,8 +215,14 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
     auto out_read = [&](int u) {
       if (wv + NW * u < H) held = *(const f16x8*)(yrd + u * NW * SM_YH_HEAD);
     };
-    auto out_store = [&](int u, int jc) {                   // jc: first of the lane's 8 keys
-      if (wv + NW * u >= H || jc >= vis) return;
+    auto out_store = [&](int u, int tile) {                 // the lane's 8 keys of key tile `tile`
+      if (wv + NW * u >= H) return;
+      if (TILED) {
+        *(f16x8*)(a.scores + trow + tile * tile_stride + (wv + NW * u) * (PF_ROWS * PF_TK)) = held;
+        return;
+      }
+      const int jc = tile * PF_TK + 8 * och;                // first of the lane's 8 keys
+      if (jc >= vis) return;
       half_t* sp = obase + u * ohead + jc - 8 * och;
       if (jc + 8 <= vis) {
         *(f16x8*)sp = held;
@@ -240,31 +260,37 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
     constexpr int N_OPS = XCH + 1 + XCH + 2 * HPW;          // read / store pairs of a tile, then the loads of the next
     constexpr int N_GROUPS = (FS / SC) * (2 * SC + HBO);
     constexpr int OPG = (N_OPS + N_GROUPS - 1) / N_GROUPS;
-    for (int tile = t_first; tile < t_last; ++tile) {
-      const bool pending = tile > t_first;
+    const bool x_all = Din == 32 * KS;
+    // one tile; PEND (a compile-time constant: the first tile of a run has its own copy of the
+    // loop body, so that no store of the others sits behind a branch): the result of the tile
+    // before is in yh and leaves during this tile's FFN
+    auto do_tile = [&](auto pend, int tile) {
+      constexpr bool PEND = decltype(pend)::value;
       stage_tile();
-      if (pending) write_y();
+      if (PEND) write_y();
       lds_barrier();                                         // A: xs and yh are complete
       f16x8 x[NBW][KS];
-      read_x(x);
-      const int jn = (tile + 1) * PF_TK, jo = (tile - 1) * PF_TK + 8 * och;
+      read_x(x, x_all);
+      const int jn = (tile + 1) * PF_TK;
       const int xoff = min(jn + xq8, Lk - 8);
+      const size_t toff = trow + min(tile + 1, n_kt - 1) * tile_stride;
       int koff[2];
 #pragma unroll
       for (int half = 0; half < 2; ++half) koff[half] = min(jn + 16 * half + c, Lk - 1) * 32 + 8 * g;
       // (the loads are not conditional on a next tile: its clamped addresses are in bounds, and a
       // branch around a load makes the compiler wait for every earlier one)
-      Ffn::template apply_lds_chunked<NBW, SC>(w_s, x, y, [&](int gidx) {
+      Ffn::template apply_lds_chunked_ahead<NBW, SC>(w_s, x, y, [&](int gidx) {
 #pragma unroll
         for (int k = gidx * OPG; k < (gidx + 1) * OPG && k < N_OPS; ++k) {
           if (k <= XCH) {                                    // stores first: the wait for the loads, at the
-            if (pending) {                                   // next staging, also waits for them
-              if (k > 0) out_store(k - 1, jo);
+            if (PEND) {                                      // next staging, also waits for them
+              if (k > 0) out_store(k - 1, tile - 1);
               if (k < XCH) out_read(k);
             }
           } else if (k <= 2 * XCH) {
-            const int u = k - XCH - 1;
-            xr[u] = *(const pf_u32x4*)(pbase + min(wv + NW * u, H - 1) * phead + xoff);
+            const int u = k - XCH - 1, h = min(wv + NW * u, H - 1);
+            if (TILED) xr[u] = *(const pf_u32x4*)(a.prev + toff + h * (PF_ROWS * PF_TK));
+            else xr[u] = *(const pf_u32x4*)(pbase + h * phead + xoff);
           } else {
             const int u = (k - 2 * XCH - 1) >> 1, half = (k - 2 * XCH - 1) & 1;
             const int h = min(wv + NW * u, H - 1);
@@ -273,14 +299,16 @@ __global__ __launch_bounds__(512) void k_lisa_scores_mfma(ScoresMfmaArgs a) {
         }
       });
       lds_barrier();                                         // B: xs and yh have been read
-    }
+    };
+    do_tile(std::false_type{}, t_first);
+    for (int tile = t_first + 1; tile < t_last; ++tile) do_tile(std::true_type{}, tile);
     // the result of the last tile of the run
     write_y();
     lds_barrier();
 #pragma unroll
     for (int u = 0; u < XCH; ++u) {
       out_read(u);
-      out_store(u, (t_last - 1) * PF_TK + 8 * och);
+      out_store(u, t_last - 1);
     }
   } else
   for (int tile = t_first; tile < t_last; ++tile) {

@@ -34,7 +34,7 @@ struct StdPrefillArgs {
   int H, Hkv, Lq, Lk, Lkp, causal, out_f32;
   int pair;               // 1: a workgroup takes two row groups (grid.y = ceil(n_groups / 2)), 0: one
   float scale;
-  int tiled;              // scores are written as [B,ceil(Lq/16),ceil(Lk/32),H,16,32] (not with GIVEN)
+  int tiled;              // scores are written (GIVEN = 2: read) as [B,ceil(Lq/16),ceil(Lk/32),H,16,32]
 };
 
 __device__ __forceinline__ float halves_max(float v) {
@@ -155,10 +155,16 @@ __global__ __launch_bounds__(256, 2) void k_std_prefill(StdPrefillArgs a) {
     // GIVEN = 2: the wave's scores of a tile are loaded two tiles ahead (nothing else hides the
     // latency of these loads: there is no score product to wait behind)
     f16x8 gq[2][2];
+    // (tiled: row my_row of head h, tile t at (((my_row / 16) n_kt + t) H + h) KB + 64 (my_row % 16) bytes)
+    const half_t* grow_t = GIVEN == 2 ? (const half_t*)a.given + (size_t)b * seq_elems +
+                                            ((size_t)(my_row >> 4) * n_kt * H + h) * (16 * SP_TK) +
+                                            (my_row & 15) * SP_TK + 8 * half
+                                      : nullptr;
     auto load_scores = [&](int tile, f16x8 (&dst)[2]) {
 #pragma unroll
       for (int u = 0; u < 2; ++u)    // (keys beyond Lk: any in-bounds 8 scores will do, those positions are masked)
-        dst[u] = *(const f16x8*)(grow_h + min(tile * SP_TK + 16 * u + 8 * half, Lk - 8));
+        dst[u] = *(const f16x8*)(a.tiled ? grow_t + (size_t)tile * H * (16 * SP_TK) + 16 * u
+                                         : grow_h + min(tile * SP_TK + 16 * u + 8 * half, Lk - 8));
     };
     if (rep) __syncthreads();                              // the first pass is done with both buffers
     load_tile(0, regs_a);

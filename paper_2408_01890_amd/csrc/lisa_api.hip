@@ -203,10 +203,11 @@ bool scores_mfma_ok(const lisa_desc* d) {
   return (long long)d->Lq * d->Lk < (1LL << 31);
 }
 
-template <int HBI, int FS, int HBO>
+template <int HBI, int FS, int HBO, bool TILED = false>
 int launch_scores_mfma_t(const lisa_desc* d, const ScoresMfmaArgs& a, hipStream_t st) {
   const int lds = scores_mfma_lds<HBI, FS, HBO>(d->H);
-  auto kern = d->act == LISA_ACT_SILU ? k_lisa_scores_mfma<HBI, FS, HBO, 1> : k_lisa_scores_mfma<HBI, FS, HBO, 0>;
+  auto kern = d->act == LISA_ACT_SILU ? k_lisa_scores_mfma<HBI, FS, HBO, 1, TILED>
+                                      : k_lisa_scores_mfma<HBI, FS, HBO, 0, TILED>;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e != hipSuccess) return hip_fail(e);
   // one workgroup per compute unit, each with an equal run of the tiles
@@ -224,11 +225,14 @@ struct ConcatWs {
   int Lqp, Lkp;
 };
 bool std_prefill_fast_ok(const lisa_desc* d);
+// The CONCAT pipeline on tiled score tensors: the pipelined scores kernel (up to 32 heads) followed
+// by the matrix-core softmax kernel, which then reads tiles.
+bool concat_tiled_ok(const lisa_desc* d) { return scores_mfma_ok(d) && d->H <= 32 && std_prefill_fast_ok(d); }
 ConcatWs concat_ws(const lisa_desc* d) {
   ConcatWs w;
   w.Lqp = (d->Lq + PF_ROWS - 1) / PF_ROWS * PF_ROWS;
   w.Lkp = (d->Lk + 63) / 64 * 64;
-  w.qp = round_up((size_t)d->B * d->H * d->Lq * d->Lk * 2, 256);
+  w.qp = round_up(scores_bytes(d), 256);                   // (2-byte scores, in the layout of the call)
   w.kp = w.qp + round_up((size_t)d->B * d->H * w.Lqp * 32 * 2, 256);
   w.vt = w.kp + round_up((size_t)d->B * d->Hkv * w.Lkp * 32 * 2, 256);
   w.total = w.vt + (std_prefill_fast_ok(d) ? round_up((size_t)d->B * d->Hkv * d->d_k * w.Lkp * 2, 256) : 0);
@@ -274,7 +278,13 @@ int launch_scores_mfma(const lisa_desc* d, const void* q_lr, const void* k_lr, c
   a.F = d->F;
   a.causal = d->causal;
   a.dscale = pick_scale(d->delta_scale, d->r);
+  a.tiled = d->score_tiled;
   const bool wide = d->F > 128;
+  if (d->score_tiled) {                                      // (concat_tiled_ok: up to 32 heads)
+    if (d->H <= 16)
+      return wide ? launch_scores_mfma_t<2, 8, 1, true>(d, a, st) : launch_scores_mfma_t<2, 4, 1, true>(d, a, st);
+    return wide ? launch_scores_mfma_t<4, 8, 2, true>(d, a, st) : launch_scores_mfma_t<4, 4, 2, true>(d, a, st);
+  }
   if (d->H <= 16) return wide ? launch_scores_mfma_t<2, 8, 1>(d, a, st) : launch_scores_mfma_t<2, 4, 1>(d, a, st);
   if (d->H <= 32) return wide ? launch_scores_mfma_t<4, 8, 2>(d, a, st) : launch_scores_mfma_t<4, 4, 2>(d, a, st);
   return wide ? launch_scores_mfma_t<6, 8, 3>(d, a, st) : launch_scores_mfma_t<6, 4, 3>(d, a, st);
@@ -738,6 +748,7 @@ int run_softmax_given_fast(const lisa_desc* d, const void* given, bool given_hal
   a.causal = d->causal;
   a.out_f32 = d->out_f32;
   a.scale = 1.f;
+  a.tiled = given_half ? d->score_tiled : 0;
   if (v) {                                                   // (null: vt_ws already holds the regrouped V)
     dim3 grid(a.Lkp / 64, d->d_k / 64, d->B * d->Hkv);
     StageScope prof("k_regroup_v", st);
@@ -1309,7 +1320,9 @@ int lisa_attn_prefill(const lisa_desc* desc, const void* q_lr, const void* k_lr,
     if (rc) return rc;
     return run_prefill_fused(&eq, q_lr, k_lr, v, scores_prev, w1e, w2e, out, scores, workspace, st);
   }
-  if (desc->score_tiled) return LISA_ERR_UNSUPPORTED;       // the fused kernels alone read and write tiles
+  // tiles are read and written by the fused kernels and by the matrix-core CONCAT pipeline alone
+  if (desc->score_tiled && !concat_tiled_ok(desc) && !(relu_equivalent(desc, &eq) && concat_tiled_ok(&eq)))
+    return LISA_ERR_UNSUPPORTED;
   if (relu_equivalent(desc, &eq) && scores_mfma_ok(&eq)) {   // the single layer over the concatenation
     const void *w1e, *w2e;
     rc = synth_relu_ffn(desc, w1, workspace, round_up(concat_ws(&eq).total, 256), &w1e, &w2e, &q_lr, &k_lr, st);

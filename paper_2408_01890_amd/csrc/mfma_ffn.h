@@ -286,6 +286,72 @@ struct MfmaFfn {
     }
   }
 
+  // apply_lds_chunked() with the weight operands of a group read two groups ahead, into three
+  // rotating operand sets: with eight waves reading at once an operand takes longer to arrive than
+  // the 64 - 128 cycles of one group of MFMAs.
+  template <int NBLK, int SC, class Between>
+  __device__ __forceinline__ static void apply_lds_chunked_ahead(const unsigned short* lds,
+                                                                 const f16x8 (&x)[NBLK][KS],
+                                                                 f32x4 (&y)[NBLK][HBO], Between&& between) {
+    static_assert(FS % SC == 0, "chunk size");
+    constexpr int GPC = 2 * SC + HBO;                       // groups per chunk
+    constexpr int NGR = (FS / SC) * GPC;
+    constexpr int MAXOP = KS > SC ? KS : SC;
+    constexpr int AH = 2, NBUF = AH + 1;                     // groups ahead, operand sets
+    const int lane = threadIdx.x & 63;
+    const unsigned short* l1 = lds + lane * 8;
+    const unsigned short* l2 = l1 + FB * KS * 512;
+#pragma unroll
+    for (int n = 0; n < NBLK; ++n)
+#pragma unroll
+      for (int hb = 0; hb < HBO; ++hb) y[n][hb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    f16x8 w[NBUF][MAXOP];
+    auto read_ops = [&](int gi) {                           // the operands of group gi
+      const int s0 = (gi / GPC) * SC, idx = gi % GPC;
+      if (idx < 2 * SC) {
+        const int fb = 2 * s0 + idx;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) w[gi % NBUF][ks] = *(const f16x8*)(l1 + (fb * KS + ks) * 512);
+      } else {
+        const int hb = idx - 2 * SC;
+#pragma unroll
+        for (int s = 0; s < SC; ++s) w[gi % NBUF][s] = *(const f16x8*)(l2 + (hb * FS + s0 + s) * 512);
+      }
+    };
+#pragma unroll
+    for (int gi = 0; gi < AH && gi < NGR; ++gi) read_ops(gi);
+    f16x8 hid[NBLK][SC];
+#pragma unroll
+    for (int gi = 0; gi < NGR; ++gi) {
+      const int s0 = (gi / GPC) * SC, idx = gi % GPC;
+      between(gi);
+      if (gi + AH < NGR) read_ops(gi + AH);
+      if (idx < 2 * SC) {                                   // hidden block fb = 2 s + half
+        const int fb = 2 * s0 + idx;
+        f32x4 acc[NBLK];
+#pragma unroll
+        for (int n = 0; n < NBLK; ++n) acc[n] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+          for (int n = 0; n < NBLK; ++n)
+            acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w[gi % NBUF][ks], x[n][ks], acc[n], 0, 0, 0);
+#pragma unroll
+        for (int n = 0; n < NBLK; ++n)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) hid[n][(fb >> 1) - s0][4 * (fb & 1) + v] = activate(acc[n][v]);
+      } else {
+        const int hb = idx - 2 * SC;
+#pragma unroll
+        for (int s = 0; s < SC; ++s)
+#pragma unroll
+          for (int n = 0; n < NBLK; ++n)
+            y[n][hb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w[gi % NBUF][s], hid[n][s], y[n][hb], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+
   // NBLK independent blocks of 16 positions at once: the MFMAs of the blocks are interleaved so
   // that none has to wait for the result of the one issued just before it.
   // x[n][ks]: B operand of the first product of block n: lane (c, g) holds x[head 32 ks + 8 g + e]

@@ -122,11 +122,53 @@ def test_variants_on_the_fused_kernel_tiled(variant):
     assert path == "mfma_fused"
 
 
-def test_tiled_requests_outside_the_fused_kernels_are_refused():
-    cfg, inp = make_case("h32_l136", 1, 32, 32, 136, 136, 20, 256, 47)      # F = 256: not a fused shape
+CONCAT_TILED = [
+    # name, B, H, Hkv, Lq, Lk, r, F, act
+    ("paper_widths_l328", 1, 32, 32, 328, 328, 20, 256, "relu"),
+    ("paper_widths_gqa_shift", 2, 32, 8, 200, 264, 20, 256, "relu"),
+    ("h16_f128_l520", 1, 16, 16, 520, 520, 22, 128, "relu"),
+    ("h24_f96_l136", 1, 24, 8, 136, 136, 16, 96, "relu"),
+    ("h8_f64_silu_l264", 2, 8, 2, 264, 264, 11, 64, "silu"),
+    ("h32_single_layer_l264", 1, 32, 32, 264, 264, 32, 0, "single"),
+]
+
+
+@pytest.mark.parametrize("case", CONCAT_TILED, ids=[c[0] for c in CONCAT_TILED])
+@pytest.mark.parametrize("causal", [True, False])
+def test_concat_pipeline_tiled_equals_row_major(case, causal):
+    """CONCAT form (Sec. 5.1 overview, Sec. 5.3 widths) on the matrix cores: the scores kernel reads and
+    writes tiles, the softmax / P V kernel reads them."""
+    name, B, H, Hkv, Lq, Lk, r, F, act = case
+    log(f"[case] tiled concat {name} causal={causal}")
+    cfg = synth.LayerShape(name, "bf16", B, H, Hkv, Lk, 256, 128, r, max(F, 32))
+    inp = synth.make_prefill_inputs(cfg, 53, DEV, mix="concat", ffn="fan_in")
+    shift = Lk - Lq
+    inp["q_lr"] = inp["q_lr"][:, :, shift:].contiguous()
+    inp["q"] = inp["q"][:, :, shift:].contiguous()
+    kw = dict(mix=lisa.MIX_CONCAT)
+    if act == "silu":
+        kw["act"] = lisa.ACT_SILU
+    elif act == "single":                                   # LiSA_SL: one layer over the concatenation
+        g = torch.Generator(device=DEV).manual_seed(7)
+        inp["w1"] = (torch.randn((2 * H, H), generator=g, device=DEV) / (2 * H) ** 0.5).to(torch.bfloat16)
+        inp["w2"] = None
+        kw["act"] = lisa.ACT_SINGLE
+    path, *_ = both_layouts(inp, Lq, Lk, causal, **kw)
+    assert path == "mfma_scores"
+
+
+def test_tiled_requests_outside_the_matrix_core_kernels_are_refused():
+    cfg, inp = make_case("h32_l136", 1, 32, 32, 136, 136, 20, 160, 47)      # ADD with F = 160: not a fused shape
     prev_t, _ = lisa.std_attn_scores(inp["q"], inp["k"], tiled=True)
     with pytest.raises(lisa.LisaError) as e:
         lisa.lisa_attn_prefill(inp["q_lr"], inp["k_lr"], inp["v"], prev_t, inp["w1"], inp["w2"], tiled=True)
+    assert e.value.status == -3
+    cfg = synth.LayerShape("h40_concat", "bf16", 1, 40, 40, 136, 256, 128, 20, 256)   # CONCAT beyond 32 heads
+    inp = synth.make_prefill_inputs(cfg, 47, DEV, mix="concat")
+    prev_t, _ = lisa.std_attn_scores(inp["q"], inp["k"], tiled=True)
+    with pytest.raises(lisa.LisaError) as e:
+        lisa.lisa_attn_prefill(inp["q_lr"], inp["k_lr"], inp["v"], prev_t, inp["w1"], inp["w2"], tiled=True,
+                               mix=lisa.MIX_CONCAT)
     assert e.value.status == -3
     q32 = torch.randn((1, 2, 40, 16), device=DEV)
     with pytest.raises(lisa.LisaError) as e:
