@@ -349,10 +349,11 @@ def test_tiled_score_layout_is_validated_and_sized_on_the_host():
     dec = lisa.make_desc(lisa.BF16, 2, 32, 8, 1, 200, 128, 22, 64, write_scores=1, Lmax=256, score_tiled=1)
     ptrs = [C.c_void_p(0x10000 + 0x1000 * i) for i in range(11)]
     assert lib.lisa_attn_decode(C.byref(dec), *ptrs, big, None) == -3
-    # shapes that run on the generic kernels (fp32; F beyond the fused kernel; the CONCAT form)
+    # shapes whose kernels take row-major scores only (fp32; F beyond the fused kernel; the CONCAT form
+    # beyond 32 heads)
     f32 = lisa.make_desc(lisa.F32, 1, 4, 4, 64, 64, 64, 8, 16, write_scores=1, score_tiled=1)
     wide = lisa.make_desc(lisa.BF16, 1, 32, 32, 64, 64, 128, 20, 256, write_scores=1, score_tiled=1)
-    cat = lisa.make_desc(lisa.BF16, 1, 32, 32, 64, 64, 128, 20, 256, mix=lisa.MIX_CONCAT, write_scores=1,
+    cat = lisa.make_desc(lisa.BF16, 1, 40, 40, 64, 64, 128, 20, 256, mix=lisa.MIX_CONCAT, write_scores=1,
                          score_tiled=1)
     for desc in (f32, wide, cat):
         assert lib.lisa_attn_prefill(C.byref(desc), *([FAKE] * 6), FAKE, C.c_void_p(0x20000), FAKE, big, None) == -3
