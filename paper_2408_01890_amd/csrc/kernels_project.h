@@ -517,8 +517,80 @@ __global__ __launch_bounds__(512) void k_project_mfma(ProjectArgs a) {
 // matrix cores.  One workgroup = one block of 32 virtual columns (a Q_LR / K_LR head, or 32
 // features of V) and all rows; its 8 waves split the reduction axis and stream their slices of
 // the weight rows and of X straight into MFMA operand registers (no LDS: nothing is reused),
-// then add their partial sums through the LDS.  Wave mb < MB finishes row block mb: rotation,
-// rounding and element stores (few outputs).
+// then add their partial sums through the LDS (project_skinny_finish).
+// The end of both skinny kernels: the partial sums of the 8 waves (their slices of the reduction
+// axis) are added through the LDS, and every wave finishes 2 MB of the 16 MB result registers:
+// rotation, rounding and element stores (with one wave per row block this tail took 5 us of
+// the kernel's 19).  acc layout: token row 32 mb + 8 (v/4) + 4 half + v%4, virtual column nvb + l32.
+template <int MB>
+__device__ __forceinline__ void project_skinny_finish(const ProjectArgs a, const pj_f32x16 (&acc)[MB], float* red,
+                                                      int nvb) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int half = lane >> 5, l32 = lane & 31;
+  const int M = a.B * a.L;
+  const int nheads_qk = a.H + a.Hkv;
+  const int nv_qk = PJ_HEADW * nheads_qk;
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) red[((wv * MB + mb) * 16 + v) * 64 + lane] = acc[mb][v];
+  __syncthreads();
+  // the 16 MB registers (row block mb, register v) of the result are dealt to the 8 waves
+  constexpr int PER = 2 * MB;
+  float y[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int pi = wv * PER + i;                            // = 16 mb + v
+    float sum = 0.f;
+#pragma unroll
+    for (int w = 0; w < 8; ++w) sum += red[(w * MB * 16 + pi) * 64 + lane];
+    y[i] = sum;
+  }
+  int head, c;
+  bool valid;
+  if (nvb < nv_qk) {
+    head = nvb >> 5;
+    c = l32;
+    valid = c < a.r;
+  } else {
+    const int col = nvb - nv_qk + l32;
+    head = nheads_qk + col / a.dk;
+    c = col % a.dk;
+    valid = col < a.Hkv * a.dk;
+  }
+  const bool rot = a.rope && nvb < nv_qk;
+  const int hr = a.r >> 1;
+  const bool lower = c < hr;
+  double inv_freq_rev = 0.0;
+  int partner = lane;
+  if (rot) {
+    const int t = lower ? c : c - hr;
+    inv_freq_rev = exp2((double)min(t, hr - 1) * a.freq_log2) * 0.15915494309189535;
+    partner = (lane & 32) | (valid ? (lower ? c + hr : c - hr) : l32);
+  }
+  bf16_t* dst_base = (bf16_t*)(head < a.H ? a.q_lr : head < nheads_qk ? a.k_lr : a.v);
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int pi = wv * PER + i, mb = pi >> 4, v = pi & 15;
+    const int m = mb * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+    const int mc = min(m, M - 1);
+    const int b = mc / a.L, l = mc - b * a.L;
+    float out = y[i];
+    if (rot) {
+      const float other = __shfl(out, partner, 64);
+      float cs, sn;
+      rope_cos_sin_fast(a.pos0 + l, inv_freq_rev, cs, sn);
+      out = lower ? out * cs - other * sn : other * sn + out * cs;
+    }
+    if (valid && m < M) {
+      int which;
+      const size_t at = project_dest(a, b, l, head, c, which);
+      dst_base[at].bits = (uint16_t)f32_to_bf16_bits(out);
+    }
+  }
+}
+
 template <int MB>
 __global__ __launch_bounds__(512) void k_project_skinny(ProjectArgs a) {
   extern __shared__ __align__(16) unsigned char pj_lds[];
@@ -559,63 +631,106 @@ __global__ __launch_bounds__(512) void k_project_skinny(ProjectArgs a) {
       acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop, bop, acc[mb], 0, 0, 0);
     }
   }
+  project_skinny_finish<MB>(a, acc, red, nvb);
+}
+
+// The same product with both operands staged through the LDS.  Read straight into MFMA operand
+// registers, a load touches 32 rows for 32 bytes each (the operand layout wants a lane per row):
+// four requests per 128-byte line, for the weights and, from the L2, for X, which every workgroup
+// reads whole.  Here a wave loads its slice of the reduction axis in chunks of 64 elements, 8 rows
+// x 128 bytes per load (whole lines), writes them to its own LDS region (rows of 128 + 16 bytes:
+// conflict-free 16-byte operand reads) and reads its operands from there; the next chunk's loads
+// are in flight meanwhile.  No barrier in the loop: the region is private to the wave, and LDS
+// operations of a wave execute in order.  Requires D % 512 == 0 (8 waves x whole chunks), MB <= 2
+// (LDS: 8 waves x (1 + MB) x 4.5 KB).
+constexpr int PJS_ROW = 128 + 16;                           // bytes per staged row (64 elements + pad)
+template <int MB>
+__global__ __launch_bounds__(512) void k_project_skinny_lds(ProjectArgs a) {
+  extern __shared__ __align__(16) unsigned char pj_lds[];
+  float* red = (float*)pj_lds;                              // after the loop: [8 waves][MB][16][64]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int half = lane >> 5, l32 = lane & 31;
+  const int M = a.B * a.L, D = a.D;
+  const int nheads_qk = a.H + a.Hkv;
+  const int nv_qk = PJ_HEADW * nheads_qk;
+  const int n_real = nheads_qk * a.r + a.Hkv * a.dk;
+  const int nvb = blockIdx.x * 32;                          // first virtual column of the block
+  constexpr int NX = 4 * MB;                                // X loads per chunk (8 rows each)
+  unsigned char* wst = pj_lds + (size_t)wv * (1 + MB) * 32 * PJS_ROW;   // this wave's region: W rows, then X rows
+  unsigned char* xst = wst + 32 * PJS_ROW;
+  const int lrow = lane >> 3, lpiece = lane & 7;            // load: row lrow + 8 j, 16-byte piece lpiece
+  // This wave's slice of the reduction axis, and the chunk it starts with, rotate with the
+  // workgroup: rows are D elements apart (a multiple of the channel interleave), so workgroups
+  // that walk the axis in step all load from the same few L2 / HBM channels at any one time
+  // (19 -> ... us on the LLaMA2-7B width).  The order of a sum does not matter to its parity bound.
+  const int kslice = D / 8, k0 = ((wv + (int)blockIdx.x) & 7) * kslice;
+  const int ch_rot = (int)(blockIdx.x >> 3);
+  const bf16_t* wsrc[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int n = lrow + 8 * j;
+    const int real = nvb < nv_qk ? (nvb >> 5) * a.r + min(n, a.r - 1) : nheads_qk * a.r + (nvb - nv_qk) + n;
+    wsrc[j] = (const bf16_t*)a.w + (size_t)min(real, n_real - 1) * D + k0 + 8 * lpiece;
+  }
+  const bf16_t* xsrc[NX];
+#pragma unroll
+  for (int j = 0; j < NX; ++j) xsrc[j] = (const bf16_t*)a.x + (size_t)min(lrow + 8 * j, M - 1) * D + k0 + 8 * lpiece;
+  const int st_at = lrow * PJS_ROW + lpiece * 16;           // + 8 j rows
+  const int op_at = l32 * PJS_ROW + half * 16;              // + 32 ks (+ 32 mb rows for X)
+
+  pj_f32x16 acc[MB];
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) red[((wv * MB + mb) * 16 + v) * 64 + lane] = acc[mb][v];
-  __syncthreads();
-  if (wv >= MB) return;
-  const int mb = wv;
-  float y[16];
+    for (int v = 0; v < 16; ++v) acc[mb][v] = 0.f;
+  // NPF chunks in flight per wave (12 KB each with two row blocks): at one, the loop ran at the
+  // latency of a load per chunk.  The chunk count of a slice is rounded up to a multiple of NPF;
+  // the chunks of the round-up enter the product with a zero weight operand.
+  constexpr int NPF = 2;
+  pj_u32x4 wr[NPF][4], xr[NPF][NX];
+  const int n_chunks = kslice / 64;
+  auto load_chunk = [&](int ch, int p) {                   // (beyond the slice: the first chunks again, no
+    const int at = 64 * ((ch + ch_rot) % n_chunks);        //  branch around loads)
 #pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    float sum = 0.f;
+    for (int j = 0; j < 4; ++j) wr[p][j] = *(const pj_u32x4*)(wsrc[j] + at);
 #pragma unroll
-    for (int w = 0; w < 8; ++w) sum += red[((w * MB + mb) * 16 + v) * 64 + lane];
-    y[v] = sum;
-  }
-  // acc layout: token row 32 mb + 8 (v/4) + 4 half + v%4, virtual column nvb + l32
-  int head, c;
-  bool valid;
-  if (nvb < nv_qk) {
-    head = nvb >> 5;
-    c = l32;
-    valid = c < a.r;
-  } else {
-    const int col = nvb - nv_qk + l32;
-    head = nheads_qk + col / a.dk;
-    c = col % a.dk;
-    valid = col < a.Hkv * a.dk;
-  }
-  const bool rot = a.rope && nvb < nv_qk;
-  const int hr = a.r >> 1;
-  const bool lower = c < hr;
-  double inv_freq_rev = 0.0;
-  int partner = lane;
-  if (rot) {
-    const int t = lower ? c : c - hr;
-    inv_freq_rev = exp2((double)min(t, hr - 1) * a.freq_log2) * 0.15915494309189535;
-    partner = (lane & 32) | (valid ? (lower ? c + hr : c - hr) : l32);
-  }
-  bf16_t* dst_base = (bf16_t*)(head < a.H ? a.q_lr : head < nheads_qk ? a.k_lr : a.v);
+    for (int j = 0; j < NX; ++j) xr[p][j] = *(const pj_u32x4*)(xsrc[j] + at);
+  };
 #pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const int m = mb * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-    const int mc = min(m, M - 1);
-    const int b = mc / a.L, l = mc - b * a.L;
-    float out = y[v];
-    if (rot) {
-      const float other = __shfl(out, partner, 64);
-      float cs, sn;
-      rope_cos_sin_fast(a.pos0 + l, inv_freq_rev, cs, sn);
-      out = lower ? out * cs - other * sn : other * sn + out * cs;
-    }
-    if (valid && m < M) {
-      int which;
-      const size_t at = project_dest(a, b, l, head, c, which);
-      dst_base[at].bits = (uint16_t)f32_to_bf16_bits(out);
+  for (int p = 0; p < NPF; ++p) {                           // (in this order: the loop waits for the older set only)
+    load_chunk(p, p);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  for (int ch0 = 0; ch0 < n_chunks; ch0 += NPF) {
+#pragma unroll
+    for (int p = 0; p < NPF; ++p) {
+      const int ch = ch0 + p;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) *(pj_u32x4*)(wst + st_at + 8 * j * PJS_ROW) = wr[p][j];
+#pragma unroll
+      for (int j = 0; j < NX; ++j) *(pj_u32x4*)(xst + st_at + 8 * j * PJS_ROW) = xr[p][j];
+      // (fences: left alone, the compiler issues these loads after the MFMAs and waits for them
+      // before the next set is written, which leaves one chunk in flight)
+      __builtin_amdgcn_sched_barrier(0);
+      load_chunk(ch + NPF, p);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        pj_u32x4 braw = *(const pj_u32x4*)(wst + op_at + 32 * ks);
+        if (ch >= n_chunks) braw = pj_u32x4{0u, 0u, 0u, 0u};      // (a chunk of the round-up: adds nothing)
+        const pj_bf16x8 bop = __builtin_bit_cast(pj_bf16x8, braw);
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+          const pj_bf16x8 aop = *(const pj_bf16x8*)(xst + op_at + mb * 32 * PJS_ROW + 32 * ks);
+          acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop, bop, acc[mb], 0, 0, 0);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
+  __syncthreads();                                          // every wave is done with its staging region
+  project_skinny_finish<MB>(a, acc, red, nvb);
 }
 
 }  // namespace lisa

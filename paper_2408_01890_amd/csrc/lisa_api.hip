@@ -896,7 +896,10 @@ int lisa_project_qkv(const lisa_proj_desc* d, const void* x, const void* w, void
     // a decode step: few rows, bound by one pass over the weights
     const long long n_virtual = (long long)PJ_HEADW * (d->H + d->Hkv) + (long long)d->Hkv * d->d_k;
     const int mb = (int)((M + 31) / 32);
-    const int lds = 8 * mb * 16 * 64 * (int)sizeof(float);
+    // both operands through the LDS (whole-line loads) where the reduction axis splits into whole
+    // chunks per wave and the staging regions fit
+    const bool staged = d->d_model % 512 == 0 && mb <= 2;
+    const int lds = std::max(8 * mb * 16 * 64 * (int)sizeof(float), staged ? 8 * (1 + mb) * 32 * PJS_ROW : 0);
     StageScope scope("k_project_skinny", st);
     auto launch = [&](auto kern) -> int {
       hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -904,7 +907,8 @@ int lisa_project_qkv(const lisa_proj_desc* d, const void* x, const void* w, void
       kern<<<dim3((unsigned)((n_virtual + 31) / 32)), 512, lds, st>>>(a);
       return LISA_OK;
     };
-    int lrc = mb == 1 ? launch(k_project_skinny<1>) : mb == 2 ? launch(k_project_skinny<2>)
+    int lrc = staged ? (mb == 1 ? launch(k_project_skinny_lds<1>) : launch(k_project_skinny_lds<2>))
+            : mb == 1 ? launch(k_project_skinny<1>) : mb == 2 ? launch(k_project_skinny<2>)
             : mb == 3 ? launch(k_project_skinny<3>) : launch(k_project_skinny<4>);
     if (lrc) return lrc;
     path = "project_skinny";

@@ -824,6 +824,12 @@ PROJ_SKINNY = [
     (2, 4, 4, 40, 64, 96, 10, None, 3, True, 1),            # d_k = 96, sequences inside a row block
     (2, 4, 2, 33, 128, 32, 7, None, 0, False, 0),           # odd r
     (1, 8, 8, 128, 2048, 128, 22, 10000.0, 0, False, 0),    # 128 rows (the most), a long reduction axis
+    # d % 512 == 0 and at most 64 rows: the kernel that stages both operands through the LDS
+    (3, 8, 2, 1, 512, 128, 22, 500000.0, 9, False, 2),      # one chunk per wave (two of the round-up), three rows
+    (1, 16, 16, 64, 2048, 64, 32, 10000.0, 1000, True, 0),  # r = 32, two full row blocks, four chunks
+    (2, 4, 4, 20, 1536, 96, 10, None, 3, True, 1),          # d_k = 96, ragged second row block, three chunks
+    (2, 4, 2, 9, 1024, 32, 7, None, 0, False, 0),           # odd r, two chunks
+    (37, 2, 1, 1, 5120, 128, 16, 10000.0, 77, True, 3),     # the LLaMA2-13B width, odd head count
 ]
 
 
