@@ -592,6 +592,36 @@ def c2_extras(cfg, sets, ws, steps):
     return extra
 
 
+def chip_reference(buf):
+    """What plain kernels reach on this chip (the library's reference kernels, timed here): one read
+    pass over `buf` (1 GiB, beyond the last-level cache) and chains of independent MFMAs of the two
+    f16 shapes at two waves per SIMD.  Context for the roofline fractions, which stay against the
+    published peaks."""
+    import torch
+    from paper_2408_01890_amd import lisa
+    sink = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+
+    def timed(fn, n):
+        fn()
+        torch.cuda.synchronize()
+        ev[0].record()
+        for _ in range(n):
+            fn()
+        ev[1].record()
+        torch.cuda.synchronize()
+        return ev[0].elapsed_time(ev[1]) * 1e-3 / n
+
+    out = {}
+    sec = timed(lambda: lisa.probe_hbm_read(buf, sink), 5)
+    out["hbm_read_GBs"] = buf.numel() / sec / 1e9
+    wgs, iters = 512, 20000
+    for shape, name in ((0, "mfma_16x16x32_f16_TFLOPs"), (1, "mfma_32x32x16_f16_TFLOPs")):
+        sec = timed(lambda: lisa.probe_mfma(shape, iters, wgs, sink), 2)
+        out[name] = wgs * 4 * iters * 131072.0 / sec / 1e12
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -627,7 +657,9 @@ def main():
     cal2 = torch.empty_like(cal)
     cal2.copy_(cal)
     torch.cuda.synchronize()
-    del cal, cal2
+    del cal2
+    reference = chip_reference(cal)
+    del cal
     if args.decode_only:
         print(json.dumps(decode_stack(synth.C5, args.decode_steps, 1)), flush=True)
         return
@@ -648,6 +680,7 @@ def main():
     torch.cuda.empty_cache()
     extra = {k: head[k] for k in head if k not in ("roofline", "cpu_baseline", "workload", "tokens_per_s",
                                                    "ms_per_step")}
+    extra["chip_reference"] = reference
     extra["paper_context"] = ("end-to-end generation throughput gains on one A800-80GB: +19.5% LLaMA3-8B, "
                               "+32.3% LLaMA2-7B, +40.1% LLaMA2-13B (not this metric)")
     # ---- the other two bf16 prefill configurations, each with its own roofline and baseline -----

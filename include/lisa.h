@@ -409,6 +409,24 @@ typedef enum {
 int lisa_tune_set(int knob, int value);
 
 /*
+ * Reference kernels for benchmarks (diagnostic; nothing of the method is computed).  The caller times
+ * them with events on the stream it passes; bench.py reports their rates next to the roofline
+ * fractions of the library's kernels, as what a plain kernel reaches on the chip at hand.
+ *   lisa_probe_hbm_read   reads `bytes` bytes (device memory, 16-byte aligned; a multiple of 16 is
+ *                         read) once with 8 loads of 16 bytes in flight per lane and writes nothing.
+ *                         `sink`: 16 bytes of device memory that stay untouched (they keep the loads
+ *                         alive for the compiler).  Use a buffer larger than the last-level cache.
+ *   lisa_probe_mfma       `workgroups` workgroups of four waves, each wave `iters` rounds of
+ *                         independent MFMAs on constant operands: shape 0 = 8 x 16x16x32 f16 per round
+ *                         (the shape of the library's FFNs), 1 = 4 x 32x32x16 f16 (the same
+ *                         2 x 65536 flop per wave and round).  `sink` as above (4 bytes used).
+ * Return LISA_OK, LISA_ERR_NULL / LISA_ERR_ALIGN / LISA_ERR_SHAPE (checked before the launch) or
+ * LISA_ERR_HIP.
+ */
+int lisa_probe_hbm_read(const void* src, size_t bytes, void* sink, void* hip_stream);
+int lisa_probe_mfma(int shape, int iters, int workgroups, void* sink, void* hip_stream);
+
+/*
  * Stage timing for benchmarks (diagnostic, per calling thread, off by default).  While
  * enabled, every entry point brackets each kernel it launches with HIP events recorded on
  * the call's own stream; nothing is synchronised until lisa_profile_collect().

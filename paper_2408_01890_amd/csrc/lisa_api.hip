@@ -15,6 +15,7 @@
 #include "kernels_kd.h"
 #include "kernels_generic.h"
 #include "kernels_prefill.h"
+#include "kernels_probe.h"
 #include "kernels_project.h"
 #include "kernels_scores_mfma.h"
 #include "kernels_std_prefill.h"
@@ -1288,6 +1289,23 @@ int lisa_tune_set(int knob, int value) {
   if (knob < 0 || knob >= LISA_TUNE_COUNT) return LISA_ERR_SHAPE;
   g_tune[knob] = value < 0 ? -1 : value;
   return LISA_OK;
+}
+
+int lisa_probe_hbm_read(const void* src, size_t bytes, void* sink, void* hip_stream) {
+  if (!src || !sink) return LISA_ERR_NULL;
+  if (!aligned16(src) || !aligned16(sink)) return LISA_ERR_ALIGN;
+  if (bytes < 16) return LISA_ERR_SHAPE;
+  k_probe_read<<<8 * kComputeUnits, 256, 0, (hipStream_t)hip_stream>>>((const probe_u32x4*)src, bytes / 16, (probe_u32x4*)sink);
+  return check_launch();
+}
+
+int lisa_probe_mfma(int shape, int iters, int workgroups, void* sink, void* hip_stream) {
+  if (!sink) return LISA_ERR_NULL;
+  if ((shape != 0 && shape != 1) || iters < 1 || workgroups < 1 || workgroups > 65536) return LISA_ERR_SHAPE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (shape == 0) k_probe_mfma<0><<<workgroups, 256, 0, st>>>(iters, 0.25f, (float*)sink);
+  else k_probe_mfma<1><<<workgroups, 256, 0, st>>>(iters, 0.25f, (float*)sink);
+  return check_launch();
 }
 
 const char* lisa_last_hip_error(void) { return g_hip_err; }

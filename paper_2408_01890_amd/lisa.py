@@ -29,6 +29,7 @@ EXPORTS = (
     "lisa_profile_collect", "lisa_cache_fill", "lisa_project_qkv", "lisa_layer_prefill",
     "lisa_layer_offsets", "lisa_layer_decode", "lisa_tune_set", "lisa_attn_decode_static",
     "lisa_decode_stack", "lisa_stack_workspace_bytes", "lisa_scores_elems", "lisa_kd_huber",
+    "lisa_probe_hbm_read", "lisa_probe_mfma",
 )
 TUNE_PREFILL_GROUPS, TUNE_PREFILL_SPLIT, TUNE_PREFILL_PAIR, TUNE_STD_PAIR, TUNE_PROJECT_TN, TUNE_PREFILL_SLICES = range(6)
 
@@ -116,6 +117,10 @@ def _lib():
         h.lisa_last_path.restype = C.c_char_p
         h.lisa_profile_enable.argtypes = [C.c_int]
         h.lisa_profile_enable.restype = C.c_int
+        h.lisa_probe_hbm_read.argtypes = [vp, sz, vp, vp]
+        h.lisa_probe_hbm_read.restype = C.c_int
+        h.lisa_probe_mfma.argtypes = [C.c_int, C.c_int, C.c_int, vp, vp]
+        h.lisa_probe_mfma.restype = C.c_int
         h.lisa_cache_fill.argtypes = [dp] + [vp] * 5
         h.lisa_cache_fill.restype = C.c_int
         h.lisa_project_qkv.argtypes = [C.POINTER(ProjDesc)] + [vp] * 6
@@ -221,6 +226,22 @@ class tune:
         for k, _ in self.knobs:
             _lib().lisa_tune_set(k, -1)
         return False
+
+
+def probe_hbm_read(buf: torch.Tensor, sink: torch.Tensor) -> None:
+    """Reference kernel: one read pass over `buf` (device tensor), nothing written; time it with events."""
+    rc = _lib().lisa_probe_hbm_read(C.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(),
+                                    C.c_void_p(sink.data_ptr()), _stream())
+    if rc:
+        raise LisaError(rc, "lisa_probe_hbm_read")
+
+
+def probe_mfma(shape: int, iters: int, workgroups: int, sink: torch.Tensor) -> None:
+    """Reference kernel: `iters` rounds of 2 x 65536 flop of independent MFMAs per wave, four waves per
+    workgroup; shape 0 = 16x16x32 f16, 1 = 32x32x16 f16."""
+    rc = _lib().lisa_probe_mfma(shape, iters, workgroups, C.c_void_p(sink.data_ptr()), _stream())
+    if rc:
+        raise LisaError(rc, "lisa_probe_mfma")
 
 
 def profile_enable(on: bool) -> None:

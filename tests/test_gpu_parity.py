@@ -1447,3 +1447,18 @@ def test_projection_random_shapes(seed):
     rows = {b: np.unique(np.concatenate([np.arange(min(L, 3)), rs.randint(0, L, 24), [L - 1]])) for b in range(B)}
     path = check_projection(cfg, pin, rows, theta, pos0, dim_major, pos0 + L + extra)
     assert path == ("project_skinny" if B * L <= 128 else "project_mfma")
+
+
+def test_reference_kernels_run_and_leave_their_sink_alone():
+    """The benchmark's reference kernels (a read pass, chains of MFMAs) launch, finish and write nothing."""
+    buf = torch.full((1 << 22,), 7, dtype=torch.uint8, device=DEV)
+    sink = torch.full((64,), 3, dtype=torch.uint8, device=DEV)
+    lisa.probe_hbm_read(buf, sink)
+    lisa.probe_hbm_read(buf[: (1 << 22) - 4096 + 16], sink)      # a ragged tail
+    for shape in (0, 1):
+        lisa.probe_mfma(shape, 100, 16, sink)
+    torch.cuda.synchronize()
+    assert bool((sink == 3).all())
+    with pytest.raises(lisa.LisaError) as e:
+        lisa.probe_mfma(2, 100, 16, sink)
+    assert e.value.status == -2
