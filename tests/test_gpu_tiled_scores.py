@@ -207,3 +207,19 @@ def test_lisa_prefill_tiled_full_size_sampled_rows(cfg, ffn):
     per_b = 256 // cfg.B + 24
     rows_by_b = {b: synth.sample_rows(cfg.L, per_b, 100 + b) for b in range(cfg.B)}
     check_prefill(cfg, inp, prev, out, scores, rows_by_b, tag=f"/{ffn}/tiled")
+
+
+@pytest.mark.parametrize("ffn", ["paper", "fan_in"])
+def test_concat_tiled_full_size_sampled_rows_against_the_oracle(ffn):
+    """The paper's module at its own widths (Sec. 5.3: 64 -> 256 -> 32, r = 20) on the LLaMA2-7B shape,
+    on tiled score tensors as bench.py times it."""
+    cfg = synth.LayerShape("c2_concat_64_256_32_r20_tiled", "bf16", 1, 32, 32, 2048, 4096, 128, 20, 256)
+    log(f"[case] prefill {cfg.name} ffn={ffn} sampled")
+    inp = synth.make_prefill_inputs(cfg, synth.BASE_SEED + 21, DEV, mix="concat", ffn=ffn)
+    prev, _ = lisa.std_attn_scores(inp["q"], inp["k"], tiled=True)
+    out, scores = lisa.lisa_attn_prefill(inp["q_lr"], inp["k_lr"], inp["v"], prev, inp["w1"], inp["w2"],
+                                         mix=lisa.MIX_CONCAT, tiled=True)
+    torch.cuda.synchronize()
+    assert lisa.last_path() == "mfma_scores"
+    rows = synth.sample_rows(cfg.L, 280, 121)
+    check_prefill(cfg, inp, prev, out, scores, {0: rows}, mix=1, tag=f"/{ffn}/tiled")
