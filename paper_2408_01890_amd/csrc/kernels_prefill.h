@@ -264,7 +264,9 @@ __device__ __forceinline__ void st_uv_stream(void* ubase, unsigned voff, T v) {
 // NG = 1 and 32 heads (XSTG below) the whole layer of a row block runs in one workgroup: the FFN is
 // computed once, the A_{n-1} tile is read once, and a wave issues 10 operand loads per tile and
 // key/value head for four query heads.
-template <int NG, int FS, int HPW, int NW, int ACT = 0, int RS = 1, int SHG = 0>
+// FTRIM: F <= 32 FS - 16, the last 16 hidden units are padding and their products are left out
+// (the 40 -> 80 -> 40 network of the LLaMA2-13B shape: 10 instead of 12 MFMAs of the first layer).
+template <int NG, int FS, int HPW, int NW, int ACT = 0, int RS = 1, int SHG = 0, bool FTRIM = false>
 __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
   static_assert(RS == 1 || HPW == 1, "row slices: one head per wave");
   // XSTG: the A_{n-1} piece is double buffered by tile parity and the buffers double as the staging
@@ -626,7 +628,7 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
         }
         f32x4 y[NBLK][HBO];
         if (WREG) ffn.template apply<NBLK>(x, y);
-        else Ffn::template apply_lds<NBLK>(w_s, x, y);
+        else Ffn::template apply_lds<NBLK, FTRIM>(w_s, x, y);
 #pragma unroll
         for (int n = 0; n < NBLK; ++n)
 #pragma unroll

@@ -606,7 +606,7 @@ PrefillWs prefill_fused_ws(const lisa_desc* d) {
   return w;
 }
 
-template <int NG, int FS, int HPW, int NW, int ACT, int RS, int SHG = 0>
+template <int NG, int FS, int HPW, int NW, int ACT, int RS, int SHG = 0, bool FTRIM = false>
 int launch_prefill_fused_t(const lisa_desc* d, const PrefillArgs& a, hipStream_t st) {
   constexpr int GH = NW * HPW, H = NG * GH;
   typedef MfmaFfn<(H + 15) / 16, FS, (GH + 15) / 16> Ffn;
@@ -616,7 +616,7 @@ int launch_prefill_fused_t(const lisa_desc* d, const PrefillArgs& a, hipStream_t
                               : (size_t)H * PF_XS_HEAD + (size_t)GH * PF_YS_HEAD + Ffn::kStageBytes +
                                     (size_t)GH * RS * PF_AS_HEAD;
   static_assert(lds <= 160 * 1024, "LDS of one compute unit");
-  auto kern = k_lisa_prefill_fused<NG, FS, HPW, NW, ACT, RS, SHG>;
+  auto kern = k_lisa_prefill_fused<NG, FS, HPW, NW, ACT, RS, SHG, FTRIM>;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)lds);
   if (e != hipSuccess) return hip_fail(e);
@@ -632,9 +632,12 @@ int launch_prefill_fused_t(const lisa_desc* d, const PrefillArgs& a, hipStream_t
 
 template <int NG, int HPW, int NW, int ACT, int RS, int SHG = 0>
 int launch_prefill_fused_act(const lisa_desc* d, const PrefillArgs& a, hipStream_t st) {
-  if (RS > 1)                                                // row slices: 33..96 hidden units (prefill_slices_ok)
-    return (d->F + 31) / 32 == 2 ? launch_prefill_fused_t<NG, 2, HPW, NW, ACT, RS, SHG>(d, a, st)
-                                 : launch_prefill_fused_t<NG, 3, HPW, NW, ACT, RS, SHG>(d, a, st);
+  if (RS > 1) {                                              // row slices: 33..96 hidden units (prefill_slices_ok)
+    if ((d->F + 31) / 32 == 2) return launch_prefill_fused_t<NG, 2, HPW, NW, ACT, RS, SHG>(d, a, st);
+    // (two slices, 65..80 hidden units: the last block of 16 is padding)
+    if (RS == 2 && d->F <= 80) return launch_prefill_fused_t<NG, 3, HPW, NW, ACT, RS, SHG, true>(d, a, st);
+    return launch_prefill_fused_t<NG, 3, HPW, NW, ACT, RS, SHG>(d, a, st);
+  }
   switch ((d->F + 31) / 32) {
     case 1: return launch_prefill_fused_t<NG, 1, HPW, NW, ACT, 1, SHG>(d, a, st);
     case 2: return launch_prefill_fused_t<NG, 2, HPW, NW, ACT, 1, SHG>(d, a, st);

@@ -103,7 +103,10 @@ struct MfmaFfn {
 
   // apply() with the weight operands read from the staged LDS image as the products need them
   // (no weight registers held by the caller).
-  template <int NBLK>
+  // skip_last: the last block of 16 hidden units is all padding (F <= 32 FS - 16, e.g.
+  // the 40 -> 80 -> 40 network of the LLaMA2-13B shape): its products are left out, its hidden
+  // units are the activation of zero, which is zero for both activations.
+  template <int NBLK, bool skip_last = false>
   __device__ __forceinline__ static void apply_lds(const unsigned short* lds, const f16x8 (&x)[NBLK][KS],
                                                    f32x4 (&y)[NBLK][HBO]) {
     const int lane = threadIdx.x & 63;
@@ -117,12 +120,14 @@ struct MfmaFfn {
         f32x4 acc[NBLK];
 #pragma unroll
         for (int n = 0; n < NBLK; ++n) acc[n] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (!(s == FS - 1 && half == 1 && skip_last)) {
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          const f16x8 w = *(const f16x8*)(l1 + ((2 * s + half) * KS + ks) * 512);
+          for (int ks = 0; ks < KS; ++ks) {
+            const f16x8 w = *(const f16x8*)(l1 + ((2 * s + half) * KS + ks) * 512);
 #pragma unroll
-          for (int n = 0; n < NBLK; ++n)
-            acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w, x[n][ks], acc[n], 0, 0, 0);
+            for (int n = 0; n < NBLK; ++n)
+              acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w, x[n][ks], acc[n], 0, 0, 0);
+          }
         }
 #pragma unroll
         for (int n = 0; n < NBLK; ++n)
