@@ -679,7 +679,15 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
           f16x8 hv;
 #pragma unroll
           for (int e = 0; e < 8; ++e) hv[e] = f32_to_half_sat(an[e]);
-          if (XSTG) *(f16x8*)(xs_t + (wv * HPW + hh) * PF_XS_HEAD + c * (2 * PF_TK) + g * 16) = hv;
+          if (a.tiled && !XSTG) {
+            // tiled scores: the lane's 8 keys of row c are 16 bytes of the head's KB and leave from
+            // the registers (through the staging tile, which row-major scores need to pair two
+            // tiles into whole lines, the layer took 1 - 3 % longer)
+            if (i0 + PF_ROWS * rs < Lq) {
+              const size_t at = ((size_t)((i0 >> 4) + rs) * n_kt + tile) * tile_stride;   // wave-uniform
+              st_uv_stream<f16x8>(s_base[hh] + at, (unsigned)(c * 64 + g * 16), hv);
+            }
+          } else if (XSTG) *(f16x8*)(xs_t + (wv * HPW + hh) * PF_XS_HEAD + c * (2 * PF_TK) + g * 16) = hv;
           else *(f16x8*)(as_ + sl * PF_AS_HEAD + c * PF_AS_ROW + (tile & 1) * 64 + g * 16) = hv;
         }
         // online softmax, statistics of row c kept by all four lanes 16 g + c; exponentials in
@@ -730,7 +738,7 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
       // A_n is written once both tiles of a pair are staged (64-byte pieces of a line reach HBM at
       // half the rate of whole lines): after the odd tile when walking upwards (or after the
       // slice's last tile, which may have no partner), after the even tile when walking downwards.
-      if (a.scores && (rep ? (tile & 1) == 0 : ((tile & 1) == 1 || tile >= last_tile_of(rs)))) pending[rs] = tile;
+      if (a.scores && (XSTG || !a.tiled) && (rep ? (tile & 1) == 0 : ((tile & 1) == 1 || tile >= last_tile_of(rs)))) pending[rs] = tile;
       if (XSTG && pending[rs] >= 0) {
         // the pair sits in the two A_{n-1} buffers, which the next pieces are about to overwrite
 #pragma unroll
