@@ -41,6 +41,12 @@ struct DecodeArgs {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+// 16 bytes of a K / K_LR / V cache, read once per step and never again before the whole cache has
+// passed: a non-temporal load.  A read stream shaped like this kernel's (2112 regions of 1 MB, a
+// wave per head, 256-byte pieces 8 KB apart) reaches 5.7 TB/s with plain loads and 6.4 - 6.6 TB/s
+// with these.
+__device__ __forceinline__ u32x4 ld_stream(const bf16_t* p) { return __builtin_nontemporal_load((const u32x4*)p); }
+
 // LISA_MODE: 0 = standard layer, 1 = LiSA layer in ADD form (HB = blocks of 16 heads), 2 = LiSA
 // layer in CONCAT form (HB = blocks of 16 FFN inputs, 2H of them; (HB + 1) / 2 output blocks; the
 // FFN weights stay in LDS), 3 = direct sharing: the scores are the previous layer's row as it
@@ -75,7 +81,7 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
       const int jc = min(v_js + (it + u) * KPW, n_here - 1);
-      vv[u] = *(const u32x4*)(vb + (size_t)(j0 + jc) * a.vs.j);
+      vv[u] = ld_stream(vb + (size_t)(j0 + jc) * a.vs.j);
     }
   };
   u32x4 va[UN];
@@ -126,7 +132,7 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
           for (int t0 = 0; t0 < a.r; t0 += UN) {
             u32x4 kvv[UN];
 #pragma unroll
-            for (int u = 0; u < UN; ++u) kvv[u] = *(const u32x4*)(kp + (size_t)min(t0 + u, a.r - 1) * a.ks.t);
+            for (int u = 0; u < UN; ++u) kvv[u] = ld_stream(kp + (size_t)min(t0 + u, a.r - 1) * a.ks.t);
 #pragma unroll
             for (int u = 0; u < UN; ++u) {
               const float qt = t0 + u < a.r ? q_s[h * a.r + t0 + u] : 0.f;
@@ -166,7 +172,7 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
 #pragma unroll
       for (int u = 0; u < UN; ++u) {
         const int jc = min(js + (it + u) * KPW, n_here - 1);     // clamped, result unused
-        kvv[u] = *(const u32x4*)(kb + (size_t)(j0 + jc) * a.ks.j);
+        kvv[u] = ld_stream(kb + (size_t)(j0 + jc) * a.ks.j);
       }
     };
     float qf[8];
