@@ -51,8 +51,11 @@ __device__ __forceinline__ u32x4 ld_stream(const bf16_t* p) { return __builtin_n
 // layer in CONCAT form (HB = blocks of 16 FFN inputs, 2H of them; (HB + 1) / 2 output blocks; the
 // FFN weights stay in LDS), 3 = direct sharing: the scores are the previous layer's row as it
 // stands (no key-side operand, no FFN; HB, FS unused).  DK: head dimension (64 or 128).
+// (four workgroups per compute unit where the kernel is within a few registers of 128 per lane: with
+// the caches streamed past the L2 that is worth 2 - 3 % of the step; with plain loads it was not)
 template <int LISA_MODE, int HB, int FS, int DK, int ACT = 0>
-__global__ __launch_bounds__(DEC_THREADS) void k_decode_part(DecodeArgs a) {
+__global__ __launch_bounds__(DEC_THREADS, (LISA_MODE != 2 && HB <= 2 && FS <= 2 && DK == 128) ? 4 : 1)
+void k_decode_part(DecodeArgs a) {
   constexpr int LPK = DK / 8;        // lanes per key in the 16-byte streams
   constexpr int KPW = 64 / LPK;      // keys per wave instruction
   constexpr int UN = 8;              // independent loads in flight per lane in the streams
