@@ -18,6 +18,14 @@ namespace lisa {
 
 constexpr int KD_UN = 4;   // tiles of a wave whose loads are in flight together (tiled layout)
 
+// 16 bytes of a score tensor, read once by this kernel: a non-temporal load
+template <class P>
+__device__ __forceinline__ uint4 kd_ld16(const P* p) {
+  typedef unsigned kd_u32x4 __attribute__((ext_vector_type(4)));
+  const kd_u32x4 v = __builtin_nontemporal_load((const kd_u32x4*)p);
+  return make_uint4(v[0], v[1], v[2], v[3]);
+}
+
 struct KdArgs {
   const void* a;          // student scores
   const void* t;          // teacher scores, same layout
@@ -46,49 +54,57 @@ __global__ __launch_bounds__(256) void k_kd_huber_part(KdArgs g) {
   const S* t = (const S*)g.t;
   double acc = 0.0;
   if (g.tiled) {
-    // [B, n_rb, n_kt, H, 16, 32]: one wave per tile of a head (1 KB of each tensor, lane -> row
-    // lane / 4, 8 keys); tiles that no row of their block can see are skipped unread
-    const long long n_tiles = (long long)g.B * n_rb * n_kt * g.H;
-    const long long stride = (long long)gridDim.x * 4;
-    for (long long tile0 = (long long)blockIdx.x * 4 + wv; tile0 < n_tiles; tile0 += KD_UN * stride) {
-      uint4 av[KD_UN], tv[KD_UN];
-      int nvis[KD_UN], j8[KD_UN];
-#pragma unroll
-      for (int u = 0; u < KD_UN; ++u) {
-        const long long tile = tile0 + u * stride;
-        nvis[u] = 0;
-        j8[u] = 0;
-        av[u] = tv[u] = uint4{0, 0, 0, 0};
-        if (tile >= n_tiles) continue;                        // (wave-uniform)
-        const int kt = (int)((tile / g.H) % n_kt);
-        const int rb = (int)((tile / g.H / n_kt) % n_rb);
+    // [B, n_rb, n_kt, H, 16, 32]: the visible tiles of a row block (key tiles 0 .. last, all heads)
+    // are one run of consecutive KB in each tensor.  A workgroup takes a long and a short row block
+    // at a time (equal work), a wave every fourth KB of the run, KD_UN of them in flight; the
+    // loads of the run's tail are clamped, not branched around (a load behind a branch makes the
+    // compiler wait for all earlier ones), and count nothing.  Tiles above the diagonal are not read.
+    const int n_half = (n_rb + 1) / 2;
+    const long long n_pairs = (long long)g.B * n_half;
+    for (long long pair = blockIdx.x; pair < n_pairs; pair += gridDim.x) {
+      const int b = (int)(pair / n_half), p = (int)(pair % n_half);
+#pragma unroll 1
+      for (int side = 0; side < 2; ++side) {
+        const int rb = side ? p : n_rb - 1 - p;
+        if (side && rb >= n_rb - 1 - p) break;               // (the middle block of an odd count is alone)
         const int i_last = min(16 * rb + 15, g.Lq - 1);
-        if (32 * kt >= (g.causal ? min(g.Lk, i_last + 1 + shift) : g.Lk)) continue;   // (wave-uniform)
+        const int n_keys = g.causal ? min(g.Lk, i_last + 1 + shift) : g.Lk;
+        const int run = (n_keys + 31) / 32 * g.H;            // KB of this row block that hold visible entries
+        if (run <= 0) continue;
+        const size_t base = ((size_t)b * n_rb + rb) * n_kt * g.H * 512 + lane * 8;
         const int i = 16 * rb + (lane >> 2);
-        j8[u] = 32 * kt + 8 * (lane & 3);
-        nvis[u] = i < g.Lq ? (g.causal ? min(g.Lk, i + 1 + shift) : g.Lk) : 0;
-        const size_t at = (size_t)tile * 512 + lane * 8;
-        if (sizeof(S) == 2) {
-          av[u] = *(const uint4*)(a + at);
-          tv[u] = *(const uint4*)(t + at);
-        } else {
-          float s = 0.f;
+        const int vis_row = i < g.Lq ? (g.causal ? min(g.Lk, i + 1 + shift) : g.Lk) : 0;
+        for (int k0 = wv; k0 < run; k0 += 4 * KD_UN) {
+          uint4 av[KD_UN], tv[KD_UN];
 #pragma unroll
-          for (int e = 0; e < 8; ++e)
-            if (j8[u] + e < nvis[u]) s += huber1(elem<S>::load(a + at + e), elem<S>::load(t + at + e), g.delta);
-          acc += (double)s;
-          nvis[u] = 0;
+          for (int u = 0; u < KD_UN; ++u) {
+            const size_t at = base + (size_t)min(k0 + 4 * u, run - 1) * 512;
+            if (sizeof(S) == 2) {
+              av[u] = kd_ld16(a + at);
+              tv[u] = kd_ld16(t + at);
+            }
+          }
+#pragma unroll
+          for (int u = 0; u < KD_UN; ++u) {
+            const int k = k0 + 4 * u;
+            const int j8 = 32 * (k / g.H) + 8 * (lane & 3);
+            const int nvis = k < run ? vis_row : 0;
+            float sm = 0.f;
+            if (sizeof(S) == 2) {
+              const half_t* ah = (const half_t*)&av[u];
+              const half_t* th = (const half_t*)&tv[u];
+#pragma unroll
+              for (int e = 0; e < 8; ++e)
+                if (j8 + e < nvis) sm += huber1((float)ah[e], (float)th[e], g.delta);
+            } else {
+              const size_t at = base + (size_t)min(k, run - 1) * 512;
+#pragma unroll
+              for (int e = 0; e < 8; ++e)
+                if (j8 + e < nvis) sm += huber1(elem<S>::load(a + at + e), elem<S>::load(t + at + e), g.delta);
+            }
+            acc += (double)sm;
+          }
         }
-      }
-#pragma unroll
-      for (int u = 0; u < KD_UN; ++u) {
-        const half_t* ah = (const half_t*)&av[u];
-        const half_t* th = (const half_t*)&tv[u];
-        float s = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-          if (j8[u] + e < nvis[u]) s += huber1((float)ah[e], (float)th[e], g.delta);
-        acc += (double)s;
       }
     }
   } else {
@@ -100,7 +116,7 @@ __global__ __launch_bounds__(256) void k_kd_huber_part(KdArgs g) {
       const bool vec = sizeof(S) == 2 && g.Lk % 8 == 0;      // 16-byte aligned runs of 8 (bases are checked on the host)
       for (int j8 = lane * 8; j8 < nvis; j8 += 512) {
         if (vec) {
-          const uint4 av = *(const uint4*)(a + base + j8), tv = *(const uint4*)(t + base + j8);
+          const uint4 av = kd_ld16(a + base + j8), tv = kd_ld16(t + base + j8);
           const half_t* ah = (const half_t*)&av;
           const half_t* th = (const half_t*)&tv;
 #pragma unroll
