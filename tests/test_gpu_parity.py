@@ -453,6 +453,8 @@ SLICE_SHAPES = [
     ("h8_chunk_shift128", 2, 8, 4, 136, 264, 11, 64),
     ("h16_f40", 1, 16, 16, 296, 296, 22, 40),
     ("h32_shift24", 1, 32, 32, 248, 272, 22, 64),
+    ("h8_f72", 1, 8, 8, 136, 136, 11, 72),       # 65..80 hidden units: the sixth block of 16 is left out
+    ("h16_f96", 1, 16, 4, 168, 168, 22, 96),      # ... and 81..96: it is not
 ]
 
 
