@@ -218,7 +218,10 @@ int lisa_attn_decode_static(const lisa_desc* desc, const void* q_lr, const void*
  *     out        [B,H,d_k]  out  the layer's attention output
  *     score_row  [B,H,Lk]   out  or NULL: where to keep this layer's A_n (score type)
  *   workspace    at least lisa_stack_workspace_bytes(desc) bytes
- * All layers are enqueued on hip_stream in order; the call returns after the last launch.
+ * All layers are enqueued on hip_stream in order; the call returns after the last launch.  The
+ * partial results of a layer (split over the cached keys) are combined into its `out` by trailing
+ * workgroups of the next layer's launch, the last layer's by a launch of their own: a layer's
+ * `out` is complete when the call's work on the stream is, not before.
  */
 typedef enum { LISA_LAYER_STD = 0, LISA_LAYER_LISA = 1, LISA_LAYER_SHARE = 2 } lisa_layer_kind;
 typedef struct lisa_stack_layer {
@@ -234,7 +237,7 @@ typedef struct lisa_stack_layer {
 } lisa_stack_layer;
 int lisa_decode_stack(const lisa_desc* desc, const lisa_stack_layer* layers, int32_t n_layers,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
-/* Scratch bytes of lisa_decode_stack for this descriptor (two score rows + the largest layer). */
+/* Scratch bytes of lisa_decode_stack for this descriptor (two score rows + twice the largest layer). */
 size_t lisa_stack_workspace_bytes(const lisa_desc* desc);
 
 /*

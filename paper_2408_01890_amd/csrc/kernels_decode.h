@@ -37,6 +37,14 @@ struct DecodeArgs {
   float* part_ml;        // [B][n_chunk][H][2]  (max, sum)
   int H, Hkv, Lk, r, F, n_chunk;
   float scale;
+  // Rows of the grid from B on (none in a single call) combine the partial results of the layer
+  // before, which a stack leaves to the next layer's launch: unit u = head u % cmb_H of sequence
+  // u / cmb_H, cmb_units of them, the same d_k as this launch.
+  int B;
+  const float* cmb_o;
+  const float* cmb_ml;
+  void* cmb_out;
+  int cmb_units, cmb_H, cmb_nchunk, cmb_out_f32;
 };
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -46,6 +54,75 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 // wave per head, 256-byte pieces 8 KB apart) reaches 5.7 TB/s with plain loads and 6.4 - 6.6 TB/s
 // with these.
 __device__ __forceinline__ u32x4 ld_stream(const bf16_t* p) { return __builtin_nontemporal_load((const u32x4*)p); }
+
+// out[b][h][:] = sum_c e^{m_c - M} O_c / sum_c e^{m_c - M} s_c,  M = max_c m_c, for one (h, b) by a
+// workgroup of 256 threads: the chunks are dealt to 256 / (DK / 4) groups of DK / 4 lanes (four
+// features per lane, independent 16-byte loads), the groups' sums are merged through `lds`
+// (4.2 KB, 16-byte aligned).
+template <typename O, int DK>
+__device__ __forceinline__ void decode_combine_unit(const float* __restrict__ part_o,
+                                                    const float* __restrict__ part_ml, O* __restrict__ out,
+                                                    int H, int n_chunk, int h, int b, float* lds) {
+  constexpr int LPG = DK / 4, NGRP = 256 / LPG;
+  float4* s_num = (float4*)lds;                              // [NGRP][LPG]
+  float* s_den = lds + NGRP * LPG * 4;                       // [NGRP]
+  float* s_max = s_den + NGRP;
+  const int tid = threadIdx.x;
+  const size_t row0 = (size_t)b * n_chunk * H + h;            // chunk c: row0 + c * H
+  if (tid < 64) {
+    float m = -INFINITY;
+    for (int c = tid; c < n_chunk; c += 64) m = fmaxf(m, part_ml[(row0 + (size_t)c * H) * 2]);
+    m = wave_max(m);
+    if (tid == 0) *s_max = m;
+  }
+  __syncthreads();
+  const float M = *s_max;
+  const int grp = tid / LPG, l = tid % LPG;
+  float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+  float den = 0.f;
+  for (int c = grp; c < n_chunk; c += NGRP) {
+    const size_t at = row0 + (size_t)c * H;
+    const float2 ml = *(const float2*)(part_ml + at * 2);
+    const float4 po = *(const float4*)(part_o + at * DK + 4 * l);
+    const float w = __expf(ml.x - M);
+    den += w * ml.y;
+    num.x += w * po.x;
+    num.y += w * po.y;
+    num.z += w * po.z;
+    num.w += w * po.w;
+  }
+  s_num[grp * LPG + l] = num;
+  if (l == 0) s_den[grp] = den;
+  __syncthreads();
+  if (tid < LPG) {
+    float4 n = s_num[tid];
+    float dsum = s_den[0];
+#pragma unroll
+    for (int gi = 1; gi < NGRP; ++gi) {
+      const float4 x = s_num[gi * LPG + tid];
+      n.x += x.x;
+      n.y += x.y;
+      n.z += x.z;
+      n.w += x.w;
+      dsum += s_den[gi];
+    }
+    const float inv = 1.f / dsum;
+    O* o = out + ((size_t)b * H + h) * DK + 4 * tid;
+    elem<O>::store(o, n.x * inv);
+    elem<O>::store(o + 1, n.y * inv);
+    elem<O>::store(o + 2, n.z * inv);
+    elem<O>::store(o + 3, n.w * inv);
+  }
+}
+
+// grid (H, B), block 256
+template <typename O, int DK>
+__global__ __launch_bounds__(256) void k_decode_combine(const float* __restrict__ part_o,
+                                                        const float* __restrict__ part_ml,
+                                                        O* __restrict__ out, int H, int n_chunk) {
+  __shared__ __align__(16) float s_lds[256 * 4 + 64];
+  decode_combine_unit<O, DK>(part_o, part_ml, out, H, n_chunk, blockIdx.x, blockIdx.y, s_lds);
+}
 
 // LISA_MODE: 0 = standard layer, 1 = LiSA layer in ADD form (HB = blocks of 16 heads), 2 = LiSA
 // layer in CONCAT form (HB = blocks of 16 FFN inputs, 2H of them; (HB + 1) / 2 output blocks; the
@@ -65,6 +142,20 @@ void k_decode_part(DecodeArgs a) {
   float* q_s = a_s + H * DEC_CK;              // LiSA: [H][r], then the FFN weights
   unsigned short* w_s = (unsigned short*)(q_s + ((H * a.r + 3) & ~3));   // 16-byte aligned
   const int chunk = blockIdx.x, b = blockIdx.y;
+  if (b >= a.B) {
+    // a trailing row of the grid: one (head, sequence) of the combine that the layer before left
+    // behind (its partial results lie in the other half of the stack's workspace); it shares
+    // nothing with this layer's work and runs beside its last workgroups
+    const int unit = (b - a.B) * (int)gridDim.x + chunk;
+    if (unit >= a.cmb_units) return;                         // (workgroup-uniform)
+    if (a.cmb_out_f32)
+      decode_combine_unit<float, DK>(a.cmb_o, a.cmb_ml, (float*)a.cmb_out, a.cmb_H, a.cmb_nchunk, unit % a.cmb_H,
+                                     unit / a.cmb_H, dec_lds);
+    else
+      decode_combine_unit<bf16_t, DK>(a.cmb_o, a.cmb_ml, (bf16_t*)a.cmb_out, a.cmb_H, a.cmb_nchunk, unit % a.cmb_H,
+                                      unit / a.cmb_H, dec_lds);
+    return;
+  }
   const int j0 = chunk * DEC_CK;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int group = H / a.Hkv;
@@ -346,65 +437,6 @@ void k_decode_part(DecodeArgs a) {
         consume(item + 1, vb2);
       }
     }
-  }
-}
-
-// out[b][h][:] = sum_c e^{m_c - M} O_c / sum_c e^{m_c - M} s_c,  M = max_c m_c.
-// grid (H, B), block 256: the chunks are dealt to 256 / (DK / 4) groups of DK / 4 lanes (four
-// features per lane, independent 16-byte loads), the groups' sums are merged through LDS.
-template <typename O, int DK>
-__global__ __launch_bounds__(256) void k_decode_combine(const float* __restrict__ part_o,
-                                                        const float* __restrict__ part_ml,
-                                                        O* __restrict__ out, int H, int n_chunk) {
-  constexpr int LPG = DK / 4, NGRP = 256 / LPG;
-  __shared__ float s_max;
-  __shared__ float4 s_num[NGRP][LPG];
-  __shared__ float s_den[NGRP];
-  const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
-  const size_t row0 = (size_t)b * n_chunk * H + h;            // chunk c: row0 + c * H
-  if (tid < 64) {
-    float m = -INFINITY;
-    for (int c = tid; c < n_chunk; c += 64) m = fmaxf(m, part_ml[(row0 + (size_t)c * H) * 2]);
-    m = wave_max(m);
-    if (tid == 0) s_max = m;
-  }
-  __syncthreads();
-  const float M = s_max;
-  const int grp = tid / LPG, l = tid % LPG;
-  float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
-  float den = 0.f;
-  for (int c = grp; c < n_chunk; c += NGRP) {
-    const size_t at = row0 + (size_t)c * H;
-    const float2 ml = *(const float2*)(part_ml + at * 2);
-    const float4 po = *(const float4*)(part_o + at * DK + 4 * l);
-    const float w = __expf(ml.x - M);
-    den += w * ml.y;
-    num.x += w * po.x;
-    num.y += w * po.y;
-    num.z += w * po.z;
-    num.w += w * po.w;
-  }
-  s_num[grp][l] = num;
-  if (l == 0) s_den[grp] = den;
-  __syncthreads();
-  if (tid < LPG) {
-    float4 n = s_num[0][tid];
-    float dsum = s_den[0];
-#pragma unroll
-    for (int gi = 1; gi < NGRP; ++gi) {
-      const float4 x = s_num[gi][tid];
-      n.x += x.x;
-      n.y += x.y;
-      n.z += x.z;
-      n.w += x.w;
-      dsum += s_den[gi];
-    }
-    const float inv = 1.f / dsum;
-    O* o = out + ((size_t)b * H + h) * DK + 4 * tid;
-    elem<O>::store(o, n.x * inv);
-    elem<O>::store(o + 1, n.y * inv);
-    elem<O>::store(o + 2, n.z * inv);
-    elem<O>::store(o + 3, n.w * inv);
   }
 }
 

@@ -406,9 +406,44 @@ size_t decode_fast_bytes(const lisa_desc* d) {
   return round_up(units * d->d_k * sizeof(float), 256) + round_up(units * 2 * sizeof(float), 256);
 }
 
+// A decode stack leaves the combine of a layer to the launch of the layer behind it (trailing rows
+// of that grid, see k_decode_part): per calling thread, set only inside lisa_decode_stack.
+struct DeferredCombine {
+  bool on = false, pending = false;
+  const float* o = nullptr;
+  const float* ml = nullptr;
+  void* out = nullptr;
+  int H = 0, B = 0, n_chunk = 0, dk = 0, out_f32 = 0;
+  long fast_calls = 0;
+};
+thread_local DeferredCombine g_dc;
+
+int launch_combine(const float* part_o, const float* part_ml, void* out, int H, int B, int n_chunk, int dk,
+                   int out_f32, hipStream_t st) {
+  dim3 grid(H, B);
+  StageScope prof("k_decode_combine", st);
+  if (dk == 128) {
+    if (out_f32) k_decode_combine<float, 128><<<grid, 256, 0, st>>>(part_o, part_ml, (float*)out, H, n_chunk);
+    else k_decode_combine<bf16_t, 128><<<grid, 256, 0, st>>>(part_o, part_ml, (bf16_t*)out, H, n_chunk);
+  } else {
+    if (out_f32) k_decode_combine<float, 64><<<grid, 256, 0, st>>>(part_o, part_ml, (float*)out, H, n_chunk);
+    else k_decode_combine<bf16_t, 64><<<grid, 256, 0, st>>>(part_o, part_ml, (bf16_t*)out, H, n_chunk);
+  }
+  return check_launch();
+}
+
+// The combine that a stack still owes, as a launch of its own.
+int flush_deferred_combine(hipStream_t st) {
+  if (!g_dc.pending) return LISA_OK;
+  g_dc.pending = false;
+  return launch_combine(g_dc.o, g_dc.ml, g_dc.out, g_dc.H, g_dc.B, g_dc.n_chunk, g_dc.dk, g_dc.out_f32, st);
+}
+
 template <int LISA_MODE, int HB, int FS, int ACT = 0>
 int launch_decode_part_dk(const lisa_desc* d, const DecodeArgs& a, size_t lds, hipStream_t st) {
-  dim3 grid(a.n_chunk, d->B);
+  // (+ rows of the grid for the combine units of the layer before, if one is attached)
+  dim3 grid(a.n_chunk, d->B + (a.cmb_units + a.n_chunk - 1) / a.n_chunk);
+  if (a.cmb_units > 0) lds = std::max<size_t>(lds, 4608);
   auto kern = d->d_k == 128 ? k_decode_part<LISA_MODE, HB, FS, 128, ACT> : k_decode_part<LISA_MODE, HB, FS, 64, ACT>;
   if (lds > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -459,6 +494,24 @@ int run_decode_fast(const lisa_desc* d, bool lisa_layer, DecodeArgs a, void* out
   a.r = d->r;
   a.F = d->F;
   a.n_chunk = decode_chunks(d);
+  a.B = d->B;
+  a.cmb_units = 0;
+  if (g_dc.on) {
+    ++g_dc.fast_calls;
+    if (g_dc.pending && g_dc.dk == d->d_k && (long long)g_dc.H * g_dc.B < (1 << 24)) {
+      a.cmb_o = g_dc.o;
+      a.cmb_ml = g_dc.ml;
+      a.cmb_out = g_dc.out;
+      a.cmb_units = g_dc.H * g_dc.B;
+      a.cmb_H = g_dc.H;
+      a.cmb_nchunk = g_dc.n_chunk;
+      a.cmb_out_f32 = g_dc.out_f32;
+      g_dc.pending = false;
+    } else {
+      int frc = flush_deferred_combine(st);
+      if (frc) return frc;
+    }
+  }
   size_t lds = (size_t)d->H * DEC_CK * sizeof(float);
   int rc;
   if (lisa_layer && d->mix == LISA_MIX_SHARE) {
@@ -488,21 +541,18 @@ int run_decode_fast(const lisa_desc* d, bool lisa_layer, DecodeArgs a, void* out
     rc = launch_decode_part_dk<0, 1, 1>(d, a, lds, st);
   }
   if (rc) return rc;
-  {
-    dim3 grid(d->H, d->B);
-    StageScope prof("k_decode_combine", st);
-    if (d->d_k == 128) {
-      if (d->out_f32)
-        k_decode_combine<float, 128><<<grid, 256, 0, st>>>(a.part_o, a.part_ml, (float*)out, d->H, a.n_chunk);
-      else
-        k_decode_combine<bf16_t, 128><<<grid, 256, 0, st>>>(a.part_o, a.part_ml, (bf16_t*)out, d->H, a.n_chunk);
-    } else {
-      if (d->out_f32)
-        k_decode_combine<float, 64><<<grid, 256, 0, st>>>(a.part_o, a.part_ml, (float*)out, d->H, a.n_chunk);
-      else
-        k_decode_combine<bf16_t, 64><<<grid, 256, 0, st>>>(a.part_o, a.part_ml, (bf16_t*)out, d->H, a.n_chunk);
-    }
-    rc = check_launch();
+  if (g_dc.on) {                                             // left to the next layer's launch (or the stack's end)
+    g_dc.pending = true;
+    g_dc.o = a.part_o;
+    g_dc.ml = a.part_ml;
+    g_dc.out = out;
+    g_dc.H = d->H;
+    g_dc.B = d->B;
+    g_dc.n_chunk = a.n_chunk;
+    g_dc.dk = d->d_k;
+    g_dc.out_f32 = d->out_f32;
+  } else {
+    rc = launch_combine(a.part_o, a.part_ml, out, d->H, d->B, a.n_chunk, d->d_k, d->out_f32, st);
   }
   if (rc == LISA_OK) g_path = "decode_split";
   return rc;
@@ -1474,7 +1524,7 @@ int lisa_attn_decode_static(const lisa_desc* desc, const void* q_lr, const void*
 // ---- a decode step through a stack of layers (Sec. 5.1: which layers share attention) -------------
 namespace {
 struct StackWs {
-  size_t rows, layer, total;      // byte offsets: two score rows, then the per-layer workspace
+  size_t rows, layer, half, total;   // byte offsets: two score rows, then two per-layer workspaces of `half` bytes
 };
 // Descriptors of the three kinds of layer, derived from the LiSA layer's.
 void stack_descs(const lisa_desc* d, lisa_desc* std_d, lisa_desc* share_d) {
@@ -1496,7 +1546,10 @@ StackWs stack_ws(const lisa_desc* d) {
   w.layer = round_up(2 * scores_bytes(d), 256);
   const size_t a = lisa_workspace_bytes(d, LISA_WS_DECODE), b = lisa_workspace_bytes(&hd, LISA_WS_DECODE),
                c = lisa_workspace_bytes(&sd, LISA_WS_STD);
-  w.total = w.layer + round_up(std::max(a, std::max(b, c)), 256);
+  // (two of them, used in turn: the partial results of a layer wait there for the launch of the
+  // next layer, which combines them)
+  w.half = round_up(std::max(a, std::max(b, c)), 256);
+  w.total = w.layer + 2 * w.half;
   return w;
 }
 }  // namespace
@@ -1533,11 +1586,15 @@ int lisa_decode_stack(const lisa_desc* desc, const lisa_stack_layer* layers, int
   stack_descs(desc, &std_d, &share_d);
   char* ws = (char*)workspace;
   void* own[2] = {ws + w.rows, ws + w.rows + scores_bytes(desc)};
-  void* lws = ws + w.layer;
-  const size_t lws_bytes = w.total - w.layer;
+  const size_t lws_bytes = w.half;
   const void* cur = nullptr;                                 // the row A_{n-1} that the next layer may share
-  for (int n = 0; n < n_layers; ++n) {
+  hipStream_t st = (hipStream_t)hip_stream;
+  g_dc = DeferredCombine{};
+  g_dc.on = true;
+  for (int n = 0; n < n_layers && rc == LISA_OK; ++n) {
     const lisa_stack_layer& ly = layers[n];
+    void* lws = ws + w.layer + (n & 1) * w.half;
+    const long calls_before = g_dc.fast_calls;
     const bool next_shares = n + 1 < n_layers && layers[n + 1].kind != LISA_LAYER_STD;
     void* dst = ly.score_row ? ly.score_row : (cur == own[0] ? own[1] : own[0]);
     if (ly.kind == LISA_LAYER_STD) {
@@ -1559,9 +1616,13 @@ int lisa_decode_stack(const lisa_desc* desc, const lisa_stack_layer* layers, int
                             share_d.write_scores ? dst : nullptr, lws, lws_bytes, hip_stream);
       if (share_d.write_scores) cur = dst;
     }
-    if (rc) return rc;
+    // a layer that ran on other kernels took no combine with it: the one owed goes out now, before
+    // its half of the workspace comes round again
+    if (rc == LISA_OK && g_dc.fast_calls == calls_before) rc = flush_deferred_combine(st);
   }
-  return LISA_OK;
+  if (rc == LISA_OK) rc = flush_deferred_combine(st);
+  g_dc = DeferredCombine{};
+  return rc;
 }
 
 int std_attn_scores(const lisa_desc* desc, const void* q, const void* k, const void* v,
