@@ -720,6 +720,16 @@ def test_decode_stack_driver_small_mixed_pattern():
     run_pattern_stack(stk, kinds, [0, 1, 2], Lmax=304)
 
 
+def test_decode_stack_with_layers_on_the_generic_kernels_in_between():
+    """A stack whose LiSA layers (160 hidden units) run on the generic kernels while its standard
+    and direct-sharing layers run on the split-context kernels: the combine that a split-context
+    layer leaves to the next launch has to go out on its own when that launch is not one."""
+    from paper_2408_01890_amd import patterns as pt
+    stk = synth.DecodeStack("stack_mixed_kernels", "bf16", 2, 8, 4, 200, 512, 128, 12, 160, 8, 1)
+    kinds = (pt.STD, pt.LISA, pt.STD, pt.STD, pt.LISA, pt.SHARE, pt.SHARE, pt.STD)
+    run_pattern_stack(stk, kinds, [0, 1], Lmax=208)
+
+
 @pytest.mark.parametrize("name", ["lisa_21_of_32", "lisa_sl_7_10_of_32"])
 def test_decode_stack_paper_patterns_full_size(name):
     """The paper's layer patterns (Sec. 5.1 table of configurations) at the shape of the decode
