@@ -663,7 +663,7 @@ __global__ __launch_bounds__(512) void k_project_skinny_lds(ProjectArgs a) {
   // This wave's slice of the reduction axis, and the chunk it starts with, rotate with the
   // workgroup: rows are D elements apart (a multiple of the channel interleave), so workgroups
   // that walk the axis in step all load from the same few L2 / HBM channels at any one time
-  // (19 -> ... us on the LLaMA2-7B width).  The order of a sum does not matter to its parity bound.
+  // (a few percent on the LLaMA2-7B width).  The order of a sum does not matter to its parity bound.
   const int kslice = D / 8, k0 = ((wv + (int)blockIdx.x) & 7) * kslice;
   const int ch_rot = (int)(blockIdx.x >> 3);
   const bf16_t* wsrc[4];
