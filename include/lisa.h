@@ -219,7 +219,7 @@ int lisa_attn_decode_static(const lisa_desc* desc, const void* q_lr, const void*
  *     score_row  [B,H,Lk]   out  or NULL: where to keep this layer's A_n (score type)
  *   workspace    at least lisa_stack_workspace_bytes(desc) bytes
  * All layers are enqueued on hip_stream in order; the call returns after the last launch.  The
- * partial results of a layer (split over the cached keys) are combined into its `out` by trailing
+ * partial results of a layer (split over the cached keys) are combined into its `out` by the
  * workgroups of the next layer's launch, the last layer's by a launch of their own: a layer's
  * `out` is complete when the call's work on the stream is, not before.
  */

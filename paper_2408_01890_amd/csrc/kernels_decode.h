@@ -37,9 +37,9 @@ struct DecodeArgs {
   float* part_ml;        // [B][n_chunk][H][2]  (max, sum)
   int H, Hkv, Lk, r, F, n_chunk;
   float scale;
-  // Rows of the grid from B on (none in a single call) combine the partial results of the layer
-  // before, which a stack leaves to the next layer's launch: unit u = head u % cmb_H of sequence
-  // u / cmb_H, cmb_units of them, the same d_k as this launch.
+  // The combine of the layer before, which a stack leaves to the next layer's launch (none in a
+  // single call): unit u = head u % cmb_H of sequence u / cmb_H, cmb_units of them, the same d_k as
+  // this launch.
   int B;
   const float* cmb_o;
   const float* cmb_ml;
@@ -142,20 +142,6 @@ void k_decode_part(DecodeArgs a) {
   float* q_s = a_s + H * DEC_CK;              // LiSA: [H][r], then the FFN weights
   unsigned short* w_s = (unsigned short*)(q_s + ((H * a.r + 3) & ~3));   // 16-byte aligned
   const int chunk = blockIdx.x, b = blockIdx.y;
-  if (b >= a.B) {
-    // a trailing row of the grid: one (head, sequence) of the combine that the layer before left
-    // behind (its partial results lie in the other half of the stack's workspace); it shares
-    // nothing with this layer's work and runs beside its last workgroups
-    const int unit = (b - a.B) * (int)gridDim.x + chunk;
-    if (unit >= a.cmb_units) return;                         // (workgroup-uniform)
-    if (a.cmb_out_f32)
-      decode_combine_unit<float, DK>(a.cmb_o, a.cmb_ml, (float*)a.cmb_out, a.cmb_H, a.cmb_nchunk, unit % a.cmb_H,
-                                     unit / a.cmb_H, dec_lds);
-    else
-      decode_combine_unit<bf16_t, DK>(a.cmb_o, a.cmb_ml, (bf16_t*)a.cmb_out, a.cmb_H, a.cmb_nchunk, unit % a.cmb_H,
-                                      unit / a.cmb_H, dec_lds);
-    return;
-  }
   const int j0 = chunk * DEC_CK;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int group = H / a.Hkv;
@@ -436,6 +422,23 @@ void k_decode_part(DecodeArgs a) {
         v_issue(item + 2, va);
         consume(item + 1, vb2);
       }
+    }
+  }
+  // ---- the combine that the layer before left behind (stacks only) ----------------------------
+  // Its (head, sequence) units are dealt to the workgroups of this launch, which take them when
+  // their own work is done: a unit waits on a few loads from the L2 while the other workgroups
+  // of the compute unit stream.  The partial results lie in the other half of the stack's
+  // workspace; nothing of this layer depends on them.
+  if (a.cmb_units > 0) {                                     // (uniform over the grid)
+    const int n_wg = (int)(gridDim.x * gridDim.y);
+    for (int unit = b * (int)gridDim.x + chunk; unit < a.cmb_units; unit += n_wg) {
+      __syncthreads();                                       // dec_lds: done with as scores / by the unit before
+      if (a.cmb_out_f32)
+        decode_combine_unit<float, DK>(a.cmb_o, a.cmb_ml, (float*)a.cmb_out, a.cmb_H, a.cmb_nchunk, unit % a.cmb_H,
+                                       unit / a.cmb_H, dec_lds);
+      else
+        decode_combine_unit<bf16_t, DK>(a.cmb_o, a.cmb_ml, (bf16_t*)a.cmb_out, a.cmb_H, a.cmb_nchunk,
+                                        unit % a.cmb_H, unit / a.cmb_H, dec_lds);
     }
   }
 }

@@ -406,8 +406,8 @@ size_t decode_fast_bytes(const lisa_desc* d) {
   return round_up(units * d->d_k * sizeof(float), 256) + round_up(units * 2 * sizeof(float), 256);
 }
 
-// A decode stack leaves the combine of a layer to the launch of the layer behind it (trailing rows
-// of that grid, see k_decode_part): per calling thread, set only inside lisa_decode_stack.
+// A decode stack leaves the combine of a layer to the launch of the layer behind it (its workgroups
+// take the units when their own work is done, see k_decode_part): per calling thread, set only inside lisa_decode_stack.
 struct DeferredCombine {
   bool on = false, pending = false;
   const float* o = nullptr;
@@ -441,9 +441,8 @@ int flush_deferred_combine(hipStream_t st) {
 
 template <int LISA_MODE, int HB, int FS, int ACT = 0>
 int launch_decode_part_dk(const lisa_desc* d, const DecodeArgs& a, size_t lds, hipStream_t st) {
-  // (+ rows of the grid for the combine units of the layer before, if one is attached)
-  dim3 grid(a.n_chunk, d->B + (a.cmb_units + a.n_chunk - 1) / a.n_chunk);
-  if (a.cmb_units > 0) lds = std::max<size_t>(lds, 4608);
+  dim3 grid(a.n_chunk, d->B);
+  if (a.cmb_units > 0) lds = std::max<size_t>(lds, 4608);   // (the combine units use the same LDS)
   auto kern = d->d_k == 128 ? k_decode_part<LISA_MODE, HB, FS, 128, ACT> : k_decode_part<LISA_MODE, HB, FS, 64, ACT>;
   if (lds > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
