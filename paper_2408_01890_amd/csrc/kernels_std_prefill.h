@@ -244,7 +244,11 @@ __global__ __launch_bounds__(256, 2) void k_std_prefill(StdPrefillArgs a) {
             if (16 * rbq >= Lq) continue;                      // (wave-uniform)
             const f16x8 hv =
                 *(const f16x8*)(stg + (16 * q + (lane >> 2)) * SP_SROW + (tile & 1) * 64 + (lane & 3) * 16);
-            *(f16x8*)((char*)sbase + ((size_t)rbq * n_kt + tile) * H * (16 * SP_TK * 2) + lane * 16) = hv;
+            // (non-temporal: nobody reads the scores before the whole tensor is written; 2.45 -> 2.14 ms
+            // on the LLaMA3-8B shape, and the layer that reads them next is not slower, also where
+            // the tensor would fit the last-level cache)
+            __builtin_nontemporal_store(__builtin_bit_cast(pf_u32x4, hv),
+                                        (pf_u32x4*)((char*)sbase + ((size_t)rbq * n_kt + tile) * H * (16 * SP_TK * 2) + lane * 16));
           }
         } else if ((tile & 1) == 1 || tile == n_tiles_w - 1) {
           const int jc = (tile >> 1) * (2 * SP_TK) + 8 * (lane & 7);
@@ -256,7 +260,7 @@ __global__ __launch_bounds__(256, 2) void k_std_prefill(StdPrefillArgs a) {
             const int vis = gi < Lq ? (a.causal ? min(Lk, gi + 1 + shift) : Lk) : 0;
             half_t* sp = sbase + (size_t)min(gi, Lq - 1) * Lk + jc;
             if (pair_full || jc + 8 <= vis) {
-              *(f16x8*)sp = hv;
+              __builtin_nontemporal_store(__builtin_bit_cast(pf_u32x4, hv), (pf_u32x4*)sp);
             } else {
 #pragma unroll
               for (int e = 0; e < 8; ++e)
