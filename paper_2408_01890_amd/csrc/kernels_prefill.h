@@ -225,8 +225,9 @@ __device__ __forceinline__ void st_uv(void* ubase, unsigned voff, T v) {
 }
 // The same for the A_{n-1} and A_n streams, kept apart because cache hints were tried on them:
 // non-temporal loads stop the head groups of a row block from sharing the A_{n-1} tile in the L2
-// (fetch 36.9 GB instead of 22.9 GB on the LLaMA3-8B shape), non-temporal stores change nothing
-// (21.4 GB, same time); plain accesses are what is used.
+// (fetch 36.9 GB instead of 22.9 GB on the LLaMA3-8B shape), non-temporal stores of row-major
+// scores change nothing (21.4 GB, same time); plain accesses are what is used here.  (The stores of
+// tiled scores, which do not come through these helpers, are non-temporal.)
 template <class T>
 __device__ __forceinline__ T ld_uv_stream(const void* ubase, unsigned voff) {
   return *(const T*)((const char*)ubase + voff);
@@ -685,7 +686,9 @@ __global__ __launch_bounds__(NW * 64) void k_lisa_prefill_fused(PrefillArgs a) {
             // tiles into whole lines, the layer took 1 - 3 % longer)
             if (i0 + PF_ROWS * rs < Lq) {
               const size_t at = ((size_t)((i0 >> 4) + rs) * n_kt + tile) * tile_stride;   // wave-uniform
-              st_uv_stream<f16x8>(s_base[hh] + at, (unsigned)(c * 64 + g * 16), hv);
+              // (a non-temporal store: 1 - 6 % on the three benchmark shapes)
+              __builtin_nontemporal_store(__builtin_bit_cast(pf_u32x4, hv),
+                                          (pf_u32x4*)((char*)(s_base[hh] + at) + (unsigned)(c * 64 + g * 16)));
             }
           } else if (XSTG) *(f16x8*)(xs_t + (wv * HPW + hh) * PF_XS_HEAD + c * (2 * PF_TK) + g * 16) = hv;
           else *(f16x8*)(as_ + sl * PF_AS_HEAD + c * PF_AS_ROW + (tile & 1) * 64 + g * 16) = hv;
