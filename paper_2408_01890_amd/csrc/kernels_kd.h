@@ -59,9 +59,13 @@ __global__ __launch_bounds__(256) void k_kd_huber_part(KdArgs g) {
     // at a time (equal work), a wave every fourth KB of the run, KD_UN of them in flight; the
     // loads of the run's tail are clamped, not branched around (a load behind a branch makes the
     // compiler wait for all earlier ones), and count nothing.  Tiles above the diagonal are not read.
+    // (few pairs: each is cut into `parts` interleaved shares of its runs, so that the grid has work)
     const int n_half = (n_rb + 1) / 2;
     const long long n_pairs = (long long)g.B * n_half;
-    for (long long pair = blockIdx.x; pair < n_pairs; pair += gridDim.x) {
+    const int parts = (int)max(1LL, min((long long)gridDim.x / n_pairs, 64LL));
+    for (long long item = blockIdx.x; item < n_pairs * parts; item += gridDim.x) {
+      const long long pair = item / parts;
+      const int part = (int)(item % parts), kw = 4 * parts;   // this wave: every kw-th KB from 4 part + wv
       const int b = (int)(pair / n_half), p = (int)(pair % n_half);
 #pragma unroll 1
       for (int side = 0; side < 2; ++side) {
@@ -74,11 +78,11 @@ __global__ __launch_bounds__(256) void k_kd_huber_part(KdArgs g) {
         const size_t base = ((size_t)b * n_rb + rb) * n_kt * g.H * 512 + lane * 8;
         const int i = 16 * rb + (lane >> 2);
         const int vis_row = i < g.Lq ? (g.causal ? min(g.Lk, i + 1 + shift) : g.Lk) : 0;
-        for (int k0 = wv; k0 < run; k0 += 4 * KD_UN) {
+        for (int k0 = 4 * part + wv; k0 < run; k0 += kw * KD_UN) {
           uint4 av[KD_UN], tv[KD_UN];
 #pragma unroll
           for (int u = 0; u < KD_UN; ++u) {
-            const size_t at = base + (size_t)min(k0 + 4 * u, run - 1) * 512;
+            const size_t at = base + (size_t)min(k0 + kw * u, run - 1) * 512;
             if (sizeof(S) == 2) {
               av[u] = kd_ld16(a + at);
               tv[u] = kd_ld16(t + at);
@@ -86,7 +90,7 @@ __global__ __launch_bounds__(256) void k_kd_huber_part(KdArgs g) {
           }
 #pragma unroll
           for (int u = 0; u < KD_UN; ++u) {
-            const int k = k0 + 4 * u;
+            const int k = k0 + kw * u;
             const int j8 = 32 * (k / g.H) + 8 * (lane & 3);
             const int nvis = k < run ? vis_row : 0;
             float sm = 0.f;
