@@ -360,8 +360,6 @@ def prefill_layer(cfg, seed_idx, steps, warmup, n_sets, cpu_budget, want_cpu):
     for s in range(n_sets):       # rotating sets: no step finds its scores in a cache
         inp = synth.make_prefill_inputs(cfg, synth.BASE_SEED + seed_idx + 100 * s, dev)
         prev, _ = lisa.std_attn_scores(inp["q"], inp["k"], tiled=TILED)
-        if n_sets == 1:
-            del inp["q"], inp["k"]
         sets.append(dict(inp=inp, prev=prev,
                          out=torch.empty((cfg.B, cfg.L, cfg.H, cfg.d_k), dtype=torch.float32, device=dev),
                          a_n=torch.empty_like(prev)))
@@ -432,6 +430,24 @@ def prefill_layer(cfg, seed_idx, steps, warmup, n_sets, cpu_budget, want_cpu):
 
     sec_kd = time_steps(step_kd, max(steps // 4, 2), 1)
     kd_bytes = 2.0 * pos * cfg.H * 2
+    # the standard layer that produces A_{n-1} (Eq. 1-2): scores only, and scores with its own O
+    # (it overwrites `prev` with the same values: the set stays valid)
+    ds = lisa.make_desc(cfg.torch_dtype, cfg.B, cfg.H, cfg.Hkv, cfg.L, cfg.L, cfg.d_k, out_f32=1)
+    ws_std = torch.empty(max(lisa.workspace_bytes(ds, lisa.WS_STD), 256), dtype=torch.uint8, device=dev)
+
+    def step_std():
+        i = s0["inp"]
+        lisa.std_attn_scores(i["q"], i["k"], scores_out=s0["prev"], tiled=TILED)
+
+    def step_std_full():
+        i = s0["inp"]
+        lisa.std_attn_scores(i["q"], i["k"], i["v"], scores_out=s0["prev"], out=s0["out"], workspace=ws_std,
+                             tiled=TILED)
+
+    sec_std = time_steps(step_std, max(steps // 4, 2), 1)
+    sec_std_full = time_steps(step_std_full, max(steps // 4, 2), 1)
+    del ws_std
+    std_bytes = pos * cfg.H * 2.0                       # the visible scores, written once
     rec = {
         "workload": workload_name(cfg), "tokens_per_s": cfg.B * cfg.L / sec, "ms_per_step": sec * 1e3,
         "ms_per_step_median": each[len(each) // 2], "ms_per_step_min": each[0], "timed_iterations": len(each),
@@ -445,6 +461,8 @@ def prefill_layer(cfg, seed_idx, steps, warmup, n_sets, cpu_budget, want_cpu):
         "score_layout": "tiles of 16 rows x 32 keys" if TILED else "row-major",
         "lisa_layer_row_major_scores_ms": sec_rm * 1e3,
         "kd_huber_loss_ms": sec_kd * 1e3, "kd_huber_hbm_frac": kd_bytes / sec_kd / 1e9 / HBM_PEAK_GBS,
+        "std_layer_scores_ms": sec_std * 1e3, "std_layer_scores_write_hbm_frac": std_bytes / sec_std / 1e9 / HBM_PEAK_GBS,
+        "std_layer_scores_and_output_ms": sec_std_full * 1e3,
     }
     if want_cpu:
         rec["cpu_baseline"] = cpu_baseline(cfg, sets[0]["inp"], sets[0]["prev"], cpu_budget)
