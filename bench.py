@@ -612,7 +612,7 @@ def c2_extras(cfg, sets, ws, steps):
 
 def chip_reference(buf):
     """What plain kernels reach on this chip (the library's reference kernels, timed here): one read
-    pass over `buf` (1 GiB, beyond the last-level cache) and chains of independent MFMAs of the two
+    pass and one write pass over `buf` (1 GiB, beyond the last-level cache) and chains of independent MFMAs of the two
     f16 shapes at two waves per SIMD.  Context for the roofline fractions, which stay against the
     published peaks."""
     import torch
@@ -633,6 +633,8 @@ def chip_reference(buf):
     out = {}
     sec = timed(lambda: lisa.probe_hbm_read(buf, sink), 5)
     out["hbm_read_GBs"] = buf.numel() / sec / 1e9
+    sec = timed(lambda: lisa.probe_hbm_write(buf), 5)
+    out["hbm_write_GBs"] = buf.numel() / sec / 1e9
     wgs, iters = 512, 20000
     for shape, name in ((0, "mfma_16x16x32_f16_TFLOPs"), (1, "mfma_32x32x16_f16_TFLOPs")):
         sec = timed(lambda: lisa.probe_mfma(shape, iters, wgs, sink), 2)

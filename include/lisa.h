@@ -419,6 +419,9 @@ int lisa_tune_set(int knob, int value);
  *                         read) once with 8 loads of 16 bytes in flight per lane and writes nothing.
  *                         `sink`: 16 bytes of device memory that stay untouched (they keep the loads
  *                         alive for the compiler).  Use a buffer larger than the last-level cache.
+ *   lisa_probe_hbm_write  writes floor(bytes / 16) 16-byte pieces of `dst` (device memory, 16-byte
+ *                         aligned) once with non-temporal stores: piece i becomes the four 32-bit
+ *                         words {seed, i mod 2^32, i / 2^32, ~seed}.
  *   lisa_probe_mfma       `workgroups` workgroups of four waves, each wave `iters` rounds of
  *                         independent MFMAs on constant operands: shape 0 = 8 x 16x16x32 f16 per round
  *                         (the shape of the library's FFNs), 1 = 4 x 32x32x16 f16 (the same
@@ -427,6 +430,7 @@ int lisa_tune_set(int knob, int value);
  * LISA_ERR_HIP.
  */
 int lisa_probe_hbm_read(const void* src, size_t bytes, void* sink, void* hip_stream);
+int lisa_probe_hbm_write(void* dst, size_t bytes, unsigned seed, void* hip_stream);
 int lisa_probe_mfma(int shape, int iters, int workgroups, void* sink, void* hip_stream);
 
 /*

@@ -1,5 +1,5 @@
 // Reference kernels for benchmarks: what a plain read stream and a plain chain of MFMAs reach on the
-// chip the library runs on.  They compute nothing of the method; bench.py times them next to the
+// chip the library runs on (and a plain write stream).  They compute nothing of the method; bench.py times them next to the
 // library's kernels so that a roofline fraction can also be read against what is reachable.
 #pragma once
 #include "mfma_ffn.h"
@@ -25,6 +25,25 @@ __global__ __launch_bounds__(256) void k_probe_read(const probe_u32x4* __restric
   for (size_t i = n_chunks * 2048 + (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256)
     acc ^= src[i];
   if (acc[0] == 0x9e3779b9u && acc[1] == 0x7f4a7c15u && acc[2] == 0xf39cc060u && acc[3] == 0x5cedc834u) sink[0] = acc;
+}
+
+// Writes n16 16-byte pieces once with non-temporal stores, a workgroup 32 KB at a time: piece i gets
+// {seed, low word of i, high word of i, ~seed}.  Any grid, block 256.
+__global__ __launch_bounds__(256) void k_probe_write(probe_u32x4* __restrict__ dst, size_t n16, unsigned seed) {
+  const size_t n_chunks = n16 / 2048;
+  for (size_t ch = blockIdx.x; ch < n_chunks; ch += gridDim.x) {
+    const size_t i0 = ch * 2048 + threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const size_t i = i0 + u * 256;
+      const probe_u32x4 v = {seed, (unsigned)i, (unsigned)(i >> 32), ~seed};
+      __builtin_nontemporal_store(v, dst + i);
+    }
+  }
+  for (size_t i = n_chunks * 2048 + (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) {
+    const probe_u32x4 v = {seed, (unsigned)i, (unsigned)(i >> 32), ~seed};
+    dst[i] = v;
+  }
 }
 
 // iters rounds of independent MFMAs on constant operands per wave: SHAPE 0: 8 x 16x16x32 f16 (the

@@ -1351,6 +1351,14 @@ int lisa_probe_hbm_read(const void* src, size_t bytes, void* sink, void* hip_str
   return check_launch();
 }
 
+int lisa_probe_hbm_write(void* dst, size_t bytes, unsigned seed, void* hip_stream) {
+  if (!dst) return LISA_ERR_NULL;
+  if (!aligned16(dst)) return LISA_ERR_ALIGN;
+  if (bytes < 16) return LISA_ERR_SHAPE;
+  k_probe_write<<<8 * kComputeUnits, 256, 0, (hipStream_t)hip_stream>>>((probe_u32x4*)dst, bytes / 16, seed);
+  return check_launch();
+}
+
 int lisa_probe_mfma(int shape, int iters, int workgroups, void* sink, void* hip_stream) {
   if (!sink) return LISA_ERR_NULL;
   if ((shape != 0 && shape != 1) || iters < 1 || workgroups < 1 || workgroups > 65536) return LISA_ERR_SHAPE;

@@ -29,7 +29,7 @@ EXPORTS = (
     "lisa_profile_collect", "lisa_cache_fill", "lisa_project_qkv", "lisa_layer_prefill",
     "lisa_layer_offsets", "lisa_layer_decode", "lisa_tune_set", "lisa_attn_decode_static",
     "lisa_decode_stack", "lisa_stack_workspace_bytes", "lisa_scores_elems", "lisa_kd_huber",
-    "lisa_probe_hbm_read", "lisa_probe_mfma",
+    "lisa_probe_hbm_read", "lisa_probe_hbm_write", "lisa_probe_mfma",
 )
 TUNE_PREFILL_GROUPS, TUNE_PREFILL_SPLIT, TUNE_PREFILL_PAIR, TUNE_STD_PAIR, TUNE_PROJECT_TN, TUNE_PREFILL_SLICES = range(6)
 
@@ -119,6 +119,8 @@ def _lib():
         h.lisa_profile_enable.restype = C.c_int
         h.lisa_probe_hbm_read.argtypes = [vp, sz, vp, vp]
         h.lisa_probe_hbm_read.restype = C.c_int
+        h.lisa_probe_hbm_write.argtypes = [vp, sz, C.c_uint, vp]
+        h.lisa_probe_hbm_write.restype = C.c_int
         h.lisa_probe_mfma.argtypes = [C.c_int, C.c_int, C.c_int, vp, vp]
         h.lisa_probe_mfma.restype = C.c_int
         h.lisa_cache_fill.argtypes = [dp] + [vp] * 5
@@ -234,6 +236,15 @@ def probe_hbm_read(buf: torch.Tensor, sink: torch.Tensor) -> None:
                                     C.c_void_p(sink.data_ptr()), _stream())
     if rc:
         raise LisaError(rc, "lisa_probe_hbm_read")
+
+
+def probe_hbm_write(buf: torch.Tensor, seed: int = 1) -> None:
+    """Reference kernel: one write pass over `buf` (device tensor; 16-byte piece i becomes the words
+    {seed, i mod 2^32, i / 2^32, ~seed}); time it with events."""
+    rc = _lib().lisa_probe_hbm_write(C.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(),
+                                     seed & 0xffffffff, _stream())
+    if rc:
+        raise LisaError(rc, "lisa_probe_hbm_write")
 
 
 def probe_mfma(shape: int, iters: int, workgroups: int, sink: torch.Tensor) -> None:

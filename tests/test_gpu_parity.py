@@ -1474,3 +1474,13 @@ def test_reference_kernels_run_and_leave_their_sink_alone():
     with pytest.raises(lisa.LisaError) as e:
         lisa.probe_mfma(2, 100, 16, sink)
     assert e.value.status == -2
+    # the write pass: whole 32 KB chunks and a ragged tail, nothing beyond the last whole piece
+    n = (1 << 20) + 4096 + 16 + 8
+    wbuf = torch.full((n,), 7, dtype=torch.uint8, device=DEV)
+    lisa.probe_hbm_write(wbuf, seed=0x1234)
+    torch.cuda.synchronize()
+    words = wbuf[: n // 16 * 16].view(torch.int32).view(-1, 4)
+    idx = torch.arange(words.shape[0], dtype=torch.int32, device=DEV)
+    assert bool((words[:, 0] == 0x1234).all()) and bool((words[:, 1] == idx).all())
+    assert bool((words[:, 2] == 0).all()) and bool((words[:, 3] == ~0x1234).all())
+    assert bool((wbuf[n // 16 * 16:] == 7).all())
