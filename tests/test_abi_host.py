@@ -375,3 +375,17 @@ def test_kd_huber_rejects_bad_arguments_before_any_launch():
     assert lib.lisa_kd_huber(C.byref(d), FAKE, FAKE, 1.0, 1.0, 0, out, None, 0, None) == -5
     f32t = lisa.make_desc(lisa.F32, 2, 8, 8, 64, 64, 1, score_tiled=1)
     assert lib.lisa_kd_huber(C.byref(f32t), FAKE, FAKE, 1.0, 1.0, 0, out, FAKE, 1 << 20, None) == -3
+
+
+def test_reference_kernels_reject_bad_arguments_before_any_launch():
+    lib = lisa.library()
+    assert lib.lisa_probe_hbm_read(None, 1 << 20, FAKE, None) == -1
+    assert lib.lisa_probe_hbm_read(FAKE, 1 << 20, None, None) == -1
+    assert lib.lisa_probe_hbm_read(ODD, 1 << 20, FAKE, None) == -4
+    assert lib.lisa_probe_hbm_read(FAKE, 8, FAKE, None) == -2
+    assert lib.lisa_probe_hbm_write(None, 1 << 20, 1, None) == -1
+    assert lib.lisa_probe_hbm_write(ODD, 1 << 20, 1, None) == -4
+    assert lib.lisa_probe_hbm_write(FAKE, 15, 1, None) == -2
+    assert lib.lisa_probe_mfma(0, 10, 16, None, None) == -1
+    assert lib.lisa_probe_mfma(0, 0, 16, FAKE, None) == -2
+    assert lib.lisa_probe_mfma(1, 10, 1 << 20, FAKE, None) == -2
