@@ -209,6 +209,28 @@ def test_lisa_prefill_tiled_full_size_sampled_rows(cfg, ffn):
     check_prefill(cfg, inp, prev, out, scores, rows_by_b, tag=f"/{ffn}/tiled")
 
 
+@pytest.mark.parametrize("cfg", [synth.C3, synth.C4], ids=["c3", "c4"])
+def test_std_layer_tiled_full_size_sampled_rows(cfg):
+    """The standard layer (Eq. 1-2) as bench.py times it on the two large shapes: tiled scores and
+    its own O, sampled query rows of every sequence against the oracle."""
+    from oracle import cref
+    idx = 3 if cfg is synth.C3 else 4
+    inp = synth.make_prefill_inputs(cfg, synth.BASE_SEED + 30 + idx, DEV)
+    scores, out = lisa.std_attn_scores(inp["q"], inp["k"], inp["v"], tiled=True)
+    torch.cuda.synchronize()
+    assert lisa.last_path() == "mfma_std"
+    tol = hp.TOL[cfg.torch_dtype]
+    ea = eo = 0.0
+    for b in range(cfg.B):
+        rows = synth.sample_rows(cfg.L, 64 // cfg.B + 8, 200 + b)
+        ref = hp.oracle_std_rows(inp["q"], inp["k"], b, rows)
+        ea = max(ea, hp.scores_row_rel_err(hp.gather_score_rows(scores, b, rows, cfg.L), ref, rows, cfg.L, cfg.L))
+        o_ref = cref.softmax_v_rows(hp.f64(inp["v"][b]), rows, ref, cfg.L)
+        eo = max(eo, hp.row_rel_err(hp.gather_out_rows(out, b, rows), o_ref))
+    log(f"[parity] std mfma tiled {cfg.name}: err_scores={ea:.3e} err_out={eo:.3e} tol={tol:g}")
+    assert max(ea, eo) <= tol
+
+
 @pytest.mark.parametrize("ffn", ["paper", "fan_in"])
 def test_concat_tiled_full_size_sampled_rows_against_the_oracle(ffn):
     """The paper's module at its own widths (Sec. 5.3: 64 -> 256 -> 32, r = 20) on the LLaMA2-7B shape,
